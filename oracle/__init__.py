@@ -1,0 +1,11 @@
+"""fp64 CPU oracle of the truncated path-signature transform (test infrastructure only).
+
+Nothing in the product imports this package: it exists so that tests, the smoke
+check and the benchmark's cpu_baseline leg can compare the HIP path against the
+paper's definition (Section 2.1, Eqs. 2-5 and Eq. 10).
+"""
+from .sig_oracle import (build, signature, tensor_exp, tensor_mul, sig_size,
+                         num_threads, level_slices)
+
+__all__ = ["build", "signature", "tensor_exp", "tensor_mul", "sig_size",
+           "num_threads", "level_slices"]

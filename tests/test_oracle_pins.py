@@ -1,0 +1,291 @@
+"""Pins of the fp64 oracle against facts that do not come from the oracle itself.
+
+Every check below is derived from the paper's definitions (Section 2.1: Eq. 1
+iterated integrals, Eq. 2 tensor exponential, Eq. 3 recursion, Eq. 4 product,
+Eq. 10 output row) or from textbook properties of signatures, and is computed
+here with explicit indices or numpy outer products, not by calling the oracle's
+own routines on the expected side.
+"""
+import itertools
+import math
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+from paper_2501_08455_amd import workloads
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+def levels(row, d, N):
+    out, start = [], 0
+    for n in range(1, N + 1):
+        out.append(np.asarray(row[start:start + d ** n]).reshape((d,) * n))
+        start += d ** n
+    assert start == len(row)
+    return out
+
+
+def np_product(a, b, d, N):
+    """Truncated product written with numpy outer products (independent of the oracle's C loop).
+
+    a, b: lists [level1, ..., levelN] of arrays shaped (d,)*n; level 0 is 1 on both sides.
+    """
+    out = []
+    for n in range(1, N + 1):
+        c = a[n - 1] + b[n - 1]
+        for i in range(1, n):
+            c = c + np.multiply.outer(a[i - 1], b[n - i - 1])
+        out.append(c)
+    return out
+
+
+def rand_path(rng, L, d, scale=0.5):
+    return np.cumsum(rng.normal(0, scale, size=(L, d)), axis=0)
+
+
+# ---------------------------------------------------------------- sizes (Eq. 10 drops level 0)
+@pytest.mark.parametrize("d,N,D", [(2, 3, 14), (5, 4, 780), (4, 4, 340), (10, 6, 1111110), (10, 4, 11110)])
+def test_output_sizes(oracle, d, N, D):
+    assert oracle.sig_size(d, N) == D
+    assert workloads.sig_size(d, N) == D
+    x = np.zeros((1, 2, d))
+    if D < 100000:
+        assert oracle.signature(x, N).shape == (1, D)
+
+
+# ---------------------------------------------------------------- 1. single segment (Eq. 2 + first line of Eq. 3)
+@pytest.mark.parametrize("d,N", [(1, 6), (2, 5), (3, 4), (4, 4)])
+def test_single_segment_is_tensor_exponential(oracle, d, N):
+    rng = np.random.default_rng(1)
+    x0 = rng.normal(size=d)
+    delta = rng.normal(size=d)
+    sig = oracle.signature(np.stack([x0, x0 + delta])[None], N)[0]
+    power = np.ones(())
+    for n, lev in enumerate(levels(sig, d, N), start=1):
+        power = np.multiply.outer(power, delta)
+        np.testing.assert_allclose(lev, power / math.factorial(n), rtol=1e-12, atol=1e-15)
+
+
+# ---------------------------------------------------------------- 2. level 1 is the total increment (Eq. 1)
+def test_level_one_is_total_increment(oracle):
+    rng = np.random.default_rng(2)
+    x = np.stack([rand_path(rng, 9, 3) for _ in range(5)])
+    sig = oracle.signature(x, 3)
+    np.testing.assert_allclose(sig[:, :3], x[:, -1] - x[:, 0], rtol=1e-12, atol=1e-14)
+
+
+# ---------------------------------------------------------------- 3. collinear path: product of exponentials of parallel vectors
+def test_collinear_path_is_one_exponential(oracle):
+    rng = np.random.default_rng(3)
+    d, N = 3, 5
+    v = rng.normal(size=d)
+    c = rng.normal(size=7)  # signed steps back and forth along v
+    x = np.concatenate([np.zeros((1, d)), np.cumsum(c[:, None] * v[None, :], axis=0)])
+    sig = oracle.signature(x[None], N)[0]
+    total = c.sum() * v
+    power = np.ones(())
+    for n, lev in enumerate(levels(sig, d, N), start=1):
+        power = np.multiply.outer(power, total)
+        np.testing.assert_allclose(lev, power / math.factorial(n), rtol=1e-10, atol=1e-13)
+
+
+def test_inserting_a_midpoint_changes_nothing(oracle):
+    rng = np.random.default_rng(4)
+    x = rand_path(rng, 6, 2)
+    mid = 0.25 * x[2] + 0.75 * x[3]
+    y = np.concatenate([x[:3], mid[None], x[3:]])
+    np.testing.assert_allclose(oracle.signature(y[None], 4), oracle.signature(x[None], 4),
+                               rtol=1e-11, atol=1e-13)
+
+
+# ---------------------------------------------------------------- 4. one channel
+def test_one_channel(oracle):
+    rng = np.random.default_rng(5)
+    x = rand_path(rng, 12, 1)
+    sig = oracle.signature(x[None], 6)[0]
+    t = x[-1, 0] - x[0, 0]
+    np.testing.assert_allclose(sig, [t ** n / math.factorial(n) for n in range(1, 7)], rtol=1e-11, atol=1e-14)
+
+
+# ---------------------------------------------------------------- 5. hand-worked example (tests/golden)
+def test_hand_worked_two_segment_example(oracle):
+    want = {}
+    with open(os.path.join(HERE, "golden", "two_segment_2d.txt")) as fh:
+        for line in fh:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            word, frac = line.split()
+            want[tuple(int(ch) for ch in word)] = float(Fraction(frac))
+    assert len(want) == 14
+    x = np.array([[0.0, 0.0], [1.0, 0.0], [1.0, 1.0]])
+    got = levels(oracle.signature(x[None], 3)[0], 2, 3)
+    for word, value in want.items():
+        assert got[len(word) - 1][word] == pytest.approx(value, abs=1e-15), word
+    # flat layout: first letter slowest (row-major) -- word 01 sits at offset 2 + 0*2 + 1
+    flat = oracle.signature(x[None], 3)[0]
+    assert flat[2 + 1] == pytest.approx(1.0) and flat[2 + 2] == pytest.approx(0.0)
+
+
+# ---------------------------------------------------------------- 6. shuffle identities, total length <= 3
+def test_shuffle_identities(oracle):
+    rng = np.random.default_rng(6)
+    d = 3
+    x = rand_path(rng, 8, d)
+    s1, s2, s3 = levels(oracle.signature(x[None], 3)[0], d, 3)
+    for i in range(d):
+        for j in range(d):
+            assert s1[i] * s1[j] == pytest.approx(s2[i, j] + s2[j, i], rel=1e-11, abs=1e-13)
+            for k in range(d):
+                lhs = s1[i] * s2[j, k]
+                rhs = s3[i, j, k] + s3[j, i, k] + s3[j, k, i]
+                assert lhs == pytest.approx(rhs, rel=1e-11, abs=1e-13)
+
+
+# ---------------------------------------------------------------- 7. antisymmetric part of level 2 = Levy area (shoelace)
+def test_levy_area_shoelace(oracle):
+    rng = np.random.default_rng(7)
+    d = 3
+    x = rand_path(rng, 10, d)
+    s2 = levels(oracle.signature(x[None], 2)[0], d, 2)[1]
+    dx = np.diff(x, axis=0)
+    rel = x[:-1] - x[0]
+    for i in range(d):
+        for j in range(d):
+            area = 0.5 * np.sum(rel[:, i] * dx[:, j] - rel[:, j] * dx[:, i])
+            assert 0.5 * (s2[i, j] - s2[j, i]) == pytest.approx(area, rel=1e-11, abs=1e-13)
+
+
+# ---------------------------------------------------------------- 8. Chen: Sig(X[0..m]) (x) Sig(X[m..]) = Sig(X)
+def test_chen_concatenation(oracle):
+    rng = np.random.default_rng(8)
+    d, N = 3, 4
+    x = rand_path(rng, 9, d)
+    whole = levels(oracle.signature(x[None], N)[0], d, N)
+    for m in range(1, 8):
+        left = levels(oracle.signature(x[None, :m + 1], N)[0], d, N)
+        right = levels(oracle.signature(x[None, m:], N)[0], d, N)
+        for got, want in zip(np_product(left, right, d, N), whole):
+            np.testing.assert_allclose(got, want, rtol=1e-10, atol=1e-12)
+
+
+def test_oracle_product_matches_outer_product_definition(oracle):
+    rng = np.random.default_rng(80)
+    d, N = 2, 4
+    D = oracle.sig_size(d, N)
+    a = np.concatenate([[1.0], rng.normal(size=D)])
+    b = np.concatenate([[1.0], rng.normal(size=D)])
+    c = oracle.tensor_mul(a, b, d, N)
+    want = np_product(levels(a[1:], d, N), levels(b[1:], d, N), d, N)
+    assert c[0] == 1.0
+    for got, w in zip(levels(c[1:], d, N), want):
+        np.testing.assert_allclose(got, w, rtol=1e-12, atol=1e-13)
+
+
+# ---------------------------------------------------------------- 9. time reversal gives the inverse
+def test_time_reversal_is_inverse(oracle):
+    rng = np.random.default_rng(9)
+    d, N = 2, 5
+    x = rand_path(rng, 7, d)
+    fwd = levels(oracle.signature(x[None], N)[0], d, N)
+    bwd = levels(oracle.signature(x[None, ::-1], N)[0], d, N)
+    for lev in np_product(fwd, bwd, d, N):
+        assert np.max(np.abs(lev)) < 1e-12
+
+
+# ---------------------------------------------------------------- 10. scaling and translation
+def test_scaling_and_translation(oracle):
+    rng = np.random.default_rng(10)
+    d, N = 3, 4
+    x = rand_path(rng, 6, d)
+    lam, shift = -1.7, rng.normal(size=d)
+    base = levels(oracle.signature(x[None], N)[0], d, N)
+    moved = levels(oracle.signature((lam * x + shift)[None], N)[0], d, N)
+    for n, (a, b) in enumerate(zip(base, moved), start=1):
+        np.testing.assert_allclose(b, lam ** n * a, rtol=1e-10, atol=1e-12)
+
+
+# ---------------------------------------------------------------- 11. brute-force iterated sums with explicit indices
+def brute_force_signature(x, N):
+    """Iterated integrals of the piecewise-linear path through the rows of x.
+
+    The integral over t_1 < ... < t_n of a piecewise-linear path splits by which
+    segment each t_r falls in: segment indices are weakly increasing, and r
+    variables inside one segment contribute the simplex volume 1/r!.  (Eq. 6 of
+    the paper prints strict inequalities, which would make level 2 of a single
+    segment vanish and contradict Eq. 2; the weak form with the simplex weights
+    is what Eq. 1 gives.)
+    """
+    dx = np.diff(x, axis=0)
+    K, d = dx.shape
+    out = []
+    for n in range(1, N + 1):
+        lev = np.zeros((d,) * n)
+        for ks in itertools.combinations_with_replacement(range(K), n):
+            weight = 1.0
+            for _, run in itertools.groupby(ks):
+                weight /= math.factorial(len(list(run)))
+            for word in itertools.product(range(d), repeat=n):
+                term = weight
+                for k, i in zip(ks, word):
+                    term *= dx[k, i]
+                lev[word] += term
+        out.append(lev)
+    return out
+
+
+@pytest.mark.parametrize("L,d,N", [(2, 2, 4), (4, 2, 4), (6, 3, 3), (7, 2, 3), (5, 3, 4)])
+def test_brute_force_iterated_sums(oracle, L, d, N):
+    rng = np.random.default_rng(100 + L + d + N)
+    x = rand_path(rng, L, d)
+    got = levels(oracle.signature(x[None], N)[0], d, N)
+    for g, w in zip(got, brute_force_signature(x, N)):
+        np.testing.assert_allclose(g, w, rtol=1e-11, atol=1e-13)
+
+
+# ---------------------------------------------------------------- 12. stream rows are signatures of truncated paths
+def test_stream_rows_are_prefix_signatures(oracle):
+    rng = np.random.default_rng(12)
+    d, N, L = 3, 3, 8
+    x = np.stack([rand_path(rng, L, d) for _ in range(3)])
+    st = oracle.signature(x, N, stream=True)
+    assert st.shape == (3, L - 1, oracle.sig_size(d, N))
+    for k in range(L - 1):
+        np.testing.assert_array_equal(st[:, k], oracle.signature(x[:, :k + 2], N))
+    np.testing.assert_array_equal(st[:, -1], oracle.signature(x, N))
+    # the first stream row is the exponential of the first increment, not a trivial prefix
+    d1 = x[0, 1] - x[0, 0]
+    np.testing.assert_allclose(st[0, 0, :d], d1, rtol=1e-13)
+
+
+def test_batch_entries_are_independent(oracle):
+    rng = np.random.default_rng(13)
+    x = np.stack([rand_path(rng, 6, 2) for _ in range(9)])
+    all_at_once = oracle.signature(x, 4)
+    for b in range(9):
+        np.testing.assert_array_equal(all_at_once[b], oracle.signature(x[b:b + 1], 4)[0])
+
+
+def test_repeated_point_is_identity_step(oracle):
+    rng = np.random.default_rng(14)
+    x = rand_path(rng, 5, 2)
+    y = np.concatenate([x[:2], x[1:2], x[2:]])
+    np.testing.assert_array_equal(oracle.signature(y[None], 4), oracle.signature(x[None], 4))
+
+
+def test_depth_one_and_bad_shapes(oracle):
+    rng = np.random.default_rng(15)
+    x = rand_path(rng, 5, 3)
+    np.testing.assert_allclose(oracle.signature(x[None], 1)[0], x[-1] - x[0], rtol=1e-13)
+    with pytest.raises(ValueError):
+        oracle.signature(x[None, :1], 2)  # one point: no increment
+    assert oracle.signature(np.zeros((0, 4, 2)), 3).shape == (0, 14)
+
+
+def test_float32_input_is_widened_exactly(oracle):
+    x32 = workloads.make_paths("C1")
+    assert x32.dtype == np.float32 and x32.shape == (4, 16, 2)
+    np.testing.assert_array_equal(oracle.signature(x32, 3), oracle.signature(x32.astype(np.float64), 3))
