@@ -1,0 +1,150 @@
+"""Benchmark of the signature transform on one MI355X.
+
+One "step" is one sig_compute call over one batch that already sits in HBM.  The headline
+workload is the second benchmark configuration (128 paths, 100 points, 5 channels, depth 4,
+final signature); the other configurations and their batch-saturated variants are reported in
+`all_configs` of the same JSON line.  The fp64 CPU oracle is timed beside it as a baseline.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_FP32_TFLOPS = 157.3   # MI355X vector fp32, published (assumes packed fp32 issue)
+PEAK_HBM_GBS = 8000.0      # MI355X HBM3E, published
+
+
+def time_calls(binding, ctx, xt, depth, stream_flag, out, steps, warmup, plan=None):
+    """Mean milliseconds per sig_compute call over `steps` back-to-back calls, from HIP events on the
+    stream the kernels are launched on (torch's current stream) and from the host clock."""
+    import torch
+    for _ in range(warmup):
+        rc = binding.sig_compute(ctx, xt, depth, stream_flag, out, plan=plan)
+        assert rc == 0, rc
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(steps):
+        rc = binding.sig_compute(ctx, xt, depth, stream_flag, out, plan=plan)
+    e1.record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    assert rc == 0, rc
+    return e0.elapsed_time(e1) / steps, (t1 - t0) * 1e3 / steps
+
+
+def algorithmic_work(cfg, B, workloads):
+    """(flops, bytes) of one call: fused Horner steps, and path read once + output written once."""
+    K = cfg.L - 1
+    D = workloads.sig_size(cfg.d, cfg.depth)
+    flops = 2.0 * workloads.fused_fma_per_step(cfg.d, cfg.depth) * B * K
+    rows = K if cfg.stream else 1
+    nbytes = 4.0 * (B * cfg.L * cfg.d + B * rows * D)
+    return flops, nbytes, D, rows
+
+
+def roofline(flops, nbytes, ms):
+    """Roofline entry for a call lasting `ms`: the bound is the one whose ideal time is larger."""
+    t_alu = flops / (PEAK_FP32_TFLOPS * 1e12)
+    t_hbm = nbytes / (PEAK_HBM_GBS * 1e9)
+    if t_alu >= t_hbm:
+        ach = flops / (ms * 1e-3) / 1e12
+        return {"bound": "alu", "achieved": ach, "peak": PEAK_FP32_TFLOPS, "unit": "TFLOP/s",
+                "frac": ach / PEAK_FP32_TFLOPS, "traffic": None}
+    ach = nbytes / (ms * 1e-3) / 1e9
+    return {"bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+            "frac": ach / PEAK_HBM_GBS, "traffic": None}
+
+
+def bench_config(binding, workloads, ctx, cfg, B, steps, warmup):
+    import torch
+    x = workloads.make_paths(cfg, B=B)
+    xt = torch.from_numpy(x).cuda()
+    flops, nbytes, D, rows = algorithmic_work(cfg, B, workloads)
+    out = torch.empty((B, rows, D) if cfg.stream else (B, D), dtype=torch.float32, device="cuda")
+    ms_ev, ms_wall = time_calls(binding, ctx, xt, cfg.depth, int(cfg.stream), out, steps, warmup)
+    rc, pl = binding.sig_plan(ctx, B, cfg.L, cfg.d, cfg.depth, int(cfg.stream))
+    res = {"workload": "%s B=%d L=%d d=%d depth=%d %s" % (cfg.name, B, cfg.L, cfg.d, cfg.depth,
+                                                          "stream" if cfg.stream else "final"),
+           "ms_per_step": ms_ev, "ms_per_step_host_clock": ms_wall, "steps": steps,
+           "paths_per_s": B / (ms_ev * 1e-3), "terms_per_s": B * rows * D / (ms_ev * 1e-3),
+           "roofline": roofline(flops, nbytes, ms_ev), "plan": pl.as_dict()}
+    del xt, out
+    return res
+
+
+def cpu_baseline(workloads, cfg, max_paths, budget_s=20.0):
+    """The fp64 oracle on the host cores, on (a sample of) the same workload."""
+    import numpy as np
+    import oracle
+    oracle.build()
+    x = workloads.make_paths(cfg)
+    n = min(cfg.B, max_paths)
+    xs = x[:n]
+    oracle.signature(xs[:1], cfg.depth, stream=cfg.stream)  # load the library
+    times = []
+    t_start = time.perf_counter()
+    while len(times) < 5 and (time.perf_counter() - t_start < budget_s or not times):
+        t0 = time.perf_counter()
+        oracle.signature(xs, cfg.depth, stream=cfg.stream)
+        times.append(time.perf_counter() - t0)
+    t = float(np.median(times))
+    return {"value": n / t, "unit": "paths/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": "%d of %d paths of the workload, median of %d runs, %.4f s per run" % (n, cfg.B, len(times), t)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=50)
+    ap.add_argument("--no-extras", action="store_true", help="skip the other configurations")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (a box has one MI355X); --gpus %d is not supported"
+              % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2501_08455_amd import binding, workloads
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    torch.cuda.set_device(0)
+    binding.load()
+    ctx = binding.default_ctx()
+
+    cfg = workloads.CONFIGS["C2"]
+    head = bench_config(binding, workloads, ctx, cfg, cfg.B, args.steps, args.warmup)
+    line = {
+        "metric": "signatures/sec at (B=128, L=100, d=5, N=4), final signature",
+        "value": head["paths_per_s"], "unit": "paths/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": head["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": head["workload"], "terms_per_s": head["terms_per_s"], "plan": head["plan"],
+                   "input": "Brownian paths, increments N(0, 1/L), seeded, resident in HBM"},
+        "roofline": head["roofline"],
+    }
+    if not args.no_cpu:
+        line["cpu_baseline"] = cpu_baseline(workloads, cfg, max_paths=cfg.B)
+    if not args.no_extras:
+        extras = []
+        plan = [("C1", None, 500), ("C3", None, 300), ("C4", None, 300), ("C5", None, 50),
+                ("C1", 1 << 20, 50), ("C2", 65536, 50), ("C3", 4096, 30), ("C4", 4096, 20)]
+        for name, B, steps in plan:
+            c = workloads.CONFIGS[name]
+            extras.append(bench_config(binding, workloads, ctx, c, B or c.B, steps, 5))
+        line["all_configs"] = extras
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,152 @@
+/*
+ * sig.h -- C ABI of libsig: the batched truncated path-signature transform on
+ * one AMD MI355X (gfx950), hand-written HIP behind plain pointers and sizes.
+ *
+ * The operation (paper Section 2.1):
+ *   a path is L points in R^d; its K = L - 1 increments are dX_k = X_{k+1} - X_k;
+ *   exp^N(v) = (1, v, v(x)v/2!, ..., v^{(x)N}/N!)                         (Eq. 2)
+ *   Sig_1 = exp^N(dX_1),  Sig_k = Sig_{k-1} (x) exp^N(dX_k)               (Eq. 3, batched Eq. 5)
+ *   (a (x) b)_n = sum_{i+j=n} a_i (x) b_j,  i, j >= 0,  a_0 = b_0 = 1     (Eq. 4)
+ *   the output row of a prefix is the concatenation [S_1, ..., S_N]       (Eq. 10)
+ * so level 0 (the constant 1) is not stored.  Level n occupies d^n floats
+ * starting at offset d + ... + d^{n-1} of a row, flattened row-major with the
+ * earliest tensor factor as the slowest index.  A row has
+ * D = d + d^2 + ... + d^N floats.
+ *
+ * Conventions common to all entry points
+ *   - every pointer named DEVICE is device memory of the GPU that was current
+ *     when the context was created; the caller allocates and frees it and keeps
+ *     it alive until the HIP stream has passed the call;
+ *   - `hip_stream` is a hipStream_t passed as void* (NULL = the default
+ *     stream), so that this header needs no HIP include.  All work is enqueued
+ *     on it and the call returns without synchronising;
+ *   - nothing is thrown, printed or aborted across this boundary: every
+ *     failure is a return code (enum below) and leaves `out` unspecified;
+ *   - a context owns reusable device scratch, so one context serves one stream
+ *     at a time; calls on the same stream are ordered by the stream.
+ *   - results are deterministic for a fixed plan (no atomics, fixed combine order).
+ */
+#ifndef SIG_H
+#define SIG_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct sig_ctx sig_ctx; /* opaque: device properties, scratch buffers */
+
+enum sig_status {
+    SIG_OK = 0,
+    SIG_ERR_INVALID = 1,   /* NULL pointer, B < 0, L < 2, d < 1, depth < 1, flag not 0/1, bad plan */
+    SIG_ERR_TOO_LARGE = 2, /* D or an output size overflows int64, or a grid limit is exceeded */
+    SIG_ERR_ALLOC = 3,     /* device scratch could not be allocated */
+    SIG_ERR_HIP = 4,       /* a HIP call or kernel launch reported an error */
+    SIG_ERR_NO_DEVICE = 5  /* no usable HIP device when the context was created */
+};
+
+/* Which kernel family runs (see sig_plan). */
+enum sig_variant {
+    SIG_VARIANT_AUTO = 0,
+    /* state of every path lives in HBM (in the output rows themselves) and is read-modified-written
+     * once per increment; any (d, depth); the fallback for shapes with no compiled on-chip kernel */
+    SIG_VARIANT_HBM_STREAMING = 1,
+    /* state lives in registers: each lane owns the words below one prefix of length `prefix_depth`
+     * and runs the fused multiply-by-exponential of Eq. 3 over its time chunk; chunks of one path
+     * are joined by Eq. 4 products; only for the compiled (d, depth, prefix_depth) combinations */
+    SIG_VARIANT_ON_CHIP = 2
+};
+
+/*
+ * How one sig_compute call is mapped onto the GPU.  Filled by sig_plan; may be
+ * edited and passed to sig_compute_planned (tests and tuning).  Fields:
+ *   variant       one of enum sig_variant (never AUTO after sig_plan)
+ *   prefix_depth  p: the index space of a row is cut into d^p independent sub-trees
+ *   chunks        time chunks of one path folded concurrently inside one workgroup (>= 1)
+ *   segments      workgroups per path along time (>= 1); partial signatures of segments
+ *                 are joined by a second launch
+ *   threads       workgroup size (multiple of 64)
+ *   tile_steps    increments staged through LDS per tile by the loader
+ */
+typedef struct sig_plan_t {
+    int32_t variant;
+    int32_t prefix_depth;
+    int32_t chunks;
+    int32_t segments;
+    int32_t threads;
+    int32_t tile_steps;
+    int32_t reserved[6];
+} sig_plan_t;
+
+/*
+ * D = d + d^2 + ... + d^depth (row length of Eq. 10), or -1 if d < 1, depth < 1
+ * or the sum does not fit in int64.  Host only.
+ */
+int64_t sig_size(int d, int depth);
+
+/*
+ * Create a context on the current HIP device.  *ctx receives the handle.
+ * Returns SIG_ERR_INVALID for ctx == NULL, SIG_ERR_NO_DEVICE when HIP reports
+ * no device.  Allocates nothing on the device until the first compute call
+ * that needs scratch.
+ */
+int sig_create(sig_ctx **ctx);
+
+/* Synchronise the device, free the context's scratch and the context.  NULL is a no-op. */
+void sig_destroy(sig_ctx *ctx);
+
+/*
+ * Signatures of a batch of piecewise-linear paths (Eqs. 2-5, output Eq. 10).
+ *   path         DEVICE, float32 [B][L][d], contiguous, read only
+ *   B, L, d      batch, points per path (>= 2), channels (>= 1)
+ *   depth        truncation level N (>= 1)
+ *   stream_flag  0: out is [B][D], the signature of the whole path
+ *                1: out is [B][L-1][D]; row k is the signature of points 0..k+1
+ *   out          DEVICE, float32, fully overwritten; must not overlap path
+ *   hip_stream   hipStream_t as void*
+ * B == 0 returns SIG_OK and launches nothing.  L == 1 has no increment and is
+ * SIG_ERR_INVALID.  NaN/Inf propagate.  Arithmetic is float32 with FMA.
+ */
+int sig_compute(sig_ctx *ctx, const float *path, int64_t B, int64_t L, int d, int depth,
+                int stream_flag, float *out, void *hip_stream);
+
+/*
+ * The mapping sig_compute would use for this shape.  Host only; `ctx` may be
+ * NULL (then a 256-CU device is assumed).  Returns SIG_ERR_INVALID /
+ * SIG_ERR_TOO_LARGE exactly as sig_compute would for the same shape.
+ */
+int sig_plan(const sig_ctx *ctx, int64_t B, int64_t L, int d, int depth, int stream_flag,
+             sig_plan_t *plan);
+
+/*
+ * SIG_OK if sig_compute_planned would accept `plan` for this shape (the same checks, nothing is
+ * launched), else the status it would return.  Host only.
+ */
+int sig_plan_validate(int64_t B, int64_t L, int d, int depth, int stream_flag, const sig_plan_t *plan);
+
+/*
+ * sig_compute with an explicit mapping.  The plan is validated against the
+ * shape and the compiled kernels; an unsupported plan is SIG_ERR_INVALID and
+ * nothing is launched.
+ */
+int sig_compute_planned(sig_ctx *ctx, const float *path, int64_t B, int64_t L, int d, int depth,
+                        int stream_flag, float *out, const sig_plan_t *plan, void *hip_stream);
+
+/*
+ * Batched truncated product of Eq. 4 on output rows (level 0 = 1 implied on both sides):
+ *   out[b] = a[b] (x) b[b],  a, b, out DEVICE float32 [B][D]; out must not overlap a or b.
+ */
+int sig_combine(sig_ctx *ctx, const float *a, const float *b, int64_t B, int d, int depth,
+                float *out, void *hip_stream);
+
+/* 1 if an on-chip kernel is compiled for (d, depth, prefix_depth), else 0.  Host only. */
+int sig_on_chip_available(int d, int depth, int prefix_depth);
+
+/* Static, NUL-terminated description of a status code. */
+const char *sig_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SIG_H */

@@ -1,0 +1,171 @@
+"""Python binding of libsig.so: the same entry points as include/sig.h, argument marshalling only.
+
+torch is used for device memory and streams; every arithmetic step runs in the
+HIP kernels behind the C ABI.  There is no CPU fallback: if the library is not
+built, loading raises.
+"""
+import ctypes
+import os
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libsig.so")
+
+SIG_OK = 0
+SIG_ERR_INVALID = 1
+SIG_ERR_TOO_LARGE = 2
+SIG_ERR_ALLOC = 3
+SIG_ERR_HIP = 4
+SIG_ERR_NO_DEVICE = 5
+
+SIG_VARIANT_AUTO = 0
+SIG_VARIANT_HBM_STREAMING = 1
+SIG_VARIANT_ON_CHIP = 2
+
+
+class sig_plan_t(ctypes.Structure):
+    _fields_ = [("variant", ctypes.c_int32), ("prefix_depth", ctypes.c_int32),
+                ("chunks", ctypes.c_int32), ("segments", ctypes.c_int32),
+                ("threads", ctypes.c_int32), ("tile_steps", ctypes.c_int32),
+                ("reserved", ctypes.c_int32 * 6)]
+
+    def as_dict(self):
+        return {k: int(getattr(self, k)) for k, _ in self._fields_ if k != "reserved"}
+
+
+class SigError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        super().__init__("%s: status %d (%s)" % (where, status, sig_strerror(status)))
+
+
+_lib = None
+
+
+def load():
+    """dlopen libsig.so (building it first only if it does not exist) and declare the prototypes."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        from . import build as _build
+        _build.build()
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
+    lib.sig_size.restype = i64
+    lib.sig_size.argtypes = [i32, i32]
+    lib.sig_create.restype = i32
+    lib.sig_create.argtypes = [ctypes.POINTER(vp)]
+    lib.sig_destroy.restype = None
+    lib.sig_destroy.argtypes = [vp]
+    lib.sig_compute.restype = i32
+    lib.sig_compute.argtypes = [vp, vp, i64, i64, i32, i32, i32, vp, vp]
+    lib.sig_plan.restype = i32
+    lib.sig_plan.argtypes = [vp, i64, i64, i32, i32, i32, ctypes.POINTER(sig_plan_t)]
+    lib.sig_plan_validate.restype = i32
+    lib.sig_plan_validate.argtypes = [i64, i64, i32, i32, i32, ctypes.POINTER(sig_plan_t)]
+    lib.sig_compute_planned.restype = i32
+    lib.sig_compute_planned.argtypes = [vp, vp, i64, i64, i32, i32, i32, vp, ctypes.POINTER(sig_plan_t), vp]
+    lib.sig_combine.restype = i32
+    lib.sig_combine.argtypes = [vp, vp, vp, i64, i32, i32, vp, vp]
+    lib.sig_on_chip_available.restype = i32
+    lib.sig_on_chip_available.argtypes = [i32, i32, i32]
+    lib.sig_strerror.restype = ctypes.c_char_p
+    lib.sig_strerror.argtypes = [i32]
+    _lib = lib
+    return lib
+
+
+# ---------------------------------------------------------------- thin wrappers, one per C entry point
+def sig_size(d, depth):
+    return int(load().sig_size(int(d), int(depth)))
+
+
+def sig_strerror(status):
+    return load().sig_strerror(int(status)).decode()
+
+
+def sig_create():
+    h = ctypes.c_void_p()
+    rc = load().sig_create(ctypes.byref(h))
+    if rc != SIG_OK:
+        raise SigError(rc, "sig_create")
+    return h
+
+
+def sig_destroy(ctx):
+    load().sig_destroy(ctx)
+
+
+def sig_on_chip_available(d, depth, prefix_depth):
+    return bool(load().sig_on_chip_available(int(d), int(depth), int(prefix_depth)))
+
+
+def sig_plan(ctx, B, L, d, depth, stream_flag):
+    """Returns (status, sig_plan_t).  `ctx` may be None."""
+    pl = sig_plan_t()
+    rc = load().sig_plan(ctx, int(B), int(L), int(d), int(depth), int(stream_flag), ctypes.byref(pl))
+    return rc, pl
+
+
+def sig_plan_validate(B, L, d, depth, stream_flag, plan):
+    return int(load().sig_plan_validate(int(B), int(L), int(d), int(depth), int(stream_flag), ctypes.byref(plan)))
+
+
+def make_plan(variant, prefix_depth=0, chunks=1, segments=1, threads=256, tile_steps=0):
+    pl = sig_plan_t()
+    pl.variant, pl.prefix_depth, pl.chunks = int(variant), int(prefix_depth), int(chunks)
+    pl.segments, pl.threads, pl.tile_steps = int(segments), int(threads), int(tile_steps)
+    return pl
+
+
+def _stream_handle(stream):
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def sig_compute(ctx, path, depth, stream_flag, out, stream=None, plan=None):
+    """Raw call: `path` [B, L, d] and `out` are contiguous float32 torch tensors on the GPU.  Returns the status."""
+    B, L, d = path.shape
+    args = [ctx, ctypes.c_void_p(path.data_ptr()), B, L, d, int(depth), int(stream_flag),
+            ctypes.c_void_p(out.data_ptr())]
+    if plan is None:
+        return load().sig_compute(*args, _stream_handle(stream))
+    return load().sig_compute_planned(*args, ctypes.byref(plan), _stream_handle(stream))
+
+
+def sig_combine(ctx, a, b, d, depth, out, stream=None):
+    return load().sig_combine(ctx, ctypes.c_void_p(a.data_ptr()), ctypes.c_void_p(b.data_ptr()),
+                              a.shape[0], int(d), int(depth), ctypes.c_void_p(out.data_ptr()),
+                              _stream_handle(stream))
+
+
+# ---------------------------------------------------------------- convenience on top of the raw calls
+_default_ctx = None
+
+
+def default_ctx():
+    global _default_ctx
+    if _default_ctx is None:
+        _default_ctx = sig_create()
+    return _default_ctx
+
+
+def signature(path, depth, stream=False, plan=None, ctx=None, out=None):
+    """Depth-`depth` signatures of `path` (float32 CUDA tensor [B, L, d]); allocates the output with torch."""
+    import torch
+    if not path.is_cuda or path.dtype != torch.float32:
+        raise ValueError("path must be a float32 tensor on the GPU")
+    path = path.contiguous()
+    B, L, d = path.shape
+    D = sig_size(d, depth)
+    if D < 0:
+        raise SigError(SIG_ERR_TOO_LARGE, "sig_size")
+    shape = (B, L - 1, D) if stream else (B, D)
+    if out is None:
+        out = torch.empty(shape, dtype=torch.float32, device=path.device)
+    rc = sig_compute(ctx or default_ctx(), path, depth, 1 if stream else 0, out, plan=plan)
+    if rc != SIG_OK:
+        raise SigError(rc, "sig_compute")
+    return out

@@ -1,0 +1,339 @@
+// Host side of libsig: argument checking, the planner that maps a shape onto the GPU, scratch
+// management and kernel dispatch.  The C ABI is declared and documented in include/sig.h.
+#include <new>
+
+#include "sig_internal.h"
+
+using namespace sig;
+
+struct sig_ctx {
+    int device;
+    int num_cu;
+    float *scratch;        // partial signatures of time segments, [B][segments][D]
+    size_t scratch_bytes;
+};
+
+namespace {
+
+constexpr int kDefaultCUs = 256;
+constexpr int kThreads = 256;
+constexpr int kMinChunkSteps = 8;   // do not cut time finer than this: every cut costs one Eq. 4 product
+
+int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// Argument checks shared by sig_plan and the compute entry points (pointers are checked by the latter).
+int check_shape(int64_t B, int64_t L, int d, int depth, int stream_flag, RowShape *rs)
+{
+    if (B < 0 || L < 2 || d < 1 || depth < 1 || (stream_flag != 0 && stream_flag != 1)) return SIG_ERR_INVALID;
+    if (depth > kMaxDepth || d > 8192) return SIG_ERR_TOO_LARGE;
+    if (!make_row_shape(d, depth, rs)) return SIG_ERR_TOO_LARGE;
+    // sizes in floats must fit in int64 with room to spare: B * L * d and B * (L-1) * D
+    const int64_t lim = INT64_MAX / 8;
+    if (B > 0) {
+        if (L > lim / d || B > lim / (L * d)) return SIG_ERR_TOO_LARGE;
+        int64_t rows = stream_flag ? L - 1 : 1;
+        if (rs->D > lim / rows || B > lim / (rs->D * rows)) return SIG_ERR_TOO_LARGE;
+    }
+    return SIG_OK;
+}
+
+// Fill the derived launch fields of an on-chip plan (chunk_steps, tile_steps) and check every limit the kernel
+// relies on.  Returns false if the plan cannot run.
+bool finish_on_chip(const OnChipKernelInfo *ki, int64_t B, int64_t L, int stream_flag, const sig_plan_t &pl,
+                    const RowShape &rs, OnChipArgs *args)
+{
+    const int Q = ki->lanes_per_chunk;
+    const int64_t K = L - 1;
+    if (pl.threads < kWave || pl.threads > 256 || pl.threads % kWave) return false;
+    if (pl.chunks < 1 || pl.segments < 1) return false;
+    if ((int64_t)pl.chunks * pl.segments > K) return false;  // no more pieces than increments
+    if (Q > pl.threads && pl.chunks != 1) return false;
+    if (Q <= pl.threads && (int64_t)pl.chunks * Q > pl.threads) return false;
+    if (stream_flag && pl.segments != 1) return false;       // carries across workgroups are not implemented
+    if (pl.segments > 1 && rs.D * (int64_t)sizeof(float) > kMaxLdsBytes) return false;
+    if (B * (int64_t)pl.segments > INT32_MAX) return false;
+    args->B = B;
+    args->L = L;
+    args->chunks = pl.chunks;
+    args->segments = pl.segments;
+    args->threads = pl.threads;
+    args->stream_flag = stream_flag;
+    args->chunk_steps = (int)ceil_div(K, (int64_t)pl.chunks * pl.segments);
+    if (ceil_div(K, (int64_t)pl.chunks * pl.segments) > INT32_MAX) return false;
+    // groups per workgroup: as many as the threads hold, fewer if their chunk signatures overflow LDS
+    int G = Q > pl.threads ? 1 : pl.threads / (pl.chunks * Q);
+    if (pl.chunks > 1) {
+        int64_t fit = (kMaxLdsBytes * 3 / 4) / ((int64_t)pl.chunks * rs.D * (int64_t)sizeof(float));
+        if (fit < 1) return false;
+        if (G > fit) G = (int)fit;
+    }
+    args->groups = G;
+    // tile: bounded by the loader's registers (kLoaderStage floats per thread) and, if asked, by the plan
+    const int64_t ngc = (int64_t)G * pl.chunks;
+    int64_t tt = (kLoaderStage * (int64_t)pl.threads) / (ngc * ki->d);
+    if (tt < 1) return false;
+    if (tt > args->chunk_steps) tt = args->chunk_steps;
+    if (pl.tile_steps > 0 && pl.tile_steps < tt) tt = pl.tile_steps;
+    args->tile_steps = (int)tt;
+    while (args->tile_steps > 1 && ki->lds_bytes(*args) > kMaxLdsBytes) args->tile_steps /= 2;
+    if (ki->lds_bytes(*args) > kMaxLdsBytes) return false;
+    return true;
+}
+
+// Smallest compiled prefix depth for (d, depth), or the next one up when more lanes are needed.
+const OnChipKernelInfo *pick_on_chip(int d, int depth, int64_t B, int64_t want_lanes)
+{
+    const OnChipKernelInfo *best = nullptr;
+    for (const OnChipKernelInfo *e = on_chip_table(); e->launch; ++e) {
+        if (e->d != d || e->depth != depth) continue;
+        if (!best) { best = e; continue; }
+        // entries are ordered by increasing prefix depth: move up only while the batch alone cannot fill the chip
+        if (B * best->lanes_per_chunk < want_lanes) best = e;
+    }
+    return best;
+}
+
+int plan_auto(const sig_ctx *ctx, int64_t B, int64_t L, int stream_flag, const RowShape &rs, sig_plan_t *pl)
+{
+    const int cus = ctx ? ctx->num_cu : kDefaultCUs;
+    const int64_t K = L - 1;
+    const int64_t want_lanes = (int64_t)cus * kThreads;  // one wave per SIMD
+    *pl = sig_plan_t{};
+    pl->threads = kThreads;
+
+    const OnChipKernelInfo *ki = (B > 0) ? pick_on_chip(rs.d, rs.depth, B, want_lanes) : nullptr;
+    if (ki) {
+        pl->variant = SIG_VARIANT_ON_CHIP;
+        pl->prefix_depth = ki->p;
+        pl->chunks = 1;
+        pl->segments = 1;
+        const int Q = ki->lanes_per_chunk;
+        if (Q <= kThreads) {
+            // cut time into pieces only as far as needed to fill the chip
+            int64_t pieces = ceil_div(want_lanes, B * Q);
+            int64_t max_pieces = K / kMinChunkSteps;
+            if (max_pieces < 1) max_pieces = 1;
+            if (pieces > max_pieces) pieces = max_pieces;
+            int64_t cmax = kThreads / Q;                                  // chunks side by side in a workgroup
+            int64_t clds = (kMaxLdsBytes / 2) / (rs.D * (int64_t)sizeof(float));  // half of LDS for chunk signatures
+            if (cmax > clds) cmax = clds;
+            if (cmax < 1) cmax = 1;
+            int64_t C = pieces < cmax ? pieces : cmax;
+            int64_t W = stream_flag ? 1 : ceil_div(pieces, C);
+            if (W > 16) W = 16;
+            if (rs.D * (int64_t)sizeof(float) > kMaxLdsBytes) W = 1;
+            pl->chunks = (int)C;
+            pl->segments = (int)W;
+        }
+        OnChipArgs args{};
+        if (finish_on_chip(ki, B, L, stream_flag, *pl, rs, &args)) {
+            pl->tile_steps = args.tile_steps;
+            return SIG_OK;
+        }
+        // fall through to the streaming family
+        *pl = sig_plan_t{};
+        pl->threads = kThreads;
+    }
+    pl->variant = SIG_VARIANT_HBM_STREAMING;
+    pl->chunks = 1;
+    pl->segments = 1;
+    pl->tile_steps = 0;
+    // cut the index space until there are enough workgroups, but keep at least one level to the workgroup
+    int p = 0;
+    const int64_t want_wgs = 4 * (int64_t)cus;
+    while (p < rs.depth - 1 && B * rs.pow[p] < want_wgs && rs.pow[rs.depth - p - 1] >= 4 * kThreads) ++p;
+    pl->prefix_depth = p;
+    if (B * rs.pow[p] > INT32_MAX) return SIG_ERR_TOO_LARGE;
+    return SIG_OK;
+}
+
+int ensure_scratch(sig_ctx *ctx, size_t bytes)
+{
+    if (bytes <= ctx->scratch_bytes) return SIG_OK;
+    if (ctx->scratch) {
+        // earlier launches on the caller's stream may still read the old buffer
+        if (hipDeviceSynchronize() != hipSuccess) return SIG_ERR_HIP;
+        (void)hipFree(ctx->scratch);
+        ctx->scratch = nullptr;
+        ctx->scratch_bytes = 0;
+    }
+    void *p = nullptr;
+    if (hipMalloc(&p, bytes) != hipSuccess) {
+        (void)hipGetLastError();
+        return SIG_ERR_ALLOC;
+    }
+    ctx->scratch = static_cast<float *>(p);
+    ctx->scratch_bytes = bytes;
+    return SIG_OK;
+}
+
+int run_plan(sig_ctx *ctx, const float *path, int64_t B, int64_t L, const RowShape &rs, int stream_flag,
+             float *out, const sig_plan_t &pl, hipStream_t st)
+{
+    if (pl.variant == SIG_VARIANT_HBM_STREAMING) {
+        if (pl.prefix_depth < 0 || pl.prefix_depth > rs.depth - 1) return SIG_ERR_INVALID;
+        if (pl.threads < kWave || pl.threads > 256 || pl.threads % kWave) return SIG_ERR_INVALID;
+        if (B * rs.pow[pl.prefix_depth] > INT32_MAX) return SIG_ERR_TOO_LARGE;
+        hipError_t e = launch_hbm_streaming(path, out, B, L, rs, pl.prefix_depth, stream_flag, pl.threads, st);
+        return e == hipSuccess ? SIG_OK : SIG_ERR_HIP;
+    }
+    if (pl.variant != SIG_VARIANT_ON_CHIP) return SIG_ERR_INVALID;
+    const OnChipKernelInfo *ki = find_on_chip(rs.d, rs.depth, pl.prefix_depth);
+    if (!ki) return SIG_ERR_INVALID;
+    OnChipArgs args{};
+    if (!finish_on_chip(ki, B, L, stream_flag, pl, rs, &args)) return SIG_ERR_INVALID;
+    args.path = path;
+    args.out = out;
+    args.partial = nullptr;
+    if (pl.segments > 1) {
+        size_t bytes = (size_t)B * pl.segments * rs.D * sizeof(float);
+        int rc = ensure_scratch(ctx, bytes);
+        if (rc != SIG_OK) return rc;
+        args.partial = ctx->scratch;
+    }
+    hipError_t e = ki->launch(args, st);
+    if (e != hipSuccess) return SIG_ERR_HIP;
+    if (pl.segments > 1) {
+        e = launch_join_segments(ctx->scratch, out, B, pl.segments, rs, st);
+        if (e != hipSuccess) return SIG_ERR_HIP;
+    }
+    return SIG_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int64_t sig_size(int d, int depth)
+{
+    if (d < 1 || depth < 1) return -1;
+    int64_t total = 0, p = 1;
+    for (int n = 1; n <= depth; ++n) {
+        if (p > INT64_MAX / d) return -1;
+        p *= d;
+        if (total > INT64_MAX - p) return -1;
+        total += p;
+    }
+    return total;
+}
+
+int sig_create(sig_ctx **ctx)
+{
+    if (!ctx) return SIG_ERR_INVALID;
+    *ctx = nullptr;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) {
+        (void)hipGetLastError();
+        return SIG_ERR_NO_DEVICE;
+    }
+    int cus = 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) {
+        (void)hipGetLastError();
+        return SIG_ERR_NO_DEVICE;
+    }
+    sig_ctx *c = new (std::nothrow) sig_ctx;
+    if (!c) return SIG_ERR_ALLOC;
+    c->device = dev;
+    c->num_cu = cus;
+    c->scratch = nullptr;
+    c->scratch_bytes = 0;
+    *ctx = c;
+    return SIG_OK;
+}
+
+void sig_destroy(sig_ctx *ctx)
+{
+    if (!ctx) return;
+    if (ctx->scratch) {
+        (void)hipDeviceSynchronize();
+        (void)hipFree(ctx->scratch);
+    }
+    delete ctx;
+}
+
+int sig_plan(const sig_ctx *ctx, int64_t B, int64_t L, int d, int depth, int stream_flag, sig_plan_t *plan)
+{
+    if (!plan) return SIG_ERR_INVALID;
+    RowShape rs;
+    int rc = check_shape(B, L, d, depth, stream_flag, &rs);
+    if (rc != SIG_OK) return rc;
+    return plan_auto(ctx, B, L, stream_flag, rs, plan);
+}
+
+int sig_plan_validate(int64_t B, int64_t L, int d, int depth, int stream_flag, const sig_plan_t *plan)
+{
+    if (!plan) return SIG_ERR_INVALID;
+    RowShape rs;
+    int rc = check_shape(B, L, d, depth, stream_flag, &rs);
+    if (rc != SIG_OK) return rc;
+    if (plan->variant == SIG_VARIANT_HBM_STREAMING) {
+        if (plan->prefix_depth < 0 || plan->prefix_depth > rs.depth - 1) return SIG_ERR_INVALID;
+        if (plan->threads < kWave || plan->threads > 256 || plan->threads % kWave) return SIG_ERR_INVALID;
+        if (B * rs.pow[plan->prefix_depth] > INT32_MAX) return SIG_ERR_TOO_LARGE;
+        return SIG_OK;
+    }
+    if (plan->variant != SIG_VARIANT_ON_CHIP) return SIG_ERR_INVALID;
+    const OnChipKernelInfo *ki = find_on_chip(rs.d, rs.depth, plan->prefix_depth);
+    OnChipArgs args{};
+    if (!ki || !finish_on_chip(ki, B, L, stream_flag, *plan, rs, &args)) return SIG_ERR_INVALID;
+    return SIG_OK;
+}
+
+int sig_compute_planned(sig_ctx *ctx, const float *path, int64_t B, int64_t L, int d, int depth,
+                        int stream_flag, float *out, const sig_plan_t *plan, void *hip_stream)
+{
+    if (!ctx || !plan) return SIG_ERR_INVALID;
+    RowShape rs;
+    int rc = check_shape(B, L, d, depth, stream_flag, &rs);
+    if (rc != SIG_OK) return rc;
+    if (B == 0) return SIG_OK;
+    if (!path || !out) return SIG_ERR_INVALID;
+    return run_plan(ctx, path, B, L, rs, stream_flag, out, *plan, static_cast<hipStream_t>(hip_stream));
+}
+
+int sig_compute(sig_ctx *ctx, const float *path, int64_t B, int64_t L, int d, int depth,
+                int stream_flag, float *out, void *hip_stream)
+{
+    if (!ctx) return SIG_ERR_INVALID;
+    RowShape rs;
+    int rc = check_shape(B, L, d, depth, stream_flag, &rs);
+    if (rc != SIG_OK) return rc;
+    if (B == 0) return SIG_OK;
+    if (!path || !out) return SIG_ERR_INVALID;
+    sig_plan_t pl;
+    rc = plan_auto(ctx, B, L, stream_flag, rs, &pl);
+    if (rc != SIG_OK) return rc;
+    return run_plan(ctx, path, B, L, rs, stream_flag, out, pl, static_cast<hipStream_t>(hip_stream));
+}
+
+int sig_combine(sig_ctx *ctx, const float *a, const float *b, int64_t B, int d, int depth,
+                float *out, void *hip_stream)
+{
+    if (!ctx || B < 0 || d < 1 || depth < 1) return SIG_ERR_INVALID;
+    RowShape rs;
+    if (depth > kMaxDepth || !make_row_shape(d, depth, &rs)) return SIG_ERR_TOO_LARGE;
+    if (B == 0) return SIG_OK;
+    if (!a || !b || !out) return SIG_ERR_INVALID;
+    hipError_t e = launch_combine_rows(a, rs.D, b, rs.D, out, rs.D, B, rs, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? SIG_OK : SIG_ERR_HIP;
+}
+
+int sig_on_chip_available(int d, int depth, int prefix_depth)
+{
+    return find_on_chip(d, depth, prefix_depth) ? 1 : 0;
+}
+
+const char *sig_strerror(int status)
+{
+    switch (status) {
+    case SIG_OK: return "ok";
+    case SIG_ERR_INVALID: return "invalid argument or plan";
+    case SIG_ERR_TOO_LARGE: return "shape too large for the supported index range";
+    case SIG_ERR_ALLOC: return "allocation of scratch memory failed";
+    case SIG_ERR_HIP: return "a HIP call or kernel launch failed";
+    case SIG_ERR_NO_DEVICE: return "no usable HIP device";
+    default: return "unknown status";
+    }
+}
+
+}  // extern "C"

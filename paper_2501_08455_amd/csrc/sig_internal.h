@@ -1,0 +1,75 @@
+// Internal declarations shared by the host API and the kernel translation units of libsig.
+// Nothing here is part of the C ABI (that is include/sig.h).
+#ifndef SIG_INTERNAL_H
+#define SIG_INTERNAL_H
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "sig.h"
+
+namespace sig {
+
+constexpr int kMaxDepth = 30;        // d^depth must also fit in int32
+constexpr int kWave = 64;
+constexpr int kMaxLdsBytes = 64 * 1024;  // per-workgroup LDS this library asks for at most
+constexpr int kLoaderStage = 8;          // floats of the next increment tile one thread holds in registers
+
+// Offsets of the levels inside an output row (Eq. 10: level 0 dropped): level n starts at
+// d + ... + d^{n-1} and holds d^n floats.
+struct RowShape {
+    int d;
+    int depth;
+    int64_t D;                      // row length
+    int64_t pow[kMaxDepth + 2];     // pow[n] = d^n
+    int64_t off[kMaxDepth + 2];     // off[n] = start of level n (n >= 1), off[depth + 1] = D
+};
+
+// returns false if d^depth or D overflow the supported range
+bool make_row_shape(int d, int depth, RowShape *rs);
+
+// ---------------------------------------------------------------- HBM-streaming family (any d, depth)
+// One workgroup per (path, sub-tree of prefix depth p); the state is the output row itself.
+hipError_t launch_hbm_streaming(const float *path, float *out, int64_t B, int64_t L, const RowShape &rs,
+                                int p, int stream_flag, int threads, hipStream_t st);
+
+// out[b] = a[b] (x) b[b] on rows of D floats (Eq. 4 with implied level 0 = 1); strides in floats.
+hipError_t launch_combine_rows(const float *a, int64_t a_stride, const float *b, int64_t b_stride,
+                               float *out, int64_t out_stride, int64_t B, const RowShape &rs,
+                               hipStream_t st);
+
+// out[b] = partial[b][0] (x) partial[b][1] (x) ... (x) partial[b][W-1], rows of D floats, D*8 <= kMaxLdsBytes
+hipError_t launch_join_segments(const float *partial, float *out, int64_t B, int W, const RowShape &rs,
+                                hipStream_t st);
+
+// ---------------------------------------------------------------- on-chip family (compiled (d, depth, p) only)
+struct OnChipArgs {
+    const float *path;   // [B][L][d]
+    float *out;          // final: [B][D]; stream: [B][K][D]
+    float *partial;      // [B][segments][D] scratch when segments > 1, else unused
+    int64_t B;
+    int64_t L;
+    int32_t chunks;      // C: time chunks per (path, segment) folded side by side in one workgroup
+    int32_t segments;    // W: workgroups per path along time
+    int32_t chunk_steps; // T: increments per chunk; segments * chunks * T >= L - 1
+    int32_t tile_steps;  // TT: increments per LDS tile
+    int32_t threads;     // workgroup size
+    int32_t groups;      // (path, segment) pairs per workgroup (1 when a chunk's lanes span several workgroups)
+    int32_t stream_flag;
+};
+
+struct OnChipKernelInfo {
+    int d, depth, p;
+    int lanes_per_chunk;                       // Q = d^p
+    int state_floats;                          // registers of state per lane
+    hipError_t (*launch)(const OnChipArgs &, hipStream_t);
+    // LDS bytes the launch needs for these arguments (for validation before launching)
+    int64_t (*lds_bytes)(const OnChipArgs &);
+};
+
+// table of compiled on-chip kernels; terminated by an entry with launch == nullptr
+const OnChipKernelInfo *on_chip_table();
+const OnChipKernelInfo *find_on_chip(int d, int depth, int p);
+
+}  // namespace sig
+#endif

@@ -1,0 +1,28 @@
+// Table of the compiled on-chip kernels: one entry per (d, depth, prefix depth).
+#include "sig_onchip.h"
+
+namespace sig {
+
+namespace {
+const OnChipKernelInfo kTable[] = {
+    SIG_ON_CHIP_ENTRY(2, 3, 0),
+    SIG_ON_CHIP_ENTRY(2, 3, 1),
+    SIG_ON_CHIP_ENTRY(4, 4, 1),
+    SIG_ON_CHIP_ENTRY(4, 4, 2),
+    SIG_ON_CHIP_ENTRY(5, 4, 1),
+    SIG_ON_CHIP_ENTRY(5, 4, 2),
+    SIG_ON_CHIP_ENTRY(10, 6, 4),
+    {0, 0, 0, 0, 0, nullptr, nullptr},
+};
+}  // namespace
+
+const OnChipKernelInfo *on_chip_table() { return kTable; }
+
+const OnChipKernelInfo *find_on_chip(int d, int depth, int p)
+{
+    for (const OnChipKernelInfo *e = kTable; e->launch; ++e)
+        if (e->d == d && e->depth == depth && e->p == p) return e;
+    return nullptr;
+}
+
+}  // namespace sig

@@ -1,0 +1,272 @@
+// HBM-streaming kernels: any (d, depth), state in device memory.
+//
+//   sig_hbm_streaming_kernel  the fused multiply-by-exponential of Eq. 3 applied increment by
+//                             increment to state that lives in the output rows themselves
+//   sig_combine_rows_kernel   batched truncated product of Eq. 4
+//   sig_join_segments_kernel  left-to-right product of the partial signatures of one path
+//
+// Writing out (S (x) exp(v))[w] for a word w = (i_1 .. i_n) with Eqs. 2 and 4 gives
+//   S'[w] = S[w] + sum_{m=0}^{n-1} S[w_{1:m}] * v[i_{m+1}] ... v[i_n] / (n - m)!      (S[empty] = 1)
+// i.e. the new coefficient of w needs only the old coefficients of the prefixes of w.  In
+// Horner form:  g_0 = 1,  g_m = S[w_{1:m}] + g_{m-1} * v[i_m] / (n - m + 1)  (m = 1 .. n-1),
+//               S'[w] = S[w] + g_{n-1} * v[i_n].
+// Two consequences used here: (i) the words below a fixed prefix u form a sub-tree that evolves
+// on its own, given the few scalars S[u_{1:m}], so sub-trees go to different workgroups with no
+// communication; (ii) updating levels from depth down to 1 may be done in place.
+#include "sig_internal.h"
+
+namespace sig {
+
+namespace {
+
+struct StreamingParams {
+    const float *path;
+    float *out;
+    int64_t L;
+    int64_t D;
+    int d;
+    int depth;
+    int p;          // prefix depth of the sub-tree a workgroup owns
+    int stream;     // 0: in place in out[b]; 1: row k is written from row k-1
+    int tile_steps; // increments staged in LDS at a time
+    uint32_t ntiles;             // d^p
+    uint32_t pw[kMaxDepth + 1];  // d^n
+    int64_t off[kMaxDepth + 2];  // start of level n in a row
+};
+
+// Dynamic LDS: [tile_steps][d] increments.
+extern __shared__ float sig_smem[];
+
+__global__ __launch_bounds__(256) void sig_hbm_streaming_kernel(StreamingParams P)
+{
+    __shared__ float pre[kMaxDepth + 1];   // pre[m] = S[u_{1:m}], m = 1..p (old values during a step)
+    __shared__ int ulet[kMaxDepth + 1];    // ulet[m] = letter u_m
+
+    const int d = P.d, depth = P.depth, p = P.p;
+    const uint32_t tile = blockIdx.x % P.ntiles;   // u as a number in base d
+    const int64_t b = blockIdx.x / P.ntiles;
+    const int tid = threadIdx.x, nthr = blockDim.x;
+    const int64_t K = P.L - 1;
+    const float *X = P.path + b * P.L * d;
+    float *sh_delta = sig_smem;
+
+    if (tid == 0) {
+        uint32_t rest = tile;
+        for (int m = p; m >= 1; --m) { ulet[m] = (int)(rest % (uint32_t)d); rest /= (uint32_t)d; }
+        for (int m = 0; m <= p; ++m) pre[m] = 0.0f;
+    }
+    __syncthreads();
+
+    for (int64_t k = 0; k < K; ++k) {
+        const int kt = (int)(k % P.tile_steps);
+        if (kt == 0) {
+            // coalesced loader: consecutive threads read consecutive floats of the path
+            int64_t steps = K - k < P.tile_steps ? K - k : P.tile_steps;
+            int64_t n = steps * d;
+            __syncthreads();
+            for (int64_t i = tid; i < n; i += nthr) sh_delta[i] = X[k * d + i + d] - X[k * d + i];
+            __syncthreads();
+        }
+        const float *dl = sh_delta + kt * d;
+        const bool first = (k == 0);  // the state before the first increment is the identity: all levels >= 1 are 0
+        const float *src = P.stream ? P.out + (b * K + (first ? 0 : k - 1)) * P.D : P.out + b * P.D;
+        float *dst = P.stream ? P.out + (b * K + k) * P.D : P.out + b * P.D;
+
+        for (int n = depth; n > p; --n) {
+            // one work item = one parent word (u, v) of length n-1; it updates its d children
+            const uint32_t nparents = P.pw[n - 1 - p];
+            for (uint32_t v = tid; v < nparents; v += nthr) {
+                float g = 1.0f;
+                for (int m = 1; m <= p; ++m) g = fmaf(g, dl[ulet[m]] * (1.0f / (float)(n - m + 1)), pre[m]);
+                for (int m = p + 1; m <= n - 1; ++m) {
+                    uint32_t idx = v / P.pw[n - 1 - m];          // (u, v)_{1:m} inside the sub-tree level m
+                    int letter = (int)(idx % (uint32_t)d);
+                    float Sm = first ? 0.0f : src[P.off[m] + (int64_t)tile * P.pw[m - p] + idx];
+                    g = fmaf(g, dl[letter] * (1.0f / (float)(n - m + 1)), Sm);
+                }
+                const int64_t base = P.off[n] + ((int64_t)tile * nparents + v) * d;
+                for (int a = 0; a < d; ++a) {
+                    float old = first ? 0.0f : src[base + a];
+                    dst[base + a] = fmaf(g, dl[a], old);
+                }
+            }
+            // in place: level n-1 may only be overwritten after every reader of it at level n is done
+            if (!P.stream) __syncthreads();
+        }
+        __syncthreads();
+        if (tid == 0) {
+            // the words u_{1:n}, n = p .. 1, shared by every sub-tree with this prefix; kept per workgroup
+            for (int n = p; n >= 1; --n) {
+                float g = 1.0f;
+                for (int m = 1; m <= n - 1; ++m) g = fmaf(g, dl[ulet[m]] * (1.0f / (float)(n - m + 1)), pre[m]);
+                pre[n] = fmaf(g, dl[ulet[n]], pre[n]);
+                // exactly one sub-tree (remaining letters all 0) writes the shared word to the row
+                uint32_t span = P.pw[p - n];
+                if (tile % span == 0) dst[P.off[n] + tile / span] = pre[n];
+            }
+        }
+        __syncthreads();
+    }
+}
+
+struct CombineParams {
+    const float *a;
+    const float *b;
+    float *out;
+    int64_t a_stride, b_stride, out_stride;
+    int64_t D;
+    int d;
+    int depth;
+    uint32_t pw[kMaxDepth + 1];
+    int64_t off[kMaxDepth + 2];
+};
+
+// one thread per output word:  c_n[w] = a_n[w] + b_n[w] + sum_{i=1}^{n-1} a_i[w / d^{n-i}] * b_{n-i}[w mod d^{n-i}]
+__global__ __launch_bounds__(256) void sig_combine_rows_kernel(CombineParams P)
+{
+    const int64_t row = blockIdx.y;
+    const int64_t pos = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (pos >= P.D) return;
+    const float *a = P.a + row * P.a_stride;
+    const float *b = P.b + row * P.b_stride;
+    int n = 1;
+    while (pos >= P.off[n + 1]) ++n;
+    const uint32_t w = (uint32_t)(pos - P.off[n]);
+    float c = a[pos] + b[pos];
+    for (int i = 1; i < n; ++i) {
+        uint32_t split = P.pw[n - i];
+        c = fmaf(a[P.off[i] + w / split], b[P.off[n - i] + w % split], c);
+    }
+    P.out[row * P.out_stride + pos] = c;
+}
+
+struct JoinParams {
+    const float *partial;  // [B][W][D]
+    float *out;            // [B][D]
+    int W;
+    int D;
+    int d;
+    int depth;
+    int pw[kMaxDepth + 1];
+    int off[kMaxDepth + 2];
+};
+
+// One workgroup per path; the running product sits in LDS and is multiplied from the right by
+// each further partial signature.  Levels are processed from depth down to 1 so that the
+// update can be done in place (level n of the product needs levels < n of the left factor, which
+// are still the old ones, and its own old level-n entry).
+__global__ __launch_bounds__(256) void sig_join_segments_kernel(JoinParams P)
+{
+    float *acc = sig_smem;  // [D]
+    const int64_t b = blockIdx.x;
+    const int tid = threadIdx.x, nthr = blockDim.x;
+    const float *part = P.partial + b * P.W * (int64_t)P.D;
+    for (int i = tid; i < P.D; i += nthr) acc[i] = part[i];
+    __syncthreads();
+    for (int j = 1; j < P.W; ++j) {
+        const float *r = part + (int64_t)j * P.D;
+        for (int n = P.depth; n >= 1; --n) {
+            const int sz = P.pw[n];
+            for (int w = tid; w < sz; w += nthr) {
+                float c = acc[P.off[n] + w] + r[P.off[n] + w];
+                for (int i = 1; i < n; ++i) {
+                    int split = P.pw[n - i];
+                    c = fmaf(acc[P.off[i] + w / split], r[P.off[n - i] + w % split], c);
+                }
+                acc[P.off[n] + w] = c;
+            }
+            __syncthreads();
+        }
+    }
+    float *o = P.out + b * (int64_t)P.D;
+    for (int i = tid; i < P.D; i += nthr) o[i] = acc[i];
+}
+
+}  // namespace
+
+bool make_row_shape(int d, int depth, RowShape *rs)
+{
+    if (d < 1 || depth < 1 || depth > kMaxDepth) return false;
+    rs->d = d;
+    rs->depth = depth;
+    int64_t p = 1, total = 0;
+    rs->pow[0] = 1;
+    for (int n = 1; n <= depth; ++n) {
+        if (p > (int64_t)INT32_MAX / d) return false;  // d^n must fit in int32
+        p *= d;
+        rs->pow[n] = p;
+        rs->off[n] = total;
+        total += p;
+    }
+    rs->off[depth + 1] = total;
+    rs->pow[depth + 1] = 0;
+    rs->D = total;
+    return true;
+}
+
+hipError_t launch_hbm_streaming(const float *path, float *out, int64_t B, int64_t L, const RowShape &rs,
+                                int p, int stream_flag, int threads, hipStream_t st)
+{
+    StreamingParams P;
+    P.path = path;
+    P.out = out;
+    P.L = L;
+    P.D = rs.D;
+    P.d = rs.d;
+    P.depth = rs.depth;
+    P.p = p;
+    P.stream = stream_flag;
+    int tile = 8192 / rs.d;
+    if (tile > 64) tile = 64;
+    if (tile < 1) tile = 1;
+    P.tile_steps = tile;
+    P.ntiles = (uint32_t)rs.pow[p];
+    for (int n = 0; n <= rs.depth; ++n) P.pw[n] = (uint32_t)rs.pow[n];
+    for (int n = 1; n <= rs.depth + 1; ++n) P.off[n] = rs.off[n];
+    P.off[0] = 0;
+    int64_t grid = B * rs.pow[p];
+    if (grid <= 0 || grid > INT32_MAX) return hipErrorInvalidValue;
+    size_t lds = (size_t)tile * rs.d * sizeof(float);
+    hipLaunchKernelGGL(sig_hbm_streaming_kernel, dim3((unsigned)grid), dim3(threads), lds, st, P);
+    return hipGetLastError();
+}
+
+hipError_t launch_combine_rows(const float *a, int64_t a_stride, const float *b, int64_t b_stride,
+                               float *out, int64_t out_stride, int64_t B, const RowShape &rs,
+                               hipStream_t st)
+{
+    CombineParams P;
+    P.a = a; P.b = b; P.out = out;
+    P.a_stride = a_stride; P.b_stride = b_stride; P.out_stride = out_stride;
+    P.D = rs.D; P.d = rs.d; P.depth = rs.depth;
+    for (int n = 0; n <= rs.depth; ++n) P.pw[n] = (uint32_t)rs.pow[n];
+    for (int n = 1; n <= rs.depth + 1; ++n) P.off[n] = rs.off[n];
+    P.off[0] = 0;
+    int64_t gx = (rs.D + 255) / 256;
+    if (gx > INT32_MAX) return hipErrorInvalidValue;
+    // grid.y is limited to 65535 workgroups: walk the batch in slabs
+    for (int64_t b0 = 0; b0 < B; b0 += 65535) {
+        int64_t nb = B - b0 < 65535 ? B - b0 : 65535;
+        CombineParams Q = P;
+        Q.a += b0 * a_stride; Q.b += b0 * b_stride; Q.out += b0 * out_stride;
+        hipLaunchKernelGGL(sig_combine_rows_kernel, dim3((unsigned)gx, (unsigned)nb), dim3(256), 0, st, Q);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+hipError_t launch_join_segments(const float *partial, float *out, int64_t B, int W, const RowShape &rs,
+                                hipStream_t st)
+{
+    if (rs.D * (int64_t)sizeof(float) > kMaxLdsBytes || B > INT32_MAX) return hipErrorInvalidValue;
+    JoinParams P;
+    P.partial = partial; P.out = out; P.W = W; P.D = (int)rs.D; P.d = rs.d; P.depth = rs.depth;
+    for (int n = 0; n <= rs.depth; ++n) P.pw[n] = (int)rs.pow[n];
+    for (int n = 1; n <= rs.depth + 1; ++n) P.off[n] = (int)rs.off[n];
+    P.off[0] = 0;
+    hipLaunchKernelGGL(sig_join_segments_kernel, dim3((unsigned)B), dim3(256), (size_t)rs.D * sizeof(float), st, P);
+    return hipGetLastError();
+}
+
+}  // namespace sig

@@ -1,0 +1,111 @@
+"""CPU-only checks of the C-ABI library: it loads, exports what include/sig.h declares, and its
+host-only entry points (sizes, planner, error strings) behave."""
+import os
+import re
+
+import pytest
+
+from paper_2501_08455_amd import binding, workloads
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "sig.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(sig_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = binding.load()
+    names = declared_functions()
+    assert {"sig_create", "sig_compute", "sig_destroy", "sig_size", "sig_plan", "sig_compute_planned",
+            "sig_combine", "sig_strerror", "sig_on_chip_available"} <= set(names)
+    for name in names:
+        assert hasattr(lib, name), name
+
+
+@pytest.mark.parametrize("d,depth,D", [(2, 3, 14), (5, 4, 780), (4, 4, 340), (10, 6, 1111110), (10, 4, 11110),
+                                       (1, 7, 7), (3, 1, 3)])
+def test_sig_size(d, depth, D):
+    assert binding.sig_size(d, depth) == D == workloads.sig_size(d, depth)
+
+
+def test_sig_size_rejects_bad_or_overflowing_shapes():
+    assert binding.sig_size(0, 3) == -1
+    assert binding.sig_size(3, 0) == -1
+    assert binding.sig_size(10, 30) == -1
+
+
+def test_error_strings():
+    seen = {binding.sig_strerror(c) for c in range(6)}
+    assert len(seen) == 6 and all(seen)
+    assert binding.sig_strerror(99) == "unknown status"
+
+
+def test_plan_rejects_what_compute_rejects():
+    for args in [(-1, 5, 2, 3, 0), (4, 1, 2, 3, 0), (4, 5, 0, 3, 0), (4, 5, 2, 0, 0), (4, 5, 2, 3, 2)]:
+        rc, _ = binding.sig_plan(None, *args)
+        assert rc == binding.SIG_ERR_INVALID, args
+    rc, _ = binding.sig_plan(None, 4, 5, 10, 12, 0)
+    assert rc == binding.SIG_ERR_TOO_LARGE
+
+
+@pytest.mark.parametrize("name", ["C1", "C2", "C3", "C4", "C5"])
+def test_plan_of_the_five_configs_is_on_chip_and_consistent(name):
+    cfg = workloads.CONFIGS[name]
+    rc, pl = binding.sig_plan(None, cfg.B, cfg.L, cfg.d, cfg.depth, int(cfg.stream))
+    assert rc == binding.SIG_OK
+    assert pl.variant == binding.SIG_VARIANT_ON_CHIP
+    assert binding.sig_on_chip_available(cfg.d, cfg.depth, pl.prefix_depth)
+    K = cfg.L - 1
+    assert 1 <= pl.chunks * pl.segments <= K
+    assert pl.threads % 64 == 0 and 64 <= pl.threads <= 256
+    lanes = cfg.d ** pl.prefix_depth
+    assert lanes > pl.threads or pl.chunks * lanes <= pl.threads
+    if cfg.stream:
+        assert pl.segments == 1
+
+
+def test_plan_falls_back_to_streaming_for_uncompiled_shapes():
+    rc, pl = binding.sig_plan(None, 7, 30, 3, 5, 0)
+    assert rc == binding.SIG_OK and pl.variant == binding.SIG_VARIANT_HBM_STREAMING
+    assert 0 <= pl.prefix_depth <= 4
+
+
+def test_large_batches_are_not_cut_in_time():
+    rc, pl = binding.sig_plan(None, 65536, 100, 5, 4, 0)
+    assert rc == binding.SIG_OK and pl.chunks == 1 and pl.segments == 1
+
+
+def test_create_without_a_gpu_reports_no_device():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    with pytest.raises(binding.SigError) as err:
+        binding.sig_create()
+    assert err.value.status == binding.SIG_ERR_NO_DEVICE
+
+
+def test_every_forced_plan_of_the_gpu_tests_is_accepted_by_the_host_checks():
+    import importlib
+    cases = importlib.import_module("test_gpu_parity").ON_CHIP_CASES
+    for (d, depth, p, B, L, chunks, segments, tile, stream) in cases:
+        plan = binding.make_plan(binding.SIG_VARIANT_ON_CHIP, prefix_depth=p, chunks=chunks, segments=segments,
+                                 tile_steps=tile)
+        assert binding.sig_plan_validate(B, L, d, depth, int(stream), plan) == binding.SIG_OK, \
+            (d, depth, p, B, L, chunks, segments, tile, stream)
+
+
+def test_plan_validate_rejects_plans_the_kernels_cannot_run():
+    mk = binding.make_plan
+    on = binding.SIG_VARIANT_ON_CHIP
+    assert binding.sig_plan_validate(4, 16, 3, 3, 0, mk(on, prefix_depth=1)) == binding.SIG_ERR_INVALID  # not compiled
+    assert binding.sig_plan_validate(4, 16, 5, 4, 0, mk(on, prefix_depth=2, chunks=11)) == binding.SIG_ERR_INVALID
+    assert binding.sig_plan_validate(4, 16, 5, 4, 1, mk(on, prefix_depth=2, segments=2)) == binding.SIG_ERR_INVALID
+    assert binding.sig_plan_validate(4, 6, 5, 4, 0, mk(on, prefix_depth=2, chunks=3, segments=2)) == binding.SIG_ERR_INVALID
+    assert binding.sig_plan_validate(4, 16, 5, 4, 0, mk(on, prefix_depth=2, threads=100)) == binding.SIG_ERR_INVALID
+    assert binding.sig_plan_validate(4, 16, 5, 4, 0, mk(binding.SIG_VARIANT_HBM_STREAMING, prefix_depth=4)) \
+        == binding.SIG_ERR_INVALID
+    assert binding.sig_plan_validate(4, 16, 5, 4, 0, mk(binding.SIG_VARIANT_HBM_STREAMING, prefix_depth=3)) \
+        == binding.SIG_OK

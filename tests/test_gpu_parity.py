@@ -1,0 +1,194 @@
+"""GPU parity: libsig (through the C ABI binding) against the fp64 oracle, element by element.
+
+Gate (per level n): ||gpu_n - oracle_n||_F / ||oracle_n||_F <= 1e-4, the norm taken over
+every emitted row of the call.  A stricter per-row figure is printed for information.
+"""
+import sys
+
+import numpy as np
+import pytest
+
+from paper_2501_08455_amd import workloads
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-4
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2501_08455_amd import binding
+    binding.load()
+    return binding
+
+
+def say(msg):
+    print(msg)
+    sys.stdout.flush()
+
+
+def level_errors(got, want, d, depth):
+    got = np.asarray(got, dtype=np.float64).reshape(-1, got.shape[-1])
+    want = want.reshape(-1, want.shape[-1])
+    errs, start = [], 0
+    for n in range(1, depth + 1):
+        sl = slice(start, start + d ** n)
+        num = np.linalg.norm(got[:, sl] - want[:, sl])
+        den = np.linalg.norm(want[:, sl])
+        errs.append(num / den if den > 0 else num)
+        start += d ** n
+    return errs
+
+
+def run_gpu(gpu, x, depth, stream, plan=None):
+    import torch
+    xt = torch.from_numpy(x).cuda()
+    out = gpu.signature(xt, depth, stream=stream, plan=plan)
+    torch.cuda.synchronize()
+    return out.cpu().numpy()
+
+
+def check(gpu, oracle, x, depth, stream, plan=None, label=""):
+    say("case %s shape=%s depth=%d stream=%s plan=%s" % (label, x.shape, depth, stream,
+                                                        plan.as_dict() if plan is not None else "auto"))
+    got = run_gpu(gpu, x, depth, stream, plan)
+    want = oracle.signature(x, depth, stream=stream)
+    assert got.shape == want.shape
+    assert np.all(np.isfinite(got))
+    errs = level_errors(got, want, x.shape[2], depth)
+    say("  per-level rel err: " + " ".join("%.2e" % e for e in errs))
+    assert max(errs) <= TOL, errs
+    return got
+
+
+# ---------------------------------------------------------------- the five configurations, automatic plan
+@pytest.mark.parametrize("name", ["C1", "C2", "C3", "C4", "C5"])
+def test_config_auto_plan(gpu, oracle, name):
+    cfg = workloads.CONFIGS[name]
+    x = workloads.make_paths(cfg)
+    check(gpu, oracle, x, cfg.depth, cfg.stream, label=name)
+
+
+# ---------------------------------------------------------------- HBM-streaming family on shapes with and without compiled kernels
+@pytest.mark.parametrize("B,L,d,depth,stream,p", [
+    (4, 16, 2, 3, False, 0), (4, 16, 2, 3, True, 1), (3, 9, 3, 5, False, 2), (3, 9, 3, 5, True, 0),
+    (2, 40, 5, 4, False, 1), (2, 40, 5, 4, True, 3), (5, 7, 1, 6, False, 0), (5, 7, 1, 6, True, 0),
+    (2, 12, 7, 2, False, 1), (2, 12, 6, 1, True, 0), (1, 130, 2, 10, False, 3), (2, 70, 4, 4, True, 2),
+    (1, 20, 10, 5, False, 2), (3, 2, 3, 4, False, 0), (3, 2, 3, 4, True, 1),
+])
+def test_hbm_streaming_family(gpu, oracle, B, L, d, depth, stream, p):
+    rng = np.random.default_rng(1000 + B + L + d + depth)
+    x = np.cumsum(rng.normal(0, 0.3, size=(B, L, d)), axis=1).astype(np.float32)
+    plan = gpu.make_plan(gpu.SIG_VARIANT_HBM_STREAMING, prefix_depth=p)
+    check(gpu, oracle, x, depth, stream, plan, label="hbm")
+
+
+def test_uncompiled_shapes_fall_back(gpu, oracle):
+    for (B, L, d, depth) in [(3, 33, 3, 4), (2, 17, 6, 3), (130, 5, 2, 5)]:
+        rc, pl = gpu.sig_plan(None, B, L, d, depth, 0)
+        assert rc == 0 and pl.variant == gpu.SIG_VARIANT_HBM_STREAMING
+        x = workloads.brownian_paths(B, L, d, seed=77 + d)
+        check(gpu, oracle, x, depth, False, label="fallback")
+        check(gpu, oracle, x, depth, True, label="fallback-stream")
+
+
+# ---------------------------------------------------------------- on-chip family: every compiled kernel, several time cuttings
+ON_CHIP_CASES = [
+    # d, depth, p, B, L, chunks, segments, tile_steps, stream
+    (2, 3, 0, 300, 16, 1, 1, 0, False), (2, 3, 0, 7, 41, 4, 2, 3, False), (2, 3, 0, 5, 41, 5, 1, 0, True),
+    (2, 3, 1, 4, 16, 1, 1, 0, False), (2, 3, 1, 4, 16, 1, 1, 0, True), (2, 3, 1, 9, 100, 7, 3, 4, False),
+    (2, 3, 1, 3, 100, 9, 1, 5, True),
+    (4, 4, 1, 70, 37, 1, 1, 0, False), (4, 4, 1, 70, 37, 1, 1, 5, True), (4, 4, 1, 3, 256, 8, 4, 0, False),
+    (4, 4, 1, 5, 256, 16, 1, 0, True), (4, 4, 2, 64, 256, 16, 1, 0, True), (4, 4, 2, 3, 100, 3, 5, 7, False),
+    (4, 4, 2, 20, 50, 1, 1, 0, True),
+    (5, 4, 1, 128, 100, 1, 1, 0, False), (5, 4, 1, 60, 23, 1, 1, 3, True), (5, 4, 1, 2, 333, 10, 4, 0, False),
+    (5, 4, 1, 3, 90, 6, 1, 0, True),
+    (5, 4, 2, 128, 100, 10, 1, 0, False), (5, 4, 2, 128, 100, 5, 2, 4, False), (5, 4, 2, 11, 100, 1, 1, 0, False),
+    (5, 4, 2, 2, 2000, 10, 16, 0, False), (5, 4, 2, 4, 61, 4, 1, 0, True), (5, 4, 2, 13, 30, 1, 1, 0, True),
+    (10, 6, 4, 2, 9, 1, 1, 0, False), (10, 6, 4, 1, 4, 1, 1, 2, True),
+]
+
+
+@pytest.mark.parametrize("d,depth,p,B,L,chunks,segments,tile,stream", ON_CHIP_CASES)
+def test_on_chip_family(gpu, oracle, d, depth, p, B, L, chunks, segments, tile, stream):
+    assert gpu.sig_on_chip_available(d, depth, p)
+    x = workloads.brownian_paths(B, L, d, seed=5000 + 17 * B + L + chunks)
+    plan = gpu.make_plan(gpu.SIG_VARIANT_ON_CHIP, prefix_depth=p, chunks=chunks, segments=segments,
+                         tile_steps=tile)
+    check(gpu, oracle, x, depth, stream, plan, label="on-chip")
+
+
+def test_single_increment_and_repeated_points(gpu, oracle):
+    x = workloads.brownian_paths(6, 2, 5, seed=3)
+    check(gpu, oracle, x, 4, False, label="L=2")
+    check(gpu, oracle, x, 4, True, label="L=2 stream")
+    y = workloads.brownian_paths(3, 20, 4, seed=4)
+    y[:, 5] = y[:, 4]
+    y[:, 11:14] = y[:, 10:11]
+    check(gpu, oracle, y, 4, True, label="repeated points")
+
+
+def test_error_codes_and_empty_batch(gpu):
+    import torch
+    ctx = gpu.default_ctx()
+    x = torch.zeros((2, 5, 3), device="cuda")
+    out = torch.zeros((2, gpu.sig_size(3, 2)), device="cuda")
+    assert gpu.sig_compute(ctx, x, 2, 0, out) == gpu.SIG_OK
+    assert gpu.sig_compute(ctx, x, 0, 0, out) == gpu.SIG_ERR_INVALID
+    assert gpu.sig_compute(ctx, x, 2, 2, out) == gpu.SIG_ERR_INVALID
+    assert gpu.sig_compute(ctx, x[:, :1].contiguous(), 2, 0, out) == gpu.SIG_ERR_INVALID
+    assert gpu.sig_compute(ctx, x, 40, 0, out) == gpu.SIG_ERR_TOO_LARGE
+    assert gpu.sig_compute(None, x, 2, 0, out) == gpu.SIG_ERR_INVALID
+    empty = torch.zeros((0, 5, 3), device="cuda")
+    assert gpu.sig_compute(ctx, empty, 2, 0, out) == gpu.SIG_OK
+    bad = gpu.make_plan(gpu.SIG_VARIANT_ON_CHIP, prefix_depth=1, chunks=1, segments=1)
+    assert gpu.sig_compute(ctx, x, 2, 0, out, plan=bad) == gpu.SIG_ERR_INVALID  # (3, 2) has no on-chip kernel
+    torch.cuda.synchronize()
+
+
+def test_runs_are_bitwise_reproducible(gpu):
+    for name in ["C2", "C4"]:
+        cfg = workloads.CONFIGS[name]
+        x = workloads.make_paths(cfg)
+        a = run_gpu(gpu, x, cfg.depth, cfg.stream)
+        b = run_gpu(gpu, x, cfg.depth, cfg.stream)
+        np.testing.assert_array_equal(a, b)
+
+
+def test_sig_combine_matches_eq4(gpu, oracle):
+    import torch
+    d, depth, B = 3, 4, 37
+    D = gpu.sig_size(d, depth)
+    rng = np.random.default_rng(9)
+    a = rng.normal(size=(B, D)).astype(np.float32)
+    b = rng.normal(size=(B, D)).astype(np.float32)
+    out = torch.empty((B, D), device="cuda")
+    rc = gpu.sig_combine(gpu.default_ctx(), torch.from_numpy(a).cuda(), torch.from_numpy(b).cuda(), d, depth, out)
+    assert rc == gpu.SIG_OK
+    torch.cuda.synchronize()
+    want = np.stack([oracle.tensor_mul(np.concatenate([[1.0], a[i]]), np.concatenate([[1.0], b[i]]), d, depth)[1:]
+                     for i in range(B)])
+    assert max(level_errors(out.cpu().numpy(), want, d, depth)) <= 1e-5
+
+
+# ---------------------------------------------------------------- batch-saturated variants, checked on a sample of paths
+@pytest.mark.parametrize("name,B", [("C2", 65536), ("C3", 4096), ("C4", 4096), ("C1", 1 << 20)])
+def test_saturated_variants_sampled(gpu, oracle, name, B):
+    import torch
+    cfg = workloads.CONFIGS[name]
+    x = workloads.make_paths(cfg, B=B, seed=99)
+    say("case %s-sat B=%d" % (name, B))
+    xt = torch.from_numpy(x).cuda()
+    out = gpu.signature(xt, cfg.depth, stream=cfg.stream)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(5)
+    pick = np.sort(rng.choice(B, size=128, replace=False))
+    pick[0], pick[-1] = 0, B - 1
+    got = out[torch.from_numpy(pick).cuda()].cpu().numpy()
+    want = oracle.signature(x[pick], cfg.depth, stream=cfg.stream)
+    errs = level_errors(got, want, cfg.d, cfg.depth)
+    say("  per-level rel err: " + " ".join("%.2e" % e for e in errs))
+    assert max(errs) <= TOL
