@@ -84,8 +84,8 @@ def cpu_baseline(workloads, cfg, max_paths, budget_s=20.0):
     import numpy as np
     import oracle
     oracle.build()
-    x = workloads.make_paths(cfg)
-    n = min(cfg.B, max_paths)
+    n = max_paths
+    x = workloads.make_paths(cfg, B=n)
     xs = x[:n]
     oracle.signature(xs[:1], cfg.depth, stream=cfg.stream)  # load the library
     times = []
@@ -96,7 +96,7 @@ def cpu_baseline(workloads, cfg, max_paths, budget_s=20.0):
         times.append(time.perf_counter() - t0)
     t = float(np.median(times))
     return {"value": n / t, "unit": "paths/s", "cores": oracle.num_threads(), "kind": "oracle",
-            "sample": "%d of %d paths of the workload, median of %d runs, %.4f s per run" % (n, cfg.B, len(times), t)}
+            "sample": "%d paths of the workload's shape, median of %d runs, %.4f s per run" % (n, len(times), t)}
 
 
 def main():
@@ -105,6 +105,8 @@ def main():
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--no-extras", action="store_true", help="skip the other configurations")
+    ap.add_argument("--workload", default="C2", help="configuration to time as the headline (C1..C5)")
+    ap.add_argument("--batch", type=int, default=0, help="override the batch size (batch-saturated variants)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -121,10 +123,12 @@ def main():
     binding.load()
     ctx = binding.default_ctx()
 
-    cfg = workloads.CONFIGS["C2"]
-    head = bench_config(binding, workloads, ctx, cfg, cfg.B, args.steps, args.warmup)
+    cfg = workloads.CONFIGS[args.workload]
+    B = args.batch or cfg.B
+    head = bench_config(binding, workloads, ctx, cfg, B, args.steps, args.warmup)
     line = {
-        "metric": "signatures/sec at (B=128, L=100, d=5, N=4), final signature",
+        "metric": "signatures/sec at (B=%d, L=%d, d=%d, N=%d), %s" % (
+            B, cfg.L, cfg.d, cfg.depth, "every prefix (stream)" if cfg.stream else "final signature"),
         "value": head["paths_per_s"], "unit": "paths/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": head["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
@@ -134,7 +138,7 @@ def main():
         "roofline": head["roofline"],
     }
     if not args.no_cpu:
-        line["cpu_baseline"] = cpu_baseline(workloads, cfg, max_paths=cfg.B)
+        line["cpu_baseline"] = cpu_baseline(workloads, cfg, max_paths=min(B, 128))
     if not args.no_extras:
         extras = []
         plan = [("C1", None, 500), ("C3", None, 300), ("C4", None, 300), ("C5", None, 50),
