@@ -23,15 +23,16 @@ def time_calls(binding, ctx, xt, depth, stream_flag, out, steps, warmup, plan=No
     """Mean milliseconds per sig_compute call over `steps` back-to-back calls, from HIP events on the
     stream the kernels are launched on (torch's current stream) and from the host clock."""
     import torch
+    call = binding.bind_compute(ctx, xt, depth, stream_flag, out, plan=plan)  # arguments marshalled once
     for _ in range(warmup):
-        rc = binding.sig_compute(ctx, xt, depth, stream_flag, out, plan=plan)
+        rc = call()
         assert rc == 0, rc
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
     e0.record()
     for _ in range(steps):
-        rc = binding.sig_compute(ctx, xt, depth, stream_flag, out, plan=plan)
+        rc = call()
     e1.record()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
@@ -79,6 +80,30 @@ def bench_config(binding, workloads, ctx, cfg, B, steps, warmup):
     return res
 
 
+def anchors(binding):
+    """Achievable rates on this GPU: a plain copy (HBM) and an fp32 FMA loop without packed instructions."""
+    import torch
+    n = 1 << 28  # 1 GiB each way
+    src = torch.ones(n, dtype=torch.float32, device="cuda")
+    dst = torch.empty_like(src)
+    out = torch.empty(8192 * 64, dtype=torch.float32, device="cuda")
+    res = {}
+    for name, fn, work in [("copy_GBps", lambda: binding.sig_probe_copy(dst, src), 8.0 * n / 1e9),
+                           ("fma_TFLOPs", lambda: binding.sig_probe_fma(out, 8192, 20000),
+                            2.0 * 16 * 20000 * 8192 * 64 / 1e12)]:
+        for _ in range(3):
+            assert fn() == 0
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(10):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        res[name] = work / (e0.elapsed_time(e1) / 10 * 1e-3)
+    return res
+
+
 def cpu_baseline(workloads, cfg, max_paths, budget_s=20.0):
     """The fp64 oracle on the host cores, on (a sample of) the same workload."""
     import numpy as np
@@ -105,6 +130,7 @@ def main():
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--no-extras", action="store_true", help="skip the other configurations")
+    ap.add_argument("--anchors", action="store_true", help="also measure the copy and FMA-loop anchors")
     ap.add_argument("--workload", default="C2", help="configuration to time as the headline (C1..C5)")
     ap.add_argument("--batch", type=int, default=0, help="override the batch size (batch-saturated variants)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
@@ -147,6 +173,8 @@ def main():
             c = workloads.CONFIGS[name]
             extras.append(bench_config(binding, workloads, ctx, c, B or c.B, steps, 5))
         line["all_configs"] = extras
+    if args.anchors:
+        line["anchors"] = anchors(binding)
     print(json.dumps(line))
 
 

@@ -1,0 +1,34 @@
+/*
+ * sig_probe.h -- two measurement anchors that ship with libsig.  They are not part of the
+ * signature transform; callers are benchmarks and profiling runs that need (a) a copy kernel
+ * of known size, to calibrate the HBM byte counters and to measure the achievable HBM rate, and
+ * (b) an FMA loop of known flop count, to measure the achievable fp32 vector rate without packed
+ * instructions (every translation unit of this library is built with packed fp32 switched off).
+ * Same conventions as sig.h: DEVICE pointers, hipStream_t passed as void*, status codes of enum
+ * sig_status, nothing synchronises.
+ */
+#ifndef SIG_PROBE_H
+#define SIG_PROBE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* dst[i] = src[i] for n_floats floats (n_floats % 4 == 0, both 16-byte aligned); reads and writes 4*n_floats bytes each. */
+int sig_probe_copy(float *dst, const float *src, int64_t n_floats, void *hip_stream);
+
+/*
+ * Every lane of `waves` wavefronts (workgroups of 4) runs `iters` rounds of 16 fp32 FMAs arranged as
+ * `ilp` independent dependency chains (1, 2, 4, 8 or 16) and stores one float to out[lane id]
+ * (out: DEVICE, waves * 64 floats).  `lds_bytes` (0 .. 65536) of dynamic LDS are requested per
+ * workgroup only to limit how many workgroups share a compute unit.
+ * Flops = 2 * 16 * iters * waves * 64.
+ */
+int sig_probe_fma(float *out, int64_t waves, int64_t iters, int ilp, int lds_bytes, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -69,6 +69,10 @@ def load():
     lib.sig_combine.argtypes = [vp, vp, vp, i64, i32, i32, vp, vp]
     lib.sig_on_chip_available.restype = i32
     lib.sig_on_chip_available.argtypes = [i32, i32, i32]
+    lib.sig_probe_copy.restype = i32
+    lib.sig_probe_copy.argtypes = [vp, vp, i64, vp]
+    lib.sig_probe_fma.restype = i32
+    lib.sig_probe_fma.argtypes = [vp, i64, i64, i32, i32, vp]
     lib.sig_strerror.restype = ctypes.c_char_p
     lib.sig_strerror.argtypes = [i32]
     _lib = lib
@@ -135,10 +139,43 @@ def sig_compute(ctx, path, depth, stream_flag, out, stream=None, plan=None):
     return load().sig_compute_planned(*args, ctypes.byref(plan), _stream_handle(stream))
 
 
+def bind_compute(ctx, path, depth, stream_flag, out, stream=None, plan=None):
+    """Marshal the arguments of one sig_compute / sig_compute_planned call once and return a
+    zero-argument callable that issues it (for tight loops: no per-call tensor introspection)."""
+    lib = load()
+    B, L, d = path.shape
+    args = [ctx, ctypes.c_void_p(path.data_ptr()), ctypes.c_int64(B), ctypes.c_int64(L), ctypes.c_int(d),
+            ctypes.c_int(int(depth)), ctypes.c_int(int(stream_flag)), ctypes.c_void_p(out.data_ptr())]
+    if plan is None:
+        fn = lib.sig_compute
+    else:
+        fn = lib.sig_compute_planned
+        args.append(ctypes.byref(plan))
+    args.append(_stream_handle(stream))
+    args = tuple(args)
+    keep = (path, out, plan)
+
+    def call(_fn=fn, _args=args, _keep=keep):
+        return _fn(*_args)
+    return call
+
+
 def sig_combine(ctx, a, b, d, depth, out, stream=None):
     return load().sig_combine(ctx, ctypes.c_void_p(a.data_ptr()), ctypes.c_void_p(b.data_ptr()),
                               a.shape[0], int(d), int(depth), ctypes.c_void_p(out.data_ptr()),
                               _stream_handle(stream))
+
+
+def sig_probe_copy(dst, src, stream=None):
+    """Copy kernel of include/sig_probe.h on two equally sized float32 CUDA tensors."""
+    return load().sig_probe_copy(ctypes.c_void_p(dst.data_ptr()), ctypes.c_void_p(src.data_ptr()),
+                                 src.numel(), _stream_handle(stream))
+
+
+def sig_probe_fma(out, waves, iters, ilp=16, lds_bytes=0, stream=None):
+    """FMA loop of include/sig_probe.h; `out` holds waves * 64 floats."""
+    return load().sig_probe_fma(ctypes.c_void_p(out.data_ptr()), int(waves), int(iters), int(ilp), int(lds_bytes),
+                                _stream_handle(stream))
 
 
 # ---------------------------------------------------------------- convenience on top of the raw calls

@@ -17,7 +17,8 @@ namespace {
 
 constexpr int kDefaultCUs = 256;
 constexpr int kThreads = 256;
-constexpr int kMinChunkSteps = 8;   // do not cut time finer than this: every cut costs one Eq. 4 product
+constexpr int kMinChunkSteps = 8;          // chunks inside a workgroup are at least this long
+constexpr int kMinSegmentChunkSteps = 32;  // ... and this long before time is also cut across workgroups
 
 int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
@@ -63,32 +64,50 @@ bool finish_on_chip(const OnChipKernelInfo *ki, int64_t B, int64_t L, int stream
     // groups per workgroup: as many as the threads hold, fewer if their chunk signatures overflow LDS
     int G = Q > pl.threads ? 1 : pl.threads / (pl.chunks * Q);
     if (pl.chunks > 1) {
-        int64_t fit = (kMaxLdsBytes * 3 / 4) / ((int64_t)pl.chunks * rs.D * (int64_t)sizeof(float));
+        // two buffers of chunk signatures (the second one half as large in final mode)
+        const int64_t per_group = (int64_t)(stream_flag ? 2 * pl.chunks : pl.chunks + (pl.chunks + 1) / 2) *
+                                  rs.D * (int64_t)sizeof(float);
+        int64_t fit = (kMaxLdsBytes - 4096) / per_group;
         if (fit < 1) return false;
         if (G > fit) G = (int)fit;
     }
+    if ((int64_t)G > B * pl.segments) G = (int)(B * pl.segments);  // a tiny batch does not fill a workgroup
     args->groups = G;
-    // tile: bounded by the loader's registers (kLoaderStage floats per thread) and, if asked, by the plan
+    // Tile of staged increments.  The whole chunk in one tile if it fits the tile budget; otherwise two
+    // tiles (double buffer), each short enough for the budget and for the registers that hold the next
+    // tile in flight (kLoaderStage floats per thread over rows padded to a power of two).
     const int64_t ngc = (int64_t)G * pl.chunks;
-    int64_t tt = (kLoaderStage * (int64_t)pl.threads) / (ngc * ki->d);
-    if (tt < 1) return false;
-    if (tt > args->chunk_steps) tt = args->chunk_steps;
-    if (pl.tile_steps > 0 && pl.tile_steps < tt) tt = pl.tile_steps;
+    const int64_t T = args->chunk_steps;
+    int64_t tt = T;
+    const bool forced = pl.tile_steps > 0 && pl.tile_steps < T;
+    if (forced) tt = pl.tile_steps;
+    if (forced || ngc * T * ki->d * (int64_t)sizeof(float) > kTileLdsBytes) {
+        int64_t by_lds = kTileLdsBytes / (2 * ngc * ki->d * (int64_t)sizeof(float));
+        int64_t row_pow2 = 1;
+        while (row_pow2 * 2 * ngc <= (int64_t)kLoaderStage * pl.threads) row_pow2 *= 2;
+        int64_t by_regs = row_pow2 / ki->d;
+        if (tt > by_lds) tt = by_lds;
+        if (tt > by_regs) tt = by_regs;
+        if (tt < 1) return false;
+    }
     args->tile_steps = (int)tt;
-    while (args->tile_steps > 1 && ki->lds_bytes(*args) > kMaxLdsBytes) args->tile_steps /= 2;
+    int shift = 0;
+    while (((int64_t)1 << shift) < tt * ki->d) ++shift;
+    args->row_shift = shift;
     if (ki->lds_bytes(*args) > kMaxLdsBytes) return false;
     return true;
 }
 
-// Smallest compiled prefix depth for (d, depth), or the next one up when more lanes are needed.
-const OnChipKernelInfo *pick_on_chip(int d, int depth, int64_t B, int64_t want_lanes)
+// Which compiled prefix depth to use for (d, depth).  A wavefront issues a vector instruction only every
+// five to six cycles, so the fp32 rate needs several wavefronts per SIMD: prefer the smallest prefix
+// depth whose per-lane state leaves room for four of them (<= 96 floats of state), else the deepest one.
+const OnChipKernelInfo *pick_on_chip(int d, int depth)
 {
     const OnChipKernelInfo *best = nullptr;
     for (const OnChipKernelInfo *e = on_chip_table(); e->launch; ++e) {
         if (e->d != d || e->depth != depth) continue;
         if (!best) { best = e; continue; }
-        // entries are ordered by increasing prefix depth: move up only while the batch alone cannot fill the chip
-        if (B * best->lanes_per_chunk < want_lanes) best = e;
+        if (best->state_floats > 96) best = e;  // entries are ordered by increasing prefix depth
     }
     return best;
 }
@@ -97,11 +116,11 @@ int plan_auto(const sig_ctx *ctx, int64_t B, int64_t L, int stream_flag, const R
 {
     const int cus = ctx ? ctx->num_cu : kDefaultCUs;
     const int64_t K = L - 1;
-    const int64_t want_lanes = (int64_t)cus * kThreads;  // one wave per SIMD
+    const int64_t want_lanes = (int64_t)cus * 4 * 4 * kWave;  // four wavefronts on every SIMD
     *pl = sig_plan_t{};
     pl->threads = kThreads;
 
-    const OnChipKernelInfo *ki = (B > 0) ? pick_on_chip(rs.d, rs.depth, B, want_lanes) : nullptr;
+    const OnChipKernelInfo *ki = (B > 0) ? pick_on_chip(rs.d, rs.depth) : nullptr;
     if (ki) {
         pl->variant = SIG_VARIANT_ON_CHIP;
         pl->prefix_depth = ki->p;
@@ -109,19 +128,23 @@ int plan_auto(const sig_ctx *ctx, int64_t B, int64_t L, int stream_flag, const R
         pl->segments = 1;
         const int Q = ki->lanes_per_chunk;
         if (Q <= kThreads) {
-            // cut time into pieces only as far as needed to fill the chip
+            // cut time into pieces only as far as needed to fill the chip; every cut costs one Eq. 4 product
             int64_t pieces = ceil_div(want_lanes, B * Q);
-            int64_t max_pieces = K / kMinChunkSteps;
-            if (max_pieces < 1) max_pieces = 1;
-            if (pieces > max_pieces) pieces = max_pieces;
-            int64_t cmax = kThreads / Q;                                  // chunks side by side in a workgroup
-            int64_t clds = (kMaxLdsBytes / 2) / (rs.D * (int64_t)sizeof(float));  // half of LDS for chunk signatures
+            int64_t cmax = kThreads / Q;  // chunks side by side in a workgroup
+            int64_t clds = (kMaxLdsBytes - kTileLdsBytes) / (2 * rs.D * (int64_t)sizeof(float));  // two signature buffers
             if (cmax > clds) cmax = clds;
+            if (cmax > K / kMinChunkSteps) cmax = K / kMinChunkSteps;
             if (cmax < 1) cmax = 1;
             int64_t C = pieces < cmax ? pieces : cmax;
-            int64_t W = stream_flag ? 1 : ceil_div(pieces, C);
-            if (W > 16) W = 16;
-            if (rs.D * (int64_t)sizeof(float) > kMaxLdsBytes) W = 1;
+            // further workgroups along time only while each chunk keeps a long sequential run
+            int64_t W = 1;
+            if (!stream_flag && rs.D * (int64_t)sizeof(float) <= kMaxLdsBytes) {
+                W = ceil_div(pieces, C);
+                int64_t wmax = K / (C * kMinSegmentChunkSteps);
+                if (W > wmax) W = wmax;
+                if (W > 16) W = 16;
+                if (W < 1) W = 1;
+            }
             pl->chunks = (int)C;
             pl->segments = (int)W;
         }

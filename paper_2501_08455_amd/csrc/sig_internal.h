@@ -13,7 +13,8 @@ namespace sig {
 constexpr int kMaxDepth = 30;        // d^depth must also fit in int32
 constexpr int kWave = 64;
 constexpr int kMaxLdsBytes = 64 * 1024;  // per-workgroup LDS this library asks for at most
-constexpr int kLoaderStage = 8;          // floats of the next increment tile one thread holds in registers
+constexpr int kTileLdsBytes = 19968;     // LDS the increment tile(s) of one workgroup may take (8 workgroups share 160 KB)
+constexpr int kLoaderStage = 8;          // floats of the next tile one thread holds in registers when tiles are pipelined
 
 // Offsets of the levels inside an output row (Eq. 10: level 0 dropped): level n starts at
 // d + ... + d^{n-1} and holds d^n floats.
@@ -55,6 +56,7 @@ struct OnChipArgs {
     int32_t tile_steps;  // TT: increments per LDS tile
     int32_t threads;     // workgroup size
     int32_t groups;      // (path, segment) pairs per workgroup (1 when a chunk's lanes span several workgroups)
+    int32_t row_shift;   // log2 of the padded length of one chunk's stretch of a tile (tile_steps * d floats)
     int32_t stream_flag;
 };
 
@@ -62,6 +64,7 @@ struct OnChipKernelInfo {
     int d, depth, p;
     int lanes_per_chunk;                       // Q = d^p
     int state_floats;                          // registers of state per lane
+    int row_floats;                            // LDS floats per staged increment (= d)
     hipError_t (*launch)(const OnChipArgs &, hipStream_t);
     // LDS bytes the launch needs for these arguments (for validation before launching)
     int64_t (*lds_bytes)(const OnChipArgs &);

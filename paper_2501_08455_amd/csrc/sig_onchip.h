@@ -1,4 +1,4 @@
-// On-chip (register-resident) signature kernel, compiled per (d, depth N, prefix depth P).
+// On-chip (register-resident) signature kernels, compiled per (d, depth N, prefix depth P).
 //
 // Lane ownership.  By the prefix-closure of the fused update (see sig_streaming.hip: the new
 // coefficient of a word needs only old coefficients of its prefixes) the words below a fixed
@@ -7,22 +7,29 @@
 // P-1 scalars S[u_{1:m}] it shares with its neighbours and recomputes redundantly.  Q = d^P
 // lanes cover one (path, time chunk); no lane ever needs another lane's registers.
 //
+// Occupancy.  One wavefront issues a vector instruction only every five to six cycles on this
+// chip, so the fp32 rate needs three or more wavefronts per SIMD; the kernels are split by mode
+// (final / stream, one chunk / several) so that each keeps its register count low.
+//
 // Time.  A path's K = L-1 increments are cut into `segments` (one workgroup each) times `chunks`
 // (side by side inside a workgroup) pieces of `chunk_steps` increments.  Every piece is folded from
 // the identity with the fused step of Eq. 3; pieces are joined with the product of Eq. 4, which
-// is associative, in LDS (tree for the final signature, left-to-right scan for stream mode where
-// every piece is then folded a second time from its carry-in while emitting each prefix).
+// is associative, in LDS (pairwise tree for the final signature, left-to-right scan for stream
+// mode, where every piece is then folded a second time from its carry-in while emitting each prefix).
 //
-// Loader.  Increments are staged through LDS: the workgroup reads the path with consecutive
-// threads on consecutive floats, subtracts neighbouring points and stores rows of one increment
-// each, double-buffered with the next tile's global loads in flight during the current tile's
-// arithmetic.
+// Loader.  Increments are staged through LDS one tile of `tile_steps` steps at a time: the
+// workgroup reads the path with consecutive lanes on consecutive floats, subtracts neighbouring
+// points and stores one row per step.
 #ifndef SIG_ONCHIP_H
 #define SIG_ONCHIP_H
 
 #include <type_traits>
 
 #include "sig_internal.h"
+
+#ifndef SIG_STEP_UNROLL
+#define SIG_STEP_UNROLL 1
+#endif
 
 namespace sig {
 namespace onchip {
@@ -34,30 +41,34 @@ constexpr int cpow(int b, int e)
     return r;
 }
 
-constexpr int kStage = kLoaderStage;
+constexpr int geom(int d, int terms)  // 1 + d + ... + d^(terms-1)
+{
+    int s = 0, p = 1;
+    for (int i = 0; i < terms; ++i) { s += p; p *= d; }
+    return s;
+}
 
 template <int d, int N, int P>
 struct Shape {
     static_assert(P >= 0 && P < N, "prefix depth must leave at least one level to the lane");
     static constexpr int R = N - P;       // levels below the prefix word
     static constexpr int Q = cpow(d, P);  // lanes per (path, chunk)
-    static constexpr int sub_off(int r)   // start of sub-level r (level P + r) in the lane's state
-    {
-        int s = 0, p = 1;
-        for (int i = 0; i < r; ++i) { s += p; p *= d; }
-        return s;
-    }
-    static constexpr int SZ = sub_off(R + 1);
+    static constexpr int sub_off(int r) { return geom(d, r); }  // start of sub-level r (level P + r) in the lane's state
+    static constexpr int SZ = geom(d, R + 1);
     static constexpr int NPRE = P > 1 ? P - 1 : 1;
-    static constexpr int row_off(int n)   // start of level n >= 1 in an output row
-    {
-        int s = 0, p = d;
-        for (int i = 1; i < n; ++i) { s += p; p *= d; }
-        return s;
-    }
-    static constexpr int D = row_off(N + 1);
-    static constexpr int DP = (d + 3) / 4 * 4;  // LDS row of one increment, padded to float4
+    static constexpr int row_off(int n) { return geom(d, n) - 1; }  // start of level n >= 1 in an output row
+    static constexpr int D = geom(d, N + 1) - 1;
 };
+
+// compile-time loop: f(std::integral_constant<int, I>) for I in [B, E)
+template <int I, int E, class F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    if constexpr (I < E) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, E>(f);
+    }
+}
 
 // registers of one lane: s = the sub-tree below its prefix word u (sub-level r at sub_off(r)),
 // pre[m-1] = S[u_{1:m}] for m = 1 .. P-1
@@ -69,14 +80,14 @@ struct Lane {
 
 // ------------------------------------------------------------------------------------------
 // Fused step  S <- S (x) exp^N(v)  on one lane's sub-tree (Eq. 3 with Eqs. 2 and 4 expanded, Horner form).
-//   dls[c-1][a] = v[a] / c ;  du[m-1] = v[u_m]
+//   row[a] = v[a] (LDS);  dls[c-1][a] = v[a] / c;  du[m-1] = v[u_m]
 // Level n is updated from g_{n-1}, where g_0 = 1 and g_m[w a] = S_m[w a] + g_{m-1}[w] v[a] / (n - m + 1).
 // Levels go from N down to 1 so that the old lower levels are still in place when needed.
 template <int d, int N, int P, int n, int r>
 struct Descend {
     using Sh = Shape<d, N, P>;
     // g belongs to the word (u, v) where v has index idx in sub-level r
-    static __device__ __forceinline__ void run(float (&s)[Sh::SZ], const float (&dls)[N][d], float g, int idx)
+    static __device__ __forceinline__ void run(float (&s)[Sh::SZ], const float (&dls)[Sh::R][d], float g, int idx)
     {
         constexpr int tgt = n - P;  // sub-level being updated
 #pragma unroll
@@ -84,6 +95,10 @@ struct Descend {
             const int child = idx * d + a;
             if constexpr (r + 1 == tgt) {
                 s[Sh::sub_off(tgt) + child] = fmaf(g, dls[0][a], s[Sh::sub_off(tgt) + child]);
+            } else if constexpr (r == 0) {
+                // a single parent: scale it once (hoisted out of the loop over a) instead of scaling v
+                float g2 = fmaf(g * (1.0f / (float)(tgt - r)), dls[0][a], s[Sh::sub_off(r + 1) + child]);
+                Descend<d, N, P, n, r + 1>::run(s, dls, g2, child);
             } else {
                 float g2 = fmaf(g, dls[tgt - r - 1][a], s[Sh::sub_off(r + 1) + child]);
                 Descend<d, N, P, n, r + 1>::run(s, dls, g2, child);
@@ -96,7 +111,7 @@ template <int d, int N, int P, int n>
 struct Level {
     using Sh = Shape<d, N, P>;
     static __device__ __forceinline__ void run(float (&s)[Sh::SZ], float (&pre)[Sh::NPRE],
-                                               const float (&dls)[N][d], const float (&du)[P > 0 ? P : 1])
+                                               const float (&dls)[Sh::R][d], const float (&du)[P > 0 ? P : 1])
     {
         float g = 1.0f;
         constexpr int mtop = (n - 1 < P) ? n - 1 : P;
@@ -115,31 +130,37 @@ struct Level {
     }
 };
 
-template <int d, int N, int P>
-__device__ __forceinline__ void fused_step(Lane<d, N, P> &ln, const float *row, const int *letter)
-{
-    float dls[N][d];
+// one staged increment as a lane needs it: all d components and the components at its own prefix letters
+template <int d, int P>
+struct Inc {
+    float v[d];
     float du[P > 0 ? P : 1];
+};
+
+template <int d, int P>
+__device__ __forceinline__ void load_inc(Inc<d, P> &inc, const float *row, const int *letter)
+{
 #pragma unroll
-    for (int a = 0; a < d; ++a) dls[0][a] = row[a];
+    for (int a = 0; a < d; ++a) inc.v[a] = row[a];
+    inc.du[0] = 0.0f;
 #pragma unroll
-    for (int c = 2; c <= N; ++c)
-#pragma unroll
-        for (int a = 0; a < d; ++a) dls[c - 1][a] = dls[0][a] * (1.0f / (float)c);
-    du[0] = 0.0f;
-#pragma unroll
-    for (int m = 0; m < P; ++m) du[m] = row[letter[m]];
-    Level<d, N, P, N>::run(ln.s, ln.pre, dls, du);
+    for (int m = 0; m < P; ++m) inc.du[m] = row[letter[m]];
 }
 
-// compile-time loop: f(std::integral_constant<int, I>) for I in [B, E)
-template <int I, int E, class F>
-__device__ __forceinline__ void static_for(F &&f)
+template <int d, int N, int P>
+__device__ __forceinline__ void fused_step(Lane<d, N, P> &ln, const Inc<d, P> &inc)
 {
-    if constexpr (I < E) {
-        f(std::integral_constant<int, I>{});
-        static_for<I + 1, E>(f);
-    }
+    using Sh = Shape<d, N, P>;
+    float dls[Sh::R][d];
+    // the scaled copies v/2 .. v/R cost a multiply each, which is cheaper than reading them from LDS
+    // (one LDS serves four SIMDs)
+#pragma unroll
+    for (int a = 0; a < d; ++a) dls[0][a] = inc.v[a];
+#pragma unroll
+    for (int c = 1; c < Sh::R; ++c)
+#pragma unroll
+        for (int a = 0; a < d; ++a) dls[c][a] = inc.v[a] * (1.0f / (float)(c + 1));
+    Level<d, N, P, N>::run(ln.s, ln.pre, dls, inc.du);
 }
 
 // write / read a lane's state to / from a row laid out like an output row
@@ -190,84 +211,100 @@ __device__ __forceinline__ void identity_state(Lane<d, N, P> &ln)
 }
 
 // ------------------------------------------------------------------------------------------
-// In-LDS product of Eq. 4 on rows of D floats, level by level from N down to 1 with a barrier
-// after each level, so it may overwrite one of its operands:
-//   c_n[w] = a_n[w] + b_n[w] + sum_{i=1}^{n-1} a_i[w / d^{n-i}] * b_{n-i}[w mod d^{n-i}]
-// Products are addressed as (pair index) -> rows; TO_LEFT stores c over a, else over b.
-template <int d, int N, int n, bool TO_LEFT, class PairRows>
-__device__ __forceinline__ void lds_product_levels(float *sig, int npairs, PairRows rows, int tid, int nthr)
-{
+// Product of Eq. 4 on rows of D floats:  c = a (x) b,  c not overlapping a or b.
+//   c_n[w] = a_n[w] + b_n[w] + sum_{i=1}^{n-1} a_i[w_{1:i}] * b_{n-i}[w_{i+1:n}]
+// One work item is a parent word v of length n-1 (levels n = 1..N, geom(d, N) items in all); it
+// produces the d children v.j: the a-factors depend on v only and the b-factors are contiguous in j.
+template <int d, int N>
+struct RowProduct {
     using Sh = Shape<d, N, 0>;
-    constexpr int sz = cpow(d, n);
-    const int items = npairs * sz;
-    for (int it = tid; it < items; it += nthr) {
-        const int w = it % sz;
-        const int pq = it / sz;
-        int ia, ib;
-        rows(pq, ia, ib);
-        float *a = sig + ia * Sh::D;
-        float *b = sig + ib * Sh::D;
-        float c = a[Sh::row_off(n) + w] + b[Sh::row_off(n) + w];
-        static_for<1, n>([&](auto ic) {
-            constexpr int i = decltype(ic)::value;
-            constexpr int split = cpow(d, n - i);
-            c = fmaf(a[Sh::row_off(i) + w / split], b[Sh::row_off(n - i) + w % split], c);
+    static constexpr int ITEMS = geom(d, N);
+
+    static __device__ __forceinline__ void item(const float *a, const float *b, float *c, int it)
+    {
+        static_for<1, N + 1>([&](auto nc) {
+            constexpr int n = decltype(nc)::value;
+            constexpr int start = geom(d, n - 1);
+            constexpr int cnt = cpow(d, n - 1);
+            if (it >= start && it < start + cnt) {
+                const int v = it - start;
+                float acc[d];
+#pragma unroll
+                for (int j = 0; j < d; ++j) acc[j] = a[Sh::row_off(n) + v * d + j] + b[Sh::row_off(n) + v * d + j];
+                static_for<1, n>([&](auto ic) {
+                    constexpr int i = decltype(ic)::value;
+                    constexpr int tail = cpow(d, n - 1 - i);  // words of length n-1-i between the prefix and j
+                    const float ai = a[Sh::row_off(i) + v / tail];
+                    const float *bs = b + Sh::row_off(n - i) + (v % tail) * d;
+#pragma unroll
+                    for (int j = 0; j < d; ++j) acc[j] = fmaf(ai, bs[j], acc[j]);
+                });
+#pragma unroll
+                for (int j = 0; j < d; ++j) c[Sh::row_off(n) + v * d + j] = acc[j];
+            }
         });
-        (TO_LEFT ? a : b)[Sh::row_off(n) + w] = c;
     }
-    __syncthreads();
-    if constexpr (n > 1) lds_product_levels<d, N, n - 1, TO_LEFT>(sig, npairs, rows, tid, nthr);
-}
+};
 
-extern __shared__ float sig_onchip_smem[];
+extern __shared__ __align__(16) float sig_onchip_smem[];
 
-template <int d, int N, int P, int MAXT>
-__global__ __launch_bounds__(MAXT) void sig_on_chip_kernel(OnChipArgs A)
+// per (group, chunk) of a workgroup: where its increments start in the path and how many it has
+struct ChunkDesc {
+    int64_t base;   // float offset of x[b][k_begin][0] in the path array
+    int32_t steps;  // valid increments of this chunk (0 for chunks beyond the path or the batch)
+    int32_t pad;
+};
+
+constexpr int kStage = kLoaderStage;  // floats of the next tile a thread holds in registers (PIPE kernels)
+
+// floats of LDS in front of the increment tiles (descriptors, 16 bytes each, even count)
+__host__ __device__ constexpr int desc_floats(int ngc) { return 4 * ((ngc + 1) / 2 * 2); }
+__host__ __device__ constexpr int round4(int x) { return (x + 3) / 4 * 4; }
+
+// CHUNKED: several time chunks per group, joined in LDS.  STREAM: every prefix is emitted.
+// PIPE: the chunk spans several LDS tiles; the next tile's global loads are kept in flight in
+// registers while the current tile is consumed (one barrier per tile).
+template <int d, int N, int P, bool CHUNKED, bool STREAM, bool PIPE>
+__global__ __launch_bounds__(256) void sig_on_chip_kernel(OnChipArgs A)
 {
     using Sh = Shape<d, N, P>;
     constexpr int Q = Sh::Q;
-    constexpr int DP = Sh::DP;
     constexpr int D = Sh::D;
 
     const int tid = threadIdx.x;
     const int nthr = blockDim.x;
     const int64_t K = A.L - 1;
-    const int C = A.chunks, W = A.segments, T = A.chunk_steps, TT = A.tile_steps;
-    const int64_t ngroups = A.B * W;  // (path, segment) pairs
+    const int C = CHUNKED ? A.chunks : 1;
+    const int W = A.segments, T = A.chunk_steps, TT = A.tile_steps;
+    const unsigned ngroups = (unsigned)(A.B * W);  // (path, segment) pairs; fits 31 bits (checked on the host)
 
     // ---- lane -> (group, chunk, prefix word)
     const bool big = Q > nthr;  // one chunk's lanes span several workgroups (then C == 1)
     int G, gi, c;
-    unsigned u;
-    int64_t group0;  // first group of this workgroup
+    unsigned u, group0;  // group0: first group of this workgroup
     bool active;
     if (!big) {
         const int LG = C * Q;
         G = A.groups;
         gi = tid / LG;
         const int rem = tid - gi * LG;
-        c = rem / Q;
+        c = CHUNKED ? rem / Q : 0;
         u = (unsigned)(rem - c * Q);
-        group0 = (int64_t)blockIdx.x * G;
+        group0 = blockIdx.x * (unsigned)G;
         active = gi < G && group0 + gi < ngroups;
         if (gi >= G) { gi = 0; c = 0; }
     } else {
-        const int NB = (Q + nthr - 1) / nthr;
+        const unsigned NB = (Q + nthr - 1) / nthr;
         G = 1;
         gi = 0;
         c = 0;
         group0 = blockIdx.x / NB;
-        u = (unsigned)((blockIdx.x % NB) * nthr + tid);
+        u = (blockIdx.x % NB) * nthr + tid;
         active = u < (unsigned)Q;
         if (!active) u = 0;
     }
     const int NGC = G * C;
     const int mygc = gi * C + c;
-    int64_t mygroup = group0 + gi;
-    if (mygroup >= ngroups) mygroup = ngroups - 1;
-    const int64_t b = mygroup / W;
-    const int seg = (int)(mygroup - b * W);
-    const int64_t k_begin = ((int64_t)seg * C + c) * T;
 
     int letter[P > 0 ? P : 1];
     letter[0] = 0;
@@ -277,155 +314,218 @@ __global__ __launch_bounds__(MAXT) void sig_on_chip_kernel(OnChipArgs A)
         for (int m = P - 1; m >= 0; --m) { letter[m] = (int)(rest % d); rest /= d; }
     }
 
-    // ---- LDS: two increment tiles, then the chunk signatures
-    const int tile_floats = NGC * TT * DP;
-    float *tile0 = sig_onchip_smem;
-    float *sigrows = sig_onchip_smem + 2 * tile_floats;  // [NGC][D], used when C > 1
+    // ---- LDS: chunk descriptors, one or two increment tiles, then (CHUNKED) the chunk signatures
+    ChunkDesc *desc = reinterpret_cast<ChunkDesc *>(sig_onchip_smem);
+    const int row_floats = TT * d;                      // one chunk's part of a tile, rows of d floats, unpadded
+    const int tile_floats = round4(NGC * row_floats);
+    float *tile0 = sig_onchip_smem + desc_floats(NGC);
+    float *sigA = tile0 + (PIPE ? 2 : 1) * tile_floats;  // [NGC][D]
+    (void)sigA;
 
-    // ---- loader.  Which floats of the path a thread stages does not depend on the tile, only the
-    // time offset does, so the address and the number of valid steps are worked out once.
-    float stage[kStage];
-    const float *src[kStage];  // x[b][k0][a] of this thread's element e for the first tile
-    int lim[kStage];           // element e is inside its chunk and inside the path while t0 < lim[e]
-    const int tile_elems = NGC * TT * d;  // <= kStage * nthr (checked on the host)
-#pragma unroll
-    for (int e = 0; e < kStage; ++e) {
-        const int idx = tid + e * nthr;
-        src[e] = A.path;
-        lim[e] = 0;
-        if (idx < tile_elems) {
-            const int gc = idx / (TT * d);
-            const int r = idx - gc * (TT * d);
-            const int t = r / d;
-            const int g2 = gc / C;
-            const int c2 = gc - g2 * C;
-            const int64_t grp = group0 + g2;
-            if (grp < ngroups) {
-                const int64_t b2 = grp / W;
-                const int64_t k0 = ((grp - b2 * W) * C + c2) * (int64_t)T + t;
-                int64_t left = K - k0;
-                if (left > T - t) left = T - t;
-                lim[e] = left > 0 ? (int)left : 0;
-                src[e] = A.path + (b2 * A.L + k0) * d + (r - t * d);
+    if (tid < NGC) {
+        const unsigned g2 = (unsigned)tid / (unsigned)C;
+        const unsigned c2 = (unsigned)tid - g2 * C;
+        const unsigned grp = group0 + g2;
+        ChunkDesc dsc;
+        dsc.base = 0;
+        dsc.steps = 0;
+        dsc.pad = 0;
+        if (grp < ngroups) {
+            const unsigned b2 = grp / (unsigned)W;
+            const int64_t k0 = (int64_t)((grp - b2 * W) * C + c2) * T;
+            int64_t left = K - k0;
+            if (left > T) left = T;
+            if (left > 0) {
+                dsc.steps = (int)left;
+                dsc.base = ((int64_t)b2 * A.L + k0) * d;
             }
         }
+        desc[tid] = dsc;
     }
-    auto fetch_tile = [&](int t0) {  // global -> registers
-#pragma unroll
-        for (int e = 0; e < kStage; ++e) {
-            float v = 0.0f;
-            if (t0 < lim[e]) {
-                const float *x = src[e] + (int64_t)t0 * d;
+
+    // Loader.  A tile is addressed as [chunk][r] with r < row_floats padded to a power of two
+    // (A.row_shift), so consecutive threads read consecutive floats of one chunk's stretch of the path.
+    const int rshift = A.row_shift;
+    const int rmask = (1 << rshift) - 1;
+    const int flat = NGC << rshift;
+    auto fetch_one = [&](int idx, int t0) -> float {
+        const int gc = idx >> rshift;
+        const int r = idx & rmask;
+        float v = 0.0f;
+        if (idx < flat && r < row_floats) {
+            const ChunkDesc dsc = desc[gc];
+            if (r < (dsc.steps - t0) * d) {
+                const float *x = A.path + dsc.base + (int64_t)t0 * d + r;
                 v = x[d] - x[0];
             }
-            stage[e] = v;
         }
+        return v;
     };
-    auto commit_tile = [&](float *tile) {  // registers -> LDS rows of DP floats
-#pragma unroll
-        for (int e = 0; e < kStage; ++e) {
-            const int idx = tid + e * nthr;
-            if (idx < tile_elems) {
-                const int row = idx / d;
-                tile[row * DP + (idx - row * d)] = stage[e];
-            }
-        }
+    auto put_one = [&](float *tile, int idx, float v) {
+        const int gc = idx >> rshift;
+        const int r = idx & rmask;
+        if (idx < flat && r < row_floats) tile[gc * row_floats + r] = v;
     };
 
     Lane<d, N, P> ln;
+    int64_t b = 0, k_begin = 0;
+    unsigned mygroup = 0;
+    if (active) {
+        mygroup = group0 + gi;
+        const unsigned bb = mygroup / (unsigned)W;
+        b = bb;
+        k_begin = (int64_t)((mygroup - bb * W) * C + c) * T;
+    }
 
     // fold this lane's chunk, optionally emitting every prefix (stream mode)
     auto fold_chunk = [&](auto emit_tag) {
         constexpr bool emit = decltype(emit_tag)::value;
-        const int ntile = (T + TT - 1) / TT;
-        fetch_tile(0);
-        commit_tile(tile0);
-        __syncthreads();
-        for (int i = 0; i < ntile; ++i) {
-            float *cur = tile0 + (i & 1) * tile_floats;
-            float *nxt = tile0 + ((i + 1) & 1) * tile_floats;
-            const bool more = i + 1 < ntile;
-            if (more) fetch_tile((i + 1) * TT);
-            const int steps = (T - i * TT < TT) ? T - i * TT : TT;
-            const float *row = cur + mygc * TT * DP;
-            for (int t = 0; t < steps; ++t, row += DP) {
-                fused_step<d, N, P>(ln, row, letter);
+        auto consume = [&](const float *tile, int t0) {
+            const int steps = (T - t0 < TT) ? T - t0 : TT;
+            const float *row = tile + mygc * row_floats;
+            Inc<d, P> inc;
+            for (int t = 0; t < steps; ++t, row += d) {
+                load_inc<d, P>(inc, row, letter);
+                fused_step<d, N, P>(ln, inc);
                 if constexpr (emit) {
-                    const int64_t k = k_begin + (int64_t)i * TT + t;
+                    const int64_t k = k_begin + t0 + t;
                     if (active && k < K) store_state<d, N, P>(A.out + (b * K + k) * D, u, ln);
                 }
             }
-            if (more) commit_tile(nxt);
+        };
+        if constexpr (!PIPE) {
+            for (int t0 = 0; t0 < T; t0 += TT) {
+                __syncthreads();
+                for (int idx = tid; idx < flat; idx += nthr) put_one(tile0, idx, fetch_one(idx, t0));
+                __syncthreads();
+                consume(tile0, t0);
+            }
+        } else {
+            float stage[kStage];  // flat <= kStage * nthr (checked on the host)
             __syncthreads();
+#pragma unroll
+            for (int e = 0; e < kStage; ++e) stage[e] = fetch_one(tid + e * nthr, 0);
+#pragma unroll
+            for (int e = 0; e < kStage; ++e) put_one(tile0, tid + e * nthr, stage[e]);
+            __syncthreads();
+            int buf = 0;
+            for (int t0 = 0; t0 < T; t0 += TT, buf ^= 1) {
+                const bool more = t0 + TT < T;
+                if (more) {
+#pragma unroll
+                    for (int e = 0; e < kStage; ++e) stage[e] = fetch_one(tid + e * nthr, t0 + TT);
+                }
+                consume(tile0 + buf * tile_floats, t0);
+                if (more) {
+#pragma unroll
+                    for (int e = 0; e < kStage; ++e) put_one(tile0 + (buf ^ 1) * tile_floats, tid + e * nthr, stage[e]);
+                }
+                __syncthreads();
+            }
         }
     };
 
     identity_state<d, N, P>(ln);
-    const bool stream = A.stream_flag != 0;
-    // with one chunk per path, stream mode is a single emitting fold
-    if (!(stream && C == 1)) fold_chunk(std::false_type{});
+    __syncthreads();  // descriptors visible
 
-    if (C == 1 && !stream) {
-        if (active) {
-            float *dst = (W == 1) ? A.out + b * D : A.partial + mygroup * D;
-            store_state<d, N, P>(dst, u, ln);
-        }
-        return;
-    }
-
-    // ---- several chunks per group: join them in LDS
-    if (C > 1) {
-        if (active) store_state<d, N, P>(sigrows + mygc * D, u, ln);
-        __syncthreads();
-    }
-
-    if (!stream) {
-        // pairwise tree: round with stride st joins chunk q*2st with chunk q*2st + st, result on the left
-        for (int st = 1; st < C; st <<= 1) {
-            const int per_group = (C - st + 2 * st - 1) / (2 * st);
-            auto rows = [=](int pq, int &ia, int &ib) {
-                const int g2 = pq / per_group;
-                const int q = pq - g2 * per_group;
-                ia = g2 * C + q * 2 * st;
-                ib = ia + st;
-            };
-            lds_product_levels<d, N, N, true>(sigrows, G * per_group, rows, tid, nthr);
-        }
-        for (int idx = tid; idx < G * D; idx += nthr) {
-            const int g2 = idx / D;
-            const int pos = idx - g2 * D;
-            const int64_t grp = group0 + g2;
-            if (grp < ngroups) {
-                float *dst = (W == 1) ? A.out + grp * D : A.partial + grp * D;
-                dst[pos] = sigrows[(g2 * C) * D + pos];
+    if constexpr (!CHUNKED) {
+        fold_chunk(std::integral_constant<bool, STREAM>{});
+        if constexpr (!STREAM) {
+            if (active) {
+                float *dst = (W == 1) ? A.out + b * D : A.partial + (int64_t)mygroup * D;
+                store_state<d, N, P>(dst, u, ln);
             }
         }
-        return;
+    } else {
+        using RP = RowProduct<d, N>;
+        fold_chunk(std::false_type{});
+        if (active) store_state<d, N, P>(sigA + mygc * D, u, ln);
+        float *sigB = sigA + NGC * D;  // second buffer: [G][(C+1)/2][D] (final) or [NGC][D] (stream)
+        __syncthreads();
+        if constexpr (!STREAM) {
+            // pairwise tree, ping-pong between the two buffers; order of the factors is kept
+            float *src = sigA, *dst = sigB;
+            int rows = C, src_stride = C, dst_stride = (C + 1) / 2;
+            while (rows > 1) {
+                const int pairs = rows / 2;
+                const int total = G * pairs * RP::ITEMS;
+                for (int x = tid; x < total; x += nthr) {
+                    const int pq = x / RP::ITEMS;
+                    const int it = x - pq * RP::ITEMS;
+                    const int g2 = pq / pairs;
+                    const int q = pq - g2 * pairs;
+                    const float *a = src + (g2 * src_stride + 2 * q) * D;
+                    RP::item(a, a + D, dst + (g2 * dst_stride + q) * D, it);
+                }
+                if (rows & 1) {  // odd row out: carried to the next round unchanged
+                    for (int x = tid; x < G * D; x += nthr) {
+                        const int g2 = x / D;
+                        const int pos = x - g2 * D;
+                        dst[(g2 * dst_stride + pairs) * D + pos] = src[(g2 * src_stride + rows - 1) * D + pos];
+                    }
+                }
+                __syncthreads();
+                rows = (rows + 1) / 2;
+                float *tmp = src; src = dst; dst = tmp;
+                const int ts = src_stride; src_stride = dst_stride; dst_stride = ts;
+            }
+            for (int x = tid; x < G * D; x += nthr) {
+                const int g2 = x / D;
+                const int pos = x - g2 * D;
+                const unsigned grp = group0 + g2;
+                if (grp < ngroups) {
+                    float *o = (W == 1) ? A.out + (int64_t)grp * D : A.partial + (int64_t)grp * D;
+                    o[pos] = src[(g2 * src_stride) * D + pos];
+                }
+            }
+        } else {
+            // inclusive scan left to right into the second buffer: B[0] = A[0], B[c] = B[c-1] (x) A[c]
+            for (int x = tid; x < G * D; x += nthr) {
+                const int g2 = x / D;
+                const int pos = x - g2 * D;
+                sigB[(g2 * C) * D + pos] = sigA[(g2 * C) * D + pos];
+            }
+            __syncthreads();
+            for (int c2 = 1; c2 < C; ++c2) {
+                const int total = G * RP::ITEMS;
+                for (int x = tid; x < total; x += nthr) {
+                    const int g2 = x / RP::ITEMS;
+                    const int it = x - g2 * RP::ITEMS;
+                    const int rowi = g2 * C + c2;
+                    RP::item(sigB + (rowi - 1) * D, sigA + rowi * D, sigB + rowi * D, it);
+                }
+                __syncthreads();
+            }
+            // every chunk restarts from the signature of everything before it and emits its prefixes
+            if (c == 0) identity_state<d, N, P>(ln);
+            else load_state<d, N, P>(sigB + (mygc - 1) * D, u, ln);
+            fold_chunk(std::true_type{});
+        }
     }
-
-    // stream mode: inclusive scan left to right (chunk c2 <- chunk c2-1 (x) chunk c2), then every
-    // chunk restarts from the signature of everything before it and emits each of its prefixes
-    for (int c2 = 1; c2 < C; ++c2) {
-        auto rows = [=](int pq, int &ia, int &ib) {
-            ib = pq * C + c2;
-            ia = ib - 1;
-        };
-        lds_product_levels<d, N, N, false>(sigrows, G, rows, tid, nthr);
-    }
-    if (c == 0) identity_state<d, N, P>(ln);
-    else load_state<d, N, P>(sigrows + (mygc - 1) * D, u, ln);
-    fold_chunk(std::true_type{});
 }
 
-// LDS bytes of a launch (same formula as in the kernel)
+// LDS bytes of a launch (same layout as in the kernel)
 template <int d, int N, int P>
 int64_t on_chip_lds_bytes(const OnChipArgs &A)
 {
     using Sh = Shape<d, N, P>;
     const int64_t NGC = (int64_t)A.groups * A.chunks;
-    int64_t floats = 2 * NGC * A.tile_steps * Sh::DP;
-    if (A.chunks > 1) floats += NGC * Sh::D;
+    const bool pipe = A.tile_steps < A.chunk_steps;
+    int64_t floats = desc_floats((int)NGC) + (pipe ? 2 : 1) * (int64_t)round4((int)(NGC * A.tile_steps * d));
+    if (A.chunks > 1) {
+        floats += NGC * Sh::D;
+        floats += (A.stream_flag ? NGC : (int64_t)A.groups * ((A.chunks + 1) / 2)) * Sh::D;
+    }
     return floats * (int64_t)sizeof(float);
+}
+
+template <int d, int N, int P, bool CHUNKED, bool STREAM>
+void on_chip_launch_pipe(const OnChipArgs &A, dim3 g, dim3 blk, size_t lds, hipStream_t st)
+{
+    if (A.tile_steps < A.chunk_steps)
+        hipLaunchKernelGGL((sig_on_chip_kernel<d, N, P, CHUNKED, STREAM, true>), g, blk, lds, st, A);
+    else
+        hipLaunchKernelGGL((sig_on_chip_kernel<d, N, P, CHUNKED, STREAM, false>), g, blk, lds, st, A);
 }
 
 template <int d, int N, int P>
@@ -435,23 +535,36 @@ hipError_t on_chip_launch(const OnChipArgs &A, hipStream_t st)
     const int64_t ngroups = A.B * A.segments;
     int64_t grid;
     if (Sh::Q > A.threads) {
+        if (A.chunks != 1 || A.groups != 1) return hipErrorInvalidValue;
         grid = ngroups * ((Sh::Q + A.threads - 1) / A.threads);
     } else {
         const int G = A.groups;
         if (G < 1 || (int64_t)G * A.chunks * Sh::Q > A.threads) return hipErrorInvalidValue;
         grid = (ngroups + G - 1) / G;
     }
-    if (grid <= 0 || grid > INT32_MAX) return hipErrorInvalidValue;
+    if (grid <= 0 || grid > INT32_MAX || ngroups > INT32_MAX) return hipErrorInvalidValue;
+    // loader geometry the kernel relies on
+    const int64_t NGC = (int64_t)A.groups * A.chunks;
+    if (A.row_shift < 0 || A.row_shift > 20 || (1 << A.row_shift) < A.tile_steps * d) return hipErrorInvalidValue;
+    if (A.tile_steps < A.chunk_steps && (NGC << A.row_shift) > (int64_t)kStage * A.threads) return hipErrorInvalidValue;
     const int64_t lds = on_chip_lds_bytes<d, N, P>(A);
     if (lds > kMaxLdsBytes) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((sig_on_chip_kernel<d, N, P, 256>), dim3((unsigned)grid), dim3(A.threads), (size_t)lds, st, A);
+    const dim3 g((unsigned)grid), blk(A.threads);
+    if (A.chunks > 1) {
+        if (A.stream_flag) on_chip_launch_pipe<d, N, P, true, true>(A, g, blk, (size_t)lds, st);
+        else on_chip_launch_pipe<d, N, P, true, false>(A, g, blk, (size_t)lds, st);
+    } else {
+        if (A.stream_flag) on_chip_launch_pipe<d, N, P, false, true>(A, g, blk, (size_t)lds, st);
+        else on_chip_launch_pipe<d, N, P, false, false>(A, g, blk, (size_t)lds, st);
+    }
     return hipGetLastError();
 }
 
-#define SIG_ON_CHIP_ENTRY(d, N, P)                                                        \
-    {                                                                                     \
-        d, N, P, ::sig::onchip::Shape<d, N, P>::Q, ::sig::onchip::Shape<d, N, P>::SZ,     \
-            &::sig::onchip::on_chip_launch<d, N, P>, &::sig::onchip::on_chip_lds_bytes<d, N, P> \
+#define SIG_ON_CHIP_ENTRY(d, N, P)                                                              \
+    {                                                                                           \
+        d, N, P, ::sig::onchip::Shape<d, N, P>::Q, ::sig::onchip::Shape<d, N, P>::SZ,           \
+            d, &::sig::onchip::on_chip_launch<d, N, P>,         \
+            &::sig::onchip::on_chip_lds_bytes<d, N, P>                                          \
     }
 
 }  // namespace onchip

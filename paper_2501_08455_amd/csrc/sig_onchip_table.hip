@@ -12,7 +12,7 @@ const OnChipKernelInfo kTable[] = {
     SIG_ON_CHIP_ENTRY(5, 4, 1),
     SIG_ON_CHIP_ENTRY(5, 4, 2),
     SIG_ON_CHIP_ENTRY(10, 6, 4),
-    {0, 0, 0, 0, 0, nullptr, nullptr},
+    {0, 0, 0, 0, 0, 0, nullptr, nullptr},
 };
 }  // namespace
 

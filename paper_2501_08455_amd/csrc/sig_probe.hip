@@ -1,0 +1,70 @@
+// Measurement anchors declared in include/sig_probe.h: a plain copy and an fp32 FMA loop.
+#include "sig_internal.h"
+#include "sig_probe.h"
+
+namespace {
+
+__global__ __launch_bounds__(256) void sig_probe_copy_kernel(float4 *dst, const float4 *src, int64_t n4)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (; i < n4; i += stride) dst[i] = src[i];
+}
+
+extern __shared__ float sig_probe_smem[];
+
+// ILP independent FMA chains per lane; dynamic LDS is only there to limit how many workgroups share a CU
+template <int ILP>
+__global__ __launch_bounds__(256) void sig_probe_fma_kernel(float *out, int64_t iters)
+{
+    const int64_t lane = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    float a[ILP];
+#pragma unroll
+    for (int i = 0; i < ILP; ++i) a[i] = 1.0f + (float)((lane + i) & 7) * 0.125f;
+    const float x = 0.999f, y = 0.001f + (float)(lane & 3) * 1e-6f;
+    for (int64_t it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int r = 0; r < 16 / ILP; ++r)
+#pragma unroll
+            for (int i = 0; i < ILP; ++i) a[i] = fmaf(a[i], x, y);
+    }
+    float s = 0.0f;
+#pragma unroll
+    for (int i = 0; i < ILP; ++i) s += a[i];
+    out[lane] = s;
+}
+
+}  // namespace
+
+extern "C" {
+
+int sig_probe_copy(float *dst, const float *src, int64_t n_floats, void *hip_stream)
+{
+    if (!dst || !src || n_floats < 0 || n_floats % 4 || ((uintptr_t)dst & 15) || ((uintptr_t)src & 15)) return SIG_ERR_INVALID;
+    if (n_floats == 0) return SIG_OK;
+    const int64_t n4 = n_floats / 4;
+    int64_t blocks = (n4 + 255) / 256;
+    if (blocks > 256 * 32) blocks = 256 * 32;
+    hipLaunchKernelGGL(sig_probe_copy_kernel, dim3((unsigned)blocks), dim3(256), 0, static_cast<hipStream_t>(hip_stream),
+                       reinterpret_cast<float4 *>(dst), reinterpret_cast<const float4 *>(src), n4);
+    return hipGetLastError() == hipSuccess ? SIG_OK : SIG_ERR_HIP;
+}
+
+int sig_probe_fma(float *out, int64_t waves, int64_t iters, int ilp, int lds_bytes, void *hip_stream)
+{
+    if (!out || waves < 4 || waves % 4 || iters < 0 || waves / 4 > INT32_MAX) return SIG_ERR_INVALID;
+    if (lds_bytes < 0 || lds_bytes > sig::kMaxLdsBytes) return SIG_ERR_INVALID;
+    const dim3 grid((unsigned)(waves / 4)), block(256);
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    switch (ilp) {
+    case 1: hipLaunchKernelGGL(sig_probe_fma_kernel<1>, grid, block, (size_t)lds_bytes, st, out, iters); break;
+    case 2: hipLaunchKernelGGL(sig_probe_fma_kernel<2>, grid, block, (size_t)lds_bytes, st, out, iters); break;
+    case 4: hipLaunchKernelGGL(sig_probe_fma_kernel<4>, grid, block, (size_t)lds_bytes, st, out, iters); break;
+    case 8: hipLaunchKernelGGL(sig_probe_fma_kernel<8>, grid, block, (size_t)lds_bytes, st, out, iters); break;
+    case 16: hipLaunchKernelGGL(sig_probe_fma_kernel<16>, grid, block, (size_t)lds_bytes, st, out, iters); break;
+    default: return SIG_ERR_INVALID;
+    }
+    return hipGetLastError() == hipSuccess ? SIG_OK : SIG_ERR_HIP;
+}
+
+}  // extern "C"

@@ -11,16 +11,20 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def declared_functions():
-    text = open(os.path.join(ROOT, "include", "sig.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(sig_[a-z_]+)\s*\(", text)))
+    names = set()
+    for header in sorted(os.listdir(os.path.join(ROOT, "include"))):
+        text = open(os.path.join(ROOT, "include", header)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(sig_[a-z_]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_library_exports_every_declared_symbol():
     lib = binding.load()
     names = declared_functions()
     assert {"sig_create", "sig_compute", "sig_destroy", "sig_size", "sig_plan", "sig_compute_planned",
-            "sig_combine", "sig_strerror", "sig_on_chip_available"} <= set(names)
+            "sig_combine", "sig_strerror", "sig_on_chip_available", "sig_plan_validate",
+            "sig_probe_copy", "sig_probe_fma"} <= set(names)
     for name in names:
         assert hasattr(lib, name), name
 
