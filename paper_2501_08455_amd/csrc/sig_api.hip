@@ -40,18 +40,20 @@ int check_shape(int64_t B, int64_t L, int d, int depth, int stream_flag, RowShap
 
 // Fill the derived launch fields of an on-chip plan (chunk_steps, tile_steps) and check every limit the kernel
 // relies on.  Returns false if the plan cannot run.
-bool finish_on_chip(const OnChipKernelInfo *ki, int64_t B, int64_t L, int stream_flag, const sig_plan_t &pl,
+bool finish_on_chip(const OnChipKernelInfo *ki, int cus, int64_t B, int64_t L, int stream_flag, const sig_plan_t &pl,
                     const RowShape &rs, OnChipArgs *args)
 {
     const int Q = ki->lanes_per_chunk;
     const int64_t K = L - 1;
-    if (pl.threads < kWave || pl.threads > 256 || pl.threads % kWave) return false;
     if (pl.chunks < 1 || pl.segments < 1) return false;
+    // only the chunked kernels with a small lane state are built for workgroups above 256 threads
+    const int max_threads = (pl.chunks > 1 && ki->state_floats <= 64) ? 1024 : 256;
+    if (pl.threads < kWave || pl.threads > max_threads || pl.threads % kWave) return false;
     if ((int64_t)pl.chunks * pl.segments > K) return false;  // no more pieces than increments
     if (Q > pl.threads && pl.chunks != 1) return false;
     if (Q <= pl.threads && (int64_t)pl.chunks * Q > pl.threads) return false;
     if (stream_flag && pl.segments != 1) return false;       // carries across workgroups are not implemented
-    if (pl.segments > 1 && rs.D * (int64_t)sizeof(float) > kMaxLdsBytes) return false;
+    if (pl.segments > 1 && (pl.segments + (pl.segments + 1) / 2) * rs.D * (int64_t)sizeof(float) > kMaxLdsBytes) return false;
     if (B * (int64_t)pl.segments > INT32_MAX) return false;
     args->B = B;
     args->L = L;
@@ -71,7 +73,9 @@ bool finish_on_chip(const OnChipKernelInfo *ki, int64_t B, int64_t L, int stream
         if (fit < 1) return false;
         if (G > fit) G = (int)fit;
     }
-    if ((int64_t)G > B * pl.segments) G = (int)(B * pl.segments);  // a tiny batch does not fill a workgroup
+    // spread the groups over the compute units before packing several into one workgroup
+    const int64_t per_cu = ceil_div(B * pl.segments, cus);
+    if ((int64_t)G > per_cu) G = (int)per_cu;
     args->groups = G;
     // Tile of staged increments.  The whole chunk in one tile if it fits the tile budget; otherwise two
     // tiles (double buffer), each short enough for the budget and for the registers that hold the next
@@ -99,15 +103,17 @@ bool finish_on_chip(const OnChipKernelInfo *ki, int64_t B, int64_t L, int stream
 }
 
 // Which compiled prefix depth to use for (d, depth).  A wavefront issues a vector instruction only every
-// five to six cycles, so the fp32 rate needs several wavefronts per SIMD: prefer the smallest prefix
-// depth whose per-lane state leaves room for four of them (<= 96 floats of state), else the deepest one.
-const OnChipKernelInfo *pick_on_chip(int d, int depth)
+// five to six cycles, so the fp32 rate needs several wavefronts per SIMD: for the final signature prefer
+// the smallest prefix depth whose per-lane state leaves room for four of them (<= 96 floats of state),
+// else the deepest one.  Stream mode is bound by the stores, not the arithmetic: take the deepest
+// prefix (most lanes, fewest registers, most stores in flight).
+const OnChipKernelInfo *pick_on_chip(int d, int depth, int stream_flag)
 {
     const OnChipKernelInfo *best = nullptr;
     for (const OnChipKernelInfo *e = on_chip_table(); e->launch; ++e) {
         if (e->d != d || e->depth != depth) continue;
         if (!best) { best = e; continue; }
-        if (best->state_floats > 96) best = e;  // entries are ordered by increasing prefix depth
+        if (stream_flag || best->state_floats > 96) best = e;  // entries are ordered by increasing prefix depth
     }
     return best;
 }
@@ -116,11 +122,13 @@ int plan_auto(const sig_ctx *ctx, int64_t B, int64_t L, int stream_flag, const R
 {
     const int cus = ctx ? ctx->num_cu : kDefaultCUs;
     const int64_t K = L - 1;
-    const int64_t want_lanes = (int64_t)cus * 4 * 4 * kWave;  // four wavefronts on every SIMD
+    // lanes that fill the chip: eight wavefronts on every SIMD for the arithmetic-bound final mode, two for
+    // stream mode (cutting time there costs a second fold)
+    const int64_t want_lanes = (int64_t)cus * 4 * kWave * (stream_flag ? 2 : 8);
     *pl = sig_plan_t{};
     pl->threads = kThreads;
 
-    const OnChipKernelInfo *ki = (B > 0) ? pick_on_chip(rs.d, rs.depth) : nullptr;
+    const OnChipKernelInfo *ki = (B > 0) ? pick_on_chip(rs.d, rs.depth, stream_flag) : nullptr;
     if (ki) {
         pl->variant = SIG_VARIANT_ON_CHIP;
         pl->prefix_depth = ki->p;
@@ -138,18 +146,19 @@ int plan_auto(const sig_ctx *ctx, int64_t B, int64_t L, int stream_flag, const R
             int64_t C = pieces < cmax ? pieces : cmax;
             // further workgroups along time only while each chunk keeps a long sequential run
             int64_t W = 1;
-            if (!stream_flag && rs.D * (int64_t)sizeof(float) <= kMaxLdsBytes) {
+            if (!stream_flag) {
                 W = ceil_div(pieces, C);
                 int64_t wmax = K / (C * kMinSegmentChunkSteps);
                 if (W > wmax) W = wmax;
-                if (W > 16) W = 16;
+                if (W > 8) W = 8;
+                while (W > 1 && (W + (W + 1) / 2) * rs.D * (int64_t)sizeof(float) > kMaxLdsBytes) --W;
                 if (W < 1) W = 1;
             }
             pl->chunks = (int)C;
             pl->segments = (int)W;
         }
         OnChipArgs args{};
-        if (finish_on_chip(ki, B, L, stream_flag, *pl, rs, &args)) {
+        if (finish_on_chip(ki, cus, B, L, stream_flag, *pl, rs, &args)) {
             pl->tile_steps = args.tile_steps;
             return SIG_OK;
         }
@@ -204,7 +213,7 @@ int run_plan(sig_ctx *ctx, const float *path, int64_t B, int64_t L, const RowSha
     const OnChipKernelInfo *ki = find_on_chip(rs.d, rs.depth, pl.prefix_depth);
     if (!ki) return SIG_ERR_INVALID;
     OnChipArgs args{};
-    if (!finish_on_chip(ki, B, L, stream_flag, pl, rs, &args)) return SIG_ERR_INVALID;
+    if (!finish_on_chip(ki, ctx->num_cu, B, L, stream_flag, pl, rs, &args)) return SIG_ERR_INVALID;
     args.path = path;
     args.out = out;
     args.partial = nullptr;
@@ -217,7 +226,7 @@ int run_plan(sig_ctx *ctx, const float *path, int64_t B, int64_t L, const RowSha
     hipError_t e = ki->launch(args, st);
     if (e != hipSuccess) return SIG_ERR_HIP;
     if (pl.segments > 1) {
-        e = launch_join_segments(ctx->scratch, out, B, pl.segments, rs, st);
+        e = ki->join(ctx->scratch, out, B, pl.segments, st);
         if (e != hipSuccess) return SIG_ERR_HIP;
     }
     return SIG_OK;
@@ -298,7 +307,7 @@ int sig_plan_validate(int64_t B, int64_t L, int d, int depth, int stream_flag, c
     if (plan->variant != SIG_VARIANT_ON_CHIP) return SIG_ERR_INVALID;
     const OnChipKernelInfo *ki = find_on_chip(rs.d, rs.depth, plan->prefix_depth);
     OnChipArgs args{};
-    if (!ki || !finish_on_chip(ki, B, L, stream_flag, *plan, rs, &args)) return SIG_ERR_INVALID;
+    if (!ki || !finish_on_chip(ki, kDefaultCUs, B, L, stream_flag, *plan, rs, &args)) return SIG_ERR_INVALID;
     return SIG_OK;
 }
 

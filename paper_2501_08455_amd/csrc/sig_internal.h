@@ -39,10 +39,6 @@ hipError_t launch_combine_rows(const float *a, int64_t a_stride, const float *b,
                                float *out, int64_t out_stride, int64_t B, const RowShape &rs,
                                hipStream_t st);
 
-// out[b] = partial[b][0] (x) partial[b][1] (x) ... (x) partial[b][W-1], rows of D floats, D*8 <= kMaxLdsBytes
-hipError_t launch_join_segments(const float *partial, float *out, int64_t B, int W, const RowShape &rs,
-                                hipStream_t st);
-
 // ---------------------------------------------------------------- on-chip family (compiled (d, depth, p) only)
 struct OnChipArgs {
     const float *path;   // [B][L][d]
@@ -68,6 +64,8 @@ struct OnChipKernelInfo {
     hipError_t (*launch)(const OnChipArgs &, hipStream_t);
     // LDS bytes the launch needs for these arguments (for validation before launching)
     int64_t (*lds_bytes)(const OnChipArgs &);
+    // out[b] = product over the `segments` partial rows of path b (second launch when segments > 1)
+    hipError_t (*join)(const float *partial, float *out, int64_t B, int segments, hipStream_t);
 };
 
 // table of compiled on-chip kernels; terminated by an entry with launch == nullptr

@@ -34,6 +34,14 @@
 namespace sig {
 namespace onchip {
 
+// Phase time stamps of workgroup 0, only in diagnostic builds (-DSIG_DIAG_TIMING); read back with sig_diag_read.
+#ifdef SIG_DIAG_TIMING
+__device__ unsigned long long sig_diag_ticks[16];
+#define SIG_TICK(i) do { if (threadIdx.x == 0 && blockIdx.x == 0) sig_diag_ticks[i] = wall_clock64(); } while (0)
+#else
+#define SIG_TICK(i) do { } while (0)
+#endif
+
 constexpr int cpow(int b, int e)
 {
     int r = 1;
@@ -246,6 +254,41 @@ struct RowProduct {
     }
 };
 
+
+// Pairwise tree over `rows` consecutive rows of each of G groups in LDS, ping-pong between two buffers;
+// the left-to-right order of the factors is kept.  On return src / src_stride address the results
+// (row 0 of every group).  Every thread of the workgroup must call it (it contains barriers).
+template <int d, int N>
+__device__ __forceinline__ void lds_tree_reduce(float *&src, float *&dst, int G, int rows, int &src_stride,
+                                                int &dst_stride, int tid, int nthr)
+{
+    using RP = RowProduct<d, N>;
+    constexpr int D = Shape<d, N, 0>::D;
+    while (rows > 1) {
+        const int pairs = rows / 2;
+        const int total = G * pairs * RP::ITEMS;
+        for (int x = tid; x < total; x += nthr) {
+            const int pq = x / RP::ITEMS;
+            const int it = x - pq * RP::ITEMS;
+            const int g2 = pq / pairs;
+            const int q = pq - g2 * pairs;
+            const float *a = src + (g2 * src_stride + 2 * q) * D;
+            RP::item(a, a + D, dst + (g2 * dst_stride + q) * D, it);
+        }
+        if (rows & 1) {  // odd row out: carried to the next round unchanged
+            for (int x = tid; x < G * D; x += nthr) {
+                const int g2 = x / D;
+                const int pos = x - g2 * D;
+                dst[(g2 * dst_stride + pairs) * D + pos] = src[(g2 * src_stride + rows - 1) * D + pos];
+            }
+        }
+        __syncthreads();
+        rows = (rows + 1) / 2;
+        float *tmp = src; src = dst; dst = tmp;
+        const int ts = src_stride; src_stride = dst_stride; dst_stride = ts;
+    }
+}
+
 extern __shared__ __align__(16) float sig_onchip_smem[];
 
 // per (group, chunk) of a workgroup: where its increments start in the path and how many it has
@@ -264,13 +307,20 @@ __host__ __device__ constexpr int round4(int x) { return (x + 3) / 4 * 4; }
 // CHUNKED: several time chunks per group, joined in LDS.  STREAM: every prefix is emitted.
 // PIPE: the chunk spans several LDS tiles; the next tile's global loads are kept in flight in
 // registers while the current tile is consumed (one barrier per tile).
+// largest workgroup a kernel is built for (1024 threads leave 128 registers per lane)
+template <int d, int N, int P, bool CHUNKED>
+constexpr int max_threads() { return (CHUNKED && Shape<d, N, P>::SZ <= 64) ? 1024 : 256; }
+
+// Workgroups of the CHUNKED kernels may have up to 1024 threads (when the lane state is small enough): only chunks * Q lanes fold, but every
+// thread takes part in the LDS products, which are latency bound with one wavefront per SIMD.
 template <int d, int N, int P, bool CHUNKED, bool STREAM, bool PIPE>
-__global__ __launch_bounds__(256) void sig_on_chip_kernel(OnChipArgs A)
+__global__ __launch_bounds__((max_threads<d, N, P, CHUNKED>())) void sig_on_chip_kernel(OnChipArgs A)
 {
     using Sh = Shape<d, N, P>;
     constexpr int Q = Sh::Q;
     constexpr int D = Sh::D;
 
+    SIG_TICK(0);
     const int tid = threadIdx.x;
     const int nthr = blockDim.x;
     const int64_t K = A.L - 1;
@@ -398,6 +448,7 @@ __global__ __launch_bounds__(256) void sig_on_chip_kernel(OnChipArgs A)
                 __syncthreads();
                 for (int idx = tid; idx < flat; idx += nthr) put_one(tile0, idx, fetch_one(idx, t0));
                 __syncthreads();
+                if (t0 == 0) SIG_TICK(6);
                 consume(tile0, t0);
             }
         } else {
@@ -427,6 +478,7 @@ __global__ __launch_bounds__(256) void sig_on_chip_kernel(OnChipArgs A)
 
     identity_state<d, N, P>(ln);
     __syncthreads();  // descriptors visible
+    SIG_TICK(1);
 
     if constexpr (!CHUNKED) {
         fold_chunk(std::integral_constant<bool, STREAM>{});
@@ -439,36 +491,16 @@ __global__ __launch_bounds__(256) void sig_on_chip_kernel(OnChipArgs A)
     } else {
         using RP = RowProduct<d, N>;
         fold_chunk(std::false_type{});
+        SIG_TICK(2);
         if (active) store_state<d, N, P>(sigA + mygc * D, u, ln);
         float *sigB = sigA + NGC * D;  // second buffer: [G][(C+1)/2][D] (final) or [NGC][D] (stream)
         __syncthreads();
         if constexpr (!STREAM) {
-            // pairwise tree, ping-pong between the two buffers; order of the factors is kept
             float *src = sigA, *dst = sigB;
-            int rows = C, src_stride = C, dst_stride = (C + 1) / 2;
-            while (rows > 1) {
-                const int pairs = rows / 2;
-                const int total = G * pairs * RP::ITEMS;
-                for (int x = tid; x < total; x += nthr) {
-                    const int pq = x / RP::ITEMS;
-                    const int it = x - pq * RP::ITEMS;
-                    const int g2 = pq / pairs;
-                    const int q = pq - g2 * pairs;
-                    const float *a = src + (g2 * src_stride + 2 * q) * D;
-                    RP::item(a, a + D, dst + (g2 * dst_stride + q) * D, it);
-                }
-                if (rows & 1) {  // odd row out: carried to the next round unchanged
-                    for (int x = tid; x < G * D; x += nthr) {
-                        const int g2 = x / D;
-                        const int pos = x - g2 * D;
-                        dst[(g2 * dst_stride + pairs) * D + pos] = src[(g2 * src_stride + rows - 1) * D + pos];
-                    }
-                }
-                __syncthreads();
-                rows = (rows + 1) / 2;
-                float *tmp = src; src = dst; dst = tmp;
-                const int ts = src_stride; src_stride = dst_stride; dst_stride = ts;
-            }
+            int src_stride = C, dst_stride = (C + 1) / 2;
+            SIG_TICK(3);
+            lds_tree_reduce<d, N>(src, dst, G, C, src_stride, dst_stride, tid, nthr);
+            SIG_TICK(4);
             for (int x = tid; x < G * D; x += nthr) {
                 const int g2 = x / D;
                 const int pos = x - g2 * D;
@@ -502,6 +534,7 @@ __global__ __launch_bounds__(256) void sig_on_chip_kernel(OnChipArgs A)
             fold_chunk(std::true_type{});
         }
     }
+    SIG_TICK(5);
 }
 
 // LDS bytes of a launch (same layout as in the kernel)
@@ -543,6 +576,7 @@ hipError_t on_chip_launch(const OnChipArgs &A, hipStream_t st)
         grid = (ngroups + G - 1) / G;
     }
     if (grid <= 0 || grid > INT32_MAX || ngroups > INT32_MAX) return hipErrorInvalidValue;
+    if (A.threads > (A.chunks > 1 ? max_threads<d, N, P, true>() : 256)) return hipErrorInvalidValue;
     // loader geometry the kernel relies on
     const int64_t NGC = (int64_t)A.groups * A.chunks;
     if (A.row_shift < 0 || A.row_shift > 20 || (1 << A.row_shift) < A.tile_steps * d) return hipErrorInvalidValue;
@@ -560,11 +594,52 @@ hipError_t on_chip_launch(const OnChipArgs &A, hipStream_t st)
     return hipGetLastError();
 }
 
+// Join the partial signatures of the W time segments of each path: out[b] = partial[b][0] (x) ... (x) partial[b][W-1].
+// One workgroup handles G paths: all their partial rows are read into LDS in one go, then reduced by the tree.
+template <int d, int N>
+__global__ __launch_bounds__(256) void sig_join_kernel(const float *partial, float *out, int B, int W, int G)
+{
+    constexpr int D = Shape<d, N, 0>::D;
+    const int tid = threadIdx.x, nthr = blockDim.x;
+    const int b0 = blockIdx.x * G;
+    const int nb = (B - b0 < G) ? B - b0 : G;
+    float *bufA = sig_onchip_smem;               // [G][W][D]
+    float *bufB = bufA + G * W * D;              // [G][(W+1)/2][D]
+    const float *srcg = partial + (int64_t)b0 * W * D;
+    for (int x = tid; x < nb * W * D; x += nthr) bufA[x] = srcg[x];
+    __syncthreads();
+    float *src = bufA, *dst = bufB;
+    int src_stride = W, dst_stride = (W + 1) / 2;
+    lds_tree_reduce<d, N>(src, dst, G, W, src_stride, dst_stride, tid, nthr);
+    for (int x = tid; x < nb * D; x += nthr) {
+        const int g2 = x / D;
+        const int pos = x - g2 * D;
+        out[(int64_t)(b0 + g2) * D + pos] = src[(g2 * src_stride) * D + pos];
+    }
+}
+
+template <int d, int N>
+hipError_t on_chip_join(const float *partial, float *out, int64_t B, int W, hipStream_t st)
+{
+    constexpr int D = Shape<d, N, 0>::D;
+    if (B <= 0 || B > INT32_MAX || W < 2) return hipErrorInvalidValue;
+    const int64_t per_path = (int64_t)(W + (W + 1) / 2) * D * (int64_t)sizeof(float);
+    int64_t G = kMaxLdsBytes / 2 / per_path;  // half of the LDS limit keeps two workgroups on a CU
+    if (G < 1) G = kMaxLdsBytes / per_path;
+    if (G < 1) return hipErrorInvalidValue;
+    if (G > 8) G = 8;
+    if (G > B) G = B;
+    const int64_t grid = (B + G - 1) / G;
+    hipLaunchKernelGGL((sig_join_kernel<d, N>), dim3((unsigned)grid), dim3(256), (size_t)(G * per_path), st, partial, out,
+                       (int)B, W, (int)G);
+    return hipGetLastError();
+}
+
 #define SIG_ON_CHIP_ENTRY(d, N, P)                                                              \
     {                                                                                           \
         d, N, P, ::sig::onchip::Shape<d, N, P>::Q, ::sig::onchip::Shape<d, N, P>::SZ,           \
             d, &::sig::onchip::on_chip_launch<d, N, P>,         \
-            &::sig::onchip::on_chip_lds_bytes<d, N, P>                                          \
+            &::sig::onchip::on_chip_lds_bytes<d, N, P>, &::sig::onchip::on_chip_join<d, N>      \
     }
 
 }  // namespace onchip

@@ -12,7 +12,7 @@ const OnChipKernelInfo kTable[] = {
     SIG_ON_CHIP_ENTRY(5, 4, 1),
     SIG_ON_CHIP_ENTRY(5, 4, 2),
     SIG_ON_CHIP_ENTRY(10, 6, 4),
-    {0, 0, 0, 0, 0, 0, nullptr, nullptr},
+    {0, 0, 0, 0, 0, 0, nullptr, nullptr, nullptr},
 };
 }  // namespace
 
@@ -26,3 +26,10 @@ const OnChipKernelInfo *find_on_chip(int d, int depth, int p)
 }
 
 }  // namespace sig
+
+#ifdef SIG_DIAG_TIMING
+extern "C" int sig_diag_read(unsigned long long *host16)
+{
+    return (int)hipMemcpyFromSymbol(host16, HIP_SYMBOL(sig::onchip::sig_diag_ticks), 16 * sizeof(unsigned long long));
+}
+#endif

@@ -3,7 +3,6 @@
 //   sig_hbm_streaming_kernel  the fused multiply-by-exponential of Eq. 3 applied increment by
 //                             increment to state that lives in the output rows themselves
 //   sig_combine_rows_kernel   batched truncated product of Eq. 4
-//   sig_join_segments_kernel  left-to-right product of the partial signatures of one path
 //
 // Writing out (S (x) exp(v))[w] for a word w = (i_1 .. i_n) with Eqs. 2 and 4 gives
 //   S'[w] = S[w] + sum_{m=0}^{n-1} S[w_{1:m}] * v[i_{m+1}] ... v[i_n] / (n - m)!      (S[empty] = 1)
@@ -140,48 +139,6 @@ __global__ __launch_bounds__(256) void sig_combine_rows_kernel(CombineParams P)
     P.out[row * P.out_stride + pos] = c;
 }
 
-struct JoinParams {
-    const float *partial;  // [B][W][D]
-    float *out;            // [B][D]
-    int W;
-    int D;
-    int d;
-    int depth;
-    int pw[kMaxDepth + 1];
-    int off[kMaxDepth + 2];
-};
-
-// One workgroup per path; the running product sits in LDS and is multiplied from the right by
-// each further partial signature.  Levels are processed from depth down to 1 so that the
-// update can be done in place (level n of the product needs levels < n of the left factor, which
-// are still the old ones, and its own old level-n entry).
-__global__ __launch_bounds__(256) void sig_join_segments_kernel(JoinParams P)
-{
-    float *acc = sig_smem;  // [D]
-    const int64_t b = blockIdx.x;
-    const int tid = threadIdx.x, nthr = blockDim.x;
-    const float *part = P.partial + b * P.W * (int64_t)P.D;
-    for (int i = tid; i < P.D; i += nthr) acc[i] = part[i];
-    __syncthreads();
-    for (int j = 1; j < P.W; ++j) {
-        const float *r = part + (int64_t)j * P.D;
-        for (int n = P.depth; n >= 1; --n) {
-            const int sz = P.pw[n];
-            for (int w = tid; w < sz; w += nthr) {
-                float c = acc[P.off[n] + w] + r[P.off[n] + w];
-                for (int i = 1; i < n; ++i) {
-                    int split = P.pw[n - i];
-                    c = fmaf(acc[P.off[i] + w / split], r[P.off[n - i] + w % split], c);
-                }
-                acc[P.off[n] + w] = c;
-            }
-            __syncthreads();
-        }
-    }
-    float *o = P.out + b * (int64_t)P.D;
-    for (int i = tid; i < P.D; i += nthr) o[i] = acc[i];
-}
-
 }  // namespace
 
 bool make_row_shape(int d, int depth, RowShape *rs)
@@ -254,19 +211,6 @@ hipError_t launch_combine_rows(const float *a, int64_t a_stride, const float *b,
         if (e != hipSuccess) return e;
     }
     return hipSuccess;
-}
-
-hipError_t launch_join_segments(const float *partial, float *out, int64_t B, int W, const RowShape &rs,
-                                hipStream_t st)
-{
-    if (rs.D * (int64_t)sizeof(float) > kMaxLdsBytes || B > INT32_MAX) return hipErrorInvalidValue;
-    JoinParams P;
-    P.partial = partial; P.out = out; P.W = W; P.D = (int)rs.D; P.d = rs.d; P.depth = rs.depth;
-    for (int n = 0; n <= rs.depth; ++n) P.pw[n] = (int)rs.pow[n];
-    for (int n = 1; n <= rs.depth + 1; ++n) P.off[n] = (int)rs.off[n];
-    P.off[0] = 0;
-    hipLaunchKernelGGL(sig_join_segments_kernel, dim3((unsigned)B), dim3(256), (size_t)rs.D * sizeof(float), st, P);
-    return hipGetLastError();
 }
 
 }  // namespace sig

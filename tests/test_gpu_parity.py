@@ -107,7 +107,7 @@ ON_CHIP_CASES = [
     (5, 4, 1, 128, 100, 1, 1, 0, False), (5, 4, 1, 60, 23, 1, 1, 3, True), (5, 4, 1, 2, 333, 10, 4, 0, False),
     (5, 4, 1, 3, 90, 6, 1, 0, True),
     (5, 4, 2, 128, 100, 10, 1, 0, False), (5, 4, 2, 128, 100, 5, 2, 4, False), (5, 4, 2, 11, 100, 1, 1, 0, False),
-    (5, 4, 2, 2, 2000, 10, 16, 0, False), (5, 4, 2, 4, 61, 4, 1, 0, True), (5, 4, 2, 13, 30, 1, 1, 0, True),
+    (5, 4, 2, 2, 2000, 10, 8, 0, False), (5, 4, 2, 3, 700, 3, 13, 9, False), (5, 4, 2, 4, 61, 4, 1, 0, True), (5, 4, 2, 13, 30, 1, 1, 0, True),
     (10, 6, 4, 2, 9, 1, 1, 0, False), (10, 6, 4, 1, 4, 1, 1, 2, True),
 ]
 
