@@ -51,7 +51,11 @@ bool finish_on_chip(const OnChipKernelInfo *ki, int cus, int64_t B, int64_t L, i
     if (pl.threads < kWave || pl.threads > max_threads || pl.threads % kWave) return false;
     if ((int64_t)pl.chunks * pl.segments > K) return false;  // no more pieces than increments
     if (Q > pl.threads && pl.chunks != 1) return false;
-    if (Q <= pl.threads && (int64_t)pl.chunks * Q > pl.threads) return false;
+    // slots of Q lanes a workgroup offers: packed in final mode, kept inside wavefronts in stream mode
+    const int64_t slots = Q > pl.threads ? 1
+                          : (stream_flag && Q <= kWave) ? (int64_t)(pl.threads / kWave) * (kWave / Q)
+                                                        : pl.threads / Q;
+    if (Q <= pl.threads && pl.chunks > slots) return false;
     if (stream_flag && pl.segments != 1) return false;       // carries across workgroups are not implemented
     if (pl.segments > 1 && (pl.segments + (pl.segments + 1) / 2) * rs.D * (int64_t)sizeof(float) > kMaxLdsBytes) return false;
     if (B * (int64_t)pl.segments > INT32_MAX) return false;
@@ -64,7 +68,7 @@ bool finish_on_chip(const OnChipKernelInfo *ki, int cus, int64_t B, int64_t L, i
     args->chunk_steps = (int)ceil_div(K, (int64_t)pl.chunks * pl.segments);
     if (ceil_div(K, (int64_t)pl.chunks * pl.segments) > INT32_MAX) return false;
     // groups per workgroup: as many as the threads hold, fewer if their chunk signatures overflow LDS
-    int G = Q > pl.threads ? 1 : pl.threads / (pl.chunks * Q);
+    int G = Q > pl.threads ? 1 : (int)(slots / pl.chunks);
     if (pl.chunks > 1) {
         // two buffers of chunk signatures (the second one half as large in final mode)
         const int64_t per_group = (int64_t)(stream_flag ? 2 * pl.chunks : pl.chunks + (pl.chunks + 1) / 2) *
@@ -138,7 +142,8 @@ int plan_auto(const sig_ctx *ctx, int64_t B, int64_t L, int stream_flag, const R
         if (Q <= kThreads) {
             // cut time into pieces only as far as needed to fill the chip; every cut costs one Eq. 4 product
             int64_t pieces = ceil_div(want_lanes, B * Q);
-            int64_t cmax = kThreads / Q;  // chunks side by side in a workgroup
+            // chunks side by side in a workgroup (stream kernels keep a chunk's lanes inside one wavefront)
+            int64_t cmax = (stream_flag && Q <= kWave) ? (int64_t)(kThreads / kWave) * (kWave / Q) : kThreads / Q;
             int64_t clds = (kMaxLdsBytes - kTileLdsBytes) / (2 * rs.D * (int64_t)sizeof(float));  // two signature buffers
             if (cmax > clds) cmax = clds;
             if (cmax > K / kMinChunkSteps) cmax = K / kMinChunkSteps;

@@ -293,15 +293,16 @@ extern __shared__ __align__(16) float sig_onchip_smem[];
 
 // per (group, chunk) of a workgroup: where its increments start in the path and how many it has
 struct ChunkDesc {
-    int64_t base;   // float offset of x[b][k_begin][0] in the path array
-    int32_t steps;  // valid increments of this chunk (0 for chunks beyond the path or the batch)
-    int32_t pad;
+    int64_t base;      // float offset of x[b][k_begin][0] in the path array
+    int64_t out_row0;  // stream mode: float offset of out[b][k_begin][0]
+    int32_t steps;     // valid increments of this chunk (0 for chunks beyond the path or the batch)
+    int32_t pad[3];
 };
 
 constexpr int kStage = kLoaderStage;  // floats of the next tile a thread holds in registers (PIPE kernels)
 
-// floats of LDS in front of the increment tiles (descriptors, 16 bytes each, even count)
-__host__ __device__ constexpr int desc_floats(int ngc) { return 4 * ((ngc + 1) / 2 * 2); }
+// floats of LDS in front of the increment tiles (descriptors, 32 bytes each)
+__host__ __device__ constexpr int desc_floats(int ngc) { return 8 * ngc; }
 __host__ __device__ constexpr int round4(int x) { return (x + 3) / 4 * 4; }
 
 // CHUNKED: several time chunks per group, joined in LDS.  STREAM: every prefix is emitted.
@@ -333,7 +334,23 @@ __global__ __launch_bounds__((max_threads<d, N, P, CHUNKED>())) void sig_on_chip
     int G, gi, c;
     unsigned u, group0;  // group0: first group of this workgroup
     bool active;
-    if (!big) {
+    // Stream kernels with Q <= 64 keep every (group, chunk) slot inside one wavefront (64 / Q slots per
+    // wavefront, the remaining lanes idle) so that a wavefront can gather its slots' rows in LDS and write
+    // them out with consecutive lanes on consecutive addresses, without a workgroup barrier per step.
+    constexpr bool WAVE_SLOTS = STREAM && Q <= kWave;
+    constexpr int SPW = WAVE_SLOTS ? kWave / Q : 1;  // slots per wavefront
+    if constexpr (WAVE_SLOTS) {
+        const int wave = tid / kWave, lw = tid - wave * kWave;
+        const int sw = lw / Q;
+        const int slot = wave * SPW + sw;
+        G = A.groups;
+        u = (unsigned)(lw - sw * Q);
+        gi = slot / C;
+        c = slot - gi * C;
+        group0 = blockIdx.x * (unsigned)G;
+        active = sw < SPW && gi < G && group0 + gi < ngroups;
+        if (sw >= SPW || gi >= G) { gi = 0; c = 0; }
+    } else if (!big) {
         const int LG = C * Q;
         G = A.groups;
         gi = tid / LG;
@@ -369,7 +386,7 @@ __global__ __launch_bounds__((max_threads<d, N, P, CHUNKED>())) void sig_on_chip
     const int row_floats = TT * d;                      // one chunk's part of a tile, rows of d floats, unpadded
     const int tile_floats = round4(NGC * row_floats);
     float *tile0 = sig_onchip_smem + desc_floats(NGC);
-    float *sigA = tile0 + (PIPE ? 2 : 1) * tile_floats;  // [NGC][D]
+    float *sigA = tile0 + (PIPE ? 2 : 1) * tile_floats;  // [NGC][D]: chunk signatures, and the rows staged for emission
     (void)sigA;
 
     if (tid < NGC) {
@@ -378,8 +395,9 @@ __global__ __launch_bounds__((max_threads<d, N, P, CHUNKED>())) void sig_on_chip
         const unsigned grp = group0 + g2;
         ChunkDesc dsc;
         dsc.base = 0;
+        dsc.out_row0 = 0;
         dsc.steps = 0;
-        dsc.pad = 0;
+        dsc.pad[0] = dsc.pad[1] = dsc.pad[2] = 0;
         if (grp < ngroups) {
             const unsigned b2 = grp / (unsigned)W;
             const int64_t k0 = (int64_t)((grp - b2 * W) * C + c2) * T;
@@ -388,6 +406,7 @@ __global__ __launch_bounds__((max_threads<d, N, P, CHUNKED>())) void sig_on_chip
             if (left > 0) {
                 dsc.steps = (int)left;
                 dsc.base = ((int64_t)b2 * A.L + k0) * d;
+                dsc.out_row0 = ((int64_t)b2 * K + k0) * D;
             }
         }
         desc[tid] = dsc;
@@ -417,6 +436,8 @@ __global__ __launch_bounds__((max_threads<d, N, P, CHUNKED>())) void sig_on_chip
         if (idx < flat && r < row_floats) tile[gc * row_floats + r] = v;
     };
 
+    const bool vec_ok = (reinterpret_cast<uintptr_t>(A.out) & 15) == 0;  // rows of D floats, D % 4 == 0, stay 16-byte aligned
+    (void)vec_ok;
     Lane<d, N, P> ln;
     int64_t b = 0, k_begin = 0;
     unsigned mygroup = 0;
@@ -430,6 +451,37 @@ __global__ __launch_bounds__((max_threads<d, N, P, CHUNKED>())) void sig_on_chip
     // fold this lane's chunk, optionally emitting every prefix (stream mode)
     auto fold_chunk = [&](auto emit_tag) {
         constexpr bool emit = decltype(emit_tag)::value;
+        // Emission through LDS (WAVE_SLOTS): the rows of a wavefront's slots form one flat range of
+        // vectors; lane lw copies elements lw, lw + 64, ...  Which slot and column an element belongs to
+        // does not change from step to step, so the output address at step 0 of the chunk, the LDS offset
+        // and the number of valid steps are worked out once per lane (NIT elements).
+        constexpr int VEC = (D % 4 == 0) ? 4 : 1;
+        constexpr int ROWV = D / VEC;
+        constexpr int NIT = (SPW * ROWV + kWave - 1) / kWave;
+        constexpr bool FAST_EMIT = emit && WAVE_SLOTS && NIT <= 8;
+        using V = std::conditional_t<VEC == 4, float4, float>;
+        V *eptr[FAST_EMIT ? NIT : 1];  // output address of the element at step 0 of its chunk
+        int eoff[FAST_EMIT ? NIT : 1];  // offset (in vectors) into the staged rows
+        int elim[FAST_EMIT ? NIT : 1];  // steps for which the element is written (0: never)
+        const bool use_vec = VEC == 1 || vec_ok;
+        if constexpr (FAST_EMIT) {
+            const int wave = tid / kWave, lw = tid - wave * kWave;
+#pragma unroll
+            for (int j = 0; j < NIT; ++j) {
+                const int i = lw + j * kWave;
+                const int sw = i / ROWV;
+                const int col = i - sw * ROWV;
+                const int slot = wave * SPW + sw;
+                eptr[j] = reinterpret_cast<V *>(A.out);
+                eoff[j] = 0;
+                elim[j] = 0;
+                if (use_vec && i < SPW * ROWV && slot < NGC) {
+                    eptr[j] = reinterpret_cast<V *>(A.out + desc[slot].out_row0) + col;
+                    eoff[j] = slot * ROWV + col;
+                    elim[j] = desc[slot].steps;
+                }
+            }
+        }
         auto consume = [&](const float *tile, int t0) {
             const int steps = (T - t0 < TT) ? T - t0 : TT;
             const float *row = tile + mygc * row_floats;
@@ -437,7 +489,30 @@ __global__ __launch_bounds__((max_threads<d, N, P, CHUNKED>())) void sig_on_chip
             for (int t = 0; t < steps; ++t, row += d) {
                 load_inc<d, P>(inc, row, letter);
                 fused_step<d, N, P>(ln, inc);
-                if constexpr (emit) {
+                if constexpr (emit && WAVE_SLOTS) {
+                    // gather this wavefront's rows in LDS, then write them with consecutive lanes on
+                    // consecutive addresses (LDS operations of one wavefront execute in order)
+                    if (active) store_state<d, N, P>(sigA + mygc * D, u, ln);
+                    if (FAST_EMIT && use_vec) {
+                        if constexpr (FAST_EMIT) {
+                            V val[NIT];
+#pragma unroll
+                            for (int j = 0; j < NIT; ++j) val[j] = reinterpret_cast<const V *>(sigA)[eoff[j]];
+#pragma unroll
+                            for (int j = 0; j < NIT; ++j)
+                                if (t0 + t < elim[j]) eptr[j][(int64_t)(t0 + t) * ROWV] = val[j];
+                        }
+                    } else {
+                        const int wave = tid / kWave, lw = tid - wave * kWave;
+                        for (int i = lw; i < SPW * D; i += kWave) {
+                            const int sw = i / D;
+                            const int col = i - sw * D;
+                            const int slot = wave * SPW + sw;
+                            if (slot < NGC && t0 + t < desc[slot].steps)
+                                A.out[desc[slot].out_row0 + (int64_t)(t0 + t) * D + col] = sigA[slot * D + col];
+                        }
+                    }
+                } else if constexpr (emit) {
                     const int64_t k = k_begin + t0 + t;
                     if (active && k < K) store_state<d, N, P>(A.out + (b * K + k) * D, u, ln);
                 }
@@ -548,6 +623,8 @@ int64_t on_chip_lds_bytes(const OnChipArgs &A)
     if (A.chunks > 1) {
         floats += NGC * Sh::D;
         floats += (A.stream_flag ? NGC : (int64_t)A.groups * ((A.chunks + 1) / 2)) * Sh::D;
+    } else if (A.stream_flag && Sh::Q <= kWave) {
+        floats += NGC * Sh::D;  // rows staged for emission
     }
     return floats * (int64_t)sizeof(float);
 }
@@ -572,7 +649,12 @@ hipError_t on_chip_launch(const OnChipArgs &A, hipStream_t st)
         grid = ngroups * ((Sh::Q + A.threads - 1) / A.threads);
     } else {
         const int G = A.groups;
-        if (G < 1 || (int64_t)G * A.chunks * Sh::Q > A.threads) return hipErrorInvalidValue;
+        if (G < 1) return hipErrorInvalidValue;
+        if (A.stream_flag && Sh::Q <= kWave) {
+            if ((int64_t)G * A.chunks > (int64_t)(A.threads / kWave) * (kWave / Sh::Q)) return hipErrorInvalidValue;
+        } else if ((int64_t)G * A.chunks * Sh::Q > A.threads) {
+            return hipErrorInvalidValue;
+        }
         grid = (ngroups + G - 1) / G;
     }
     if (grid <= 0 || grid > INT32_MAX || ngroups > INT32_MAX) return hipErrorInvalidValue;
