@@ -15,8 +15,20 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-PEAK_FP32_TFLOPS = 157.3   # MI355X vector fp32, published (assumes packed fp32 issue)
+PEAK_FP32_TFLOPS = 157.3   # MI355X vector fp32, published
 PEAK_HBM_GBS = 8000.0      # MI355X HBM3E, published
+
+# HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs scaled by the
+# copy kernel of the same run (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0); see profiles/hbm_traffic.md.
+# Keyed by (configuration, batch).
+MEASURED_TRAFFIC_BYTES = {
+    ("C2", 128): (2 * 169.1 + 392.0) * 1024,
+    ("C2", 65536): (2 * 64335.0 + 199682.3) * 1024,
+    ("C3", 128): (2 * 2605.3 + 3136.0) * 1024,
+    ("C4", 64): (2 * 179.8 + 21724.8) * 1024,
+    ("C4", 4096): (2 * 9784.8 + 1389407.9) * 1024,
+    ("C5", 16): (2 * 359.5 + 69714.2) * 1024,
+}
 
 
 def time_calls(binding, ctx, xt, depth, stream_flag, out, steps, warmup, plan=None):
@@ -50,17 +62,17 @@ def algorithmic_work(cfg, B, workloads):
     return flops, nbytes, D, rows
 
 
-def roofline(flops, nbytes, ms):
+def roofline(flops, nbytes, ms, traffic=None):
     """Roofline entry for a call lasting `ms`: the bound is the one whose ideal time is larger."""
     t_alu = flops / (PEAK_FP32_TFLOPS * 1e12)
     t_hbm = nbytes / (PEAK_HBM_GBS * 1e9)
     if t_alu >= t_hbm:
         ach = flops / (ms * 1e-3) / 1e12
         return {"bound": "alu", "achieved": ach, "peak": PEAK_FP32_TFLOPS, "unit": "TFLOP/s",
-                "frac": ach / PEAK_FP32_TFLOPS, "traffic": None}
+                "frac": ach / PEAK_FP32_TFLOPS, "traffic": traffic}
     ach = nbytes / (ms * 1e-3) / 1e9
     return {"bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-            "frac": ach / PEAK_HBM_GBS, "traffic": None}
+            "frac": ach / PEAK_HBM_GBS, "traffic": traffic}
 
 
 def bench_config(binding, workloads, ctx, cfg, B, steps, warmup):
@@ -75,7 +87,8 @@ def bench_config(binding, workloads, ctx, cfg, B, steps, warmup):
                                                           "stream" if cfg.stream else "final"),
            "ms_per_step": ms_ev, "ms_per_step_host_clock": ms_wall, "steps": steps,
            "paths_per_s": B / (ms_ev * 1e-3), "terms_per_s": B * rows * D / (ms_ev * 1e-3),
-           "roofline": roofline(flops, nbytes, ms_ev), "plan": pl.as_dict()}
+           "roofline": roofline(flops, nbytes, ms_ev, MEASURED_TRAFFIC_BYTES.get((cfg.name, B))),
+           "algorithmic": {"flops": flops, "bytes": nbytes}, "plan": pl.as_dict()}
     del xt, out
     return res
 
@@ -127,8 +140,8 @@ def cpu_baseline(workloads, cfg, max_paths, budget_s=20.0):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=2000)
-    ap.add_argument("--warmup", type=int, default=50)
+    ap.add_argument("--steps", type=int, default=5000)
+    ap.add_argument("--warmup", type=int, default=2000)
     ap.add_argument("--no-extras", action="store_true", help="skip the other configurations")
     ap.add_argument("--anchors", action="store_true", help="also measure the copy and FMA-loop anchors")
     ap.add_argument("--workload", default="C2", help="configuration to time as the headline (C1..C5)")
@@ -167,11 +180,13 @@ def main():
         line["cpu_baseline"] = cpu_baseline(workloads, cfg, max_paths=min(B, 128))
     if not args.no_extras:
         extras = []
-        plan = [("C1", None, 500), ("C3", None, 300), ("C4", None, 300), ("C5", None, 50),
-                ("C1", 1 << 20, 50), ("C2", 65536, 50), ("C3", 4096, 30), ("C4", 4096, 20)]
-        for name, B, steps in plan:
+        # (configuration, batch, timed steps, warm-up steps); warm-ups are long enough (tens of ms) for the
+        # shader clock to ramp up after idle
+        plan = [("C1", None, 3000, 3000), ("C3", None, 1000, 500), ("C4", None, 1000, 500), ("C5", None, 300, 200),
+                ("C1", 1 << 20, 200, 200), ("C2", 65536, 150, 100), ("C3", 4096, 80, 50), ("C4", 4096, 60, 60)]
+        for name, B, steps, warm in plan:
             c = workloads.CONFIGS[name]
-            extras.append(bench_config(binding, workloads, ctx, c, B or c.B, steps, 5))
+            extras.append(bench_config(binding, workloads, ctx, c, B or c.B, steps, warm))
         line["all_configs"] = extras
     if args.anchors:
         line["anchors"] = anchors(binding)

@@ -126,9 +126,9 @@ int plan_auto(const sig_ctx *ctx, int64_t B, int64_t L, int stream_flag, const R
 {
     const int cus = ctx ? ctx->num_cu : kDefaultCUs;
     const int64_t K = L - 1;
-    // lanes that fill the chip: eight wavefronts on every SIMD for the arithmetic-bound final mode, two for
-    // stream mode (cutting time there costs a second fold)
-    const int64_t want_lanes = (int64_t)cus * 4 * kWave * (stream_flag ? 2 : 8);
+    // lanes that fill the chip: eight wavefronts on every SIMD for the arithmetic-bound final mode, one for
+    // stream mode (bound by the stores; cutting time there costs a second fold)
+    const int64_t want_lanes = (int64_t)cus * 4 * kWave * (stream_flag ? 1 : 8);
     *pl = sig_plan_t{};
     pl->threads = kThreads;
 
