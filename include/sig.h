@@ -67,7 +67,10 @@ enum sig_variant {
  *   segments      workgroups per path along time (>= 1); partial signatures of segments
  *                 are joined by a second launch
  *   threads       workgroup size (multiple of 64)
- *   tile_steps    increments staged through LDS per tile by the loader
+ *   tile_steps    increments staged through LDS per tile by the loader (0: chosen by the library)
+ *   reserved[0]   with chunks == 1: 0 = workgroup-wide tiles of increments (the default, faster in every
+ *                 measurement so far); 1 = every wavefront stages its own increments and workgroups walk
+ *                 several batches of paths without any barrier (kept for comparison)
  */
 typedef struct sig_plan_t {
     int32_t variant;

@@ -47,7 +47,7 @@ bool finish_on_chip(const OnChipKernelInfo *ki, int cus, int64_t B, int64_t L, i
     const int64_t K = L - 1;
     if (pl.chunks < 1 || pl.segments < 1) return false;
     // only the chunked kernels with a small lane state are built for workgroups above 256 threads
-    const int max_threads = (pl.chunks > 1 && ki->state_floats <= 64) ? 1024 : 256;
+    const int max_threads = (pl.chunks > 1 && ki->state_floats <= 64) ? 512 : 256;
     if (pl.threads < kWave || pl.threads > max_threads || pl.threads % kWave) return false;
     if ((int64_t)pl.chunks * pl.segments > K) return false;  // no more pieces than increments
     if (Q > pl.threads && pl.chunks != 1) return false;
@@ -65,6 +65,7 @@ bool finish_on_chip(const OnChipKernelInfo *ki, int cus, int64_t B, int64_t L, i
     args->segments = pl.segments;
     args->threads = pl.threads;
     args->stream_flag = stream_flag;
+    args->cooperative = pl.reserved[0] != 1 && pl.chunks == 1;
     args->chunk_steps = (int)ceil_div(K, (int64_t)pl.chunks * pl.segments);
     if (ceil_div(K, (int64_t)pl.chunks * pl.segments) > INT32_MAX) return false;
     // groups per workgroup: as many as the threads hold, fewer if their chunk signatures overflow LDS
@@ -81,15 +82,20 @@ bool finish_on_chip(const OnChipKernelInfo *ki, int cus, int64_t B, int64_t L, i
     const int64_t per_cu = ceil_div(B * pl.segments, cus);
     if ((int64_t)G > per_cu) G = (int)per_cu;
     args->groups = G;
-    // Tile of staged increments.  The whole chunk in one tile if it fits the tile budget; otherwise two
-    // tiles (double buffer), each short enough for the budget and for the registers that hold the next
-    // tile in flight (kLoaderStage floats per thread over rows padded to a power of two).
+    // Tile of staged increments.
+    //  - chunked kernels: the whole chunk in one tile if it fits the tile budget, otherwise two tiles
+    //    (double buffer) short enough for the budget and for the registers that hold the next tile in
+    //    flight (kLoaderStage floats per thread over rows padded to a power of two);
+    //  - the fold kernel (chunks == 1): every wavefront stages its own groups; 32 steps per tile unless
+    //    the plan asks for fewer (LDS per workgroup is checked below).
     const int64_t ngc = (int64_t)G * pl.chunks;
     const int64_t T = args->chunk_steps;
     int64_t tt = T;
     const bool forced = pl.tile_steps > 0 && pl.tile_steps < T;
     if (forced) tt = pl.tile_steps;
-    if (forced || ngc * T * ki->d * (int64_t)sizeof(float) > kTileLdsBytes) {
+    if (pl.chunks == 1 && !args->cooperative) {
+        if (!forced && tt > kFoldTileSteps) tt = kFoldTileSteps;
+    } else if (forced || ngc * T * ki->d * (int64_t)sizeof(float) > kTileLdsBytes) {
         int64_t by_lds = kTileLdsBytes / (2 * ngc * ki->d * (int64_t)sizeof(float));
         int64_t row_pow2 = 1;
         while (row_pow2 * 2 * ngc <= (int64_t)kLoaderStage * pl.threads) row_pow2 *= 2;
@@ -102,7 +108,30 @@ bool finish_on_chip(const OnChipKernelInfo *ki, int cus, int64_t B, int64_t L, i
     int shift = 0;
     while (((int64_t)1 << shift) < tt * ki->d) ++shift;
     args->row_shift = shift;
-    if (ki->lds_bytes(*args) > kMaxLdsBytes) return false;
+    if ((pl.chunks > 1 || args->cooperative) && tt < T && (ngc << shift) > (int64_t)kLoaderStage * pl.threads) return false;
+    int64_t lds = ki->lds_bytes(*args);
+    while (pl.chunks == 1 && !args->cooperative && !forced && lds > kMaxLdsBytes / 2 && args->tile_steps > 1) {
+        // keep at least two workgroups per 64 KB: shorter tiles
+        args->tile_steps /= 2;
+        shift = 0;
+        while (((int64_t)1 << shift) < (int64_t)args->tile_steps * ki->d) ++shift;
+        args->row_shift = shift;
+        lds = ki->lds_bytes(*args);
+    }
+    if (lds > kMaxLdsBytes) return false;
+    // workgroups that stay resident at once (persistent kernel): limited by registers (estimated from the
+    // lane state), LDS (160 KB per CU) and wavefront slots (8 per SIMD)
+    {
+        const int waves_per_wg = pl.threads / kWave;
+        int waves_per_simd = 512 / (ki->state_floats + 45);
+        if (waves_per_simd > 8) waves_per_simd = 8;
+        if (waves_per_simd < 1) waves_per_simd = 1;
+        int64_t per_cu = (int64_t)waves_per_simd * 4 / waves_per_wg;
+        if (per_cu < 1) per_cu = 1;
+        const int64_t by_lds_cu = (160 * 1024) / (lds > 0 ? lds : 1);
+        if (by_lds_cu >= 1 && per_cu > by_lds_cu) per_cu = by_lds_cu;
+        args->resident_workgroups = (int32_t)(per_cu * cus);
+    }
     return true;
 }
 
@@ -117,7 +146,9 @@ const OnChipKernelInfo *pick_on_chip(int d, int depth, int stream_flag)
     for (const OnChipKernelInfo *e = on_chip_table(); e->launch; ++e) {
         if (e->d != d || e->depth != depth) continue;
         if (!best) { best = e; continue; }
-        if (stream_flag || best->state_floats > 96) best = e;  // entries are ordered by increasing prefix depth
+        // entries are ordered by increasing prefix depth; p = 0 (one lane per path) is skipped when there is an
+        // alternative: its LDS reads of the increments are not broadcasts (every lane reads another path's row)
+        if (stream_flag || best->state_floats > 96 || best->p == 0) best = e;
     }
     return best;
 }

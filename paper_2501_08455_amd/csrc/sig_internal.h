@@ -14,6 +14,7 @@ constexpr int kMaxDepth = 30;        // d^depth must also fit in int32
 constexpr int kWave = 64;
 constexpr int kMaxLdsBytes = 64 * 1024;  // per-workgroup LDS this library asks for at most
 constexpr int kTileLdsBytes = 19968;     // LDS the increment tile(s) of one workgroup may take (8 workgroups share 160 KB)
+constexpr int kFoldTileSteps = 32;       // increments a wavefront of the fold kernel stages at a time
 constexpr int kLoaderStage = 8;          // floats of the next tile one thread holds in registers when tiles are pipelined
 
 // Offsets of the levels inside an output row (Eq. 10: level 0 dropped): level n starts at
@@ -53,6 +54,8 @@ struct OnChipArgs {
     int32_t threads;     // workgroup size
     int32_t groups;      // (path, segment) pairs per workgroup (1 when a chunk's lanes span several workgroups)
     int32_t row_shift;   // log2 of the padded length of one chunk's stretch of a tile (tile_steps * d floats)
+    int32_t resident_workgroups;  // workgroups the device keeps resident at once (persistent kernels); 0: no limit
+    int32_t cooperative;  // chunks == 1 only: 1 = workgroup-wide tiles with barriers instead of independent wavefronts
     int32_t stream_flag;
 };
 

@@ -42,6 +42,8 @@ __device__ unsigned long long sig_diag_ticks[16];
 #define SIG_TICK(i) do { } while (0)
 #endif
 
+typedef float vec4f __attribute__((ext_vector_type(4)));  // plain 16-byte vector for LDS -> HBM row copies
+
 constexpr int cpow(int b, int e)
 {
     int r = 1;
@@ -176,14 +178,14 @@ template <int d, int N, int P>
 __device__ __forceinline__ void store_state(float *row, unsigned u, const Lane<d, N, P> &ln)
 {
     using Sh = Shape<d, N, P>;
-    static_for<(P == 0 ? 1 : 0), Sh::R + 1>([&](auto rc) {
+    static_for<(P == 0 ? 1 : 0), Sh::R + 1>([&](auto rc) __attribute__((always_inline)) {
         constexpr int r = decltype(rc)::value;
         constexpr int cnt = cpow(d, r);
         float *dst = row + Sh::row_off(P + r) + u * cnt;
 #pragma unroll
         for (int i = 0; i < cnt; ++i) dst[i] = ln.s[Sh::sub_off(r) + i];
     });
-    static_for<1, P>([&](auto mc) {
+    static_for<1, P>([&](auto mc) __attribute__((always_inline)) {
         constexpr int m = decltype(mc)::value;
         constexpr unsigned span = cpow(d, P - m);
         if (u % span == 0) row[Sh::row_off(m) + u / span] = ln.pre[m - 1];
@@ -194,14 +196,14 @@ template <int d, int N, int P>
 __device__ __forceinline__ void load_state(const float *row, unsigned u, Lane<d, N, P> &ln)
 {
     using Sh = Shape<d, N, P>;
-    static_for<(P == 0 ? 1 : 0), Sh::R + 1>([&](auto rc) {
+    static_for<(P == 0 ? 1 : 0), Sh::R + 1>([&](auto rc) __attribute__((always_inline)) {
         constexpr int r = decltype(rc)::value;
         constexpr int cnt = cpow(d, r);
         const float *src = row + Sh::row_off(P + r) + u * cnt;
 #pragma unroll
         for (int i = 0; i < cnt; ++i) ln.s[Sh::sub_off(r) + i] = src[i];
     });
-    static_for<1, P>([&](auto mc) {
+    static_for<1, P>([&](auto mc) __attribute__((always_inline)) {
         constexpr int m = decltype(mc)::value;
         ln.pre[m - 1] = row[Sh::row_off(m) + u / (unsigned)cpow(d, P - m)];
     });
@@ -230,7 +232,7 @@ struct RowProduct {
 
     static __device__ __forceinline__ void item(const float *a, const float *b, float *c, int it)
     {
-        static_for<1, N + 1>([&](auto nc) {
+        static_for<1, N + 1>([&](auto nc) __attribute__((always_inline)) {
             constexpr int n = decltype(nc)::value;
             constexpr int start = geom(d, n - 1);
             constexpr int cnt = cpow(d, n - 1);
@@ -239,7 +241,7 @@ struct RowProduct {
                 float acc[d];
 #pragma unroll
                 for (int j = 0; j < d; ++j) acc[j] = a[Sh::row_off(n) + v * d + j] + b[Sh::row_off(n) + v * d + j];
-                static_for<1, n>([&](auto ic) {
+                static_for<1, n>([&](auto ic) __attribute__((always_inline)) {
                     constexpr int i = decltype(ic)::value;
                     constexpr int tail = cpow(d, n - 1 - i);  // words of length n-1-i between the prefix and j
                     const float ai = a[Sh::row_off(i) + v / tail];
@@ -308,11 +310,11 @@ __host__ __device__ constexpr int round4(int x) { return (x + 3) / 4 * 4; }
 // CHUNKED: several time chunks per group, joined in LDS.  STREAM: every prefix is emitted.
 // PIPE: the chunk spans several LDS tiles; the next tile's global loads are kept in flight in
 // registers while the current tile is consumed (one barrier per tile).
-// largest workgroup a kernel is built for (1024 threads leave 128 registers per lane)
+// largest workgroup a kernel is built for (512 threads leave 256 registers per lane)
 template <int d, int N, int P, bool CHUNKED>
-constexpr int max_threads() { return (CHUNKED && Shape<d, N, P>::SZ <= 64) ? 1024 : 256; }
+constexpr int max_threads() { return (CHUNKED && Shape<d, N, P>::SZ <= 64) ? 512 : 256; }
 
-// Workgroups of the CHUNKED kernels may have up to 1024 threads (when the lane state is small enough): only chunks * Q lanes fold, but every
+// Workgroups of the CHUNKED kernels may have up to 512 threads (when the lane state is small enough): only chunks * Q lanes fold, but every
 // thread takes part in the LDS products, which are latency bound with one wavefront per SIMD.
 template <int d, int N, int P, bool CHUNKED, bool STREAM, bool PIPE>
 __global__ __launch_bounds__((max_threads<d, N, P, CHUNKED>())) void sig_on_chip_kernel(OnChipArgs A)
@@ -449,7 +451,7 @@ __global__ __launch_bounds__((max_threads<d, N, P, CHUNKED>())) void sig_on_chip
     }
 
     // fold this lane's chunk, optionally emitting every prefix (stream mode)
-    auto fold_chunk = [&](auto emit_tag) {
+    auto fold_chunk = [&](auto emit_tag) __attribute__((always_inline)) {
         constexpr bool emit = decltype(emit_tag)::value;
         // Emission through LDS (WAVE_SLOTS): the rows of a wavefront's slots form one flat range of
         // vectors; lane lw copies elements lw, lw + 64, ...  Which slot and column an element belongs to
@@ -459,7 +461,7 @@ __global__ __launch_bounds__((max_threads<d, N, P, CHUNKED>())) void sig_on_chip
         constexpr int ROWV = D / VEC;
         constexpr int NIT = (SPW * ROWV + kWave - 1) / kWave;
         constexpr bool FAST_EMIT = emit && WAVE_SLOTS && NIT <= 8;
-        using V = std::conditional_t<VEC == 4, float4, float>;
+        using V = std::conditional_t<VEC == 4, vec4f, float>;
         V *eptr[FAST_EMIT ? NIT : 1];  // output address of the element at step 0 of its chunk
         int eoff[FAST_EMIT ? NIT : 1];  // offset (in vectors) into the staged rows
         int elim[FAST_EMIT ? NIT : 1];  // steps for which the element is written (0: never)
@@ -612,11 +614,262 @@ __global__ __launch_bounds__((max_threads<d, N, P, CHUNKED>())) void sig_on_chip
     SIG_TICK(5);
 }
 
+// ------------------------------------------------------------------------------------------
+// Fold kernel for plans with one time chunk per (path, segment): independent wavefronts.
+//
+// A work item is a batch of `groups` (path, segment) pairs (or, when a chunk's Q lanes exceed the
+// workgroup, one workgroup-sized slice of one pair's lanes).  A workgroup walks items blockIdx.x,
+// blockIdx.x + gridDim.x, ...  Inside it every wavefront works on its own: it stages the increments of
+// the groups its 64 lanes belong to in a private LDS region (groups that straddle two wavefronts are
+// staged by both), so there is no workgroup barrier anywhere and wavefronts drift apart in time.  The
+// stall of one wavefront on its tile loads is then covered by the arithmetic of the others on the same
+// SIMD, and the final stores of an item drain while the next item is folded.  (With workgroup-wide tiles
+// all workgroups of a launch load, fold and store in lock-step and the HBM phases are not overlapped.)
+template <int d, int N, int P, bool STREAM>
+struct FoldGeom {
+    using Sh = Shape<d, N, P>;
+    static constexpr bool WAVE_SLOTS = STREAM && Sh::Q <= kWave;
+    static constexpr int SPW = WAVE_SLOTS ? kWave / Sh::Q : 1;
+    // groups a wavefront can touch: all of them aligned (stream), one (Q >= workgroup) or straddling
+    static constexpr int NGW = WAVE_SLOTS ? SPW : (Sh::Q >= kWave ? 2 : (kWave + Sh::Q - 2) / Sh::Q + 1);
+};
+
+template <int d, int N, int P, bool STREAM>
+__global__ __launch_bounds__(256) void sig_fold_kernel(OnChipArgs A)
+{
+    using Sh = Shape<d, N, P>;
+    using Geo = FoldGeom<d, N, P, STREAM>;
+    constexpr int Q = Sh::Q;
+    constexpr int D = Sh::D;
+    constexpr bool WAVE_SLOTS = Geo::WAVE_SLOTS;
+    constexpr int SPW = Geo::SPW;
+    constexpr int NGW = Geo::NGW;
+
+    const int tid = threadIdx.x;
+    const int nthr = blockDim.x;
+    const int wave = tid / kWave, lw = tid - wave * kWave;
+    const int64_t K = A.L - 1;
+    const int W = A.segments, T = A.chunk_steps, TT = A.tile_steps;
+    const unsigned ngroups = (unsigned)(A.B * W);
+    const bool big = Q > nthr;
+    const unsigned NB = big ? (Q + nthr - 1) / nthr : 1;
+    const int G = big ? 1 : A.groups;  // groups (slots) per item
+    const unsigned nitems = big ? ngroups * NB : (ngroups + G - 1) / G;
+
+    // ---- lane -> (slot in the item, prefix word); fixed, except the prefix word in `big` mode
+    int gi;
+    unsigned u = 0;
+    bool lane_ok;
+    int g_lo, ng;  // slots this wavefront stages: g_lo .. g_lo + ng - 1
+    if constexpr (WAVE_SLOTS) {
+        const int sw = lw / Q;
+        gi = wave * SPW + sw;
+        u = (unsigned)(lw - sw * Q);
+        lane_ok = sw < SPW && gi < G;
+        g_lo = wave * SPW;
+        ng = G - g_lo < SPW ? G - g_lo : SPW;
+    } else if (!big) {
+        gi = tid / Q;
+        u = (unsigned)(tid - gi * Q);
+        lane_ok = gi < G;
+        g_lo = (wave * kWave) / Q;
+        int g_hi = (wave * kWave + kWave - 1) / Q;
+        if (g_hi > G - 1) g_hi = G - 1;
+        ng = g_hi - g_lo + 1;
+    } else {
+        gi = 0;
+        lane_ok = true;
+        g_lo = 0;
+        ng = 1;
+    }
+    if (ng < 0) ng = 0;
+    if (!lane_ok) gi = g_lo < G ? g_lo : 0;
+    const int gl = lane_ok ? gi - g_lo : 0;  // my slot inside the set this wavefront stages
+    int letter[P > 0 ? P : 1];
+    letter[0] = 0;
+    auto set_letters = [&]() {
+        unsigned rest = u;
+#pragma unroll
+        for (int m = P - 1; m >= 0; --m) { letter[m] = (int)(rest % d); rest /= d; }
+    };
+    set_letters();
+
+    // ---- LDS, private to the wavefront: NGW descriptors, one tile [NGW][TT*d], staged rows (stream)
+    const int row_floats = TT * d;
+    const int wave_floats = desc_floats(NGW) + round4(NGW * row_floats) + (WAVE_SLOTS ? SPW * D : 0);
+    float *wbase = sig_onchip_smem + wave * wave_floats;
+    ChunkDesc *desc = reinterpret_cast<ChunkDesc *>(wbase);
+    float *tile = wbase + desc_floats(NGW);
+    float *rows = tile + round4(NGW * row_floats);  // [SPW][D], WAVE_SLOTS only
+    (void)rows;
+
+    const int rshift = A.row_shift;
+    const int rmask = (1 << rshift) - 1;
+    const bool vec_ok = (reinterpret_cast<uintptr_t>(A.out) & 15) == 0;
+    (void)vec_ok;
+    Lane<d, N, P> ln;
+
+    for (unsigned item = blockIdx.x; item < nitems; item += gridDim.x) {
+        const unsigned group0 = big ? item / NB : item * (unsigned)G;
+        if (big) {
+            u = (item % NB) * nthr + tid;
+            lane_ok = u < (unsigned)Q;
+            if (!lane_ok) u = 0;
+            set_letters();
+        }
+        const unsigned grp = group0 + gi;
+        const bool active = lane_ok && grp < ngroups;
+
+        // descriptors of the groups this wavefront stages (LDS operations of one wavefront execute in order,
+        // so the other lanes may read them right after)
+        if (lw < ng) {
+            const unsigned g2 = group0 + g_lo + lw;
+            ChunkDesc dsc;
+            dsc.base = 0;
+            dsc.out_row0 = 0;
+            dsc.steps = 0;
+            dsc.pad[0] = dsc.pad[1] = dsc.pad[2] = 0;
+            if (g2 < ngroups) {
+                const unsigned b2 = g2 / (unsigned)W;
+                const int64_t k0 = (int64_t)(g2 - b2 * W) * T;
+                int64_t left = K - k0;
+                if (left > T) left = T;
+                if (left > 0) {
+                    dsc.steps = (int)left;
+                    dsc.base = ((int64_t)b2 * A.L + k0) * d;
+                    dsc.out_row0 = ((int64_t)b2 * K + k0) * D;
+                }
+            }
+            desc[lw] = dsc;
+        }
+        __builtin_amdgcn_wave_barrier();
+        identity_state<d, N, P>(ln);
+
+        // emission through LDS (stream): per-lane copy descriptors, see the chunked kernel
+        constexpr int VEC = (D % 4 == 0) ? 4 : 1;
+        constexpr int ROWV = D / VEC;
+        constexpr int NIT = (SPW * ROWV + kWave - 1) / kWave;
+        constexpr bool FAST_EMIT = WAVE_SLOTS && NIT <= 8;
+        using V = std::conditional_t<VEC == 4, vec4f, float>;
+        V *eptr[FAST_EMIT ? NIT : 1];
+        int eoff[FAST_EMIT ? NIT : 1];
+        int elim[FAST_EMIT ? NIT : 1];
+        const bool use_vec = VEC == 1 || vec_ok;
+        if constexpr (FAST_EMIT) {
+            static_for<0, NIT>([&](auto jc) __attribute__((always_inline)) {
+                constexpr int j = decltype(jc)::value;
+                const int i = lw + j * kWave;
+                const int sw = i / ROWV;
+                const int col = i - sw * ROWV;
+                eptr[j] = reinterpret_cast<V *>(A.out);
+                eoff[j] = 0;
+                elim[j] = 0;
+                if (use_vec && i < SPW * ROWV && sw < ng) {
+                    eptr[j] = reinterpret_cast<V *>(A.out + desc[sw].out_row0) + col;
+                    eoff[j] = sw * ROWV + col;
+                    elim[j] = desc[sw].steps;
+                }
+            });
+        }
+        int64_t my_out_row0 = 0;
+        int my_steps = 0;
+        if (STREAM && !WAVE_SLOTS && active) {
+            my_out_row0 = desc[gl].out_row0;
+            my_steps = desc[gl].steps;
+        }
+
+        for (int t0 = 0; t0 < T; t0 += TT) {
+            // ---- stage this wavefront's tile: consecutive lanes on consecutive floats of a group's stretch
+            // (eight elements per lane and trip, so that their global loads are in flight together)
+            const int flat = ng << rshift;
+            for (int base = 0; base < flat; base += 8 * kWave) {
+                float v[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const int idx = base + e * kWave + lw;
+                    const int g = idx >> rshift;
+                    const int r = idx & rmask;
+                    v[e] = 0.0f;
+                    if (idx < flat && r < (desc[g].steps - t0) * d && r < row_floats) {
+                        const float *x = A.path + desc[g].base + (int64_t)t0 * d + r;
+                        v[e] = x[d] - x[0];
+                    }
+                }
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const int idx = base + e * kWave + lw;
+                    const int g = idx >> rshift;
+                    const int r = idx & rmask;
+                    if (idx < flat && r < row_floats) tile[g * row_floats + r] = v[e];
+                }
+            }
+            __builtin_amdgcn_wave_barrier();
+            // ---- consume it
+            const int steps = (T - t0 < TT) ? T - t0 : TT;
+            const float *row = tile + gl * row_floats;
+            Inc<d, P> inc;
+            for (int t = 0; t < steps; ++t, row += d) {
+                load_inc<d, P>(inc, row, letter);
+                fused_step<d, N, P>(ln, inc);
+                if constexpr (WAVE_SLOTS) {
+                    if (active) store_state<d, N, P>(rows + gl * D, u, ln);
+                    if (FAST_EMIT && use_vec) {
+                        if constexpr (FAST_EMIT) {
+                            V val[NIT];
+                            static_for<0, NIT>([&](auto jc) __attribute__((always_inline)) {
+                                constexpr int j = decltype(jc)::value;
+                                val[j] = reinterpret_cast<const V *>(rows)[eoff[j]];
+                            });
+                            static_for<0, NIT>([&](auto jc) __attribute__((always_inline)) {
+                                constexpr int j = decltype(jc)::value;
+                                if (t0 + t < elim[j]) eptr[j][(int64_t)(t0 + t) * ROWV] = val[j];
+                            });
+                        }
+                    } else {
+                        for (int i = lw; i < SPW * D; i += kWave) {
+                            const int sw = i / D;
+                            const int col = i - sw * D;
+                            if (sw < ng && t0 + t < desc[sw].steps)
+                                A.out[desc[sw].out_row0 + (int64_t)(t0 + t) * D + col] = rows[sw * D + col];
+                        }
+                    }
+                } else if constexpr (STREAM) {
+                    if (active && t0 + t < my_steps)
+                        store_state<d, N, P>(A.out + my_out_row0 + (int64_t)(t0 + t) * D, u, ln);
+                }
+            }
+            __builtin_amdgcn_wave_barrier();
+        }
+        if (!STREAM && active) {
+            float *dst = (W == 1) ? A.out + (int64_t)grp * D : A.partial + (int64_t)grp * D;
+            store_state<d, N, P>(dst, u, ln);
+        }
+    }
+}
+
+// LDS bytes of the fold kernel (same layout as in the kernel)
+template <int d, int N, int P>
+int64_t fold_lds_bytes(const OnChipArgs &A)
+{
+    using Sh = Shape<d, N, P>;
+    const int waves = A.threads / kWave;
+    int64_t per_wave;
+    if (A.stream_flag) {
+        using Geo = FoldGeom<d, N, P, true>;
+        per_wave = desc_floats(Geo::NGW) + round4(Geo::NGW * A.tile_steps * d) + (Geo::WAVE_SLOTS ? Geo::SPW * Sh::D : 0);
+    } else {
+        using Geo = FoldGeom<d, N, P, false>;
+        per_wave = desc_floats(Geo::NGW) + round4(Geo::NGW * A.tile_steps * d);
+    }
+    return per_wave * waves * (int64_t)sizeof(float);
+}
+
 // LDS bytes of a launch (same layout as in the kernel)
 template <int d, int N, int P>
 int64_t on_chip_lds_bytes(const OnChipArgs &A)
 {
     using Sh = Shape<d, N, P>;
+    if (A.chunks == 1 && !A.cooperative) return fold_lds_bytes<d, N, P>(A);
     const int64_t NGC = (int64_t)A.groups * A.chunks;
     const bool pipe = A.tile_steps < A.chunk_steps;
     int64_t floats = desc_floats((int)NGC) + (pipe ? 2 : 1) * (int64_t)round4((int)(NGC * A.tile_steps * d));
@@ -662,16 +915,28 @@ hipError_t on_chip_launch(const OnChipArgs &A, hipStream_t st)
     // loader geometry the kernel relies on
     const int64_t NGC = (int64_t)A.groups * A.chunks;
     if (A.row_shift < 0 || A.row_shift > 20 || (1 << A.row_shift) < A.tile_steps * d) return hipErrorInvalidValue;
-    if (A.tile_steps < A.chunk_steps && (NGC << A.row_shift) > (int64_t)kStage * A.threads) return hipErrorInvalidValue;
+    if ((A.chunks > 1 || A.cooperative) && A.tile_steps < A.chunk_steps && (NGC << A.row_shift) > (int64_t)kStage * A.threads)
+        return hipErrorInvalidValue;
     const int64_t lds = on_chip_lds_bytes<d, N, P>(A);
     if (lds > kMaxLdsBytes) return hipErrorInvalidValue;
-    const dim3 g((unsigned)grid), blk(A.threads);
+    const dim3 blk(A.threads);
     if (A.chunks > 1) {
+        const dim3 g((unsigned)grid);
         if (A.stream_flag) on_chip_launch_pipe<d, N, P, true, true>(A, g, blk, (size_t)lds, st);
         else on_chip_launch_pipe<d, N, P, true, false>(A, g, blk, (size_t)lds, st);
-    } else {
+    } else if (A.cooperative) {
+        const dim3 g((unsigned)grid);
         if (A.stream_flag) on_chip_launch_pipe<d, N, P, false, true>(A, g, blk, (size_t)lds, st);
         else on_chip_launch_pipe<d, N, P, false, false>(A, g, blk, (size_t)lds, st);
+    } else {
+        // persistent: `grid` counts the work items; launch no more workgroups than stay resident, and so
+        // that every workgroup walks the same number of items
+        int64_t resident = A.resident_workgroups > 0 ? A.resident_workgroups : grid;
+        if (resident > grid) resident = grid;
+        const int64_t rounds = (grid + resident - 1) / resident;
+        const dim3 g((unsigned)((grid + rounds - 1) / rounds));
+        if (A.stream_flag) hipLaunchKernelGGL((sig_fold_kernel<d, N, P, true>), g, blk, (size_t)lds, st, A);
+        else hipLaunchKernelGGL((sig_fold_kernel<d, N, P, false>), g, blk, (size_t)lds, st, A);
     }
     return hipGetLastError();
 }

@@ -93,12 +93,12 @@ def test_create_without_a_gpu_reports_no_device():
 
 def test_every_forced_plan_of_the_gpu_tests_is_accepted_by_the_host_checks():
     import importlib
-    cases = importlib.import_module("test_gpu_parity").ON_CHIP_CASES
-    for (d, depth, p, B, L, chunks, segments, tile, stream) in cases:
+    mod = importlib.import_module("test_gpu_parity")
+    for case in mod.ON_CHIP_CASES:
+        d, depth, p, B, L, chunks, segments, tile, stream, threads = mod.split_case(case)
         plan = binding.make_plan(binding.SIG_VARIANT_ON_CHIP, prefix_depth=p, chunks=chunks, segments=segments,
-                                 tile_steps=tile)
-        assert binding.sig_plan_validate(B, L, d, depth, int(stream), plan) == binding.SIG_OK, \
-            (d, depth, p, B, L, chunks, segments, tile, stream)
+                                 tile_steps=tile, threads=threads)
+        assert binding.sig_plan_validate(B, L, d, depth, int(stream), plan) == binding.SIG_OK, case
 
 
 def test_plan_validate_rejects_plans_the_kernels_cannot_run():

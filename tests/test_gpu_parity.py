@@ -97,28 +97,49 @@ def test_uncompiled_shapes_fall_back(gpu, oracle):
 
 # ---------------------------------------------------------------- on-chip family: every compiled kernel, several time cuttings
 ON_CHIP_CASES = [
-    # d, depth, p, B, L, chunks, segments, tile_steps, stream
+    # d, depth, p, B, L, chunks, segments, tile_steps, stream[, threads]
     (2, 3, 0, 300, 16, 1, 1, 0, False), (2, 3, 0, 7, 41, 4, 2, 3, False), (2, 3, 0, 5, 41, 5, 1, 0, True),
     (2, 3, 1, 4, 16, 1, 1, 0, False), (2, 3, 1, 4, 16, 1, 1, 0, True), (2, 3, 1, 9, 100, 7, 3, 4, False),
     (2, 3, 1, 3, 100, 9, 1, 5, True),
-    (4, 4, 1, 70, 37, 1, 1, 0, False), (4, 4, 1, 70, 37, 1, 1, 5, True), (4, 4, 1, 3, 256, 8, 4, 0, False),
+    (4, 4, 1, 70, 37, 1, 1, 0, False), (4, 4, 1, 70, 37, 1, 1, 5, True, 64), (4, 4, 1, 3, 256, 8, 4, 0, False),
     (4, 4, 1, 5, 256, 16, 1, 0, True), (4, 4, 2, 64, 256, 16, 1, 0, True), (4, 4, 2, 3, 100, 3, 5, 7, False),
     (4, 4, 2, 20, 50, 1, 1, 0, True),
-    (5, 4, 1, 128, 100, 1, 1, 0, False), (5, 4, 1, 60, 23, 1, 1, 3, True), (5, 4, 1, 2, 333, 10, 4, 0, False),
+    (5, 4, 1, 128, 100, 1, 1, 0, False), (5, 4, 1, 60, 23, 1, 1, 3, True, 64), (5, 4, 1, 2, 333, 10, 4, 0, False),
     (5, 4, 1, 3, 90, 6, 1, 0, True),
     (5, 4, 2, 128, 100, 10, 1, 0, False), (5, 4, 2, 128, 100, 5, 2, 4, False), (5, 4, 2, 11, 100, 1, 1, 0, False),
     (5, 4, 2, 2, 2000, 10, 8, 0, False), (5, 4, 2, 3, 700, 3, 13, 9, False), (5, 4, 2, 4, 61, 4, 1, 0, True), (5, 4, 2, 13, 30, 1, 1, 0, True),
     (10, 6, 4, 2, 9, 1, 1, 0, False), (10, 6, 4, 1, 4, 1, 1, 2, True),
+    (5, 4, 2, 40, 100, 7, 1, 0, False, 512), (4, 4, 2, 9, 256, 16, 1, 0, True, 512), (5, 4, 2, 9000, 30, 1, 1, 7, False),
+    (4, 4, 2, 3000, 20, 1, 1, 6, True), (2, 3, 1, 70000, 9, 1, 1, 0, False), (5, 4, 2, 33, 300, 1, 4, 0, False, 128),
 ]
 
 
-@pytest.mark.parametrize("d,depth,p,B,L,chunks,segments,tile,stream", ON_CHIP_CASES)
-def test_on_chip_family(gpu, oracle, d, depth, p, B, L, chunks, segments, tile, stream):
+def split_case(case):
+    d, depth, p, B, L, chunks, segments, tile, stream = case[:9]
+    threads = case[9] if len(case) > 9 else 256
+    return d, depth, p, B, L, chunks, segments, tile, stream, threads
+
+
+@pytest.mark.parametrize("case", ON_CHIP_CASES, ids=lambda c: "-".join(str(v) for v in c))
+def test_on_chip_family(gpu, oracle, case):
+    d, depth, p, B, L, chunks, segments, tile, stream, threads = split_case(case)
     assert gpu.sig_on_chip_available(d, depth, p)
     x = workloads.brownian_paths(B, L, d, seed=5000 + 17 * B + L + chunks)
     plan = gpu.make_plan(gpu.SIG_VARIANT_ON_CHIP, prefix_depth=p, chunks=chunks, segments=segments,
-                         tile_steps=tile)
+                         tile_steps=tile, threads=threads)
     check(gpu, oracle, x, depth, stream, plan, label="on-chip")
+
+
+@pytest.mark.parametrize("case", [c for c in ON_CHIP_CASES if c[5] == 1], ids=lambda c: "-".join(str(v) for v in c))
+def test_on_chip_independent_wavefronts(gpu, oracle, case):
+    """The barrier-free variant of the single-chunk kernels (plan.reserved[0] = 1)."""
+    d, depth, p, B, L, chunks, segments, tile, stream, threads = split_case(case)
+    x = workloads.brownian_paths(B, L, d, seed=7000 + 13 * B + L)
+    plan = gpu.make_plan(gpu.SIG_VARIANT_ON_CHIP, prefix_depth=p, chunks=1, segments=segments,
+                         tile_steps=tile, threads=threads, independent_waves=1)
+    if gpu.sig_plan_validate(B, L, d, depth, int(stream), plan) != gpu.SIG_OK:
+        pytest.skip("plan not valid for this variant")
+    check(gpu, oracle, x, depth, stream, plan, label="independent")
 
 
 def test_single_increment_and_repeated_points(gpu, oracle):
