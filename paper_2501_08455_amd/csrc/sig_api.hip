@@ -131,6 +131,33 @@ bool finish_on_chip(const OnChipKernelInfo *ki, int cus, int64_t B, int64_t L, i
         const int64_t by_lds_cu = (160 * 1024) / (lds > 0 ? lds : 1);
         if (by_lds_cu >= 1 && per_cu > by_lds_cu) per_cu = by_lds_cu;
         args->resident_workgroups = (int32_t)(per_cu * cus);
+        args->num_cus = cus;
+        // Skewed start (see the kernel): only when the launch needs more than one round of workgroups, so
+        // that the lock-step of loads, arithmetic and stores would repeat.  One workgroup's lifetime is
+        // estimated as steps x vector instructions per step (1.25 x the FMAs per lane) x resident wavefronts
+        // per SIMD x 2.4 cycles at 2.3 GHz, in 100 MHz ticks; the skew per residency slot is that lifetime
+        // divided by the slots of a CU.  plan.reserved[1]: > 0 sets the ticks, < 0 switches the skew off.
+        args->stagger_ticks = 0;
+        if (pl.reserved[1] > 0) {
+            args->stagger_ticks = pl.reserved[1];
+        } else if (pl.reserved[1] == 0 && !stream_flag && pl.chunks == 1 && args->cooperative && Q <= pl.threads) {
+            const int64_t items = ceil_div(B * pl.segments, G);
+            // worth it only where the HBM time is a large part of the arithmetic time (measured: it gains 12 % at
+            // 5 KB and 0.19 MFLOP per path, and loses a little from twice that path length on)
+            double fma_per_path_step = 0.0;
+            for (int m = 1; m <= rs.depth; ++m) fma_per_path_step += (double)(rs.depth - m + 1) * (double)rs.pow[m];
+            const double t_hbm = 4.0 * ((double)L * ki->d + (double)rs.D) / 4.58e12;  // at the measured copy rate
+            const double t_alu = 2.0 * fma_per_path_step * (double)K / 126e12;      // at the measured FMA rate
+            if (items > args->resident_workgroups && per_cu > 1 && t_hbm > 0.6 * t_alu) {
+                double fma_per_lane = fma_per_path_step;
+                fma_per_lane /= (double)Q;
+                const double waves_per_simd_res = (double)per_cu * waves_per_wg / 4.0;
+                const double life_us = (double)T * 1.25 * fma_per_lane * waves_per_simd_res * 2.4 / 2300.0;
+                double ticks = life_us * 100.0 / (double)per_cu;
+                if (ticks > 5000.0) ticks = 5000.0;
+                args->stagger_ticks = (int32_t)ticks;
+            }
+        }
     }
     return true;
 }

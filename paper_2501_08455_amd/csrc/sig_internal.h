@@ -55,6 +55,8 @@ struct OnChipArgs {
     int32_t groups;      // (path, segment) pairs per workgroup (1 when a chunk's lanes span several workgroups)
     int32_t row_shift;   // log2 of the padded length of one chunk's stretch of a tile (tile_steps * d floats)
     int32_t resident_workgroups;  // workgroups the device keeps resident at once (persistent kernels); 0: no limit
+    int32_t stagger_ticks;  // start delay (100 MHz ticks) per residency slot of the first wave of workgroups; 0: none
+    int32_t num_cus;        // compute units of the device
     int32_t cooperative;  // chunks == 1 only: 1 = workgroup-wide tiles with barriers instead of independent wavefronts
     int32_t stream_flag;
 };

@@ -173,6 +173,28 @@ __device__ __forceinline__ void fused_step(Lane<d, N, P> &ln, const Inc<d, P> &i
     Level<d, N, P, N>::run(ln.s, ln.pre, dls, inc.du);
 }
 
+// 16- and 8-byte vectors that are only 4-byte aligned: a lane's blocks start at multiples of d^r floats, so
+// their alignment varies from lane to lane, and the hardware takes dword-aligned vector accesses
+typedef float vec4f_u __attribute__((ext_vector_type(4), aligned(4)));
+typedef float vec2f_u __attribute__((ext_vector_type(2), aligned(4)));
+
+// copy CNT consecutive registers s[OFF ..] to dst[0 ..] with the widest stores
+template <int OFF, int CNT, int SZ>
+__device__ __forceinline__ void store_run(float *dst, const float (&s)[SZ])
+{
+    if constexpr (CNT >= 4) {
+        vec4f_u v = {s[OFF], s[OFF + 1], s[OFF + 2], s[OFF + 3]};
+        *reinterpret_cast<vec4f_u *>(dst) = v;
+        store_run<OFF + 4, CNT - 4, SZ>(dst + 4, s);
+    } else if constexpr (CNT >= 2) {
+        vec2f_u v = {s[OFF], s[OFF + 1]};
+        *reinterpret_cast<vec2f_u *>(dst) = v;
+        store_run<OFF + 2, CNT - 2, SZ>(dst + 2, s);
+    } else if constexpr (CNT == 1) {
+        dst[0] = s[OFF];
+    }
+}
+
 // write / read a lane's state to / from a row laid out like an output row
 template <int d, int N, int P>
 __device__ __forceinline__ void store_state(float *row, unsigned u, const Lane<d, N, P> &ln)
@@ -181,9 +203,7 @@ __device__ __forceinline__ void store_state(float *row, unsigned u, const Lane<d
     static_for<(P == 0 ? 1 : 0), Sh::R + 1>([&](auto rc) __attribute__((always_inline)) {
         constexpr int r = decltype(rc)::value;
         constexpr int cnt = cpow(d, r);
-        float *dst = row + Sh::row_off(P + r) + u * cnt;
-#pragma unroll
-        for (int i = 0; i < cnt; ++i) dst[i] = ln.s[Sh::sub_off(r) + i];
+        store_run<Sh::sub_off(r), cnt, Sh::SZ>(row + Sh::row_off(P + r) + u * cnt, ln.s);
     });
     static_for<1, P>([&](auto mc) __attribute__((always_inline)) {
         constexpr int m = decltype(mc)::value;
@@ -324,6 +344,15 @@ __global__ __launch_bounds__((max_threads<d, N, P, CHUNKED>())) void sig_on_chip
     constexpr int D = Sh::D;
 
     SIG_TICK(0);
+    // Skewed start.  All workgroups of a launch would otherwise load, fold and store in lock-step, and
+    // the HBM phases would not overlap the arithmetic.  The workgroups that are resident first are delayed by
+    // their residency slot (about blockIdx / number of CUs) times a fraction of one workgroup's lifetime;
+    // later workgroups start when earlier ones retire and inherit the skew.  The wait ends by the clock.
+    if (!CHUNKED && A.stagger_ticks > 0 && (int)blockIdx.x < A.resident_workgroups) {
+        const unsigned long long until =
+            wall_clock64() + (unsigned long long)(blockIdx.x / (unsigned)A.num_cus) * (unsigned long long)A.stagger_ticks;
+        while (wall_clock64() < until) __builtin_amdgcn_s_sleep(32);
+    }
     const int tid = threadIdx.x;
     const int nthr = blockDim.x;
     const int64_t K = A.L - 1;
@@ -523,7 +552,51 @@ __global__ __launch_bounds__((max_threads<d, N, P, CHUNKED>())) void sig_on_chip
         if constexpr (!PIPE) {
             for (int t0 = 0; t0 < T; t0 += TT) {
                 __syncthreads();
-                for (int idx = tid; idx < flat; idx += nthr) put_one(tile0, idx, fetch_one(idx, t0));
+                // four consecutive floats per thread and element (dword-aligned 16-byte loads), two elements
+                // per trip so that their loads are in flight together (more would raise the kernel's register count)
+                const int vshift = rshift > 2 ? rshift - 2 : 0;  // vectors per chunk row, padded to a power of two
+                const int vmask = (1 << vshift) - 1;
+                const int vflat = NGC << vshift;
+                for (int base = 0; base < vflat; base += 2 * nthr) {
+                    vec4f_u dv[2];
+#pragma unroll
+                    for (int e = 0; e < 2; ++e) {
+                        const int idx = base + e * nthr + tid;
+                        const int gc = idx >> vshift;
+                        const int r = (idx & vmask) * 4;
+                        dv[e] = vec4f_u{0.0f, 0.0f, 0.0f, 0.0f};
+                        if (idx < vflat && r < row_floats) {
+                            const ChunkDesc dsc = desc[gc];
+                            const int valid = (dsc.steps - t0) * d;  // floats of this chunk still inside the path
+                            const float *x = A.path + dsc.base + (int64_t)t0 * d + r;
+                            if (r + 3 < valid) {
+                                const vec4f_u lo = *reinterpret_cast<const vec4f_u *>(x);
+                                const vec4f_u hi = *reinterpret_cast<const vec4f_u *>(x + d);
+                                dv[e] = hi - lo;
+                            } else {
+#pragma unroll
+                                for (int j = 0; j < 4; ++j)
+                                    if (r + j < valid) dv[e][j] = x[j + d] - x[j];
+                            }
+                        }
+                    }
+#pragma unroll
+                    for (int e = 0; e < 2; ++e) {
+                        const int idx = base + e * nthr + tid;
+                        const int gc = idx >> vshift;
+                        const int r = (idx & vmask) * 4;
+                        if (idx < vflat && r < row_floats) {
+                            float *trow = tile0 + gc * row_floats + r;
+                            if (r + 3 < row_floats) {
+                                *reinterpret_cast<vec4f_u *>(trow) = dv[e];
+                            } else {
+#pragma unroll
+                                for (int j = 0; j < 4; ++j)
+                                    if (r + j < row_floats) trow[j] = dv[e][j];
+                            }
+                        }
+                    }
+                }
                 __syncthreads();
                 if (t0 == 0) SIG_TICK(6);
                 consume(tile0, t0);
@@ -559,6 +632,7 @@ __global__ __launch_bounds__((max_threads<d, N, P, CHUNKED>())) void sig_on_chip
 
     if constexpr (!CHUNKED) {
         fold_chunk(std::integral_constant<bool, STREAM>{});
+        SIG_TICK(2);
         if constexpr (!STREAM) {
             if (active) {
                 float *dst = (W == 1) ? A.out + b * D : A.partial + (int64_t)mygroup * D;
