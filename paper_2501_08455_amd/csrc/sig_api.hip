@@ -71,9 +71,11 @@ bool finish_on_chip(const OnChipKernelInfo *ki, int cus, int64_t B, int64_t L, i
     // groups per workgroup: as many as the threads hold, fewer if their chunk signatures overflow LDS
     int G = Q > pl.threads ? 1 : (int)(slots / pl.chunks);
     if (pl.chunks > 1) {
-        // two buffers of chunk signatures (the second one half as large in final mode)
-        const int64_t per_group = (int64_t)(stream_flag ? 2 * pl.chunks : pl.chunks + (pl.chunks + 1) / 2) *
-                                  rs.D * (int64_t)sizeof(float);
+        // chunk signatures in LDS: one buffer (final mode, lane state small enough for the register tree),
+        // one and a half (final mode, LDS tree) or two (stream mode: the scan's prefixes)
+        const int64_t rows = stream_flag ? 2 * pl.chunks
+                             : ki->state_floats <= 64 ? pl.chunks : pl.chunks + (pl.chunks + 1) / 2;
+        const int64_t per_group = rows * rs.D * (int64_t)sizeof(float);
         int64_t fit = (kMaxLdsBytes - 4096) / per_group;
         if (fit < 1) return false;
         if (G > fit) G = (int)fit;
@@ -202,7 +204,9 @@ int plan_auto(const sig_ctx *ctx, int64_t B, int64_t L, int stream_flag, const R
             int64_t pieces = ceil_div(want_lanes, B * Q);
             // chunks side by side in a workgroup (stream kernels keep a chunk's lanes inside one wavefront)
             int64_t cmax = (stream_flag && Q <= kWave) ? (int64_t)(kThreads / kWave) * (kWave / Q) : kThreads / Q;
-            int64_t clds = (kMaxLdsBytes - kTileLdsBytes) / (2 * rs.D * (int64_t)sizeof(float));  // two signature buffers
+            // LDS for the chunk signatures: two buffers in stream mode, one when the tree runs in registers
+            int64_t clds = (kMaxLdsBytes - kTileLdsBytes) /
+                           ((stream_flag || ki->state_floats > 64 ? 2 : 1) * rs.D * (int64_t)sizeof(float));
             if (cmax > clds) cmax = clds;
             if (cmax > K / kMinChunkSteps) cmax = K / kMinChunkSteps;
             if (cmax < 1) cmax = 1;

@@ -311,6 +311,69 @@ __device__ __forceinline__ void lds_tree_reduce(float *&src, float *&dst, int G,
     }
 }
 
+
+// ------------------------------------------------------------------------------------------
+// Product of Eq. 4 with the left factor in registers:  ln <- ln (x) b,  b a row of D floats (LDS).
+// A lane holds the left factor's coefficients of the words below its prefix u and of u's own prefixes, which
+// are exactly the a-factors its words need:
+//   c[u v] = a[u v] + b[u v] + sum_{i=1}^{P} a[u_{1:i}] b[(u_{i+1:P}, v)] + sum_{j=1}^{r-1} a[u v_{1:j}] b[v_{j+1:r}]
+// for a word (u, v), |v| = r >= 1, and for the prefix words u_{1:n}, n <= P,
+//   c[u_{1:n}] = a[u_{1:n}] + b[u_{1:n}] + sum_{i=1}^{n-1} a[u_{1:i}] b[u_{i+1:n}].
+// The b-factors are suffix words: runs of d^r consecutive floats at lane-dependent offsets.  Levels go from
+// N down to 1 so that the result can replace the left factor in place.
+template <int d, int N, int P>
+__device__ __forceinline__ void reg_product(Lane<d, N, P> &ln, const float *b, unsigned u)
+{
+    using Sh = Shape<d, N, P>;
+    // a[u_{1:i}] for i = 1..P (old values, kept while the prefix words are updated last)
+    float apre[P > 0 ? P : 1];
+    apre[0] = 0.0f;
+    static_for<1, P + 1>([&](auto ic) __attribute__((always_inline)) {
+        constexpr int i = decltype(ic)::value;
+        apre[i - 1] = (i < P) ? ln.pre[i - 1] : ln.s[0];
+    });
+    // sub-tree levels, deepest first
+    static_for<0, Sh::R>([&](auto qc) __attribute__((always_inline)) {
+        constexpr int r = Sh::R - decltype(qc)::value;  // R .. 1
+        constexpr int n = P + r;
+        constexpr int cnt = cpow(d, r);
+        float acc[cnt];
+        const float *bn = b + Sh::row_off(n) + u * cnt;
+#pragma unroll
+        for (int v = 0; v < cnt; ++v) acc[v] = ln.s[Sh::sub_off(r) + v] + bn[v];
+        // a-factors that are prefixes of u: b-factor (u_{i+1:P}, v) is a run of cnt floats of level n - i
+        static_for<1, P + 1>([&](auto ic) __attribute__((always_inline)) {
+            constexpr int i = decltype(ic)::value;
+            const float *bs = b + Sh::row_off(n - i) + (u % (unsigned)cpow(d, P - i)) * cnt;
+#pragma unroll
+            for (int v = 0; v < cnt; ++v) acc[v] = fmaf(apre[i - 1], bs[v], acc[v]);
+        });
+        // a-factors inside the sub-tree: a[u v_{1:j}] times b[v_{j+1:r}]
+        static_for<1, r>([&](auto jc) __attribute__((always_inline)) {
+            constexpr int j = decltype(jc)::value;
+            constexpr int tail = cpow(d, r - j);
+            const float *bs = b + Sh::row_off(r - j);
+#pragma unroll
+            for (int v = 0; v < cnt; ++v) acc[v] = fmaf(ln.s[Sh::sub_off(j) + v / tail], bs[v % tail], acc[v]);
+        });
+#pragma unroll
+        for (int v = 0; v < cnt; ++v) ln.s[Sh::sub_off(r) + v] = acc[v];
+    });
+    // prefix words u_{1:n}, n = P .. 1 (every lane keeps its own copy)
+    static_for<0, P>([&](auto qc) __attribute__((always_inline)) {
+        constexpr int n = P - decltype(qc)::value;  // P .. 1
+        float acc = apre[n - 1] + b[Sh::row_off(n) + u / (unsigned)cpow(d, P - n)];
+        static_for<1, n>([&](auto ic) __attribute__((always_inline)) {
+            constexpr int i = decltype(ic)::value;
+            // suffix u_{i+1:n}: letters i+1..n of u
+            const unsigned suffix = (u / (unsigned)cpow(d, P - n)) % (unsigned)cpow(d, n - i);
+            acc = fmaf(apre[i - 1], b[Sh::row_off(n - i) + suffix], acc);
+        });
+        if constexpr (n < P) ln.pre[n - 1] = acc;
+        else ln.s[0] = acc;
+    });
+}
+
 extern __shared__ __align__(16) float sig_onchip_smem[];
 
 // per (group, chunk) of a workgroup: where its increments start in the path and how many it has
@@ -646,7 +709,23 @@ __global__ __launch_bounds__((max_threads<d, N, P, CHUNKED>())) void sig_on_chip
         if (active) store_state<d, N, P>(sigA + mygc * D, u, ln);
         float *sigB = sigA + NGC * D;  // second buffer: [G][(C+1)/2][D] (final) or [NGC][D] (stream)
         __syncthreads();
-        if constexpr (!STREAM) {
+        if constexpr (!STREAM && Sh::SZ <= 64) {
+            // pairwise tree with the left factor in registers: in the round with stride st chunk c (a multiple
+            // of 2 st) absorbs chunk c + st, which has put its row into LDS; the result stays in c's lanes
+            SIG_TICK(3);
+            for (int st = 1; st < C; st <<= 1) {
+                if (st > 1) {
+                    if (active && (c & (2 * st - 1)) == st) store_state<d, N, P>(sigA + mygc * D, u, ln);
+                    __syncthreads();
+                }
+                if (active && (c & (2 * st - 1)) == 0 && c + st < C) reg_product<d, N, P>(ln, sigA + (mygc + st) * D, u);
+            }
+            SIG_TICK(4);
+            if (active && c == 0) {
+                float *o = (W == 1) ? A.out + (int64_t)mygroup * D : A.partial + (int64_t)mygroup * D;
+                store_state<d, N, P>(o, u, ln);
+            }
+        } else if constexpr (!STREAM) {
             float *src = sigA, *dst = sigB;
             int src_stride = C, dst_stride = (C + 1) / 2;
             SIG_TICK(3);
@@ -663,21 +742,34 @@ __global__ __launch_bounds__((max_threads<d, N, P, CHUNKED>())) void sig_on_chip
             }
         } else {
             // inclusive scan left to right into the second buffer: B[0] = A[0], B[c] = B[c-1] (x) A[c]
-            for (int x = tid; x < G * D; x += nthr) {
-                const int g2 = x / D;
-                const int pos = x - g2 * D;
-                sigB[(g2 * C) * D + pos] = sigA[(g2 * C) * D + pos];
-            }
-            __syncthreads();
-            for (int c2 = 1; c2 < C; ++c2) {
-                const int total = G * RP::ITEMS;
-                for (int x = tid; x < total; x += nthr) {
-                    const int g2 = x / RP::ITEMS;
-                    const int it = x - g2 * RP::ITEMS;
-                    const int rowi = g2 * C + c2;
-                    RP::item(sigB + (rowi - 1) * D, sigA + rowi * D, sigB + rowi * D, it);
+            if constexpr (Sh::SZ <= 64 && WAVE_SLOTS) {
+                // the lanes of chunk 0 (one wavefront's slot) keep the running product in registers and
+                // multiply it by each later chunk's row; B[C-1] is nobody's carry and is skipped
+                if (active && c == 0) {
+                    store_state<d, N, P>(sigB + mygc * D, u, ln);
+                    for (int c2 = 1; c2 + 1 < C; ++c2) {
+                        reg_product<d, N, P>(ln, sigA + (mygc + c2) * D, u);
+                        store_state<d, N, P>(sigB + (mygc + c2) * D, u, ln);
+                    }
                 }
                 __syncthreads();
+            } else {
+                for (int x = tid; x < G * D; x += nthr) {
+                    const int g2 = x / D;
+                    const int pos = x - g2 * D;
+                    sigB[(g2 * C) * D + pos] = sigA[(g2 * C) * D + pos];
+                }
+                __syncthreads();
+                for (int c2 = 1; c2 < C; ++c2) {
+                    const int total = G * RP::ITEMS;
+                    for (int x = tid; x < total; x += nthr) {
+                        const int g2 = x / RP::ITEMS;
+                        const int it = x - g2 * RP::ITEMS;
+                        const int rowi = g2 * C + c2;
+                        RP::item(sigB + (rowi - 1) * D, sigA + rowi * D, sigB + rowi * D, it);
+                    }
+                    __syncthreads();
+                }
             }
             // every chunk restarts from the signature of everything before it and emits its prefixes
             if (c == 0) identity_state<d, N, P>(ln);
@@ -949,7 +1041,9 @@ int64_t on_chip_lds_bytes(const OnChipArgs &A)
     int64_t floats = desc_floats((int)NGC) + (pipe ? 2 : 1) * (int64_t)round4((int)(NGC * A.tile_steps * d));
     if (A.chunks > 1) {
         floats += NGC * Sh::D;
-        floats += (A.stream_flag ? NGC : (int64_t)A.groups * ((A.chunks + 1) / 2)) * Sh::D;
+        // second buffer: the scan's prefixes (stream) or the ping-pong half of the LDS tree (final, large state)
+        if (A.stream_flag) floats += NGC * Sh::D;
+        else if (Sh::SZ > 64) floats += (int64_t)A.groups * ((A.chunks + 1) / 2) * Sh::D;
     } else if (A.stream_flag && Sh::Q <= kWave) {
         floats += NGC * Sh::D;  // rows staged for emission
     }
