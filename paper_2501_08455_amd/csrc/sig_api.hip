@@ -18,7 +18,7 @@ namespace {
 constexpr int kDefaultCUs = 256;
 constexpr int kThreads = 256;
 constexpr int kMinChunkSteps = 8;          // chunks inside a workgroup are at least this long
-constexpr int kMinSegmentChunkSteps = 32;  // ... and this long before time is also cut across workgroups
+constexpr int kMinSegmentChunkSteps = 48;  // ... and this long before time is also cut across workgroups
 
 int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
@@ -57,7 +57,11 @@ bool finish_on_chip(const OnChipKernelInfo *ki, int cus, int64_t B, int64_t L, i
                                                         : pl.threads / Q;
     if (Q <= pl.threads && pl.chunks > slots) return false;
     if (stream_flag && pl.segments != 1) return false;       // carries across workgroups are not implemented
-    if (pl.segments > 1 && (pl.segments + (pl.segments + 1) / 2) * rs.D * (int64_t)sizeof(float) > kMaxLdsBytes) return false;
+    // the LDS-tree join holds all rows of a path at once; the register join stages one row at a time
+    if (pl.segments > 1 && ki->state_floats > 64 &&
+        (pl.segments + (pl.segments + 1) / 2) * rs.D * (int64_t)sizeof(float) > kMaxLdsBytes)
+        return false;
+    if (pl.segments > 1 && pl.segments * rs.D * (int64_t)sizeof(float) > kMaxLdsBytes) return false;
     if (B * (int64_t)pl.segments > INT32_MAX) return false;
     args->B = B;
     args->L = L;
@@ -218,7 +222,7 @@ int plan_auto(const sig_ctx *ctx, int64_t B, int64_t L, int stream_flag, const R
                 int64_t wmax = K / (C * kMinSegmentChunkSteps);
                 if (W > wmax) W = wmax;
                 if (W > 8) W = 8;
-                while (W > 1 && (W + (W + 1) / 2) * rs.D * (int64_t)sizeof(float) > kMaxLdsBytes) --W;
+                while (W > 1 && (W + (ki->state_floats > 64 ? (W + 1) / 2 : 0)) * rs.D * (int64_t)sizeof(float) > kMaxLdsBytes) --W;
                 if (W < 1) W = 1;
             }
             pl->chunks = (int)C;

@@ -1150,11 +1150,67 @@ hipError_t on_chip_join(const float *partial, float *out, int64_t B, int W, hipS
     return hipGetLastError();
 }
 
+// Join with the running product in registers (lane state small enough).  One workgroup per path: all of its
+// W partial rows are copied to LDS in one go (every thread helps, loads batched), then the Q lanes that own the
+// sub-trees multiply them left to right; no barrier is needed between the products.
+template <int d, int N, int P>
+__global__ __launch_bounds__(256) void sig_join_reg_kernel(const float *partial, float *out, int W)
+{
+    using Sh = Shape<d, N, P>;
+    constexpr int Q = Sh::Q;
+    constexpr int D = Sh::D;
+    const int tid = threadIdx.x, nthr = blockDim.x;
+    const int64_t b = blockIdx.x;
+    float *rows = sig_onchip_smem;  // [W][D]
+    const float *src = partial + b * W * D;
+    const int total = W * D;
+    for (int base = 0; base < total; base += 8 * nthr) {
+        float v[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int x = base + e * nthr + tid;
+            v[e] = x < total ? src[x] : 0.0f;
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int x = base + e * nthr + tid;
+            if (x < total) rows[x] = v[e];
+        }
+    }
+    __syncthreads();
+    if (tid < Q) {
+        const unsigned u = (unsigned)tid;
+        Lane<d, N, P> ln;
+        load_state<d, N, P>(rows, u, ln);
+        for (int w = 1; w < W; ++w) reg_product<d, N, P>(ln, rows + w * D, u);
+        store_state<d, N, P>(out + b * D, u, ln);
+    }
+}
+
+template <int d, int N, int P>
+hipError_t on_chip_join_reg(const float *partial, float *out, int64_t B, int W, hipStream_t st)
+{
+    using Sh = Shape<d, N, P>;
+    if (B <= 0 || B > INT32_MAX || W < 2 || Sh::Q > 256) return hipErrorInvalidValue;
+    const int64_t lds = (int64_t)W * Sh::D * (int64_t)sizeof(float);
+    if (lds > kMaxLdsBytes) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((sig_join_reg_kernel<d, N, P>), dim3((unsigned)B), dim3(256), (size_t)lds, st, partial, out, W);
+    return hipGetLastError();
+}
+
+// the join a table entry uses: in registers when the lane state is small, else the LDS tree
+template <int d, int N, int P>
+hipError_t on_chip_join_any(const float *partial, float *out, int64_t B, int W, hipStream_t st)
+{
+    if constexpr (Shape<d, N, P>::SZ <= 64 && Shape<d, N, P>::Q <= 256) return on_chip_join_reg<d, N, P>(partial, out, B, W, st);
+    else return on_chip_join<d, N>(partial, out, B, W, st);
+}
+
 #define SIG_ON_CHIP_ENTRY(d, N, P)                                                              \
     {                                                                                           \
         d, N, P, ::sig::onchip::Shape<d, N, P>::Q, ::sig::onchip::Shape<d, N, P>::SZ,           \
             d, &::sig::onchip::on_chip_launch<d, N, P>,         \
-            &::sig::onchip::on_chip_lds_bytes<d, N, P>, &::sig::onchip::on_chip_join<d, N>      \
+            &::sig::onchip::on_chip_lds_bytes<d, N, P>, &::sig::onchip::on_chip_join_any<d, N, P> \
     }
 
 }  // namespace onchip
