@@ -215,10 +215,19 @@ int plan_auto(const sig_ctx *ctx, int64_t B, int64_t L, int stream_flag, const R
             if (cmax > K / kMinChunkSteps) cmax = K / kMinChunkSteps;
             if (cmax < 1) cmax = 1;
             int64_t C = pieces < cmax ? pieces : cmax;
+            if (!(stream_flag && Q <= kWave)) {
+                // lanes are packed group after group: prefer a nearby chunk count whose groups fill the workgroup
+                // (e.g. Q = 25: 6 chunks leave 106 of 256 lanes idle, 5 chunks fit twice)
+                auto used = [&](int64_t c) { return (kThreads / (c * Q)) * c * Q; };
+                int64_t best = C;
+                for (int64_t c = (C > 2 ? C - 2 : 1); c <= C + 4 && c <= cmax; ++c)
+                    if (used(c) * 100 > used(best) * 105 || (used(c) * 100 > used(best) * 95 && best > C && c >= C && c < best)) best = c;
+                C = best;
+            }
             // further workgroups along time only while each chunk keeps a long sequential run
             int64_t W = 1;
             if (!stream_flag) {
-                W = ceil_div(pieces, C);
+                W = (pieces + C / 2) / C;  // rounded: a second launch is not worth a few missing lanes
                 int64_t wmax = K / (C * kMinSegmentChunkSteps);
                 if (W > wmax) W = wmax;
                 if (W > 8) W = 8;
