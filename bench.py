@@ -22,12 +22,15 @@ PEAK_HBM_GBS = 8000.0      # MI355X HBM3E, published
 # copy kernel of the same run (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0); see profiles/hbm_traffic.md.
 # Keyed by (configuration, batch).
 MEASURED_TRAFFIC_BYTES = {
-    ("C2", 128): (2 * 169.1 + 392.0) * 1024,
-    ("C2", 65536): (2 * 64335.0 + 199682.3) * 1024,
-    ("C3", 128): (2 * 2605.3 + 3136.0) * 1024,
-    ("C4", 64): (2 * 179.8 + 21724.8) * 1024,
-    ("C4", 4096): (2 * 9784.8 + 1389407.9) * 1024,
-    ("C5", 16): (2 * 359.5 + 69714.2) * 1024,
+    ("C1", 4): (2 * 14.1 + 0.3) * 1024,
+    ("C2", 128): (2 * 178.7 + 392.0) * 1024,
+    ("C3", 128): (2 * 2578.8 + 1568.0) * 1024,
+    ("C4", 64): (2 * 190.8 + 21722.6) * 1024,
+    ("C5", 16): (2 * 366.5 + 69748.0) * 1024,
+    ("C1", 1 << 20): (2 * 65564.3 + 57344.0) * 1024,
+    ("C2", 65536): (2 * 64522.5 + 199687.7) * 1024,
+    ("C3", 4096): (2 * 81160.2 + 12480.0) * 1024,
+    ("C4", 4096): (2 * 9782.7 + 1389374.0) * 1024,
 }
 
 
