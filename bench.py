@@ -78,20 +78,31 @@ def roofline(flops, nbytes, ms, traffic=None):
             "frac": ach / PEAK_HBM_GBS, "traffic": traffic}
 
 
-def bench_config(binding, workloads, ctx, cfg, B, steps, warmup):
+def bench_config(binding, workloads, ctx, cfg, B, steps, warmup, plan=None, label=""):
     import torch
     x = workloads.make_paths(cfg, B=B)
     xt = torch.from_numpy(x).cuda()
     flops, nbytes, D, rows = algorithmic_work(cfg, B, workloads)
     out = torch.empty((B, rows, D) if cfg.stream else (B, D), dtype=torch.float32, device="cuda")
-    ms_ev, ms_wall = time_calls(binding, ctx, xt, cfg.depth, int(cfg.stream), out, steps, warmup)
-    rc, pl = binding.sig_plan(ctx, B, cfg.L, cfg.d, cfg.depth, int(cfg.stream))
-    res = {"workload": "%s B=%d L=%d d=%d depth=%d %s" % (cfg.name, B, cfg.L, cfg.d, cfg.depth,
-                                                          "stream" if cfg.stream else "final"),
+    ms_ev, ms_wall = time_calls(binding, ctx, xt, cfg.depth, int(cfg.stream), out, steps, warmup, plan=plan)
+    if plan is None:
+        rc, pl = binding.sig_plan(ctx, B, cfg.L, cfg.d, cfg.depth, int(cfg.stream))
+    else:
+        pl = plan
+    res = {"workload": "%s B=%d L=%d d=%d depth=%d %s%s" % (cfg.name, B, cfg.L, cfg.d, cfg.depth,
+                                                            "stream" if cfg.stream else "final", label),
            "ms_per_step": ms_ev, "ms_per_step_host_clock": ms_wall, "steps": steps,
            "paths_per_s": B / (ms_ev * 1e-3), "terms_per_s": B * rows * D / (ms_ev * 1e-3),
            "roofline": roofline(flops, nbytes, ms_ev, MEASURED_TRAFFIC_BYTES.get((cfg.name, B))),
            "algorithmic": {"flops": flops, "bytes": nbytes}, "plan": pl.as_dict()}
+    if plan is not None and plan.variant == binding.SIG_VARIANT_HBM_STREAMING:
+        # the state-in-HBM design reads and writes every coefficient once per increment: its own byte count
+        design_bytes = 8.0 * D * B * (cfg.L - 1)
+        ach = design_bytes / (ms_ev * 1e-3) / 1e9
+        res["roofline"] = {"bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                           "frac": ach / PEAK_HBM_GBS, "traffic": None,
+                           "note": "bytes of the state-in-HBM design (8 B per coefficient and increment), "
+                                   "much of which is served by L2 / Infinity Cache at this size"}
     del xt, out
     return res
 
@@ -190,6 +201,12 @@ def main():
         for name, B, steps, warm in plan:
             c = workloads.CONFIGS[name]
             extras.append(bench_config(binding, workloads, ctx, c, B or c.B, steps, warm))
+        # the HBM-streaming family (the fallback for shapes without a compiled on-chip kernel) on C5
+        c5 = workloads.CONFIGS["C5"]
+        rc, auto = binding.sig_plan(ctx, c5.B, c5.L, c5.d, c5.depth, 0)
+        hbm_plan = binding.make_plan(binding.SIG_VARIANT_HBM_STREAMING, prefix_depth=2)
+        extras.append(bench_config(binding, workloads, ctx, c5, c5.B, 20, 5, plan=hbm_plan,
+                                   label=" (HBM-streaming family)"))
         line["all_configs"] = extras
     if args.anchors:
         line["anchors"] = anchors(binding)

@@ -38,6 +38,16 @@ int check_shape(int64_t B, int64_t L, int d, int depth, int stream_flag, RowShap
     return SIG_OK;
 }
 
+// LDS of the HBM-streaming kernel for prefix depth p: one tile of increments and two chain buffers
+bool streaming_fits(const RowShape &rs, int p)
+{
+    int tile = 8192 / rs.d;
+    if (tile > 64) tile = 64;
+    if (tile < 1) tile = 1;
+    const int64_t gcap = rs.depth - 1 - p >= 0 ? rs.pow[rs.depth - 1 - p] : 1;
+    return ((int64_t)tile * rs.d + 2 * gcap) * (int64_t)sizeof(float) <= kMaxLdsBytes;
+}
+
 // Fill the derived launch fields of an on-chip plan (chunk_steps, tile_steps) and check every limit the kernel
 // relies on.  Returns false if the plan cannot run.
 bool finish_on_chip(const OnChipKernelInfo *ki, int cus, int64_t B, int64_t L, int stream_flag, const sig_plan_t &pl,
@@ -250,10 +260,13 @@ int plan_auto(const sig_ctx *ctx, int64_t B, int64_t L, int stream_flag, const R
     pl->chunks = 1;
     pl->segments = 1;
     pl->tile_steps = 0;
-    // cut the index space until there are enough workgroups, but keep at least one level to the workgroup
+    // cut the index space until the Horner-chain buffers of a sub-tree fit LDS (2 x d^{depth-1-p} floats) and
+    // there are enough workgroups, but keep at least one level to the workgroup
     int p = 0;
     const int64_t want_wgs = 4 * (int64_t)cus;
+    while (p < rs.depth - 1 && !streaming_fits(rs, p)) ++p;
     while (p < rs.depth - 1 && B * rs.pow[p] < want_wgs && rs.pow[rs.depth - p - 1] >= 4 * kThreads) ++p;
+    if (!streaming_fits(rs, p)) return SIG_ERR_TOO_LARGE;
     pl->prefix_depth = p;
     if (B * rs.pow[p] > INT32_MAX) return SIG_ERR_TOO_LARGE;
     return SIG_OK;
@@ -286,6 +299,7 @@ int run_plan(sig_ctx *ctx, const float *path, int64_t B, int64_t L, const RowSha
         if (pl.prefix_depth < 0 || pl.prefix_depth > rs.depth - 1) return SIG_ERR_INVALID;
         if (pl.threads < kWave || pl.threads > 256 || pl.threads % kWave) return SIG_ERR_INVALID;
         if (B * rs.pow[pl.prefix_depth] > INT32_MAX) return SIG_ERR_TOO_LARGE;
+        if (!streaming_fits(rs, pl.prefix_depth)) return SIG_ERR_INVALID;
         hipError_t e = launch_hbm_streaming(path, out, B, L, rs, pl.prefix_depth, stream_flag, pl.threads, st);
         return e == hipSuccess ? SIG_OK : SIG_ERR_HIP;
     }
@@ -382,6 +396,7 @@ int sig_plan_validate(int64_t B, int64_t L, int d, int depth, int stream_flag, c
         if (plan->prefix_depth < 0 || plan->prefix_depth > rs.depth - 1) return SIG_ERR_INVALID;
         if (plan->threads < kWave || plan->threads > 256 || plan->threads % kWave) return SIG_ERR_INVALID;
         if (B * rs.pow[plan->prefix_depth] > INT32_MAX) return SIG_ERR_TOO_LARGE;
+        if (!streaming_fits(rs, plan->prefix_depth)) return SIG_ERR_INVALID;
         return SIG_OK;
     }
     if (plan->variant != SIG_VARIANT_ON_CHIP) return SIG_ERR_INVALID;

@@ -28,18 +28,28 @@ struct StreamingParams {
     int p;          // prefix depth of the sub-tree a workgroup owns
     int stream;     // 0: in place in out[b]; 1: row k is written from row k-1
     int tile_steps; // increments staged in LDS at a time
+    int gcap;       // floats of each of the two Horner-chain buffers in LDS (>= d^{depth-1-p})
     uint32_t ntiles;             // d^p
     uint32_t pw[kMaxDepth + 1];  // d^n
     int64_t off[kMaxDepth + 2];  // start of level n in a row
 };
 
-// Dynamic LDS: [tile_steps][d] increments.
+// Dynamic LDS: [tile_steps][d] increments, then two chain buffers of gcap floats.
 extern __shared__ float sig_smem[];
 
+// One workgroup per (path, sub-tree below a prefix u of length p).  Per increment and level n (from depth
+// down to p+1) the Horner chain g_m (m = p .. n-1, see the file header) is swept level by level over the whole
+// sub-tree: g_m[c] = S_m[c] + g_{m-1}[c / d] * v[c mod d] / (n - m + 1), one thread per word c, reading S_m with
+// consecutive threads on consecutive floats and keeping g in LDS; then S_n[c] += g_{n-1}[c / d] * v[c mod d]
+// streams through the level once (read-modify-write in final mode, row k-1 -> row k in stream mode).  The
+// levels below the top one are d times smaller each, so the traffic is that of the top level: 8 bytes per
+// coefficient and increment.
 __global__ __launch_bounds__(256) void sig_hbm_streaming_kernel(StreamingParams P)
 {
-    __shared__ float pre[kMaxDepth + 1];   // pre[m] = S[u_{1:m}], m = 1..p (old values during a step)
-    __shared__ int ulet[kMaxDepth + 1];    // ulet[m] = letter u_m
+    __shared__ float pre[kMaxDepth + 1];    // pre[m] = S[u_{1:m}], m = 1..p (old values during a step)
+    __shared__ int ulet[kMaxDepth + 1];     // ulet[m] = letter u_m
+    __shared__ uint32_t pw[kMaxDepth + 1];  // d^n (copied out of the kernel arguments: they are indexed at run time)
+    __shared__ int64_t off[kMaxDepth + 2];
 
     const int d = P.d, depth = P.depth, p = P.p;
     const uint32_t tile = blockIdx.x % P.ntiles;   // u as a number in base d
@@ -48,7 +58,11 @@ __global__ __launch_bounds__(256) void sig_hbm_streaming_kernel(StreamingParams 
     const int64_t K = P.L - 1;
     const float *X = P.path + b * P.L * d;
     float *sh_delta = sig_smem;
+    float *g0 = sig_smem + P.tile_steps * d;
+    float *g1 = g0 + P.gcap;
 
+    for (int i = tid; i <= depth; i += nthr) pw[i] = P.pw[i];
+    for (int i = tid; i <= depth + 1; i += nthr) off[i] = P.off[i];
     if (tid == 0) {
         uint32_t rest = tile;
         for (int m = p; m >= 1; --m) { ulet[m] = (int)(rest % (uint32_t)d); rest /= (uint32_t)d; }
@@ -72,27 +86,39 @@ __global__ __launch_bounds__(256) void sig_hbm_streaming_kernel(StreamingParams 
         float *dst = P.stream ? P.out + (b * K + k) * P.D : P.out + b * P.D;
 
         for (int n = depth; n > p; --n) {
-            // one work item = one parent word (u, v) of length n-1; it updates its d children
-            const uint32_t nparents = P.pw[n - 1 - p];
-            for (uint32_t v = tid; v < nparents; v += nthr) {
-                float g = 1.0f;
-                for (int m = 1; m <= p; ++m) g = fmaf(g, dl[ulet[m]] * (1.0f / (float)(n - m + 1)), pre[m]);
-                for (int m = p + 1; m <= n - 1; ++m) {
-                    uint32_t idx = v / P.pw[n - 1 - m];          // (u, v)_{1:m} inside the sub-tree level m
-                    int letter = (int)(idx % (uint32_t)d);
-                    float Sm = first ? 0.0f : src[P.off[m] + (int64_t)tile * P.pw[m - p] + idx];
-                    g = fmaf(g, dl[letter] * (1.0f / (float)(n - m + 1)), Sm);
+            // g_p at the word u itself, from the prefix scalars (every thread computes it: p is small)
+            float gu = 1.0f;
+            for (int m = 1; m <= p; ++m) gu = fmaf(gu, dl[ulet[m]] * (1.0f / (float)(n - m + 1)), pre[m]);
+            // sweep the chain down the sub-tree: gprev holds g_{m-1} (size d^{m-1-p}), gcur receives g_m
+            float *gprev = g0, *gcur = g1;
+            if (tid == 0) gprev[0] = gu;
+            __syncthreads();
+            for (int m = p + 1; m <= n - 1; ++m) {
+                const uint32_t cnt = pw[m - p];
+                const float scale = 1.0f / (float)(n - m + 1);
+                const float *sm = src + off[m] + (int64_t)tile * cnt;
+                for (uint32_t c = tid; c < cnt; c += nthr) {
+                    const uint32_t w = c / (uint32_t)d;
+                    const float Sm = first ? 0.0f : sm[c];
+                    gcur[c] = fmaf(gprev[w], dl[c - w * d] * scale, Sm);
                 }
-                const int64_t base = P.off[n] + ((int64_t)tile * nparents + v) * d;
-                for (int a = 0; a < d; ++a) {
-                    float old = first ? 0.0f : src[base + a];
-                    dst[base + a] = fmaf(g, dl[a], old);
+                __syncthreads();
+                float *t = gprev; gprev = gcur; gcur = t;
+            }
+            // update level n: consecutive threads on consecutive coefficients
+            {
+                const uint32_t cnt = pw[n - p];
+                const int64_t base = off[n] + (int64_t)tile * cnt;
+                for (uint32_t c = tid; c < cnt; c += nthr) {
+                    const uint32_t w = c / (uint32_t)d;
+                    const float old = first ? 0.0f : src[base + c];
+                    dst[base + c] = fmaf(gprev[w], dl[c - w * d], old);
                 }
             }
-            // in place: level n-1 may only be overwritten after every reader of it at level n is done
-            if (!P.stream) __syncthreads();
+            // in place: level n-1 may only be overwritten after every reader of it at level n is done; the
+            // chain buffers are reused by the next level
+            __syncthreads();
         }
-        __syncthreads();
         if (tid == 0) {
             // the words u_{1:n}, n = p .. 1, shared by every sub-tree with this prefix; kept per workgroup
             for (int n = p; n >= 1; --n) {
@@ -100,8 +126,8 @@ __global__ __launch_bounds__(256) void sig_hbm_streaming_kernel(StreamingParams 
                 for (int m = 1; m <= n - 1; ++m) g = fmaf(g, dl[ulet[m]] * (1.0f / (float)(n - m + 1)), pre[m]);
                 pre[n] = fmaf(g, dl[ulet[n]], pre[n]);
                 // exactly one sub-tree (remaining letters all 0) writes the shared word to the row
-                uint32_t span = P.pw[p - n];
-                if (tile % span == 0) dst[P.off[n] + tile / span] = pre[n];
+                uint32_t span = pw[p - n];
+                if (tile % span == 0) dst[off[n] + tile / span] = pre[n];
             }
         }
         __syncthreads();
@@ -183,7 +209,12 @@ hipError_t launch_hbm_streaming(const float *path, float *out, int64_t B, int64_
     P.off[0] = 0;
     int64_t grid = B * rs.pow[p];
     if (grid <= 0 || grid > INT32_MAX) return hipErrorInvalidValue;
-    size_t lds = (size_t)tile * rs.d * sizeof(float);
+    // the chain buffers hold up to d^{depth-1-p} floats each
+    const int64_t gcap = rs.depth - 1 - p >= 0 ? rs.pow[rs.depth - 1 - p] : 1;
+    P.gcap = (int)gcap;
+    const int64_t lds_floats = (int64_t)tile * rs.d + 2 * gcap;
+    if (lds_floats * (int64_t)sizeof(float) > kMaxLdsBytes) return hipErrorInvalidValue;
+    size_t lds = (size_t)lds_floats * sizeof(float);
     hipLaunchKernelGGL(sig_hbm_streaming_kernel, dim3((unsigned)grid), dim3(threads), lds, st, P);
     return hipGetLastError();
 }
