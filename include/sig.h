@@ -71,6 +71,8 @@ enum sig_variant {
  *   reserved[0]   with chunks == 1: 0 = workgroup-wide tiles of increments (the default, faster in every
  *                 measurement so far); 1 = every wavefront stages its own increments and workgroups walk
  *                 several batches of paths without any barrier (kept for comparison)
+ *   reserved[2]   loader of plans with several tiles per chunk: 0 = chosen by the library, 1 = the next tile's
+ *                 loads stay in flight in registers while the current tile is consumed, 2 = load, barrier, consume
  *   reserved[1]   skewed start of the workgroups of a multi-round final-mode launch: 0 = chosen by the
  *                 library, > 0 = delay per residency slot in 100 MHz ticks, < 0 = off
  */

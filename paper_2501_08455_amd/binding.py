@@ -116,10 +116,11 @@ def sig_plan_validate(B, L, d, depth, stream_flag, plan):
 
 
 def make_plan(variant, prefix_depth=0, chunks=1, segments=1, threads=256, tile_steps=0, independent_waves=0,
-              stagger_ticks=0):
+              stagger_ticks=0, tile_loader=0):
     pl = sig_plan_t()
     pl.reserved[0] = int(independent_waves)
     pl.reserved[1] = int(stagger_ticks)
+    pl.reserved[2] = int(tile_loader)
     pl.variant, pl.prefix_depth, pl.chunks = int(variant), int(prefix_depth), int(chunks)
     pl.segments, pl.threads, pl.tile_steps = int(segments), int(threads), int(tile_steps)
     return pl

@@ -109,22 +109,52 @@ bool finish_on_chip(const OnChipKernelInfo *ki, int cus, int64_t B, int64_t L, i
     int64_t tt = T;
     const bool forced = pl.tile_steps > 0 && pl.tile_steps < T;
     if (forced) tt = pl.tile_steps;
+    args->pipe = 0;
     if (pl.chunks == 1 && !args->cooperative) {
         if (!forced && tt > kFoldTileSteps) tt = kFoldTileSteps;
     } else if (forced || ngc * T * ki->d * (int64_t)sizeof(float) > kTileLdsBytes) {
-        int64_t by_lds = kTileLdsBytes / (2 * ngc * ki->d * (int64_t)sizeof(float));
-        int64_t row_pow2 = 1;
-        while (row_pow2 * 2 * ngc <= (int64_t)kLoaderStage * pl.threads) row_pow2 *= 2;
-        int64_t by_regs = row_pow2 / ki->d;
-        if (tt > by_lds) tt = by_lds;
-        if (tt > by_regs) tt = by_regs;
+        // Several tiles per chunk.  With four or more wavefronts per SIMD resident the other workgroups hide a
+        // tile's load latency and the plain loader (load, barrier, consume) keeps the register count low; with
+        // fewer, the next tile is kept in flight in registers while the current one is consumed.
+        // plan.reserved[2]: 1 forces the register-staged loader, 2 the plain one.
+        bool pipe;
+        if (pl.reserved[2] == 1 || pl.reserved[2] == 2) {
+            pipe = pl.reserved[2] == 1;
+        } else {
+            const int waves_per_wg = pl.threads / kWave;
+            int by_vgpr = 512 / (ki->state_floats + 45);
+            if (by_vgpr > 8) by_vgpr = 8;
+            if (by_vgpr < 1) by_vgpr = 1;
+            const int64_t items = ceil_div(B * pl.segments, G);
+            int64_t resident = (int64_t)by_vgpr * 4 / waves_per_wg * cus;
+            if (resident > items) resident = items;
+            pipe = resident * waves_per_wg < (int64_t)4 * 4 * cus;
+        }
+        if (pipe) {
+            int64_t by_lds = kTileLdsBytes / (2 * ngc * ki->d * (int64_t)sizeof(float));
+            int64_t row_pow2 = 1;
+            while (row_pow2 * 2 * ngc <= (int64_t)kLoaderStage * pl.threads) row_pow2 *= 2;
+            int64_t by_regs = row_pow2 / ki->d;
+            if (tt > by_lds) tt = by_lds;
+            if (tt > by_regs) tt = by_regs;
+        } else {
+            int64_t by_lds = kTileLdsBytes / (ngc * ki->d * (int64_t)sizeof(float));
+            if (tt > by_lds) tt = by_lds;
+        }
         if (tt < 1) return false;
+        args->pipe = pipe && tt < T;
     }
     args->tile_steps = (int)tt;
     int shift = 0;
     while (((int64_t)1 << shift) < tt * ki->d) ++shift;
     args->row_shift = shift;
-    if ((pl.chunks > 1 || args->cooperative) && tt < T && (ngc << shift) > (int64_t)kLoaderStage * pl.threads) return false;
+    if (args->pipe && (ngc << shift) > (int64_t)kLoaderStage * pl.threads) return false;
+    // straight-copy tile: whole paths (one chunk, one segment), one tile, the workgroup-wide kernel, and a path
+    // array long enough that the last full vector pair lies inside it
+    // (not with few lanes per path: then a wavefront reads many rows at once, and rows of L * d floats, unlike the
+    // (L - 1) * d of the generic tile, tend to start in the same LDS bank)
+    args->flat_tile = pl.chunks == 1 && pl.segments == 1 && args->cooperative && tt >= T && L * ki->d >= ki->d + 8 &&
+                      (int64_t)G * L * ki->d < (1 << 20) && Q >= 8;
     int64_t lds = ki->lds_bytes(*args);
     while (pl.chunks == 1 && !args->cooperative && !forced && lds > kMaxLdsBytes / 2 && args->tile_steps > 1) {
         // keep at least two workgroups per 64 KB: shorter tiles
@@ -156,7 +186,8 @@ bool finish_on_chip(const OnChipKernelInfo *ki, int cus, int64_t B, int64_t L, i
         args->stagger_ticks = 0;
         if (pl.reserved[1] > 0) {
             args->stagger_ticks = pl.reserved[1];
-        } else if (pl.reserved[1] == 0 && !stream_flag && pl.chunks == 1 && args->cooperative && Q <= pl.threads) {
+        } else if (pl.reserved[1] == 0 && !stream_flag && pl.chunks == 1 && args->cooperative && Q <= pl.threads &&
+                   !args->flat_tile) {
             const int64_t items = ceil_div(B * pl.segments, G);
             // worth it only where the HBM time is a large part of the arithmetic time (measured: it gains 12 % at
             // 5 KB and 0.19 MFLOP per path, and loses a little from twice that path length on)

@@ -58,6 +58,11 @@ struct OnChipArgs {
     int32_t stagger_ticks;  // start delay (100 MHz ticks) per residency slot of the first wave of workgroups; 0: none
     int32_t num_cus;        // compute units of the device
     int32_t cooperative;  // chunks == 1 only: 1 = workgroup-wide tiles with barriers instead of independent wavefronts
+    int32_t pipe;         // several tiles per chunk: 1 = the next tile's loads stay in flight in registers while the current
+                          // one is consumed (hides the load latency inside one workgroup), 0 = load, barrier, consume
+                          // (fewer registers; the other resident workgroups hide the latency)
+    int32_t flat_tile;    // 1: the workgroup's paths are whole and adjacent in memory and fit one tile: the tile is a
+                          // straight copy of that range (rows of L * d floats), differenced on the way
     int32_t stream_flag;
 };
 

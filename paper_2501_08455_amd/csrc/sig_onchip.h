@@ -31,13 +31,33 @@
 #define SIG_STEP_UNROLL 1
 #endif
 
+// Wavefront priority of the phases that wait on HBM (staging increments, writing results).  The SIMD's
+// arbiter favours older wavefronts, so a freshly started workgroup would otherwise issue its loads only in
+// the gaps its neighbours' arithmetic leaves; with the priority raised the loads go out at once and the
+// arithmetic of the other wavefronts fills the time they are in flight.
+#ifndef SIG_FLAT_BATCH
+#define SIG_FLAT_BATCH 3  // vectors per thread whose loads are in flight together in the straight-copy loader
+#endif
+#ifndef SIG_MEMORY_PHASE_PRIORITY
+#define SIG_MEMORY_PHASE_PRIORITY 3
+#endif
+#define SIG_PRIO_MEMORY() __builtin_amdgcn_s_setprio(SIG_MEMORY_PHASE_PRIORITY)
+#define SIG_PRIO_COMPUTE() __builtin_amdgcn_s_setprio(0)
+
 namespace sig {
 namespace onchip {
 
 // Phase time stamps of workgroup 0, only in diagnostic builds (-DSIG_DIAG_TIMING); read back with sig_diag_read.
 #ifdef SIG_DIAG_TIMING
 __device__ unsigned long long sig_diag_ticks[16];
+#ifdef SIG_DIAG_TRACE
+// every workgroup's stamps (8 per workgroup; slot 7 holds the hardware id register)
+__device__ unsigned long long sig_diag_trace[16384 * 8];
+#define SIG_TICK(i) do { if (threadIdx.x == 0 && blockIdx.x < 16384) { sig_diag_trace[blockIdx.x * 8 + (i)] = wall_clock64(); \
+    if ((i) == 0) sig_diag_trace[blockIdx.x * 8 + 7] = __builtin_amdgcn_s_getreg(63492) | ((unsigned long long)__builtin_amdgcn_s_getreg(6164) << 32); } } while (0)
+#else
 #define SIG_TICK(i) do { if (threadIdx.x == 0 && blockIdx.x == 0) sig_diag_ticks[i] = wall_clock64(); } while (0)
+#endif
 #else
 #define SIG_TICK(i) do { } while (0)
 #endif
@@ -399,7 +419,7 @@ constexpr int max_threads() { return (CHUNKED && Shape<d, N, P>::SZ <= 64) ? 512
 
 // Workgroups of the CHUNKED kernels may have up to 512 threads (when the lane state is small enough): only chunks * Q lanes fold, but every
 // thread takes part in the LDS products, which are latency bound with one wavefront per SIMD.
-template <int d, int N, int P, bool CHUNKED, bool STREAM, bool PIPE>
+template <int d, int N, int P, bool CHUNKED, bool STREAM, bool PIPE, bool FLAT = false>
 __global__ __launch_bounds__((max_threads<d, N, P, CHUNKED>())) void sig_on_chip_kernel(OnChipArgs A)
 {
     using Sh = Shape<d, N, P>;
@@ -407,6 +427,7 @@ __global__ __launch_bounds__((max_threads<d, N, P, CHUNKED>())) void sig_on_chip
     constexpr int D = Sh::D;
 
     SIG_TICK(0);
+    SIG_PRIO_MEMORY();
     // Skewed start.  All workgroups of a launch would otherwise load, fold and store in lock-step, and
     // the HBM phases would not overlap the arithmetic.  The workgroups that are resident first are delayed by
     // their residency slot (about blockIdx / number of CUs) times a fraction of one workgroup's lifetime;
@@ -576,9 +597,9 @@ __global__ __launch_bounds__((max_threads<d, N, P, CHUNKED>())) void sig_on_chip
                 }
             }
         }
-        auto consume = [&](const float *tile, int t0) {
+        auto consume = [&](const float *tile, int t0, int row_stride) {
             const int steps = (T - t0 < TT) ? T - t0 : TT;
-            const float *row = tile + mygc * row_floats;
+            const float *row = tile + mygc * row_stride;
             Inc<d, P> inc;
             for (int t = 0; t < steps; ++t, row += d) {
                 load_inc<d, P>(inc, row, letter);
@@ -613,56 +634,118 @@ __global__ __launch_bounds__((max_threads<d, N, P, CHUNKED>())) void sig_on_chip
             }
         };
         if constexpr (!PIPE) {
+            if constexpr (FLAT) {
+                // One tile, whole paths, one segment: the groups of this workgroup are one contiguous range of
+                // the path array.  Thread i takes vectors i, i + nthr, ... of that range (from the 16-byte
+                // boundary below its start), loads each and the one d floats further on, and writes their
+                // difference to the same place in the tile, so row g of the tile starts at g * L * d floats
+                // and its last d entries (differences across two paths) are never consumed.  No index
+                // arithmetic per vector and all loads of a batch in flight together.  The last vectors of
+                // the array are taken from the last position that can be read in full.
+                constexpr int LB = SIG_FLAT_BATCH;
+                const int64_t NF = A.B * A.L * d;
+                const int row_stride = (int)A.L * d;
+                const int64_t F0 = (int64_t)group0 * row_stride;
+                const int mis = (int)(F0 & 3);
+                const int64_t F0a = F0 - mis;
+                int64_t nfl = (int64_t)G * row_stride + mis;
+                if (nfl > NF - F0a) nfl = NF - F0a;
+                const int nvec = (int)((nfl + 3) >> 2);
+                const int qmax = (int)(NF - d - 4 - F0a);  // >= 0: checked on the host
+                const float *src = A.path + F0a;
+                __syncthreads();
+                SIG_PRIO_MEMORY();
+                for (int base = 0; base < nvec; base += LB * nthr) {
+                    vec4f_u lo[LB], hi[LB];
+                    int off[LB];
+#pragma unroll
+                    for (int e = 0; e < LB; ++e) {
+                        int i = base + e * nthr + tid;
+                        if (i > nvec - 1) i = nvec - 1;
+                        int q = 4 * i;
+                        if (q > qmax) q = qmax;
+                        off[e] = q;
+                        lo[e] = *reinterpret_cast<const vec4f_u *>(src + q);
+                        hi[e] = *reinterpret_cast<const vec4f_u *>(src + q + d);
+                    }
+#pragma unroll
+                    for (int e = 0; e < LB; ++e) *reinterpret_cast<vec4f_u *>(tile0 + off[e]) = hi[e] - lo[e];
+                }
+                __syncthreads();
+                SIG_PRIO_COMPUTE();
+                SIG_TICK(6);
+                consume(tile0 + mis, 0, row_stride);
+            } else {
             for (int t0 = 0; t0 < T; t0 += TT) {
                 __syncthreads();
-                // four consecutive floats per thread and element (dword-aligned 16-byte loads), two elements
-                // per trip so that their loads are in flight together (more would raise the kernel's register count)
+                SIG_PRIO_MEMORY();
+                // One element = four consecutive increments of one chunk's row (dword-aligned 16-byte loads of
+                // the points and of the points d floats on).  The loads of a batch of elements are issued
+                // together and nothing waits inside a branch.  The last element of a row is taken from the
+                // last position that lies in the row in full (valid - 4), so no load is split; what a tile
+                // row holds beyond the chunk's end is zero (an increment of zero leaves the state unchanged).
+                // (the lane state is live here: with a small state one more element in flight costs a whole
+                // wavefront of occupancy, with a large one the occupancy is low anyway)
+                constexpr int LB = Sh::SZ <= 64 ? 1 : 3;
                 const int vshift = rshift > 2 ? rshift - 2 : 0;  // vectors per chunk row, padded to a power of two
                 const int vmask = (1 << vshift) - 1;
                 const int vflat = NGC << vshift;
-                for (int base = 0; base < vflat; base += 2 * nthr) {
-                    vec4f_u dv[2];
+                for (int base = 0; base < vflat; base += LB * nthr) {
+                    vec4f_u lo[LB], hi[LB];
+                    int qv[LB];  // position of the loaded vector in its row, or -1 if none was loaded
 #pragma unroll
-                    for (int e = 0; e < 2; ++e) {
+                    for (int e = 0; e < LB; ++e) {
                         const int idx = base + e * nthr + tid;
                         const int gc = idx >> vshift;
                         const int r = (idx & vmask) * 4;
-                        dv[e] = vec4f_u{0.0f, 0.0f, 0.0f, 0.0f};
+                        qv[e] = -1;
+                        lo[e] = vec4f_u{0.0f, 0.0f, 0.0f, 0.0f};
+                        hi[e] = lo[e];
                         if (idx < vflat && r < row_floats) {
                             const ChunkDesc dsc = desc[gc];
-                            const int valid = (dsc.steps - t0) * d;  // floats of this chunk still inside the path
-                            const float *x = A.path + dsc.base + (int64_t)t0 * d + r;
-                            if (r + 3 < valid) {
-                                const vec4f_u lo = *reinterpret_cast<const vec4f_u *>(x);
-                                const vec4f_u hi = *reinterpret_cast<const vec4f_u *>(x + d);
-                                dv[e] = hi - lo;
-                            } else {
-#pragma unroll
-                                for (int j = 0; j < 4; ++j)
-                                    if (r + j < valid) dv[e][j] = x[j + d] - x[j];
+                            int valid = (dsc.steps - t0) * d;  // floats of this chunk still inside the path
+                            if (valid > row_floats) valid = row_floats;
+                            if (valid >= 4 && r < valid) {
+                                const int q = r < valid - 4 ? r : valid - 4;
+                                const float *x = A.path + dsc.base + (int64_t)t0 * d + q;
+                                lo[e] = *reinterpret_cast<const vec4f_u *>(x);
+                                hi[e] = *reinterpret_cast<const vec4f_u *>(x + d);
+                                qv[e] = q;
                             }
                         }
                     }
 #pragma unroll
-                    for (int e = 0; e < 2; ++e) {
+                    for (int e = 0; e < LB; ++e) {
                         const int idx = base + e * nthr + tid;
                         const int gc = idx >> vshift;
                         const int r = (idx & vmask) * 4;
                         if (idx < vflat && r < row_floats) {
-                            float *trow = tile0 + gc * row_floats + r;
-                            if (r + 3 < row_floats) {
-                                *reinterpret_cast<vec4f_u *>(trow) = dv[e];
-                            } else {
+                            float *trow = tile0 + gc * row_floats;
+                            if (qv[e] >= 0) *reinterpret_cast<vec4f_u *>(trow + qv[e]) = hi[e] - lo[e];
+                            const ChunkDesc dsc = desc[gc];
+                            int valid = (dsc.steps - t0) * d;
+                            if (valid > row_floats) valid = row_floats;
+                            if (valid < 0) valid = 0;
+                            if (r + 4 > valid) {
+                                // the end of the row: zeros beyond the chunk, and rows shorter than one vector float by float
+                                const float *x = A.path + dsc.base + (int64_t)t0 * d;
 #pragma unroll
-                                for (int j = 0; j < 4; ++j)
-                                    if (r + j < row_floats) trow[j] = dv[e][j];
+                                for (int j = 0; j < 4; ++j) {
+                                    const int pos = r + j;
+                                    if (pos < row_floats) {
+                                        if (pos >= valid) trow[pos] = 0.0f;
+                                        else if (valid < 4) trow[pos] = x[pos + d] - x[pos];
+                                    }
+                                }
                             }
                         }
                     }
                 }
                 __syncthreads();
+                SIG_PRIO_COMPUTE();
                 if (t0 == 0) SIG_TICK(6);
-                consume(tile0, t0);
+                consume(tile0, t0, row_floats);
+            }
             }
         } else {
             float stage[kStage];  // flat <= kStage * nthr (checked on the host)
@@ -672,6 +755,7 @@ __global__ __launch_bounds__((max_threads<d, N, P, CHUNKED>())) void sig_on_chip
 #pragma unroll
             for (int e = 0; e < kStage; ++e) put_one(tile0, tid + e * nthr, stage[e]);
             __syncthreads();
+            SIG_PRIO_COMPUTE();
             int buf = 0;
             for (int t0 = 0; t0 < T; t0 += TT, buf ^= 1) {
                 const bool more = t0 + TT < T;
@@ -679,7 +763,7 @@ __global__ __launch_bounds__((max_threads<d, N, P, CHUNKED>())) void sig_on_chip
 #pragma unroll
                     for (int e = 0; e < kStage; ++e) stage[e] = fetch_one(tid + e * nthr, t0 + TT);
                 }
-                consume(tile0 + buf * tile_floats, t0);
+                consume(tile0 + buf * tile_floats, t0, row_floats);
                 if (more) {
 #pragma unroll
                     for (int e = 0; e < kStage; ++e) put_one(tile0 + (buf ^ 1) * tile_floats, tid + e * nthr, stage[e]);
@@ -696,6 +780,7 @@ __global__ __launch_bounds__((max_threads<d, N, P, CHUNKED>())) void sig_on_chip
     if constexpr (!CHUNKED) {
         fold_chunk(std::integral_constant<bool, STREAM>{});
         SIG_TICK(2);
+        SIG_PRIO_MEMORY();
         if constexpr (!STREAM) {
             if (active) {
                 float *dst = (W == 1) ? A.out + b * D : A.partial + (int64_t)mygroup * D;
@@ -1037,8 +1122,9 @@ int64_t on_chip_lds_bytes(const OnChipArgs &A)
     using Sh = Shape<d, N, P>;
     if (A.chunks == 1 && !A.cooperative) return fold_lds_bytes<d, N, P>(A);
     const int64_t NGC = (int64_t)A.groups * A.chunks;
-    const bool pipe = A.tile_steps < A.chunk_steps;
+    const bool pipe = A.pipe != 0;
     int64_t floats = desc_floats((int)NGC) + (pipe ? 2 : 1) * (int64_t)round4((int)(NGC * A.tile_steps * d));
+    if (A.flat_tile) floats = desc_floats((int)NGC) + round4((int)(A.groups * A.L * d) + 3);
     if (A.chunks > 1) {
         floats += NGC * Sh::D;
         // second buffer: the scan's prefixes (stream) or the ping-pong half of the LDS tree (final, large state)
@@ -1053,10 +1139,17 @@ int64_t on_chip_lds_bytes(const OnChipArgs &A)
 template <int d, int N, int P, bool CHUNKED, bool STREAM>
 void on_chip_launch_pipe(const OnChipArgs &A, dim3 g, dim3 blk, size_t lds, hipStream_t st)
 {
-    if (A.tile_steps < A.chunk_steps)
+    if (A.pipe) {
         hipLaunchKernelGGL((sig_on_chip_kernel<d, N, P, CHUNKED, STREAM, true>), g, blk, lds, st, A);
-    else
-        hipLaunchKernelGGL((sig_on_chip_kernel<d, N, P, CHUNKED, STREAM, false>), g, blk, lds, st, A);
+        return;
+    }
+    if constexpr (!CHUNKED) {
+        if (A.flat_tile) {
+            hipLaunchKernelGGL((sig_on_chip_kernel<d, N, P, false, STREAM, false, true>), g, blk, lds, st, A);
+            return;
+        }
+    }
+    hipLaunchKernelGGL((sig_on_chip_kernel<d, N, P, CHUNKED, STREAM, false>), g, blk, lds, st, A);
 }
 
 template <int d, int N, int P>
@@ -1083,7 +1176,7 @@ hipError_t on_chip_launch(const OnChipArgs &A, hipStream_t st)
     // loader geometry the kernel relies on
     const int64_t NGC = (int64_t)A.groups * A.chunks;
     if (A.row_shift < 0 || A.row_shift > 20 || (1 << A.row_shift) < A.tile_steps * d) return hipErrorInvalidValue;
-    if ((A.chunks > 1 || A.cooperative) && A.tile_steps < A.chunk_steps && (NGC << A.row_shift) > (int64_t)kStage * A.threads)
+    if ((A.chunks > 1 || A.cooperative) && A.pipe && (NGC << A.row_shift) > (int64_t)kStage * A.threads)
         return hipErrorInvalidValue;
     const int64_t lds = on_chip_lds_bytes<d, N, P>(A);
     if (lds > kMaxLdsBytes) return hipErrorInvalidValue;

@@ -130,6 +130,19 @@ def test_on_chip_family(gpu, oracle, case):
     check(gpu, oracle, x, depth, stream, plan, label="on-chip")
 
 
+@pytest.mark.parametrize("loader", [1, 2], ids=["staged", "plain"])
+@pytest.mark.parametrize("case", [c for c in ON_CHIP_CASES if c[7] > 0], ids=lambda c: "-".join(str(v) for v in c))
+def test_on_chip_tile_loaders(gpu, oracle, case, loader):
+    """Plans with several tiles per chunk, with either loader (plan.reserved[2]) forced."""
+    d, depth, p, B, L, chunks, segments, tile, stream, threads = split_case(case)
+    x = workloads.brownian_paths(B, L, d, seed=9000 + 11 * B + L + loader)
+    plan = gpu.make_plan(gpu.SIG_VARIANT_ON_CHIP, prefix_depth=p, chunks=chunks, segments=segments,
+                         tile_steps=tile, threads=threads, tile_loader=loader)
+    if gpu.sig_plan_validate(B, L, d, depth, int(stream), plan) != gpu.SIG_OK:
+        pytest.skip("plan not valid with this loader")
+    check(gpu, oracle, x, depth, stream, plan, label="tile loader %d" % loader)
+
+
 @pytest.mark.parametrize("case", [c for c in ON_CHIP_CASES if c[5] == 1], ids=lambda c: "-".join(str(v) for v in c))
 def test_on_chip_independent_wavefronts(gpu, oracle, case):
     """The barrier-free variant of the single-chunk kernels (plan.reserved[0] = 1)."""
