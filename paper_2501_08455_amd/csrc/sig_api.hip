@@ -85,10 +85,10 @@ bool finish_on_chip(const OnChipKernelInfo *ki, int cus, int64_t B, int64_t L, i
     // groups per workgroup: as many as the threads hold, fewer if their chunk signatures overflow LDS
     int G = Q > pl.threads ? 1 : (int)(slots / pl.chunks);
     if (pl.chunks > 1) {
-        // chunk signatures in LDS: one buffer (final mode, lane state small enough for the register tree),
+        // chunk signatures in LDS: half a buffer (final mode, lane state small enough for the register tree),
         // one and a half (final mode, LDS tree) or two (stream mode: the scan's prefixes)
         const int64_t rows = stream_flag ? 2 * pl.chunks
-                             : ki->state_floats <= 64 ? pl.chunks : pl.chunks + (pl.chunks + 1) / 2;
+                             : ki->state_floats <= 64 ? (pl.chunks + 1) / 2 : pl.chunks + (pl.chunks + 1) / 2;
         const int64_t per_group = rows * rs.D * (int64_t)sizeof(float);
         int64_t fit = (kMaxLdsBytes - 4096) / per_group;
         if (fit < 1) return false;
@@ -128,7 +128,8 @@ bool finish_on_chip(const OnChipKernelInfo *ki, int cus, int64_t B, int64_t L, i
             const int64_t items = ceil_div(B * pl.segments, G);
             int64_t resident = (int64_t)by_vgpr * 4 / waves_per_wg * cus;
             if (resident > items) resident = items;
-            pipe = resident * waves_per_wg < (int64_t)4 * 4 * cus;
+            // stream mode is bound by its stores; the plain loader with long tiles measured a few percent faster
+            pipe = !stream_flag && resident * waves_per_wg < (int64_t)4 * 4 * cus;
         }
         if (pipe) {
             int64_t by_lds = kTileLdsBytes / (2 * ngc * ki->d * (int64_t)sizeof(float));

@@ -50,7 +50,12 @@ namespace onchip {
 // Phase time stamps of workgroup 0, only in diagnostic builds (-DSIG_DIAG_TIMING); read back with sig_diag_read.
 #ifdef SIG_DIAG_TIMING
 __device__ unsigned long long sig_diag_ticks[16];
-#ifdef SIG_DIAG_TRACE
+#ifdef SIG_DIAG_STEPS
+// stamps inside the step loop of workgroup 0, thread 0: 8 per step for the first 256 steps
+__device__ unsigned long long sig_diag_trace[16384 * 8];
+#define SIG_TICK(i) do { } while (0)
+#define SIG_STEP_TICK(step, i) do { if (threadIdx.x == 0 && blockIdx.x == 0 && (step) < 256) sig_diag_trace[(step) * 8 + (i)] = wall_clock64(); } while (0)
+#elif defined(SIG_DIAG_TRACE)
 // every workgroup's stamps (8 per workgroup; slot 7 holds the hardware id register)
 __device__ unsigned long long sig_diag_trace[16384 * 8];
 #define SIG_TICK(i) do { if (threadIdx.x == 0 && blockIdx.x < 16384) { sig_diag_trace[blockIdx.x * 8 + (i)] = wall_clock64(); \
@@ -60,6 +65,9 @@ __device__ unsigned long long sig_diag_trace[16384 * 8];
 #endif
 #else
 #define SIG_TICK(i) do { } while (0)
+#endif
+#ifndef SIG_STEP_TICK
+#define SIG_STEP_TICK(step, i) do { } while (0)
 #endif
 
 typedef float vec4f __attribute__((ext_vector_type(4)));  // plain 16-byte vector for LDS -> HBM row copies
@@ -602,20 +610,30 @@ __global__ __launch_bounds__((max_threads<d, N, P, CHUNKED>())) void sig_on_chip
             const float *row = tile + mygc * row_stride;
             Inc<d, P> inc;
             for (int t = 0; t < steps; ++t, row += d) {
+                SIG_STEP_TICK(t0 + t, 0);
                 load_inc<d, P>(inc, row, letter);
+#ifndef SIG_DIAG_NO_FOLD
                 fused_step<d, N, P>(ln, inc);
+#endif
                 if constexpr (emit && WAVE_SLOTS) {
                     // gather this wavefront's rows in LDS, then write them with consecutive lanes on
                     // consecutive addresses (LDS operations of one wavefront execute in order)
+                    SIG_STEP_TICK(t0 + t, 1);
                     if (active) store_state<d, N, P>(sigA + mygc * D, u, ln);
+                    SIG_STEP_TICK(t0 + t, 2);
                     if (FAST_EMIT && use_vec) {
                         if constexpr (FAST_EMIT) {
                             V val[NIT];
 #pragma unroll
                             for (int j = 0; j < NIT; ++j) val[j] = reinterpret_cast<const V *>(sigA)[eoff[j]];
+                            SIG_STEP_TICK(t0 + t, 3);
 #pragma unroll
                             for (int j = 0; j < NIT; ++j)
+#ifdef SIG_DIAG_NO_STORE
+                                if (t0 + t < elim[j] && val[j].x == 12345.678f) eptr[j][(int64_t)(t0 + t) * ROWV] = val[j];
+#else
                                 if (t0 + t < elim[j]) eptr[j][(int64_t)(t0 + t) * ROWV] = val[j];
+#endif
                         }
                     } else {
                         const int wave = tid / kWave, lw = tid - wave * kWave;
@@ -791,26 +809,32 @@ __global__ __launch_bounds__((max_threads<d, N, P, CHUNKED>())) void sig_on_chip
         using RP = RowProduct<d, N>;
         fold_chunk(std::false_type{});
         SIG_TICK(2);
-        if (active) store_state<d, N, P>(sigA + mygc * D, u, ln);
-        float *sigB = sigA + NGC * D;  // second buffer: [G][(C+1)/2][D] (final) or [NGC][D] (stream)
-        __syncthreads();
         if constexpr (!STREAM && Sh::SZ <= 64) {
             // pairwise tree with the left factor in registers: in the round with stride st chunk c (a multiple
-            // of 2 st) absorbs chunk c + st, which has put its row into LDS; the result stays in c's lanes
+            // of 2 st) absorbs chunk c + st, which has put its row into LDS; the result stays in c's lanes.
+            // Only every other surviving chunk writes a row per round, so a group needs (C + 1) / 2 rows,
+            // and they take the place of the increment tiles, which are dead by now.
             SIG_TICK(3);
+            __syncthreads();  // every lane is done with the tiles
+            float *rows = tile0;
+            const int HC = (C + 1) / 2;
             for (int st = 1; st < C; st <<= 1) {
-                if (st > 1) {
-                    if (active && (c & (2 * st - 1)) == st) store_state<d, N, P>(sigA + mygc * D, u, ln);
-                    __syncthreads();
-                }
-                if (active && (c & (2 * st - 1)) == 0 && c + st < C) reg_product<d, N, P>(ln, sigA + (mygc + st) * D, u);
+                float *slot = rows + (gi * HC + c / (2 * st)) * D;  // of the pair (c, c + st)
+                if (active && (c & (2 * st - 1)) == st) store_state<d, N, P>(slot, u, ln);
+                __syncthreads();
+                if (active && (c & (2 * st - 1)) == 0 && c + st < C) reg_product<d, N, P>(ln, slot, u);
+                if (2 * st < C) __syncthreads();  // the slots are rewritten in the next round
             }
             SIG_TICK(4);
             if (active && c == 0) {
                 float *o = (W == 1) ? A.out + (int64_t)mygroup * D : A.partial + (int64_t)mygroup * D;
                 store_state<d, N, P>(o, u, ln);
             }
-        } else if constexpr (!STREAM) {
+        } else {
+        if (active) store_state<d, N, P>(sigA + mygc * D, u, ln);
+        float *sigB = sigA + NGC * D;  // second buffer: [G][(C+1)/2][D] (final) or [NGC][D] (stream)
+        __syncthreads();
+        if constexpr (!STREAM) {
             float *src = sigA, *dst = sigB;
             int src_stride = C, dst_stride = (C + 1) / 2;
             SIG_TICK(3);
@@ -860,6 +884,7 @@ __global__ __launch_bounds__((max_threads<d, N, P, CHUNKED>())) void sig_on_chip
             if (c == 0) identity_state<d, N, P>(ln);
             else load_state<d, N, P>(sigB + (mygc - 1) * D, u, ln);
             fold_chunk(std::true_type{});
+        }
         }
     }
     SIG_TICK(5);
@@ -1073,7 +1098,11 @@ __global__ __launch_bounds__(256) void sig_fold_kernel(OnChipArgs A)
                             });
                             static_for<0, NIT>([&](auto jc) __attribute__((always_inline)) {
                                 constexpr int j = decltype(jc)::value;
+#ifdef SIG_DIAG_NO_STORE
+                                if (t0 + t < elim[j] && val[j].x == 12345.678f) eptr[j][(int64_t)(t0 + t) * ROWV] = val[j];
+#else
                                 if (t0 + t < elim[j]) eptr[j][(int64_t)(t0 + t) * ROWV] = val[j];
+#endif
                             });
                         }
                     } else {
@@ -1125,11 +1154,16 @@ int64_t on_chip_lds_bytes(const OnChipArgs &A)
     const bool pipe = A.pipe != 0;
     int64_t floats = desc_floats((int)NGC) + (pipe ? 2 : 1) * (int64_t)round4((int)(NGC * A.tile_steps * d));
     if (A.flat_tile) floats = desc_floats((int)NGC) + round4((int)(A.groups * A.L * d) + 3);
-    if (A.chunks > 1) {
+    if (A.chunks > 1 && !A.stream_flag && Sh::SZ <= 64) {
+        // register tree: (chunks + 1) / 2 rows per group, in the place of the tiles
+        const int64_t rows = (int64_t)A.groups * ((A.chunks + 1) / 2) * Sh::D;
+        const int64_t tiles = floats - desc_floats((int)NGC);
+        if (rows > tiles) floats += rows - tiles;
+    } else if (A.chunks > 1) {
         floats += NGC * Sh::D;
         // second buffer: the scan's prefixes (stream) or the ping-pong half of the LDS tree (final, large state)
         if (A.stream_flag) floats += NGC * Sh::D;
-        else if (Sh::SZ > 64) floats += (int64_t)A.groups * ((A.chunks + 1) / 2) * Sh::D;
+        else floats += (int64_t)A.groups * ((A.chunks + 1) / 2) * Sh::D;
     } else if (A.stream_flag && Sh::Q <= kWave) {
         floats += NGC * Sh::D;  // rows staged for emission
     }

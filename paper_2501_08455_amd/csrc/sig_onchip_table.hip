@@ -32,7 +32,7 @@ extern "C" int sig_diag_read(unsigned long long *host16)
 {
     return (int)hipMemcpyFromSymbol(host16, HIP_SYMBOL(sig::onchip::sig_diag_ticks), 16 * sizeof(unsigned long long));
 }
-#ifdef SIG_DIAG_TRACE
+#if defined(SIG_DIAG_TRACE) || defined(SIG_DIAG_STEPS)
 extern "C" int sig_diag_trace_read(unsigned long long *host, int workgroups)
 {
     if (workgroups > 16384) workgroups = 16384;
