@@ -22,15 +22,15 @@ PEAK_HBM_GBS = 8000.0      # MI355X HBM3E, published
 # copy kernel of the same run (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0); see profiles/hbm_traffic.md.
 # Keyed by (configuration, batch).
 MEASURED_TRAFFIC_BYTES = {
-    ("C1", 4): (2 * 14.1 + 0.3) * 1024,
-    ("C2", 128): (2 * 178.7 + 392.0) * 1024,
-    ("C3", 128): (2 * 2578.8 + 1568.0) * 1024,
-    ("C4", 64): (2 * 190.8 + 21722.6) * 1024,
-    ("C5", 16): (2 * 366.5 + 69748.0) * 1024,
-    ("C1", 1 << 20): (2 * 65564.3 + 57344.0) * 1024,
-    ("C2", 65536): (2 * 64522.5 + 199687.7) * 1024,
-    ("C3", 4096): (2 * 81160.2 + 12480.0) * 1024,
-    ("C4", 4096): (2 * 9782.7 + 1389374.0) * 1024,
+    ("C1", 4): (2 * 11.9 + 0.3) * 1024,
+    ("C2", 128): (2 * 171.2 + 392.0) * 1024,
+    ("C3", 128): (2 * (2571.3 + 814.1) + 1568.0 + 392.0) * 1024,
+    ("C4", 64): (2 * 190.3 + 21722.9) * 1024,
+    ("C5", 16): (2 * 361.0 + 69693.7) * 1024,
+    ("C1", 1 << 20): (2 * 65559.8 + 57344.0) * 1024,
+    ("C2", 65536): (2 * 64439.9 + 199681.7) * 1024,
+    ("C3", 4096): (2 * 83023.9 + 12480.0) * 1024,
+    ("C4", 4096): (2 * 8994.7 + 1389440.0) * 1024,
 }
 
 
@@ -161,6 +161,8 @@ def main():
     ap.add_argument("--workload", default="C2", help="configuration to time as the headline (C1..C5)")
     ap.add_argument("--batch", type=int, default=0, help="override the batch size (batch-saturated variants)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    ap.add_argument("--hbm-streaming", type=int, default=-1, metavar="P",
+                    help="time the HBM-streaming kernel family with prefix depth P instead of the planner's choice")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (a box has one MI355X); --gpus %d is not supported"
@@ -178,7 +180,11 @@ def main():
 
     cfg = workloads.CONFIGS[args.workload]
     B = args.batch or cfg.B
-    head = bench_config(binding, workloads, ctx, cfg, B, args.steps, args.warmup)
+    forced = None
+    if args.hbm_streaming >= 0:
+        forced = binding.make_plan(binding.SIG_VARIANT_HBM_STREAMING, prefix_depth=args.hbm_streaming)
+    head = bench_config(binding, workloads, ctx, cfg, B, args.steps, args.warmup, plan=forced,
+                        label=" (HBM-streaming family)" if forced is not None else "")
     line = {
         "metric": "signatures/sec at (B=%d, L=%d, d=%d, N=%d), %s" % (
             B, cfg.L, cfg.d, cfg.depth, "every prefix (stream)" if cfg.stream else "final signature"),
@@ -203,7 +209,6 @@ def main():
             extras.append(bench_config(binding, workloads, ctx, c, B or c.B, steps, warm))
         # the HBM-streaming family (the fallback for shapes without a compiled on-chip kernel) on C5
         c5 = workloads.CONFIGS["C5"]
-        rc, auto = binding.sig_plan(ctx, c5.B, c5.L, c5.d, c5.depth, 0)
         hbm_plan = binding.make_plan(binding.SIG_VARIANT_HBM_STREAMING, prefix_depth=2)
         extras.append(bench_config(binding, workloads, ctx, c5, c5.B, 20, 5, plan=hbm_plan,
                                    label=" (HBM-streaming family)"))
