@@ -2,10 +2,10 @@
 
 Nothing in the product imports this package: it exists so that tests, the smoke
 check and the benchmark's cpu_baseline leg can compare the HIP path against the
-paper's definition (Section 2.1, Eqs. 2-5 and Eq. 10).
+paper's definition (Section 2.1, Eqs. 2-5 and Eq. 10) and its gradient (Section 4.2, Eq. 11).
 """
-from .sig_oracle import (build, signature, tensor_exp, tensor_mul, sig_size,
+from .sig_oracle import (build, signature, signature_backward, tensor_exp, tensor_mul, sig_size,
                          num_threads, level_slices)
 
-__all__ = ["build", "signature", "tensor_exp", "tensor_mul", "sig_size",
+__all__ = ["build", "signature", "signature_backward", "tensor_exp", "tensor_mul", "sig_size",
            "num_threads", "level_slices"]

@@ -12,16 +12,18 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "sig_oracle.c")
+_SRC_GRAD = os.path.join(_HERE, "sig_grad_oracle.c")
 _LIB = os.path.join(_HERE, "libsig_oracle.so")
 _lib = None
 
 
 def build(force=False):
-    """Compile sig_oracle.c with gcc (OpenMP over the batch only)."""
-    if not force and os.path.exists(_LIB) and os.path.getmtime(_LIB) >= os.path.getmtime(_SRC):
+    """Compile sig_oracle.c and sig_grad_oracle.c with gcc (OpenMP over the batch only)."""
+    newest = max(os.path.getmtime(_SRC), os.path.getmtime(_SRC_GRAD))
+    if not force and os.path.exists(_LIB) and os.path.getmtime(_LIB) >= newest:
         return _LIB
     cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
-           "-ffp-contract=off", "-o", _LIB, _SRC]
+           "-ffp-contract=off", "-o", _LIB, _SRC, _SRC_GRAD]
     subprocess.run(cmd, check=True)
     return _LIB
 
@@ -41,6 +43,9 @@ def _load():
         lib.oracle_signature.restype = ctypes.c_int
         lib.oracle_signature.argtypes = [dp, ctypes.c_int64, ctypes.c_int64, ctypes.c_int,
                                          ctypes.c_int, ctypes.c_int, dp]
+        lib.oracle_signature_backward.restype = ctypes.c_int
+        lib.oracle_signature_backward.argtypes = [dp, ctypes.c_int64, ctypes.c_int64, ctypes.c_int,
+                                                  ctypes.c_int, ctypes.c_int, dp, dp]
         lib.oracle_num_threads.restype = ctypes.c_int
         lib.oracle_num_threads.argtypes = []
         _lib = lib
@@ -108,4 +113,28 @@ def signature(path, depth, stream=False):
     rc = _load().oracle_signature(_dptr(x), B, L, d, depth, 1 if stream else 0, _dptr(out))
     if rc != 0:
         raise RuntimeError("oracle_signature failed with code %d" % rc)
+    return out
+
+
+def signature_backward(path, depth, grad_out, stream=False):
+    """Gradient of a scalar loss with respect to `path` ([B, L, d]) given `grad_out`, the gradient with
+    respect to the output of signature(path, depth, stream) (same shape as that output).  float64 [B, L, d].
+    """
+    x = np.ascontiguousarray(path, dtype=np.float64)
+    g = np.ascontiguousarray(grad_out, dtype=np.float64)
+    if x.ndim != 3:
+        raise ValueError("path must be [B, L, d]")
+    B, L, d = x.shape
+    D = sig_size(d, depth)
+    if D < 0 or L < 2:
+        raise ValueError("bad shape")
+    want = (B, L - 1, D) if stream else (B, D)
+    if g.shape != want:
+        raise ValueError("grad_out must have shape %r" % (want,))
+    out = np.empty((B, L, d), dtype=np.float64)
+    if B == 0:
+        return out
+    rc = _load().oracle_signature_backward(_dptr(x), B, L, d, depth, 1 if stream else 0, _dptr(g), _dptr(out))
+    if rc != 0:
+        raise RuntimeError("oracle_signature_backward failed with code %d" % rc)
     return out
