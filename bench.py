@@ -107,6 +107,56 @@ def bench_config(binding, workloads, ctx, cfg, B, steps, warmup, plan=None, labe
     return res
 
 
+def backward_work(cfg, B, workloads):
+    """(flops, bytes) of one sig_backward call.  Per increment and path: undoing the increment is one fused
+    step (2 F flops); the transposed step spends 2 FMAs per top-of-chain coefficient (sum_n d^n of them) and
+    3 FMAs + 1 add per inner chain coefficient (F - sum_n d^n of them).  Bytes: path, final signature and
+    upstream gradient read once, gradient written once."""
+    K = cfg.L - 1
+    d, N = cfg.d, cfg.depth
+    D = workloads.sig_size(d, N)
+    F = workloads.fused_fma_per_step(d, N)
+    flops = (2.0 * F + 4.0 * D + 7.0 * (F - D)) * B * K
+    rows = K if cfg.stream else 1
+    nbytes = 4.0 * (2 * B * cfg.L * d + B * D + B * rows * D)
+    return flops, nbytes
+
+
+def bench_backward(binding, workloads, ctx, cfg, B, steps, warmup):
+    """Time sig_backward on the named configuration (forward result and upstream gradient resident in HBM)."""
+    import torch
+    x = workloads.make_paths(cfg, B=B)
+    xt = torch.from_numpy(x).cuda()
+    D = workloads.sig_size(cfg.d, cfg.depth)
+    rows = cfg.L - 1 if cfg.stream else 1
+    out = torch.empty((B, rows, D) if cfg.stream else (B, D), dtype=torch.float32, device="cuda")
+    assert binding.sig_compute(ctx, xt, cfg.depth, int(cfg.stream), out) == binding.SIG_OK
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(7)
+    gout = torch.randn(out.shape, dtype=torch.float32, device="cuda", generator=gen)
+    gx = torch.empty_like(xt)
+    call = binding.bind_backward(ctx, xt, cfg.depth, int(cfg.stream), out, gout, gx)
+    for _ in range(warmup):
+        rc = call()
+        if rc != binding.SIG_OK:
+            raise binding.SigError(rc, "sig_backward")
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(steps):
+        call()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / steps
+    flops, nbytes = backward_work(cfg, B, workloads)
+    res = {"workload": "%s B=%d L=%d d=%d depth=%d %s, gradient with respect to the path" % (
+               cfg.name, B, cfg.L, cfg.d, cfg.depth, "stream" if cfg.stream else "final"),
+           "ms_per_step": ms, "steps": steps, "paths_per_s": B / (ms * 1e-3),
+           "roofline": roofline(flops, nbytes, ms), "algorithmic": {"flops": flops, "bytes": nbytes}}
+    del xt, out, gout, gx
+    return res
+
+
 def anchors(binding):
     """Achievable rates on this GPU: a plain copy (HBM) and an fp32 FMA loop without packed instructions."""
     import torch
@@ -161,6 +211,7 @@ def main():
     ap.add_argument("--workload", default="C2", help="configuration to time as the headline (C1..C5)")
     ap.add_argument("--batch", type=int, default=0, help="override the batch size (batch-saturated variants)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    ap.add_argument("--backward", action="store_true", help="time sig_backward on the named workload instead")
     ap.add_argument("--hbm-streaming", type=int, default=-1, metavar="P",
                     help="time the HBM-streaming kernel family with prefix depth P instead of the planner's choice")
     args = ap.parse_args()
@@ -183,8 +234,13 @@ def main():
     forced = None
     if args.hbm_streaming >= 0:
         forced = binding.make_plan(binding.SIG_VARIANT_HBM_STREAMING, prefix_depth=args.hbm_streaming)
-    head = bench_config(binding, workloads, ctx, cfg, B, args.steps, args.warmup, plan=forced,
-                        label=" (HBM-streaming family)" if forced is not None else "")
+    if args.backward:
+        head = bench_backward(binding, workloads, ctx, cfg, B, args.steps, args.warmup)
+        head["terms_per_s"] = None
+        head["plan"] = None
+    else:
+        head = bench_config(binding, workloads, ctx, cfg, B, args.steps, args.warmup, plan=forced,
+                            label=" (HBM-streaming family)" if forced is not None else "")
     line = {
         "metric": "signatures/sec at (B=%d, L=%d, d=%d, N=%d), %s" % (
             B, cfg.L, cfg.d, cfg.depth, "every prefix (stream)" if cfg.stream else "final signature"),
@@ -212,6 +268,11 @@ def main():
         hbm_plan = binding.make_plan(binding.SIG_VARIANT_HBM_STREAMING, prefix_depth=2)
         extras.append(bench_config(binding, workloads, ctx, c5, c5.B, 20, 5, plan=hbm_plan,
                                    label=" (HBM-streaming family)"))
+        # the gradient with respect to the path (reverse sweep) on the shapes it is compiled for
+        for name, B, steps, warm in [("C2", None, 1000, 500), ("C4", None, 300, 200), ("C2", 65536, 30, 20),
+                                     ("C4", 4096, 20, 10)]:
+            c = workloads.CONFIGS[name]
+            extras.append(bench_backward(binding, workloads, ctx, c, B or c.B, steps, warm))
         line["all_configs"] = extras
     if args.anchors:
         line["anchors"] = anchors(binding)

@@ -43,7 +43,8 @@ enum sig_status {
     SIG_ERR_TOO_LARGE = 2, /* D or an output size overflows int64, or a grid limit is exceeded */
     SIG_ERR_ALLOC = 3,     /* device scratch could not be allocated */
     SIG_ERR_HIP = 4,       /* a HIP call or kernel launch reported an error */
-    SIG_ERR_NO_DEVICE = 5  /* no usable HIP device when the context was created */
+    SIG_ERR_NO_DEVICE = 5, /* no usable HIP device when the context was created */
+    SIG_ERR_UNSUPPORTED = 6 /* no kernel is compiled for this (d, depth), or the shape exceeds what it handles */
 };
 
 /* Which kernel family runs (see sig_plan). */
@@ -146,6 +147,26 @@ int sig_compute_planned(sig_ctx *ctx, const float *path, int64_t B, int64_t L, i
  */
 int sig_combine(sig_ctx *ctx, const float *a, const float *b, int64_t B, int d, int depth,
                 float *out, void *hip_stream);
+
+/*
+ * Gradient of a scalar loss with respect to the path.  The signature layer is trained between other
+ * layers (paper Section 4.2, Eq. 11), which needs d(loss)/d(path) from d(loss)/d(output); this is the
+ * derivative of Eqs. 2-5 (output layout Eq. 10) written out as a reverse sweep over the increments.
+ *   path         DEVICE, float32 [B][L][d], the same array sig_compute was given
+ *   out          DEVICE, float32, what sig_compute wrote for (path, depth, stream_flag): [B][D] or [B][L-1][D];
+ *                read only (the sweep starts from the final signature and undoes one increment at a time)
+ *   grad_out     DEVICE, float32, d(loss)/d(out), same shape as out, read only
+ *   grad_path    DEVICE, float32 [B][L][d], fully overwritten; must not overlap the inputs
+ * Same conventions and status codes as sig_compute (B == 0 returns SIG_OK and launches nothing);
+ * SIG_ERR_UNSUPPORTED when no gradient kernel is compiled
+ * for (d, depth) (see sig_backward_available) or a path of L points does not fit the kernel's LDS staging.
+ * Deterministic (fixed summation order).  Arithmetic is float32 with FMA.
+ */
+int sig_backward(sig_ctx *ctx, const float *path, int64_t B, int64_t L, int d, int depth, int stream_flag,
+                 const float *out, const float *grad_out, float *grad_path, void *hip_stream);
+
+/* 1 if sig_backward has a kernel for (d, depth), else 0.  Host only. */
+int sig_backward_available(int d, int depth);
 
 /* 1 if an on-chip kernel is compiled for (d, depth, prefix_depth), else 0.  Host only. */
 int sig_on_chip_available(int d, int depth, int prefix_depth);

@@ -17,6 +17,7 @@ SIG_ERR_ALLOC = 3
 SIG_ERR_HIP = 4
 SIG_ERR_NO_DEVICE = 5
 
+SIG_ERR_UNSUPPORTED = 6
 SIG_VARIANT_AUTO = 0
 SIG_VARIANT_HBM_STREAMING = 1
 SIG_VARIANT_ON_CHIP = 2
@@ -69,6 +70,10 @@ def load():
     lib.sig_combine.argtypes = [vp, vp, vp, i64, i32, i32, vp, vp]
     lib.sig_on_chip_available.restype = i32
     lib.sig_on_chip_available.argtypes = [i32, i32, i32]
+    lib.sig_backward.restype = i32
+    lib.sig_backward.argtypes = [vp, vp, i64, i64, i32, i32, i32, vp, vp, vp, vp]
+    lib.sig_backward_available.restype = i32
+    lib.sig_backward_available.argtypes = [i32, i32]
     lib.sig_probe_copy.restype = i32
     lib.sig_probe_copy.argtypes = [vp, vp, i64, vp]
     lib.sig_probe_fma.restype = i32
@@ -168,6 +173,32 @@ def sig_combine(ctx, a, b, d, depth, out, stream=None):
     return load().sig_combine(ctx, ctypes.c_void_p(a.data_ptr()), ctypes.c_void_p(b.data_ptr()),
                               a.shape[0], int(d), int(depth), ctypes.c_void_p(out.data_ptr()),
                               _stream_handle(stream))
+
+
+def sig_backward(ctx, path, depth, stream_flag, out, grad_out, grad_path, stream=None):
+    """Raw call: gradient with respect to `path` given the forward result `out` and d(loss)/d(out)."""
+    B, L, d = path.shape
+    return load().sig_backward(ctx, ctypes.c_void_p(path.data_ptr()), B, L, d, int(depth), int(stream_flag),
+                               ctypes.c_void_p(out.data_ptr()), ctypes.c_void_p(grad_out.data_ptr()),
+                               ctypes.c_void_p(grad_path.data_ptr()), _stream_handle(stream))
+
+
+def bind_backward(ctx, path, depth, stream_flag, out, grad_out, grad_path, stream=None):
+    """sig_backward with the arguments marshalled once (see bind_compute)."""
+    lib = load()
+    B, L, d = path.shape
+    args = (ctx, ctypes.c_void_p(path.data_ptr()), ctypes.c_int64(B), ctypes.c_int64(L), ctypes.c_int(d),
+            ctypes.c_int(int(depth)), ctypes.c_int(int(stream_flag)), ctypes.c_void_p(out.data_ptr()),
+            ctypes.c_void_p(grad_out.data_ptr()), ctypes.c_void_p(grad_path.data_ptr()), _stream_handle(stream))
+    keep = (path, out, grad_out, grad_path)
+
+    def call(_fn=lib.sig_backward, _args=args, _keep=keep):
+        return _fn(*_args)
+    return call
+
+
+def sig_backward_available(d, depth):
+    return int(load().sig_backward_available(int(d), int(depth)))
 
 
 def sig_probe_copy(dst, src, stream=None):

@@ -477,6 +477,26 @@ int sig_combine(sig_ctx *ctx, const float *a, const float *b, int64_t B, int d, 
     return e == hipSuccess ? SIG_OK : SIG_ERR_HIP;
 }
 
+int sig_backward(sig_ctx *ctx, const float *path, int64_t B, int64_t L, int d, int depth, int stream_flag,
+                 const float *out, const float *grad_out, float *grad_path, void *hip_stream)
+{
+    if (!ctx) return SIG_ERR_INVALID;
+    RowShape rs;
+    int rc = check_shape(B, L, d, depth, stream_flag, &rs);
+    if (rc != SIG_OK) return rc;
+    if (B == 0) return SIG_OK;
+    if (!path || !out || !grad_out || !grad_path) return SIG_ERR_INVALID;
+    if (!backward_available(d, depth) || !backward_fits(d, depth, L)) return SIG_ERR_UNSUPPORTED;
+    hipError_t e = launch_backward(path, out, grad_out, grad_path, B, L, d, depth, stream_flag, ctx->num_cu,
+                                   (hipStream_t)hip_stream);
+    return e == hipSuccess ? SIG_OK : SIG_ERR_HIP;
+}
+
+int sig_backward_available(int d, int depth)
+{
+    return backward_available(d, depth) ? 1 : 0;
+}
+
 int sig_on_chip_available(int d, int depth, int prefix_depth)
 {
     return find_on_chip(d, depth, prefix_depth) ? 1 : 0;
@@ -491,6 +511,7 @@ const char *sig_strerror(int status)
     case SIG_ERR_ALLOC: return "allocation of scratch memory failed";
     case SIG_ERR_HIP: return "a HIP call or kernel launch failed";
     case SIG_ERR_NO_DEVICE: return "no usable HIP device";
+    case SIG_ERR_UNSUPPORTED: return "no kernel is compiled for this shape";
     default: return "unknown status";
     }
 }

@@ -1,0 +1,349 @@
+// Gradient of the signature with respect to the path (reverse sweep), on-chip family.
+//
+// The signature layer is trained between other layers (paper Section 4.2, Eq. 11), so d(loss)/d(path) is
+// needed from d(loss)/d(output).  The paper differentiates Eqs. 2-5 automatically; here the reverse sweep is
+// written by hand on the same lane layout as the forward kernels:
+//
+//   * A lane owns the sub-tree of words below its prefix u, |u| = P, of BOTH the signature S and its adjoint
+//     A = d(loss)/dS, plus private copies of the prefix scalars S[u_{1:m}] and private PARTIAL adjoints of
+//     them (everything is linear in A, so the partials of the lanes that share a prefix word never have to be
+//     added up: only their sum would be the adjoint of that word, and nothing needs it).
+//   * No prefix signature is stored: signatures of paths are invertible, S_{k-1} = S_k (x) exp(-dX_k), so the
+//     sweep k = K-1 .. 0 first takes the forward fused step with the negated increment and then runs the
+//     transpose of the forward step S_{k-1} -> S_k.
+//   * Forward step in Horner form (see sig_onchip.h): for every target level n, g_{n,0} = 1,
+//       g_{n,m}[w a] = S_m[w a] + g_{n,m-1}[w] v[a] / (n-m+1)   (m < n),   S'_n[w a] = S_n[w a] + g_{n,n-1}[w] v[a].
+//     Transposed, with gb the adjoint of g:  gb_{n,n-1}[w] = sum_a A'_n[w a] v[a],
+//       A_m[w a] += gb_{n,m}[w a],  gb_{n,m-1}[w] = sum_a gb_{n,m}[w a] v[a] / (n-m+1),
+//     and d(loss)/dv[a] collects A'_n[w a] g_{n,n-1}[w] and gb_{n,m}[w a] g_{n,m-1}[w] / (n-m+1).
+//     Chains are taken in the order n = 1 .. N so that A can be updated in place (chain n reads level n as it
+//     came in and adds to the levels below it).
+//   * d(loss)/dv of one step is a sum over the Q = d^P lanes of a path.  Lanes park their partial sums of
+//     TS = max(1, Q / d) consecutive steps in LDS; then lane c of the path adds up column c = (step, channel)
+//     in a fixed order (deterministic) and writes the sum over the increment it belongs to, which is no
+//     longer needed.  When the sweep is done the tile holds d(loss)/d(dX_k) and the workgroup writes
+//     d(loss)/dX_j = d/d(dX_{j-1}) - d/d(dX_j) with consecutive threads on consecutive floats.
+//   * Stream mode: row k of the output is S_k, so its upstream gradient is added to A when the sweep reaches
+//     k (prefix words by the one lane of each prefix whose remaining letters are 0).
+#include "sig_internal.h"
+#include "sig_onchip.h"
+
+namespace sig {
+namespace onchip {
+
+// Transposed chain n inside a lane's sub-tree.  The node has index idx in sub-level r and forward chain
+// value g; returns the adjoint of g.  s = S_{k-1} (read only), ad = adjoint (updated in place),
+// dbar[a] accumulates d(loss)/dv[a].
+template <int d, int N, int P, int n, int r>
+struct Ascend {
+    using Sh = Shape<d, N, P>;
+    static __device__ __forceinline__ float run(const float (&s)[Sh::SZ], float (&ad)[Sh::SZ],
+                                                const float (&dls)[Sh::R][d], float (&dbar)[d], float g, int idx)
+    {
+        constexpr int tgt = n - P;  // sub-level of the chain's target
+        constexpr int m = r + 1;    // sub-level of this node's children
+        float gb = 0.0f;
+        if constexpr (m == tgt) {
+#pragma unroll
+            for (int a = 0; a < d; ++a) {
+                const float up = ad[Sh::sub_off(tgt) + idx * d + a];
+                gb = fmaf(up, dls[0][a], gb);
+                dbar[a] = fmaf(up, g, dbar[a]);
+            }
+        } else {
+            constexpr int c = tgt - r;  // the forward step divides v by this on the way to the children
+            const float gs = g * (1.0f / (float)c);
+#pragma unroll
+            for (int a = 0; a < d; ++a) {
+                const int child = idx * d + a;
+                const float gc = fmaf(g, dls[c - 1][a], s[Sh::sub_off(m) + child]);
+                const float cb = Ascend<d, N, P, n, m>::run(s, ad, dls, dbar, gc, child);
+                ad[Sh::sub_off(m) + child] += cb;
+                gb = fmaf(cb, dls[c - 1][a], gb);
+                dbar[a] = fmaf(cb, gs, dbar[a]);
+            }
+        }
+        return gb;
+    }
+};
+
+// Transpose of the fused step: ln = S_{k-1}, ad = A_k on entry and A_{k-1} on return; dbar (zeroed here)
+// receives this lane's part of d(loss)/dv.
+template <int d, int N, int P>
+__device__ __forceinline__ void backward_step(const Lane<d, N, P> &ln, Lane<d, N, P> &ad, const Inc<d, P> &inc,
+                                              const int *letter, float (&dbar)[d])
+{
+    using Sh = Shape<d, N, P>;
+    float dls[Sh::R][d];
+#pragma unroll
+    for (int a = 0; a < d; ++a) dls[0][a] = inc.v[a];
+#pragma unroll
+    for (int c = 1; c < Sh::R; ++c)
+#pragma unroll
+        for (int a = 0; a < d; ++a) dls[c][a] = inc.v[a] * (1.0f / (float)(c + 1));
+#pragma unroll
+    for (int a = 0; a < d; ++a) dbar[a] = 0.0f;
+    float dbu[P > 0 ? P : 1];  // adjoint of inc.du[m-1] = v[u_m]
+#pragma unroll
+    for (int m = 0; m < (P > 0 ? P : 1); ++m) dbu[m] = 0.0f;
+
+    static_for<1, N + 1>([&](auto nc) __attribute__((always_inline)) {
+        constexpr int n = decltype(nc)::value;
+        constexpr int mtop = (n - 1 < P) ? n - 1 : P;
+        // forward values of the chain along the lane's own prefix
+        float gp[P + 1];
+        gp[0] = 1.0f;
+        static_for<1, mtop + 1>([&](auto mc) __attribute__((always_inline)) {
+            constexpr int m = decltype(mc)::value;
+            const float Sm = (m < P) ? ln.pre[m - 1] : ln.s[0];
+            gp[m] = fmaf(gp[m - 1], inc.du[m - 1] * (1.0f / (float)(n - m + 1)), Sm);
+        });
+        float gb;  // adjoint of gp[mtop]
+        if constexpr (n <= P) {
+            const float up = (n < P) ? ad.pre[n - 1] : ad.s[0];
+            gb = up * inc.du[n - 1];
+            dbu[n - 1] = fmaf(up, gp[n - 1], dbu[n - 1]);
+        } else {
+            gb = Ascend<d, N, P, n, 0>::run(ln.s, ad.s, dls, dbar, gp[P], 0);
+        }
+        static_for<0, mtop>([&](auto qc) __attribute__((always_inline)) {
+            constexpr int m = mtop - decltype(qc)::value;  // mtop .. 1
+            if constexpr (m < P) ad.pre[m - 1] += gb;
+            else ad.s[0] += gb;
+            constexpr float c = 1.0f / (float)(n - m + 1);
+            dbu[m - 1] = fmaf(gb * c, gp[m - 1], dbu[m - 1]);
+            gb = gb * (inc.du[m - 1] * c);
+        });
+    });
+    // v[u_m] is component letter[m-1] of v
+    static_for<0, P>([&](auto mc) __attribute__((always_inline)) {
+        constexpr int m = decltype(mc)::value;
+#pragma unroll
+        for (int a = 0; a < d; ++a) dbar[a] += (letter[m] == a) ? dbu[m] : 0.0f;
+    });
+}
+
+// ad (+)= row, laid out like an output row; the prefix words are taken by the lane whose remaining letters are 0
+template <int d, int N, int P, bool ADD>
+__device__ __forceinline__ void load_adjoint(const float *row, unsigned u, Lane<d, N, P> &ad)
+{
+    using Sh = Shape<d, N, P>;
+    static_for<(P == 0 ? 1 : 0), Sh::R + 1>([&](auto rc) __attribute__((always_inline)) {
+        constexpr int r = decltype(rc)::value;
+        constexpr int cnt = cpow(d, r);
+        const float *src = row + Sh::row_off(P + r) + u * cnt;
+#pragma unroll
+        for (int i = 0; i < cnt; ++i) {
+            if constexpr (ADD) ad.s[Sh::sub_off(r) + i] += src[i];
+            else ad.s[Sh::sub_off(r) + i] = src[i];
+        }
+    });
+    if constexpr (P == 0 && !ADD) ad.s[0] = 0.0f;
+    static_for<1, P>([&](auto mc) __attribute__((always_inline)) {
+        constexpr int m = decltype(mc)::value;
+        constexpr unsigned span = cpow(d, P - m);
+        float g = 0.0f;
+        if (u % span == 0) g = row[Sh::row_off(m) + u / span];
+        if constexpr (ADD) ad.pre[m - 1] += g;
+        else ad.pre[m - 1] = g;
+    });
+}
+
+struct BackwardArgs {
+    const float *path;      // [B][L][d]
+    const float *sig;       // the forward result: [B][D] or [B][K][D]
+    const float *grad_out;  // same shape as sig
+    float *grad_path;       // [B][L][d]
+    int64_t B, L;
+    int32_t groups;         // paths per workgroup
+    int32_t stream_flag;
+};
+
+template <int d, int P>
+constexpr int reduce_steps() { return cpow(d, P) / d > 1 ? cpow(d, P) / d : 1; }
+
+extern __shared__ float sig_backward_smem[];
+
+template <int d, int N, int P, bool STREAM>
+__global__ __launch_bounds__(256) void sig_backward_kernel(BackwardArgs A)
+{
+    using Sh = Shape<d, N, P>;
+    constexpr int Q = Sh::Q;
+    constexpr int D = Sh::D;
+    constexpr int TS = reduce_steps<d, P>();  // steps whose partial sums are parked before they are added up
+    const int tid = threadIdx.x, nthr = blockDim.x;
+    const int64_t K = A.L - 1;
+    const int G = A.groups;
+    const int gi_raw = tid / Q;
+    const unsigned u = (unsigned)(tid - gi_raw * Q);
+    const int64_t b0 = (int64_t)blockIdx.x * G;
+    const bool active = gi_raw < G && b0 + gi_raw < A.B;
+    const int gi = gi_raw < G ? gi_raw : 0;
+    const int64_t b = active ? b0 + gi : 0;
+
+    int letter[P > 0 ? P : 1];
+    letter[0] = 0;
+    {
+        unsigned rest = u;
+#pragma unroll
+        for (int m = P - 1; m >= 0; --m) { letter[m] = (int)(rest % d); rest /= d; }
+    }
+
+    // LDS: increments [G][K*d] (overwritten step by step with their gradients), parked partial sums [G][TS][Q][d]
+    const int row_floats = (int)K * d;
+    float *tile = sig_backward_smem;
+    float *park = tile + (G * row_floats + 3) / 4 * 4;
+    for (int i = tid; i < G * row_floats; i += nthr) {
+        const int g2 = i / row_floats;
+        const int r = i - g2 * row_floats;
+        float v = 0.0f;
+        if (b0 + g2 < A.B) {
+            const float *x = A.path + (b0 + g2) * A.L * d + r;
+            v = x[d] - x[0];
+        }
+        tile[i] = v;
+    }
+
+    Lane<d, N, P> ln, ad;
+    identity_state<d, N, P>(ln);
+    identity_state<d, N, P>(ad);
+    if (P == 0) ad.s[0] = 0.0f;
+    if (active) {
+        const float *srow = STREAM ? A.sig + (b * K + (K - 1)) * D : A.sig + b * D;
+        load_state<d, N, P>(srow, u, ln);
+        if constexpr (!STREAM) load_adjoint<d, N, P, false>(A.grad_out + b * D, u, ad);
+    }
+    __syncthreads();
+
+    float *mypark = park + (size_t)gi * TS * Q * d;
+    float *myrow = tile + gi * row_floats;
+    for (int64_t k = K - 1; k >= 0; --k) {
+        const int ts = (int)((K - 1 - k) % TS);
+        if constexpr (STREAM) {
+            if (active) load_adjoint<d, N, P, true>(A.grad_out + (b * K + k) * D, u, ad);
+        }
+        Inc<d, P> inc, neg;
+        load_inc<d, P>(inc, myrow + k * d, letter);
+#pragma unroll
+        for (int a = 0; a < d; ++a) neg.v[a] = -inc.v[a];
+        neg.du[0] = 0.0f;
+#pragma unroll
+        for (int m = 0; m < P; ++m) neg.du[m] = -inc.du[m];
+        if (k > 0) fused_step<d, N, P>(ln, neg);  // S_{k-1} = S_k (x) exp(-dX_k)
+        else identity_state<d, N, P>(ln);          // before the first increment: the identity, exactly
+        float dbar[d];
+        backward_step<d, N, P>(ln, ad, inc, letter, dbar);
+        if (active) {
+#pragma unroll
+            for (int a = 0; a < d; ++a) mypark[(ts * Q + u) * d + a] = dbar[a];
+        }
+        if (ts == TS - 1 || k == 0) {
+            __syncthreads();
+            // column c = (parked step t, channel a): the sum over the path's lanes is d(loss)/d(dX)[a] of step
+            // k + (ts - t); it replaces that increment, which no lane reads again
+            if (active) {
+                for (int c = (int)u; c < (ts + 1) * d; c += Q) {
+                    const int t = c / d, a = c - t * d;
+                    float sum = 0.0f;
+                    for (int q = 0; q < Q; ++q) sum += mypark[(t * Q + q) * d + a];
+                    myrow[(k + (ts - t)) * d + a] = sum;
+                }
+            }
+            __syncthreads();
+        }
+    }
+
+    // d(loss)/dX_j = d/d(dX_{j-1}) - d/d(dX_j)
+    const int out_row = (int)A.L * d;
+    for (int i = tid; i < G * out_row; i += nthr) {
+        const int g2 = i / out_row;
+        const int r = i - g2 * out_row;
+        if (b0 + g2 < A.B) {
+            const float *t = tile + g2 * row_floats;
+            const float before = r >= d ? t[r - d] : 0.0f;
+            const float after = r < row_floats ? t[r] : 0.0f;
+            A.grad_path[(b0 + g2) * out_row + r] = before - after;
+        }
+    }
+}
+
+template <int d, int N, int P>
+int64_t backward_lds_bytes(int64_t L, int groups)
+{
+    const int64_t tile = ((int64_t)groups * (L - 1) * d + 3) / 4 * 4;
+    const int64_t park = (int64_t)groups * reduce_steps<d, P>() * Shape<d, N, P>::Q * d;
+    return (tile + park) * (int64_t)sizeof(float);
+}
+
+template <int d, int N, int P>
+hipError_t backward_launch(const BackwardArgs &A0, int threads, int cus, hipStream_t st)
+{
+    constexpr int Q = Shape<d, N, P>::Q;
+    if (threads < Q || threads > 256 || threads % kWave) return hipErrorInvalidValue;
+    BackwardArgs A = A0;
+    // paths per workgroup: as many as the threads hold, fewer if their LDS does not fit, spread over the CUs first
+    int G = threads / Q;
+    const int64_t per_cu = (A.B + cus - 1) / (cus > 0 ? cus : 1);
+    if ((int64_t)G > per_cu) G = per_cu > 1 ? (int)per_cu : 1;
+    while (G > 1 && backward_lds_bytes<d, N, P>(A.L, G) > kMaxLdsBytes) --G;
+    if (backward_lds_bytes<d, N, P>(A.L, G) > kMaxLdsBytes) return hipErrorInvalidValue;
+    A.groups = G;
+    const int64_t grid = (A.B + G - 1) / G;
+    if (grid <= 0 || grid > INT32_MAX) return hipErrorInvalidValue;
+    const size_t lds = (size_t)backward_lds_bytes<d, N, P>(A.L, G);
+    if (A.stream_flag)
+        hipLaunchKernelGGL((sig_backward_kernel<d, N, P, true>), dim3((unsigned)grid), dim3(threads), lds, st, A);
+    else
+        hipLaunchKernelGGL((sig_backward_kernel<d, N, P, false>), dim3((unsigned)grid), dim3(threads), lds, st, A);
+    return hipGetLastError();
+}
+
+}  // namespace onchip
+
+namespace {
+struct BackwardEntry {
+    int d, depth;
+    hipError_t (*launch)(const onchip::BackwardArgs &, int, int, hipStream_t);
+    int64_t (*lds_bytes)(int64_t, int);
+};
+#define SIG_BACKWARD_ENTRY(d, N, P) {d, N, &onchip::backward_launch<d, N, P>, &onchip::backward_lds_bytes<d, N, P>}
+// one prefix depth per (d, depth): the one whose two lane states (S and its adjoint) fit the registers
+const BackwardEntry kBackward[] = {
+    SIG_BACKWARD_ENTRY(2, 3, 1),
+    SIG_BACKWARD_ENTRY(4, 4, 2),
+    SIG_BACKWARD_ENTRY(5, 4, 2),
+    {0, 0, nullptr, nullptr},
+};
+const BackwardEntry *find_backward(int d, int depth)
+{
+    for (const BackwardEntry *e = kBackward; e->launch; ++e)
+        if (e->d == d && e->depth == depth) return e;
+    return nullptr;
+}
+}  // namespace
+
+bool backward_available(int d, int depth) { return find_backward(d, depth) != nullptr; }
+
+bool backward_fits(int d, int depth, int64_t L)
+{
+    const BackwardEntry *e = find_backward(d, depth);
+    return e && e->lds_bytes(L, 1) <= kMaxLdsBytes;
+}
+
+hipError_t launch_backward(const float *path, const float *sig, const float *grad_out, float *grad_path, int64_t B,
+                           int64_t L, int d, int depth, int stream_flag, int cus, hipStream_t st)
+{
+    const BackwardEntry *e = find_backward(d, depth);
+    if (!e) return hipErrorInvalidValue;
+    onchip::BackwardArgs A{};
+    A.path = path;
+    A.sig = sig;
+    A.grad_out = grad_out;
+    A.grad_path = grad_path;
+    A.B = B;
+    A.L = L;
+    A.stream_flag = stream_flag;
+    return e->launch(A, 256, cus, st);
+}
+
+}  // namespace sig

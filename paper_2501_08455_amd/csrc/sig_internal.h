@@ -40,6 +40,13 @@ hipError_t launch_combine_rows(const float *a, int64_t a_stride, const float *b,
                                float *out, int64_t out_stride, int64_t B, const RowShape &rs,
                                hipStream_t st);
 
+// ---------------------------------------------------------------- gradient with respect to the path (compiled (d, depth) only)
+bool backward_available(int d, int depth);
+// false if even one path per workgroup does not fit LDS (the increments of a whole path are staged at once)
+bool backward_fits(int d, int depth, int64_t L);
+hipError_t launch_backward(const float *path, const float *sig, const float *grad_out, float *grad_path, int64_t B,
+                           int64_t L, int d, int depth, int stream_flag, int cus, hipStream_t st);
+
 // ---------------------------------------------------------------- on-chip family (compiled (d, depth, p) only)
 struct OnChipArgs {
     const float *path;   // [B][L][d]
