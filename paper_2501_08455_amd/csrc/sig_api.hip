@@ -218,7 +218,8 @@ bool finish_on_chip(const OnChipKernelInfo *ki, int cus, int64_t B, int64_t L, i
 const OnChipKernelInfo *pick_on_chip(int d, int depth, int stream_flag)
 {
     const OnChipKernelInfo *best = nullptr;
-    for (const OnChipKernelInfo *e = on_chip_table(); e->launch; ++e) {
+    for (int t = 0; on_chip_subtable(t); ++t)
+    for (const OnChipKernelInfo *e = on_chip_subtable(t); e->launch; ++e) {
         if (e->d != d || e->depth != depth) continue;
         if (!best) { best = e; continue; }
         // entries are ordered by increasing prefix depth; p = 0 (one lane per path) is skipped when there is an
@@ -279,10 +280,22 @@ int plan_auto(const sig_ctx *ctx, int64_t B, int64_t L, int stream_flag, const R
             pl->chunks = (int)C;
             pl->segments = (int)W;
         }
-        OnChipArgs args{};
-        if (finish_on_chip(ki, cus, B, L, stream_flag, *pl, rs, &args)) {
-            pl->tile_steps = args.tile_steps;
-            return SIG_OK;
+        // the preferred cut may not fit (LDS for the chunk rows and for the rows staged for emission grows with
+        // the row length): fall back to smaller workgroups, then to fewer chunks, before giving up on the family
+        const sig_plan_t want = *pl;
+        for (int c = want.chunks; c >= 1; c = (c > 1 ? (c + 1) / 2 : 0)) {
+            for (int threads = kThreads; threads >= kWave; threads /= 2) {
+                *pl = want;
+                pl->chunks = c;
+                pl->threads = threads;
+                if (c != want.chunks) pl->segments = 1;
+                OnChipArgs args{};
+                if (finish_on_chip(ki, cus, B, L, stream_flag, *pl, rs, &args)) {
+                    pl->tile_steps = args.tile_steps;
+                    return SIG_OK;
+                }
+            }
+            if (c == 1) break;
         }
         // fall through to the streaming family
         *pl = sig_plan_t{};

@@ -509,7 +509,9 @@ __global__ __launch_bounds__((max_threads<d, N, P, CHUNKED>())) void sig_on_chip
     const int row_floats = TT * d;                      // one chunk's part of a tile, rows of d floats, unpadded
     const int tile_floats = round4(NGC * row_floats);
     float *tile0 = sig_onchip_smem + desc_floats(NGC);
-    float *sigA = tile0 + (PIPE ? 2 : 1) * tile_floats;  // [NGC][D]: chunk signatures, and the rows staged for emission
+    // [NGC][D]: chunk signatures, and the rows staged for emission; behind the tile(s) (the straight-copy tile
+    // holds rows of L * d floats plus up to three floats of alignment)
+    float *sigA = tile0 + (FLAT ? round4(G * (int)A.L * d + 3) : (PIPE ? 2 : 1) * tile_floats);
     (void)sigA;
 
     if (tid < NGC) {

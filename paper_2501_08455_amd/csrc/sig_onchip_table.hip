@@ -16,12 +16,25 @@ const OnChipKernelInfo kTable[] = {
 };
 }  // namespace
 
-const OnChipKernelInfo *on_chip_table() { return kTable; }
+const OnChipKernelInfo *on_chip_table_base() { return kTable; }
+
+const OnChipKernelInfo *on_chip_subtable(int i)
+{
+    switch (i) {
+    case 0: return on_chip_table_base();
+    case 1: return on_chip_table_depth2();
+    case 2: return on_chip_table_depth3();
+    case 3: return on_chip_table_depth4();
+    case 4: return on_chip_table_depth56();
+    default: return nullptr;
+    }
+}
 
 const OnChipKernelInfo *find_on_chip(int d, int depth, int p)
 {
-    for (const OnChipKernelInfo *e = kTable; e->launch; ++e)
-        if (e->d == d && e->depth == depth && e->p == p) return e;
+    for (int t = 0; on_chip_subtable(t); ++t)
+        for (const OnChipKernelInfo *e = on_chip_subtable(t); e->launch; ++e)
+            if (e->d == d && e->depth == depth && e->p == p) return e;
     return nullptr;
 }
 

@@ -72,7 +72,7 @@ def test_plan_of_the_five_configs_is_on_chip_and_consistent(name):
 
 
 def test_plan_falls_back_to_streaming_for_uncompiled_shapes():
-    rc, pl = binding.sig_plan(None, 7, 30, 3, 5, 0)
+    rc, pl = binding.sig_plan(None, 7, 30, 9, 5, 0)
     assert rc == binding.SIG_OK and pl.variant == binding.SIG_VARIANT_HBM_STREAMING
     assert 0 <= pl.prefix_depth <= 4
 
@@ -104,7 +104,7 @@ def test_every_forced_plan_of_the_gpu_tests_is_accepted_by_the_host_checks():
 def test_plan_validate_rejects_plans_the_kernels_cannot_run():
     mk = binding.make_plan
     on = binding.SIG_VARIANT_ON_CHIP
-    assert binding.sig_plan_validate(4, 16, 3, 3, 0, mk(on, prefix_depth=1)) == binding.SIG_ERR_INVALID  # not compiled
+    assert binding.sig_plan_validate(4, 16, 9, 3, 0, mk(on, prefix_depth=1)) == binding.SIG_ERR_INVALID  # not compiled
     assert binding.sig_plan_validate(4, 16, 5, 4, 0, mk(on, prefix_depth=2, chunks=11)) == binding.SIG_ERR_INVALID
     assert binding.sig_plan_validate(4, 16, 5, 4, 1, mk(on, prefix_depth=2, segments=2)) == binding.SIG_ERR_INVALID
     assert binding.sig_plan_validate(4, 6, 5, 4, 0, mk(on, prefix_depth=2, chunks=3, segments=2)) == binding.SIG_ERR_INVALID
@@ -113,3 +113,19 @@ def test_plan_validate_rejects_plans_the_kernels_cannot_run():
         == binding.SIG_ERR_INVALID
     assert binding.sig_plan_validate(4, 16, 5, 4, 0, mk(binding.SIG_VARIANT_HBM_STREAMING, prefix_depth=3)) \
         == binding.SIG_OK
+
+
+def test_planner_keeps_the_shape_grid_on_chip():
+    """Every compiled (d, depth) gets an on-chip plan that validates, over the batch sizes and lengths of the
+    paper's direct-computation tables (Section 4.1) and beyond; host only."""
+    grid = [(2, 3), (4, 4), (5, 4), (10, 6), (2, 2), (3, 2), (4, 2), (5, 2), (6, 2), (8, 2), (10, 2), (3, 3), (4, 3),
+            (5, 3), (6, 3), (7, 3), (8, 3), (10, 3), (2, 4), (3, 4), (6, 4), (7, 4), (8, 4), (10, 4), (2, 5), (3, 5),
+            (4, 5), (5, 5), (6, 5), (2, 6), (3, 6), (4, 6)]
+    for d, depth in grid:
+        for B in (1, 7, 32, 128, 512, 4096, 65536):
+            for L in (2, 9, 50, 200, 1000):
+                for stream in (0, 1):
+                    rc, pl = binding.sig_plan(None, B, L, d, depth, stream)
+                    assert rc == binding.SIG_OK, (d, depth, B, L, stream)
+                    assert pl.variant == binding.SIG_VARIANT_ON_CHIP, (d, depth, B, L, stream, pl.as_dict())
+                    assert binding.sig_plan_validate(B, L, d, depth, stream, pl) == binding.SIG_OK

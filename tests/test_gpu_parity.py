@@ -87,7 +87,7 @@ def test_hbm_streaming_family(gpu, oracle, B, L, d, depth, stream, p):
 
 
 def test_uncompiled_shapes_fall_back(gpu, oracle):
-    for (B, L, d, depth) in [(3, 33, 3, 4), (2, 17, 6, 3), (130, 5, 2, 5)]:
+    for (B, L, d, depth) in [(3, 33, 9, 3), (2, 17, 7, 2), (130, 5, 3, 7)]:
         rc, pl = gpu.sig_plan(None, B, L, d, depth, 0)
         assert rc == 0 and pl.variant == gpu.SIG_VARIANT_HBM_STREAMING
         x = workloads.brownian_paths(B, L, d, seed=77 + d)
@@ -155,6 +155,44 @@ def test_on_chip_independent_wavefronts(gpu, oracle, case):
     check(gpu, oracle, x, depth, stream, plan, label="independent")
 
 
+# ---------------------------------------------------------------- the wider shape grid (channels 2..10, depths 2..6)
+SHAPE_GRID = [(2, 2, 1), (3, 2, 1), (4, 2, 1), (5, 2, 1), (6, 2, 1), (8, 2, 1), (10, 2, 1),
+              (3, 3, 1), (4, 3, 1), (5, 3, 1), (6, 3, 1), (7, 3, 1), (8, 3, 2), (10, 3, 2),
+              (2, 4, 1), (3, 4, 1), (6, 4, 2), (7, 4, 2), (8, 4, 2), (10, 4, 2),
+              (2, 5, 1), (3, 5, 2), (4, 5, 3), (5, 5, 3), (6, 5, 3), (2, 6, 1), (3, 6, 3), (4, 6, 4)]
+
+
+@pytest.mark.parametrize("shape", SHAPE_GRID, ids=lambda c: "-".join(str(v) for v in c))
+def test_shape_grid(gpu, oracle, shape):
+    """Every further compiled kernel: the planner's choice at two batch sizes, and forced time cuts."""
+    d, depth, p = shape
+    assert gpu.sig_on_chip_available(d, depth, p)
+    Q = d ** p
+    for B, L in [(3, 23), (70, 9)]:
+        x = workloads.brownian_paths(B, L, d, seed=6000 + 31 * d + depth + B)
+        for stream in (False, True):
+            rc, pl = gpu.sig_plan(None, B, L, d, depth, int(stream))
+            assert rc == gpu.SIG_OK and pl.variant == gpu.SIG_VARIANT_ON_CHIP
+            check(gpu, oracle, x, depth, stream, label="grid auto")
+    x = workloads.brownian_paths(4, 41, d, seed=6100 + d + depth)
+    forced = [(1, 3, 4, False), (1, 1, 7, True)]
+    if Q <= 64:
+        forced += [(3, 2, 0, False), (2, 1, 0, True), (3, 1, 5, True)]
+    ran = 0
+    for chunks, segments, tile, stream in forced:
+        for threads in (256, 128, 64):
+            plan = gpu.make_plan(gpu.SIG_VARIANT_ON_CHIP, prefix_depth=p, chunks=chunks, segments=segments,
+                                 tile_steps=tile, threads=threads)
+            if gpu.sig_plan_validate(4, 41, d, depth, int(stream), plan) == gpu.SIG_OK:
+                check(gpu, oracle, x, depth, stream, plan, label="grid forced")
+                ran += 1
+                break
+        else:
+            # long rows: the rows of all chunks / segments of a path do not fit LDS at any workgroup size
+            say("plan %r does not fit this shape" % ((chunks, segments, tile, stream),))
+    assert ran >= 1
+
+
 def test_single_increment_and_repeated_points(gpu, oracle):
     x = workloads.brownian_paths(6, 2, 5, seed=3)
     check(gpu, oracle, x, 4, False, label="L=2")
@@ -178,8 +216,8 @@ def test_error_codes_and_empty_batch(gpu):
     assert gpu.sig_compute(None, x, 2, 0, out) == gpu.SIG_ERR_INVALID
     empty = torch.zeros((0, 5, 3), device="cuda")
     assert gpu.sig_compute(ctx, empty, 2, 0, out) == gpu.SIG_OK
-    bad = gpu.make_plan(gpu.SIG_VARIANT_ON_CHIP, prefix_depth=1, chunks=1, segments=1)
-    assert gpu.sig_compute(ctx, x, 2, 0, out, plan=bad) == gpu.SIG_ERR_INVALID  # (3, 2) has no on-chip kernel
+    bad = gpu.make_plan(gpu.SIG_VARIANT_ON_CHIP, prefix_depth=0, chunks=1, segments=1)
+    assert gpu.sig_compute(ctx, x, 2, 0, out, plan=bad) == gpu.SIG_ERR_INVALID  # (3, 2) has no kernel with p = 0
     torch.cuda.synchronize()
 
 
