@@ -157,6 +157,30 @@ def bench_backward(binding, workloads, ctx, cfg, B, steps, warmup):
     return res
 
 
+# The rows of the paper's Table 1 (direct signature computation on GPU): batch, length, depth and the paper's own
+# "KS GPU" time in milliseconds on an RTX 4090.  The paper does not state the channel count of that table; d = 5
+# (the channel count of the headline configuration) is used here, so the two columns are context, not a comparison.
+TABLE1_ROWS = [(32, 100, 4, 0.1312), (64, 100, 4, 0.1424), (128, 100, 4, 0.1785), (256, 100, 4, 0.1833),
+               (512, 100, 4, 0.2621), (128, 50, 4, 0.1399), (128, 200, 4, 0.1798), (128, 500, 4, 0.5718),
+               (128, 1000, 4, 0.5417), (128, 100, 2, 0.1689), (128, 100, 3, 0.1712), (128, 100, 5, 0.1585),
+               (128, 100, 6, 0.2903)]
+
+
+def table1(binding, workloads, ctx, d=5):
+    """Time sig_compute (final signature) on the shapes of the paper's Table 1."""
+    import torch
+    rows = []
+    for B, L, depth, paper_ms in TABLE1_ROWS:
+        x = torch.from_numpy(workloads.brownian_paths(B, L, d, seed=1000 + B + L + depth)).cuda()
+        out = torch.empty((B, workloads.sig_size(d, depth)), dtype=torch.float32, device="cuda")
+        ms, _ = time_calls(binding, ctx, x, depth, 0, out, 500, 300)
+        rc, pl = binding.sig_plan(ctx, B, L, d, depth, 0)
+        rows.append({"batch": B, "length": L, "depth": depth, "channels": d, "ms": ms,
+                     "paper_ks_gpu_ms_rtx4090": paper_ms, "plan": pl.as_dict()})
+        del x, out
+    return rows
+
+
 def anchors(binding):
     """Achievable rates on this GPU: a plain copy (HBM) and an fp32 FMA loop without packed instructions."""
     import torch
@@ -274,6 +298,7 @@ def main():
             c = workloads.CONFIGS[name]
             extras.append(bench_backward(binding, workloads, ctx, c, B or c.B, steps, warm))
         line["all_configs"] = extras
+        line["table1_shapes"] = table1(binding, workloads, ctx)
     if args.anchors:
         line["anchors"] = anchors(binding)
     print(json.dumps(line))

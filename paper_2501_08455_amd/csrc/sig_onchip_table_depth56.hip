@@ -14,6 +14,7 @@ const OnChipKernelInfo kTable[] = {
     SIG_ON_CHIP_ENTRY(2, 6, 1),
     SIG_ON_CHIP_ENTRY(3, 6, 3),
     SIG_ON_CHIP_ENTRY(4, 6, 4),
+    SIG_ON_CHIP_ENTRY(5, 6, 4),
     {0, 0, 0, 0, 0, 0, nullptr, nullptr, nullptr},
 };
 }  // namespace

@@ -120,7 +120,7 @@ def test_planner_keeps_the_shape_grid_on_chip():
     paper's direct-computation tables (Section 4.1) and beyond; host only."""
     grid = [(2, 3), (4, 4), (5, 4), (10, 6), (2, 2), (3, 2), (4, 2), (5, 2), (6, 2), (8, 2), (10, 2), (3, 3), (4, 3),
             (5, 3), (6, 3), (7, 3), (8, 3), (10, 3), (2, 4), (3, 4), (6, 4), (7, 4), (8, 4), (10, 4), (2, 5), (3, 5),
-            (4, 5), (5, 5), (6, 5), (2, 6), (3, 6), (4, 6)]
+            (4, 5), (5, 5), (6, 5), (2, 6), (3, 6), (4, 6), (5, 6)]
     for d, depth in grid:
         for B in (1, 7, 32, 128, 512, 4096, 65536):
             for L in (2, 9, 50, 200, 1000):
