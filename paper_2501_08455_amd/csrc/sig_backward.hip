@@ -31,6 +31,20 @@
 namespace sig {
 namespace onchip {
 
+// value / reference of the lane's copy of the prefix word u_{1:m}, m = 1 .. P (u itself is s[0])
+template <int m, int d, int N, int P>
+__device__ __forceinline__ float prefix_value(const Lane<d, N, P> &x)
+{
+    if constexpr (m < P) return x.pre[m - 1];
+    else return x.s[0];
+}
+template <int m, int d, int N, int P>
+__device__ __forceinline__ float &prefix_ref(Lane<d, N, P> &x)
+{
+    if constexpr (m < P) return x.pre[m - 1];
+    else return x.s[0];
+}
+
 // Transposed chain n inside a lane's sub-tree.  The node has index idx in sub-level r and forward chain
 // value g; returns the adjoint of g.  s = S_{k-1} (read only), ad = adjoint (updated in place),
 // dbar[a] accumulates d(loss)/dv[a].
@@ -95,12 +109,11 @@ __device__ __forceinline__ void backward_step(const Lane<d, N, P> &ln, Lane<d, N
         gp[0] = 1.0f;
         static_for<1, mtop + 1>([&](auto mc) __attribute__((always_inline)) {
             constexpr int m = decltype(mc)::value;
-            const float Sm = (m < P) ? ln.pre[m - 1] : ln.s[0];
-            gp[m] = fmaf(gp[m - 1], inc.du[m - 1] * (1.0f / (float)(n - m + 1)), Sm);
+            gp[m] = fmaf(gp[m - 1], inc.du[m - 1] * (1.0f / (float)(n - m + 1)), prefix_value<m>(ln));
         });
         float gb;  // adjoint of gp[mtop]
         if constexpr (n <= P) {
-            const float up = (n < P) ? ad.pre[n - 1] : ad.s[0];
+            const float up = prefix_value<n>(ad);
             gb = up * inc.du[n - 1];
             dbu[n - 1] = fmaf(up, gp[n - 1], dbu[n - 1]);
         } else {
@@ -108,8 +121,7 @@ __device__ __forceinline__ void backward_step(const Lane<d, N, P> &ln, Lane<d, N
         }
         static_for<0, mtop>([&](auto qc) __attribute__((always_inline)) {
             constexpr int m = mtop - decltype(qc)::value;  // mtop .. 1
-            if constexpr (m < P) ad.pre[m - 1] += gb;
-            else ad.s[0] += gb;
+            prefix_ref<m>(ad) += gb;
             constexpr float c = 1.0f / (float)(n - m + 1);
             dbu[m - 1] = fmaf(gb * c, gp[m - 1], dbu[m - 1]);
             gb = gb * (inc.du[m - 1] * c);
@@ -267,6 +279,206 @@ __global__ __launch_bounds__(256) void sig_backward_kernel(BackwardArgs A)
     }
 }
 
+// Transpose of reg_product with respect to its left factor.  For c = a (x) b (Eq. 4), c[w] = sum over the
+// splits w = (v, x) of a[v] b[x], so d(loss)/da[v] = sum_x d(loss)/dc[(v, x)] b[x].  `ad` holds d(loss)/dc on
+// entry and d(loss)/da on return, in the lane layout of the sweep (sub-tree below u, private partials for the
+// prefix words); b is a row of D floats in LDS.  All words (v, x) a lane needs lie in its own sub-tree or on its
+// own prefix, so nothing crosses lanes.
+template <int d, int N, int P>
+__device__ __forceinline__ void reg_adjoint_product(Lane<d, N, P> &ad, const float *b, unsigned u)
+{
+    using Sh = Shape<d, N, P>;
+    // prefix words u_{1:i}, i = 1 .. P, shortest first (they read the longer ones and the sub-tree as they came in)
+    static_for<1, P + 1>([&](auto ic) __attribute__((always_inline)) {
+        constexpr int i = decltype(ic)::value;
+        float acc = prefix_value<i>(ad);
+        // longer prefix words u_{1:n}: x = u_{i+1:n}
+        static_for<i + 1, P + 1>([&](auto nc) __attribute__((always_inline)) {
+            constexpr int n = decltype(nc)::value;
+            const unsigned suffix = (u / (unsigned)cpow(d, P - n)) % (unsigned)cpow(d, n - i);
+            acc = fmaf(prefix_value<n>(ad), b[Sh::row_off(n - i) + suffix], acc);
+        });
+        // words (u, v), |v| = r >= 1: x = (u_{i+1:P}, v), a run of d^r floats of level P + r - i
+        static_for<1, Sh::R + 1>([&](auto rc) __attribute__((always_inline)) {
+            constexpr int r = decltype(rc)::value;
+            constexpr int cnt = cpow(d, r);
+            const float *bs = b + Sh::row_off(P + r - i) + (u % (unsigned)cpow(d, P - i)) * cnt;
+#pragma unroll
+            for (int v = 0; v < cnt; ++v) acc = fmaf(ad.s[Sh::sub_off(r) + v], bs[v], acc);
+        });
+        prefix_ref<i>(ad) = acc;
+    });
+    // the empty prefix (P == 0): the lane's root is the empty word, whose gradient is not needed
+    // sub-tree words (u, v), |v| = r = 1 .. R-1, shallowest first: x = the rest of a deeper word
+    static_for<1, Sh::R>([&](auto rc) __attribute__((always_inline)) {
+        constexpr int r = decltype(rc)::value;
+        constexpr int cnt = cpow(d, r);
+        static_for<r + 1, Sh::R + 1>([&](auto qc) __attribute__((always_inline)) {
+            constexpr int r2 = decltype(qc)::value;
+            constexpr int tail = cpow(d, r2 - r);
+            const float *bs = b + Sh::row_off(r2 - r);
+#pragma unroll
+            for (int v = 0; v < cnt; ++v) {
+                float acc = ad.s[Sh::sub_off(r) + v];
+#pragma unroll
+                for (int x = 0; x < tail; ++x) acc = fmaf(ad.s[Sh::sub_off(r2) + v * tail + x], bs[x], acc);
+                ad.s[Sh::sub_off(r) + v] = acc;
+            }
+        });
+    });
+}
+
+template <int d, int N, int P>
+constexpr int chunk_row_floats()  // one chunk's row in either LDS buffer of the chunked sweep
+{
+    using Sh = Shape<d, N, P>;
+    int a = Sh::D;
+    const int park = reduce_steps<d, P>() * Sh::Q * d;
+    if (park > a) a = park;
+    return (a + 3) / 4 * 4;
+}
+
+// Final-mode sweep cut in time: one workgroup per path, C chunks of T increments side by side.
+//   1. every chunk folds its increments from the identity: its own signature E_c                (T steps)
+//   2. a scan from the left gives every prefix S_end(c) = E_0 (x) ... (x) E_c, a scan from the right every
+//      X_c = E_{c+1} (x) ... (x) E_{C-1}; the workgroup shares each product                       (2 (C-1) products)
+//   3. every chunk pulls the upstream gradient back through X_c: A_end(c)                        (1 product)
+//   4. every chunk runs the reverse sweep over its own increments from (S_end(c), A_end(c))       (T steps)
+// so the critical path is about 2 T steps and 2 C short products instead of C T steps.
+template <int d, int N, int P>
+__global__ __launch_bounds__(256) void sig_backward_chunked_kernel(BackwardArgs A)
+{
+    using Sh = Shape<d, N, P>;
+    constexpr int Q = Sh::Q;
+    constexpr int D = Sh::D;
+    constexpr int TS = reduce_steps<d, P>();
+    constexpr int ROW = chunk_row_floats<d, N, P>();
+    const int tid = threadIdx.x, nthr = blockDim.x;
+    const int K = (int)(A.L - 1);
+    const int C = A.groups;  // chunks per path
+    const int T = (K + C - 1) / C;
+    const int c_raw = tid / Q;
+    const unsigned u = (unsigned)(tid - c_raw * Q);
+    const bool active = c_raw < C;
+    const int c = active ? c_raw : 0;
+    const int64_t b = blockIdx.x;
+    int steps = K - c * T;
+    if (steps > T) steps = T;
+    if (steps < 0 || !active) steps = 0;
+
+    int letter[P > 0 ? P : 1];
+    letter[0] = 0;
+    {
+        unsigned rest = u;
+#pragma unroll
+        for (int m = P - 1; m >= 0; --m) { letter[m] = (int)(rest % d); rest /= d; }
+    }
+
+    float *tile = sig_backward_smem;                 // [K][d] increments, later their gradients
+    float *rowsE = tile + (K * d + 3) / 4 * 4;       // [C][ROW] chunk signatures, later the parked partial sums
+    float *rowsS = rowsE + C * ROW;                  // [C][ROW] prefixes S_end(c), later the adjoints A_end(c)
+    for (int i = tid; i < K * d; i += nthr) {
+        const float *x = A.path + b * A.L * d + i;
+        tile[i] = x[d] - x[0];
+    }
+    __syncthreads();
+
+    // 1. chunk signatures
+    Lane<d, N, P> ln, ad;
+    identity_state<d, N, P>(ln);
+    for (int t = 0; t < steps; ++t) {
+        Inc<d, P> inc;
+        load_inc<d, P>(inc, tile + (c * T + t) * d, letter);
+        fused_step<d, N, P>(ln, inc);
+    }
+    if (active) store_state<d, N, P>(rowsE + c * ROW, u, ln);
+    __syncthreads();
+    // 2. prefixes S_end(c) = E_0 (x) ... (x) E_c, left to right; the whole workgroup shares each product
+    //    (one work item per parent word, see RowProduct)
+    using RP = RowProduct<d, N>;
+    for (int x = tid; x < D; x += nthr) rowsS[x] = rowsE[x];
+    __syncthreads();
+    for (int c2 = 1; c2 < C; ++c2) {
+        for (int x = tid; x < RP::ITEMS; x += nthr)
+            RP::item(rowsS + (c2 - 1) * ROW, rowsE + c2 * ROW, rowsS + c2 * ROW, x);
+        __syncthreads();
+    }
+    if (active) load_state<d, N, P>(rowsS + c * ROW, u, ln);
+    __syncthreads();
+    // 3. the adjoint at the end of chunk c is the upstream gradient pulled back through everything after the
+    //    chunk: A_end(c) = transpose of (. (x) X_c) applied to d(loss)/d(out), X_c = E_{c+1} (x) ... (x) E_{C-1}.
+    //    The X_c are a scan from the right (X_{C-1} is the identity: a row of zeros); then every chunk pulls
+    //    the gradient back on its own.
+    for (int x = tid; x < D; x += nthr) rowsS[(C - 1) * ROW + x] = 0.0f;
+    __syncthreads();
+    for (int c2 = C - 1; c2 >= 1; --c2) {
+        for (int x = tid; x < RP::ITEMS; x += nthr)
+            RP::item(rowsE + c2 * ROW, rowsS + c2 * ROW, rowsS + (c2 - 1) * ROW, x);
+        __syncthreads();
+    }
+    identity_state<d, N, P>(ad);
+    if (P == 0) ad.s[0] = 0.0f;
+    if (active) {
+        load_adjoint<d, N, P, false>(A.grad_out + b * D, u, ad);
+        if (c < C - 1) reg_adjoint_product<d, N, P>(ad, rowsS + c * ROW, u);
+    }
+    __syncthreads();
+    // 4. the sweep of every chunk; rowsE now parks the partial sums
+    float *mypark = rowsE + c * ROW;
+    for (int t = T - 1; t >= 0; --t) {
+        const int ts = (T - 1 - t) % TS;
+        float dbar[d];
+#pragma unroll
+        for (int a = 0; a < d; ++a) dbar[a] = 0.0f;
+        if (t < steps) {
+            const int k = c * T + t;
+            Inc<d, P> inc, neg;
+            load_inc<d, P>(inc, tile + k * d, letter);
+#pragma unroll
+            for (int a = 0; a < d; ++a) neg.v[a] = -inc.v[a];
+            neg.du[0] = 0.0f;
+#pragma unroll
+            for (int m = 0; m < P; ++m) neg.du[m] = -inc.du[m];
+            if (k > 0) fused_step<d, N, P>(ln, neg);
+            else identity_state<d, N, P>(ln);
+            backward_step<d, N, P>(ln, ad, inc, letter, dbar);
+        }
+        if (active) {
+#pragma unroll
+            for (int a = 0; a < d; ++a) mypark[(ts * Q + u) * d + a] = dbar[a];
+        }
+        if (ts == TS - 1 || t == 0) {
+            __syncthreads();
+            if (active) {
+                for (int col = (int)u; col < (ts + 1) * d; col += Q) {
+                    const int tp = col / d, a = col - tp * d;
+                    const int tt = t + (ts - tp);  // step of this chunk the column belongs to
+                    if (tt < steps) {
+                        float sum = 0.0f;
+                        for (int q = 0; q < Q; ++q) sum += mypark[(tp * Q + q) * d + a];
+                        tile[(c * T + tt) * d + a] = sum;
+                    }
+                }
+            }
+            __syncthreads();
+        }
+    }
+
+    const int out_row = (int)A.L * d;
+    for (int i = tid; i < out_row; i += nthr) {
+        const float before = i >= d ? tile[i - d] : 0.0f;
+        const float after = i < K * d ? tile[i] : 0.0f;
+        A.grad_path[b * out_row + i] = before - after;
+    }
+}
+
+template <int d, int N, int P>
+int64_t backward_chunked_lds_bytes(int64_t L, int chunks)
+{
+    const int64_t tile = ((L - 1) * d + 3) / 4 * 4;
+    return (tile + 2 * (int64_t)chunks * chunk_row_floats<d, N, P>()) * (int64_t)sizeof(float);
+}
+
 template <int d, int N, int P>
 int64_t backward_lds_bytes(int64_t L, int groups)
 {
@@ -281,6 +493,19 @@ hipError_t backward_launch(const BackwardArgs &A0, int threads, int cus, hipStre
     constexpr int Q = Shape<d, N, P>::Q;
     if (threads < Q || threads > 256 || threads % kWave) return hipErrorInvalidValue;
     BackwardArgs A = A0;
+    // Few paths (fewer lanes than two wavefronts per SIMD) and no stream mode: cut the sweep in time, one
+    // workgroup per path with as many chunks as its threads and LDS hold, at least eight increments each.
+    if (!A.stream_flag && A.B * Q < (int64_t)cus * 4 * kWave * 2 && A.B <= INT32_MAX) {
+        int C = threads / Q;
+        if (C > (A.L - 1) / 8) C = (int)((A.L - 1) / 8);
+        while (C > 1 && backward_chunked_lds_bytes<d, N, P>(A.L, C) > kMaxLdsBytes) --C;
+        if (C > 1) {
+            A.groups = C;
+            const size_t lds = (size_t)backward_chunked_lds_bytes<d, N, P>(A.L, C);
+            hipLaunchKernelGGL((sig_backward_chunked_kernel<d, N, P>), dim3((unsigned)A.B), dim3(threads), lds, st, A);
+            return hipGetLastError();
+        }
+    }
     // paths per workgroup: as many as the threads hold, fewer if their LDS does not fit, spread over the CUs first
     int G = threads / Q;
     const int64_t per_cu = (A.B + cus - 1) / (cus > 0 ? cus : 1);
