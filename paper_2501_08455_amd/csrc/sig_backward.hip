@@ -19,7 +19,7 @@
 //     Chains are taken in the order n = 1 .. N so that A can be updated in place (chain n reads level n as it
 //     came in and adds to the levels below it).
 //   * d(loss)/dv of one step is a sum over the Q = d^P lanes of a path.  Lanes park their partial sums of
-//     TS = max(1, Q / d) consecutive steps in LDS; then lane c of the path adds up column c = (step, channel)
+//     TS = min(max(1, Q / d), 8) consecutive steps in LDS; then lane c of the path adds up column c = (step, channel)
 //     in a fixed order (deterministic) and writes the sum over the increment it belongs to, which is no
 //     longer needed.  When the sweep is done the tile holds d(loss)/d(dX_k) and the workgroup writes
 //     d(loss)/dX_j = d/d(dX_{j-1}) - d/d(dX_j) with consecutive threads on consecutive floats.
@@ -171,8 +171,14 @@ struct BackwardArgs {
     int32_t stream_flag;
 };
 
+// steps whose partial sums are parked before they are added up: enough for every lane of a path to have a
+// column (Q / d), but no more than eight (the parked sums take TS * Q * d floats of LDS per path)
 template <int d, int P>
-constexpr int reduce_steps() { return cpow(d, P) / d > 1 ? cpow(d, P) / d : 1; }
+constexpr int reduce_steps()
+{
+    const int want = cpow(d, P) / d;
+    return want < 1 ? 1 : (want > 8 ? 8 : want);
+}
 
 extern __shared__ float sig_backward_smem[];
 
@@ -534,9 +540,14 @@ struct BackwardEntry {
 #define SIG_BACKWARD_ENTRY(d, N, P) {d, N, &onchip::backward_launch<d, N, P>, &onchip::backward_lds_bytes<d, N, P>}
 // one prefix depth per (d, depth): the one whose two lane states (S and its adjoint) fit the registers
 const BackwardEntry kBackward[] = {
-    SIG_BACKWARD_ENTRY(2, 3, 1),
-    SIG_BACKWARD_ENTRY(4, 4, 2),
-    SIG_BACKWARD_ENTRY(5, 4, 2),
+    SIG_BACKWARD_ENTRY(2, 2, 1), SIG_BACKWARD_ENTRY(3, 2, 1), SIG_BACKWARD_ENTRY(4, 2, 1), SIG_BACKWARD_ENTRY(5, 2, 1),
+    SIG_BACKWARD_ENTRY(6, 2, 1), SIG_BACKWARD_ENTRY(8, 2, 1), SIG_BACKWARD_ENTRY(10, 2, 1),
+    SIG_BACKWARD_ENTRY(2, 3, 1), SIG_BACKWARD_ENTRY(3, 3, 1), SIG_BACKWARD_ENTRY(4, 3, 1), SIG_BACKWARD_ENTRY(5, 3, 1),
+    SIG_BACKWARD_ENTRY(6, 3, 1), SIG_BACKWARD_ENTRY(7, 3, 1), SIG_BACKWARD_ENTRY(8, 3, 2), SIG_BACKWARD_ENTRY(10, 3, 2),
+    SIG_BACKWARD_ENTRY(2, 4, 1), SIG_BACKWARD_ENTRY(3, 4, 1), SIG_BACKWARD_ENTRY(4, 4, 2), SIG_BACKWARD_ENTRY(5, 4, 2),
+    SIG_BACKWARD_ENTRY(6, 4, 2), SIG_BACKWARD_ENTRY(7, 4, 2),
+    SIG_BACKWARD_ENTRY(2, 5, 1), SIG_BACKWARD_ENTRY(3, 5, 2), SIG_BACKWARD_ENTRY(4, 5, 3), SIG_BACKWARD_ENTRY(5, 5, 3),
+    SIG_BACKWARD_ENTRY(2, 6, 1), SIG_BACKWARD_ENTRY(3, 6, 3),
     {0, 0, nullptr, nullptr},
 };
 const BackwardEntry *find_backward(int d, int depth)

@@ -83,6 +83,21 @@ def test_backward_matches_oracle(gpu, oracle, case):
     check(gpu, oracle, x, depth, stream, seed=B + L, label="on-chip")
 
 
+BACKWARD_GRID = [(2, 2), (3, 2), (4, 2), (5, 2), (6, 2), (8, 2), (10, 2), (2, 3), (3, 3), (4, 3), (5, 3), (6, 3), (7, 3),
+                 (8, 3), (10, 3), (2, 4), (3, 4), (4, 4), (5, 4), (6, 4), (7, 4), (2, 5), (3, 5), (4, 5), (5, 5),
+                 (2, 6), (3, 6)]
+
+
+@pytest.mark.parametrize("shape", BACKWARD_GRID, ids=lambda c: "-".join(str(v) for v in c))
+def test_backward_shape_grid(gpu, oracle, shape):
+    """Every (d, depth) with a gradient kernel: a few long paths (sweep cut in time), many short ones, stream mode."""
+    d, depth = shape
+    assert gpu.sig_backward_available(d, depth) == 1
+    for B, L, stream in [(3, 41, False), (300, 7, False), (4, 19, True)]:
+        x = workloads.brownian_paths(B, L, d, seed=8000 + 13 * d + depth + B)
+        check(gpu, oracle, x, depth, stream, seed=d + depth + L, label="grid")
+
+
 def test_backward_on_the_configurations(gpu, oracle):
     for name in ["C1", "C2", "C4"]:
         cfg = workloads.CONFIGS[name]
@@ -102,11 +117,11 @@ def test_backward_repeated_points_and_reproducible(gpu, oracle):
 def test_backward_status_codes(gpu):
     import torch
     ctx = gpu.default_ctx()
-    assert gpu.sig_backward_available(5, 4) == 1 and gpu.sig_backward_available(3, 2) == 0
-    x = torch.zeros((2, 5, 3), device="cuda")
-    out = torch.zeros((2, gpu.sig_size(3, 2)), device="cuda")
+    assert gpu.sig_backward_available(5, 4) == 1 and gpu.sig_backward_available(9, 2) == 0
+    x = torch.zeros((2, 5, 9), device="cuda")
+    out = torch.zeros((2, gpu.sig_size(9, 2)), device="cuda")
     gx = torch.zeros_like(x)
-    assert gpu.sig_backward(ctx, x, 2, 0, out, out, gx) == gpu.SIG_ERR_UNSUPPORTED  # no kernel for (3, 2)
+    assert gpu.sig_backward(ctx, x, 2, 0, out, out, gx) == gpu.SIG_ERR_UNSUPPORTED  # no kernel for (9, 2)
     x5 = torch.zeros((1, 20000, 5), device="cuda")  # one path's increments exceed the LDS staging
     o5 = torch.zeros((1, gpu.sig_size(5, 4)), device="cuda")
     assert gpu.sig_backward(ctx, x5, 4, 0, o5, o5, torch.zeros_like(x5)) == gpu.SIG_ERR_UNSUPPORTED
