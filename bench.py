@@ -101,8 +101,8 @@ def bench_config(binding, workloads, ctx, cfg, B, steps, warmup, plan=None, labe
         ach = design_bytes / (ms_ev * 1e-3) / 1e9
         res["roofline"] = {"bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                            "frac": ach / PEAK_HBM_GBS, "traffic": None,
-                           "note": "bytes of the state-in-HBM design (8 B per coefficient and increment), "
-                                   "much of which is served by L2 / Infinity Cache at this size"}
+                           "note": "bytes of the state-in-HBM design (8 B per coefficient and increment); the HBM "
+                                   "counters read the same amount (profiles/sig_hbm_streaming_C5.md)"}
     del xt, out
     return res
 

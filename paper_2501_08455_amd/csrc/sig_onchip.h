@@ -611,12 +611,23 @@ __global__ __launch_bounds__((max_threads<d, N, P, CHUNKED>())) void sig_on_chip
             const int steps = (T - t0 < TT) ? T - t0 : TT;
             const float *row = tile + mygc * row_stride;
             Inc<d, P> inc;
+            // large lane states run at two or three wavefronts per SIMD, too few to hide the LDS latency of the
+            // increment at the top of every step: there the next increment is read while the current step runs
+            constexpr bool AHEAD = SIG_STEP_UNROLL > 1 && Sh::SZ > 64 && !emit;
+            Inc<d, P> nxt;
+            if constexpr (AHEAD) {
+                if (steps > 0) load_inc<d, P>(nxt, row, letter);
+            }
             for (int t = 0; t < steps; ++t, row += d) {
                 SIG_STEP_TICK(t0 + t, 0);
-                load_inc<d, P>(inc, row, letter);
-#ifndef SIG_DIAG_NO_FOLD
+                if constexpr (AHEAD) {
+                    inc = nxt;
+                    // (the read one past the last step stays inside the workgroup's LDS and is not used)
+                    load_inc<d, P>(nxt, row + (t + 1 < steps ? d : 0), letter);
+                } else {
+                    load_inc<d, P>(inc, row, letter);
+                }
                 fused_step<d, N, P>(ln, inc);
-#endif
                 if constexpr (emit && WAVE_SLOTS) {
                     // gather this wavefront's rows in LDS, then write them with consecutive lanes on
                     // consecutive addresses (LDS operations of one wavefront execute in order)
@@ -631,11 +642,7 @@ __global__ __launch_bounds__((max_threads<d, N, P, CHUNKED>())) void sig_on_chip
                             SIG_STEP_TICK(t0 + t, 3);
 #pragma unroll
                             for (int j = 0; j < NIT; ++j)
-#ifdef SIG_DIAG_NO_STORE
-                                if (t0 + t < elim[j] && val[j].x == 12345.678f) eptr[j][(int64_t)(t0 + t) * ROWV] = val[j];
-#else
                                 if (t0 + t < elim[j]) eptr[j][(int64_t)(t0 + t) * ROWV] = val[j];
-#endif
                         }
                     } else {
                         const int wave = tid / kWave, lw = tid - wave * kWave;
@@ -1100,11 +1107,7 @@ __global__ __launch_bounds__(256) void sig_fold_kernel(OnChipArgs A)
                             });
                             static_for<0, NIT>([&](auto jc) __attribute__((always_inline)) {
                                 constexpr int j = decltype(jc)::value;
-#ifdef SIG_DIAG_NO_STORE
-                                if (t0 + t < elim[j] && val[j].x == 12345.678f) eptr[j][(int64_t)(t0 + t) * ROWV] = val[j];
-#else
                                 if (t0 + t < elim[j]) eptr[j][(int64_t)(t0 + t) * ROWV] = val[j];
-#endif
                             });
                         }
                     } else {
