@@ -141,6 +141,15 @@ bool finish_on_chip(const OnChipKernelInfo *ki, int cus, int64_t B, int64_t L, i
         } else {
             int64_t by_lds = kTileLdsBytes / (ngc * ki->d * (int64_t)sizeof(float));
             if (tt > by_lds) tt = by_lds;
+            // Shapes with little arithmetic per byte of path (fewer than 16 flops per byte read: depth 2, small
+            // depth 3) are bound by reading the path; short tiles keep the workgroups' LDS small, so that more of
+            // them are resident and more loads are in flight (measured with 2 to 5 channels: 10 steps per tile beat
+            // 19 by 10-30 %; with 8 channels they lose, with 10 it makes no difference).
+            if (!forced && !stream_flag && ki->d <= 6) {
+                double fma = 0.0;
+                for (int m = 1; m <= rs.depth; ++m) fma += (double)(rs.depth - m + 1) * (double)rs.pow[m];
+                if (2.0 * fma / (4.0 * ki->d) < 16.0 && tt > 10) tt = 10;
+            }
         }
         if (tt < 1) return false;
         args->pipe = pipe && tt < T;
@@ -212,8 +221,9 @@ bool finish_on_chip(const OnChipKernelInfo *ki, int cus, int64_t B, int64_t L, i
 
 // Which compiled prefix depth to use for (d, depth).  A wavefront issues a vector instruction only every
 // five to six cycles, so the fp32 rate needs several wavefronts per SIMD: for the final signature prefer
-// the smallest prefix depth whose per-lane state leaves room for four of them (<= 96 floats of state),
-// else the deepest one.  Stream mode is bound by the stores, not the arithmetic: take the deepest
+// the smallest prefix depth whose per-lane state is at most 64 floats (six or more wavefronts per SIMD, and the
+// chunk tree runs in registers; measured on d = 4, depth 4: 85 floats per lane lose to 21 by 1.5x at every
+// batch size), else the deepest one.  Stream mode is bound by the stores, not the arithmetic: take the deepest
 // prefix (most lanes, fewest registers, most stores in flight).
 const OnChipKernelInfo *pick_on_chip(int d, int depth, int stream_flag)
 {
@@ -224,7 +234,7 @@ const OnChipKernelInfo *pick_on_chip(int d, int depth, int stream_flag)
         if (!best) { best = e; continue; }
         // entries are ordered by increasing prefix depth; p = 0 (one lane per path) is skipped when there is an
         // alternative: its LDS reads of the increments are not broadcasts (every lane reads another path's row)
-        if (stream_flag || best->state_floats > 96 || best->p == 0) best = e;
+        if (stream_flag || best->state_floats > 64 || best->p == 0) best = e;
     }
     return best;
 }
@@ -235,12 +245,19 @@ int plan_auto(const sig_ctx *ctx, int64_t B, int64_t L, int stream_flag, const R
     const int64_t K = L - 1;
     // lanes that fill the chip: eight wavefronts on every SIMD for the arithmetic-bound final mode, one for
     // stream mode (bound by the stores; cutting time there costs a second fold)
-    const int64_t want_lanes = (int64_t)cus * 4 * kWave * (stream_flag ? 1 : 8);
+    int64_t want_lanes = (int64_t)cus * 4 * kWave * (stream_flag ? 1 : 8);
     *pl = sig_plan_t{};
     pl->threads = kThreads;
 
     const OnChipKernelInfo *ki = (B > 0) ? pick_on_chip(rs.d, rs.depth, stream_flag) : nullptr;
     if (ki) {
+        // a large lane state leaves room for fewer wavefronts per SIMD: do not cut time to fill slots that the
+        // registers cannot hold (estimate: state + 45 registers per lane, 512 per SIMD lane)
+        if (!stream_flag && ki->state_floats > 64) {
+            int by_vgpr = 512 / (ki->state_floats + 45);
+            if (by_vgpr < 1) by_vgpr = 1;
+            if (by_vgpr < 8) want_lanes = (int64_t)cus * 4 * kWave * by_vgpr;
+        }
         pl->variant = SIG_VARIANT_ON_CHIP;
         pl->prefix_depth = ki->p;
         pl->chunks = 1;

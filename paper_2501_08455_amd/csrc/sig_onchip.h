@@ -27,10 +27,6 @@
 
 #include "sig_internal.h"
 
-#ifndef SIG_STEP_UNROLL
-#define SIG_STEP_UNROLL 1
-#endif
-
 // Wavefront priority of the phases that wait on HBM (staging increments, writing results).  The SIMD's
 // arbiter favours older wavefronts, so a freshly started workgroup would otherwise issue its loads only in
 // the gaps its neighbours' arithmetic leaves; with the priority raised the loads go out at once and the
@@ -611,22 +607,9 @@ __global__ __launch_bounds__((max_threads<d, N, P, CHUNKED>())) void sig_on_chip
             const int steps = (T - t0 < TT) ? T - t0 : TT;
             const float *row = tile + mygc * row_stride;
             Inc<d, P> inc;
-            // large lane states run at two or three wavefronts per SIMD, too few to hide the LDS latency of the
-            // increment at the top of every step: there the next increment is read while the current step runs
-            constexpr bool AHEAD = SIG_STEP_UNROLL > 1 && Sh::SZ > 64 && !emit;
-            Inc<d, P> nxt;
-            if constexpr (AHEAD) {
-                if (steps > 0) load_inc<d, P>(nxt, row, letter);
-            }
             for (int t = 0; t < steps; ++t, row += d) {
                 SIG_STEP_TICK(t0 + t, 0);
-                if constexpr (AHEAD) {
-                    inc = nxt;
-                    // (the read one past the last step stays inside the workgroup's LDS and is not used)
-                    load_inc<d, P>(nxt, row + (t + 1 < steps ? d : 0), letter);
-                } else {
-                    load_inc<d, P>(inc, row, letter);
-                }
+                load_inc<d, P>(inc, row, letter);
                 fused_step<d, N, P>(ln, inc);
                 if constexpr (emit && WAVE_SLOTS) {
                     // gather this wavefront's rows in LDS, then write them with consecutive lanes on
@@ -712,7 +695,8 @@ __global__ __launch_bounds__((max_threads<d, N, P, CHUNKED>())) void sig_on_chip
                 // last position that lies in the row in full (valid - 4), so no load is split; what a tile
                 // row holds beyond the chunk's end is zero (an increment of zero leaves the state unchanged).
                 // (the lane state is live here: with a small state one more element in flight costs a whole
-                // wavefront of occupancy, with a large one the occupancy is low anyway)
+                // wavefront of occupancy, and measured slower even on the shapes bound by reading the path; with a
+                // large state the occupancy is low anyway)
                 constexpr int LB = Sh::SZ <= 64 ? 1 : 3;
                 const int vshift = rshift > 2 ? rshift - 2 : 0;  // vectors per chunk row, padded to a power of two
                 const int vmask = (1 << vshift) - 1;
