@@ -235,10 +235,14 @@ __global__ __launch_bounds__(256) void sig_backward_kernel(BackwardArgs A)
 
     float *mypark = park + (size_t)gi * TS * Q * d;
     float *myrow = tile + gi * row_floats;
-    for (int64_t k = K - 1; k >= 0; --k) {
+    // One step of the sweep; `upk` is the upstream gradient of row k (stream mode).
+    auto step = [&](int64_t k, const Lane<d, N, P> *upk) __attribute__((always_inline)) {
         const int ts = (int)((K - 1 - k) % TS);
         if constexpr (STREAM) {
-            if (active) load_adjoint<d, N, P, true>(A.grad_out + (b * K + k) * D, u, ad);
+#pragma unroll
+            for (int i = 0; i < Sh::SZ; ++i) ad.s[i] += upk->s[i];
+#pragma unroll
+            for (int i = 0; i < Sh::NPRE; ++i) ad.pre[i] += upk->pre[i];
         }
         Inc<d, P> inc, neg;
         load_inc<d, P>(inc, myrow + k * d, letter);
@@ -269,6 +273,31 @@ __global__ __launch_bounds__(256) void sig_backward_kernel(BackwardArgs A)
             }
             __syncthreads();
         }
+    };
+    if constexpr (STREAM) {
+        // The upstream gradient rows are fetched PD steps ahead into registers: a row's HBM latency (well over
+        // a microsecond) is several steps long, and at one or two wavefronts per SIMD nothing else hides it.
+        // (as many rows as the registers hold beside the two lane states)
+        constexpr int PD = Sh::SZ <= 24 ? 4 : Sh::SZ <= 48 ? 2 : 1;
+        Lane<d, N, P> up[PD];
+        static_for<0, PD>([&](auto jc) __attribute__((always_inline)) {
+            constexpr int j = decltype(jc)::value;
+            identity_state<d, N, P>(up[j]);
+            if (P == 0) up[j].s[0] = 0.0f;
+            if (active && K - 1 - j >= 0) load_adjoint<d, N, P, false>(A.grad_out + (b * K + (K - 1 - j)) * D, u, up[j]);
+        });
+        for (int64_t kk = K - 1; kk >= 0; kk -= PD) {
+            static_for<0, PD>([&](auto jc) __attribute__((always_inline)) {
+                constexpr int j = decltype(jc)::value;
+                const int64_t k = kk - j;
+                if (k >= 0) {
+                    step(k, &up[j]);
+                    if (active && k - PD >= 0) load_adjoint<d, N, P, false>(A.grad_out + (b * K + (k - PD)) * D, u, up[j]);
+                }
+            });
+        }
+    } else {
+        for (int64_t k = K - 1; k >= 0; --k) step(k, nullptr);
     }
 
     // d(loss)/dX_j = d/d(dX_{j-1}) - d/d(dX_j)
