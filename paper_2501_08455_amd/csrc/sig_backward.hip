@@ -363,6 +363,30 @@ __device__ __forceinline__ void reg_adjoint_product(Lane<d, N, P> &ad, const flo
     });
 }
 
+// a lane's registers in LDS, register i of lane u at i * Q + u (consecutive lanes on consecutive banks)
+template <int d, int N, int P>
+constexpr int private_floats() { return (Shape<d, N, P>::SZ + Shape<d, N, P>::NPRE) * Shape<d, N, P>::Q; }
+
+template <int d, int N, int P>
+__device__ __forceinline__ void store_private(float *buf, unsigned u, const Lane<d, N, P> &x)
+{
+    using Sh = Shape<d, N, P>;
+#pragma unroll
+    for (int i = 0; i < Sh::SZ; ++i) buf[i * Sh::Q + u] = x.s[i];
+#pragma unroll
+    for (int i = 0; i < Sh::NPRE; ++i) buf[(Sh::SZ + i) * Sh::Q + u] = x.pre[i];
+}
+
+template <int d, int N, int P>
+__device__ __forceinline__ void load_private(const float *buf, unsigned u, Lane<d, N, P> &x)
+{
+    using Sh = Shape<d, N, P>;
+#pragma unroll
+    for (int i = 0; i < Sh::SZ; ++i) x.s[i] = buf[i * Sh::Q + u];
+#pragma unroll
+    for (int i = 0; i < Sh::NPRE; ++i) x.pre[i] = buf[(Sh::SZ + i) * Sh::Q + u];
+}
+
 template <int d, int N, int P>
 constexpr int chunk_row_floats()  // one chunk's row in either LDS buffer of the chunked sweep
 {
@@ -373,14 +397,17 @@ constexpr int chunk_row_floats()  // one chunk's row in either LDS buffer of the
     return (a + 3) / 4 * 4;
 }
 
-// Final-mode sweep cut in time: one workgroup per path, C chunks of T increments side by side.
+// The sweep cut in time: one workgroup per path, C chunks of T increments side by side.
 //   1. every chunk folds its increments from the identity: its own signature E_c                (T steps)
-//   2. a scan from the left gives every prefix S_end(c) = E_0 (x) ... (x) E_c, a scan from the right every
-//      X_c = E_{c+1} (x) ... (x) E_{C-1}; the workgroup shares each product                       (2 (C-1) products)
-//   3. every chunk pulls the upstream gradient back through X_c: A_end(c)                        (1 product)
+//   2. a scan from the left gives every prefix S_end(c) = E_0 (x) ... (x) E_c; the workgroup shares each product
+//   3. the adjoint A_end(c) at the end of every chunk:
+//      final mode  - a scan from the right gives X_c = E_{c+1} (x) ... (x) E_{C-1}, and every chunk pulls the
+//                    upstream gradient back through X_c on its own                               (C products)
+//      stream mode - a first sweep of every chunk from a zero adjoint gives what its own rows leave at its
+//                    start; the lanes of chunk 0 then walk the chunks from the last to the first   (T steps, C products)
 //   4. every chunk runs the reverse sweep over its own increments from (S_end(c), A_end(c))       (T steps)
-// so the critical path is about 2 T steps and 2 C short products instead of C T steps.
-template <int d, int N, int P>
+// so the critical path is about 2 T (stream: 3 T) steps and 2 C short products instead of C T steps.
+template <int d, int N, int P, bool STREAM>
 __global__ __launch_bounds__(256) void sig_backward_chunked_kernel(BackwardArgs A)
 {
     using Sh = Shape<d, N, P>;
@@ -411,7 +438,8 @@ __global__ __launch_bounds__(256) void sig_backward_chunked_kernel(BackwardArgs 
 
     float *tile = sig_backward_smem;                 // [K][d] increments, later their gradients
     float *rowsE = tile + (K * d + 3) / 4 * 4;       // [C][ROW] chunk signatures, later the parked partial sums
-    float *rowsS = rowsE + C * ROW;                  // [C][ROW] prefixes S_end(c), later the adjoints A_end(c)
+    float *rowsS = rowsE + C * ROW;                  // [C][ROW] prefixes S_end(c), then (final mode) the X_c
+    float *rowsA = rowsS + C * ROW;                  // stream mode: [C][private_floats] adjoints, lane layout
     for (int i = tid; i < K * d; i += nthr) {
         const float *x = A.path + b * A.L * d + i;
         tile[i] = x[d] - x[0];
@@ -440,63 +468,138 @@ __global__ __launch_bounds__(256) void sig_backward_chunked_kernel(BackwardArgs 
     }
     if (active) load_state<d, N, P>(rowsS + c * ROW, u, ln);
     __syncthreads();
-    // 3. the adjoint at the end of chunk c is the upstream gradient pulled back through everything after the
-    //    chunk: A_end(c) = transpose of (. (x) X_c) applied to d(loss)/d(out), X_c = E_{c+1} (x) ... (x) E_{C-1}.
-    //    The X_c are a scan from the right (X_{C-1} is the identity: a row of zeros); then every chunk pulls
-    //    the gradient back on its own.
-    for (int x = tid; x < D; x += nthr) rowsS[(C - 1) * ROW + x] = 0.0f;
-    __syncthreads();
-    for (int c2 = C - 1; c2 >= 1; --c2) {
-        for (int x = tid; x < RP::ITEMS; x += nthr)
-            RP::item(rowsE + c2 * ROW, rowsS + c2 * ROW, rowsS + (c2 - 1) * ROW, x);
-        __syncthreads();
-    }
-    identity_state<d, N, P>(ad);
-    if (P == 0) ad.s[0] = 0.0f;
-    if (active) {
-        load_adjoint<d, N, P, false>(A.grad_out + b * D, u, ad);
-        if (c < C - 1) reg_adjoint_product<d, N, P>(ad, rowsS + c * ROW, u);
-    }
-    __syncthreads();
-    // 4. the sweep of every chunk; rowsE now parks the partial sums
+    // The sweep of this lane's chunk from (ln, ad) = (S_end(c), A_end(c)), t = T-1 .. 0 for every chunk alike
+    // (chunks with fewer increments idle in the surplus iterations).  EMIT: the partial sums of d(loss)/d(dX) are
+    // parked in rowsE, added up and written over the increments.  Stream mode adds row k's upstream gradient
+    // before step k; the rows are fetched PD steps ahead (see the unchunked kernel).
     float *mypark = rowsE + c * ROW;
-    for (int t = T - 1; t >= 0; --t) {
-        const int ts = (T - 1 - t) % TS;
-        float dbar[d];
-#pragma unroll
-        for (int a = 0; a < d; ++a) dbar[a] = 0.0f;
-        if (t < steps) {
-            const int k = c * T + t;
-            Inc<d, P> inc, neg;
-            load_inc<d, P>(inc, tile + k * d, letter);
-#pragma unroll
-            for (int a = 0; a < d; ++a) neg.v[a] = -inc.v[a];
-            neg.du[0] = 0.0f;
-#pragma unroll
-            for (int m = 0; m < P; ++m) neg.du[m] = -inc.du[m];
-            if (k > 0) fused_step<d, N, P>(ln, neg);
-            else identity_state<d, N, P>(ln);
-            backward_step<d, N, P>(ln, ad, inc, letter, dbar);
+    constexpr int PD = !STREAM ? 1 : Sh::SZ <= 24 ? 4 : Sh::SZ <= 48 ? 2 : 1;
+    auto sweep = [&](auto emit_tag) __attribute__((always_inline)) {
+        constexpr bool EMIT = decltype(emit_tag)::value;
+        Lane<d, N, P> up[PD];
+        if constexpr (STREAM) {
+            static_for<0, PD>([&](auto jc) __attribute__((always_inline)) {
+                constexpr int j = decltype(jc)::value;
+                identity_state<d, N, P>(up[j]);
+                const int t = T - 1 - j;
+                if (t >= 0 && t < steps)
+                    load_adjoint<d, N, P, false>(A.grad_out + (b * K + (c * T + t)) * D, u, up[j]);
+            });
         }
-        if (active) {
+        for (int t0 = T - 1; t0 >= 0; t0 -= PD) {
+            static_for<0, PD>([&](auto jc) __attribute__((always_inline)) {
+                constexpr int j = decltype(jc)::value;
+                const int t = t0 - j;
+                if (t >= 0) {
+                    const int ts = (T - 1 - t) % TS;
+                    float dbar[d];
 #pragma unroll
-            for (int a = 0; a < d; ++a) mypark[(ts * Q + u) * d + a] = dbar[a];
-        }
-        if (ts == TS - 1 || t == 0) {
-            __syncthreads();
-            if (active) {
-                for (int col = (int)u; col < (ts + 1) * d; col += Q) {
-                    const int tp = col / d, a = col - tp * d;
-                    const int tt = t + (ts - tp);  // step of this chunk the column belongs to
-                    if (tt < steps) {
-                        float sum = 0.0f;
-                        for (int q = 0; q < Q; ++q) sum += mypark[(tp * Q + q) * d + a];
-                        tile[(c * T + tt) * d + a] = sum;
+                    for (int a = 0; a < d; ++a) dbar[a] = 0.0f;
+                    if (t < steps) {
+                        const int k = c * T + t;
+                        if constexpr (STREAM) {
+#pragma unroll
+                            for (int i = 0; i < Sh::SZ; ++i) ad.s[i] += up[j].s[i];
+#pragma unroll
+                            for (int i = 0; i < Sh::NPRE; ++i) ad.pre[i] += up[j].pre[i];
+                        }
+                        Inc<d, P> inc, neg;
+                        load_inc<d, P>(inc, tile + k * d, letter);
+#pragma unroll
+                        for (int a = 0; a < d; ++a) neg.v[a] = -inc.v[a];
+                        neg.du[0] = 0.0f;
+#pragma unroll
+                        for (int m = 0; m < P; ++m) neg.du[m] = -inc.du[m];
+                        if (k > 0) fused_step<d, N, P>(ln, neg);
+                        else identity_state<d, N, P>(ln);
+                        backward_step<d, N, P>(ln, ad, inc, letter, dbar);
+                    }
+                    if constexpr (STREAM) {
+                        const int tn = t - PD;
+                        if (tn >= 0 && tn < steps)
+                            load_adjoint<d, N, P, false>(A.grad_out + (b * K + (c * T + tn)) * D, u, up[j]);
+                    }
+                    if constexpr (EMIT) {
+                        if (active) {
+#pragma unroll
+                            for (int a = 0; a < d; ++a) mypark[(ts * Q + u) * d + a] = dbar[a];
+                        }
+                        if (ts == TS - 1 || t == 0) {
+                            __syncthreads();
+                            if (active) {
+                                for (int col = (int)u; col < (ts + 1) * d; col += Q) {
+                                    const int tp = col / d, a = col - tp * d;
+                                    const int tt = t + (ts - tp);  // step of this chunk the column belongs to
+                                    if (tt < steps) {
+                                        float sum = 0.0f;
+                                        for (int q = 0; q < Q; ++q) sum += mypark[(tp * Q + q) * d + a];
+                                        tile[(c * T + tt) * d + a] = sum;
+                                    }
+                                }
+                            }
+                            __syncthreads();
+                        }
                     }
                 }
-            }
+            });
+        }
+    };
+
+    identity_state<d, N, P>(ad);
+    if (P == 0) ad.s[0] = 0.0f;
+    if constexpr (!STREAM) {
+        // 3. the adjoint at the end of chunk c is the upstream gradient pulled back through everything after
+        //    the chunk: A_end(c) = transpose of (. (x) X_c) applied to d(loss)/d(out), X_c = E_{c+1} (x) ... (x)
+        //    E_{C-1}.  The X_c are a scan from the right (X_{C-1} is the identity: a row of zeros); then every
+        //    chunk pulls the gradient back on its own.
+        for (int x = tid; x < D; x += nthr) rowsS[(C - 1) * ROW + x] = 0.0f;
+        __syncthreads();
+        for (int c2 = C - 1; c2 >= 1; --c2) {
+            for (int x = tid; x < RP::ITEMS; x += nthr)
+                RP::item(rowsE + c2 * ROW, rowsS + c2 * ROW, rowsS + (c2 - 1) * ROW, x);
             __syncthreads();
         }
+        if (active) {
+            load_adjoint<d, N, P, false>(A.grad_out + b * D, u, ad);
+            if (c < C - 1) reg_adjoint_product<d, N, P>(ad, rowsS + c * ROW, u);
+        }
+        __syncthreads();
+        // 4. the sweep of every chunk; rowsE now parks the partial sums
+        sweep(std::true_type{});
+    } else {
+        // Stream mode: every row has its own upstream gradient, so what reaches the end of chunk c from the later
+        // chunks is r_{c+1} + transpose of (. (x) E_{c+1}) applied to A_end(c+1), where r_c is what chunk c's own
+        // rows leave at its start.
+        // 3a. a first sweep from a zero adjoint, without output, gives r_c
+        sweep(std::false_type{});
+        if (active) store_private<d, N, P>(rowsA + c * private_floats<d, N, P>(), u, ad);
+        __syncthreads();
+        // 3b. the lanes of chunk 0 walk the chunks from the last to the first: A_end(c-1) = r_c + pull-back of
+        //     A_end(c) through E_c; A_end(c) takes r_c's place in LDS
+        if (active && c == 0) {
+            Lane<d, N, P> run, r;
+            identity_state<d, N, P>(run);
+            if (P == 0) run.s[0] = 0.0f;
+            for (int c2 = C - 1; c2 >= 1; --c2) {
+                float *slot = rowsA + c2 * private_floats<d, N, P>();
+                load_private<d, N, P>(slot, u, r);
+                store_private<d, N, P>(slot, u, run);
+                reg_adjoint_product<d, N, P>(run, rowsE + c2 * ROW, u);
+#pragma unroll
+                for (int i = 0; i < Sh::SZ; ++i) run.s[i] += r.s[i];
+#pragma unroll
+                for (int i = 0; i < Sh::NPRE; ++i) run.pre[i] += r.pre[i];
+            }
+            store_private<d, N, P>(rowsA, u, run);
+        }
+        __syncthreads();
+        // 4. the second sweep, from the true adjoint, with output (rowsE parks the partial sums from here on)
+        if (active) {
+            load_state<d, N, P>(rowsS + c * ROW, u, ln);
+            load_private<d, N, P>(rowsA + c * private_floats<d, N, P>(), u, ad);
+        }
+        __syncthreads();
+        sweep(std::true_type{});
     }
 
     const int out_row = (int)A.L * d;
@@ -508,10 +611,12 @@ __global__ __launch_bounds__(256) void sig_backward_chunked_kernel(BackwardArgs 
 }
 
 template <int d, int N, int P>
-int64_t backward_chunked_lds_bytes(int64_t L, int chunks)
+int64_t backward_chunked_lds_bytes(int64_t L, int chunks, int stream_flag)
 {
     const int64_t tile = ((L - 1) * d + 3) / 4 * 4;
-    return (tile + 2 * (int64_t)chunks * chunk_row_floats<d, N, P>()) * (int64_t)sizeof(float);
+    int64_t per_chunk = 2 * (int64_t)chunk_row_floats<d, N, P>();
+    if (stream_flag) per_chunk += private_floats<d, N, P>();
+    return (tile + chunks * per_chunk) * (int64_t)sizeof(float);
 }
 
 template <int d, int N, int P>
@@ -528,16 +633,19 @@ hipError_t backward_launch(const BackwardArgs &A0, int threads, int cus, hipStre
     constexpr int Q = Shape<d, N, P>::Q;
     if (threads < Q || threads > 256 || threads % kWave) return hipErrorInvalidValue;
     BackwardArgs A = A0;
-    // Few paths (fewer lanes than two wavefronts per SIMD) and no stream mode: cut the sweep in time, one
-    // workgroup per path with as many chunks as its threads and LDS hold, at least eight increments each.
-    if (!A.stream_flag && A.B * Q < (int64_t)cus * 4 * kWave * 2 && A.B <= INT32_MAX) {
+    // Few paths (fewer lanes than two wavefronts per SIMD): cut the sweep in time, one workgroup per path with
+    // as many chunks as its threads and LDS hold, at least eight increments each.
+    if (A.B * Q < (int64_t)cus * 4 * kWave * 2 && A.B <= INT32_MAX) {
         int C = threads / Q;
         if (C > (A.L - 1) / 8) C = (int)((A.L - 1) / 8);
-        while (C > 1 && backward_chunked_lds_bytes<d, N, P>(A.L, C) > kMaxLdsBytes) --C;
+        while (C > 1 && backward_chunked_lds_bytes<d, N, P>(A.L, C, A.stream_flag) > kMaxLdsBytes) --C;
         if (C > 1) {
             A.groups = C;
-            const size_t lds = (size_t)backward_chunked_lds_bytes<d, N, P>(A.L, C);
-            hipLaunchKernelGGL((sig_backward_chunked_kernel<d, N, P>), dim3((unsigned)A.B), dim3(threads), lds, st, A);
+            const size_t lds = (size_t)backward_chunked_lds_bytes<d, N, P>(A.L, C, A.stream_flag);
+            if (A.stream_flag)
+                hipLaunchKernelGGL((sig_backward_chunked_kernel<d, N, P, true>), dim3((unsigned)A.B), dim3(threads), lds, st, A);
+            else
+                hipLaunchKernelGGL((sig_backward_chunked_kernel<d, N, P, false>), dim3((unsigned)A.B), dim3(threads), lds, st, A);
             return hipGetLastError();
         }
     }
