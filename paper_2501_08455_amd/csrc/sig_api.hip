@@ -297,6 +297,20 @@ int plan_auto(const sig_ctx *ctx, int64_t B, int64_t L, int stream_flag, const R
             pl->chunks = (int)C;
             pl->segments = (int)W;
         }
+        // Stream mode without time cuts: one wavefront per workgroup if its paths then fit one straight-copy tile
+        // with room for six workgroups per CU.  A tile boundary costs a stream kernel a drain of its store
+        // queue (the loader's wait also waits for every store issued before it); measured 5 % on d = 4, depth 4.
+        if (stream_flag && pl->chunks == 1 && pl->segments == 1 && Q <= kWave) {
+            sig_plan_t narrow = *pl;
+            narrow.threads = kWave;
+            OnChipArgs args{};
+            if (finish_on_chip(ki, cus, B, L, stream_flag, narrow, rs, &args) && args.flat_tile &&
+                ki->lds_bytes(args) <= 26 * 1024) {
+                *pl = narrow;
+                pl->tile_steps = args.tile_steps;
+                return SIG_OK;
+            }
+        }
         // the preferred cut may not fit (LDS for the chunk rows and for the rows staged for emission grows with
         // the row length): fall back to smaller workgroups, then to fewer chunks, before giving up on the family
         const sig_plan_t want = *pl;
