@@ -181,6 +181,47 @@ def table1(binding, workloads, ctx, d=5):
     return rows
 
 
+def training_step(workloads, B, L, d, depth, steps, warmup):
+    """One optimisation step of the paper's model (Section 4.2, Eq. 11): Dense(20 -> d) with tanh, signature of
+    depth `depth`, Dense(D -> 10), mean squared error, plain gradient descent; synthetic inputs of the stated
+    shape.  The two Dense layers are torch (rocBLAS / hipBLASLt GEMMs); the signature layer and its gradient are
+    libsig's kernels.  The paper does not name the activation; tanh is used here."""
+    import torch
+    from paper_2501_08455_amd import autograd
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(11)
+    D = workloads.sig_size(d, depth)
+    X = torch.randn((B, L, 20), device="cuda", generator=gen).cumsum(1) * (1.0 / L) ** 0.5
+    Y = torch.randn((B, 10), device="cuda", generator=gen)
+    W1 = (torch.randn((20, d), device="cuda", generator=gen) * 0.2).requires_grad_(True)
+    b1 = torch.zeros(d, device="cuda", requires_grad=True)
+    W2 = (torch.randn((D, 10), device="cuda", generator=gen) * 0.05).requires_grad_(True)
+    b2 = torch.zeros(10, device="cuda", requires_grad=True)
+    params = [W1, b1, W2, b2]
+
+    def one_step():
+        Z = torch.tanh(X @ W1 + b1)
+        S = autograd.signature(Z, depth)
+        loss = ((S @ W2 + b2 - Y) ** 2).mean()
+        grads = torch.autograd.grad(loss, params)
+        with torch.no_grad():
+            for p_, g_ in zip(params, grads):
+                p_ -= 1e-3 * g_
+        return loss
+
+    for _ in range(warmup):
+        one_step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(steps):
+        loss = one_step()
+    e1.record()
+    torch.cuda.synchronize()
+    return {"model": "Dense(20->%d, tanh) -> signature depth %d -> Dense(%d->10), MSE, SGD" % (d, depth, D),
+            "batch": B, "length": L, "ms_per_step": e0.elapsed_time(e1) / steps, "final_loss": float(loss.detach())}
+
+
 def anchors(binding):
     """Achievable rates on this GPU: a plain copy (HBM) and an fp32 FMA loop without packed instructions."""
     import torch
@@ -299,6 +340,9 @@ def main():
             extras.append(bench_backward(binding, workloads, ctx, c, B or c.B, steps, warm))
         line["all_configs"] = extras
         line["table1_shapes"] = table1(binding, workloads, ctx)
+        # a training step of the paper's model with the signature layer in the middle (context for Section 4.2)
+        line["training_step"] = [training_step(workloads, 128, L, d, depth, 100, 30)
+                                 for (L, d, depth) in [(100, 5, 4), (200, 6, 3), (500, 4, 4)]]
     if args.anchors:
         line["anchors"] = anchors(binding)
     print(json.dumps(line))

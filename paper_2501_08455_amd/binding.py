@@ -47,6 +47,12 @@ def load():
     global _lib
     if _lib is not None:
         return _lib
+    # torch brings its own copy of the HIP runtime; loading it first keeps one runtime in charge of the device
+    # (libsig loaded before torch has been seen to end in "no usable HIP device" at sig_create)
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     if not os.path.exists(LIB_PATH):
         from . import build as _build
         _build.build()

@@ -635,7 +635,9 @@ hipError_t backward_launch(const BackwardArgs &A0, int threads, int cus, hipStre
     BackwardArgs A = A0;
     // Few paths (fewer lanes than two wavefronts per SIMD): cut the sweep in time, one workgroup per path with
     // as many chunks as its threads and LDS hold, at least eight increments each.
-    if (A.B * Q < (int64_t)cus * 4 * kWave * 2 && A.B <= INT32_MAX) {
+    // (stream mode reads the upstream gradient twice when cut, so only far below one wavefront per SIMD)
+    const int64_t few_lanes = A.stream_flag ? (int64_t)cus * kWave : (int64_t)cus * 4 * kWave * 2;
+    if (A.B * Q < few_lanes && A.B <= INT32_MAX) {
         int C = threads / Q;
         if (C > (A.L - 1) / 8) C = (int)((A.L - 1) / 8);
         while (C > 1 && backward_chunked_lds_bytes<d, N, P>(A.L, C, A.stream_flag) > kMaxLdsBytes) --C;

@@ -130,3 +130,20 @@ def test_backward_status_codes(gpu):
     empty = torch.zeros((0, 10, 5), device="cuda")
     assert gpu.sig_backward(ctx, empty, 4, 0, o5, o5, empty) == gpu.SIG_OK
     torch.cuda.synchronize()
+
+
+def test_autograd_wrapper(gpu, oracle):
+    """torch.autograd through the layer: Dense -> signature -> weighted sum, gradients against the oracle."""
+    import torch
+    from paper_2501_08455_amd import autograd
+    rng = np.random.default_rng(41)
+    for stream in (False, True):
+        x = workloads.brownian_paths(6, 30, 5, seed=90)
+        xt = torch.from_numpy(x).cuda().requires_grad_(True)
+        sig = autograd.signature(xt, 4, stream=stream)
+        w = rng.normal(size=tuple(sig.shape)).astype(np.float32)
+        (sig * torch.from_numpy(w).cuda()).sum().backward()
+        torch.cuda.synchronize()
+        want = oracle.signature_backward(x, 4, w, stream=stream)
+        got = xt.grad.cpu().numpy()
+        assert np.linalg.norm(got - want) / np.linalg.norm(want) <= TOL
