@@ -30,7 +30,7 @@ MEASURED_TRAFFIC_BYTES = {
     ("C1", 1 << 20): (2 * 65559.8 + 57344.0) * 1024,
     ("C2", 65536): (2 * 64439.9 + 199681.7) * 1024,
     ("C3", 4096): (2 * 83023.9 + 12480.0) * 1024,
-    ("C4", 4096): (2 * 8994.7 + 1389440.0) * 1024,
+    ("C4", 4096): (2 * 8286.8 + 1389966.8) * 1024,
 }
 
 
