@@ -147,3 +147,29 @@ def test_autograd_wrapper(gpu, oracle):
         want = oracle.signature_backward(x, 4, w, stream=stream)
         got = xt.grad.cpu().numpy()
         assert np.linalg.norm(got - want) / np.linalg.norm(want) <= TOL
+
+
+@pytest.mark.parametrize("name,B", [("C2", 65536), ("C4", 4096)])
+def test_backward_saturated_variants_sampled(gpu, oracle, name, B):
+    """The batch sizes bench.py times (not cut in time), checked on a sample of paths."""
+    import torch
+    cfg = workloads.CONFIGS[name]
+    x = workloads.make_paths(cfg, B=B, seed=98)
+    say("backward case %s-sat B=%d" % (name, B))
+    xt = torch.from_numpy(x).cuda()
+    out = gpu.signature(xt, cfg.depth, stream=cfg.stream)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(3)
+    gt = torch.randn(out.shape, dtype=torch.float32, device="cuda", generator=gen)
+    gx = torch.empty_like(xt)
+    assert gpu.sig_backward(gpu.default_ctx(), xt, cfg.depth, int(cfg.stream), out, gt, gx) == gpu.SIG_OK
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(6)
+    pick = np.sort(rng.choice(B, size=64, replace=False))
+    pick[0], pick[-1] = 0, B - 1
+    idx = torch.from_numpy(pick).cuda()
+    want = oracle.signature_backward(x[pick], cfg.depth, gt[idx].cpu().numpy(), stream=cfg.stream)
+    got = gx[idx].cpu().numpy()
+    err = np.linalg.norm(got - want) / np.linalg.norm(want)
+    say("  rel err %.2e" % err)
+    assert err <= TOL
