@@ -223,7 +223,8 @@ def training_step(workloads, B, L, d, depth, steps, warmup):
 
 
 def anchors(binding):
-    """Achievable rates on this GPU: a plain copy (HBM) and an fp32 FMA loop without packed instructions."""
+    """Achievable rates on this GPU: a plain copy, a plain fill and the stream kernels' write pattern (HBM), and an
+    fp32 FMA loop without packed instructions."""
     import torch
     n = 1 << 28  # 1 GiB each way
     src = torch.ones(n, dtype=torch.float32, device="cuda")
@@ -231,6 +232,9 @@ def anchors(binding):
     out = torch.empty(8192 * 64, dtype=torch.float32, device="cuda")
     res = {}
     for name, fn, work in [("copy_GBps", lambda: binding.sig_probe_copy(dst, src), 8.0 * n / 1e9),
+                           ("fill_GBps", lambda: binding.sig_probe_write(dst, 1), 4.0 * n / 1e9),
+                           ("write_4096_streams_GBps", lambda: binding.sig_probe_write(dst, 4096), 4.0 * n / 1e9),
+                           ("write_1024_streams_GBps", lambda: binding.sig_probe_write(dst, 1024), 4.0 * n / 1e9),
                            ("fma_TFLOPs", lambda: binding.sig_probe_fma(out, 8192, 20000),
                             2.0 * 16 * 20000 * 8192 * 64 / 1e12)]:
         for _ in range(3):

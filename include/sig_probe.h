@@ -1,9 +1,10 @@
 /*
- * sig_probe.h -- two measurement anchors that ship with libsig.  They are not part of the
+ * sig_probe.h -- measurement anchors that ship with libsig.  They are not part of the
  * signature transform; callers are benchmarks and profiling runs that need (a) a copy kernel
  * of known size, to calibrate the HBM byte counters and to measure the achievable HBM rate, and
  * (b) an FMA loop of known flop count, to measure the achievable fp32 vector rate without packed
- * instructions (every translation unit of this library is built with packed fp32 switched off).
+ * instructions (every translation unit of this library is built with packed fp32 switched off), and
+ * (c) write-only kernels, plain and with the access pattern of the stream-mode kernels.
  * Same conventions as sig.h: DEVICE pointers, hipStream_t passed as void*, status codes of enum
  * sig_status, nothing synchronises.
  */
@@ -27,6 +28,16 @@ int sig_probe_copy(float *dst, const float *src, int64_t n_floats, void *hip_str
  * Flops = 2 * 16 * iters * waves * 64.
  */
 int sig_probe_fma(float *out, int64_t waves, int64_t iters, int ilp, int lds_bytes, void *hip_stream);
+
+/*
+ * Write-only anchors for the stream-mode kernels, whose traffic is almost all stores.
+ * streams == 1: a plain fill, dst[i] = 1 for n_floats floats, the grid sweeping memory front to back.
+ * streams  > 1: `streams` sequential write cursors advancing together, one wavefront per cursor (the pattern of
+ *   a stream-mode launch: every path's rows are a region of its own): dst is cut into `streams` equal regions of
+ *   n_floats / streams floats (a multiple of 4), each written front to back by its own wavefront.
+ * dst: DEVICE, 16-byte aligned, n_floats % (4 * streams) == 0.  Writes 4 * n_floats bytes.
+ */
+int sig_probe_write(float *dst, int64_t n_floats, int64_t streams, void *hip_stream);
 
 #ifdef __cplusplus
 }

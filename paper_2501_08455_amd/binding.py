@@ -82,6 +82,8 @@ def load():
     lib.sig_backward_available.argtypes = [i32, i32]
     lib.sig_probe_copy.restype = i32
     lib.sig_probe_copy.argtypes = [vp, vp, i64, vp]
+    lib.sig_probe_write.restype = i32
+    lib.sig_probe_write.argtypes = [vp, i64, i64, vp]
     lib.sig_probe_fma.restype = i32
     lib.sig_probe_fma.argtypes = [vp, i64, i64, i32, i32, vp]
     lib.sig_strerror.restype = ctypes.c_char_p
@@ -211,6 +213,12 @@ def sig_probe_copy(dst, src, stream=None):
     """Copy kernel of include/sig_probe.h on two equally sized float32 CUDA tensors."""
     return load().sig_probe_copy(ctypes.c_void_p(dst.data_ptr()), ctypes.c_void_p(src.data_ptr()),
                                  src.numel(), _stream_handle(stream))
+
+
+def sig_probe_write(dst, streams=1, stream=None):
+    """Write-only kernel of include/sig_probe.h over the float32 CUDA tensor `dst` (plain fill, or `streams`
+    sequential write cursors)."""
+    return load().sig_probe_write(ctypes.c_void_p(dst.data_ptr()), dst.numel(), int(streams), _stream_handle(stream))
 
 
 def sig_probe_fma(out, waves, iters, ilp=16, lds_bytes=0, stream=None):

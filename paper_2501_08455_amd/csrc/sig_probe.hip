@@ -1,14 +1,47 @@
-// Measurement anchors declared in include/sig_probe.h: a plain copy and an fp32 FMA loop.
+// Measurement anchors declared in include/sig_probe.h: a plain copy, write-only kernels and an fp32 FMA loop.
 #include "sig_internal.h"
 #include "sig_probe.h"
 
 namespace {
 
+// every workgroup copies one contiguous 16 KB piece (four vectors per thread, all four loads in flight together)
 __global__ __launch_bounds__(256) void sig_probe_copy_kernel(float4 *dst, const float4 *src, int64_t n4)
 {
-    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (; i < n4; i += stride) dst[i] = src[i];
+    const int64_t base = (int64_t)blockIdx.x * 1024 + threadIdx.x;
+    float4 v[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int64_t i = base + j * 256;
+        if (i < n4) v[j] = src[i];
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int64_t i = base + j * 256;
+        if (i < n4) dst[i] = v[j];
+    }
+}
+
+// every workgroup writes one contiguous 16 KB piece (four vectors per thread, 4 KB apart), pieces in grid order
+__global__ __launch_bounds__(256) void sig_probe_fill_kernel(float4 *dst, int64_t n4)
+{
+    const int64_t base = (int64_t)blockIdx.x * 1024 + threadIdx.x;
+    const float4 one = {1.0f, 1.0f, 1.0f, 1.0f};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int64_t i = base + j * 256;
+        if (i < n4) dst[i] = one;
+    }
+}
+
+// one wavefront per region of region4 vectors, written front to back 1 KB at a time
+__global__ __launch_bounds__(256) void sig_probe_streams_kernel(float4 *dst, int64_t region4, int64_t streams)
+{
+    const int64_t wave = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / 64;
+    const int lane = threadIdx.x & 63;
+    if (wave >= streams) return;
+    float4 *base = dst + wave * region4;
+    const float4 one = {1.0f, 1.0f, 1.0f, 1.0f};
+    for (int64_t i = lane; i < region4; i += 64) base[i] = one;
 }
 
 extern __shared__ float sig_probe_smem[];
@@ -43,10 +76,30 @@ int sig_probe_copy(float *dst, const float *src, int64_t n_floats, void *hip_str
     if (!dst || !src || n_floats < 0 || n_floats % 4 || ((uintptr_t)dst & 15) || ((uintptr_t)src & 15)) return SIG_ERR_INVALID;
     if (n_floats == 0) return SIG_OK;
     const int64_t n4 = n_floats / 4;
-    int64_t blocks = (n4 + 255) / 256;
-    if (blocks > 256 * 32) blocks = 256 * 32;
+    const int64_t blocks = (n4 + 1023) / 1024;
+    if (blocks > INT32_MAX) return SIG_ERR_TOO_LARGE;
     hipLaunchKernelGGL(sig_probe_copy_kernel, dim3((unsigned)blocks), dim3(256), 0, static_cast<hipStream_t>(hip_stream),
                        reinterpret_cast<float4 *>(dst), reinterpret_cast<const float4 *>(src), n4);
+    return hipGetLastError() == hipSuccess ? SIG_OK : SIG_ERR_HIP;
+}
+
+int sig_probe_write(float *dst, int64_t n_floats, int64_t streams, void *hip_stream)
+{
+    if (!dst || n_floats < 0 || streams < 1 || ((uintptr_t)dst & 15) || n_floats % (4 * streams)) return SIG_ERR_INVALID;
+    if (n_floats == 0) return SIG_OK;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (streams == 1) {
+        const int64_t n4 = n_floats / 4;
+        const int64_t blocks = (n4 + 1023) / 1024;
+        if (blocks > INT32_MAX) return SIG_ERR_TOO_LARGE;
+        hipLaunchKernelGGL(sig_probe_fill_kernel, dim3((unsigned)blocks), dim3(256), 0, st,
+                           reinterpret_cast<float4 *>(dst), n4);
+    } else {
+        const int64_t blocks = (streams + 3) / 4;
+        if (blocks > INT32_MAX) return SIG_ERR_TOO_LARGE;
+        hipLaunchKernelGGL(sig_probe_streams_kernel, dim3((unsigned)blocks), dim3(256), 0, st,
+                           reinterpret_cast<float4 *>(dst), n_floats / 4 / streams, streams);
+    }
     return hipGetLastError() == hipSuccess ? SIG_OK : SIG_ERR_HIP;
 }
 
