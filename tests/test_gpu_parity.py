@@ -264,3 +264,23 @@ def test_saturated_variants_sampled(gpu, oracle, name, B):
     errs = level_errors(got, want, cfg.d, cfg.depth)
     say("  per-level rel err: " + " ".join("%.2e" % e for e in errs))
     assert max(errs) <= TOL
+
+
+# ---------------------------------------------------------------- long paths and very large batches
+@pytest.mark.parametrize("B,L,d,depth,stream", [(3, 50000, 5, 4, False), (2, 20000, 4, 4, True),
+                                                (1, 100000, 2, 3, False), (5, 3000, 10, 3, False)])
+def test_long_paths(gpu, oracle, B, L, d, depth, stream):
+    x = workloads.brownian_paths(B, L, d, seed=300 + L)
+    check(gpu, oracle, x, depth, stream, label="long path")
+
+
+def test_very_large_batch_sampled(gpu, oracle):
+    import torch
+    B, L, d, depth = 1 << 21, 3, 2, 3
+    x = workloads.brownian_paths(B, L, d, seed=17)
+    out = gpu.signature(torch.from_numpy(x).cuda(), depth)
+    torch.cuda.synchronize()
+    pick = np.array([0, 1, 255, 256, 65535, 65536, B // 2, B - 2, B - 1])
+    got = out[torch.from_numpy(pick).cuda()].cpu().numpy()
+    want = oracle.signature(x[pick], depth)
+    assert max(level_errors(got, want, d, depth)) <= TOL
