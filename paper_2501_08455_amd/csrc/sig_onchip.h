@@ -345,7 +345,11 @@ __device__ __forceinline__ void lds_tree_reduce(float *&src, float *&dst, int G,
 //   c[u_{1:n}] = a[u_{1:n}] + b[u_{1:n}] + sum_{i=1}^{n-1} a[u_{1:i}] b[u_{i+1:n}].
 // The b-factors are suffix words: runs of d^r consecutive floats at lane-dependent offsets.  Levels go from
 // N down to 1 so that the result can replace the left factor in place.
-template <int d, int N, int P>
+// BATCH: every run of b is read into registers in one go and only then used (a scheduling fence keeps the loads
+// together).  That costs about a dozen registers; it pays in the join kernel, which runs one workgroup per path
+// with nothing else to hide the LDS latency (the compiler's own order waits once per handful of reads), and
+// loses in the fold kernels, where the registers are worth a wavefront of occupancy.
+template <int d, int N, int P, bool BATCH = false>
 __device__ __forceinline__ void reg_product(Lane<d, N, P> &ln, const float *b, unsigned u)
 {
     using Sh = Shape<d, N, P>;
@@ -362,15 +366,22 @@ __device__ __forceinline__ void reg_product(Lane<d, N, P> &ln, const float *b, u
         constexpr int n = P + r;
         constexpr int cnt = cpow(d, r);
         float acc[cnt];
+        float tmp[cnt];
         const float *bn = b + Sh::row_off(n) + u * cnt;
 #pragma unroll
-        for (int v = 0; v < cnt; ++v) acc[v] = ln.s[Sh::sub_off(r) + v] + bn[v];
+        for (int v = 0; v < cnt; ++v) tmp[v] = bn[v];
+        if constexpr (BATCH) __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int v = 0; v < cnt; ++v) acc[v] = ln.s[Sh::sub_off(r) + v] + tmp[v];
         // a-factors that are prefixes of u: b-factor (u_{i+1:P}, v) is a run of cnt floats of level n - i
         static_for<1, P + 1>([&](auto ic) __attribute__((always_inline)) {
             constexpr int i = decltype(ic)::value;
             const float *bs = b + Sh::row_off(n - i) + (u % (unsigned)cpow(d, P - i)) * cnt;
 #pragma unroll
-            for (int v = 0; v < cnt; ++v) acc[v] = fmaf(apre[i - 1], bs[v], acc[v]);
+            for (int v = 0; v < cnt; ++v) tmp[v] = bs[v];
+            if constexpr (BATCH) __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int v = 0; v < cnt; ++v) acc[v] = fmaf(apre[i - 1], tmp[v], acc[v]);
         });
         // a-factors inside the sub-tree: a[u v_{1:j}] times b[v_{j+1:r}]
         static_for<1, r>([&](auto jc) __attribute__((always_inline)) {
@@ -1298,7 +1309,7 @@ __global__ __launch_bounds__(256) void sig_join_reg_kernel(const float *partial,
         const unsigned u = (unsigned)tid;
         Lane<d, N, P> ln;
         load_state<d, N, P>(rows, u, ln);
-        for (int w = 1; w < W; ++w) reg_product<d, N, P>(ln, rows + w * D, u);
+        for (int w = 1; w < W; ++w) reg_product<d, N, P, true>(ln, rows + w * D, u);
         store_state<d, N, P>(out + b * D, u, ln);
     }
 }
