@@ -56,7 +56,13 @@ enum sig_variant {
     /* state lives in registers: each lane owns the words below one prefix of length `prefix_depth`
      * and runs the fused multiply-by-exponential of Eq. 3 over its time chunk; chunks of one path
      * are joined by Eq. 4 products; only for the compiled (d, depth, prefix_depth) combinations */
-    SIG_VARIANT_ON_CHIP = 2
+    SIG_VARIANT_ON_CHIP = 2,
+    /* the level-by-level formulation of the paper's Section 2.2 (Eqs. 6-10): one launch per level, each a
+     * cumulative sum over time of per-step terms built from the lower levels of every prefix; those live in the
+     * output rows (stream mode) or in context scratch of B * (L-1) * (D - d^depth) floats (final mode).
+     * d <= 10, depth <= 8.  Never chosen by sig_plan: it exists to measure the paper's own design against the
+     * fused fold on the same chip.  Plan fields used: chunks (time chunks per word and launch; 0 = chosen per level) */
+    SIG_VARIANT_LEVEL_SCAN = 3
 };
 
 /*

@@ -21,6 +21,7 @@ SIG_ERR_UNSUPPORTED = 6
 SIG_VARIANT_AUTO = 0
 SIG_VARIANT_HBM_STREAMING = 1
 SIG_VARIANT_ON_CHIP = 2
+SIG_VARIANT_LEVEL_SCAN = 3
 
 
 class sig_plan_t(ctypes.Structure):

@@ -358,6 +358,18 @@ int plan_auto(const sig_ctx *ctx, int64_t B, int64_t L, int stream_flag, const R
     return SIG_OK;
 }
 
+// the level-scan family takes chunks >= 0 and ignores the other mapping fields
+int check_level_scan(int64_t B, int64_t L, const RowShape &rs, int stream_flag, const sig_plan_t &pl)
+{
+    if (!level_scan_available(rs.d, rs.depth)) return SIG_ERR_INVALID;
+    if (pl.chunks < 0) return SIG_ERR_INVALID;
+    // rows of the scratch tensor are addressed with 64-bit offsets; the launch grid must fit 31 bits
+    if (B * rs.pow[rs.depth - 1] > INT32_MAX) return SIG_ERR_TOO_LARGE;
+    const int64_t floats = level_scan_scratch_floats(B, L, rs, stream_flag);
+    if (floats < 0 || floats > (int64_t)1 << 36) return SIG_ERR_TOO_LARGE;
+    return SIG_OK;
+}
+
 int ensure_scratch(sig_ctx *ctx, size_t bytes)
 {
     if (bytes <= ctx->scratch_bytes) return SIG_OK;
@@ -387,6 +399,17 @@ int run_plan(sig_ctx *ctx, const float *path, int64_t B, int64_t L, const RowSha
         if (B * rs.pow[pl.prefix_depth] > INT32_MAX) return SIG_ERR_TOO_LARGE;
         if (!streaming_fits(rs, pl.prefix_depth)) return SIG_ERR_INVALID;
         hipError_t e = launch_hbm_streaming(path, out, B, L, rs, pl.prefix_depth, stream_flag, pl.threads, st);
+        return e == hipSuccess ? SIG_OK : SIG_ERR_HIP;
+    }
+    if (pl.variant == SIG_VARIANT_LEVEL_SCAN) {
+        int rc = check_level_scan(B, L, rs, stream_flag, pl);
+        if (rc != SIG_OK) return rc;
+        const int64_t floats = level_scan_scratch_floats(B, L, rs, stream_flag);
+        if (floats > 0) {
+            rc = ensure_scratch(ctx, (size_t)floats * sizeof(float));
+            if (rc != SIG_OK) return rc;
+        }
+        hipError_t e = launch_level_scan(path, out, ctx->scratch, B, L, rs, stream_flag, pl.chunks, ctx->num_cu, st);
         return e == hipSuccess ? SIG_OK : SIG_ERR_HIP;
     }
     if (pl.variant != SIG_VARIANT_ON_CHIP) return SIG_ERR_INVALID;
@@ -485,6 +508,7 @@ int sig_plan_validate(int64_t B, int64_t L, int d, int depth, int stream_flag, c
         if (!streaming_fits(rs, plan->prefix_depth)) return SIG_ERR_INVALID;
         return SIG_OK;
     }
+    if (plan->variant == SIG_VARIANT_LEVEL_SCAN) return check_level_scan(B, L, rs, stream_flag, *plan);
     if (plan->variant != SIG_VARIANT_ON_CHIP) return SIG_ERR_INVALID;
     const OnChipKernelInfo *ki = find_on_chip(rs.d, rs.depth, plan->prefix_depth);
     OnChipArgs args{};
