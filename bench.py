@@ -103,6 +103,20 @@ def bench_config(binding, workloads, ctx, cfg, B, steps, warmup, plan=None, labe
                            "frac": ach / PEAK_HBM_GBS, "traffic": None,
                            "note": "bytes of the state-in-HBM design (8 B per coefficient and increment); the HBM "
                                    "counters read the same amount (profiles/sig_hbm_streaming_C5.md)"}
+    if plan is not None and plan.variant == binding.SIG_VARIANT_LEVEL_SCAN:
+        # the level-by-level design keeps the lower levels of every prefix in memory: per path and step it writes
+        # level n once (all levels in stream mode, all but the top one in final mode) and level n's launch reads
+        # the distinct coefficients of levels 1 .. n-1 once
+        d, N, K = cfg.d, cfg.depth, cfg.L - 1
+        reads = sum(d ** m for n in range(2, N + 1) for m in range(1, n))
+        writes = D if cfg.stream else D - d ** N
+        design_bytes = 4.0 * B * (K * (reads + writes) + cfg.L * d + (0 if cfg.stream else D))
+        ach = design_bytes / (ms_ev * 1e-3) / 1e9
+        res["roofline"] = {"bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                           "frac": ach / PEAK_HBM_GBS, "traffic": None,
+                           "note": "bytes of the level-by-level design of Section 2.2 (lower levels of every prefix "
+                                   "written once and read once per level above); the HBM counters read the same "
+                                   "amount (profiles/sig_level_scan.md)"}
     del xt, out
     return res
 
@@ -281,6 +295,8 @@ def main():
     ap.add_argument("--batch", type=int, default=0, help="override the batch size (batch-saturated variants)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--backward", action="store_true", help="time sig_backward on the named workload instead")
+    ap.add_argument("--level-scan", action="store_true",
+                    help="time the level-by-level kernel family (the paper's Section 2.2) instead of the planner's choice")
     ap.add_argument("--hbm-streaming", type=int, default=-1, metavar="P",
                     help="time the HBM-streaming kernel family with prefix depth P instead of the planner's choice")
     args = ap.parse_args()
@@ -301,15 +317,20 @@ def main():
     cfg = workloads.CONFIGS[args.workload]
     B = args.batch or cfg.B
     forced = None
+    forced_label = ""
     if args.hbm_streaming >= 0:
         forced = binding.make_plan(binding.SIG_VARIANT_HBM_STREAMING, prefix_depth=args.hbm_streaming)
+        forced_label = " (HBM-streaming family)"
+    if args.level_scan:
+        forced = binding.make_plan(binding.SIG_VARIANT_LEVEL_SCAN, chunks=0)
+        forced_label = " (level-scan family)"
     if args.backward:
         head = bench_backward(binding, workloads, ctx, cfg, B, args.steps, args.warmup)
         head["terms_per_s"] = None
         head["plan"] = None
     else:
         head = bench_config(binding, workloads, ctx, cfg, B, args.steps, args.warmup, plan=forced,
-                            label=" (HBM-streaming family)" if forced is not None else "")
+                            label=forced_label)
     line = {
         "metric": "signatures/sec at (B=%d, L=%d, d=%d, N=%d), %s" % (
             B, cfg.L, cfg.d, cfg.depth, "every prefix (stream)" if cfg.stream else "final signature"),
@@ -337,6 +358,13 @@ def main():
         hbm_plan = binding.make_plan(binding.SIG_VARIANT_HBM_STREAMING, prefix_depth=2)
         extras.append(bench_config(binding, workloads, ctx, c5, c5.B, 20, 5, plan=hbm_plan,
                                    label=" (HBM-streaming family)"))
+        # the paper's own level-by-level formulation (Section 2.2) as a kernel family, next to the fused fold above
+        ls_plan = binding.make_plan(binding.SIG_VARIANT_LEVEL_SCAN, chunks=0)
+        for name, B, steps, warm in [("C2", None, 500, 200), ("C4", None, 500, 200), ("C5", None, 50, 20),
+                                     ("C2", 65536, 10, 3), ("C4", 4096, 20, 5)]:
+            c = workloads.CONFIGS[name]
+            extras.append(bench_config(binding, workloads, ctx, c, B or c.B, steps, warm, plan=ls_plan,
+                                       label=" (level-scan family)"))
         # the gradient with respect to the path (reverse sweep) on the shapes it is compiled for
         for name, B, steps, warm in [("C2", None, 1000, 500), ("C4", None, 300, 200), ("C2", 65536, 30, 20),
                                      ("C4", 4096, 20, 10)]:

@@ -61,7 +61,8 @@ enum sig_variant {
      * cumulative sum over time of per-step terms built from the lower levels of every prefix; those live in the
      * output rows (stream mode) or in context scratch of B * (L-1) * (D - d^depth) floats (final mode).
      * d <= 10, depth <= 8.  Never chosen by sig_plan: it exists to measure the paper's own design against the
-     * fused fold on the same chip.  Plan fields used: chunks (time chunks per word and launch; 0 = chosen per level) */
+     * fused fold on the same chip.  Plan fields used: chunks (time chunks per word and launch, at most 64; 0 = chosen
+     * per level) */
     SIG_VARIANT_LEVEL_SCAN = 3
 };
 

@@ -363,8 +363,7 @@ int check_level_scan(int64_t B, int64_t L, const RowShape &rs, int stream_flag, 
 {
     if (!level_scan_available(rs.d, rs.depth)) return SIG_ERR_INVALID;
     if (pl.chunks < 0) return SIG_ERR_INVALID;
-    // rows of the scratch tensor are addressed with 64-bit offsets; the launch grid must fit 31 bits
-    if (B * rs.pow[rs.depth - 1] > INT32_MAX) return SIG_ERR_TOO_LARGE;
+    if (B * rs.pow[rs.depth - 1] > INT32_MAX || !level_scan_fits(L, rs, stream_flag)) return SIG_ERR_TOO_LARGE;
     const int64_t floats = level_scan_scratch_floats(B, L, rs, stream_flag);
     if (floats < 0 || floats > (int64_t)1 << 36) return SIG_ERR_TOO_LARGE;
     return SIG_OK;

@@ -43,9 +43,11 @@ hipError_t launch_combine_rows(const float *a, int64_t a_stride, const float *b,
 // ---------------------------------------------------------------- level-scan family (d <= 10, depth <= 8)
 // The level-by-level formulation of the paper's Section 2.2: one launch per level, each a cumulative sum over time
 // of per-step terms built from the lower levels of every prefix, which live in the output rows (stream mode) or
-// in `scratch` (final mode: level_scan_scratch_floats floats).
+// in `scratch` (final mode: level_scan_scratch_floats floats, one dense [B][L-1][d^m] tensor per level m < depth).
 bool level_scan_available(int d, int depth);
 int64_t level_scan_scratch_floats(int64_t B, int64_t L, const RowShape &rs, int stream_flag);
+// false if the rows of one path cannot be addressed with 32-bit offsets
+bool level_scan_fits(int64_t L, const RowShape &rs, int stream_flag);
 // time chunks of one (path, parent word) at `level`; forced > 0 overrides the choice (clamped to the path)
 int level_scan_chunks(int64_t B, int64_t L, const RowShape &rs, int level, int forced, int cus);
 hipError_t launch_level_scan(const float *path, float *out, float *scratch, int64_t B, int64_t L, const RowShape &rs,

@@ -9,9 +9,11 @@
 //     g_0 = 1,  g_m = S_m(i-1)[w_{1:m}] + g_{m-1} * dX_i[w_m] / (n-m+1)   (m = 1 .. n-1),   T_n(i)[w.a] = g_{n-1} * dX_i[a],
 // so a term costs n-1 loads of lower-level coefficients, n-1+d FMAs and touches no other word.  The lower levels
 // of every prefix must therefore be in memory (the intermediates of shape (B, L-1, d^m) the paper names as its
-// memory cost): in stream mode they are the output rows themselves, in final mode a scratch tensor.
+// memory cost): in stream mode they are the output rows themselves, in final mode one dense scratch tensor per
+// level, [B][L-1][d^m], as in the paper.
 //
-// Mapping.  Launch n computes level n from levels 1 .. n-1.  A lane owns one parent word w (its d children are
+// Mapping.  Level 1 is the running sum of the increments, which telescopes to X_{j+1} - X_0: one elementwise
+// launch.  Launch n >= 2 computes level n from levels 1 .. n-1.  A lane owns one parent word w (its d children are
 // adjacent floats of the level) and one time chunk; lanes of a wavefront take consecutive parents, so the loads of
 // S_{n-1}(i-1)[w] and the stores of S_n(i)[w.*] of a wavefront are contiguous.  The increments of the workgroup's
 // paths are differenced on the way into an LDS tile; a lane reads dX_i[.] (the same address across the lanes
@@ -31,38 +33,82 @@ namespace sig {
 namespace {
 
 constexpr int kLsThreads = 256;
-constexpr int kLsTileFloats = 4096;  // LDS floats of the increment tile of one workgroup
-constexpr int kLsBatch = 4;          // steps whose lower-level loads are in flight together
+constexpr int kLsTileFloats = 12288; // most LDS floats the increment tile of one workgroup may take
+constexpr int kLsBatch = 4;          // steps whose lower-level loads are in flight together (deeper did not measure faster)
+constexpr int kLsMaxChunks = 64;     // so that a tile of one batch pair per (path, chunk) always fits
 constexpr int kLsMaxD = 10;
 constexpr int kLsMaxLevel = 8;
 
 struct LevelScanArgs {
-    const float *path;   // [B][L][d]
-    const float *lo;     // levels 1 .. n-1 of prefix (b, j) at lo + (b * K + j) * lo_stride + off[m]
-    float *hi;           // level n of prefix (b, j) goes to hi + (b * K + j) * hi_stride + off_n; null: not stored
-    float *fin;          // level n of the whole path goes to fin + b * fin_stride + off_n; null: not stored
-    int64_t lo_stride, hi_stride, fin_stride;
+    const float *path;               // [B][L][d]
+    const float *lo[kLsMaxLevel];    // lo[m], m = 1 .. n-1: level m of prefix (b, j) at lo[m] + (b * K + j) * lo_stride[m]
+    int32_t lo_stride[kLsMaxLevel];  // K * lo_stride[m] fits 31 bits (checked by the host)
+    float *hi;                       // level n of prefix (b, j) goes to hi + (b * K + j) * hi_stride; null: not stored
+    float *fin;                      // level n of the whole path goes to fin + b * fin_stride; null: not stored
+    int64_t hi_stride, fin_stride;
     int64_t B, L;
-    int32_t off[kLsMaxLevel + 1];  // off[m] = d + ... + d^{m-1}, m = 1 .. n
     int32_t parents;     // P = d^{n-1}
     int32_t pw;          // parents per workgroup
     int32_t wblocks;     // ceil(P / pw)
     int32_t chunks;      // C
     int32_t groups;      // G paths per workgroup; G * C * pw <= blockDim.x
     int32_t chunk_steps; // T = ceil(K / C)
-    int32_t tile_steps;  // TT <= T; G * C * TT * d <= kLsTileFloats
+    int32_t tile_steps;  // TT <= T; a tile holds TT rounded up to whole batches of steps, G * C * that * d <= kLsTileFloats
+    int32_t sub_shift;   // the loader gives 2^sub_shift adjacent threads to one (path, chunk) stretch of a tile
 };
 
-template <int d, int n>
+struct No { static constexpr bool value = false; };   // compile-time switches of the sweep
+struct Yes { static constexpr bool value = true; };
+
+// VEC floats per store instruction (the host picks the widest the alignment of the rows allows)
+template <int d, int VEC>
+__device__ __forceinline__ void store_children(float *dst, const float (&acc)[d])
+{
+    static_assert(d % VEC == 0, "store width must divide the number of children");
+    if constexpr (VEC == 4) {
+#pragma unroll
+        for (int q = 0; q < d / 4; ++q)
+            *reinterpret_cast<float4 *>(dst + 4 * q) = make_float4(acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]);
+    } else if constexpr (VEC == 2) {
+#pragma unroll
+        for (int q = 0; q < d / 2; ++q) *reinterpret_cast<float2 *>(dst + 2 * q) = make_float2(acc[2 * q], acc[2 * q + 1]);
+    } else {
+#pragma unroll
+        for (int a = 0; a < d; ++a) dst[a] = acc[a];
+    }
+}
+
+// Level 1: S_1(j) = X_{j+1} - X_0, one thread per float of the level.
+__global__ __launch_bounds__(kLsThreads) void sig_level_one_kernel(const float *path, float *hi, int64_t hi_stride,
+                                                                   float *fin, int64_t fin_stride, int64_t B,
+                                                                   int64_t L, int d)
+{
+    const int64_t K = L - 1;
+    const int64_t per_path = K * d;
+    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= B * per_path) return;
+    const int64_t b = e / per_path;
+    const int64_t r = e - b * per_path;
+    const int64_t j = r / d;
+    const int a = (int)(r - j * d);
+    const float *x = path + b * L * d;
+    const float v = x[d + r] - x[a];
+    if (hi) hi[(b * K + j) * hi_stride + a] = v;
+    if (fin && j == K - 1) fin[b * fin_stride + a] = v;
+}
+
+template <int d, int n, int VEC>
 __global__ __launch_bounds__(kLsThreads) void sig_level_scan_kernel(LevelScanArgs A)
 {
+    static_assert(n >= 2, "level 1 has its own kernel");
     constexpr int M = n - 1;  // lower levels on the chain
     extern __shared__ float ls_smem[];
-    float *tile = ls_smem;                  // [G][C][TT][d]
-    float *tot = ls_smem + kLsTileFloats;   // [G][C][pw][d], used when C > 1
-
     const int tid = threadIdx.x;
     const int PW = A.pw, C = A.chunks, G = A.groups, T = A.chunk_steps, TT = A.tile_steps;
+    const int TP = (TT + 2 * kLsBatch - 1) / (2 * kLsBatch) * (2 * kLsBatch);  // stretch of a tile, whole batches
+    float *tile = ls_smem;                        // [G * C][TP * d]
+    float *tot = ls_smem + G * C * TP * d;        // [G][C][pw][d], used when C > 1
+
     const int64_t K = A.L - 1;
     const int wl = tid % PW;
     const int c = (tid / PW) % C;
@@ -72,130 +118,141 @@ __global__ __launch_bounds__(kLsThreads) void sig_level_scan_kernel(LevelScanArg
     const int w = (int)(blockIdx.x % A.wblocks) * PW + wl;
     const bool lane_ok = g < G && b < A.B && w < A.parents;
 
-    // prefixes of the parent word: idx[m] = w_{1:m} as a number in base d, let[m] = w_m
-    int ofs[M > 0 ? M : 1], let[M > 0 ? M : 1];
-    float rc[M > 0 ? M : 1];
+    // Addresses are a workgroup-uniform base plus a 32-bit lane offset (the host checks that the rows of the
+    // workgroup's paths stay below 2^30 floats and the strides below 2^24, so offsets are one 24-bit multiply-add).
+    // prefixes of the parent word: w_{1:m} as a number in base d addresses level m; let[m-1] = w_m
+    const int K32 = (int)K;
+    const float *base[M];
+    uint32_t lane_off[M];
+    int stride[M], let[M];
+    float rc[M];
     {
         int rest = lane_ok ? w : 0;
 #pragma unroll
         for (int m = M; m >= 1; --m) {
-            ofs[m - 1] = A.off[m] + rest;
+            stride[m - 1] = A.lo_stride[m];
+            base[m - 1] = A.lo[m] + b0 * K * A.lo_stride[m];
+            lane_off[m - 1] = (uint32_t)(lane_ok ? g : 0) * (uint32_t)(K32 * A.lo_stride[m]) + (uint32_t)rest;
             let[m - 1] = rest % d;
             rest /= d;
             rc[m - 1] = 1.0f / (float)(n - m + 1);
         }
     }
-    const int64_t j_begin = (int64_t)c * T;
-    const int64_t j_end = (j_begin + T < K) ? j_begin + T : K;   // may be <= j_begin for trailing chunks
-    const float *lo_path = A.lo + (lane_ok ? b : 0) * K * A.lo_stride;
-    float *hi_path = A.hi ? A.hi + (lane_ok ? b : 0) * K * A.hi_stride + A.off[n] + (int64_t)w * d : nullptr;
-    const float *my_tile = tile + (size_t)((g < G ? g : 0) * C + c) * TT * d;
+    const int j_begin = c * T;
+    const int j_end = (j_begin + T < K32) ? j_begin + T : K32;   // may be <= j_begin for trailing chunks
+    const int hi_stride = (int)A.hi_stride;
+    float *hi_base = A.hi ? A.hi + b0 * K * A.hi_stride : nullptr;
+    const uint32_t hi_off = (uint32_t)(lane_ok ? g : 0) * (uint32_t)(K32 * hi_stride) + (uint32_t)(lane_ok ? w : 0) * d;
+    const float *my_tile = tile + (size_t)((g < G ? g : 0) * C + c) * TP * d;
     const int tiles = (T + TT - 1) / TT;
 
     float acc[d];
 #pragma unroll
     for (int a = 0; a < d; ++a) acc[a] = 0.0f;
 
-    // differenced increments of tile i of every (path, chunk) of the workgroup; zero past the end of a chunk
+    // differenced increments of tile i: the stretch of every (path, chunk) of the workgroup is a straight run of
+    // the path, taken by 2^sub_shift adjacent threads; the rest of the stretch (past the end of a chunk, and the
+    // padding up to a whole number of batches) is zero
     auto load_tile = [&](int i) {
-        const int total = G * C * TT * d;
-        for (int e = tid; e < total; e += blockDim.x) {
-            const int a = e % d;
-            const int t = (e / d) % TT;
-            const int gc = e / (d * TT);
-            const int cc = gc % C;
-            const int64_t bb = b0 + gc / C;
-            const int64_t j = (int64_t)cc * T + (int64_t)i * TT + t;
-            const int64_t jend = ((int64_t)(cc + 1) * T < K) ? (int64_t)(cc + 1) * T : K;
-            float v = 0.0f;
-            if (bb < A.B && j < jend && (int64_t)i * TT + t < T) {
-                const float *x = A.path + (bb * A.L + j) * d + a;
-                v = x[d] - x[0];
-            }
-            tile[e] = v;
+        const int sub = tid >> A.sub_shift, lane_in = tid & ((1 << A.sub_shift) - 1);
+        const int per_pass = blockDim.x >> A.sub_shift;
+        for (int pair = sub; pair < G * C; pair += per_pass) {
+            const int cc = pair % C;
+            const int64_t bb = b0 + pair / C;
+            const int64_t j0 = (int64_t)cc * T + (int64_t)i * TT;
+            int64_t jend = (int64_t)(cc + 1) * T;
+            if (jend > K) jend = K;
+            int64_t steps = jend - j0;
+            if (steps > TT) steps = TT;
+            const int len = (bb < A.B && steps > 0) ? (int)steps * d : 0;
+            const float *x = A.path + (bb < A.B ? (bb * A.L + j0) * d : 0);
+            float *dst = tile + (size_t)pair * TP * d;
+            for (int e = lane_in; e < TP * d; e += 1 << A.sub_shift) dst[e] = e < len ? x[e + d] - x[e] : 0.0f;
         }
     };
 
-    // lower-level coefficients of the prefix before step j (zero before the first step)
-    auto fetch = [&](int64_t j, bool on, float (&s)[M > 0 ? M : 1]) {
-        const bool rd = on && j > 0;
-        const float *row = lo_path + (rd ? j - 1 : 0) * A.lo_stride;
+    // Lower-level coefficients of the prefix before step jt + t.  Always loaded, from a row clamped into the path, so
+    // that no load sits in a divergent branch (the wait counters then let a batch stay in flight behind the one
+    // being consumed); steps outside the chunk are masked when the values are used.
+    const int last_row = K32 >= 2 ? K32 - 2 : 0;
+    auto fetch = [&](int jt, int t, float (&s)[M]) {
+        int jj = jt + t - 1;
+        jj = jj < 0 ? 0 : jj;
+        jj = jj > last_row ? last_row : jj;
 #pragma unroll
-        for (int m = 0; m < M; ++m) s[m] = rd ? row[ofs[m]] : 0.0f;
+        for (int m = 0; m < M; ++m) s[m] = base[m][lane_off[m] + __umul24((uint32_t)jj, (uint32_t)stride[m])];
+    };
+    // n_on: steps of this tile that belong to the lane's chunk; `first` is set when the tile starts at the first
+    // step of the path, whose prefix is the empty path (all lower levels zero).  A step outside the chunk adds
+    // nothing; when levels are stored it stores the unchanged sum once more over the row of the chunk's last step, so
+    // that every step issues the same memory operations and the wait counters stay exact.
+    const bool has_work = lane_ok && j_begin < j_end;
+    auto step = [&](int jt, int t, int n_on, bool first, const float (&s)[M], auto emit_c) {
+        const float *dx = my_tile + t * d;
+        float h = 1.0f;
+#pragma unroll
+        for (int m = 0; m < M; ++m) h = fmaf(h, dx[let[m]] * rc[m], first ? 0.0f : s[m]);
+        h = t < n_on ? h : 0.0f;
+#pragma unroll
+        for (int a = 0; a < d; ++a) acc[a] = fmaf(h, dx[a], acc[a]);
+        if constexpr (decltype(emit_c)::value) {
+            int row = jt + t;
+            row = row < j_end ? row : j_end - 1;
+            store_children<d, VEC>(hi_base + (hi_off + __umul24((uint32_t)row, (uint32_t)hi_stride)), acc);
+        }
     };
 
-    auto sweep = [&](bool emit, bool reload) {
+    auto sweep = [&](auto emit_c, bool reload) {
         for (int i = 0; i < tiles; ++i) {
             if (reload) {
                 __syncthreads();   // the previous tile has been consumed
                 load_tile(i);
                 __syncthreads();
             }
-            const int64_t jt = j_begin + (int64_t)i * TT;
-            float cur[kLsBatch][M > 0 ? M : 1], nxt[kLsBatch][M > 0 ? M : 1];
+            if (!has_work) continue;
+            const int jt = j_begin + i * TT;
+            int n_on = j_end - jt;
+            n_on = n_on > TT ? TT : n_on;
+            float ping[kLsBatch][M], pong[kLsBatch][M];
 #pragma unroll
-            for (int u = 0; u < kLsBatch; ++u) fetch(jt + u, lane_ok && jt + u < j_end && u < TT, cur[u]);
-            for (int t0 = 0; t0 < TT; t0 += kLsBatch) {
+            for (int u = 0; u < kLsBatch; ++u) fetch(jt, u, ping[u]);
+            for (int t0 = 0; t0 < TP; t0 += 2 * kLsBatch) {
 #pragma unroll
-                for (int u = 0; u < kLsBatch; ++u) {
-                    const int t = t0 + kLsBatch + u;
-                    fetch(jt + t, lane_ok && t < TT && jt + t < j_end, nxt[u]);
-                }
+                for (int u = 0; u < kLsBatch; ++u) fetch(jt, t0 + kLsBatch + u, pong[u]);
 #pragma unroll
-                for (int u = 0; u < kLsBatch; ++u) {
-                    const int t = t0 + u;
-                    const int64_t j = jt + t;
-                    const bool on = lane_ok && t < TT && j < j_end;
-                    if (on) {
-                        const float *dx = my_tile + t * d;
-                        float h = 1.0f;
+                for (int u = 0; u < kLsBatch; ++u) step(jt, t0 + u, n_on, u == 0 && jt + t0 == 0, ping[u], emit_c);
 #pragma unroll
-                        for (int m = 0; m < M; ++m) h = fmaf(h, dx[let[m]] * rc[m], cur[u][m]);
+                for (int u = 0; u < kLsBatch; ++u) fetch(jt, t0 + 2 * kLsBatch + u, ping[u]);
 #pragma unroll
-                        for (int a = 0; a < d; ++a) acc[a] = fmaf(h, dx[a], acc[a]);
-                        if (emit && hi_path) {
-                            float *dst = hi_path + j * A.hi_stride;
-#pragma unroll
-                            for (int a = 0; a < d; ++a) dst[a] = acc[a];
-                        }
-                    }
-                }
-#pragma unroll
-                for (int u = 0; u < kLsBatch; ++u)
-#pragma unroll
-                    for (int m = 0; m < M; ++m) cur[u][m] = nxt[u][m];
+                for (int u = 0; u < kLsBatch; ++u) step(jt, t0 + kLsBatch + u, n_on, false, pong[u], emit_c);
             }
         }
     };
-
     const bool one_tile = tiles == 1;
     if (one_tile) {
         load_tile(0);
         __syncthreads();
     }
     if (C > 1) {
-        sweep(false, !one_tile);
+        sweep(No{}, !one_tile);
         float *mine = tot + (size_t)tid * d;
         if (tid < G * C * PW) {
 #pragma unroll
             for (int a = 0; a < d; ++a) mine[a] = acc[a];
         }
         __syncthreads();
-        // exclusive prefix over the chunks of this (path, parent), earliest chunk first; the lane of the last
-        // chunk also needs nothing more than its own carry-in.  Without per-step stores the sum of all chunks is
-        // the result and chunk 0 writes it.
+        // Without per-step stores the sum of all chunks is the result and the lane of chunk 0 writes it; otherwise
+        // a lane starts its second pass from the sum of the chunks before its own, earliest first.
         if (!A.hi) {
             if (lane_ok && c == 0 && A.fin) {
 #pragma unroll
                 for (int a = 0; a < d; ++a) acc[a] = 0.0f;
                 for (int cc = 0; cc < C; ++cc) {
-                    const float *src = tot + (size_t)((g * C + cc) * PW + wl) * d;
+                    const float *part = tot + (size_t)((g * C + cc) * PW + wl) * d;
 #pragma unroll
-                    for (int a = 0; a < d; ++a) acc[a] += src[a];
+                    for (int a = 0; a < d; ++a) acc[a] += part[a];
                 }
-                float *dst = A.fin + b * A.fin_stride + A.off[n] + (int64_t)w * d;
-#pragma unroll
-                for (int a = 0; a < d; ++a) dst[a] = acc[a];
+                store_children<d, VEC>(A.fin + b * A.fin_stride + (int64_t)w * d, acc);
             }
             return;
         }
@@ -203,57 +260,58 @@ __global__ __launch_bounds__(kLsThreads) void sig_level_scan_kernel(LevelScanArg
         for (int a = 0; a < d; ++a) acc[a] = 0.0f;
         if (lane_ok) {
             for (int cc = 0; cc < c; ++cc) {
-                const float *src = tot + (size_t)((g * C + cc) * PW + wl) * d;
+                const float *part = tot + (size_t)((g * C + cc) * PW + wl) * d;
 #pragma unroll
-                for (int a = 0; a < d; ++a) acc[a] += src[a];
+                for (int a = 0; a < d; ++a) acc[a] += part[a];
             }
         }
     }
-    sweep(true, !one_tile);
+    if (A.hi) sweep(Yes{}, !one_tile);
+    else sweep(No{}, !one_tile);
     // the chunk that holds the last step also holds the level of the whole path
-    if (lane_ok && A.fin && j_begin < K && j_end == K) {
-        float *dst = A.fin + b * A.fin_stride + A.off[n] + (int64_t)w * d;
-#pragma unroll
-        for (int a = 0; a < d; ++a) dst[a] = acc[a];
-    }
+    if (lane_ok && A.fin && j_begin < K32 && j_end == K32)
+        store_children<d, VEC>(A.fin + b * A.fin_stride + (int64_t)w * d, acc);
 }
 
 template <int d, int n>
-hipError_t launch_one(const LevelScanArgs &A, int blocks, int threads, size_t lds, hipStream_t st)
+hipError_t launch_one(const LevelScanArgs &A, int vec, int blocks, int threads, size_t lds, hipStream_t st)
 {
-    hipLaunchKernelGGL((sig_level_scan_kernel<d, n>), dim3(blocks), dim3(threads), lds, st, A);
+    constexpr int kNatural = d % 4 == 0 ? 4 : (d % 2 == 0 ? 2 : 1);
+    if (kNatural > 1 && vec >= kNatural)
+        hipLaunchKernelGGL((sig_level_scan_kernel<d, n, kNatural>), dim3(blocks), dim3(threads), lds, st, A);
+    else
+        hipLaunchKernelGGL((sig_level_scan_kernel<d, n, 1>), dim3(blocks), dim3(threads), lds, st, A);
     return hipGetLastError();
 }
 
 template <int d>
-hipError_t launch_level(int n, const LevelScanArgs &A, int blocks, int threads, size_t lds, hipStream_t st)
+hipError_t launch_level(int n, const LevelScanArgs &A, int vec, int blocks, int threads, size_t lds, hipStream_t st)
 {
     switch (n) {
-    case 1: return launch_one<d, 1>(A, blocks, threads, lds, st);
-    case 2: return launch_one<d, 2>(A, blocks, threads, lds, st);
-    case 3: return launch_one<d, 3>(A, blocks, threads, lds, st);
-    case 4: return launch_one<d, 4>(A, blocks, threads, lds, st);
-    case 5: return launch_one<d, 5>(A, blocks, threads, lds, st);
-    case 6: return launch_one<d, 6>(A, blocks, threads, lds, st);
-    case 7: return launch_one<d, 7>(A, blocks, threads, lds, st);
-    case 8: return launch_one<d, 8>(A, blocks, threads, lds, st);
+    case 2: return launch_one<d, 2>(A, vec, blocks, threads, lds, st);
+    case 3: return launch_one<d, 3>(A, vec, blocks, threads, lds, st);
+    case 4: return launch_one<d, 4>(A, vec, blocks, threads, lds, st);
+    case 5: return launch_one<d, 5>(A, vec, blocks, threads, lds, st);
+    case 6: return launch_one<d, 6>(A, vec, blocks, threads, lds, st);
+    case 7: return launch_one<d, 7>(A, vec, blocks, threads, lds, st);
+    case 8: return launch_one<d, 8>(A, vec, blocks, threads, lds, st);
     default: return hipErrorInvalidValue;
     }
 }
 
-hipError_t launch_level_d(int d, int n, const LevelScanArgs &A, int blocks, int threads, size_t lds, hipStream_t st)
+hipError_t launch_level_d(int d, int n, const LevelScanArgs &A, int vec, int blocks, int threads, size_t lds, hipStream_t st)
 {
     switch (d) {
-    case 1: return launch_level<1>(n, A, blocks, threads, lds, st);
-    case 2: return launch_level<2>(n, A, blocks, threads, lds, st);
-    case 3: return launch_level<3>(n, A, blocks, threads, lds, st);
-    case 4: return launch_level<4>(n, A, blocks, threads, lds, st);
-    case 5: return launch_level<5>(n, A, blocks, threads, lds, st);
-    case 6: return launch_level<6>(n, A, blocks, threads, lds, st);
-    case 7: return launch_level<7>(n, A, blocks, threads, lds, st);
-    case 8: return launch_level<8>(n, A, blocks, threads, lds, st);
-    case 9: return launch_level<9>(n, A, blocks, threads, lds, st);
-    case 10: return launch_level<10>(n, A, blocks, threads, lds, st);
+    case 1: return launch_level<1>(n, A, vec, blocks, threads, lds, st);
+    case 2: return launch_level<2>(n, A, vec, blocks, threads, lds, st);
+    case 3: return launch_level<3>(n, A, vec, blocks, threads, lds, st);
+    case 4: return launch_level<4>(n, A, vec, blocks, threads, lds, st);
+    case 5: return launch_level<5>(n, A, vec, blocks, threads, lds, st);
+    case 6: return launch_level<6>(n, A, vec, blocks, threads, lds, st);
+    case 7: return launch_level<7>(n, A, vec, blocks, threads, lds, st);
+    case 8: return launch_level<8>(n, A, vec, blocks, threads, lds, st);
+    case 9: return launch_level<9>(n, A, vec, blocks, threads, lds, st);
+    case 10: return launch_level<10>(n, A, vec, blocks, threads, lds, st);
     default: return hipErrorInvalidValue;
     }
 }
@@ -263,6 +321,16 @@ int floor_pow2(int64_t v)
     int p = 1;
     while ((int64_t)p * 2 <= v) p *= 2;
     return p;
+}
+
+// widest vector store (floats) that base + k * stride keeps aligned for every k
+int store_width(const void *base, int64_t stride)
+{
+    if (!base) return 4;
+    const uintptr_t p = reinterpret_cast<uintptr_t>(base);
+    if (p % 16 == 0 && stride % 4 == 0) return 4;
+    if (p % 8 == 0 && stride % 2 == 0) return 2;
+    return 1;
 }
 
 }  // namespace
@@ -275,6 +343,14 @@ int64_t level_scan_scratch_floats(int64_t B, int64_t L, const RowShape &rs, int 
     return B * (L - 1) * (rs.D - rs.pow[rs.depth]);
 }
 
+bool level_scan_fits(int64_t L, const RowShape &rs, int stream_flag)
+{
+    // a lane addresses the rows of its workgroup's paths with 32-bit offsets built by 24-bit multiplies; when one
+    // path exceeds 2^22 floats a workgroup takes a single path (see launch_level_scan)
+    const int64_t widest = stream_flag ? rs.D : (rs.depth > 1 ? rs.pow[rs.depth - 1] : 1);
+    return L - 1 < (1 << 24) && widest < (1 << 24) && (L - 1) * widest < ((int64_t)1 << 30);
+}
+
 int level_scan_chunks(int64_t B, int64_t L, const RowShape &rs, int level, int forced, int cus)
 {
     const int64_t K = L - 1;
@@ -282,15 +358,14 @@ int level_scan_chunks(int64_t B, int64_t L, const RowShape &rs, int level, int f
     if (forced > 0) {
         C = forced;
     } else {
-        // enough lanes for four wavefronts on every SIMD, chunks of at least four steps
+        // enough lanes for four wavefronts on every SIMD, chunks of at least eight steps
         const int64_t want = (int64_t)cus * 4 * 4 * kWave;
         const int64_t items = B * rs.pow[level - 1];
         C = floor_pow2((want + items - 1) / items);
-        if (C > K / 4) C = K / 4;
-        if (C > 32) C = 32;
+        if (C > K / 8) C = floor_pow2(K / 8 > 0 ? K / 8 : 1);
     }
     if (C > K) C = K;
-    if (C > kLsThreads) C = kLsThreads;
+    if (C > kLsMaxChunks) C = kLsMaxChunks;
     if (C < 1) C = 1;
     return (int)C;
 }
@@ -298,35 +373,55 @@ int level_scan_chunks(int64_t B, int64_t L, const RowShape &rs, int level, int f
 hipError_t launch_level_scan(const float *path, float *out, float *scratch, int64_t B, int64_t L, const RowShape &rs,
                              int stream_flag, int forced_chunks, int cus, hipStream_t st)
 {
-    if (!level_scan_available(rs.d, rs.depth)) return hipErrorInvalidValue;
+    if (!level_scan_available(rs.d, rs.depth) || !level_scan_fits(L, rs, stream_flag)) return hipErrorInvalidValue;
     const int d = rs.d, N = rs.depth;
     const int64_t K = L - 1;
-    const int64_t lower = rs.D - rs.pow[N];  // row length of the scratch tensor (levels 1 .. N-1)
+    // where level m of every prefix lives: inside the output rows, or in the dense scratch tensor of the level
+    auto level_base = [&](int m) { return stream_flag ? out + rs.off[m] : scratch + B * K * rs.off[m]; };
+    auto level_stride = [&](int m) { return stream_flag ? rs.D : rs.pow[m]; };
     for (int n = 1; n <= N; ++n) {
+        float *hi = (stream_flag || n < N) ? level_base(n) : nullptr;
+        float *fin = stream_flag ? nullptr : out + rs.off[n];
+        const int64_t hi_stride = level_stride(n), fin_stride = rs.D;
+        if (n == 1) {
+            const int64_t total = B * K * d;
+            const int64_t blocks = (total + kLsThreads - 1) / kLsThreads;
+            if (blocks > INT32_MAX) return hipErrorInvalidValue;
+            hipLaunchKernelGGL(sig_level_one_kernel, dim3((unsigned)blocks), dim3(kLsThreads), 0, st, path, hi, hi_stride,
+                               fin, fin_stride, B, L, d);
+            hipError_t e = hipGetLastError();
+            if (e != hipSuccess) return e;
+            continue;
+        }
         LevelScanArgs A{};
         A.path = path;
         A.B = B;
         A.L = L;
-        if (stream_flag) {
-            A.lo = out;  A.lo_stride = rs.D;
-            A.hi = out;  A.hi_stride = rs.D;
-            A.fin = nullptr;  A.fin_stride = 0;
-        } else {
-            A.lo = scratch;  A.lo_stride = lower;
-            A.hi = n < N ? scratch : nullptr;  A.hi_stride = lower;
-            A.fin = out;  A.fin_stride = rs.D;
+        for (int m = 1; m < n; ++m) {
+            A.lo[m] = level_base(m);
+            A.lo_stride[m] = (int32_t)level_stride(m);
         }
-        for (int m = 1; m <= n; ++m) A.off[m] = (int32_t)rs.off[m];
+        A.hi = hi;
+        A.hi_stride = hi_stride;
+        A.fin = fin;
+        A.fin_stride = fin_stride;
+        const int vh = store_width(hi, hi_stride), vf = store_width(fin, fin_stride);
+        const int vec = vh < vf ? vh : vf;
         const int64_t P = rs.pow[n - 1];
         const int C = level_scan_chunks(B, L, rs, n, forced_chunks, cus);
         int64_t PW = kLsThreads / C;
         if (PW > P) PW = P;
         int64_t G = kLsThreads / (PW * C);
         if (G > B) G = B;
+        // 32-bit offsets inside the rows of a workgroup's paths
+        const int64_t widest = stream_flag ? rs.D : rs.pow[n < N ? n : n - 1];
+        while (G > 1 && G * K * widest >= ((int64_t)1 << 30)) --G;
         const int T = (int)((K + C - 1) / C);
-        int64_t TT = kLsTileFloats / (G * C * d);
+        constexpr int kPair = 2 * kLsBatch;
+        int64_t TT = kLsTileFloats / (G * C * d) / kPair * kPair;   // whole batch pairs
         if (TT > T) TT = T;
-        if (TT < 1) return hipErrorInvalidValue;  // cannot happen: G * C <= 256 and d <= 10
+        if (TT < 1) return hipErrorInvalidValue;  // cannot happen: G * C * d <= 640 (C <= 64, and PW = P >= d otherwise)
+        const int64_t TP = (TT + kPair - 1) / kPair * kPair;
         const int64_t wblocks = (P + PW - 1) / PW;
         const int64_t blocks = wblocks * ((B + G - 1) / G);
         if (blocks > INT32_MAX) return hipErrorInvalidValue;
@@ -337,10 +432,13 @@ hipError_t launch_level_scan(const float *path, float *out, float *scratch, int6
         A.groups = (int32_t)G;
         A.chunk_steps = T;
         A.tile_steps = (int32_t)TT;
+        int shift = 0;
+        while (shift < 6 && (1 << shift) < TP * d) ++shift;
+        A.sub_shift = shift;
         const int used = (int)(G * C * PW);
         const int threads = (used + kWave - 1) / kWave * kWave;
-        const size_t lds = (size_t)(kLsTileFloats + (C > 1 ? threads * d : 0)) * sizeof(float);
-        hipError_t e = launch_level_d(d, n, A, (int)blocks, threads, lds, st);
+        const size_t lds = (size_t)(G * C * TP * d + (C > 1 ? threads * d : 0)) * sizeof(float);
+        hipError_t e = launch_level_d(d, n, A, vec, (int)blocks, threads, lds, st);
         if (e != hipSuccess) return e;
     }
     return hipSuccess;

@@ -129,3 +129,24 @@ def test_planner_keeps_the_shape_grid_on_chip():
                     assert rc == binding.SIG_OK, (d, depth, B, L, stream)
                     assert pl.variant == binding.SIG_VARIANT_ON_CHIP, (d, depth, B, L, stream, pl.as_dict())
                     assert binding.sig_plan_validate(B, L, d, depth, stream, pl) == binding.SIG_OK
+
+
+def test_level_scan_plans_are_checked_on_the_host():
+    """The level-by-level family (Section 2.2) takes d <= 10, depth <= 8, chunks >= 0 and rows that 32-bit lane
+    offsets can address; the planner itself never chooses it."""
+    ls = binding.SIG_VARIANT_LEVEL_SCAN
+    mk = binding.make_plan
+    for stream in (0, 1):
+        assert binding.sig_plan_validate(128, 100, 5, 4, stream, mk(ls, chunks=0)) == binding.SIG_OK
+        assert binding.sig_plan_validate(16, 128, 10, 6, stream, mk(ls, chunks=7)) == binding.SIG_OK
+        assert binding.sig_plan_validate(4, 16, 1, 8, stream, mk(ls, chunks=1000)) == binding.SIG_OK
+        assert binding.sig_plan_validate(4, 16, 11, 2, stream, mk(ls, chunks=0)) == binding.SIG_ERR_INVALID
+        assert binding.sig_plan_validate(4, 16, 2, 9, stream, mk(ls, chunks=0)) == binding.SIG_ERR_INVALID
+        assert binding.sig_plan_validate(4, 16, 2, 3, stream, mk(ls, chunks=-1)) == binding.SIG_ERR_INVALID
+    # one path's rows beyond 2^30 floats
+    assert binding.sig_plan_validate(1, 2000, 10, 6, 1, mk(ls, chunks=0)) == binding.SIG_ERR_TOO_LARGE
+    assert binding.sig_plan_validate(1, 20000, 10, 6, 0, mk(ls, chunks=0)) == binding.SIG_ERR_TOO_LARGE
+    for name in ("C1", "C2", "C3", "C4", "C5"):
+        cfg = workloads.CONFIGS[name]
+        rc, pl = binding.sig_plan(None, cfg.B, cfg.L, cfg.d, cfg.depth, int(cfg.stream))
+        assert rc == binding.SIG_OK and pl.variant != ls
