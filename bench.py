@@ -116,7 +116,7 @@ def bench_config(binding, workloads, ctx, cfg, B, steps, warmup, plan=None, labe
                            "frac": ach / PEAK_HBM_GBS, "traffic": None,
                            "note": "bytes of the level-by-level design of Section 2.2 (lower levels of every prefix "
                                    "written once and read once per level above); the HBM counters read the same "
-                                   "amount (profiles/sig_level_scan.md)"}
+                                   "amount (profiles/sig_level_scan_*.md)"}
     del xt, out
     return res
 
@@ -366,8 +366,8 @@ def main():
             extras.append(bench_config(binding, workloads, ctx, c, B or c.B, steps, warm, plan=ls_plan,
                                        label=" (level-scan family)"))
         # the gradient with respect to the path (reverse sweep) on the shapes it is compiled for
-        for name, B, steps, warm in [("C2", None, 1000, 500), ("C4", None, 300, 200), ("C2", 65536, 30, 20),
-                                     ("C4", 4096, 20, 10)]:
+        for name, B, steps, warm in [("C2", None, 1000, 500), ("C4", None, 300, 200), ("C5", None, 30, 10),
+                                     ("C2", 65536, 30, 20), ("C4", 4096, 20, 10)]:
             c = workloads.CONFIGS[name]
             extras.append(bench_backward(binding, workloads, ctx, c, B or c.B, steps, warm))
         line["all_configs"] = extras

@@ -167,6 +167,8 @@ int sig_combine(sig_ctx *ctx, const float *a, const float *b, int64_t B, int d, 
  * Same conventions and status codes as sig_compute (B == 0 returns SIG_OK and launches nothing);
  * SIG_ERR_UNSUPPORTED when no gradient kernel is compiled
  * for (d, depth) (see sig_backward_available) or a path of L points does not fit the kernel's LDS staging.
+ * Shapes whose index space is cut into more sub-trees than one workgroup has threads keep per-workgroup sums in
+ * context scratch (B * ceil(d^p / 256) * (L-1) * d floats, allocated on first use): SIG_ERR_ALLOC if that fails.
  * Deterministic (fixed summation order).  Arithmetic is float32 with FMA.
  */
 int sig_backward(sig_ctx *ctx, const float *path, int64_t B, int64_t L, int d, int depth, int stream_flag,

@@ -564,8 +564,13 @@ int sig_backward(sig_ctx *ctx, const float *path, int64_t B, int64_t L, int d, i
     if (B == 0) return SIG_OK;
     if (!path || !out || !grad_out || !grad_path) return SIG_ERR_INVALID;
     if (!backward_available(d, depth) || !backward_fits(d, depth, L)) return SIG_ERR_UNSUPPORTED;
-    hipError_t e = launch_backward(path, out, grad_out, grad_path, B, L, d, depth, stream_flag, ctx->num_cu,
-                                   (hipStream_t)hip_stream);
+    const int64_t floats = backward_scratch_floats(d, depth, B, L);
+    if (floats > 0) {
+        rc = ensure_scratch(ctx, (size_t)floats * sizeof(float));
+        if (rc != SIG_OK) return rc;
+    }
+    hipError_t e = launch_backward(path, out, grad_out, grad_path, floats > 0 ? ctx->scratch : nullptr, B, L, d, depth,
+                                   stream_flag, ctx->num_cu, (hipStream_t)hip_stream);
     return e == hipSuccess ? SIG_OK : SIG_ERR_HIP;
 }
 

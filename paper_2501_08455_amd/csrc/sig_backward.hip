@@ -610,6 +610,178 @@ __global__ __launch_bounds__(256) void sig_backward_chunked_kernel(BackwardArgs 
     }
 }
 
+// ---------------------------------------------------------------------------------------------------------
+// Sliced sweep: shapes whose d^P lanes per path exceed one workgroup.  A workgroup takes one path and one slice
+// of up to 256 of its lanes; nothing crosses lanes in the sweep itself, only d(loss)/dv of a step is a sum over
+// all lanes of the path.  Each slice adds up its own lanes (parked partial sums, two-stage column sums in a
+// fixed order) over the increment the sum belongs to, writes its K * d partial sums to `part`, and a second
+// launch adds the slices in order and forms d(loss)/dX.
+constexpr int kSliceLanes = 256;
+constexpr int kSliceSplit = 8;   // a parked column is summed in this many stretches of lanes first
+
+template <int d>
+constexpr int slice_reduce_steps()
+{
+    const int fit = 8192 / (kSliceLanes * d);   // parked sums take TS * 256 * d floats of LDS
+    return fit < 1 ? 1 : (fit > 8 ? 8 : fit);
+}
+
+template <int d, int N, int P, bool STREAM>
+__global__ __launch_bounds__(kSliceLanes) void sig_backward_sliced_kernel(BackwardArgs A, float *part)
+{
+    using Sh = Shape<d, N, P>;
+    constexpr int Q = Sh::Q;
+    constexpr int D = Sh::D;
+    constexpr int TS = slice_reduce_steps<d>();
+    constexpr int slices = (Q + kSliceLanes - 1) / kSliceLanes;
+    const int tid = threadIdx.x, nthr = blockDim.x;
+    const int64_t K = A.L - 1;
+    const int slice = (int)(blockIdx.x % slices);
+    const int64_t b = blockIdx.x / slices;
+    const unsigned u_raw = (unsigned)(slice * kSliceLanes + tid);
+    const bool active = u_raw < (unsigned)Q;
+    const unsigned u = active ? u_raw : 0u;
+    const int lanes = Q - slice * kSliceLanes < kSliceLanes ? Q - slice * kSliceLanes : kSliceLanes;
+
+    int letter[P > 0 ? P : 1];
+    letter[0] = 0;
+    {
+        unsigned rest = u;
+#pragma unroll
+        for (int m = P - 1; m >= 0; --m) { letter[m] = (int)(rest % d); rest /= d; }
+    }
+
+    // LDS: increments [K*d] (overwritten with this slice's sums), parked partial sums [TS][256][d], stretch sums
+    const int row_floats = (int)K * d;
+    float *tile = sig_backward_smem;
+    float *park = tile + (row_floats + 3) / 4 * 4;
+    float *red = park + TS * kSliceLanes * d;
+    {
+        const float *x = A.path + b * A.L * d;
+        for (int i = tid; i < row_floats; i += nthr) tile[i] = x[i + d] - x[i];
+    }
+
+    Lane<d, N, P> ln, ad;
+    identity_state<d, N, P>(ln);
+    identity_state<d, N, P>(ad);
+    if (P == 0) ad.s[0] = 0.0f;
+    if (active) {
+        const float *srow = STREAM ? A.sig + (b * K + (K - 1)) * D : A.sig + b * D;
+        load_state<d, N, P>(srow, u, ln);
+        if constexpr (!STREAM) load_adjoint<d, N, P, false>(A.grad_out + b * D, u, ad);
+    }
+    __syncthreads();
+
+    Lane<d, N, P> up;   // upstream gradient of the row the sweep reaches next (stream mode), fetched one step ahead
+    if constexpr (STREAM) {
+        identity_state<d, N, P>(up);
+        if (P == 0) up.s[0] = 0.0f;
+        if (active) load_adjoint<d, N, P, false>(A.grad_out + (b * K + (K - 1)) * D, u, up);
+    }
+    for (int64_t k = K - 1; k >= 0; --k) {
+        const int ts = (int)((K - 1 - k) % TS);
+        if constexpr (STREAM) {
+#pragma unroll
+            for (int i = 0; i < Sh::SZ; ++i) ad.s[i] += up.s[i];
+#pragma unroll
+            for (int i = 0; i < Sh::NPRE; ++i) ad.pre[i] += up.pre[i];
+            if (active && k > 0) load_adjoint<d, N, P, false>(A.grad_out + (b * K + (k - 1)) * D, u, up);
+        }
+        Inc<d, P> inc, neg;
+        load_inc<d, P>(inc, tile + k * d, letter);
+#pragma unroll
+        for (int a = 0; a < d; ++a) neg.v[a] = -inc.v[a];
+        neg.du[0] = 0.0f;
+#pragma unroll
+        for (int m = 0; m < P; ++m) neg.du[m] = -inc.du[m];
+        if (k > 0) fused_step<d, N, P>(ln, neg);  // S_{k-1} = S_k (x) exp(-dX_k)
+        else identity_state<d, N, P>(ln);
+        float dbar[d];
+        backward_step<d, N, P>(ln, ad, inc, letter, dbar);
+#pragma unroll
+        for (int a = 0; a < d; ++a) park[(ts * kSliceLanes + tid) * d + a] = active ? dbar[a] : 0.0f;
+        if (ts == TS - 1 || k == 0) {
+            __syncthreads();
+            // column c = (parked step t, channel a), first in kSliceSplit stretches of lanes, then the stretches
+            const int cols = (ts + 1) * d;
+            constexpr int stretch = kSliceLanes / kSliceSplit;
+            for (int w = tid; w < cols * kSliceSplit; w += nthr) {
+                const int c = w / kSliceSplit, r = w - c * kSliceSplit;
+                const int t = c / d, a = c - t * d;
+                float sum = 0.0f;
+                const int q_end = (r + 1) * stretch < lanes ? (r + 1) * stretch : lanes;
+                for (int q = r * stretch; q < q_end; ++q) sum += park[(t * kSliceLanes + q) * d + a];
+                red[w] = sum;
+            }
+            __syncthreads();
+            for (int c = tid; c < cols; c += nthr) {
+                const int t = c / d, a = c - t * d;
+                float sum = 0.0f;
+#pragma unroll
+                for (int r = 0; r < kSliceSplit; ++r) sum += red[c * kSliceSplit + r];
+                tile[(k + (ts - t)) * d + a] = sum;   // replaces the increment, which no lane reads again
+            }
+            __syncthreads();
+        }
+    }
+    float *dst = part + (b * slices + slice) * row_floats;
+    for (int i = tid; i < row_floats; i += nthr) dst[i] = tile[i];
+}
+
+// d(loss)/dX_j = sum over the slices, in order, of (d/d(dX_{j-1}) - d/d(dX_j))
+__global__ __launch_bounds__(256) void sig_backward_slices_finish_kernel(const float *part, float *grad_path, int64_t B,
+                                                                         int64_t L, int d, int slices)
+{
+    const int64_t out_row = L * d, row_floats = (L - 1) * d;
+    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= B * out_row) return;
+    const int64_t b = e / out_row, r = e - b * out_row;
+    float sum = 0.0f;
+    for (int s = 0; s < slices; ++s) {
+        const float *t = part + (b * slices + s) * row_floats;
+        const float before = r >= d ? t[r - d] : 0.0f;
+        const float after = r < row_floats ? t[r] : 0.0f;
+        sum += before - after;
+    }
+    grad_path[e] = sum;
+}
+
+template <int d, int N, int P>
+int64_t backward_sliced_lds_bytes(int64_t L, int)
+{
+    constexpr int TS = slice_reduce_steps<d>();
+    const int64_t tile = ((L - 1) * d + 3) / 4 * 4;
+    return (tile + (int64_t)TS * kSliceLanes * d + (int64_t)TS * d * kSliceSplit) * (int64_t)sizeof(float);
+}
+
+template <int d, int N, int P>
+int64_t backward_sliced_scratch_floats(int64_t B, int64_t L)
+{
+    constexpr int slices = (Shape<d, N, P>::Q + kSliceLanes - 1) / kSliceLanes;
+    return B * slices * (L - 1) * d;
+}
+
+template <int d, int N, int P>
+hipError_t backward_sliced_launch(const BackwardArgs &A, float *scratch, int, int, hipStream_t st)
+{
+    constexpr int slices = (Shape<d, N, P>::Q + kSliceLanes - 1) / kSliceLanes;
+    const int64_t lds = backward_sliced_lds_bytes<d, N, P>(A.L, 1);
+    const int64_t grid = A.B * slices;
+    if (!scratch || lds > kMaxLdsBytes || grid <= 0 || grid > INT32_MAX) return hipErrorInvalidValue;
+    if (A.stream_flag)
+        hipLaunchKernelGGL((sig_backward_sliced_kernel<d, N, P, true>), dim3((unsigned)grid), dim3(kSliceLanes), (size_t)lds, st, A, scratch);
+    else
+        hipLaunchKernelGGL((sig_backward_sliced_kernel<d, N, P, false>), dim3((unsigned)grid), dim3(kSliceLanes), (size_t)lds, st, A, scratch);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const int64_t total = A.B * A.L * d;
+    const int64_t blocks = (total + 255) / 256;
+    if (blocks > INT32_MAX) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(sig_backward_slices_finish_kernel, dim3((unsigned)blocks), dim3(256), 0, st, (const float *)scratch,
+                       A.grad_path, A.B, A.L, d, slices);
+    return hipGetLastError();
+}
+
 template <int d, int N, int P>
 int64_t backward_chunked_lds_bytes(int64_t L, int chunks, int stream_flag)
 {
@@ -628,7 +800,10 @@ int64_t backward_lds_bytes(int64_t L, int groups)
 }
 
 template <int d, int N, int P>
-hipError_t backward_launch(const BackwardArgs &A0, int threads, int cus, hipStream_t st)
+int64_t backward_no_scratch(int64_t, int64_t) { return 0; }
+
+template <int d, int N, int P>
+hipError_t backward_launch(const BackwardArgs &A0, float *, int threads, int cus, hipStream_t st)
 {
     constexpr int Q = Shape<d, N, P>::Q;
     if (threads < Q || threads > 256 || threads % kWave) return hipErrorInvalidValue;
@@ -673,11 +848,17 @@ hipError_t backward_launch(const BackwardArgs &A0, int threads, int cus, hipStre
 namespace {
 struct BackwardEntry {
     int d, depth;
-    hipError_t (*launch)(const onchip::BackwardArgs &, int, int, hipStream_t);
+    hipError_t (*launch)(const onchip::BackwardArgs &, float *, int, int, hipStream_t);
     int64_t (*lds_bytes)(int64_t, int);
+    int64_t (*scratch_floats)(int64_t, int64_t);
 };
-#define SIG_BACKWARD_ENTRY(d, N, P) {d, N, &onchip::backward_launch<d, N, P>, &onchip::backward_lds_bytes<d, N, P>}
-// one prefix depth per (d, depth): the one whose two lane states (S and its adjoint) fit the registers
+#define SIG_BACKWARD_ENTRY(d, N, P) \
+    {d, N, &onchip::backward_launch<d, N, P>, &onchip::backward_lds_bytes<d, N, P>, &onchip::backward_no_scratch<d, N, P>}
+#define SIG_BACKWARD_SLICED(d, N, P)                                                                  \
+    {d, N, &onchip::backward_sliced_launch<d, N, P>, &onchip::backward_sliced_lds_bytes<d, N, P>, \
+     &onchip::backward_sliced_scratch_floats<d, N, P>}
+// one prefix depth per (d, depth): the one whose two lane states (S and its adjoint) fit the registers; shapes
+// whose lanes per path exceed a workgroup take the sliced sweep
 const BackwardEntry kBackward[] = {
     SIG_BACKWARD_ENTRY(2, 2, 1), SIG_BACKWARD_ENTRY(3, 2, 1), SIG_BACKWARD_ENTRY(4, 2, 1), SIG_BACKWARD_ENTRY(5, 2, 1),
     SIG_BACKWARD_ENTRY(6, 2, 1), SIG_BACKWARD_ENTRY(8, 2, 1), SIG_BACKWARD_ENTRY(10, 2, 1),
@@ -687,7 +868,9 @@ const BackwardEntry kBackward[] = {
     SIG_BACKWARD_ENTRY(6, 4, 2), SIG_BACKWARD_ENTRY(7, 4, 2),
     SIG_BACKWARD_ENTRY(2, 5, 1), SIG_BACKWARD_ENTRY(3, 5, 2), SIG_BACKWARD_ENTRY(4, 5, 3), SIG_BACKWARD_ENTRY(5, 5, 3),
     SIG_BACKWARD_ENTRY(2, 6, 1), SIG_BACKWARD_ENTRY(3, 6, 3),
-    {0, 0, nullptr, nullptr},
+    SIG_BACKWARD_SLICED(8, 4, 3), SIG_BACKWARD_SLICED(10, 4, 3), SIG_BACKWARD_SLICED(6, 5, 3), SIG_BACKWARD_SLICED(4, 6, 4),
+    SIG_BACKWARD_SLICED(5, 6, 4), SIG_BACKWARD_SLICED(10, 6, 4),
+    {0, 0, nullptr, nullptr, nullptr},
 };
 const BackwardEntry *find_backward(int d, int depth)
 {
@@ -705,8 +888,14 @@ bool backward_fits(int d, int depth, int64_t L)
     return e && e->lds_bytes(L, 1) <= kMaxLdsBytes;
 }
 
-hipError_t launch_backward(const float *path, const float *sig, const float *grad_out, float *grad_path, int64_t B,
-                           int64_t L, int d, int depth, int stream_flag, int cus, hipStream_t st)
+int64_t backward_scratch_floats(int d, int depth, int64_t B, int64_t L)
+{
+    const BackwardEntry *e = find_backward(d, depth);
+    return e ? e->scratch_floats(B, L) : 0;
+}
+
+hipError_t launch_backward(const float *path, const float *sig, const float *grad_out, float *grad_path, float *scratch,
+                           int64_t B, int64_t L, int d, int depth, int stream_flag, int cus, hipStream_t st)
 {
     const BackwardEntry *e = find_backward(d, depth);
     if (!e) return hipErrorInvalidValue;
@@ -718,7 +907,7 @@ hipError_t launch_backward(const float *path, const float *sig, const float *gra
     A.B = B;
     A.L = L;
     A.stream_flag = stream_flag;
-    return e->launch(A, 256, cus, st);
+    return e->launch(A, scratch, 256, cus, st);
 }
 
 }  // namespace sig

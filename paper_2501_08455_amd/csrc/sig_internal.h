@@ -57,8 +57,10 @@ hipError_t launch_level_scan(const float *path, float *out, float *scratch, int6
 bool backward_available(int d, int depth);
 // false if even one path per workgroup does not fit LDS (the increments of a whole path are staged at once)
 bool backward_fits(int d, int depth, int64_t L);
-hipError_t launch_backward(const float *path, const float *sig, const float *grad_out, float *grad_path, int64_t B,
-                           int64_t L, int d, int depth, int stream_flag, int cus, hipStream_t st);
+// device scratch the launch needs (shapes whose lanes per path span several workgroups keep per-slice sums), in floats
+int64_t backward_scratch_floats(int d, int depth, int64_t B, int64_t L);
+hipError_t launch_backward(const float *path, const float *sig, const float *grad_out, float *grad_path, float *scratch,
+                           int64_t B, int64_t L, int d, int depth, int stream_flag, int cus, hipStream_t st);
 
 // ---------------------------------------------------------------- on-chip family (compiled (d, depth, p) only)
 struct OnChipArgs {

@@ -150,3 +150,18 @@ def test_level_scan_plans_are_checked_on_the_host():
         cfg = workloads.CONFIGS[name]
         rc, pl = binding.sig_plan(None, cfg.B, cfg.L, cfg.d, cfg.depth, int(cfg.stream))
         assert rc == binding.SIG_OK and pl.variant != ls
+
+
+def test_every_compiled_forward_shape_has_a_gradient_kernel():
+    """sig_backward covers the (d, depth) grid of the on-chip forward kernels, the five configurations included."""
+    shapes = set()
+    for d in range(1, 11):
+        for depth in range(1, 7):
+            if any(binding.sig_on_chip_available(d, depth, p) for p in range(0, depth)):
+                shapes.add((d, depth))
+    assert len(shapes) >= 30
+    for name in ("C1", "C2", "C3", "C4", "C5"):
+        cfg = workloads.CONFIGS[name]
+        assert (cfg.d, cfg.depth) in shapes
+    missing = sorted(s for s in shapes if not binding.sig_backward_available(*s))
+    assert not missing, missing

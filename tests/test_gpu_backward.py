@@ -98,11 +98,41 @@ def test_backward_shape_grid(gpu, oracle, shape):
         check(gpu, oracle, x, depth, stream, seed=d + depth + L, label="grid")
 
 
+# shapes whose lanes per path exceed one workgroup (or whose parked sums would not fit): the sliced sweep
+SLICED_GRID = [(8, 4), (10, 4), (6, 5), (4, 6), (5, 6), (10, 6)]
+
+
+@pytest.mark.parametrize("shape", SLICED_GRID, ids=lambda c: "-".join(str(v) for v in c))
+def test_backward_sliced_shapes(gpu, oracle, shape):
+    d, depth = shape
+    assert gpu.sig_backward_available(d, depth) == 1
+    big = workloads.sig_size(d, depth) > 100000
+    cases = [(2, 9, False), (3, 4, False), (2, 6, True), (1, 2, False)] if big else \
+            [(3, 41, False), (40, 7, False), (4, 19, True), (2, 2, True)]
+    for B, L, stream in cases:
+        x = workloads.brownian_paths(B, L, d, seed=8100 + 13 * d + depth + B)
+        check(gpu, oracle, x, depth, stream, seed=d + depth + L, label="sliced")
+
+
+def test_backward_sliced_reproducible_and_after_a_larger_call(gpu, oracle):
+    """The per-slice sums live in context scratch: a smaller call after a larger one, and the same bits twice."""
+    x = workloads.brownian_paths(6, 30, 10, seed=77)
+    a = check(gpu, oracle, x, 4, False, seed=3, label="sliced, first")
+    check(gpu, oracle, x[:2, :9], 4, True, seed=4, label="sliced, smaller call")
+    b = check(gpu, oracle, x, 4, False, seed=3, label="sliced, again")
+    np.testing.assert_array_equal(a, b)
+
+
 def test_backward_on_the_configurations(gpu, oracle):
     for name in ["C1", "C2", "C4"]:
         cfg = workloads.CONFIGS[name]
         x = workloads.make_paths(cfg)
         check(gpu, oracle, x, cfg.depth, cfg.stream, seed=31, label=name)
+    # the large-signature configuration: its first path (the fp64 oracle keeps every prefix signature of a path,
+    # 2 GB each, and takes most of a minute for three)
+    cfg = workloads.CONFIGS["C5"]
+    x = workloads.make_paths(cfg)[:1]
+    check(gpu, oracle, x, cfg.depth, cfg.stream, seed=32, label="C5, first path")
 
 
 def test_backward_repeated_points_and_reproducible(gpu, oracle):
