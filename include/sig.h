@@ -164,17 +164,19 @@ int sig_combine(sig_ctx *ctx, const float *a, const float *b, int64_t B, int d, 
  *                read only (the sweep starts from the final signature and undoes one increment at a time)
  *   grad_out     DEVICE, float32, d(loss)/d(out), same shape as out, read only
  *   grad_path    DEVICE, float32 [B][L][d], fully overwritten; must not overlap the inputs
- * Same conventions and status codes as sig_compute (B == 0 returns SIG_OK and launches nothing);
- * SIG_ERR_UNSUPPORTED when no gradient kernel is compiled
- * for (d, depth) (see sig_backward_available) or a path of L points does not fit the kernel's LDS staging.
- * Shapes whose index space is cut into more sub-trees than one workgroup has threads keep per-workgroup sums in
- * context scratch (B * ceil(d^p / 256) * (L-1) * d floats, allocated on first use): SIG_ERR_ALLOC if that fails.
+ * Same conventions and status codes as sig_compute (B == 0 returns SIG_OK and launches nothing).  Shapes with a
+ * compiled register kernel (see sig_backward_available) whose paths fit its LDS staging take it; every other
+ * shape with d <= 256 takes a general sweep, one workgroup per path with its state in LDS or device scratch
+ * (much slower); SIG_ERR_UNSUPPORTED only for d > 256.
+ * Context scratch (allocated on first use, SIG_ERR_ALLOC if that fails): shapes whose index space is cut into more
+ * sub-trees than one workgroup has threads keep per-workgroup sums (B * ceil(d^p / 256) * (L-1) * d floats); the
+ * general sweep keeps B * (L-1) * d floats plus, when they exceed 48 KB per path, about 2.5 D floats per path.
  * Deterministic (fixed summation order).  Arithmetic is float32 with FMA.
  */
 int sig_backward(sig_ctx *ctx, const float *path, int64_t B, int64_t L, int d, int depth, int stream_flag,
                  const float *out, const float *grad_out, float *grad_path, void *hip_stream);
 
-/* 1 if sig_backward has a kernel for (d, depth), else 0.  Host only. */
+/* 1 if sig_backward has a compiled register kernel for (d, depth), 0 if it would take the general sweep.  Host only. */
 int sig_backward_available(int d, int depth);
 
 /* 1 if an on-chip kernel is compiled for (d, depth, prefix_depth), else 0.  Host only. */

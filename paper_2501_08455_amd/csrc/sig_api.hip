@@ -563,7 +563,17 @@ int sig_backward(sig_ctx *ctx, const float *path, int64_t B, int64_t L, int d, i
     if (rc != SIG_OK) return rc;
     if (B == 0) return SIG_OK;
     if (!path || !out || !grad_out || !grad_path) return SIG_ERR_INVALID;
-    if (!backward_available(d, depth) || !backward_fits(d, depth, L)) return SIG_ERR_UNSUPPORTED;
+    if (!backward_available(d, depth) || !backward_fits(d, depth, L)) {
+        // no register kernel for this shape, or the path is too long for its LDS staging: the general sweep
+        if (!backward_general_available(d) || B > INT32_MAX) return SIG_ERR_UNSUPPORTED;
+        const int64_t need = backward_general_scratch_floats(B, L, rs);
+        if (need <= 0 || need > (int64_t)1 << 36) return SIG_ERR_TOO_LARGE;
+        rc = ensure_scratch(ctx, (size_t)need * sizeof(float));
+        if (rc != SIG_OK) return rc;
+        hipError_t eg = launch_backward_general(path, out, grad_out, grad_path, ctx->scratch, B, L, rs, stream_flag,
+                                                (hipStream_t)hip_stream);
+        return eg == hipSuccess ? SIG_OK : SIG_ERR_HIP;
+    }
     const int64_t floats = backward_scratch_floats(d, depth, B, L);
     if (floats > 0) {
         rc = ensure_scratch(ctx, (size_t)floats * sizeof(float));

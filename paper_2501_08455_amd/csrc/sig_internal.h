@@ -62,6 +62,13 @@ int64_t backward_scratch_floats(int d, int depth, int64_t B, int64_t L);
 hipError_t launch_backward(const float *path, const float *sig, const float *grad_out, float *grad_path, float *scratch,
                            int64_t B, int64_t L, int d, int depth, int stream_flag, int cus, hipStream_t st);
 
+// ---------------------------------------------------------------- gradient, any (d <= 256, depth): one workgroup per path
+bool backward_general_available(int d);
+int64_t backward_general_scratch_floats(int64_t B, int64_t L, const RowShape &rs);
+hipError_t launch_backward_general(const float *path, const float *sig, const float *grad_out, float *grad_path,
+                                   float *scratch, int64_t B, int64_t L, const RowShape &rs, int stream_flag,
+                                   hipStream_t st);
+
 // ---------------------------------------------------------------- on-chip family (compiled (d, depth, p) only)
 struct OnChipArgs {
     const float *path;   // [B][L][d]

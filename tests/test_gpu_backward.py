@@ -123,6 +123,30 @@ def test_backward_sliced_reproducible_and_after_a_larger_call(gpu, oracle):
     np.testing.assert_array_equal(a, b)
 
 
+# shapes without a compiled register kernel: the general sweep (state of a path in LDS, or in device scratch for the
+# last three), one channel, depth 1, more channels than coefficients per level allow to vectorise, deep and narrow
+GENERAL_SHAPES = [(9, 2), (9, 3), (7, 5), (1, 5), (12, 1), (12, 3), (3, 8), (2, 10), (20, 2), (64, 2), (9, 4), (6, 6),
+                  (12, 4)]
+
+
+@pytest.mark.parametrize("shape", GENERAL_SHAPES, ids=lambda c: "-".join(str(v) for v in c))
+def test_backward_general_sweep(gpu, oracle, shape):
+    d, depth = shape
+    assert gpu.sig_backward_available(d, depth) == 0
+    for B, L, stream in [(3, 23, False), (17, 5, False), (2, 11, True), (2, 2, False), (1, 2, True)]:
+        x = workloads.brownian_paths(B, L, d, seed=8200 + 13 * d + depth + B)
+        check(gpu, oracle, x, depth, stream, seed=d + depth + L, label="general sweep")
+
+
+def test_backward_long_paths_take_the_general_sweep(gpu, oracle):
+    """Paths whose increments exceed the LDS staging of the register kernels (here 5,000 and 20,000 points in five
+    channels).  The sweep undoes one increment at a time in fp32, so its error grows with the length: measured
+    against the same 1e-4 gate."""
+    for B, L, stream in [(2, 5000, False), (1, 20000, False), (1, 4000, True)]:
+        x = workloads.brownian_paths(B, L, 5, seed=8300 + L)
+        check(gpu, oracle, x, 4, stream, seed=L, label="long path")
+
+
 def test_backward_on_the_configurations(gpu, oracle):
     for name in ["C1", "C2", "C4"]:
         cfg = workloads.CONFIGS[name]
@@ -148,13 +172,12 @@ def test_backward_status_codes(gpu):
     import torch
     ctx = gpu.default_ctx()
     assert gpu.sig_backward_available(5, 4) == 1 and gpu.sig_backward_available(9, 2) == 0
-    x = torch.zeros((2, 5, 9), device="cuda")
-    out = torch.zeros((2, gpu.sig_size(9, 2)), device="cuda")
+    x = torch.zeros((2, 5, 300), device="cuda")
+    out = torch.zeros((2, gpu.sig_size(300, 1)), device="cuda")
     gx = torch.zeros_like(x)
-    assert gpu.sig_backward(ctx, x, 2, 0, out, out, gx) == gpu.SIG_ERR_UNSUPPORTED  # no kernel for (9, 2)
-    x5 = torch.zeros((1, 20000, 5), device="cuda")  # one path's increments exceed the LDS staging
+    assert gpu.sig_backward(ctx, x, 1, 0, out, out, gx) == gpu.SIG_ERR_UNSUPPORTED  # more channels than a workgroup has threads
+    x5 = torch.zeros((1, 50, 5), device="cuda")
     o5 = torch.zeros((1, gpu.sig_size(5, 4)), device="cuda")
-    assert gpu.sig_backward(ctx, x5, 4, 0, o5, o5, torch.zeros_like(x5)) == gpu.SIG_ERR_UNSUPPORTED
     assert gpu.sig_backward(ctx, x5[:, :1].contiguous(), 4, 0, o5, o5, torch.zeros_like(x5)) == gpu.SIG_ERR_INVALID
     assert gpu.sig_backward(None, x5, 4, 0, o5, o5, torch.zeros_like(x5)) == gpu.SIG_ERR_INVALID
     empty = torch.zeros((0, 10, 5), device="cuda")
