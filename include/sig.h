@@ -51,7 +51,7 @@ enum sig_status {
 enum sig_variant {
     SIG_VARIANT_AUTO = 0,
     /* state of every path lives in HBM (in the output rows themselves) and is read-modified-written
-     * once per increment; any (d, depth); the fallback for shapes with no compiled on-chip kernel */
+     * once per increment; any (d, depth); the fallback for shapes that neither of the other families takes */
     SIG_VARIANT_HBM_STREAMING = 1,
     /* state lives in registers: each lane owns the words below one prefix of length `prefix_depth`
      * and runs the fused multiply-by-exponential of Eq. 3 over its time chunk; chunks of one path
@@ -60,8 +60,9 @@ enum sig_variant {
     /* the level-by-level formulation of the paper's Section 2.2 (Eqs. 6-10): one launch per level, each a
      * cumulative sum over time of per-step terms built from the lower levels of every prefix; those live in the
      * output rows (stream mode) or in context scratch of B * (L-1) * (D - d^depth) floats (final mode).
-     * d <= 10, depth <= 8.  Never chosen by sig_plan: it exists to measure the paper's own design against the
-     * fused fold on the same chip.  Plan fields used: chunks (time chunks per word and launch, at most 64; 0 = chosen
+     * d <= 10, depth <= 8.  Built to measure the paper's own design against the fused fold on the same chip (where a
+     * fused kernel is compiled, that one is several times faster); sig_plan chooses it for shapes without an on-chip
+     * kernel, where its parallelism in time beats the HBM-streaming sweep.  Plan fields used: chunks (time chunks per word and launch, at most 64; 0 = chosen
      * per level) */
     SIG_VARIANT_LEVEL_SCAN = 3
 };

@@ -71,10 +71,20 @@ def test_plan_of_the_five_configs_is_on_chip_and_consistent(name):
         assert pl.segments == 1
 
 
-def test_plan_falls_back_to_streaming_for_uncompiled_shapes():
-    rc, pl = binding.sig_plan(None, 7, 30, 9, 5, 0)
+def test_plan_falls_back_for_uncompiled_shapes():
+    """Without an on-chip kernel: the level-by-level family where it applies (d <= 10, depth <= 8, scratch below
+    8 GiB), else the HBM-streaming family."""
+    for stream in (0, 1):
+        rc, pl = binding.sig_plan(None, 7, 30, 9, 5, stream)
+        assert rc == binding.SIG_OK and pl.variant == binding.SIG_VARIANT_LEVEL_SCAN
+        assert binding.sig_plan_validate(7, 30, 9, 5, stream, pl) == binding.SIG_OK
+        rc, pl = binding.sig_plan(None, 7, 30, 12, 3, stream)      # more than 10 channels
+        assert rc == binding.SIG_OK and pl.variant == binding.SIG_VARIANT_HBM_STREAMING
+        assert 0 <= pl.prefix_depth <= 2
+        rc, pl = binding.sig_plan(None, 7, 30, 2, 9, stream)       # deeper than 8
+        assert rc == binding.SIG_OK and pl.variant == binding.SIG_VARIANT_HBM_STREAMING
+    rc, pl = binding.sig_plan(None, 4096, 1000, 9, 5, 0)           # lower levels of every prefix: 100 GB of scratch
     assert rc == binding.SIG_OK and pl.variant == binding.SIG_VARIANT_HBM_STREAMING
-    assert 0 <= pl.prefix_depth <= 4
 
 
 def test_large_batches_are_not_cut_in_time():
@@ -133,7 +143,7 @@ def test_planner_keeps_the_shape_grid_on_chip():
 
 def test_level_scan_plans_are_checked_on_the_host():
     """The level-by-level family (Section 2.2) takes d <= 10, depth <= 8, chunks >= 0 and rows that 32-bit lane
-    offsets can address; the planner itself never chooses it."""
+    offsets can address; the planner chooses it only for shapes without an on-chip kernel."""
     ls = binding.SIG_VARIANT_LEVEL_SCAN
     mk = binding.make_plan
     for stream in (0, 1):
@@ -149,7 +159,7 @@ def test_level_scan_plans_are_checked_on_the_host():
     for name in ("C1", "C2", "C3", "C4", "C5"):
         cfg = workloads.CONFIGS[name]
         rc, pl = binding.sig_plan(None, cfg.B, cfg.L, cfg.d, cfg.depth, int(cfg.stream))
-        assert rc == binding.SIG_OK and pl.variant != ls
+        assert rc == binding.SIG_OK and pl.variant == binding.SIG_VARIANT_ON_CHIP
 
 
 def test_every_compiled_forward_shape_has_a_gradient_kernel():
