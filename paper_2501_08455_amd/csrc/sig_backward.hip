@@ -870,6 +870,8 @@ const BackwardEntry kBackward[] = {
     SIG_BACKWARD_ENTRY(2, 6, 1), SIG_BACKWARD_ENTRY(3, 6, 3),
     SIG_BACKWARD_SLICED(8, 4, 3), SIG_BACKWARD_SLICED(10, 4, 3), SIG_BACKWARD_SLICED(6, 5, 3), SIG_BACKWARD_SLICED(4, 6, 4),
     SIG_BACKWARD_SLICED(5, 6, 4), SIG_BACKWARD_SLICED(10, 6, 4),
+    SIG_BACKWARD_ENTRY(7, 2, 1), SIG_BACKWARD_ENTRY(9, 2, 1), SIG_BACKWARD_ENTRY(9, 3, 2), SIG_BACKWARD_SLICED(9, 4, 3),
+    SIG_BACKWARD_SLICED(7, 5, 3), SIG_BACKWARD_SLICED(8, 5, 3), SIG_BACKWARD_SLICED(9, 5, 3), SIG_BACKWARD_SLICED(10, 5, 3),
     {0, 0, nullptr, nullptr, nullptr},
 };
 const BackwardEntry *find_backward(int d, int depth)

@@ -112,11 +112,12 @@ struct OnChipKernelInfo {
 // with an entry whose launch pointer is null, and on_chip_subtable(i) is null past the last sub-table.  Entries
 // of one (d, depth) are adjacent and ordered by increasing prefix depth.
 const OnChipKernelInfo *on_chip_subtable(int i);
-const OnChipKernelInfo *on_chip_table_base();      // sub-tables 0 .. 4, one translation unit each
+const OnChipKernelInfo *on_chip_table_base();      // sub-tables 0 .. 5, one translation unit each
 const OnChipKernelInfo *on_chip_table_depth2();
 const OnChipKernelInfo *on_chip_table_depth3();
 const OnChipKernelInfo *on_chip_table_depth4();
 const OnChipKernelInfo *on_chip_table_depth56();
+const OnChipKernelInfo *on_chip_table_odd();
 const OnChipKernelInfo *find_on_chip(int d, int depth, int p);
 
 }  // namespace sig

@@ -26,6 +26,7 @@ const OnChipKernelInfo *on_chip_subtable(int i)
     case 2: return on_chip_table_depth3();
     case 3: return on_chip_table_depth4();
     case 4: return on_chip_table_depth56();
+    case 5: return on_chip_table_odd();
     default: return nullptr;
     }
 }

@@ -75,15 +75,15 @@ def test_plan_falls_back_for_uncompiled_shapes():
     """Without an on-chip kernel: the level-by-level family where it applies (d <= 10, depth <= 8, scratch below
     8 GiB), else the HBM-streaming family."""
     for stream in (0, 1):
-        rc, pl = binding.sig_plan(None, 7, 30, 9, 5, stream)
+        rc, pl = binding.sig_plan(None, 7, 30, 9, 6, stream)
         assert rc == binding.SIG_OK and pl.variant == binding.SIG_VARIANT_LEVEL_SCAN
-        assert binding.sig_plan_validate(7, 30, 9, 5, stream, pl) == binding.SIG_OK
+        assert binding.sig_plan_validate(7, 30, 9, 6, stream, pl) == binding.SIG_OK
         rc, pl = binding.sig_plan(None, 7, 30, 12, 3, stream)      # more than 10 channels
         assert rc == binding.SIG_OK and pl.variant == binding.SIG_VARIANT_HBM_STREAMING
         assert 0 <= pl.prefix_depth <= 2
         rc, pl = binding.sig_plan(None, 7, 30, 2, 9, stream)       # deeper than 8
         assert rc == binding.SIG_OK and pl.variant == binding.SIG_VARIANT_HBM_STREAMING
-    rc, pl = binding.sig_plan(None, 4096, 1000, 9, 5, 0)           # lower levels of every prefix: 100 GB of scratch
+    rc, pl = binding.sig_plan(None, 512, 1000, 9, 6, 0)            # lower levels of every prefix: 136 GB of scratch
     assert rc == binding.SIG_OK and pl.variant == binding.SIG_VARIANT_HBM_STREAMING
 
 
@@ -114,7 +114,7 @@ def test_every_forced_plan_of_the_gpu_tests_is_accepted_by_the_host_checks():
 def test_plan_validate_rejects_plans_the_kernels_cannot_run():
     mk = binding.make_plan
     on = binding.SIG_VARIANT_ON_CHIP
-    assert binding.sig_plan_validate(4, 16, 9, 3, 0, mk(on, prefix_depth=1)) == binding.SIG_ERR_INVALID  # not compiled
+    assert binding.sig_plan_validate(4, 16, 9, 6, 0, mk(on, prefix_depth=1)) == binding.SIG_ERR_INVALID  # not compiled
     assert binding.sig_plan_validate(4, 16, 5, 4, 0, mk(on, prefix_depth=2, chunks=11)) == binding.SIG_ERR_INVALID
     assert binding.sig_plan_validate(4, 16, 5, 4, 1, mk(on, prefix_depth=2, segments=2)) == binding.SIG_ERR_INVALID
     assert binding.sig_plan_validate(4, 6, 5, 4, 0, mk(on, prefix_depth=2, chunks=3, segments=2)) == binding.SIG_ERR_INVALID
@@ -130,7 +130,8 @@ def test_planner_keeps_the_shape_grid_on_chip():
     paper's direct-computation tables (Section 4.1) and beyond; host only."""
     grid = [(2, 3), (4, 4), (5, 4), (10, 6), (2, 2), (3, 2), (4, 2), (5, 2), (6, 2), (8, 2), (10, 2), (3, 3), (4, 3),
             (5, 3), (6, 3), (7, 3), (8, 3), (10, 3), (2, 4), (3, 4), (6, 4), (7, 4), (8, 4), (10, 4), (2, 5), (3, 5),
-            (4, 5), (5, 5), (6, 5), (2, 6), (3, 6), (4, 6), (5, 6)]
+            (4, 5), (5, 5), (6, 5), (2, 6), (3, 6), (4, 6), (5, 6), (7, 2), (9, 2), (9, 3), (9, 4), (7, 5), (8, 5),
+            (9, 5), (10, 5)]
     for d, depth in grid:
         for B in (1, 7, 32, 128, 512, 4096, 65536):
             for L in (2, 9, 50, 200, 1000):

@@ -85,7 +85,7 @@ def test_backward_matches_oracle(gpu, oracle, case):
 
 BACKWARD_GRID = [(2, 2), (3, 2), (4, 2), (5, 2), (6, 2), (8, 2), (10, 2), (2, 3), (3, 3), (4, 3), (5, 3), (6, 3), (7, 3),
                  (8, 3), (10, 3), (2, 4), (3, 4), (4, 4), (5, 4), (6, 4), (7, 4), (2, 5), (3, 5), (4, 5), (5, 5),
-                 (2, 6), (3, 6)]
+                 (2, 6), (3, 6), (7, 2), (9, 2), (9, 3)]
 
 
 @pytest.mark.parametrize("shape", BACKWARD_GRID, ids=lambda c: "-".join(str(v) for v in c))
@@ -99,7 +99,7 @@ def test_backward_shape_grid(gpu, oracle, shape):
 
 
 # shapes whose lanes per path exceed one workgroup (or whose parked sums would not fit): the sliced sweep
-SLICED_GRID = [(8, 4), (10, 4), (6, 5), (4, 6), (5, 6), (10, 6)]
+SLICED_GRID = [(8, 4), (10, 4), (6, 5), (4, 6), (5, 6), (10, 6), (9, 4), (7, 5), (8, 5), (9, 5), (10, 5)]
 
 
 @pytest.mark.parametrize("shape", SLICED_GRID, ids=lambda c: "-".join(str(v) for v in c))
@@ -125,7 +125,7 @@ def test_backward_sliced_reproducible_and_after_a_larger_call(gpu, oracle):
 
 # shapes without a compiled register kernel: the general sweep (state of a path in LDS, or in device scratch for the
 # last three), one channel, depth 1, more channels than coefficients per level allow to vectorise, deep and narrow
-GENERAL_SHAPES = [(9, 2), (9, 3), (7, 5), (1, 5), (12, 1), (12, 3), (3, 8), (2, 10), (20, 2), (64, 2), (9, 4), (6, 6),
+GENERAL_SHAPES = [(11, 2), (11, 3), (7, 6), (1, 5), (12, 1), (12, 3), (3, 8), (2, 10), (20, 2), (64, 2), (3, 7), (6, 6),
                   (12, 4)]
 
 
@@ -171,7 +171,7 @@ def test_backward_repeated_points_and_reproducible(gpu, oracle):
 def test_backward_status_codes(gpu):
     import torch
     ctx = gpu.default_ctx()
-    assert gpu.sig_backward_available(5, 4) == 1 and gpu.sig_backward_available(9, 2) == 0
+    assert gpu.sig_backward_available(5, 4) == 1 and gpu.sig_backward_available(11, 2) == 0
     x = torch.zeros((2, 5, 300), device="cuda")
     out = torch.zeros((2, gpu.sig_size(300, 1)), device="cuda")
     gx = torch.zeros_like(x)
