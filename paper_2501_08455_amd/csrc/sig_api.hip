@@ -355,7 +355,7 @@ int plan_auto(const sig_ctx *ctx, int64_t B, int64_t L, int stream_flag, const R
     }
     // No on-chip kernel for this shape.  The level-by-level family is parallel in time and measured 2-25x faster
     // than the state-in-HBM sweep on every such shape (few paths above all), so it is the fallback wherever it
-    // applies (d <= 10, depth <= 8) and its scratch tensor stays below 8 GiB; the HBM-streaming family takes the rest.
+    // applies (d <= 256, depth <= 8) and its scratch tensor stays below 8 GiB; the HBM-streaming family takes the rest.
     if (B > 0) {
         sig_plan_t ls{};
         ls.variant = SIG_VARIANT_LEVEL_SCAN;

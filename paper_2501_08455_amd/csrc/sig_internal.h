@@ -40,7 +40,7 @@ hipError_t launch_combine_rows(const float *a, int64_t a_stride, const float *b,
                                float *out, int64_t out_stride, int64_t B, const RowShape &rs,
                                hipStream_t st);
 
-// ---------------------------------------------------------------- level-scan family (d <= 10, depth <= 8)
+// ---------------------------------------------------------------- level-scan family (d <= 256, depth <= 8)
 // The level-by-level formulation of the paper's Section 2.2: one launch per level, each a cumulative sum over time
 // of per-step terms built from the lower levels of every prefix, which live in the output rows (stream mode) or
 // in `scratch` (final mode: level_scan_scratch_floats floats, one dense [B][L-1][d^m] tensor per level m < depth).

@@ -36,7 +36,7 @@ constexpr int kLsThreads = 256;
 constexpr int kLsTileFloats = 12288; // most LDS floats the increment tile of one workgroup may take
 constexpr int kLsBatch = 4;          // steps whose lower-level loads are in flight together (deeper did not measure faster)
 constexpr int kLsMaxChunks = 64;     // so that a tile of one batch pair per (path, chunk) always fits
-constexpr int kLsMaxD = 10;
+constexpr int kLsMaxD = 256;         // up to 10 channels are template parameters, more are a run-time value
 constexpr int kLsMaxLevel = 8;
 
 struct LevelScanArgs {
@@ -47,9 +47,10 @@ struct LevelScanArgs {
     float *fin;                      // level n of the whole path goes to fin + b * fin_stride; null: not stored
     int64_t hi_stride, fin_stride;
     int64_t B, L;
-    int32_t parents;     // P = d^{n-1}
-    int32_t pw;          // parents per workgroup
-    int32_t wblocks;     // ceil(P / pw)
+    int32_t d;           // channels (the kernels for d <= 10 have it as a template parameter as well)
+    int32_t items;       // work items of one path: parent words P = d^{n-1}, times the blocks of children per parent
+    int32_t pw;          // items per workgroup and chunk
+    int32_t wblocks;     // ceil(items / pw)
     int32_t chunks;      // C
     int32_t groups;      // G paths per workgroup; G * C * pw <= blockDim.x
     int32_t chunk_steps; // T = ceil(K / C)
@@ -78,6 +79,18 @@ __device__ __forceinline__ void store_children(float *dst, const float (&acc)[d]
     }
 }
 
+// run-time d: a lane holds kWideBlock children starting at child `first`; children past the last one repeat it
+// (same value to the same address), so that every lane issues the same stores
+constexpr int kWideBlock = 4;
+__device__ __forceinline__ void store_block(float *parent_row, int first, int d, const float (&acc)[kWideBlock])
+{
+#pragma unroll
+    for (int a = 0; a < kWideBlock; ++a) {
+        const int ch = first + a < d ? first + a : d - 1;
+        parent_row[ch] = acc[a];
+    }
+}
+
 // Level 1: S_1(j) = X_{j+1} - X_0, one thread per float of the level.
 __global__ __launch_bounds__(kLsThreads) void sig_level_one_kernel(const float *path, float *hi, int64_t hi_stride,
                                                                    float *fin, int64_t fin_stride, int64_t B,
@@ -97,17 +110,22 @@ __global__ __launch_bounds__(kLsThreads) void sig_level_one_kernel(const float *
     if (fin && j == K - 1) fin[b * fin_stride + a] = v;
 }
 
-template <int d, int n, int VEC>
+// DT > 0: d = DT at compile time, a lane owns all d children of its parent word.  DT == 0: d at run time (more than
+// 10 channels), a lane owns a block of kWideBlock children, the lanes of one parent are adjacent and recompute its chain.
+template <int DT, int n, int VEC>
 __global__ __launch_bounds__(kLsThreads) void sig_level_scan_kernel(LevelScanArgs A)
 {
     static_assert(n >= 2, "level 1 has its own kernel");
     constexpr int M = n - 1;  // lower levels on the chain
+    constexpr int DB = DT > 0 ? DT : kWideBlock;             // children a lane owns
+    const int d = DT > 0 ? DT : A.d;
+    const int NB = DT > 0 ? 1 : (d + DB - 1) / DB;           // lanes per parent word
     extern __shared__ float ls_smem[];
     const int tid = threadIdx.x;
     const int PW = A.pw, C = A.chunks, G = A.groups, T = A.chunk_steps, TT = A.tile_steps;
     const int TP = (TT + 2 * kLsBatch - 1) / (2 * kLsBatch) * (2 * kLsBatch);  // stretch of a tile, whole batches
     float *tile = ls_smem;                        // [G * C][TP * d]
-    float *tot = ls_smem + G * C * TP * d;        // [G][C][pw][d], used when C > 1
+    float *tot = ls_smem + G * C * TP * d;        // [G][C][pw][DB], used when C > 1
 
     const int64_t K = A.L - 1;
     const int wl = tid % PW;
@@ -115,8 +133,10 @@ __global__ __launch_bounds__(kLsThreads) void sig_level_scan_kernel(LevelScanArg
     const int g = tid / (PW * C);
     const int64_t b0 = (int64_t)(blockIdx.x / A.wblocks) * G;
     const int64_t b = b0 + g;
-    const int w = (int)(blockIdx.x % A.wblocks) * PW + wl;
-    const bool lane_ok = g < G && b < A.B && w < A.parents;
+    const int item = (int)(blockIdx.x % A.wblocks) * PW + wl;
+    const bool lane_ok = g < G && b < A.B && item < A.items;
+    const int w = DT > 0 ? item : item / NB;                 // parent word
+    const int first_child = DT > 0 ? 0 : (item - w * NB) * DB;
 
     // Addresses are a workgroup-uniform base plus a 32-bit lane offset (the host checks that the rows of the
     // workgroup's paths stay below 2^30 floats and the strides below 2^24, so offsets are one 24-bit multiply-add).
@@ -146,9 +166,17 @@ __global__ __launch_bounds__(kLsThreads) void sig_level_scan_kernel(LevelScanArg
     const float *my_tile = tile + (size_t)((g < G ? g : 0) * C + c) * TP * d;
     const int tiles = (T + TT - 1) / TT;
 
-    float acc[d];
+    // children of this lane inside an increment (run-time d: clamped to the last channel)
+    int child[DB];
 #pragma unroll
-    for (int a = 0; a < d; ++a) acc[a] = 0.0f;
+    for (int a = 0; a < DB; ++a) child[a] = first_child + a < d ? first_child + a : d - 1;
+    float acc[DB];
+#pragma unroll
+    for (int a = 0; a < DB; ++a) acc[a] = 0.0f;
+    auto store_acc = [&](float *parent_row) {
+        if constexpr (DT > 0) store_children<DB, VEC>(parent_row, acc);
+        else store_block(parent_row, first_child, d, acc);
+    };
 
     // differenced increments of tile i: the stretch of every (path, chunk) of the workgroup is a straight run of
     // the path, taken by 2^sub_shift adjacent threads; the rest of the stretch (past the end of a chunk, and the
@@ -194,11 +222,11 @@ __global__ __launch_bounds__(kLsThreads) void sig_level_scan_kernel(LevelScanArg
         for (int m = 0; m < M; ++m) h = fmaf(h, dx[let[m]] * rc[m], first ? 0.0f : s[m]);
         h = t < n_on ? h : 0.0f;
 #pragma unroll
-        for (int a = 0; a < d; ++a) acc[a] = fmaf(h, dx[a], acc[a]);
+        for (int a = 0; a < DB; ++a) acc[a] = fmaf(h, dx[DT > 0 ? a : child[a]], acc[a]);
         if constexpr (decltype(emit_c)::value) {
             int row = jt + t;
             row = row < j_end ? row : j_end - 1;
-            store_children<d, VEC>(hi_base + (hi_off + __umul24((uint32_t)row, (uint32_t)hi_stride)), acc);
+            store_acc(hi_base + (hi_off + __umul24((uint32_t)row, (uint32_t)hi_stride)));
         }
     };
 
@@ -235,10 +263,10 @@ __global__ __launch_bounds__(kLsThreads) void sig_level_scan_kernel(LevelScanArg
     }
     if (C > 1) {
         sweep(No{}, !one_tile);
-        float *mine = tot + (size_t)tid * d;
+        float *mine = tot + (size_t)tid * DB;
         if (tid < G * C * PW) {
 #pragma unroll
-            for (int a = 0; a < d; ++a) mine[a] = acc[a];
+            for (int a = 0; a < DB; ++a) mine[a] = acc[a];
         }
         __syncthreads();
         // Without per-step stores the sum of all chunks is the result and the lane of chunk 0 writes it; otherwise
@@ -246,37 +274,36 @@ __global__ __launch_bounds__(kLsThreads) void sig_level_scan_kernel(LevelScanArg
         if (!A.hi) {
             if (lane_ok && c == 0 && A.fin) {
 #pragma unroll
-                for (int a = 0; a < d; ++a) acc[a] = 0.0f;
+                for (int a = 0; a < DB; ++a) acc[a] = 0.0f;
                 for (int cc = 0; cc < C; ++cc) {
-                    const float *part = tot + (size_t)((g * C + cc) * PW + wl) * d;
+                    const float *part = tot + (size_t)((g * C + cc) * PW + wl) * DB;
 #pragma unroll
-                    for (int a = 0; a < d; ++a) acc[a] += part[a];
+                    for (int a = 0; a < DB; ++a) acc[a] += part[a];
                 }
-                store_children<d, VEC>(A.fin + b * A.fin_stride + (int64_t)w * d, acc);
+                store_acc(A.fin + b * A.fin_stride + (int64_t)w * d);
             }
             return;
         }
 #pragma unroll
-        for (int a = 0; a < d; ++a) acc[a] = 0.0f;
+        for (int a = 0; a < DB; ++a) acc[a] = 0.0f;
         if (lane_ok) {
             for (int cc = 0; cc < c; ++cc) {
-                const float *part = tot + (size_t)((g * C + cc) * PW + wl) * d;
+                const float *part = tot + (size_t)((g * C + cc) * PW + wl) * DB;
 #pragma unroll
-                for (int a = 0; a < d; ++a) acc[a] += part[a];
+                for (int a = 0; a < DB; ++a) acc[a] += part[a];
             }
         }
     }
     if (A.hi) sweep(Yes{}, !one_tile);
     else sweep(No{}, !one_tile);
     // the chunk that holds the last step also holds the level of the whole path
-    if (lane_ok && A.fin && j_begin < K32 && j_end == K32)
-        store_children<d, VEC>(A.fin + b * A.fin_stride + (int64_t)w * d, acc);
+    if (lane_ok && A.fin && j_begin < K32 && j_end == K32) store_acc(A.fin + b * A.fin_stride + (int64_t)w * d);
 }
 
 template <int d, int n>
 hipError_t launch_one(const LevelScanArgs &A, int vec, int blocks, int threads, size_t lds, hipStream_t st)
 {
-    constexpr int kNatural = d % 4 == 0 ? 4 : (d % 2 == 0 ? 2 : 1);
+    constexpr int kNatural = d == 0 ? 1 : (d % 4 == 0 ? 4 : (d % 2 == 0 ? 2 : 1));
     if (kNatural > 1 && vec >= kNatural)
         hipLaunchKernelGGL((sig_level_scan_kernel<d, n, kNatural>), dim3(blocks), dim3(threads), lds, st, A);
     else
@@ -312,7 +339,7 @@ hipError_t launch_level_d(int d, int n, const LevelScanArgs &A, int vec, int blo
     case 8: return launch_level<8>(n, A, vec, blocks, threads, lds, st);
     case 9: return launch_level<9>(n, A, vec, blocks, threads, lds, st);
     case 10: return launch_level<10>(n, A, vec, blocks, threads, lds, st);
-    default: return hipErrorInvalidValue;
+    default: return launch_level<0>(n, A, 1, blocks, threads, lds, st);   // run-time d
     }
 }
 
@@ -407,25 +434,39 @@ hipError_t launch_level_scan(const float *path, float *out, float *scratch, int6
         A.fin_stride = fin_stride;
         const int vh = store_width(hi, hi_stride), vf = store_width(fin, fin_stride);
         const int vec = vh < vf ? vh : vf;
-        const int64_t P = rs.pow[n - 1];
-        const int C = level_scan_chunks(B, L, rs, n, forced_chunks, cus);
-        int64_t PW = kLsThreads / C;
-        if (PW > P) PW = P;
-        int64_t G = kLsThreads / (PW * C);
-        if (G > B) G = B;
-        // 32-bit offsets inside the rows of a workgroup's paths
-        const int64_t widest = stream_flag ? rs.D : rs.pow[n < N ? n : n - 1];
-        while (G > 1 && G * K * widest >= ((int64_t)1 << 30)) --G;
-        const int T = (int)((K + C - 1) / C);
+        // work items of a path: one per parent word, or (more than 10 channels) one per block of four children
+        const int64_t P = rs.pow[n - 1] * (d <= 10 ? 1 : (d + kWideBlock - 1) / kWideBlock);
+        if (P > INT32_MAX) return hipErrorInvalidValue;
+        const int per_item = d <= 10 ? d : kWideBlock;
+        int C = level_scan_chunks(B, L, rs, n, forced_chunks, cus);
         constexpr int kPair = 2 * kLsBatch;
+        int64_t PW, G;
+        for (;;) {
+            PW = kLsThreads / C;
+            if (PW > P) PW = P;
+            G = kLsThreads / (PW * C);
+            if (G > B) G = B;
+            // 32-bit offsets inside the rows of a workgroup's paths
+            const int64_t widest = stream_flag ? rs.D : rs.pow[n < N ? n : n - 1];
+            while (G > 1 && G * K * widest >= ((int64_t)1 << 30)) --G;
+            // the increment tile holds at least one pair of batches for every (path, chunk) of the workgroup
+            const int64_t by_tile = kLsTileFloats / ((int64_t)C * d * kPair);
+            if (by_tile >= 1) {
+                if (G > by_tile) G = by_tile;
+                break;
+            }
+            C /= 2;   // many channels: fewer chunks (C = 1 always fits: d <= 256)
+        }
+        const int T = (int)((K + C - 1) / C);
         int64_t TT = kLsTileFloats / (G * C * d) / kPair * kPair;   // whole batch pairs
         if (TT > T) TT = T;
-        if (TT < 1) return hipErrorInvalidValue;  // cannot happen: G * C * d <= 640 (C <= 64, and PW = P >= d otherwise)
+        if (TT < 1) return hipErrorInvalidValue;
         const int64_t TP = (TT + kPair - 1) / kPair * kPair;
         const int64_t wblocks = (P + PW - 1) / PW;
         const int64_t blocks = wblocks * ((B + G - 1) / G);
         if (blocks > INT32_MAX) return hipErrorInvalidValue;
-        A.parents = (int32_t)P;
+        A.d = d;
+        A.items = (int32_t)P;
         A.pw = (int32_t)PW;
         A.wblocks = (int32_t)wblocks;
         A.chunks = C;
@@ -437,7 +478,7 @@ hipError_t launch_level_scan(const float *path, float *out, float *scratch, int6
         A.sub_shift = shift;
         const int used = (int)(G * C * PW);
         const int threads = (used + kWave - 1) / kWave * kWave;
-        const size_t lds = (size_t)(G * C * TP * d + (C > 1 ? threads * d : 0)) * sizeof(float);
+        const size_t lds = (size_t)(G * C * TP * d + (C > 1 ? threads * per_item : 0)) * sizeof(float);
         hipError_t e = launch_level_d(d, n, A, vec, (int)blocks, threads, lds, st);
         if (e != hipSuccess) return e;
     }

@@ -72,15 +72,17 @@ def test_plan_of_the_five_configs_is_on_chip_and_consistent(name):
 
 
 def test_plan_falls_back_for_uncompiled_shapes():
-    """Without an on-chip kernel: the level-by-level family where it applies (d <= 10, depth <= 8, scratch below
+    """Without an on-chip kernel: the level-by-level family where it applies (d <= 256, depth <= 8, scratch below
     8 GiB), else the HBM-streaming family."""
     for stream in (0, 1):
         rc, pl = binding.sig_plan(None, 7, 30, 9, 6, stream)
         assert rc == binding.SIG_OK and pl.variant == binding.SIG_VARIANT_LEVEL_SCAN
         assert binding.sig_plan_validate(7, 30, 9, 6, stream, pl) == binding.SIG_OK
-        rc, pl = binding.sig_plan(None, 7, 30, 12, 3, stream)      # more than 10 channels
+        rc, pl = binding.sig_plan(None, 7, 30, 12, 3, stream)      # more than 10 channels: run-time d
+        assert rc == binding.SIG_OK and pl.variant == binding.SIG_VARIANT_LEVEL_SCAN
+        rc, pl = binding.sig_plan(None, 7, 30, 300, 2, stream)     # more channels than a workgroup has threads
         assert rc == binding.SIG_OK and pl.variant == binding.SIG_VARIANT_HBM_STREAMING
-        assert 0 <= pl.prefix_depth <= 2
+        assert 0 <= pl.prefix_depth <= 1
         rc, pl = binding.sig_plan(None, 7, 30, 2, 9, stream)       # deeper than 8
         assert rc == binding.SIG_OK and pl.variant == binding.SIG_VARIANT_HBM_STREAMING
     rc, pl = binding.sig_plan(None, 512, 1000, 9, 6, 0)            # lower levels of every prefix: 136 GB of scratch
@@ -143,7 +145,7 @@ def test_planner_keeps_the_shape_grid_on_chip():
 
 
 def test_level_scan_plans_are_checked_on_the_host():
-    """The level-by-level family (Section 2.2) takes d <= 10, depth <= 8, chunks >= 0 and rows that 32-bit lane
+    """The level-by-level family (Section 2.2) takes d <= 256, depth <= 8, chunks >= 0 and rows that 32-bit lane
     offsets can address; the planner chooses it only for shapes without an on-chip kernel."""
     ls = binding.SIG_VARIANT_LEVEL_SCAN
     mk = binding.make_plan
@@ -151,7 +153,8 @@ def test_level_scan_plans_are_checked_on_the_host():
         assert binding.sig_plan_validate(128, 100, 5, 4, stream, mk(ls, chunks=0)) == binding.SIG_OK
         assert binding.sig_plan_validate(16, 128, 10, 6, stream, mk(ls, chunks=7)) == binding.SIG_OK
         assert binding.sig_plan_validate(4, 16, 1, 8, stream, mk(ls, chunks=1000)) == binding.SIG_OK
-        assert binding.sig_plan_validate(4, 16, 11, 2, stream, mk(ls, chunks=0)) == binding.SIG_ERR_INVALID
+        assert binding.sig_plan_validate(4, 16, 11, 2, stream, mk(ls, chunks=0)) == binding.SIG_OK
+        assert binding.sig_plan_validate(4, 16, 300, 2, stream, mk(ls, chunks=0)) == binding.SIG_ERR_INVALID
         assert binding.sig_plan_validate(4, 16, 2, 9, stream, mk(ls, chunks=0)) == binding.SIG_ERR_INVALID
         assert binding.sig_plan_validate(4, 16, 2, 3, stream, mk(ls, chunks=-1)) == binding.SIG_ERR_INVALID
     # one path's rows beyond 2^30 floats

@@ -37,6 +37,8 @@ SHAPES = [
     (4, 16, 2, 3), (3, 9, 3, 5), (2, 40, 5, 4), (5, 7, 1, 6), (2, 12, 7, 2), (2, 12, 6, 1), (1, 130, 2, 8),
     (2, 70, 4, 4), (1, 20, 10, 5), (3, 2, 3, 4), (7, 3, 3, 3), (130, 5, 3, 4), (2, 1000, 5, 4), (1, 2100, 3, 3),
     (9, 33, 9, 3), (300, 11, 4, 4), (1, 50, 8, 4),
+    # more than 10 channels: d is a run-time value and a lane owns a block of four children
+    (3, 20, 11, 3), (2, 9, 12, 4), (5, 33, 13, 2), (2, 7, 20, 3), (3, 12, 64, 2), (1, 5, 256, 2), (40, 6, 17, 2), (2, 300, 11, 2),
 ]
 
 
@@ -87,9 +89,9 @@ def test_repeated_points(gpu, oracle):
 
 def test_rejected_plans(gpu):
     import torch
-    x = torch.zeros(2, 8, 11, device="cuda")
+    x = torch.zeros(2, 8, 300, device="cuda")
     with pytest.raises(RuntimeError):
-        gpu.signature(x, 2, plan=plan_for(gpu))           # d > 10
+        gpu.signature(x, 2, plan=plan_for(gpu))           # d > 256
     x = torch.zeros(2, 8, 2, device="cuda")
     with pytest.raises(RuntimeError):
         gpu.signature(x, 9, plan=plan_for(gpu))           # depth > 8
