@@ -106,3 +106,53 @@ def test_graph_capture_and_replay(gpu, oracle):
     finally:
         torch.cuda.synchronize()
         gpu.sig_destroy(ctx)
+
+
+def test_pointers_that_are_only_float_aligned(gpu, oracle):
+    """The ABI asks for float32 arrays, not for 16-byte alignment: every family, and the gradient, with path, output and
+    gradient buffers that start 4 bytes past a 16-byte boundary."""
+    import torch
+
+    def shifted(shape, fill=None):
+        n = int(np.prod(shape))
+        raw = torch.empty(n + 1, dtype=torch.float32, device="cuda")
+        view = raw[1:].view(*shape)
+        assert view.data_ptr() % 16 == 4
+        if fill is not None:
+            view.copy_(torch.from_numpy(fill))
+        return view
+
+    ctx = gpu.default_ctx()
+    cases = [("C1", None), ("C2", None), ("C4", None),
+             ("C2", gpu.make_plan(gpu.SIG_VARIANT_LEVEL_SCAN, chunks=0)), ("C4", gpu.make_plan(gpu.SIG_VARIANT_LEVEL_SCAN, chunks=0)),
+             ("C4", gpu.make_plan(gpu.SIG_VARIANT_HBM_STREAMING, prefix_depth=1)),
+             ("C2", gpu.make_plan(gpu.SIG_VARIANT_ON_CHIP, prefix_depth=2, chunks=4, segments=2))]
+    for name, plan in cases:
+        cfg = workloads.CONFIGS[name]
+        x = workloads.make_paths(cfg)[:16]
+        B, L, d = x.shape
+        D = gpu.sig_size(d, cfg.depth)
+        xt = shifted(x.shape, x)
+        out = shifted((B, L - 1, D) if cfg.stream else (B, D))
+        out.fill_(float("nan"))
+        assert gpu.sig_compute(ctx, xt, cfg.depth, int(cfg.stream), out, plan=plan) == gpu.SIG_OK
+        torch.cuda.synchronize()
+        errs = level_errors(out.cpu().numpy(), oracle.signature(x, cfg.depth, stream=cfg.stream), d, cfg.depth)
+        say("  shifted pointers, %s, %s: %s" % (name, "auto" if plan is None else "variant %d" % plan.variant,
+                                                " ".join("%.2e" % e for e in errs)))
+        assert max(errs) <= TOL
+    # gradient: register kernel (5, 4), sliced sweep (10, 4), general sweep (11, 2)
+    for d, depth, B, L, stream in [(5, 4, 9, 60, False), (4, 4, 5, 40, True), (10, 4, 3, 20, False), (11, 2, 4, 15, True)]:
+        x = workloads.brownian_paths(B, L, d, seed=95 + d)
+        D = gpu.sig_size(d, depth)
+        rows = (B, L - 1, D) if stream else (B, D)
+        g = np.random.default_rng(d).normal(size=rows).astype(np.float32)
+        xt, gt, out, gx = shifted(x.shape, x), shifted(rows, g), shifted(rows), shifted(x.shape)
+        gx.fill_(float("nan"))
+        assert gpu.sig_compute(ctx, xt, depth, int(stream), out) == gpu.SIG_OK
+        assert gpu.sig_backward(ctx, xt, depth, int(stream), out, gt, gx) == gpu.SIG_OK
+        torch.cuda.synchronize()
+        want = oracle.signature_backward(x, depth, g, stream=stream)
+        err = np.linalg.norm(gx.cpu().numpy() - want) / np.linalg.norm(want)
+        say("  shifted pointers, gradient (%d, %d): %.2e" % (d, depth, err))
+        assert err <= TOL
