@@ -349,6 +349,9 @@ __device__ __forceinline__ void lds_tree_reduce(float *&src, float *&dst, int G,
 // together).  That costs about a dozen registers; it pays in the join kernel, which runs one workgroup per path
 // with nothing else to hide the LDS latency (the compiler's own order waits once per handful of reads), and
 // loses in the fold kernels, where the registers are worth a wavefront of occupancy.
+#ifndef SIG_TREE_BATCH
+#define SIG_TREE_BATCH false
+#endif
 template <int d, int N, int P, bool BATCH = false>
 __device__ __forceinline__ void reg_product(Lane<d, N, P> &ln, const float *b, unsigned u)
 {
@@ -639,13 +642,21 @@ __global__ __launch_bounds__((max_threads<d, N, P, CHUNKED>())) void sig_on_chip
                                 if (t0 + t < elim[j]) eptr[j][(int64_t)(t0 + t) * ROWV] = val[j];
                         }
                     } else {
+                        // rows too long for the per-lane element table: slot by slot (both loop bounds are the
+                        // same for the whole wavefront), consecutive lanes on consecutive vectors of the row
                         const int wave = tid / kWave, lw = tid - wave * kWave;
-                        for (int i = lw; i < SPW * D; i += kWave) {
-                            const int sw = i / D;
-                            const int col = i - sw * D;
+                        for (int sw = 0; sw < SPW; ++sw) {
                             const int slot = wave * SPW + sw;
-                            if (slot < NGC && t0 + t < desc[slot].steps)
-                                A.out[desc[slot].out_row0 + (int64_t)(t0 + t) * D + col] = sigA[slot * D + col];
+                            if (slot >= NGC) break;
+                            if (t0 + t >= desc[slot].steps) continue;
+                            float *dst = A.out + desc[slot].out_row0 + (int64_t)(t0 + t) * D;
+                            const float *src = sigA + slot * D;
+                            if (VEC == 4 && use_vec) {
+                                for (int col = lw; col < ROWV; col += kWave)
+                                    reinterpret_cast<vec4f *>(dst)[col] = reinterpret_cast<const vec4f *>(src)[col];
+                            } else {
+                                for (int col = lw; col < D; col += kWave) dst[col] = src[col];
+                            }
                         }
                     }
                 } else if constexpr (emit) {
@@ -826,7 +837,7 @@ __global__ __launch_bounds__((max_threads<d, N, P, CHUNKED>())) void sig_on_chip
                 float *slot = rows + (gi * HC + c / (2 * st)) * D;  // of the pair (c, c + st)
                 if (active && (c & (2 * st - 1)) == st) store_state<d, N, P>(slot, u, ln);
                 __syncthreads();
-                if (active && (c & (2 * st - 1)) == 0 && c + st < C) reg_product<d, N, P>(ln, slot, u);
+                if (active && (c & (2 * st - 1)) == 0 && c + st < C) reg_product<d, N, P, SIG_TREE_BATCH>(ln, slot, u);
                 if (2 * st < C) __syncthreads();  // the slots are rewritten in the next round
             }
             SIG_TICK(4);
@@ -855,17 +866,27 @@ __global__ __launch_bounds__((max_threads<d, N, P, CHUNKED>())) void sig_on_chip
             }
         } else {
             // inclusive scan left to right into the second buffer: B[0] = A[0], B[c] = B[c-1] (x) A[c]
+            SIG_TICK(3);
+            float *scanned = sigB;  // where the inclusive prefixes end up
             if constexpr (Sh::SZ <= 64 && WAVE_SLOTS) {
-                // the lanes of chunk 0 (one wavefront's slot) keep the running product in registers and
-                // multiply it by each later chunk's row; B[C-1] is nobody's carry and is skipped
-                if (active && c == 0) {
-                    store_state<d, N, P>(sigB + mygc * D, u, ln);
-                    for (int c2 = 1; c2 + 1 < C; ++c2) {
-                        reg_product<d, N, P>(ln, sigA + (mygc + c2) * D, u);
-                        store_state<d, N, P>(sigB + (mygc + c2) * D, u, ln);
+                // Scan in log2(C) rounds with the left factor in registers: in the round with stride st the lanes
+                // of chunk c multiply their value by the row of chunk c + st and leave the product as that chunk's
+                // new row; then every chunk reads its own new row back.  Rows alternate between the two buffers.
+                // B[C-1] is nobody's carry and is not computed.
+                float *cur = sigA, *nxt = sigB;
+                for (int st = 1; st < C - 1; st <<= 1) {
+                    if (active) {
+                        if (c < st) store_state<d, N, P>(nxt + mygc * D, u, ln);  // already the full prefix
+                        if (c + st < C - 1) {
+                            reg_product<d, N, P, SIG_TREE_BATCH>(ln, cur + (mygc + st) * D, u);
+                            store_state<d, N, P>(nxt + (mygc + st) * D, u, ln);
+                        }
                     }
+                    __syncthreads();
+                    if (active && c < C - 1) load_state<d, N, P>(nxt + mygc * D, u, ln);
+                    float *t = cur; cur = nxt; nxt = t;
                 }
-                __syncthreads();
+                scanned = cur;
             } else {
                 for (int x = tid; x < G * D; x += nthr) {
                     const int g2 = x / D;
@@ -885,8 +906,9 @@ __global__ __launch_bounds__((max_threads<d, N, P, CHUNKED>())) void sig_on_chip
                 }
             }
             // every chunk restarts from the signature of everything before it and emits its prefixes
+            SIG_TICK(4);
             if (c == 0) identity_state<d, N, P>(ln);
-            else load_state<d, N, P>(sigB + (mygc - 1) * D, u, ln);
+            else load_state<d, N, P>(scanned + (mygc - 1) * D, u, ln);
             fold_chunk(std::true_type{});
         }
         }
