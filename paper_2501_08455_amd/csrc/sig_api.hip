@@ -318,6 +318,46 @@ int plan_auto(const sig_ctx *ctx, int64_t B, int64_t L, int stream_flag, const R
             pl->chunks = (int)C;
             pl->segments = (int)W;
         }
+        // Stream mode with few paths: the on-chip kernels walk K / C steps one after the other (twice when time is
+        // cut) and a wavefront stages every row through LDS, while the level-scan family (one launch per level,
+        // parallel in time) only pays its launches.  Estimates in microseconds fitted to a measured grid (21
+        // shapes, B = 1 .. 8192, L = 100 and 500).  On-chip, per step: 0.1 + 0.01 per state float, plus 0.022 per
+        // row-copy iteration of a wavefront (0.1 when the rows are short enough for the per-lane element table);
+        // kernels whose lanes store their own state (more than 64 lanes per path): 0.0125 per state float.  The
+        // level-scan family: 5 + 0.008 K per level (2 more from 8 paths on) plus 1.3 x its output at 2 TB/s.  It is
+        // taken when the on-chip estimate is 1.4 times larger and the on-chip plan leaves the chip below two
+        // wavefronts per SIMD (measured there: up to 15x faster, e.g. d = 8, depth 4, one path of 500 points: 49
+        // against 737 us; the estimates err on the side of the on-chip kernels).
+        auto prefer_level_scan = [&](const sig_plan_t &chosen) {
+            if (!stream_flag) return false;
+            sig_plan_t ls{};
+            ls.variant = SIG_VARIANT_LEVEL_SCAN;
+            if (check_level_scan(B, L, rs, stream_flag, ls) != SIG_OK) return false;
+            const int C = chosen.chunks;
+            const double waves = (double)B * Q * C / kWave;
+            if (waves > 2.0 * cus * 4) return false;
+            double rounds = 0;
+            for (int c = 1; c < C; c *= 2) rounds += 1.5;
+            const double seq = C > 1 ? 2.0 * (double)ceil_div(K, C) + rounds : (double)K;
+            double step = 0.0125 * ki->state_floats;
+            if (Q <= kWave) {
+                const int64_t rowv = rs.D % 4 == 0 ? rs.D / 4 : rs.D;
+                const int64_t spw = kWave / Q;
+                const int64_t table = ceil_div(spw * rowv, kWave);
+                step = 0.1 + 0.01 * ki->state_floats + (table <= 8 ? 0.1 : 0.022 * (double)(spw * ceil_div(rowv, kWave)));
+            }
+            const double on_chip = 6.0 + seq * step;
+            const double out_bytes = 4.0 * (double)B * (double)K * (double)rs.D;
+            const double level_scan = rs.depth * (5.0 + 0.008 * (double)K + (B >= 8 ? 2.0 : 0.0)) + 1.3 * out_bytes / 2.0e6;
+            return on_chip > 1.4 * level_scan;
+        };
+        auto take_level_scan = [&]() {
+            *pl = sig_plan_t{};
+            pl->variant = SIG_VARIANT_LEVEL_SCAN;
+            pl->threads = kThreads;
+            pl->segments = 1;
+            return SIG_OK;
+        };
         // Stream mode without time cuts: one wavefront per workgroup if its paths then fit one straight-copy tile
         // with room for six workgroups per CU.  A tile boundary costs a stream kernel a drain of its store
         // queue (the loader's wait also waits for every store issued before it); measured 5 % on d = 4, depth 4.
@@ -327,6 +367,7 @@ int plan_auto(const sig_ctx *ctx, int64_t B, int64_t L, int stream_flag, const R
             OnChipArgs args{};
             if (finish_on_chip(ki, cus, B, L, stream_flag, narrow, rs, &args) && args.flat_tile &&
                 ki->lds_bytes(args) <= 26 * 1024) {
+                if (prefer_level_scan(narrow)) return take_level_scan();
                 *pl = narrow;
                 pl->tile_steps = args.tile_steps;
                 return SIG_OK;
@@ -343,6 +384,7 @@ int plan_auto(const sig_ctx *ctx, int64_t B, int64_t L, int stream_flag, const R
                 if (c != want.chunks) pl->segments = 1;
                 OnChipArgs args{};
                 if (finish_on_chip(ki, cus, B, L, stream_flag, *pl, rs, &args)) {
+                    if (prefer_level_scan(*pl)) return take_level_scan();
                     pl->tile_steps = args.tile_steps;
                     return SIG_OK;
                 }

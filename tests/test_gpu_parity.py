@@ -174,7 +174,10 @@ def test_shape_grid(gpu, oracle, shape):
         x = workloads.brownian_paths(B, L, d, seed=6000 + 31 * d + depth + B)
         for stream in (False, True):
             rc, pl = gpu.sig_plan(None, B, L, d, depth, int(stream))
-            assert rc == gpu.SIG_OK and pl.variant == gpu.SIG_VARIANT_ON_CHIP
+            assert rc == gpu.SIG_OK
+            # (stream mode with few paths may take the level-by-level family; the forced plans below and
+            # test_on_chip_cases cover the register kernels' stream paths)
+            assert pl.variant == gpu.SIG_VARIANT_ON_CHIP or (stream and pl.variant == gpu.SIG_VARIANT_LEVEL_SCAN)
             check(gpu, oracle, x, depth, stream, label="grid auto")
     x = workloads.brownian_paths(4, 41, d, seed=6100 + d + depth)
     forced = [(1, 3, 4, False), (1, 1, 7, True)]
