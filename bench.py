@@ -195,6 +195,35 @@ def table1(binding, workloads, ctx, d=5):
     return rows
 
 
+STREAM_GRID_SHAPES = [(2, 3), (2, 4), (2, 6), (3, 3), (3, 4), (3, 5), (4, 3), (4, 4), (4, 5), (5, 2), (5, 3), (5, 4),
+                      (5, 5), (6, 3), (6, 4), (7, 3), (8, 3), (8, 4), (9, 3), (10, 2), (10, 3), (10, 4)]
+
+
+def stream_families(binding, workloads, ctx):
+    """Stream mode at small and medium batch: the planner's choice next to the level-scan family forced by plan,
+    on a grid of shapes (the measurements behind the planner's rule for few paths)."""
+    import torch
+    rows = []
+    ls_plan = binding.make_plan(binding.SIG_VARIANT_LEVEL_SCAN, chunks=0)
+    for d, depth in STREAM_GRID_SHAPES:
+        D = workloads.sig_size(d, depth)
+        for L in (100, 256, 500):
+            for B in (1, 16, 128, 1024):
+                if B * (L - 1) * D * 4 > 1.5e9:
+                    continue
+                x = torch.from_numpy(workloads.brownian_paths(B, L, d, seed=1)).cuda()
+                out = torch.empty((B, L - 1, D), dtype=torch.float32, device="cuda")
+                steps, warm = (10, 3) if B * L * D > 2e8 else (60, 20)
+                rc, pl = binding.sig_plan(ctx, B, L, d, depth, 1)
+                ms_auto, _ = time_calls(binding, ctx, x, depth, 1, out, steps, warm)
+                ms_ls, _ = time_calls(binding, ctx, x, depth, 1, out, steps, warm, plan=ls_plan)
+                rows.append({"channels": d, "depth": depth, "length": L, "batch": B,
+                             "planner": "level-scan" if pl.variant == binding.SIG_VARIANT_LEVEL_SCAN else "on-chip",
+                             "us_auto": ms_auto * 1e3, "us_level_scan": ms_ls * 1e3})
+                del x, out
+    return rows
+
+
 def training_step(workloads, B, L, d, depth, steps, warmup):
     """One optimisation step of the paper's model (Section 4.2, Eq. 11): Dense(20 -> d) with tanh, signature of
     depth `depth`, Dense(D -> 10), mean squared error, plain gradient descent; synthetic inputs of the stated
@@ -295,6 +324,8 @@ def main():
     ap.add_argument("--batch", type=int, default=0, help="override the batch size (batch-saturated variants)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--backward", action="store_true", help="time sig_backward on the named workload instead")
+    ap.add_argument("--stream-families", action="store_true",
+                    help="also time stream mode on a grid of small and medium batches: planner's choice vs level-scan")
     ap.add_argument("--level-scan", action="store_true",
                     help="time the level-by-level kernel family (the paper's Section 2.2) instead of the planner's choice")
     ap.add_argument("--hbm-streaming", type=int, default=-1, metavar="P",
@@ -375,6 +406,8 @@ def main():
         # a training step of the paper's model with the signature layer in the middle (context for Section 4.2)
         line["training_step"] = [training_step(workloads, 128, L, d, depth, 100, 30)
                                  for (L, d, depth) in [(100, 5, 4), (200, 6, 3), (500, 4, 4)]]
+    if args.stream_families:
+        line["stream_families"] = stream_families(binding, workloads, ctx)
     if args.anchors:
         line["anchors"] = anchors(binding)
     print(json.dumps(line))
