@@ -143,26 +143,95 @@ struct CombineParams {
     int d;
     int depth;
     uint32_t pw[kMaxDepth + 1];
+    float inv_pw[kMaxDepth + 1];   // 1 / d^n
     int64_t off[kMaxDepth + 2];
 };
 
 // one thread per output word:  c_n[w] = a_n[w] + b_n[w] + sum_{i=1}^{n-1} a_i[w / d^{n-i}] * b_{n-i}[w mod d^{n-i}]
-__global__ __launch_bounds__(256) void sig_combine_rows_kernel(CombineParams P)
+__global__ __launch_bounds__(256) void sig_combine_rows_kernel(CombineParams P, int64_t rows)
 {
-    const int64_t row = blockIdx.y;
-    const int64_t pos = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (pos >= P.D) return;
+    // rows and words flattened: no idle threads at the end of short rows
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= rows * P.D) return;
+    const int64_t row = idx / P.D;
+    const int64_t pos = idx - row * P.D;
     const float *a = P.a + row * P.a_stride;
     const float *b = P.b + row * P.b_stride;
     int n = 1;
     while (pos >= P.off[n + 1]) ++n;
     const uint32_t w = (uint32_t)(pos - P.off[n]);
     float c = a[pos] + b[pos];
+    // w = hi * split + lo.  Below 2^24 the quotient comes from a float multiply (exact integers) with a one-step
+    // correction instead of an integer division, which costs about forty instructions on this hardware.
+    const bool small = P.pw[n] <= (1u << 24);
+    const float wf = (float)w;
     for (int i = 1; i < n; ++i) {
-        uint32_t split = P.pw[n - i];
-        c = fmaf(a[P.off[i] + w / split], b[P.off[n - i] + w % split], c);
+        const uint32_t split = P.pw[n - i];
+        uint32_t hi, lo;
+        if (small) {
+            hi = (uint32_t)(wf * P.inv_pw[n - i]);
+            int32_t r = (int32_t)(w - hi * split);
+            if (r < 0) { --hi; r += (int32_t)split; }
+            else if (r >= (int32_t)split) { ++hi; r -= (int32_t)split; }
+            lo = (uint32_t)r;
+        } else {
+            hi = w / split;
+            lo = w - hi * split;
+        }
+        c = fmaf(a[P.off[i] + hi], b[P.off[n - i] + lo], c);
     }
     P.out[row * P.out_stride + pos] = c;
+}
+
+// Rows whose levels below the top one fit LDS twice over.  Every word of the product needs, besides its own
+// a[w] + b[w], only coefficients of lower levels (a_i[hi] b_{n-i}[lo], i = 1 .. n-1), so a workgroup stages levels
+// 1 .. depth-1 of a[row] and b[row] (consecutive threads on consecutive floats) and the gathers hit LDS instead of
+// the caches; the top level, most of the row, streams through once.  A row's top level is cut into `slices` pieces
+// that go to different workgroups (slice 0 also takes the lower levels); a workgroup walks (row, slice) items, and
+// within a level one thread takes one word, so the split points are the same for the whole workgroup.
+__global__ __launch_bounds__(256) void sig_combine_rows_lds_kernel(CombineParams P, int64_t rows, int slices)
+{
+    const int N = P.depth;
+    const int64_t low = P.off[N];      // floats of levels 1 .. N-1
+    float *sa = sig_smem;
+    float *sb = sig_smem + low;
+    const int tid = threadIdx.x, nthr = blockDim.x;
+    const uint32_t top = P.pw[N];
+    const uint32_t per_slice = (top + slices - 1) / slices;
+    for (int64_t item = blockIdx.x; item < rows * slices; item += gridDim.x) {
+        const int64_t row = item / slices;
+        const int slice = (int)(item - row * slices);
+        const float *a = P.a + row * P.a_stride;
+        const float *b = P.b + row * P.b_stride;
+        float *out = P.out + row * P.out_stride;
+        __syncthreads();   // the previous item has been consumed
+        for (int64_t i = tid; i < low; i += nthr) {
+            sa[i] = a[i];
+            sb[i] = b[i];
+        }
+        __syncthreads();
+        for (int n = (slice == 0 ? 1 : N); n <= N; ++n) {
+            const int64_t base = P.off[n];
+            uint32_t w_begin = 0, w_end = P.pw[n];
+            if (n == N) {
+                w_begin = (uint32_t)slice * per_slice;
+                w_end = w_begin + per_slice < top ? w_begin + per_slice : top;
+            }
+            for (uint32_t w = w_begin + tid; w < w_end; w += nthr) {
+                float c = (n == N) ? a[base + w] + b[base + w] : sa[base + w] + sb[base + w];
+                const float wf = (float)w;   // levels of at most 2^24 words (checked by the host)
+                for (int i = 1; i < n; ++i) {
+                    const uint32_t split = P.pw[n - i];
+                    uint32_t hi = (uint32_t)(wf * P.inv_pw[n - i]);
+                    int32_t r = (int32_t)(w - hi * split);
+                    if (r < 0) { --hi; r += (int32_t)split; }
+                    else if (r >= (int32_t)split) { ++hi; r -= (int32_t)split; }
+                    c = fmaf(sa[P.off[i] + hi], sb[P.off[n - i] + r], c);
+                }
+                out[base + w] = c;
+            }
+        }
+    }
 }
 
 }  // namespace
@@ -227,17 +296,35 @@ hipError_t launch_combine_rows(const float *a, int64_t a_stride, const float *b,
     P.a = a; P.b = b; P.out = out;
     P.a_stride = a_stride; P.b_stride = b_stride; P.out_stride = out_stride;
     P.D = rs.D; P.d = rs.d; P.depth = rs.depth;
-    for (int n = 0; n <= rs.depth; ++n) P.pw[n] = (uint32_t)rs.pow[n];
+    for (int n = 0; n <= rs.depth; ++n) {
+        P.pw[n] = (uint32_t)rs.pow[n];
+        P.inv_pw[n] = 1.0f / (float)rs.pow[n];
+    }
     for (int n = 1; n <= rs.depth + 1; ++n) P.off[n] = rs.off[n];
     P.off[0] = 0;
-    int64_t gx = (rs.D + 255) / 256;
-    if (gx > INT32_MAX) return hipErrorInvalidValue;
-    // grid.y is limited to 65535 workgroups: walk the batch in slabs
-    for (int64_t b0 = 0; b0 < B; b0 += 65535) {
-        int64_t nb = B - b0 < 65535 ? B - b0 : 65535;
+    const int64_t low = rs.off[rs.depth];   // floats of the levels below the top one
+    if (rs.D >= 64 && rs.pow[rs.depth] <= ((int64_t)1 << 24) && 2 * low * (int64_t)sizeof(float) <= 48 * 1024) {
+        // lower levels staged in LDS; pieces of at least 8192 top-level words, enough workgroups to fill the chip
+        int64_t slices = rs.pow[rs.depth] / 8192;
+        if (slices < 1) slices = 1;
+        if (slices > 4096) slices = 4096;
+        const int64_t items = B * slices;
+        const int64_t grid = items < 8 * 256 ? items : 8 * 256;
+        const size_t lds = (size_t)(2 * low) * sizeof(float);
+        hipLaunchKernelGGL(sig_combine_rows_lds_kernel, dim3((unsigned)grid), dim3(256), lds, st, P, B, (int)slices);
+        return hipGetLastError();
+    }
+    // very short rows, and rows too long for LDS: one thread per word of the whole batch, in slabs of rows whose
+    // word count fits the grid
+    const int64_t max_words = (int64_t)INT32_MAX / 2 * 256;
+    int64_t slab = max_words / rs.D;
+    if (slab < 1) return hipErrorInvalidValue;   // cannot happen: D < 2^32
+    for (int64_t b0 = 0; b0 < B; b0 += slab) {
+        const int64_t nb = B - b0 < slab ? B - b0 : slab;
         CombineParams Q = P;
         Q.a += b0 * a_stride; Q.b += b0 * b_stride; Q.out += b0 * out_stride;
-        hipLaunchKernelGGL(sig_combine_rows_kernel, dim3((unsigned)gx, (unsigned)nb), dim3(256), 0, st, Q);
+        const int64_t blocks = (nb * rs.D + 255) / 256;
+        hipLaunchKernelGGL(sig_combine_rows_kernel, dim3((unsigned)blocks), dim3(256), 0, st, Q, nb);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
