@@ -627,12 +627,13 @@ constexpr int slice_reduce_steps()
 }
 
 template <int d, int N, int P, bool STREAM>
-__global__ __launch_bounds__(kSliceLanes) void sig_backward_sliced_kernel(BackwardArgs A, float *part)
+__global__ __launch_bounds__(kSliceLanes) void sig_backward_sliced_kernel(BackwardArgs A, float *part, int TS)
 {
+    // TS: steps whose partial sums are parked before they are added up (at most slice_reduce_steps<d>(); fewer
+    // when a long path leaves less LDS)
     using Sh = Shape<d, N, P>;
     constexpr int Q = Sh::Q;
     constexpr int D = Sh::D;
-    constexpr int TS = slice_reduce_steps<d>();
     constexpr int slices = (Q + kSliceLanes - 1) / kSliceLanes;
     const int tid = threadIdx.x, nthr = blockDim.x;
     const int64_t K = A.L - 1;
@@ -746,12 +747,28 @@ __global__ __launch_bounds__(256) void sig_backward_slices_finish_kernel(const f
     grad_path[e] = sum;
 }
 
+template <int d>
+int64_t backward_sliced_bytes_with(int64_t L, int ts)
+{
+    const int64_t tile = ((L - 1) * d + 3) / 4 * 4;
+    return (tile + (int64_t)ts * kSliceLanes * d + (int64_t)ts * d * kSliceSplit) * (int64_t)sizeof(float);
+}
+
+// parked steps for a path of L points: as many as fit beside the path's increments, at least one (0: does not fit)
+template <int d>
+int backward_sliced_steps(int64_t L)
+{
+    int ts = slice_reduce_steps<d>();
+    while (ts > 1 && backward_sliced_bytes_with<d>(L, ts) > kMaxLdsBytes) --ts;
+    return backward_sliced_bytes_with<d>(L, ts) <= kMaxLdsBytes ? ts : 0;
+}
+
+// LDS of the launch (what backward_fits compares with the limit): with the fewest parked steps if need be
 template <int d, int N, int P>
 int64_t backward_sliced_lds_bytes(int64_t L, int)
 {
-    constexpr int TS = slice_reduce_steps<d>();
-    const int64_t tile = ((L - 1) * d + 3) / 4 * 4;
-    return (tile + (int64_t)TS * kSliceLanes * d + (int64_t)TS * d * kSliceSplit) * (int64_t)sizeof(float);
+    const int ts = backward_sliced_steps<d>(L);
+    return backward_sliced_bytes_with<d>(L, ts > 0 ? ts : 1);
 }
 
 template <int d, int N, int P>
@@ -765,13 +782,14 @@ template <int d, int N, int P>
 hipError_t backward_sliced_launch(const BackwardArgs &A, float *scratch, int, int, hipStream_t st)
 {
     constexpr int slices = (Shape<d, N, P>::Q + kSliceLanes - 1) / kSliceLanes;
-    const int64_t lds = backward_sliced_lds_bytes<d, N, P>(A.L, 1);
+    const int ts = backward_sliced_steps<d>(A.L);
+    const int64_t lds = backward_sliced_bytes_with<d>(A.L, ts > 0 ? ts : 1);
     const int64_t grid = A.B * slices;
-    if (!scratch || lds > kMaxLdsBytes || grid <= 0 || grid > INT32_MAX) return hipErrorInvalidValue;
+    if (!scratch || ts < 1 || lds > kMaxLdsBytes || grid <= 0 || grid > INT32_MAX) return hipErrorInvalidValue;
     if (A.stream_flag)
-        hipLaunchKernelGGL((sig_backward_sliced_kernel<d, N, P, true>), dim3((unsigned)grid), dim3(kSliceLanes), (size_t)lds, st, A, scratch);
+        hipLaunchKernelGGL((sig_backward_sliced_kernel<d, N, P, true>), dim3((unsigned)grid), dim3(kSliceLanes), (size_t)lds, st, A, scratch, ts);
     else
-        hipLaunchKernelGGL((sig_backward_sliced_kernel<d, N, P, false>), dim3((unsigned)grid), dim3(kSliceLanes), (size_t)lds, st, A, scratch);
+        hipLaunchKernelGGL((sig_backward_sliced_kernel<d, N, P, false>), dim3((unsigned)grid), dim3(kSliceLanes), (size_t)lds, st, A, scratch, ts);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const int64_t total = A.B * A.L * d;

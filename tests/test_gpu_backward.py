@@ -114,6 +114,14 @@ def test_backward_sliced_shapes(gpu, oracle, shape):
         check(gpu, oracle, x, depth, stream, seed=d + depth + L, label="sliced")
 
 
+def test_backward_sliced_long_paths(gpu, oracle):
+    """Long paths leave the sliced sweep less LDS for its parked sums: it parks fewer steps (down to one) before it
+    hands the shape to the general sweep."""
+    for d, depth, B, L in [(10, 4, 2, 1000), (8, 4, 1, 1600), (10, 4, 1, 1300)]:
+        x = workloads.brownian_paths(B, L, d, seed=8400 + L)
+        check(gpu, oracle, x, depth, False, seed=L, label="sliced, long path")
+
+
 def test_backward_sliced_reproducible_and_after_a_larger_call(gpu, oracle):
     """The per-slice sums live in context scratch: a smaller call after a larger one, and the same bits twice."""
     x = workloads.brownian_paths(6, 30, 10, seed=77)
