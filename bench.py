@@ -184,14 +184,20 @@ def table1(binding, workloads, ctx, d=5):
     """Time sig_compute (final signature) on the shapes of the paper's Table 1."""
     import torch
     rows = []
+    tuned_ctx = binding.sig_create()
     for B, L, depth, paper_ms in TABLE1_ROWS:
         x = torch.from_numpy(workloads.brownian_paths(B, L, d, seed=1000 + B + L + depth)).cuda()
         out = torch.empty((B, workloads.sig_size(d, depth)), dtype=torch.float32, device="cuda")
         ms, _ = time_calls(binding, ctx, x, depth, 0, out, 500, 300)
         rc, pl = binding.sig_plan(ctx, B, L, d, depth, 0)
+        # the same shape after sig_autotune (a context of its own, so that the planner's figure above stays the planner's)
+        rc_t, tuned, _ = binding.sig_autotune(tuned_ctx, B, L, d, depth, 0)
+        ms_tuned, _ = time_calls(binding, tuned_ctx, x, depth, 0, out, 500, 300) if rc_t == binding.SIG_OK else (None, None)
         rows.append({"batch": B, "length": L, "depth": depth, "channels": d, "ms": ms,
-                     "paper_ks_gpu_ms_rtx4090": paper_ms, "plan": pl.as_dict()})
+                     "paper_ks_gpu_ms_rtx4090": paper_ms, "plan": pl.as_dict(),
+                     "ms_autotuned": ms_tuned, "plan_autotuned": tuned.as_dict() if rc_t == binding.SIG_OK else None})
         del x, out
+    binding.sig_destroy(tuned_ctx)
     return rows
 
 

@@ -128,12 +128,25 @@ int sig_compute(sig_ctx *ctx, const float *path, int64_t B, int64_t L, int d, in
                 int stream_flag, float *out, void *hip_stream);
 
 /*
- * The mapping sig_compute would use for this shape.  Host only; `ctx` may be
- * NULL (then a 256-CU device is assumed).  Returns SIG_ERR_INVALID /
+ * The mapping sig_compute would use for this shape (one remembered by sig_autotune for exactly this shape, else the
+ * planner's).  Host only; `ctx` may be NULL (then a 256-CU device is assumed).  Returns SIG_ERR_INVALID /
  * SIG_ERR_TOO_LARGE exactly as sig_compute would for the same shape.
  */
 int sig_plan(const sig_ctx *ctx, int64_t B, int64_t L, int d, int depth, int stream_flag,
              sig_plan_t *plan);
+
+/*
+ * Optional tuning of the mapping of one shape (the shape grid of the paper's tables, Section 4.1, is where it
+ * pays: few paths, where launch and latency effects decide).  Times candidate mappings on the device -- the
+ * planner's choice, the level-scan family, the compiled register kernels with neighbouring time cuts -- on
+ * synthetic input of this shape and remembers the fastest in the context: later sig_compute and sig_plan calls
+ * with exactly this (B, L, d, depth, stream_flag) use it (64 shapes per context, the oldest is replaced).
+ *   chosen, microseconds   HOST, may be NULL: the mapping taken and its measured time per call
+ * Unlike the other entry points it allocates temporary device buffers of the input and output size, enqueues a few
+ * dozen calls on `hip_stream` and waits for them.  B == 0 is SIG_ERR_INVALID; SIG_ERR_ALLOC if the buffers do not fit.
+ */
+int sig_autotune(sig_ctx *ctx, int64_t B, int64_t L, int d, int depth, int stream_flag, sig_plan_t *chosen,
+                 float *microseconds, void *hip_stream);
 
 /*
  * SIG_OK if sig_compute_planned would accept `plan` for this shape (the same checks, nothing is

@@ -69,6 +69,9 @@ def load():
     lib.sig_compute.argtypes = [vp, vp, i64, i64, i32, i32, i32, vp, vp]
     lib.sig_plan.restype = i32
     lib.sig_plan.argtypes = [vp, i64, i64, i32, i32, i32, ctypes.POINTER(sig_plan_t)]
+    lib.sig_autotune.restype = i32
+    lib.sig_autotune.argtypes = [vp, i64, i64, i32, i32, i32, ctypes.POINTER(sig_plan_t),
+                                 ctypes.POINTER(ctypes.c_float), vp]
     lib.sig_plan_validate.restype = i32
     lib.sig_plan_validate.argtypes = [i64, i64, i32, i32, i32, ctypes.POINTER(sig_plan_t)]
     lib.sig_compute_planned.restype = i32
@@ -123,6 +126,16 @@ def sig_plan(ctx, B, L, d, depth, stream_flag):
     pl = sig_plan_t()
     rc = load().sig_plan(ctx, int(B), int(L), int(d), int(depth), int(stream_flag), ctypes.byref(pl))
     return rc, pl
+
+
+def sig_autotune(ctx, B, L, d, depth, stream_flag, stream=None):
+    """Measure candidate mappings of this shape on the device and remember the fastest in `ctx`.
+    Returns (status, plan, microseconds per call)."""
+    pl = sig_plan_t()
+    us = ctypes.c_float(0.0)
+    rc = load().sig_autotune(ctx, int(B), int(L), int(d), int(depth), int(stream_flag), ctypes.byref(pl),
+                             ctypes.byref(us), _stream_handle(stream))
+    return int(rc), pl, float(us.value)
 
 
 def sig_plan_validate(B, L, d, depth, stream_flag, plan):

@@ -6,11 +6,21 @@
 
 using namespace sig;
 
+// a mapping measured by sig_autotune for one shape
+struct TunedPlan {
+    int64_t B, L;
+    int d, depth, stream_flag;
+    sig_plan_t plan;
+};
+
 struct sig_ctx {
     int device;
     int num_cu;
     float *scratch;        // partial signatures of time segments, [B][segments][D]
     size_t scratch_bytes;
+    TunedPlan tuned[64];   // filled by sig_autotune, consulted by sig_compute and sig_plan (oldest overwritten)
+    int tuned_count;
+    int tuned_next;
 };
 
 namespace {
@@ -435,6 +445,26 @@ int plan_auto(const sig_ctx *ctx, int64_t B, int64_t L, int stream_flag, const R
     return SIG_OK;
 }
 
+const sig_plan_t *find_tuned(const sig_ctx *ctx, int64_t B, int64_t L, int d, int depth, int stream_flag)
+{
+    if (!ctx) return nullptr;
+    for (int i = 0; i < ctx->tuned_count; ++i) {
+        const TunedPlan &t = ctx->tuned[i];
+        if (t.B == B && t.L == L && t.d == d && t.depth == depth && t.stream_flag == stream_flag) return &t.plan;
+    }
+    return nullptr;
+}
+
+// the mapping sig_compute uses: one measured by sig_autotune for exactly this shape, else the planner's
+int plan_for(const sig_ctx *ctx, int64_t B, int64_t L, int stream_flag, const RowShape &rs, sig_plan_t *pl)
+{
+    if (const sig_plan_t *t = find_tuned(ctx, B, L, rs.d, rs.depth, stream_flag)) {
+        *pl = *t;
+        return SIG_OK;
+    }
+    return plan_auto(ctx, B, L, stream_flag, rs, pl);
+}
+
 int ensure_scratch(sig_ctx *ctx, size_t bytes)
 {
     if (bytes <= ctx->scratch_bytes) return SIG_OK;
@@ -537,6 +567,8 @@ int sig_create(sig_ctx **ctx)
     c->num_cu = cus;
     c->scratch = nullptr;
     c->scratch_bytes = 0;
+    c->tuned_count = 0;
+    c->tuned_next = 0;
     *ctx = c;
     return SIG_OK;
 }
@@ -557,7 +589,7 @@ int sig_plan(const sig_ctx *ctx, int64_t B, int64_t L, int d, int depth, int str
     RowShape rs;
     int rc = check_shape(B, L, d, depth, stream_flag, &rs);
     if (rc != SIG_OK) return rc;
-    return plan_auto(ctx, B, L, stream_flag, rs, plan);
+    return plan_for(ctx, B, L, stream_flag, rs, plan);
 }
 
 int sig_plan_validate(int64_t B, int64_t L, int d, int depth, int stream_flag, const sig_plan_t *plan)
@@ -603,9 +635,113 @@ int sig_compute(sig_ctx *ctx, const float *path, int64_t B, int64_t L, int d, in
     if (B == 0) return SIG_OK;
     if (!path || !out) return SIG_ERR_INVALID;
     sig_plan_t pl;
-    rc = plan_auto(ctx, B, L, stream_flag, rs, &pl);
+    rc = plan_for(ctx, B, L, stream_flag, rs, &pl);
     if (rc != SIG_OK) return rc;
     return run_plan(ctx, path, B, L, rs, stream_flag, out, pl, static_cast<hipStream_t>(hip_stream));
+}
+
+int sig_autotune(sig_ctx *ctx, int64_t B, int64_t L, int d, int depth, int stream_flag, sig_plan_t *chosen,
+                 float *microseconds, void *hip_stream)
+{
+    if (!ctx) return SIG_ERR_INVALID;
+    RowShape rs;
+    int rc = check_shape(B, L, d, depth, stream_flag, &rs);
+    if (rc != SIG_OK) return rc;
+    if (B == 0) return SIG_ERR_INVALID;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    sig_plan_t base;
+    rc = plan_auto(ctx, B, L, stream_flag, rs, &base);
+    if (rc != SIG_OK) return rc;
+
+    // candidates: the planner's choice, the level-scan family, and for the register kernels every compiled prefix
+    // depth with the planner's time cut and with half and twice as many chunks
+    sig_plan_t cand[24];
+    int n = 0;
+    cand[n++] = base;
+    {
+        sig_plan_t ls{};
+        ls.variant = SIG_VARIANT_LEVEL_SCAN;
+        ls.threads = kThreads;
+        ls.segments = 1;
+        if (base.variant != SIG_VARIANT_LEVEL_SCAN && check_level_scan(B, L, rs, stream_flag, ls) == SIG_OK &&
+            level_scan_scratch_floats(B, L, rs, stream_flag) <= (int64_t)1 << 31)
+            cand[n++] = ls;
+    }
+    for (int p = 0; p < depth && n < 20; ++p) {
+        const OnChipKernelInfo *ki = find_on_chip(d, depth, p);
+        if (!ki) continue;
+        const int c0 = base.variant == SIG_VARIANT_ON_CHIP ? base.chunks : 8;
+        const int w0 = base.variant == SIG_VARIANT_ON_CHIP ? base.segments : 1;
+        const int chunk_opts[3] = {c0, c0 > 1 ? c0 / 2 : 2, c0 * 2};
+        for (int ci = 0; ci < 3 && n < 20; ++ci) {
+            sig_plan_t pl{};
+            pl.variant = SIG_VARIANT_ON_CHIP;
+            pl.prefix_depth = p;
+            pl.chunks = chunk_opts[ci];
+            pl.segments = stream_flag ? 1 : w0;
+            pl.threads = kThreads;
+            OnChipArgs args{};
+            if (pl.chunks < 1 || !finish_on_chip(ki, ctx->num_cu, B, L, stream_flag, pl, rs, &args)) continue;
+            bool dup = false;
+            for (int i = 0; i < n; ++i)
+                dup = dup || (cand[i].variant == pl.variant && cand[i].prefix_depth == p && cand[i].chunks == pl.chunks &&
+                              cand[i].segments == pl.segments && cand[i].threads == pl.threads);
+            if (!dup) cand[n++] = pl;
+        }
+    }
+
+    // synthetic input (zeros: no kernel's timing depends on the values) and an output buffer of the real size
+    const size_t path_bytes = (size_t)B * (size_t)L * (size_t)d * sizeof(float);
+    const size_t out_bytes = (size_t)B * (size_t)(stream_flag ? L - 1 : 1) * (size_t)rs.D * sizeof(float);
+    float *path = nullptr, *out = nullptr;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    int status = SIG_OK;
+    if (hipMalloc(reinterpret_cast<void **>(&path), path_bytes) != hipSuccess ||
+        hipMalloc(reinterpret_cast<void **>(&out), out_bytes) != hipSuccess) {
+        (void)hipGetLastError();
+        status = SIG_ERR_ALLOC;
+    } else if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess ||
+               hipMemsetAsync(path, 0, path_bytes, st) != hipSuccess) {
+        status = SIG_ERR_HIP;
+    }
+    int best = -1;
+    float best_us = 0.0f;
+    for (int i = 0; i < n && status == SIG_OK; ++i) {
+        const int reps = 5;
+        int r = SIG_OK;
+        for (int w = 0; w < 2 && r == SIG_OK; ++w) r = run_plan(ctx, path, B, L, rs, stream_flag, out, cand[i], st);
+        if (r != SIG_OK) continue;   // a candidate the kernels refuse is skipped
+        if (hipEventRecord(e0, st) != hipSuccess) { status = SIG_ERR_HIP; break; }
+        for (int k = 0; k < reps && r == SIG_OK; ++k) r = run_plan(ctx, path, B, L, rs, stream_flag, out, cand[i], st);
+        if (hipEventRecord(e1, st) != hipSuccess || hipEventSynchronize(e1) != hipSuccess) { status = SIG_ERR_HIP; break; }
+        float ms = 0.0f;
+        if (r != SIG_OK || hipEventElapsedTime(&ms, e0, e1) != hipSuccess) continue;
+        const float us = ms * 1000.0f / reps;
+        if (best < 0 || us < best_us) { best = i; best_us = us; }
+    }
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    if (path || out) (void)hipStreamSynchronize(st);
+    if (path) (void)hipFree(path);
+    if (out) (void)hipFree(out);
+    if (status != SIG_OK) return status;
+    if (best < 0) return SIG_ERR_HIP;
+
+    TunedPlan entry{B, L, d, depth, stream_flag, cand[best]};
+    int slot = -1;
+    for (int i = 0; i < ctx->tuned_count; ++i) {
+        const TunedPlan &t = ctx->tuned[i];
+        if (t.B == B && t.L == L && t.d == d && t.depth == depth && t.stream_flag == stream_flag) slot = i;
+    }
+    if (slot < 0) {
+        const int cap = (int)(sizeof(ctx->tuned) / sizeof(ctx->tuned[0]));
+        if (ctx->tuned_count < cap) slot = ctx->tuned_count++;
+        else { slot = ctx->tuned_next; ctx->tuned_next = (ctx->tuned_next + 1) % cap; }
+    }
+    ctx->tuned[slot] = entry;
+    if (chosen) *chosen = cand[best];
+    if (microseconds) *microseconds = best_us;
+    return SIG_OK;
 }
 
 int sig_combine(sig_ctx *ctx, const float *a, const float *b, int64_t B, int d, int depth,
