@@ -293,7 +293,10 @@ int plan_auto(const sig_ctx *ctx, int64_t B, int64_t L, int stream_flag, const R
             int64_t clds = (kMaxLdsBytes - kTileLdsBytes) /
                            ((stream_flag || ki->state_floats > 64 ? 2 : 1) * rs.D * (int64_t)sizeof(float));
             if (cmax > clds) cmax = clds;
-            if (cmax > K / kMinChunkSteps) cmax = K / kMinChunkSteps;
+            // (stream kernels fold every chunk twice and are bound by the sequential steps, not by the scan over
+            // the chunk signatures: chunks of four steps measured 1.15-1.9x faster than eight on small lane states)
+            const int64_t min_steps = (stream_flag && ki->state_floats <= 32) ? kMinChunkSteps / 2 : kMinChunkSteps;
+            if (cmax > K / min_steps) cmax = K / min_steps;
             if (cmax < 1) cmax = 1;
             int64_t C = pieces < cmax ? pieces : cmax;
             if (!(stream_flag && Q <= kWave)) {
@@ -334,7 +337,7 @@ int plan_auto(const sig_ctx *ctx, int64_t B, int64_t L, int stream_flag, const R
         // shapes, B = 1 .. 8192, L = 100 and 500).  On-chip, per step: 0.1 + 0.01 per state float, plus 0.022 per
         // row-copy iteration of a wavefront (0.1 when the rows are short enough for the per-lane element table);
         // kernels whose lanes store their own state (more than 64 lanes per path): 0.0125 per state float.  The
-        // level-scan family: 6.5 + 0.008 K per level (2 more from 8 paths on) plus 1.3 x its output at 2 TB/s.  It is
+        // level-scan family: 5 + 0.008 K per level (6.5 in final mode; 2 more from 8 paths on) plus 1.3 x its output at 2 TB/s.  It is
         // taken when the on-chip estimate is 1.4 times larger and the on-chip plan leaves the chip below two
         // wavefronts per SIMD (measured there: up to 15x faster, e.g. d = 8, depth 4, one path of 500 points: 49
         // against 737 us; the estimates err on the side of the on-chip kernels).
@@ -349,7 +352,7 @@ int plan_auto(const sig_ctx *ctx, int64_t B, int64_t L, int stream_flag, const R
             const int C = chosen.chunks;
             const double waves = (double)B * Q * C / kWave;
             if (waves > 2.0 * cus * 4) return false;
-            const double launches = rs.depth * (6.5 + 0.008 * (double)K + (B >= 8 ? 2.0 : 0.0));
+            const double launches = rs.depth * ((stream_flag ? 5.0 : 6.5) + 0.008 * (double)K + (B >= 8 ? 2.0 : 0.0));
             if (!stream_flag) {
                 if (C != 1 || chosen.segments != 1) return false;
                 const int64_t floats = level_scan_scratch_floats(B, L, rs, 0);
