@@ -172,13 +172,29 @@ struct BackwardArgs {
 };
 
 // steps whose partial sums are parked before they are added up: enough for every lane of a path to have a
-// column (Q / d), but no more than eight (the parked sums take TS * Q * d floats of LDS per path)
+// column (Q / d), but no more than eight (the parked sums take TS * Park::kStepFloats floats of LDS per path)
 template <int d, int P>
 constexpr int reduce_steps()
 {
     const int want = cpow(d, P) / d;
     return want < 1 ? 1 : (want > 8 ? 8 : want);
 }
+
+// Layout of the parked sums of a path.  As [step][lane][channel] a lane's d sums are d floats from its neighbour's,
+// so the lanes of a wavefront write to 32 / gcd(d, 32) of the 32 LDS banks: all of them for odd d, half for d = 2, 6,
+// 10, but only eight for d = 4 and four for d = 8.  Those shapes keep the sums as [step][channel][lane] with rows of
+// an odd number of floats: the lanes' writes (consecutive lanes, one row) and the column sums' reads (consecutive
+// rows, one lane) then both spread over the banks (measured: d = 8, depth 3, 1.6x; d = 4, depth 4, 1.3x on
+// saturated batches; for the other channel counts the change is within a few percent either way).
+template <int d, int P>
+struct Park {
+    static constexpr int Q = cpow(d, P);
+    static constexpr bool kByChannel = d % 4 == 0;
+    static constexpr int kRow = Q | 1;
+    static constexpr int kStepFloats = kByChannel ? d * kRow : d * Q;
+    // sum of lane u for channel a in parked step t
+    static __device__ __forceinline__ int at(int t, int u, int a) { return kByChannel ? (t * d + a) * kRow + u : (t * Q + u) * d + a; }
+};
 
 extern __shared__ float sig_backward_smem[];
 
@@ -207,7 +223,7 @@ __global__ __launch_bounds__(256) void sig_backward_kernel(BackwardArgs A)
         for (int m = P - 1; m >= 0; --m) { letter[m] = (int)(rest % d); rest /= d; }
     }
 
-    // LDS: increments [G][K*d] (overwritten step by step with their gradients), parked partial sums [G][TS][Q][d]
+    // LDS: increments [G][K*d] (overwritten step by step with their gradients), parked partial sums [G][TS] x Park
     const int row_floats = (int)K * d;
     float *tile = sig_backward_smem;
     float *park = tile + (G * row_floats + 3) / 4 * 4;
@@ -233,7 +249,8 @@ __global__ __launch_bounds__(256) void sig_backward_kernel(BackwardArgs A)
     }
     __syncthreads();
 
-    float *mypark = park + (size_t)gi * TS * Q * d;
+    using Pk = Park<d, P>;
+    float *mypark = park + (size_t)gi * TS * Pk::kStepFloats;
     float *myrow = tile + gi * row_floats;
     // One step of the sweep; `upk` is the upstream gradient of row k (stream mode).
     auto step = [&](int64_t k, const Lane<d, N, P> *upk) __attribute__((always_inline)) {
@@ -257,7 +274,7 @@ __global__ __launch_bounds__(256) void sig_backward_kernel(BackwardArgs A)
         backward_step<d, N, P>(ln, ad, inc, letter, dbar);
         if (active) {
 #pragma unroll
-            for (int a = 0; a < d; ++a) mypark[(ts * Q + u) * d + a] = dbar[a];
+            for (int a = 0; a < d; ++a) mypark[Pk::at(ts, (int)u, a)] = dbar[a];
         }
         if (ts == TS - 1 || k == 0) {
             __syncthreads();
@@ -267,7 +284,7 @@ __global__ __launch_bounds__(256) void sig_backward_kernel(BackwardArgs A)
                 for (int c = (int)u; c < (ts + 1) * d; c += Q) {
                     const int t = c / d, a = c - t * d;
                     float sum = 0.0f;
-                    for (int q = 0; q < Q; ++q) sum += mypark[(t * Q + q) * d + a];
+                    for (int q = 0; q < Q; ++q) sum += mypark[Pk::at(t, q, a)];
                     myrow[(k + (ts - t)) * d + a] = sum;
                 }
             }
@@ -392,7 +409,7 @@ constexpr int chunk_row_floats()  // one chunk's row in either LDS buffer of the
 {
     using Sh = Shape<d, N, P>;
     int a = Sh::D;
-    const int park = reduce_steps<d, P>() * Sh::Q * d;
+    const int park = reduce_steps<d, P>() * Park<d, P>::kStepFloats;
     if (park > a) a = park;
     return (a + 3) / 4 * 4;
 }
@@ -473,6 +490,7 @@ __global__ __launch_bounds__(256) void sig_backward_chunked_kernel(BackwardArgs 
     // parked in rowsE, added up and written over the increments.  Stream mode adds row k's upstream gradient
     // before step k; the rows are fetched PD steps ahead (see the unchunked kernel).
     float *mypark = rowsE + c * ROW;
+    using Pk = Park<d, P>;
     constexpr int PD = !STREAM ? 1 : Sh::SZ <= 24 ? 4 : Sh::SZ <= 48 ? 2 : 1;
     auto sweep = [&](auto emit_tag) __attribute__((always_inline)) {
         constexpr bool EMIT = decltype(emit_tag)::value;
@@ -522,7 +540,7 @@ __global__ __launch_bounds__(256) void sig_backward_chunked_kernel(BackwardArgs 
                     if constexpr (EMIT) {
                         if (active) {
 #pragma unroll
-                            for (int a = 0; a < d; ++a) mypark[(ts * Q + u) * d + a] = dbar[a];
+                            for (int a = 0; a < d; ++a) mypark[Pk::at(ts, (int)u, a)] = dbar[a];
                         }
                         if (ts == TS - 1 || t == 0) {
                             __syncthreads();
@@ -532,7 +550,7 @@ __global__ __launch_bounds__(256) void sig_backward_chunked_kernel(BackwardArgs 
                                     const int tt = t + (ts - tp);  // step of this chunk the column belongs to
                                     if (tt < steps) {
                                         float sum = 0.0f;
-                                        for (int q = 0; q < Q; ++q) sum += mypark[(tp * Q + q) * d + a];
+                                        for (int q = 0; q < Q; ++q) sum += mypark[Pk::at(tp, q, a)];
                                         tile[(c * T + tt) * d + a] = sum;
                                     }
                                 }
@@ -626,6 +644,13 @@ constexpr int slice_reduce_steps()
     return fit < 1 ? 1 : (fit > 8 ? 8 : fit);
 }
 
+// Parked sums of one step: [channel][lane], lane q at q + q / 32.  Consecutive lanes write consecutive banks, and
+// the extra float per stretch of 32 lanes puts the stretches, which are read side by side when a column is summed,
+// in different LDS banks (32 floats apart they would all start in the same one).
+constexpr int kParkRow = kSliceLanes + kSliceLanes / 32;
+template <int d>
+constexpr int slice_park_floats() { return d * kParkRow; }
+
 template <int d, int N, int P, bool STREAM>
 __global__ __launch_bounds__(kSliceLanes) void sig_backward_sliced_kernel(BackwardArgs A, float *part, int TS)
 {
@@ -635,6 +660,7 @@ __global__ __launch_bounds__(kSliceLanes) void sig_backward_sliced_kernel(Backwa
     constexpr int Q = Sh::Q;
     constexpr int D = Sh::D;
     constexpr int slices = (Q + kSliceLanes - 1) / kSliceLanes;
+    constexpr int kParkStep = slice_park_floats<d>();
     const int tid = threadIdx.x, nthr = blockDim.x;
     const int64_t K = A.L - 1;
     const int slice = (int)(blockIdx.x % slices);
@@ -642,7 +668,6 @@ __global__ __launch_bounds__(kSliceLanes) void sig_backward_sliced_kernel(Backwa
     const unsigned u_raw = (unsigned)(slice * kSliceLanes + tid);
     const bool active = u_raw < (unsigned)Q;
     const unsigned u = active ? u_raw : 0u;
-    const int lanes = Q - slice * kSliceLanes < kSliceLanes ? Q - slice * kSliceLanes : kSliceLanes;
 
     int letter[P > 0 ? P : 1];
     letter[0] = 0;
@@ -652,11 +677,11 @@ __global__ __launch_bounds__(kSliceLanes) void sig_backward_sliced_kernel(Backwa
         for (int m = P - 1; m >= 0; --m) { letter[m] = (int)(rest % d); rest /= d; }
     }
 
-    // LDS: increments [K*d] (overwritten with this slice's sums), parked partial sums [TS][256][d], stretch sums
+    // LDS: increments [K*d] (overwritten with this slice's sums), parked partial sums [TS][d][kParkRow], stretch sums
     const int row_floats = (int)K * d;
     float *tile = sig_backward_smem;
     float *park = tile + (row_floats + 3) / 4 * 4;
-    float *red = park + TS * kSliceLanes * d;
+    float *red = park + TS * kParkStep;
     {
         const float *x = A.path + b * A.L * d;
         for (int i = tid; i < row_floats; i += nthr) tile[i] = x[i + d] - x[i];
@@ -700,18 +725,22 @@ __global__ __launch_bounds__(kSliceLanes) void sig_backward_sliced_kernel(Backwa
         float dbar[d];
         backward_step<d, N, P>(ln, ad, inc, letter, dbar);
 #pragma unroll
-        for (int a = 0; a < d; ++a) park[(ts * kSliceLanes + tid) * d + a] = active ? dbar[a] : 0.0f;
+        for (int a = 0; a < d; ++a) park[ts * kParkStep + a * kParkRow + tid + (tid >> 5)] = active ? dbar[a] : 0.0f;
         if (ts == TS - 1 || k == 0) {
             __syncthreads();
             // column c = (parked step t, channel a), first in kSliceSplit stretches of lanes, then the stretches
             const int cols = (ts + 1) * d;
             constexpr int stretch = kSliceLanes / kSliceSplit;
+            static_assert(stretch == 32, "the parked layout pads one float per 32 lanes");
             for (int w = tid; w < cols * kSliceSplit; w += nthr) {
                 const int c = w / kSliceSplit, r = w - c * kSliceSplit;
                 const int t = c / d, a = c - t * d;
+                // (idle lanes parked zeros, so every stretch is summed in full: a fixed trip count lets the reads
+                // be issued together)
+                const float *src = park + t * kParkStep + a * kParkRow + r * (stretch + 1);
                 float sum = 0.0f;
-                const int q_end = (r + 1) * stretch < lanes ? (r + 1) * stretch : lanes;
-                for (int q = r * stretch; q < q_end; ++q) sum += park[(t * kSliceLanes + q) * d + a];
+#pragma unroll
+                for (int q = 0; q < stretch; ++q) sum += src[q];
                 red[w] = sum;
             }
             __syncthreads();
@@ -751,7 +780,7 @@ template <int d>
 int64_t backward_sliced_bytes_with(int64_t L, int ts)
 {
     const int64_t tile = ((L - 1) * d + 3) / 4 * 4;
-    return (tile + (int64_t)ts * kSliceLanes * d + (int64_t)ts * d * kSliceSplit) * (int64_t)sizeof(float);
+    return (tile + (int64_t)ts * slice_park_floats<d>() + (int64_t)ts * d * kSliceSplit) * (int64_t)sizeof(float);
 }
 
 // parked steps for a path of L points: as many as fit beside the path's increments, at least one (0: does not fit)
@@ -813,7 +842,7 @@ template <int d, int N, int P>
 int64_t backward_lds_bytes(int64_t L, int groups)
 {
     const int64_t tile = ((int64_t)groups * (L - 1) * d + 3) / 4 * 4;
-    const int64_t park = (int64_t)groups * reduce_steps<d, P>() * Shape<d, N, P>::Q * d;
+    const int64_t park = (int64_t)groups * reduce_steps<d, P>() * Park<d, P>::kStepFloats;
     return (tile + park) * (int64_t)sizeof(float);
 }
 
