@@ -179,12 +179,17 @@ int sig_combine(sig_ctx *ctx, const float *a, const float *b, int64_t B, int d, 
  *   grad_out     DEVICE, float32, d(loss)/d(out), same shape as out, read only
  *   grad_path    DEVICE, float32 [B][L][d], fully overwritten; must not overlap the inputs
  * Same conventions and status codes as sig_compute (B == 0 returns SIG_OK and launches nothing).  Shapes with a
- * compiled register kernel (see sig_backward_available) whose paths fit its LDS staging take it; every other
- * shape with d <= 256 takes a general sweep, one workgroup per path with its state in LDS or device scratch
- * (much slower); SIG_ERR_UNSUPPORTED only for d > 256.
+ * compiled register kernel (see sig_backward_available) whose paths fit its LDS staging take it.  In final mode,
+ * few long paths (fewer workgroups than compute units, from 128 increments on; from 2,048 for shapes with at most
+ * 32 lanes per path) and paths too long for that staging are cut into up to 32 time segments that are swept by
+ * different workgroups: by Eq. 3 a segment can start from the signature of the path up to its end and the gradient
+ * with respect to it, which a scan over the segments' own signatures provides.  Every other shape with d <= 256
+ * takes a general sweep, one workgroup per path with its state in LDS or device scratch (much slower);
+ * SIG_ERR_UNSUPPORTED only for d > 256.
  * Context scratch (allocated on first use, SIG_ERR_ALLOC if that fails): shapes whose index space is cut into more
  * sub-trees than one workgroup has threads keep per-workgroup sums (B * ceil(d^p / 256) * (L-1) * d floats); the
- * general sweep keeps B * (L-1) * d floats plus, when they exceed 48 KB per path, about 2.5 D floats per path.
+ * sweep cut into W segments keeps those sums and 5 * B * W * D floats of segment rows; the general sweep keeps
+ * B * (L-1) * d floats plus, when they exceed 48 KB per path, about 2.5 D floats per path.
  * Deterministic (fixed summation order).  Arithmetic is float32 with FMA.
  */
 int sig_backward(sig_ctx *ctx, const float *path, int64_t B, int64_t L, int d, int depth, int stream_flag,

@@ -775,7 +775,21 @@ int sig_backward(sig_ctx *ctx, const float *path, int64_t B, int64_t L, int d, i
     if (rc != SIG_OK) return rc;
     if (B == 0) return SIG_OK;
     if (!path || !out || !grad_out || !grad_path) return SIG_ERR_INVALID;
-    if (!backward_available(d, depth) || !backward_fits(d, depth, L)) {
+    const bool fits = backward_available(d, depth) && backward_fits(d, depth, L);
+    if (!stream_flag && backward_available(d, depth)) {
+        // few long paths (or paths too long for the LDS of the uncut sweep): the sweep cut in time across workgroups
+        const int segs = backward_segments(d, depth, B, L, ctx->num_cu, fits);
+        if (segs > 1) {
+            const int64_t need = backward_segmented_scratch_floats(d, depth, B, L, segs);
+            if (need <= 0 || need > (int64_t)1 << 36) return SIG_ERR_TOO_LARGE;
+            rc = ensure_scratch(ctx, (size_t)need * sizeof(float));
+            if (rc != SIG_OK) return rc;
+            hipError_t es = launch_backward_segmented(path, out, grad_out, grad_path, ctx->scratch, B, L, d, depth, segs,
+                                                      (hipStream_t)hip_stream);
+            return es == hipSuccess ? SIG_OK : SIG_ERR_HIP;
+        }
+    }
+    if (!fits) {
         // no register kernel for this shape, or the path is too long for its LDS staging: the general sweep
         if (!backward_general_available(d) || B > INT32_MAX) return SIG_ERR_UNSUPPORTED;
         const int64_t need = backward_general_scratch_floats(B, L, rs);

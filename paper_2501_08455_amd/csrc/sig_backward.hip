@@ -25,178 +25,10 @@
 //     d(loss)/dX_j = d/d(dX_{j-1}) - d/d(dX_j) with consecutive threads on consecutive floats.
 //   * Stream mode: row k of the output is S_k, so its upstream gradient is added to A when the sweep reaches
 //     k (prefix words by the one lane of each prefix whose remaining letters are 0).
-#include "sig_internal.h"
-#include "sig_onchip.h"
+#include "sig_backward.h"
 
 namespace sig {
 namespace onchip {
-
-// value / reference of the lane's copy of the prefix word u_{1:m}, m = 1 .. P (u itself is s[0])
-template <int m, int d, int N, int P>
-__device__ __forceinline__ float prefix_value(const Lane<d, N, P> &x)
-{
-    if constexpr (m < P) return x.pre[m - 1];
-    else return x.s[0];
-}
-template <int m, int d, int N, int P>
-__device__ __forceinline__ float &prefix_ref(Lane<d, N, P> &x)
-{
-    if constexpr (m < P) return x.pre[m - 1];
-    else return x.s[0];
-}
-
-// Transposed chain n inside a lane's sub-tree.  The node has index idx in sub-level r and forward chain
-// value g; returns the adjoint of g.  s = S_{k-1} (read only), ad = adjoint (updated in place),
-// dbar[a] accumulates d(loss)/dv[a].
-template <int d, int N, int P, int n, int r>
-struct Ascend {
-    using Sh = Shape<d, N, P>;
-    static __device__ __forceinline__ float run(const float (&s)[Sh::SZ], float (&ad)[Sh::SZ],
-                                                const float (&dls)[Sh::R][d], float (&dbar)[d], float g, int idx)
-    {
-        constexpr int tgt = n - P;  // sub-level of the chain's target
-        constexpr int m = r + 1;    // sub-level of this node's children
-        float gb = 0.0f;
-        if constexpr (m == tgt) {
-#pragma unroll
-            for (int a = 0; a < d; ++a) {
-                const float up = ad[Sh::sub_off(tgt) + idx * d + a];
-                gb = fmaf(up, dls[0][a], gb);
-                dbar[a] = fmaf(up, g, dbar[a]);
-            }
-        } else {
-            constexpr int c = tgt - r;  // the forward step divides v by this on the way to the children
-            const float gs = g * (1.0f / (float)c);
-#pragma unroll
-            for (int a = 0; a < d; ++a) {
-                const int child = idx * d + a;
-                const float gc = fmaf(g, dls[c - 1][a], s[Sh::sub_off(m) + child]);
-                const float cb = Ascend<d, N, P, n, m>::run(s, ad, dls, dbar, gc, child);
-                ad[Sh::sub_off(m) + child] += cb;
-                gb = fmaf(cb, dls[c - 1][a], gb);
-                dbar[a] = fmaf(cb, gs, dbar[a]);
-            }
-        }
-        return gb;
-    }
-};
-
-// Transpose of the fused step: ln = S_{k-1}, ad = A_k on entry and A_{k-1} on return; dbar (zeroed here)
-// receives this lane's part of d(loss)/dv.
-template <int d, int N, int P>
-__device__ __forceinline__ void backward_step(const Lane<d, N, P> &ln, Lane<d, N, P> &ad, const Inc<d, P> &inc,
-                                              const int *letter, float (&dbar)[d])
-{
-    using Sh = Shape<d, N, P>;
-    float dls[Sh::R][d];
-#pragma unroll
-    for (int a = 0; a < d; ++a) dls[0][a] = inc.v[a];
-#pragma unroll
-    for (int c = 1; c < Sh::R; ++c)
-#pragma unroll
-        for (int a = 0; a < d; ++a) dls[c][a] = inc.v[a] * (1.0f / (float)(c + 1));
-#pragma unroll
-    for (int a = 0; a < d; ++a) dbar[a] = 0.0f;
-    float dbu[P > 0 ? P : 1];  // adjoint of inc.du[m-1] = v[u_m]
-#pragma unroll
-    for (int m = 0; m < (P > 0 ? P : 1); ++m) dbu[m] = 0.0f;
-
-    static_for<1, N + 1>([&](auto nc) __attribute__((always_inline)) {
-        constexpr int n = decltype(nc)::value;
-        constexpr int mtop = (n - 1 < P) ? n - 1 : P;
-        // forward values of the chain along the lane's own prefix
-        float gp[P + 1];
-        gp[0] = 1.0f;
-        static_for<1, mtop + 1>([&](auto mc) __attribute__((always_inline)) {
-            constexpr int m = decltype(mc)::value;
-            gp[m] = fmaf(gp[m - 1], inc.du[m - 1] * (1.0f / (float)(n - m + 1)), prefix_value<m>(ln));
-        });
-        float gb;  // adjoint of gp[mtop]
-        if constexpr (n <= P) {
-            const float up = prefix_value<n>(ad);
-            gb = up * inc.du[n - 1];
-            dbu[n - 1] = fmaf(up, gp[n - 1], dbu[n - 1]);
-        } else {
-            gb = Ascend<d, N, P, n, 0>::run(ln.s, ad.s, dls, dbar, gp[P], 0);
-        }
-        static_for<0, mtop>([&](auto qc) __attribute__((always_inline)) {
-            constexpr int m = mtop - decltype(qc)::value;  // mtop .. 1
-            prefix_ref<m>(ad) += gb;
-            constexpr float c = 1.0f / (float)(n - m + 1);
-            dbu[m - 1] = fmaf(gb * c, gp[m - 1], dbu[m - 1]);
-            gb = gb * (inc.du[m - 1] * c);
-        });
-    });
-    // v[u_m] is component letter[m-1] of v
-    static_for<0, P>([&](auto mc) __attribute__((always_inline)) {
-        constexpr int m = decltype(mc)::value;
-#pragma unroll
-        for (int a = 0; a < d; ++a) dbar[a] += (letter[m] == a) ? dbu[m] : 0.0f;
-    });
-}
-
-// ad (+)= row, laid out like an output row; the prefix words are taken by the lane whose remaining letters are 0
-template <int d, int N, int P, bool ADD>
-__device__ __forceinline__ void load_adjoint(const float *row, unsigned u, Lane<d, N, P> &ad)
-{
-    using Sh = Shape<d, N, P>;
-    static_for<(P == 0 ? 1 : 0), Sh::R + 1>([&](auto rc) __attribute__((always_inline)) {
-        constexpr int r = decltype(rc)::value;
-        constexpr int cnt = cpow(d, r);
-        const float *src = row + Sh::row_off(P + r) + u * cnt;
-#pragma unroll
-        for (int i = 0; i < cnt; ++i) {
-            if constexpr (ADD) ad.s[Sh::sub_off(r) + i] += src[i];
-            else ad.s[Sh::sub_off(r) + i] = src[i];
-        }
-    });
-    if constexpr (P == 0 && !ADD) ad.s[0] = 0.0f;
-    static_for<1, P>([&](auto mc) __attribute__((always_inline)) {
-        constexpr int m = decltype(mc)::value;
-        constexpr unsigned span = cpow(d, P - m);
-        float g = 0.0f;
-        if (u % span == 0) g = row[Sh::row_off(m) + u / span];
-        if constexpr (ADD) ad.pre[m - 1] += g;
-        else ad.pre[m - 1] = g;
-    });
-}
-
-struct BackwardArgs {
-    const float *path;      // [B][L][d]
-    const float *sig;       // the forward result: [B][D] or [B][K][D]
-    const float *grad_out;  // same shape as sig
-    float *grad_path;       // [B][L][d]
-    int64_t B, L;
-    int32_t groups;         // paths per workgroup
-    int32_t stream_flag;
-};
-
-// steps whose partial sums are parked before they are added up: enough for every lane of a path to have a
-// column (Q / d), but no more than eight (the parked sums take TS * Park::kStepFloats floats of LDS per path)
-template <int d, int P>
-constexpr int reduce_steps()
-{
-    const int want = cpow(d, P) / d;
-    return want < 1 ? 1 : (want > 8 ? 8 : want);
-}
-
-// Layout of the parked sums of a path.  As [step][lane][channel] a lane's d sums are d floats from its neighbour's,
-// so the lanes of a wavefront write to 32 / gcd(d, 32) of the 32 LDS banks: all of them for odd d, half for d = 2, 6,
-// 10, but only eight for d = 4 and four for d = 8.  Those shapes keep the sums as [step][channel][lane] with rows of
-// an odd number of floats: the lanes' writes (consecutive lanes, one row) and the column sums' reads (consecutive
-// rows, one lane) then both spread over the banks (measured: d = 8, depth 3, 1.6x; d = 4, depth 4, 1.3x on
-// saturated batches; for the other channel counts the change is within a few percent either way).
-template <int d, int P>
-struct Park {
-    static constexpr int Q = cpow(d, P);
-    static constexpr bool kByChannel = d % 4 == 0;
-    static constexpr int kRow = Q | 1;
-    static constexpr int kStepFloats = kByChannel ? d * kRow : d * Q;
-    // sum of lane u for channel a in parked step t
-    static __device__ __forceinline__ int at(int t, int u, int a) { return kByChannel ? (t * d + a) * kRow + u : (t * Q + u) * d + a; }
-};
-
-extern __shared__ float sig_backward_smem[];
 
 template <int d, int N, int P, bool STREAM>
 __global__ __launch_bounds__(256) void sig_backward_kernel(BackwardArgs A)
@@ -628,135 +460,7 @@ __global__ __launch_bounds__(256) void sig_backward_chunked_kernel(BackwardArgs 
     }
 }
 
-// ---------------------------------------------------------------------------------------------------------
-// Sliced sweep: shapes whose d^P lanes per path exceed one workgroup.  A workgroup takes one path and one slice
-// of up to 256 of its lanes; nothing crosses lanes in the sweep itself, only d(loss)/dv of a step is a sum over
-// all lanes of the path.  Each slice adds up its own lanes (parked partial sums, two-stage column sums in a
-// fixed order) over the increment the sum belongs to, writes its K * d partial sums to `part`, and a second
-// launch adds the slices in order and forms d(loss)/dX.
-constexpr int kSliceLanes = 256;
-constexpr int kSliceSplit = 8;   // a parked column is summed in this many stretches of lanes first
-
-template <int d>
-constexpr int slice_reduce_steps()
-{
-    const int fit = 8192 / (kSliceLanes * d);   // parked sums take TS * 256 * d floats of LDS
-    return fit < 1 ? 1 : (fit > 8 ? 8 : fit);
-}
-
-// Parked sums of one step: [channel][lane], lane q at q + q / 32.  Consecutive lanes write consecutive banks, and
-// the extra float per stretch of 32 lanes puts the stretches, which are read side by side when a column is summed,
-// in different LDS banks (32 floats apart they would all start in the same one).
-constexpr int kParkRow = kSliceLanes + kSliceLanes / 32;
-template <int d>
-constexpr int slice_park_floats() { return d * kParkRow; }
-
-template <int d, int N, int P, bool STREAM>
-__global__ __launch_bounds__(kSliceLanes) void sig_backward_sliced_kernel(BackwardArgs A, float *part, int TS)
-{
-    // TS: steps whose partial sums are parked before they are added up (at most slice_reduce_steps<d>(); fewer
-    // when a long path leaves less LDS)
-    using Sh = Shape<d, N, P>;
-    constexpr int Q = Sh::Q;
-    constexpr int D = Sh::D;
-    constexpr int slices = (Q + kSliceLanes - 1) / kSliceLanes;
-    constexpr int kParkStep = slice_park_floats<d>();
-    const int tid = threadIdx.x, nthr = blockDim.x;
-    const int64_t K = A.L - 1;
-    const int slice = (int)(blockIdx.x % slices);
-    const int64_t b = blockIdx.x / slices;
-    const unsigned u_raw = (unsigned)(slice * kSliceLanes + tid);
-    const bool active = u_raw < (unsigned)Q;
-    const unsigned u = active ? u_raw : 0u;
-
-    int letter[P > 0 ? P : 1];
-    letter[0] = 0;
-    {
-        unsigned rest = u;
-#pragma unroll
-        for (int m = P - 1; m >= 0; --m) { letter[m] = (int)(rest % d); rest /= d; }
-    }
-
-    // LDS: increments [K*d] (overwritten with this slice's sums), parked partial sums [TS][d][kParkRow], stretch sums
-    const int row_floats = (int)K * d;
-    float *tile = sig_backward_smem;
-    float *park = tile + (row_floats + 3) / 4 * 4;
-    float *red = park + TS * kParkStep;
-    {
-        const float *x = A.path + b * A.L * d;
-        for (int i = tid; i < row_floats; i += nthr) tile[i] = x[i + d] - x[i];
-    }
-
-    Lane<d, N, P> ln, ad;
-    identity_state<d, N, P>(ln);
-    identity_state<d, N, P>(ad);
-    if (P == 0) ad.s[0] = 0.0f;
-    if (active) {
-        const float *srow = STREAM ? A.sig + (b * K + (K - 1)) * D : A.sig + b * D;
-        load_state<d, N, P>(srow, u, ln);
-        if constexpr (!STREAM) load_adjoint<d, N, P, false>(A.grad_out + b * D, u, ad);
-    }
-    __syncthreads();
-
-    Lane<d, N, P> up;   // upstream gradient of the row the sweep reaches next (stream mode), fetched one step ahead
-    if constexpr (STREAM) {
-        identity_state<d, N, P>(up);
-        if (P == 0) up.s[0] = 0.0f;
-        if (active) load_adjoint<d, N, P, false>(A.grad_out + (b * K + (K - 1)) * D, u, up);
-    }
-    for (int64_t k = K - 1; k >= 0; --k) {
-        const int ts = (int)((K - 1 - k) % TS);
-        if constexpr (STREAM) {
-#pragma unroll
-            for (int i = 0; i < Sh::SZ; ++i) ad.s[i] += up.s[i];
-#pragma unroll
-            for (int i = 0; i < Sh::NPRE; ++i) ad.pre[i] += up.pre[i];
-            if (active && k > 0) load_adjoint<d, N, P, false>(A.grad_out + (b * K + (k - 1)) * D, u, up);
-        }
-        Inc<d, P> inc, neg;
-        load_inc<d, P>(inc, tile + k * d, letter);
-#pragma unroll
-        for (int a = 0; a < d; ++a) neg.v[a] = -inc.v[a];
-        neg.du[0] = 0.0f;
-#pragma unroll
-        for (int m = 0; m < P; ++m) neg.du[m] = -inc.du[m];
-        if (k > 0) fused_step<d, N, P>(ln, neg);  // S_{k-1} = S_k (x) exp(-dX_k)
-        else identity_state<d, N, P>(ln);
-        float dbar[d];
-        backward_step<d, N, P>(ln, ad, inc, letter, dbar);
-#pragma unroll
-        for (int a = 0; a < d; ++a) park[ts * kParkStep + a * kParkRow + tid + (tid >> 5)] = active ? dbar[a] : 0.0f;
-        if (ts == TS - 1 || k == 0) {
-            __syncthreads();
-            // column c = (parked step t, channel a), first in kSliceSplit stretches of lanes, then the stretches
-            const int cols = (ts + 1) * d;
-            constexpr int stretch = kSliceLanes / kSliceSplit;
-            static_assert(stretch == 32, "the parked layout pads one float per 32 lanes");
-            for (int w = tid; w < cols * kSliceSplit; w += nthr) {
-                const int c = w / kSliceSplit, r = w - c * kSliceSplit;
-                const int t = c / d, a = c - t * d;
-                // (idle lanes parked zeros, so every stretch is summed in full: a fixed trip count lets the reads
-                // be issued together)
-                const float *src = park + t * kParkStep + a * kParkRow + r * (stretch + 1);
-                float sum = 0.0f;
-#pragma unroll
-                for (int q = 0; q < stretch; ++q) sum += src[q];
-                red[w] = sum;
-            }
-            __syncthreads();
-            for (int c = tid; c < cols; c += nthr) {
-                const int t = c / d, a = c - t * d;
-                float sum = 0.0f;
-#pragma unroll
-                for (int r = 0; r < kSliceSplit; ++r) sum += red[c * kSliceSplit + r];
-                tile[(k + (ts - t)) * d + a] = sum;   // replaces the increment, which no lane reads again
-            }
-            __syncthreads();
-        }
-    }
-    float *dst = part + (b * slices + slice) * row_floats;
-    for (int i = tid; i < row_floats; i += nthr) dst[i] = tile[i];
-}
+}  // namespace onchip
 
 // d(loss)/dX_j = sum over the slices, in order, of (d/d(dX_{j-1}) - d/d(dX_j))
 __global__ __launch_bounds__(256) void sig_backward_slices_finish_kernel(const float *part, float *grad_path, int64_t B,
@@ -776,21 +480,17 @@ __global__ __launch_bounds__(256) void sig_backward_slices_finish_kernel(const f
     grad_path[e] = sum;
 }
 
-template <int d>
-int64_t backward_sliced_bytes_with(int64_t L, int ts)
+hipError_t launch_backward_finish(const float *part, float *grad_path, int64_t B, int64_t L, int d, int slices,
+                                  hipStream_t st)
 {
-    const int64_t tile = ((L - 1) * d + 3) / 4 * 4;
-    return (tile + (int64_t)ts * slice_park_floats<d>() + (int64_t)ts * d * kSliceSplit) * (int64_t)sizeof(float);
+    const int64_t blocks = (B * L * d + 255) / 256;
+    if (blocks <= 0 || blocks > INT32_MAX) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(sig_backward_slices_finish_kernel, dim3((unsigned)blocks), dim3(256), 0, st, part, grad_path, B, L,
+                       d, slices);
+    return hipGetLastError();
 }
 
-// parked steps for a path of L points: as many as fit beside the path's increments, at least one (0: does not fit)
-template <int d>
-int backward_sliced_steps(int64_t L)
-{
-    int ts = slice_reduce_steps<d>();
-    while (ts > 1 && backward_sliced_bytes_with<d>(L, ts) > kMaxLdsBytes) --ts;
-    return backward_sliced_bytes_with<d>(L, ts) <= kMaxLdsBytes ? ts : 0;
-}
+namespace onchip {
 
 // LDS of the launch (what backward_fits compares with the limit): with the fewest parked steps if need be
 template <int d, int N, int P>
@@ -821,12 +521,7 @@ hipError_t backward_sliced_launch(const BackwardArgs &A, float *scratch, int, in
         hipLaunchKernelGGL((sig_backward_sliced_kernel<d, N, P, false>), dim3((unsigned)grid), dim3(kSliceLanes), (size_t)lds, st, A, scratch, ts);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    const int64_t total = A.B * A.L * d;
-    const int64_t blocks = (total + 255) / 256;
-    if (blocks > INT32_MAX) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(sig_backward_slices_finish_kernel, dim3((unsigned)blocks), dim3(256), 0, st, (const float *)scratch,
-                       A.grad_path, A.B, A.L, d, slices);
-    return hipGetLastError();
+    return launch_backward_finish(scratch, A.grad_path, A.B, A.L, d, slices, st);
 }
 
 template <int d, int N, int P>
@@ -900,25 +595,12 @@ struct BackwardEntry {
     int64_t (*scratch_floats)(int64_t, int64_t);
 };
 #define SIG_BACKWARD_ENTRY(d, N, P) \
-    {d, N, &onchip::backward_launch<d, N, P>, &onchip::backward_lds_bytes<d, N, P>, &onchip::backward_no_scratch<d, N, P>}
+    {d, N, &onchip::backward_launch<d, N, P>, &onchip::backward_lds_bytes<d, N, P>, &onchip::backward_no_scratch<d, N, P>},
 #define SIG_BACKWARD_SLICED(d, N, P)                                                                  \
     {d, N, &onchip::backward_sliced_launch<d, N, P>, &onchip::backward_sliced_lds_bytes<d, N, P>, \
-     &onchip::backward_sliced_scratch_floats<d, N, P>}
-// one prefix depth per (d, depth): the one whose two lane states (S and its adjoint) fit the registers; shapes
-// whose lanes per path exceed a workgroup take the sliced sweep
+     &onchip::backward_sliced_scratch_floats<d, N, P>},
 const BackwardEntry kBackward[] = {
-    SIG_BACKWARD_ENTRY(2, 2, 1), SIG_BACKWARD_ENTRY(3, 2, 1), SIG_BACKWARD_ENTRY(4, 2, 1), SIG_BACKWARD_ENTRY(5, 2, 1),
-    SIG_BACKWARD_ENTRY(6, 2, 1), SIG_BACKWARD_ENTRY(8, 2, 1), SIG_BACKWARD_ENTRY(10, 2, 1),
-    SIG_BACKWARD_ENTRY(2, 3, 1), SIG_BACKWARD_ENTRY(3, 3, 1), SIG_BACKWARD_ENTRY(4, 3, 1), SIG_BACKWARD_ENTRY(5, 3, 1),
-    SIG_BACKWARD_ENTRY(6, 3, 1), SIG_BACKWARD_ENTRY(7, 3, 1), SIG_BACKWARD_ENTRY(8, 3, 2), SIG_BACKWARD_ENTRY(10, 3, 2),
-    SIG_BACKWARD_ENTRY(2, 4, 1), SIG_BACKWARD_ENTRY(3, 4, 1), SIG_BACKWARD_ENTRY(4, 4, 2), SIG_BACKWARD_ENTRY(5, 4, 2),
-    SIG_BACKWARD_ENTRY(6, 4, 2), SIG_BACKWARD_ENTRY(7, 4, 2),
-    SIG_BACKWARD_ENTRY(2, 5, 1), SIG_BACKWARD_ENTRY(3, 5, 2), SIG_BACKWARD_ENTRY(4, 5, 3), SIG_BACKWARD_ENTRY(5, 5, 3),
-    SIG_BACKWARD_ENTRY(2, 6, 1), SIG_BACKWARD_ENTRY(3, 6, 3),
-    SIG_BACKWARD_SLICED(8, 4, 3), SIG_BACKWARD_SLICED(10, 4, 3), SIG_BACKWARD_SLICED(6, 5, 3), SIG_BACKWARD_SLICED(4, 6, 4),
-    SIG_BACKWARD_SLICED(5, 6, 4), SIG_BACKWARD_SLICED(10, 6, 4),
-    SIG_BACKWARD_ENTRY(7, 2, 1), SIG_BACKWARD_ENTRY(9, 2, 1), SIG_BACKWARD_ENTRY(9, 3, 2), SIG_BACKWARD_SLICED(9, 4, 3),
-    SIG_BACKWARD_SLICED(7, 5, 3), SIG_BACKWARD_SLICED(8, 5, 3), SIG_BACKWARD_SLICED(9, 5, 3), SIG_BACKWARD_SLICED(10, 5, 3),
+    SIG_BACKWARD_SHAPES(SIG_BACKWARD_ENTRY, SIG_BACKWARD_SLICED)
     {0, 0, nullptr, nullptr, nullptr},
 };
 const BackwardEntry *find_backward(int d, int depth)

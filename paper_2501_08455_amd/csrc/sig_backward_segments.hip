@@ -1,0 +1,320 @@
+// Gradient of the final signature with respect to the path, cut in time across workgroups: few long paths.
+//
+// The reverse sweep (see sig_backward.hip) walks the K increments of a path one after the other, and a workgroup
+// per path (and slice of its lanes) leaves most of the chip idle when there are few paths.  Chen's relation (paper
+// Eq. 3: the signature of a concatenation is the product of the signatures) lets the sweep start anywhere: segment
+// s of W, the increments [s T, (s + 1) T), needs the signature S_end(s) of the path up to its end and the gradient
+// A_end(s) of the loss with respect to that signature.  With E_s the signature of segment s alone,
+//     S_end(s) = E_0 (x) ... (x) E_s,
+//     A_end(s)[u] = sum_x d(loss)/d(out)[(u, x)] Y_{s+1}[x],      Y_s = E_s (x) ... (x) E_{W-1}
+// (the transpose of the product of Eq. 4 with respect to its left factor; x runs over all words including the empty
+// one, whose coefficient is 1).  The launches:
+//   1. every (path, segment) folds its increments from the identity: E_s                          (T steps)
+//   2. ceil(log2 W) rounds of a scan give all prefix products S_end(s) and all suffix products Y_s at once
+//   3. every segment pulls the upstream gradient back through Y_{s+1}: A_end(s)
+//   4. every (path, segment, slice of lanes) runs the reverse sweep over its own increments       (T steps)
+//   5. the per-slice sums of d(loss)/d(increment) are added up and differenced into d(loss)/dX.
+// Launches 4 and 5 are the sliced sweep's (sig_backward.h); shapes whose lanes fit one workgroup run as one slice.
+#include "sig_backward.h"
+
+namespace sig {
+namespace onchip {
+
+// 1. E[(b, s)] = signature of segment s of path b alone
+template <int d, int N, int P>
+__global__ __launch_bounds__(kSliceLanes) void sig_backward_segment_fold_kernel(const float *path, float *E, int64_t L,
+                                                                                int W, int T)
+{
+    using Sh = Shape<d, N, P>;
+    constexpr int Q = Sh::Q;
+    constexpr int D = Sh::D;
+    constexpr int slices = (Q + kSliceLanes - 1) / kSliceLanes;
+    const int tid = threadIdx.x, nthr = blockDim.x;
+    const int slice = (int)(blockIdx.x % slices);
+    const int64_t piece = blockIdx.x / slices;
+    const int64_t b = piece / W;
+    const int seg = (int)(piece - b * W);
+    const int64_t k0 = (int64_t)seg * T;
+    int64_t K = L - 1 - k0;
+    if (K > T) K = T;
+    if (K < 0) K = 0;
+    const unsigned u_raw = (unsigned)(slice * kSliceLanes + tid);
+    const bool active = u_raw < (unsigned)Q;
+    const unsigned u = active ? u_raw : 0u;
+
+    int letter[P > 0 ? P : 1];
+    letter[0] = 0;
+    {
+        unsigned rest = u;
+#pragma unroll
+        for (int m = P - 1; m >= 0; --m) { letter[m] = (int)(rest % d); rest /= d; }
+    }
+
+    float *tile = sig_backward_smem;   // [K][d] increments
+    {
+        const float *x = path + (b * L + k0) * d;
+        for (int i = tid; i < (int)K * d; i += nthr) tile[i] = x[i + d] - x[i];
+    }
+    __syncthreads();
+    Lane<d, N, P> ln;
+    identity_state<d, N, P>(ln);
+    for (int k = 0; k < (int)K; ++k) {
+        Inc<d, P> inc;
+        load_inc<d, P>(inc, tile + k * d, letter);
+        fused_step<d, N, P>(ln, inc);
+    }
+    if (active) store_state<d, N, P>(E + piece * D, u, ln);
+}
+
+// out[u] = sum over the words x (the empty one included) of A[(u, x)] E[x] on rows of D floats: the transpose of
+// c = a (x) E (Eq. 4) with respect to a.  Word v of level j collects A_n[v d^{n-j} + x] E_{n-j}[x] for every deeper
+// level n: a wavefront per word where that is 128 terms or more (lanes stride over the terms, fixed-order butterfly
+// sum), a thread per word otherwise.  Called by `threads` threads numbered tid = 0 .. threads - 1 in whole
+// wavefronts (they may belong to several workgroups); out may not overlap A.
+template <int d, int N>
+__device__ __forceinline__ void row_adjoint_product(const float *A, const float *E, float *out, int tid, int threads)
+{
+    using Sh = Shape<d, N, 0>;
+    const int lane = tid & (kWave - 1), wave = tid / kWave;
+    const int waves = threads / kWave;
+    static_for<1, N + 1>([&](auto jc) __attribute__((always_inline)) {
+        constexpr int j = decltype(jc)::value;
+        constexpr int cnt = cpow(d, j);
+        constexpr int terms = geom(d, N - j + 1) - 1;   // d + ... + d^{N-j}
+        if constexpr (terms >= 128) {
+            for (int v = wave; v < cnt; v += waves) {
+                float acc = 0.0f;
+                static_for<j + 1, N + 1>([&](auto nc) __attribute__((always_inline)) {
+                    constexpr int n = decltype(nc)::value;
+                    constexpr int run = cpow(d, n - j);
+                    const float *a = A + Sh::row_off(n) + (int64_t)v * run;
+                    const float *e = E + Sh::row_off(n - j);
+                    // (a fixed trip count, so that the loads of several rounds are in flight together)
+                    constexpr int rounds = (run + kWave - 1) / kWave;
+#pragma unroll 8
+                    for (int i = 0; i < rounds; ++i) {
+                        const int x = lane + i * kWave;
+                        if (x < run) acc = fmaf(a[x], e[x], acc);
+                    }
+                });
+#pragma unroll
+                for (int off = kWave / 2; off >= 1; off >>= 1) acc += __shfl_xor(acc, off, kWave);
+                if (lane == 0) out[Sh::row_off(j) + v] = A[Sh::row_off(j) + v] + acc;
+            }
+        } else {
+            for (int v = tid; v < cnt; v += threads) {
+                float acc = A[Sh::row_off(j) + v];
+                static_for<j + 1, N + 1>([&](auto nc) __attribute__((always_inline)) {
+                    constexpr int n = decltype(nc)::value;
+                    constexpr int run = cpow(d, n - j);
+                    const float *a = A + Sh::row_off(n) + (int64_t)v * run;
+                    const float *e = E + Sh::row_off(n - j);
+#pragma unroll
+                    for (int x = 0; x < run; ++x) acc = fmaf(a[x], e[x], acc);
+                });
+                out[Sh::row_off(j) + v] = acc;
+            }
+        }
+    });
+}
+
+// 2. One round of both scans over the W rows of a path (ping-pong buffers):
+//    blockIdx.y = 0: Sout[s] = Sin[s - off] (x) Sin[s] for s >= off, else Sin[s]      (prefix products)
+//    blockIdx.y = 1: Yout[s] = Yin[s] (x) Yin[s + off] for s + off < W, else Yin[s]   (suffix products)
+//    row_workgroups<d, N>() workgroups (blockIdx.z) share a row; the rows stay in device memory.
+template <int d, int N>
+constexpr int row_workgroups()
+{
+    const int want = RowProduct<d, N>::ITEMS / 256;   // about one parent word per thread: the products are bound by
+                                                      // the latency of their loads, not by arithmetic
+    return want < 1 ? 1 : (want > 32 ? 32 : want);
+}
+
+template <int d, int N>
+__global__ __launch_bounds__(256) void sig_backward_segment_scan_kernel(const float *Sin, float *Sout, const float *Yin,
+                                                                        float *Yout, int W, int off)
+{
+    using RP = RowProduct<d, N>;
+    constexpr int D = Shape<d, N, 0>::D;
+    constexpr int threads = 256 * row_workgroups<d, N>();
+    const int tid = (int)(blockIdx.z * 256 + threadIdx.x);
+    const int64_t piece = blockIdx.x;
+    const int s = (int)(piece % W);
+    const bool prefix = blockIdx.y == 0;
+    const float *in = prefix ? Sin : Yin;
+    float *out = (prefix ? Sout : Yout) + piece * D;
+    const float *self = in + piece * D;
+    const bool joined = prefix ? s >= off : s + off < W;
+    if (!joined) {
+        for (int x = tid; x < D; x += threads) out[x] = self[x];
+        return;
+    }
+    const float *left = prefix ? in + (piece - off) * D : self;
+    const float *right = prefix ? self : in + (piece + off) * D;
+    for (int x = tid; x < RP::ITEMS; x += threads) RP::item(left, right, out, x);
+}
+
+// 3. A_end(s) = d(loss)/d(out) pulled back through Y_{s+1}, s = 0 .. W-2 (row W-1 is not written: the last segment
+//    starts from the upstream gradient itself)
+template <int d, int N>
+__global__ __launch_bounds__(256) void sig_backward_segment_adjoint_kernel(const float *grad_out, const float *Y, float *Aend,
+                                                                           int W)
+{
+    constexpr int D = Shape<d, N, 0>::D;
+    const int64_t piece = blockIdx.x;
+    const int64_t b = piece / W;
+    const int s = (int)(piece - b * W);
+    if (s >= W - 1) return;
+    row_adjoint_product<d, N>(grad_out + b * D, Y + (piece + 1) * D, Aend + piece * D, (int)(blockIdx.z * 256 + threadIdx.x),
+                              256 * row_workgroups<d, N>());
+}
+
+template <int d, int N, int P>
+hipError_t backward_segmented_launch(const BackwardArgs &A0, float *scratch, int W, hipStream_t st)
+{
+    using Sh = Shape<d, N, P>;
+    constexpr int slices = (Sh::Q + kSliceLanes - 1) / kSliceLanes;
+    const int64_t K = A0.L - 1;
+    if (W < 2 || W > K || !scratch || A0.stream_flag) return hipErrorInvalidValue;
+    const int64_t T = (K + W - 1) / W;
+    W = (int)((K + T - 1) / T);   // no trailing segment without increments
+    if (W < 2) return hipErrorInvalidValue;
+    const int ts = backward_sliced_steps<d>(T + 1);
+    const int64_t lds = backward_sliced_bytes_with<d>(T + 1, ts > 0 ? ts : 1);
+    const int64_t grid = A0.B * W * slices;
+    if (ts < 1 || lds > kMaxLdsBytes || grid <= 0 || grid > INT32_MAX || A0.B > INT32_MAX) return hipErrorInvalidValue;
+    const int64_t rows = A0.B * W * Sh::D;
+    float *E = scratch, *S0 = E + rows, *S1 = S0 + rows, *Y0 = S1 + rows, *Y1 = Y0 + rows, *part = Y1 + rows;
+
+    hipLaunchKernelGGL((sig_backward_segment_fold_kernel<d, N, P>), dim3((unsigned)grid), dim3(kSliceLanes),
+                       (size_t)(T * d) * sizeof(float), st, A0.path, E, A0.L, W, (int)T);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const float *Sin = E, *Yin = E;
+    float *Sout = S0, *Yout = Y0;
+    for (int off = 1; off < W; off *= 2) {
+        hipLaunchKernelGGL((sig_backward_segment_scan_kernel<d, N>), dim3((unsigned)(A0.B * W), 2, row_workgroups<d, N>()), dim3(256), 0, st, Sin, Sout,
+                           Yin, Yout, W, off);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        Sin = Sout;
+        Yin = Yout;
+        Sout = Sout == S0 ? S1 : S0;
+        Yout = Yout == Y0 ? Y1 : Y0;
+    }
+    // the scan's last input buffer of the suffix products is free now: it takes the pulled-back gradients
+    float *Aend = Yout;
+    hipLaunchKernelGGL((sig_backward_segment_adjoint_kernel<d, N>), dim3((unsigned)(A0.B * W), 1, row_workgroups<d, N>()), dim3(256), 0, st, A0.grad_out,
+                       Yin, Aend, W);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    BackwardArgs A = A0;
+    A.segs = W;
+    A.seg_steps = (int32_t)T;
+    A.seg_sig = Sin;
+    A.seg_grad = Aend;
+    hipLaunchKernelGGL((sig_backward_sliced_kernel<d, N, P, false>), dim3((unsigned)grid), dim3(kSliceLanes), (size_t)lds, st, A,
+                       part, ts);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    return launch_backward_finish(part, A.grad_path, A.B, A.L, d, slices, st);
+}
+
+}  // namespace onchip
+
+namespace {
+
+// does a segment of T increments fit the LDS of the sweep?
+template <int d>
+bool segment_fits(int64_t T)
+{
+    return onchip::backward_sliced_steps<d>(T + 1) >= 1;
+}
+
+struct SegmentedEntry {
+    int d, depth;
+    int lanes;        // Q = d^P
+    int64_t row;      // D
+    hipError_t (*launch)(const onchip::BackwardArgs &, float *, int, hipStream_t);
+    bool (*fits)(int64_t);
+};
+#define SIG_SEGMENTED_ENTRY(d, N, P) \
+    {d, N, onchip::Shape<d, N, P>::Q, onchip::Shape<d, N, P>::D, &onchip::backward_segmented_launch<d, N, P>, &segment_fits<d>},
+const SegmentedEntry kSegmented[] = {
+    SIG_BACKWARD_SHAPES(SIG_SEGMENTED_ENTRY, SIG_SEGMENTED_ENTRY)
+    {0, 0, 0, 0, nullptr, nullptr},
+};
+
+const SegmentedEntry *find_segmented(int d, int depth)
+{
+    for (const SegmentedEntry *e = kSegmented; e->launch; ++e)
+        if (e->d == d && e->depth == depth) return e;
+    return nullptr;
+}
+
+constexpr int kMaxSegments = 32;
+constexpr int64_t kMaxSegmentFloats = 1 << 21;   // floats of the B * W rows of one scan buffer
+constexpr int64_t kMaxSegmentRow = 1 << 17;   // one workgroup forms a product of two rows: rows up to this many floats
+
+}  // namespace
+
+// Time segments for the final-mode sweep of B paths of L points (<= 1: do not cut).  Cutting pays when the uncut
+// launch leaves compute units without a workgroup and the path is long: the sequential part drops from K steps to
+// about K / W steps, for ceil(log2 W) + 3 more launches; W is taken so that a segment keeps about 24 increments and
+// limited to two workgroups per compute unit.  Shapes with 32 lanes or fewer per path are cut in time inside the
+// workgroup by the plain sweep (eight or more chunks side by side), which is as fast up to a few thousand increments.
+// A path whose increments do not fit the LDS of the uncut sweep (uncut_fits == false) is cut at any batch size, as
+// little as makes a segment fit.
+int backward_segments(int d, int depth, int64_t B, int64_t L, int cus, bool uncut_fits)
+{
+    const SegmentedEntry *e = find_segmented(d, depth);
+    if (!e || e->row > kMaxSegmentRow || B <= 0) return 1;
+    const int64_t K = L - 1;
+    const int64_t slices = (e->lanes + onchip::kSliceLanes - 1) / onchip::kSliceLanes;
+    const bool busy = B * slices >= cus;   // the uncut launch already has a workgroup for every compute unit
+    const int64_t min_steps = e->lanes * 8 <= onchip::kSliceLanes ? 2048 : 128;
+    if (uncut_fits && (K < min_steps || busy)) return 1;
+    int64_t W = 2;
+    if (!busy) {
+        W = K / 24;
+        if (W > kMaxSegments) W = kMaxSegments;
+        const int64_t room = (2 * (int64_t)cus) / (B * slices);
+        if (W > room) W = room;
+        // the scan reads and writes all B * W rows in every round: keep one set of rows within 8 MB
+        const int64_t by_rows = kMaxSegmentFloats / (B * e->row);
+        if (W > by_rows) W = by_rows;
+        if (W < 2) {
+            if (uncut_fits) return 1;
+            W = 2;
+        }
+    }
+    while (W <= kMaxSegments && W <= K && !e->fits((K + W - 1) / W)) ++W;
+    if (W > kMaxSegments || W > K || (K + W - 1) / W < 2) return 1;
+    return (int)W;
+}
+
+int64_t backward_segmented_scratch_floats(int d, int depth, int64_t B, int64_t L, int segs)
+{
+    const SegmentedEntry *e = find_segmented(d, depth);
+    if (!e || segs < 2) return 0;
+    const int64_t slices = (e->lanes + onchip::kSliceLanes - 1) / onchip::kSliceLanes;
+    return 5 * B * segs * e->row + B * slices * (L - 1) * d;
+}
+
+hipError_t launch_backward_segmented(const float *path, const float *sig, const float *grad_out, float *grad_path,
+                                     float *scratch, int64_t B, int64_t L, int d, int depth, int segs, hipStream_t st)
+{
+    const SegmentedEntry *e = find_segmented(d, depth);
+    if (!e) return hipErrorInvalidValue;
+    onchip::BackwardArgs A{};
+    A.path = path;
+    A.sig = sig;
+    A.grad_out = grad_out;
+    A.grad_path = grad_path;
+    A.B = B;
+    A.L = L;
+    A.stream_flag = 0;
+    return e->launch(A, scratch, segs, st);
+}
+
+}  // namespace sig

@@ -122,6 +122,33 @@ def test_backward_sliced_long_paths(gpu, oracle):
         check(gpu, oracle, x, depth, False, seed=L, label="sliced, long path")
 
 
+SEGMENTED_CASES = [
+    # d, depth, B, L: few long paths in final mode, which the library cuts in time across workgroups (segment
+    # signatures, their running products and pulled-back gradients, then one sweep per segment); lengths that leave
+    # a ragged last segment, both kernel families, one and several paths
+    (5, 4, 1, 1000), (5, 4, 3, 777), (2, 3, 2, 4001), (4, 4, 5, 500), (3, 5, 2, 600), (5, 5, 1, 300), (9, 3, 2, 450),
+    (6, 4, 1, 130), (7, 4, 2, 513), (8, 4, 1, 400), (10, 4, 3, 333), (6, 5, 1, 200), (4, 6, 2, 260), (9, 4, 1, 129),
+    (10, 5, 1, 150), (2, 6, 4, 2000),
+]
+
+
+@pytest.mark.parametrize("case", SEGMENTED_CASES, ids=lambda c: "-".join(str(v) for v in c))
+def test_backward_few_long_paths_cut_in_time(gpu, oracle, case):
+    d, depth, B, L = case
+    x = workloads.brownian_paths(B, L, d, seed=8500 + 3 * L + d)
+    check(gpu, oracle, x, depth, False, seed=L + depth, label="cut in time")
+
+
+def test_backward_cut_in_time_reproducible_and_next_to_uncut_calls(gpu, oracle):
+    """The segment rows live in context scratch: the same bits twice, with an uncut call and a stream call between."""
+    x = workloads.brownian_paths(2, 900, 5, seed=78)
+    a = check(gpu, oracle, x, 4, False, seed=5, label="cut in time, first")
+    check(gpu, oracle, x[:, :40], 4, False, seed=6, label="uncut call")
+    check(gpu, oracle, x[:1, :300], 4, True, seed=7, label="stream call")
+    b = check(gpu, oracle, x, 4, False, seed=5, label="cut in time, again")
+    np.testing.assert_array_equal(a, b)
+
+
 def test_backward_sliced_reproducible_and_after_a_larger_call(gpu, oracle):
     """The per-slice sums live in context scratch: a smaller call after a larger one, and the same bits twice."""
     x = workloads.brownian_paths(6, 30, 10, seed=77)
@@ -146,11 +173,12 @@ def test_backward_general_sweep(gpu, oracle, shape):
         check(gpu, oracle, x, depth, stream, seed=d + depth + L, label="general sweep")
 
 
-def test_backward_long_paths_take_the_general_sweep(gpu, oracle):
-    """Paths whose increments exceed the LDS staging of the register kernels (here 5,000 and 20,000 points in five
-    channels).  The sweep undoes one increment at a time in fp32, so its error grows with the length: measured
-    against the same 1e-4 gate."""
-    for B, L, stream in [(2, 5000, False), (1, 20000, False), (1, 4000, True)]:
+def test_backward_paths_too_long_for_one_workgroup(gpu, oracle):
+    """Paths whose increments exceed the LDS staging of the register kernels (here 3,500 to 20,000 points in five
+    channels): final mode cuts them into time segments (also when the batch alone would fill the chip: 300 paths),
+    stream mode takes the general sweep.  The sweep undoes one increment at a time in fp32, so its error grows with
+    the length: measured against the same 1e-4 gate."""
+    for B, L, stream in [(2, 5000, False), (1, 20000, False), (300, 3500, False), (1, 4000, True)]:
         x = workloads.brownian_paths(B, L, 5, seed=8300 + L)
         check(gpu, oracle, x, 4, stream, seed=L, label="long path")
 

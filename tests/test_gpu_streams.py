@@ -50,7 +50,8 @@ def test_backward_on_a_side_stream(gpu, oracle):
     side = torch.cuda.Stream()
     ctx = gpu.sig_create()
     try:
-        for d, depth, B, L in [(5, 4, 9, 60), (10, 4, 3, 20)]:   # the second shape takes the two-launch sliced sweep
+        # the second shape takes the two-launch sliced sweep, the third the sweep cut into time segments (nine launches)
+        for d, depth, B, L in [(5, 4, 9, 60), (10, 4, 3, 20), (8, 4, 2, 300)]:
             x = workloads.brownian_paths(B, L, d, seed=92 + d)
             g = np.random.default_rng(d).normal(size=(B, gpu.sig_size(d, depth))).astype(np.float32)
             want = oracle.signature_backward(x, depth, g)
@@ -141,8 +142,9 @@ def test_pointers_that_are_only_float_aligned(gpu, oracle):
         say("  shifted pointers, %s, %s: %s" % (name, "auto" if plan is None else "variant %d" % plan.variant,
                                                 " ".join("%.2e" % e for e in errs)))
         assert max(errs) <= TOL
-    # gradient: register kernel (5, 4), sliced sweep (10, 4), general sweep (11, 2)
-    for d, depth, B, L, stream in [(5, 4, 9, 60, False), (4, 4, 5, 40, True), (10, 4, 3, 20, False), (11, 2, 4, 15, True)]:
+    # gradient: register kernel (5, 4), sliced sweep (10, 4), general sweep (11, 2), sweep cut into time segments
+    for d, depth, B, L, stream in [(5, 4, 9, 60, False), (4, 4, 5, 40, True), (10, 4, 3, 20, False), (11, 2, 4, 15, True),
+                                   (10, 4, 1, 200, False), (6, 4, 2, 301, False)]:
         x = workloads.brownian_paths(B, L, d, seed=95 + d)
         D = gpu.sig_size(d, depth)
         rows = (B, L - 1, D) if stream else (B, D)
