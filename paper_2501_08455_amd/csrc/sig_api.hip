@@ -785,7 +785,7 @@ int sig_backward(sig_ctx *ctx, const float *path, int64_t B, int64_t L, int d, i
             rc = ensure_scratch(ctx, (size_t)need * sizeof(float));
             if (rc != SIG_OK) return rc;
             hipError_t es = launch_backward_segmented(path, out, grad_out, grad_path, ctx->scratch, B, L, d, depth, segs,
-                                                      (hipStream_t)hip_stream);
+                                                      ctx->num_cu, (hipStream_t)hip_stream);
             return es == hipSuccess ? SIG_OK : SIG_ERR_HIP;
         }
     }

@@ -157,6 +157,7 @@ struct BackwardArgs {
     int32_t seg_steps;
     const float *seg_sig;
     const float *seg_grad;
+    float *seg_part;        // register sweep cut in time: d(loss)/d(increment), [B][L-1][d]
 };
 
 // steps whose partial sums are parked before they are added up: enough for every lane of a path to have a
@@ -185,6 +186,217 @@ struct Park {
 };
 
 extern __shared__ float sig_backward_smem[];
+
+// Register sweep: the d^P lanes of a path fit a workgroup, which takes `groups` paths side by side.
+// SEG (final mode): the sweep is cut in time and the workgroup takes `groups` (path, segment) pieces instead, piece
+// = b * segs + s; every piece is swept as seg_steps increments (the last segment of a path is filled up with zero
+// increments behind its end, which leave the signature and the adjoint as they are), starts from the rows
+// seg_sig / seg_grad (see BackwardArgs) and leaves its sums over the increments in seg_part.
+template <int d, int N, int P, bool STREAM, bool SEG = false>
+__global__ __launch_bounds__(256) void sig_backward_kernel(BackwardArgs A)
+{
+    static_assert(!(STREAM && SEG), "stream mode is not cut across workgroups");
+    using Sh = Shape<d, N, P>;
+    constexpr int Q = Sh::Q;
+    constexpr int D = Sh::D;
+    constexpr int TS = reduce_steps<d, P>();  // steps whose partial sums are parked before they are added up
+    const int tid = threadIdx.x, nthr = blockDim.x;
+    const int64_t Kall = A.L - 1;                     // increments of a path
+    const int64_t K = SEG ? A.seg_steps : Kall;       // increments of a workgroup's rows
+    const int W = SEG ? A.segs : 1;
+    const int64_t rows = A.B * W;                     // paths, or pieces
+    const int G = A.groups;
+    const int gi_raw = tid / Q;
+    const unsigned u = (unsigned)(tid - gi_raw * Q);
+    const int64_t b0 = (int64_t)blockIdx.x * G;       // first path (piece) of the workgroup
+    const bool active = gi_raw < G && b0 + gi_raw < rows;
+    const int gi = gi_raw < G ? gi_raw : 0;
+    const int64_t piece = active ? b0 + gi : 0;
+    const int64_t b = piece / W;
+    const int seg = (int)(piece - b * W);
+    const int64_t k0 = SEG ? (int64_t)seg * K : 0;    // first increment of the piece
+
+    int letter[P > 0 ? P : 1];
+    letter[0] = 0;
+    {
+        unsigned rest = u;
+#pragma unroll
+        for (int m = P - 1; m >= 0; --m) { letter[m] = (int)(rest % d); rest /= d; }
+    }
+
+    // LDS: increments [G][K*d] (overwritten step by step with their gradients), parked partial sums [G][TS] x Park
+    const int row_floats = (int)K * d;
+    float *tile = sig_backward_smem;
+    float *park = tile + (G * row_floats + 3) / 4 * 4;
+    for (int i = tid; i < G * row_floats; i += nthr) {
+        const int g2 = i / row_floats;
+        const int r = i - g2 * row_floats;
+        float v = 0.0f;
+        if (b0 + g2 < rows) {
+            if constexpr (SEG) {
+                const int64_t b2 = (b0 + g2) / W;
+                const int64_t first = (b0 + g2 - b2 * W) * K;
+                if (first * d + r < Kall * d) {
+                    const float *x = A.path + (b2 * A.L + first) * d + r;
+                    v = x[d] - x[0];
+                }
+            } else {
+                const float *x = A.path + (b0 + g2) * A.L * d + r;
+                v = x[d] - x[0];
+            }
+        }
+        tile[i] = v;
+    }
+
+    Lane<d, N, P> ln, ad;
+    identity_state<d, N, P>(ln);
+    identity_state<d, N, P>(ad);
+    if (P == 0) ad.s[0] = 0.0f;
+    if (active) {
+        const bool inner = SEG && seg < W - 1;   // a segment that ends inside the path
+        const float *srow = STREAM ? A.sig + (b * K + (K - 1)) * D : inner ? A.seg_sig + piece * D : A.sig + b * D;
+        load_state<d, N, P>(srow, u, ln);
+        if constexpr (!STREAM) load_adjoint<d, N, P, false>(inner ? A.seg_grad + piece * D : A.grad_out + b * D, u, ad);
+    }
+    __syncthreads();
+
+    using Pk = Park<d, P>;
+    float *mypark = park + (size_t)gi * TS * Pk::kStepFloats;
+    float *myrow = tile + gi * row_floats;
+    // One step of the sweep; `upk` is the upstream gradient of row k (stream mode).
+    auto step = [&](int64_t k, const Lane<d, N, P> *upk) __attribute__((always_inline)) {
+        const int ts = (int)((K - 1 - k) % TS);
+        if constexpr (STREAM) {
+#pragma unroll
+            for (int i = 0; i < Sh::SZ; ++i) ad.s[i] += upk->s[i];
+#pragma unroll
+            for (int i = 0; i < Sh::NPRE; ++i) ad.pre[i] += upk->pre[i];
+        }
+        Inc<d, P> inc, neg;
+        load_inc<d, P>(inc, myrow + k * d, letter);
+#pragma unroll
+        for (int a = 0; a < d; ++a) neg.v[a] = -inc.v[a];
+        neg.du[0] = 0.0f;
+#pragma unroll
+        for (int m = 0; m < P; ++m) neg.du[m] = -inc.du[m];
+        if (k0 + k > 0) fused_step<d, N, P>(ln, neg);  // S_{k-1} = S_k (x) exp(-dX_k)
+        else identity_state<d, N, P>(ln);               // before the first increment: the identity, exactly
+        float dbar[d];
+        backward_step<d, N, P>(ln, ad, inc, letter, dbar);
+        if (active) {
+#pragma unroll
+            for (int a = 0; a < d; ++a) mypark[Pk::at(ts, (int)u, a)] = dbar[a];
+        }
+        if (ts == TS - 1 || k == 0) {
+            __syncthreads();
+            // column c = (parked step t, channel a): the sum over the path's lanes is d(loss)/d(dX)[a] of step
+            // k + (ts - t); it replaces that increment, which no lane reads again
+            if (active) {
+                for (int c = (int)u; c < (ts + 1) * d; c += Q) {
+                    const int t = c / d, a = c - t * d;
+                    float sum = 0.0f;
+                    for (int q = 0; q < Q; ++q) sum += mypark[Pk::at(t, q, a)];
+                    myrow[(k + (ts - t)) * d + a] = sum;
+                }
+            }
+            __syncthreads();
+        }
+    };
+    if constexpr (STREAM) {
+        // The upstream gradient rows are fetched PD steps ahead into registers: a row's HBM latency (well over
+        // a microsecond) is several steps long, and at one or two wavefronts per SIMD nothing else hides it.
+        // (as many rows as the registers hold beside the two lane states)
+        constexpr int PD = Sh::SZ <= 24 ? 4 : Sh::SZ <= 48 ? 2 : 1;
+        Lane<d, N, P> up[PD];
+        static_for<0, PD>([&](auto jc) __attribute__((always_inline)) {
+            constexpr int j = decltype(jc)::value;
+            identity_state<d, N, P>(up[j]);
+            if (P == 0) up[j].s[0] = 0.0f;
+            if (active && K - 1 - j >= 0) load_adjoint<d, N, P, false>(A.grad_out + (b * K + (K - 1 - j)) * D, u, up[j]);
+        });
+        for (int64_t kk = K - 1; kk >= 0; kk -= PD) {
+            static_for<0, PD>([&](auto jc) __attribute__((always_inline)) {
+                constexpr int j = decltype(jc)::value;
+                const int64_t k = kk - j;
+                if (k >= 0) {
+                    step(k, &up[j]);
+                    if (active && k - PD >= 0) load_adjoint<d, N, P, false>(A.grad_out + (b * K + (k - PD)) * D, u, up[j]);
+                }
+            });
+        }
+    } else {
+        for (int64_t k = K - 1; k >= 0; --k) step(k, nullptr);
+    }
+
+    if constexpr (SEG) {
+        // the sums over the piece's own increments; another launch forms d(loss)/dX across the pieces
+        for (int i = tid; i < G * row_floats; i += nthr) {
+            const int g2 = i / row_floats;
+            const int r = i - g2 * row_floats;
+            if (b0 + g2 < rows) {
+                const int64_t b2 = (b0 + g2) / W;
+                const int64_t first = (b0 + g2 - b2 * W) * K;
+                if (first * d + r < Kall * d) A.seg_part[(b2 * Kall + first) * d + r] = tile[i];
+            }
+        }
+        return;
+    }
+    // d(loss)/dX_j = d/d(dX_{j-1}) - d/d(dX_j)
+    const int out_row = (int)A.L * d;
+    for (int i = tid; i < G * out_row; i += nthr) {
+        const int g2 = i / out_row;
+        const int r = i - g2 * out_row;
+        if (b0 + g2 < A.B) {
+            const float *t = tile + g2 * row_floats;
+            const float before = r >= d ? t[r - d] : 0.0f;
+            const float after = r < row_floats ? t[r] : 0.0f;
+            A.grad_path[(b0 + g2) * out_row + r] = before - after;
+        }
+    }
+}
+
+// LDS bytes of the register sweep with `groups` paths (or pieces) of L points per workgroup
+template <int d, int N, int P>
+int64_t backward_lds_bytes(int64_t L, int groups)
+{
+    const int64_t tile = ((int64_t)groups * (L - 1) * d + 3) / 4 * 4;
+    const int64_t park = (int64_t)groups * reduce_steps<d, P>() * Park<d, P>::kStepFloats;
+    return (tile + park) * (int64_t)sizeof(float);
+}
+
+// LDS of the sweep cut in time inside a workgroup (sig_backward_chunked_kernel): a lane's registers in LDS, one
+// chunk's row in either of its two buffers, and the launch's bytes
+template <int d, int N, int P>
+constexpr int private_floats() { return (Shape<d, N, P>::SZ + Shape<d, N, P>::NPRE) * Shape<d, N, P>::Q; }
+
+template <int d, int N, int P>
+constexpr int chunk_row_floats()  // one chunk's row in either LDS buffer of the chunked sweep
+{
+    using Sh = Shape<d, N, P>;
+    int a = Sh::D;
+    const int park = reduce_steps<d, P>() * Park<d, P>::kStepFloats;
+    if (park > a) a = park;
+    return (a + 3) / 4 * 4;
+}
+
+template <int d, int N, int P>
+int64_t backward_chunked_lds_bytes(int64_t L, int chunks, int stream_flag)
+{
+    const int64_t tile = ((L - 1) * d + 3) / 4 * 4;
+    int64_t per_chunk = 2 * (int64_t)chunk_row_floats<d, N, P>();
+    if (stream_flag) per_chunk += private_floats<d, N, P>();
+    return (tile + chunks * per_chunk) * (int64_t)sizeof(float);
+}
+
+// chunks of at least eight increments that one workgroup of `threads` threads sweeps side by side (1: it does not cut)
+template <int d, int N, int P>
+int backward_chunks(int64_t L, int stream_flag, int threads)
+{
+    int C = threads / Shape<d, N, P>::Q;
+    if (C > (L - 1) / 8) C = (int)((L - 1) / 8);
+    while (C > 1 && backward_chunked_lds_bytes<d, N, P>(L, C, stream_flag) > kMaxLdsBytes) --C;
+    return C < 1 ? 1 : C;
+}
 
 // ---------------------------------------------------------------------------------------------------------
 // Sliced sweep: shapes whose d^P lanes per path exceed one workgroup.  A workgroup takes one path and one slice

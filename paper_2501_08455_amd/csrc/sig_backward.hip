@@ -30,139 +30,6 @@
 namespace sig {
 namespace onchip {
 
-template <int d, int N, int P, bool STREAM>
-__global__ __launch_bounds__(256) void sig_backward_kernel(BackwardArgs A)
-{
-    using Sh = Shape<d, N, P>;
-    constexpr int Q = Sh::Q;
-    constexpr int D = Sh::D;
-    constexpr int TS = reduce_steps<d, P>();  // steps whose partial sums are parked before they are added up
-    const int tid = threadIdx.x, nthr = blockDim.x;
-    const int64_t K = A.L - 1;
-    const int G = A.groups;
-    const int gi_raw = tid / Q;
-    const unsigned u = (unsigned)(tid - gi_raw * Q);
-    const int64_t b0 = (int64_t)blockIdx.x * G;
-    const bool active = gi_raw < G && b0 + gi_raw < A.B;
-    const int gi = gi_raw < G ? gi_raw : 0;
-    const int64_t b = active ? b0 + gi : 0;
-
-    int letter[P > 0 ? P : 1];
-    letter[0] = 0;
-    {
-        unsigned rest = u;
-#pragma unroll
-        for (int m = P - 1; m >= 0; --m) { letter[m] = (int)(rest % d); rest /= d; }
-    }
-
-    // LDS: increments [G][K*d] (overwritten step by step with their gradients), parked partial sums [G][TS] x Park
-    const int row_floats = (int)K * d;
-    float *tile = sig_backward_smem;
-    float *park = tile + (G * row_floats + 3) / 4 * 4;
-    for (int i = tid; i < G * row_floats; i += nthr) {
-        const int g2 = i / row_floats;
-        const int r = i - g2 * row_floats;
-        float v = 0.0f;
-        if (b0 + g2 < A.B) {
-            const float *x = A.path + (b0 + g2) * A.L * d + r;
-            v = x[d] - x[0];
-        }
-        tile[i] = v;
-    }
-
-    Lane<d, N, P> ln, ad;
-    identity_state<d, N, P>(ln);
-    identity_state<d, N, P>(ad);
-    if (P == 0) ad.s[0] = 0.0f;
-    if (active) {
-        const float *srow = STREAM ? A.sig + (b * K + (K - 1)) * D : A.sig + b * D;
-        load_state<d, N, P>(srow, u, ln);
-        if constexpr (!STREAM) load_adjoint<d, N, P, false>(A.grad_out + b * D, u, ad);
-    }
-    __syncthreads();
-
-    using Pk = Park<d, P>;
-    float *mypark = park + (size_t)gi * TS * Pk::kStepFloats;
-    float *myrow = tile + gi * row_floats;
-    // One step of the sweep; `upk` is the upstream gradient of row k (stream mode).
-    auto step = [&](int64_t k, const Lane<d, N, P> *upk) __attribute__((always_inline)) {
-        const int ts = (int)((K - 1 - k) % TS);
-        if constexpr (STREAM) {
-#pragma unroll
-            for (int i = 0; i < Sh::SZ; ++i) ad.s[i] += upk->s[i];
-#pragma unroll
-            for (int i = 0; i < Sh::NPRE; ++i) ad.pre[i] += upk->pre[i];
-        }
-        Inc<d, P> inc, neg;
-        load_inc<d, P>(inc, myrow + k * d, letter);
-#pragma unroll
-        for (int a = 0; a < d; ++a) neg.v[a] = -inc.v[a];
-        neg.du[0] = 0.0f;
-#pragma unroll
-        for (int m = 0; m < P; ++m) neg.du[m] = -inc.du[m];
-        if (k > 0) fused_step<d, N, P>(ln, neg);  // S_{k-1} = S_k (x) exp(-dX_k)
-        else identity_state<d, N, P>(ln);          // before the first increment: the identity, exactly
-        float dbar[d];
-        backward_step<d, N, P>(ln, ad, inc, letter, dbar);
-        if (active) {
-#pragma unroll
-            for (int a = 0; a < d; ++a) mypark[Pk::at(ts, (int)u, a)] = dbar[a];
-        }
-        if (ts == TS - 1 || k == 0) {
-            __syncthreads();
-            // column c = (parked step t, channel a): the sum over the path's lanes is d(loss)/d(dX)[a] of step
-            // k + (ts - t); it replaces that increment, which no lane reads again
-            if (active) {
-                for (int c = (int)u; c < (ts + 1) * d; c += Q) {
-                    const int t = c / d, a = c - t * d;
-                    float sum = 0.0f;
-                    for (int q = 0; q < Q; ++q) sum += mypark[Pk::at(t, q, a)];
-                    myrow[(k + (ts - t)) * d + a] = sum;
-                }
-            }
-            __syncthreads();
-        }
-    };
-    if constexpr (STREAM) {
-        // The upstream gradient rows are fetched PD steps ahead into registers: a row's HBM latency (well over
-        // a microsecond) is several steps long, and at one or two wavefronts per SIMD nothing else hides it.
-        // (as many rows as the registers hold beside the two lane states)
-        constexpr int PD = Sh::SZ <= 24 ? 4 : Sh::SZ <= 48 ? 2 : 1;
-        Lane<d, N, P> up[PD];
-        static_for<0, PD>([&](auto jc) __attribute__((always_inline)) {
-            constexpr int j = decltype(jc)::value;
-            identity_state<d, N, P>(up[j]);
-            if (P == 0) up[j].s[0] = 0.0f;
-            if (active && K - 1 - j >= 0) load_adjoint<d, N, P, false>(A.grad_out + (b * K + (K - 1 - j)) * D, u, up[j]);
-        });
-        for (int64_t kk = K - 1; kk >= 0; kk -= PD) {
-            static_for<0, PD>([&](auto jc) __attribute__((always_inline)) {
-                constexpr int j = decltype(jc)::value;
-                const int64_t k = kk - j;
-                if (k >= 0) {
-                    step(k, &up[j]);
-                    if (active && k - PD >= 0) load_adjoint<d, N, P, false>(A.grad_out + (b * K + (k - PD)) * D, u, up[j]);
-                }
-            });
-        }
-    } else {
-        for (int64_t k = K - 1; k >= 0; --k) step(k, nullptr);
-    }
-
-    // d(loss)/dX_j = d/d(dX_{j-1}) - d/d(dX_j)
-    const int out_row = (int)A.L * d;
-    for (int i = tid; i < G * out_row; i += nthr) {
-        const int g2 = i / out_row;
-        const int r = i - g2 * out_row;
-        if (b0 + g2 < A.B) {
-            const float *t = tile + g2 * row_floats;
-            const float before = r >= d ? t[r - d] : 0.0f;
-            const float after = r < row_floats ? t[r] : 0.0f;
-            A.grad_path[(b0 + g2) * out_row + r] = before - after;
-        }
-    }
-}
-
 // Transpose of reg_product with respect to its left factor.  For c = a (x) b (Eq. 4), c[w] = sum over the
 // splits w = (v, x) of a[v] b[x], so d(loss)/da[v] = sum_x d(loss)/dc[(v, x)] b[x].  `ad` holds d(loss)/dc on
 // entry and d(loss)/da on return, in the lane layout of the sweep (sub-tree below u, private partials for the
@@ -214,9 +81,6 @@ __device__ __forceinline__ void reg_adjoint_product(Lane<d, N, P> &ad, const flo
 
 // a lane's registers in LDS, register i of lane u at i * Q + u (consecutive lanes on consecutive banks)
 template <int d, int N, int P>
-constexpr int private_floats() { return (Shape<d, N, P>::SZ + Shape<d, N, P>::NPRE) * Shape<d, N, P>::Q; }
-
-template <int d, int N, int P>
 __device__ __forceinline__ void store_private(float *buf, unsigned u, const Lane<d, N, P> &x)
 {
     using Sh = Shape<d, N, P>;
@@ -234,16 +98,6 @@ __device__ __forceinline__ void load_private(const float *buf, unsigned u, Lane<
     for (int i = 0; i < Sh::SZ; ++i) x.s[i] = buf[i * Sh::Q + u];
 #pragma unroll
     for (int i = 0; i < Sh::NPRE; ++i) x.pre[i] = buf[(Sh::SZ + i) * Sh::Q + u];
-}
-
-template <int d, int N, int P>
-constexpr int chunk_row_floats()  // one chunk's row in either LDS buffer of the chunked sweep
-{
-    using Sh = Shape<d, N, P>;
-    int a = Sh::D;
-    const int park = reduce_steps<d, P>() * Park<d, P>::kStepFloats;
-    if (park > a) a = park;
-    return (a + 3) / 4 * 4;
 }
 
 // The sweep cut in time: one workgroup per path, C chunks of T increments side by side.
@@ -525,23 +379,6 @@ hipError_t backward_sliced_launch(const BackwardArgs &A, float *scratch, int, in
 }
 
 template <int d, int N, int P>
-int64_t backward_chunked_lds_bytes(int64_t L, int chunks, int stream_flag)
-{
-    const int64_t tile = ((L - 1) * d + 3) / 4 * 4;
-    int64_t per_chunk = 2 * (int64_t)chunk_row_floats<d, N, P>();
-    if (stream_flag) per_chunk += private_floats<d, N, P>();
-    return (tile + chunks * per_chunk) * (int64_t)sizeof(float);
-}
-
-template <int d, int N, int P>
-int64_t backward_lds_bytes(int64_t L, int groups)
-{
-    const int64_t tile = ((int64_t)groups * (L - 1) * d + 3) / 4 * 4;
-    const int64_t park = (int64_t)groups * reduce_steps<d, P>() * Park<d, P>::kStepFloats;
-    return (tile + park) * (int64_t)sizeof(float);
-}
-
-template <int d, int N, int P>
 int64_t backward_no_scratch(int64_t, int64_t) { return 0; }
 
 template <int d, int N, int P>
@@ -555,9 +392,7 @@ hipError_t backward_launch(const BackwardArgs &A0, float *, int threads, int cus
     // (stream mode reads the upstream gradient twice when cut, so only far below one wavefront per SIMD)
     const int64_t few_lanes = A.stream_flag ? (int64_t)cus * kWave : (int64_t)cus * 4 * kWave * 2;
     if (A.B * Q < few_lanes && A.B <= INT32_MAX) {
-        int C = threads / Q;
-        if (C > (A.L - 1) / 8) C = (int)((A.L - 1) / 8);
-        while (C > 1 && backward_chunked_lds_bytes<d, N, P>(A.L, C, A.stream_flag) > kMaxLdsBytes) --C;
+        const int C = backward_chunks<d, N, P>(A.L, A.stream_flag, threads);
         if (C > 1) {
             A.groups = C;
             const size_t lds = (size_t)backward_chunked_lds_bytes<d, N, P>(A.L, C, A.stream_flag);

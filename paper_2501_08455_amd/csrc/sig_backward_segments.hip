@@ -169,32 +169,43 @@ __global__ __launch_bounds__(256) void sig_backward_segment_adjoint_kernel(const
                               256 * row_workgroups<d, N>());
 }
 
+// shapes whose lanes fit a workgroup at least twice take the register sweep with several pieces per workgroup
 template <int d, int N, int P>
-hipError_t backward_segmented_launch(const BackwardArgs &A0, float *scratch, int W, hipStream_t st)
+constexpr bool segments_packed() { return Shape<d, N, P>::Q * 2 <= 256; }
+
+// does a segment of T increments fit the LDS of its sweep?
+template <int d, int N, int P>
+bool segment_fits(int64_t T)
+{
+    if constexpr (segments_packed<d, N, P>()) return backward_lds_bytes<d, N, P>(T + 1, 1) <= kMaxLdsBytes;
+    else return backward_sliced_steps<d>(T + 1) >= 1;
+}
+
+template <int d, int N, int P>
+hipError_t backward_segmented_launch(const BackwardArgs &A0, float *scratch, int W, int cus, hipStream_t st)
 {
     using Sh = Shape<d, N, P>;
+    constexpr bool packed = segments_packed<d, N, P>();
     constexpr int slices = (Sh::Q + kSliceLanes - 1) / kSliceLanes;
     const int64_t K = A0.L - 1;
-    if (W < 2 || W > K || !scratch || A0.stream_flag) return hipErrorInvalidValue;
+    if (W < 2 || W > K || !scratch || A0.stream_flag || cus < 1) return hipErrorInvalidValue;
     const int64_t T = (K + W - 1) / W;
     W = (int)((K + T - 1) / T);   // no trailing segment without increments
-    if (W < 2) return hipErrorInvalidValue;
-    const int ts = backward_sliced_steps<d>(T + 1);
-    const int64_t lds = backward_sliced_bytes_with<d>(T + 1, ts > 0 ? ts : 1);
-    const int64_t grid = A0.B * W * slices;
-    if (ts < 1 || lds > kMaxLdsBytes || grid <= 0 || grid > INT32_MAX || A0.B > INT32_MAX) return hipErrorInvalidValue;
-    const int64_t rows = A0.B * W * Sh::D;
+    const int64_t pieces = A0.B * W;
+    if (W < 2 || !segment_fits<d, N, P>(T) || pieces * slices > INT32_MAX || A0.B > INT32_MAX) return hipErrorInvalidValue;
+    const int64_t rows = pieces * Sh::D;
     float *E = scratch, *S0 = E + rows, *S1 = S0 + rows, *Y0 = S1 + rows, *Y1 = Y0 + rows, *part = Y1 + rows;
 
-    hipLaunchKernelGGL((sig_backward_segment_fold_kernel<d, N, P>), dim3((unsigned)grid), dim3(kSliceLanes),
+    const int fold_threads = Sh::Q >= kSliceLanes ? kSliceLanes : (Sh::Q + kWave - 1) / kWave * kWave;
+    hipLaunchKernelGGL((sig_backward_segment_fold_kernel<d, N, P>), dim3((unsigned)(pieces * slices)), dim3(fold_threads),
                        (size_t)(T * d) * sizeof(float), st, A0.path, E, A0.L, W, (int)T);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const float *Sin = E, *Yin = E;
     float *Sout = S0, *Yout = Y0;
     for (int off = 1; off < W; off *= 2) {
-        hipLaunchKernelGGL((sig_backward_segment_scan_kernel<d, N>), dim3((unsigned)(A0.B * W), 2, row_workgroups<d, N>()), dim3(256), 0, st, Sin, Sout,
-                           Yin, Yout, W, off);
+        hipLaunchKernelGGL((sig_backward_segment_scan_kernel<d, N>), dim3((unsigned)pieces, 2, row_workgroups<d, N>()), dim3(256),
+                           0, st, Sin, Sout, Yin, Yout, W, off);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
         Sin = Sout;
@@ -204,8 +215,8 @@ hipError_t backward_segmented_launch(const BackwardArgs &A0, float *scratch, int
     }
     // the scan's last input buffer of the suffix products is free now: it takes the pulled-back gradients
     float *Aend = Yout;
-    hipLaunchKernelGGL((sig_backward_segment_adjoint_kernel<d, N>), dim3((unsigned)(A0.B * W), 1, row_workgroups<d, N>()), dim3(256), 0, st, A0.grad_out,
-                       Yin, Aend, W);
+    hipLaunchKernelGGL((sig_backward_segment_adjoint_kernel<d, N>), dim3((unsigned)pieces, 1, row_workgroups<d, N>()), dim3(256),
+                       0, st, A0.grad_out, Yin, Aend, W);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     BackwardArgs A = A0;
@@ -213,8 +224,23 @@ hipError_t backward_segmented_launch(const BackwardArgs &A0, float *scratch, int
     A.seg_steps = (int32_t)T;
     A.seg_sig = Sin;
     A.seg_grad = Aend;
-    hipLaunchKernelGGL((sig_backward_sliced_kernel<d, N, P, false>), dim3((unsigned)grid), dim3(kSliceLanes), (size_t)lds, st, A,
-                       part, ts);
+    A.seg_part = part;
+    if constexpr (packed) {
+        // pieces per workgroup: as many as the threads hold, spread over the compute units first, fewer if LDS is short
+        int G = 256 / Sh::Q;
+        const int64_t per_cu = (pieces + cus - 1) / cus;
+        if ((int64_t)G > per_cu) G = (int)per_cu;
+        while (G > 1 && backward_lds_bytes<d, N, P>(T + 1, G) > kMaxLdsBytes) --G;
+        A.groups = G;
+        const size_t lds = (size_t)backward_lds_bytes<d, N, P>(T + 1, G);
+        hipLaunchKernelGGL((sig_backward_kernel<d, N, P, false, true>), dim3((unsigned)((pieces + G - 1) / G)), dim3(256), lds,
+                           st, A);
+    } else {
+        const int ts = backward_sliced_steps<d>(T + 1);
+        const size_t lds = (size_t)backward_sliced_bytes_with<d>(T + 1, ts);
+        hipLaunchKernelGGL((sig_backward_sliced_kernel<d, N, P, false>), dim3((unsigned)(pieces * slices)), dim3(kSliceLanes),
+                           lds, st, A, part, ts);
+    }
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     return launch_backward_finish(part, A.grad_path, A.B, A.L, d, slices, st);
@@ -224,25 +250,27 @@ hipError_t backward_segmented_launch(const BackwardArgs &A0, float *scratch, int
 
 namespace {
 
-// does a segment of T increments fit the LDS of the sweep?
-template <int d>
-bool segment_fits(int64_t T)
+template <int d, int N, int P>
+int uncut_chunks(int64_t L)
 {
-    return onchip::backward_sliced_steps<d>(T + 1) >= 1;
+    if constexpr (onchip::Shape<d, N, P>::Q <= 256) return onchip::backward_chunks<d, N, P>(L, 0, 256);
+    else return 1;
 }
 
 struct SegmentedEntry {
     int d, depth;
     int lanes;        // Q = d^P
     int64_t row;      // D
-    hipError_t (*launch)(const onchip::BackwardArgs &, float *, int, hipStream_t);
-    bool (*fits)(int64_t);
+    hipError_t (*launch)(const onchip::BackwardArgs &, float *, int, int, hipStream_t);
+    bool (*fits)(int64_t);             // does a segment of T increments fit the LDS of its sweep?
+    int (*uncut_chunks)(int64_t L);    // chunks the uncut sweep holds side by side in a workgroup (final mode)
 };
 #define SIG_SEGMENTED_ENTRY(d, N, P) \
-    {d, N, onchip::Shape<d, N, P>::Q, onchip::Shape<d, N, P>::D, &onchip::backward_segmented_launch<d, N, P>, &segment_fits<d>},
+    {d, N, onchip::Shape<d, N, P>::Q, onchip::Shape<d, N, P>::D, &onchip::backward_segmented_launch<d, N, P>, &onchip::segment_fits<d, N, P>, \
+     &uncut_chunks<d, N, P>},
 const SegmentedEntry kSegmented[] = {
     SIG_BACKWARD_SHAPES(SIG_SEGMENTED_ENTRY, SIG_SEGMENTED_ENTRY)
-    {0, 0, 0, 0, nullptr, nullptr},
+    {0, 0, 0, 0, nullptr, nullptr, nullptr},
 };
 
 const SegmentedEntry *find_segmented(int d, int depth)
@@ -259,26 +287,40 @@ constexpr int64_t kMaxSegmentRow = 1 << 17;   // one workgroup forms a product o
 }  // namespace
 
 // Time segments for the final-mode sweep of B paths of L points (<= 1: do not cut).  Cutting pays when the uncut
-// launch leaves compute units without a workgroup and the path is long: the sequential part drops from K steps to
-// about K / W steps, for ceil(log2 W) + 3 more launches; W is taken so that a segment keeps about 24 increments and
-// limited to two workgroups per compute unit.  Shapes with 32 lanes or fewer per path are cut in time inside the
-// workgroup by the plain sweep (eight or more chunks side by side), which is as fast up to a few thousand increments.
-// A path whose increments do not fit the LDS of the uncut sweep (uncut_fits == false) is cut at any batch size, as
-// little as makes a segment fit.
+// launch leaves most of the chip idle and the path is long: the sequential part drops from K steps (2 K / C for a
+// shape whose plain sweep holds C chunks of a path side by side in its workgroup) to about K / W, for
+// ceil(log2 W) + 3 more launches of 3-6 us each.  Rules, from a measured grid (15 shapes, B = 1 .. 1,024,
+// L = 100 .. 2,000):
+//   * from 128 increments on, while the uncut launch has fewer workgroups than compute units;
+//   * shapes whose plain sweep holds eight or more chunks: only from 512 increments on; with six or more chunks:
+//     only up to 32 paths (cutting wins or ties at every measured point up to there; beyond, the plain sweep's
+//     workgroups fill enough of the chip).  Long paths leave the plain sweep fewer chunks (their increments take
+//     the LDS), so they are cut at larger batches as well (d = 5, depth 4, 128 paths of 2,000 points: three chunks,
+//     328 -> 173 us);
+//   * W = K / 24, at most 32, at most two wavefronts per SIMD over the chip, one set of rows within 8 MB;
+//   * a path whose increments do not fit the LDS of the uncut sweep (uncut_fits == false) is cut at any batch size,
+//     as little as makes a segment fit.
 int backward_segments(int d, int depth, int64_t B, int64_t L, int cus, bool uncut_fits)
 {
     const SegmentedEntry *e = find_segmented(d, depth);
     if (!e || e->row > kMaxSegmentRow || B <= 0) return 1;
     const int64_t K = L - 1;
+    const bool packed = e->lanes * 2 <= onchip::kSliceLanes;   // several pieces share a workgroup
     const int64_t slices = (e->lanes + onchip::kSliceLanes - 1) / onchip::kSliceLanes;
-    const bool busy = B * slices >= cus;   // the uncut launch already has a workgroup for every compute unit
-    const int64_t min_steps = e->lanes * 8 <= onchip::kSliceLanes ? 2048 : 128;
+    const int64_t chip_lanes = (int64_t)cus * 4 * kWave * 2;   // two wavefronts on every SIMD
+    bool busy = B * slices >= cus;   // the uncut launch already has a workgroup for every compute unit
+    int64_t min_steps = 128;
+    if (packed && uncut_fits) {
+        const int chunks = e->uncut_chunks(L);
+        if (chunks >= 8) min_steps = 512;
+        if (B > 32 && chunks >= 6) busy = true;
+    }
     if (uncut_fits && (K < min_steps || busy)) return 1;
     int64_t W = 2;
     if (!busy) {
         W = K / 24;
         if (W > kMaxSegments) W = kMaxSegments;
-        const int64_t room = (2 * (int64_t)cus) / (B * slices);
+        const int64_t room = packed ? chip_lanes / (B * e->lanes) : (2 * (int64_t)cus) / (B * slices);
         if (W > room) W = room;
         // the scan reads and writes all B * W rows in every round: keep one set of rows within 8 MB
         const int64_t by_rows = kMaxSegmentFloats / (B * e->row);
@@ -302,7 +344,8 @@ int64_t backward_segmented_scratch_floats(int d, int depth, int64_t B, int64_t L
 }
 
 hipError_t launch_backward_segmented(const float *path, const float *sig, const float *grad_out, float *grad_path,
-                                     float *scratch, int64_t B, int64_t L, int d, int depth, int segs, hipStream_t st)
+                                     float *scratch, int64_t B, int64_t L, int d, int depth, int segs, int cus,
+                                     hipStream_t st)
 {
     const SegmentedEntry *e = find_segmented(d, depth);
     if (!e) return hipErrorInvalidValue;
@@ -314,7 +357,7 @@ hipError_t launch_backward_segmented(const float *path, const float *sig, const 
     A.B = B;
     A.L = L;
     A.stream_flag = 0;
-    return e->launch(A, scratch, segs, st);
+    return e->launch(A, scratch, segs, cus, st);
 }
 
 }  // namespace sig

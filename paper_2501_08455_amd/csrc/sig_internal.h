@@ -71,7 +71,8 @@ hipError_t launch_backward_finish(const float *part, float *grad_path, int64_t B
 int backward_segments(int d, int depth, int64_t B, int64_t L, int cus, bool uncut_fits);
 int64_t backward_segmented_scratch_floats(int d, int depth, int64_t B, int64_t L, int segs);
 hipError_t launch_backward_segmented(const float *path, const float *sig, const float *grad_out, float *grad_path,
-                                     float *scratch, int64_t B, int64_t L, int d, int depth, int segs, hipStream_t st);
+                                     float *scratch, int64_t B, int64_t L, int d, int depth, int segs, int cus,
+                                     hipStream_t st);
 
 // ---------------------------------------------------------------- gradient, any (d <= 256, depth): one workgroup per path
 bool backward_general_available(int d);
