@@ -136,10 +136,10 @@ def backward_work(cfg, B, workloads):
     return flops, nbytes
 
 
-def bench_backward(binding, workloads, ctx, cfg, B, steps, warmup):
+def bench_backward(binding, workloads, ctx, cfg, B, steps, warmup, seed=None):
     """Time sig_backward on the named configuration (forward result and upstream gradient resident in HBM)."""
     import torch
-    x = workloads.make_paths(cfg, B=B)
+    x = workloads.make_paths(cfg, B=B, seed=seed)
     xt = torch.from_numpy(x).cuda()
     D = workloads.sig_size(cfg.d, cfg.depth)
     rows = cfg.L - 1 if cfg.stream else 1
@@ -407,6 +407,12 @@ def main():
                                      ("C2", 65536, 30, 20), ("C4", 4096, 20, 10)]:
             c = workloads.CONFIGS[name]
             extras.append(bench_backward(binding, workloads, ctx, c, B or c.B, steps, warm))
+        # ... and on long paths, where the sweep is cut into time segments across workgroups: C3 (2,000 points), and
+        # single paths of 1,000 points in the shapes of C2 and of a ten-channel depth-4 layer
+        extras.append(bench_backward(binding, workloads, ctx, workloads.CONFIGS["C3"], 128, 100, 50))
+        for d, depth in [(5, 4), (10, 4)]:
+            one = workloads.Config("one path", 1, 1000, d, depth, False, "normal")
+            extras.append(bench_backward(binding, workloads, ctx, one, 1, 200, 100, seed=workloads.BASE_SEED + 11))
         line["all_configs"] = extras
         line["table1_shapes"] = table1(binding, workloads, ctx)
         # a training step of the paper's model with the signature layer in the middle (context for Section 4.2)

@@ -198,6 +198,13 @@ int sig_backward(sig_ctx *ctx, const float *path, int64_t B, int64_t L, int d, i
 /* 1 if sig_backward has a compiled register kernel for (d, depth), 0 if it would take the general sweep.  Host only. */
 int sig_backward_available(int d, int depth);
 
+/*
+ * How sig_backward would sweep this shape.  Host only; ctx may be NULL (a device with 256 compute units is assumed).
+ * Returns the number of time segments the sweep is cut into across workgroups (2 .. 32), 1 for the uncut register
+ * sweep, 0 for the general sweep, or minus the SIG_ERR_* status with which sig_backward would reject the arguments.
+ */
+int sig_backward_segments(const sig_ctx *ctx, int64_t B, int64_t L, int d, int depth, int stream_flag);
+
 /* 1 if an on-chip kernel is compiled for (d, depth, prefix_depth), else 0.  Host only. */
 int sig_on_chip_available(int d, int depth, int prefix_depth);
 

@@ -84,6 +84,8 @@ def load():
     lib.sig_backward.argtypes = [vp, vp, i64, i64, i32, i32, i32, vp, vp, vp, vp]
     lib.sig_backward_available.restype = i32
     lib.sig_backward_available.argtypes = [i32, i32]
+    lib.sig_backward_segments.restype = i32
+    lib.sig_backward_segments.argtypes = [ctypes.c_void_p, i64, i64, i32, i32, i32]
     lib.sig_probe_copy.restype = i32
     lib.sig_probe_copy.argtypes = [vp, vp, i64, vp]
     lib.sig_probe_write.restype = i32
@@ -221,6 +223,11 @@ def bind_backward(ctx, path, depth, stream_flag, out, grad_out, grad_path, strea
 
 def sig_backward_available(d, depth):
     return int(load().sig_backward_available(int(d), int(depth)))
+
+
+def sig_backward_segments(ctx, B, L, d, depth, stream_flag):
+    """Time segments sig_backward cuts this shape into (1: uncut, 0: general sweep, < 0: a status); ctx may be None."""
+    return int(load().sig_backward_segments(ctx, int(B), int(L), int(d), int(depth), int(stream_flag)))
 
 
 def sig_probe_copy(dst, src, stream=None):

@@ -810,6 +810,20 @@ int sig_backward(sig_ctx *ctx, const float *path, int64_t B, int64_t L, int d, i
     return e == hipSuccess ? SIG_OK : SIG_ERR_HIP;
 }
 
+int sig_backward_segments(const sig_ctx *ctx, int64_t B, int64_t L, int d, int depth, int stream_flag)
+{
+    RowShape rs;
+    const int rc = check_shape(B, L, d, depth, stream_flag, &rs);
+    if (rc != SIG_OK) return -rc;
+    if (!backward_available(d, depth)) return backward_general_available(d) ? 0 : -SIG_ERR_UNSUPPORTED;
+    const bool fits = backward_fits(d, depth, L);
+    if (!stream_flag && B > 0) {
+        const int segs = backward_segments(d, depth, B, L, ctx ? ctx->num_cu : kDefaultCUs, fits);
+        if (segs > 1) return segs;
+    }
+    return fits ? 1 : 0;
+}
+
 int sig_backward_available(int d, int depth)
 {
     return backward_available(d, depth) ? 1 : 0;

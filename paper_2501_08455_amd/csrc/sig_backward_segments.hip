@@ -12,9 +12,10 @@
 //   1. every (path, segment) folds its increments from the identity: E_s                          (T steps)
 //   2. ceil(log2 W) rounds of a scan give all prefix products S_end(s) and all suffix products Y_s at once
 //   3. every segment pulls the upstream gradient back through Y_{s+1}: A_end(s)
-//   4. every (path, segment, slice of lanes) runs the reverse sweep over its own increments       (T steps)
-//   5. the per-slice sums of d(loss)/d(increment) are added up and differenced into d(loss)/dX.
-// Launches 4 and 5 are the sliced sweep's (sig_backward.h); shapes whose lanes fit one workgroup run as one slice.
+//   4. every piece runs the reverse sweep over its own increments                                 (T steps)
+//   5. the sums of d(loss)/d(increment) are added up over the slices and differenced into d(loss)/dX.
+// Launch 4 is the sliced sweep on (path, segment, slice of lanes) for shapes with more than 128 lanes per path, and
+// the register sweep with several (path, segment) pieces per workgroup for the others (both in sig_backward.h).
 #include "sig_backward.h"
 
 namespace sig {

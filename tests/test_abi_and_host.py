@@ -203,3 +203,29 @@ def test_every_compiled_forward_shape_has_a_gradient_kernel():
         assert (cfg.d, cfg.depth) in shapes
     missing = sorted(s for s in shapes if not binding.sig_backward_available(*s))
     assert not missing, missing
+
+
+def test_backward_segment_rule():
+    """Host rule for cutting the reverse sweep in time: few long paths in final mode, never in stream mode, paths too
+    long for one workgroup's LDS at any batch size, and the general sweep for shapes without a register kernel."""
+    seg = lambda B, L, d, depth, stream=0: binding.sig_backward_segments(None, B, L, d, depth, stream)
+    # short paths and full batches stay uncut
+    assert seg(128, 100, 5, 4) == 1 and seg(65536, 100, 5, 4) == 1 and seg(1, 100, 10, 4) == 1
+    assert seg(1024, 1000, 10, 4) == 1
+    # few long paths are cut, at most 32 times, and a segment keeps at least two dozen increments
+    for B, L, d, depth in [(1, 1000, 5, 4), (1, 1000, 10, 4), (16, 500, 8, 4), (3, 300, 5, 5), (2, 4001, 2, 3)]:
+        W = seg(B, L, d, depth)
+        assert 2 <= W <= 32 and (L - 1) // W >= 24, (B, L, d, depth, W)
+    # shapes whose plain sweep holds many chunks in a workgroup: only from 512 increments on and up to 32 paths ...
+    assert seg(1, 400, 5, 4) == 1 and seg(1, 600, 5, 4) > 1 and seg(64, 600, 5, 4) == 1
+    # ... unless the path is so long that the chunks no longer fit (the gradient of the third configuration)
+    assert seg(128, 2000, 5, 4) > 1
+    # stream mode is never cut
+    assert seg(1, 1000, 5, 4, 1) == 1 and seg(1, 1000, 10, 4, 1) == 1
+    # paths too long for the LDS of one workgroup: cut in final mode at any batch size, general sweep in stream mode
+    assert seg(300, 3500, 5, 4) >= 2 and seg(1, 20000, 5, 4) >= 2 and seg(1, 4000, 5, 4, 1) == 0
+    # no register kernel: the general sweep; beyond its limits and bad arguments: minus the status
+    assert seg(4, 50, 11, 2) == 0 and seg(4, 50, 300, 2) == -binding.SIG_ERR_UNSUPPORTED
+    assert seg(4, 1, 5, 4) == -binding.SIG_ERR_INVALID and seg(-1, 10, 5, 4) == -binding.SIG_ERR_INVALID
+    # rows of (10, 6) are too large for the scan over segments
+    assert seg(16, 128, 10, 6) == 1 and seg(1, 1000, 10, 6) == 1
