@@ -73,8 +73,9 @@ enum sig_variant {
  *   variant       one of enum sig_variant (never AUTO after sig_plan)
  *   prefix_depth  p: the index space of a row is cut into d^p independent sub-trees
  *   chunks        time chunks of one path folded concurrently inside one workgroup (>= 1)
- *   segments      workgroups per path along time (>= 1); partial signatures of segments
- *                 are joined by a second launch
+ *   segments      workgroups per path along time (>= 1); partial signatures of segments are joined by a second
+ *                 launch when all rows of a path fit the LDS of a join kernel, else (a power of two of at most 32
+ *                 segments) by a pairwise tree of batched Eq. 4 products in device memory, one launch per round
  *   threads       workgroup size (multiple of 64)
  *   tile_steps    increments staged through LDS per tile by the loader (0: chosen by the library)
  *   reserved[0]   with chunks == 1: 0 = workgroup-wide tiles of increments (the default, faster in every

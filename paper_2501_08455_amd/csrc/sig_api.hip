@@ -58,6 +58,28 @@ bool streaming_fits(const RowShape &rs, int p)
     return ((int64_t)tile * rs.d + 2 * gcap) * (int64_t)sizeof(float) <= kMaxLdsBytes;
 }
 
+// Can the partial rows of `segments` time segments be joined by the on-chip join kernels?  The LDS-tree join
+// (large lane states) holds all rows of a path at once plus half as many results; the register join stages all rows.
+constexpr int kMaxTreeSegments = 32;
+bool join_fits_lds(const OnChipKernelInfo *ki, int segments, const RowShape &rs)
+{
+    const int64_t row = rs.D * (int64_t)sizeof(float);
+    if (ki->state_floats > 64 && (segments + (segments + 1) / 2) * row > kMaxLdsBytes) return false;
+    return segments * row <= kMaxLdsBytes;
+}
+
+// Time segments for a join in device memory (a pairwise tree of batched row products, one launch of 5-8 us per
+// round): a power of two of at most `wanted`, only for long paths (the fold of K increments takes about 0.1 us per
+// increment when the chip is nearly empty, so fewer than about 500 do not pay for the rounds) and while one set of
+// partial rows stays within 8 MB.  Returns 1 when it does not pay.
+int64_t tree_segments(int64_t wanted, int64_t B, int64_t K, const RowShape &rs)
+{
+    if (K < 512 || wanted < 4) return 1;
+    int64_t W = 1;
+    while (W * 2 <= wanted && W * 2 <= kMaxTreeSegments && B * W * 2 * rs.D <= ((int64_t)1 << 21)) W *= 2;
+    return W;
+}
+
 // Fill the derived launch fields of an on-chip plan (chunk_steps, tile_steps) and check every limit the kernel
 // relies on.  Returns false if the plan cannot run.
 bool finish_on_chip(const OnChipKernelInfo *ki, int cus, int64_t B, int64_t L, int stream_flag, const sig_plan_t &pl,
@@ -77,11 +99,11 @@ bool finish_on_chip(const OnChipKernelInfo *ki, int cus, int64_t B, int64_t L, i
                                                         : pl.threads / Q;
     if (Q <= pl.threads && pl.chunks > slots) return false;
     if (stream_flag && pl.segments != 1) return false;       // carries across workgroups are not implemented
-    // the LDS-tree join holds all rows of a path at once; the register join stages one row at a time
-    if (pl.segments > 1 && ki->state_floats > 64 &&
-        (pl.segments + (pl.segments + 1) / 2) * rs.D * (int64_t)sizeof(float) > kMaxLdsBytes)
+    // rows of the segments that do not fit the LDS of a join kernel are joined in device memory by a pairwise
+    // tree of batched row products: a power of two of them
+    if (pl.segments > 1 && !join_fits_lds(ki, pl.segments, rs) &&
+        (pl.segments > kMaxTreeSegments || (pl.segments & (pl.segments - 1)) != 0))
         return false;
-    if (pl.segments > 1 && pl.segments * rs.D * (int64_t)sizeof(float) > kMaxLdsBytes) return false;
     if (B * (int64_t)pl.segments > INT32_MAX) return false;
     args->B = B;
     args->L = L;
@@ -324,12 +346,21 @@ int plan_auto(const sig_ctx *ctx, int64_t B, int64_t L, int stream_flag, const R
                 W = (pieces + C / 2) / C;  // rounded: a second launch is not worth a few missing lanes
                 int64_t wmax = K / (C * kMinSegmentChunkSteps);
                 if (W > wmax) W = wmax;
+                const int64_t wanted = W;
                 if (W > 8) W = 8;
-                while (W > 1 && (W + (ki->state_floats > 64 ? (W + 1) / 2 : 0)) * rs.D * (int64_t)sizeof(float) > kMaxLdsBytes) --W;
+                while (W > 1 && !join_fits_lds(ki, (int)W, rs)) --W;
                 if (W < 1) W = 1;
+                const int64_t tree = tree_segments(wanted, B, K, rs);
+                if (tree >= 4 && tree >= 4 * W) W = tree;
             }
             pl->chunks = (int)C;
             pl->segments = (int)W;
+        } else if (!stream_flag) {
+            // the lanes of a path span several workgroups: no chunks, but segments joined in device memory
+            int64_t W = ceil_div(want_lanes, B * Q);
+            if (W > K / kMinSegmentChunkSteps) W = K / kMinSegmentChunkSteps;
+            W = tree_segments(W, B, K, rs);
+            if (W >= 4) pl->segments = (int)W;
         }
         // Stream mode with few paths: the on-chip kernels walk K / C steps one after the other (twice when time is
         // cut) and a wavefront stages every row through LDS, while the level-scan family (one launch per level,
@@ -518,17 +549,31 @@ int run_plan(sig_ctx *ctx, const float *path, int64_t B, int64_t L, const RowSha
     args.path = path;
     args.out = out;
     args.partial = nullptr;
+    const bool lds_join = pl.segments > 1 && join_fits_lds(ki, pl.segments, rs);
+    const size_t rows = (size_t)B * pl.segments * rs.D;   // floats of the partial rows
     if (pl.segments > 1) {
-        size_t bytes = (size_t)B * pl.segments * rs.D * sizeof(float);
-        int rc = ensure_scratch(ctx, bytes);
+        // (the tree in device memory ping-pongs between two more buffers of half and a quarter of the rows)
+        int rc = ensure_scratch(ctx, (lds_join ? rows : rows + rows / 2 + rows / 4 + 4) * sizeof(float));
         if (rc != SIG_OK) return rc;
         args.partial = ctx->scratch;
     }
     hipError_t e = ki->launch(args, st);
     if (e != hipSuccess) return SIG_ERR_HIP;
-    if (pl.segments > 1) {
+    if (lds_join) {
         e = ki->join(ctx->scratch, out, B, pl.segments, st);
         if (e != hipSuccess) return SIG_ERR_HIP;
+    } else if (pl.segments > 1) {
+        // round r joins neighbours: row 2 i (x) row 2 i + 1 of the previous round's rows, the last round into `out`
+        const float *in = ctx->scratch;
+        float *buf[2] = {ctx->scratch + rows, ctx->scratch + rows + rows / 2};
+        int which = 0;
+        for (int64_t n = pl.segments; n > 1; n /= 2) {
+            float *dst = n == 2 ? out : buf[which];
+            e = launch_combine_rows(in, 2 * rs.D, in + rs.D, 2 * rs.D, dst, rs.D, B * (n / 2), rs, st);
+            if (e != hipSuccess) return SIG_ERR_HIP;
+            in = dst;
+            which ^= 1;
+        }
     }
     return SIG_OK;
 }

@@ -308,6 +308,13 @@ hipError_t launch_combine_rows(const float *a, int64_t a_stride, const float *b,
         int64_t slices = rs.pow[rs.depth] / 8192;
         if (slices < 1) slices = 1;
         if (slices > 4096) slices = 4096;
+        // few rows (the joins of a handful of long paths): shorter pieces, down to 512 words, for about two
+        // workgroups per compute unit
+        if (B * slices < 512) {
+            int64_t want = (512 + B - 1) / B, most = rs.pow[rs.depth] / 512;
+            if (want > most) want = most;
+            if (want > slices) slices = want;
+        }
         const int64_t items = B * slices;
         const int64_t grid = items < 8 * 256 ? items : 8 * 256;
         const size_t lds = (size_t)(2 * low) * sizeof(float);

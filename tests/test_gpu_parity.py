@@ -115,6 +115,40 @@ ON_CHIP_CASES = [
 ]
 
 
+# time segments whose partial rows are too long for the LDS of a join kernel: joined in device memory by a pairwise tree
+# of batched row products (a power of two of segments, up to 32); lane states above 64 floats, lanes of a path
+# within one workgroup ((10,4), (8,4), (6,5)) and across several ((7,5): 343 lanes), ragged and empty last segments
+TREE_JOIN_CASES = [
+    # d, depth, p, B, L, segments, tile_steps
+    (10, 4, 2, 1, 700, 8, 0), (10, 4, 2, 3, 333, 4, 0), (10, 4, 2, 2, 65, 32, 0), (8, 4, 2, 5, 200, 16, 7),
+    (6, 5, 3, 2, 150, 8, 0), (7, 5, 3, 1, 130, 4, 0), (7, 5, 3, 2, 97, 16, 0), (9, 4, 2, 1, 40, 32, 0),
+    (4, 6, 4, 1, 90, 8, 0),
+]
+
+
+@pytest.mark.parametrize("case", TREE_JOIN_CASES, ids=lambda c: "-".join(str(v) for v in c))
+def test_on_chip_segments_joined_in_device_memory(gpu, oracle, case):
+    d, depth, p, B, L, segments, tile = case
+    assert gpu.sig_on_chip_available(d, depth, p)
+    x = workloads.brownian_paths(B, L, d, seed=5200 + 17 * B + L + segments)
+    plan = gpu.make_plan(gpu.SIG_VARIANT_ON_CHIP, prefix_depth=p, chunks=1, segments=segments, tile_steps=tile)
+    check(gpu, oracle, x, depth, False, plan, label="on-chip, tree join")
+    # not a power of two, or more than 32: refused on the host
+    for bad in (3, 6, 64):
+        if bad * gpu.sig_size(d, depth) * 4 > 64 * 1024:
+            bad_plan = gpu.make_plan(gpu.SIG_VARIANT_ON_CHIP, prefix_depth=p, chunks=1, segments=bad)
+            assert gpu.sig_plan_validate(B, L, d, depth, 0, bad_plan) == gpu.SIG_ERR_INVALID
+
+
+@pytest.mark.parametrize("d,depth,B,L", [(10, 4, 1, 1000), (8, 4, 3, 2000), (7, 5, 1, 600), (6, 5, 2, 900), (4, 6, 1, 1500)])
+def test_few_long_paths_with_large_states_auto(gpu, oracle, d, depth, B, L):
+    """The planner cuts few long paths of shapes with large lane states into tree-joined segments."""
+    rc, pl = gpu.sig_plan(gpu.default_ctx(), B, L, d, depth, 0)
+    assert rc == gpu.SIG_OK and pl.variant == gpu.SIG_VARIANT_ON_CHIP and pl.segments >= 4
+    x = workloads.brownian_paths(B, L, d, seed=5300 + L)
+    check(gpu, oracle, x, depth, False, None, label="auto, tree join")
+
+
 def split_case(case):
     d, depth, p, B, L, chunks, segments, tile, stream = case[:9]
     threads = case[9] if len(case) > 9 else 256
