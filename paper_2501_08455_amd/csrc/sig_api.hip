@@ -373,9 +373,9 @@ int plan_auto(const sig_ctx *ctx, int64_t B, int64_t L, int stream_flag, const R
         // wavefronts per SIMD (measured there: up to 15x faster, e.g. d = 8, depth 4, one path of 500 points: 49
         // against 737 us; the estimates err on the side of the on-chip kernels).
         // Final mode: only plans that could not be cut in time at all (large lane states whose rows do not fit LDS
-        // for a join) can lose, with few long paths: K dependent steps of 0.1 + 0.002 us per state float against the
-        // level-scan family's launches plus 2.6 x its scratch tensor at 2 TB/s (d = 10, depth 4, one path of 2,000
-        // points: 207 against 570 us).
+        // for a join, on paths too short for a join in device memory) can lose, with few paths: K dependent steps
+        // of 0.1 + 0.002 us per state float against the level-scan family's launches plus 2.6 x its scratch tensor
+        // at 2 TB/s.
         auto prefer_level_scan = [&](const sig_plan_t &chosen) {
             sig_plan_t ls{};
             ls.variant = SIG_VARIANT_LEVEL_SCAN;
