@@ -333,7 +333,9 @@ int backward_segments(int d, int depth, int64_t B, int64_t L, int cus, bool uncu
     }
     while (W <= kMaxSegments && W <= K && !e->fits((K + W - 1) / W)) ++W;
     if (W > kMaxSegments || W > K || (K + W - 1) / W < 2) return 1;
-    return (int)W;
+    const int64_t T = (K + W - 1) / W;   // increments per segment; no segment is left without increments
+    W = (K + T - 1) / T;
+    return W < 2 ? 1 : (int)W;
 }
 
 int64_t backward_segmented_scratch_floats(int d, int depth, int64_t B, int64_t L, int segs)

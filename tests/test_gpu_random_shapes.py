@@ -52,3 +52,46 @@ def test_random_shape(gpu, oracle, shape):
     err = np.linalg.norm(gx - want_g) / np.linalg.norm(want_g)
     say("  gradient: %.2e (%s)" % (err, "register kernel" if gpu.sig_backward_available(d, depth) else "general sweep"))
     assert np.all(np.isfinite(gx)) and err <= TOL
+
+
+def draw_long_paths(count, seed):
+    """Few long paths in final mode: the shapes where the forward pass is cut into tree-joined segments and the
+    reverse sweep into time segments across workgroups (lengths that leave ragged last pieces)."""
+    rng = np.random.default_rng(seed)
+    shapes = []
+    while len(shapes) < count:
+        d = int(rng.integers(2, 11))
+        depth = int(rng.integers(2, 7))
+        D = workloads.sig_size(d, depth)
+        if D > 30000:
+            continue
+        L = int(rng.integers(130, 3000))
+        B = int(rng.choice([1, 1, 2, 3, 5, 9, 20, 40]))
+        if B * L * D > 3e7:
+            continue
+        shapes.append((B, L, d, depth))
+    return shapes
+
+
+LONG_PATHS = draw_long_paths(40, seed=20250108456)
+
+
+@pytest.mark.parametrize("shape", LONG_PATHS, ids=lambda c: "-".join(str(int(v)) for v in c))
+def test_random_long_paths(gpu, oracle, shape):
+    B, L, d, depth = shape
+    rc, pl = gpu.sig_plan(None, B, L, d, depth, 0)
+    assert rc == gpu.SIG_OK
+    segs = gpu.sig_backward_segments(None, B, L, d, depth, 0)
+    say("long paths B=%d L=%d d=%d depth=%d plan=%s gradient segments=%d" % (B, L, d, depth, pl.as_dict(), segs))
+    x = workloads.brownian_paths(B, L, d, seed=B * 1000 + L * 10 + d)
+    got = run_gpu(gpu, x, depth, False, None)
+    errs = level_errors(got, oracle.signature(x, depth), d, depth)
+    say("  forward: " + " ".join("%.2e" % e for e in errs))
+    assert max(errs) <= TOL
+    g = upstream(np.random.default_rng(L + d), B, 1, d, depth)[:, 0]
+    rc, gx = run_backward(gpu, x, depth, False, g)
+    assert rc == gpu.SIG_OK
+    want_g = oracle.signature_backward(x, depth, g)
+    err = np.linalg.norm(gx - want_g) / np.linalg.norm(want_g)
+    say("  gradient: %.2e" % err)
+    assert np.all(np.isfinite(gx)) and err <= TOL
