@@ -109,6 +109,51 @@ def test_graph_capture_and_replay(gpu, oracle):
         gpu.sig_destroy(ctx)
 
 
+def test_graph_capture_of_the_paths_cut_in_time(gpu, oracle):
+    """The multi-launch paths for few long paths — forward segments joined in device memory (six launches here) and
+    the gradient cut into time segments (nine) — captured together and replayed with new inputs."""
+    import torch
+    B, L, d, depth = 2, 900, 10, 4
+    D = gpu.sig_size(d, depth)
+    ctx = gpu.sig_create()
+    try:
+        rc, pl = gpu.sig_plan(ctx, B, L, d, depth, 0)
+        assert rc == gpu.SIG_OK and pl.variant == gpu.SIG_VARIANT_ON_CHIP and pl.segments >= 4
+        assert gpu.sig_backward_segments(ctx, B, L, d, depth, 0) > 1
+        xs = [workloads.brownian_paths(B, L, d, seed=96 + i) for i in range(3)]
+        g = np.random.default_rng(5).normal(size=(B, D)).astype(np.float32)
+        xt, gt = torch.from_numpy(xs[0]).cuda(), torch.from_numpy(g).cuda()
+        out, gx = torch.zeros((B, D), device="cuda"), torch.zeros(xs[0].shape, device="cuda")
+
+        def both():
+            assert gpu.sig_compute(ctx, xt, depth, 0, out) == gpu.SIG_OK
+            assert gpu.sig_backward(ctx, xt, depth, 0, out, gt, gx) == gpu.SIG_OK
+
+        both()   # sizes the scratch
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            both()
+        for i, x in enumerate(xs):
+            xt.copy_(torch.from_numpy(x).cuda())
+            out.fill_(float("nan"))
+            gx.fill_(float("nan"))
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            r_out, r_gx = out.clone(), gx.clone()
+            both()
+            torch.cuda.synchronize()
+            assert torch.equal(r_out, out) and torch.equal(r_gx, gx), i
+            assert max(level_errors(r_out.cpu().numpy(), oracle.signature(x, depth), d, depth)) <= TOL
+            want = oracle.signature_backward(x, depth, g)
+            assert np.linalg.norm(r_gx.cpu().numpy() - want) / np.linalg.norm(want) <= TOL
+        say("  graph replay, paths cut in time: three replays equal the eager calls bit for bit")
+    finally:
+        torch.cuda.synchronize()
+        gpu.sig_destroy(ctx)
+
+
 def test_pointers_that_are_only_float_aligned(gpu, oracle):
     """The ABI asks for float32 arrays, not for 16-byte alignment: every family, and the gradient, with path, output and
     gradient buffers that start 4 bytes past a 16-byte boundary."""
