@@ -201,6 +201,24 @@ def table1(binding, workloads, ctx, d=5):
     return rows
 
 
+def memory_wall_shape(binding, workloads, ctx):
+    """The shape the paper names as the memory wall of its level-by-level formulation (Section on limitations:
+    batch 128, length 500, 10 channels, depth 4, more than 700 million intermediate values): forward and gradient
+    here, with the device scratch each call needs."""
+    import torch
+    B, L, d, depth = 128, 500, 10, 4
+    x = torch.from_numpy(workloads.brownian_paths(B, L, d, seed=1500)).cuda()
+    out = torch.empty((B, workloads.sig_size(d, depth)), dtype=torch.float32, device="cuda")
+    ms, _ = time_calls(binding, ctx, x, depth, 0, out, 200, 100)
+    rc, pl = binding.sig_plan(ctx, B, L, d, depth, 0)
+    cfg = workloads.Config("memory wall", B, L, d, depth, False, "normal")
+    grad = bench_backward(binding, workloads, ctx, cfg, B, 50, 20, seed=1500)
+    partial = B * pl.segments * workloads.sig_size(d, depth) * 4 if pl.segments > 1 else 0
+    return {"batch": B, "length": L, "channels": d, "depth": depth, "ms_forward": ms, "plan": pl.as_dict(),
+            "forward_scratch_bytes": partial, "ms_gradient": grad["ms_per_step"],
+            "paper_intermediate_values": "more than 700 million (2.8 GB in fp32)"}
+
+
 STREAM_GRID_SHAPES = [(2, 3), (2, 4), (2, 6), (3, 3), (3, 4), (3, 5), (4, 3), (4, 4), (4, 5), (5, 2), (5, 3), (5, 4),
                       (5, 5), (6, 3), (6, 4), (7, 3), (8, 3), (8, 4), (9, 3), (10, 2), (10, 3), (10, 4)]
 
@@ -415,6 +433,7 @@ def main():
             extras.append(bench_backward(binding, workloads, ctx, one, 1, 200, 100, seed=workloads.BASE_SEED + 11))
         line["all_configs"] = extras
         line["table1_shapes"] = table1(binding, workloads, ctx)
+        line["memory_wall_shape"] = memory_wall_shape(binding, workloads, ctx)
         # a training step of the paper's model with the signature layer in the middle (context for Section 4.2)
         line["training_step"] = [training_step(workloads, 128, L, d, depth, 100, 30)
                                  for (L, d, depth) in [(100, 5, 4), (200, 6, 3), (500, 4, 4)]]

@@ -292,13 +292,17 @@ constexpr int64_t kMaxSegmentRow = 1 << 17;   // one workgroup forms a product o
 // shape whose plain sweep holds C chunks of a path side by side in its workgroup) to about K / W, for
 // ceil(log2 W) + 3 more launches of 3-6 us each.  Rules, from a measured grid (15 shapes, B = 1 .. 1,024,
 // L = 100 .. 2,000):
-//   * from 128 increments on, while the uncut launch has fewer workgroups than compute units;
+//   * from 128 increments on, while the uncut launch has fewer than two workgroups per compute unit (between one
+//     and two, a few segments still pay: d = 8, depth 4, 128 paths of 500 points, 292 -> 187 us with four);
 //   * shapes whose plain sweep holds eight or more chunks: only from 512 increments on; with six or more chunks:
 //     only up to 32 paths (cutting wins or ties at every measured point up to there; beyond, the plain sweep's
 //     workgroups fill enough of the chip).  Long paths leave the plain sweep fewer chunks (their increments take
 //     the LDS), so they are cut at larger batches as well (d = 5, depth 4, 128 paths of 2,000 points: three chunks,
 //     328 -> 173 us);
-//   * W = K / 24, at most 32, at most two wavefronts per SIMD over the chip, one set of rows within 8 MB;
+//   * W = K / 24, at most 32, at most two workgroups per compute unit (two wavefronts per SIMD for the shapes that
+//     pack several pieces into a workgroup), one set of rows within 8 MB (beyond, the scan's traffic costs more
+//     than the shorter sweeps save); a launch that has a workgroup per compute unit already: at most 4 segments,
+//     four workgroups per compute unit, 16 MB;
 //   * a path whose increments do not fit the LDS of the uncut sweep (uncut_fits == false) is cut at any batch size,
 //     as little as makes a segment fit.
 int backward_segments(int d, int depth, int64_t B, int64_t L, int cus, bool uncut_fits)
@@ -309,7 +313,7 @@ int backward_segments(int d, int depth, int64_t B, int64_t L, int cus, bool uncu
     const bool packed = e->lanes * 2 <= onchip::kSliceLanes;   // several pieces share a workgroup
     const int64_t slices = (e->lanes + onchip::kSliceLanes - 1) / onchip::kSliceLanes;
     const int64_t chip_lanes = (int64_t)cus * 4 * kWave * 2;   // two wavefronts on every SIMD
-    bool busy = B * slices >= cus;   // the uncut launch already has a workgroup for every compute unit
+    bool busy = B * slices >= 2 * (int64_t)cus;   // the uncut launch already has two workgroups for every compute unit
     int64_t min_steps = 128;
     if (packed && uncut_fits) {
         const int chunks = e->uncut_chunks(L);
@@ -321,10 +325,14 @@ int backward_segments(int d, int depth, int64_t B, int64_t L, int cus, bool uncu
     if (!busy) {
         W = K / 24;
         if (W > kMaxSegments) W = kMaxSegments;
-        const int64_t room = packed ? chip_lanes / (B * e->lanes) : (2 * (int64_t)cus) / (B * slices);
+        // a launch that already has a workgroup per compute unit takes at most four segments
+        const bool half_full = B * slices >= cus;
+        if (half_full && W > 4) W = 4;
+        const int64_t room = packed ? chip_lanes / (B * e->lanes) : ((half_full ? 4 : 2) * (int64_t)cus) / (B * slices);
         if (W > room) W = room;
-        // the scan reads and writes all B * W rows in every round: keep one set of rows within 8 MB
-        const int64_t by_rows = kMaxSegmentFloats / (B * e->row);
+        // the scan reads and writes all B * W rows in every round: keep one set of rows within 8 MB (16 MB for the
+        // few segments of a half-full launch)
+        const int64_t by_rows = (half_full ? 2 : 1) * kMaxSegmentFloats / (B * e->row);
         if (W > by_rows) W = by_rows;
         if (W < 2) {
             if (uncut_fits) return 1;

@@ -215,7 +215,9 @@ def test_backward_segment_rule():
     seg = lambda B, L, d, depth, stream=0: binding.sig_backward_segments(None, B, L, d, depth, stream)
     # short paths and full batches stay uncut
     assert seg(128, 100, 5, 4) == 1 and seg(65536, 100, 5, 4) == 1 and seg(1, 100, 10, 4) == 1
-    assert seg(1024, 1000, 10, 4) == 1
+    assert seg(1024, 1000, 10, 4) == 1 and seg(128, 500, 10, 4) == 1
+    # between one and two workgroups per compute unit a few segments still pay
+    assert 2 <= seg(128, 500, 8, 4) <= 4 and 2 <= seg(256, 500, 5, 5) <= 4
     # few long paths are cut, at most 32 times, and a segment keeps at least two dozen increments
     for B, L, d, depth in [(1, 1000, 5, 4), (1, 1000, 10, 4), (16, 500, 8, 4), (3, 300, 5, 5), (2, 4001, 2, 3)]:
         W = seg(B, L, d, depth)

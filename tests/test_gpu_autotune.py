@@ -10,19 +10,24 @@ from test_gpu_parity import TOL, gpu, level_errors, say  # noqa: F401  (gpu is a
 pytestmark = pytest.mark.gpu
 
 
-def time_calls(gpu, ctx, xt, depth, stream, out, plan=None, reps=30):
+def time_calls(gpu, ctx, xt, depth, stream, out, plan=None, reps=30, rounds=5):
+    """Microseconds per call: the fastest of several rounds of back-to-back calls (a round now and then takes a
+    multiple of the others on a box that has just freed or mapped memory; the comparison is about the kernels)."""
     import torch
     call = gpu.bind_compute(ctx, xt, depth, int(stream), out, plan=plan)
     for _ in range(10):
         assert call() == gpu.SIG_OK
     torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for _ in range(reps):
-        call()
-    e1.record()
-    torch.cuda.synchronize()
-    return e0.elapsed_time(e1) / reps * 1e3
+    best = float("inf")
+    for _ in range(rounds):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            call()
+        e1.record()
+        torch.cuda.synchronize()
+        best = min(best, e0.elapsed_time(e1) / reps * 1e3)
+    return best
 
 
 @pytest.mark.parametrize("B,L,d,depth,stream", [(128, 100, 5, 4, False), (16, 256, 2, 4, True), (128, 500, 10, 2, True),
