@@ -183,12 +183,14 @@ int sig_combine(sig_ctx *ctx, const float *a, const float *b, int64_t B, int d, 
  * compiled register kernel (see sig_backward_available) whose paths fit its LDS staging take it.  In final mode,
  * few long paths (fewer workgroups than compute units, from 128 increments on; from 512, and mostly up to 32
  * paths, for shapes with at most 32 lanes per path) and paths too long for that staging are cut into up to 32
- * time segments that are swept by different workgroups: by Eq. 3 a segment can start from the signature of the path up to its end and the gradient
- * with respect to it, which a scan over the segments' own signatures provides.  Every other shape with d <= 256
- * takes a general sweep, one workgroup per path with its state in LDS or device scratch (much slower);
- * SIG_ERR_UNSUPPORTED only for d > 256.
+ * time segments that are swept by different workgroups: by Eq. 3 a segment can start from the signature of the
+ * path up to its end and the gradient with respect to it, which a scan over the segments' own signatures provides.
+ * Stream-mode paths too long for the staging are walked in tiles of 256 increments by one workgroup.  Every shape
+ * without a register kernel, d <= 256, takes a general sweep, one workgroup per path with its state in LDS or
+ * device scratch (much slower); SIG_ERR_UNSUPPORTED only for d > 256.
  * Context scratch (allocated on first use, SIG_ERR_ALLOC if that fails): shapes whose index space is cut into more
- * sub-trees than one workgroup has threads keep per-workgroup sums (B * ceil(d^p / 256) * (L-1) * d floats); the
+ * sub-trees than one workgroup has threads, and paths walked in tiles, keep per-workgroup sums
+ * (B * ceil(d^p / 256) * (L-1) * d floats); the
  * sweep cut into W segments keeps those sums and 5 * B * W * D floats of segment rows; the general sweep keeps
  * B * (L-1) * d floats plus, when they exceed 48 KB per path, about 2.5 D floats per path.
  * Deterministic (fixed summation order).  Arithmetic is float32 with FMA.

@@ -834,8 +834,8 @@ int sig_backward(sig_ctx *ctx, const float *path, int64_t B, int64_t L, int d, i
             return es == hipSuccess ? SIG_OK : SIG_ERR_HIP;
         }
     }
-    if (!fits) {
-        // no register kernel for this shape, or the path is too long for its LDS staging: the general sweep
+    if (!fits && !(backward_available(d, depth) && backward_tiles_fit(d, depth))) {
+        // no register kernel for this shape: the general sweep
         if (!backward_general_available(d) || B > INT32_MAX) return SIG_ERR_UNSUPPORTED;
         const int64_t need = backward_general_scratch_floats(B, L, rs);
         if (need <= 0 || need > (int64_t)1 << 36) return SIG_ERR_TOO_LARGE;
@@ -866,7 +866,7 @@ int sig_backward_segments(const sig_ctx *ctx, int64_t B, int64_t L, int d, int d
         const int segs = backward_segments(d, depth, B, L, ctx ? ctx->num_cu : kDefaultCUs, fits);
         if (segs > 1) return segs;
     }
-    return fits ? 1 : 0;
+    return fits || backward_tiles_fit(d, depth) ? 1 : 0;
 }
 
 int sig_backward_available(int d, int depth)

@@ -158,6 +158,9 @@ struct BackwardArgs {
     const float *seg_sig;
     const float *seg_grad;
     float *seg_part;        // register sweep cut in time: d(loss)/d(increment), [B][L-1][d]
+    // Long paths whose increments do not fit LDS at once (either mode): tiled != 0 makes a workgroup walk the segs
+    // pieces of its paths one after the other, last first, with its state in registers; no seg_sig / seg_grad rows.
+    int32_t tiled;
 };
 
 // steps whose partial sums are parked before they are added up: enough for every lane of a path to have a
@@ -186,6 +189,9 @@ struct Park {
 };
 
 extern __shared__ float sig_backward_smem[];
+
+// increments per tile when a path is too long for the LDS of the uncut sweep and one workgroup walks it in tiles
+constexpr int kTiledSteps = 256;
 
 // Register sweep: the d^P lanes of a path fit a workgroup, which takes `groups` paths side by side.
 // SEG (final mode): the sweep is cut in time and the workgroup takes `groups` (path, segment) pieces instead, piece
@@ -355,6 +361,116 @@ __global__ __launch_bounds__(256) void sig_backward_kernel(BackwardArgs A)
     }
 }
 
+// Register sweep over paths whose increments do not fit LDS at once: the workgroup walks the A.segs tiles of
+// A.seg_steps increments of its `groups` paths one after the other, last first, with the lane states in registers,
+// and leaves the sums over the increments in seg_part ([B][L-1][d]); another launch forms d(loss)/dX.  Sequential in
+// time like the plain sweep (no chunks), but any length fits.  Stream mode fetches a row's upstream gradient one
+// step ahead.
+template <int d, int N, int P, bool STREAM>
+__global__ __launch_bounds__(256) void sig_backward_tiled_kernel(BackwardArgs A)
+{
+    using Sh = Shape<d, N, P>;
+    constexpr int Q = Sh::Q;
+    constexpr int D = Sh::D;
+    constexpr int TS = reduce_steps<d, P>();
+    using Pk = Park<d, P>;
+    const int tid = threadIdx.x, nthr = blockDim.x;
+    const int64_t Kall = A.L - 1;
+    const int64_t T = A.seg_steps;
+    const int G = A.groups;
+    const int gi_raw = tid / Q;
+    const unsigned u = (unsigned)(tid - gi_raw * Q);
+    const int64_t b0 = (int64_t)blockIdx.x * G;
+    const bool active = gi_raw < G && b0 + gi_raw < A.B;
+    const int gi = gi_raw < G ? gi_raw : 0;
+    const int64_t b = active ? b0 + gi : 0;
+
+    int letter[P > 0 ? P : 1];
+    letter[0] = 0;
+    {
+        unsigned rest = u;
+#pragma unroll
+        for (int m = P - 1; m >= 0; --m) { letter[m] = (int)(rest % d); rest /= d; }
+    }
+
+    const int row_stride = (int)T * d;   // a path's part of the tile
+    float *tile = sig_backward_smem;
+    float *park = tile + (G * row_stride + 3) / 4 * 4;
+    float *mypark = park + (size_t)gi * TS * Pk::kStepFloats;
+    float *myrow = tile + gi * row_stride;
+
+    Lane<d, N, P> ln, ad, up;
+    identity_state<d, N, P>(ln);
+    identity_state<d, N, P>(ad);
+    identity_state<d, N, P>(up);
+    if (P == 0) { ad.s[0] = 0.0f; up.s[0] = 0.0f; }
+    if (active) {
+        load_state<d, N, P>(STREAM ? A.sig + (b * Kall + (Kall - 1)) * D : A.sig + b * D, u, ln);
+        if constexpr (STREAM) load_adjoint<d, N, P, false>(A.grad_out + (b * Kall + (Kall - 1)) * D, u, up);
+        else load_adjoint<d, N, P, false>(A.grad_out + b * D, u, ad);
+    }
+
+    for (int tl = A.segs - 1; tl >= 0; --tl) {
+        const int64_t k0 = (int64_t)tl * T;
+        const int64_t K = Kall - k0 < T ? Kall - k0 : T;
+        const int row_floats = (int)K * d;
+        if (tl != A.segs - 1) __syncthreads();   // the previous tile's sums have been written out
+        for (int i = tid; i < G * row_floats; i += nthr) {
+            const int g2 = i / row_floats;
+            const int r = i - g2 * row_floats;
+            float v = 0.0f;
+            if (b0 + g2 < A.B) {
+                const float *x = A.path + ((b0 + g2) * A.L + k0) * d + r;
+                v = x[d] - x[0];
+            }
+            tile[g2 * row_stride + r] = v;
+        }
+        __syncthreads();
+        for (int64_t k = K - 1; k >= 0; --k) {
+            const int ts = (int)((K - 1 - k) % TS);
+            if constexpr (STREAM) {
+#pragma unroll
+                for (int i = 0; i < Sh::SZ; ++i) ad.s[i] += up.s[i];
+#pragma unroll
+                for (int i = 0; i < Sh::NPRE; ++i) ad.pre[i] += up.pre[i];
+                if (active && k0 + k > 0) load_adjoint<d, N, P, false>(A.grad_out + (b * Kall + (k0 + k - 1)) * D, u, up);
+            }
+            Inc<d, P> inc, neg;
+            load_inc<d, P>(inc, myrow + k * d, letter);
+#pragma unroll
+            for (int a = 0; a < d; ++a) neg.v[a] = -inc.v[a];
+            neg.du[0] = 0.0f;
+#pragma unroll
+            for (int m = 0; m < P; ++m) neg.du[m] = -inc.du[m];
+            if (k0 + k > 0) fused_step<d, N, P>(ln, neg);
+            else identity_state<d, N, P>(ln);
+            float dbar[d];
+            backward_step<d, N, P>(ln, ad, inc, letter, dbar);
+            if (active) {
+#pragma unroll
+                for (int a = 0; a < d; ++a) mypark[Pk::at(ts, (int)u, a)] = dbar[a];
+            }
+            if (ts == TS - 1 || k == 0) {
+                __syncthreads();
+                if (active) {
+                    for (int c = (int)u; c < (ts + 1) * d; c += Q) {
+                        const int t = c / d, a = c - t * d;
+                        float sum = 0.0f;
+                        for (int q = 0; q < Q; ++q) sum += mypark[Pk::at(t, q, a)];
+                        myrow[(k + (ts - t)) * d + a] = sum;
+                    }
+                }
+                __syncthreads();
+            }
+        }
+        for (int i = tid; i < G * row_floats; i += nthr) {
+            const int g2 = i / row_floats;
+            const int r = i - g2 * row_floats;
+            if (b0 + g2 < A.B) A.seg_part[((b0 + g2) * Kall + k0) * d + r] = tile[g2 * row_stride + r];
+        }
+    }
+}
+
 // LDS bytes of the register sweep with `groups` paths (or pieces) of L points per workgroup
 template <int d, int N, int P>
 int64_t backward_lds_bytes(int64_t L, int groups)
@@ -432,6 +548,9 @@ __global__ __launch_bounds__(kSliceLanes) void sig_backward_sliced_kernel(Backwa
 {
     // TS: steps whose partial sums are parked before they are added up (at most slice_reduce_steps<d>(); fewer
     // when a long path leaves less LDS)
+    // A.segs > 1 cuts the path into pieces of A.seg_steps increments: every piece a workgroup of its own (final
+    // mode, see BackwardArgs), or with A.tiled the workgroup walks the pieces of its path one after the other, last
+    // first, with its state in registers, so that only one piece's increments are staged in LDS at a time.
     using Sh = Shape<d, N, P>;
     constexpr int Q = Sh::Q;
     constexpr int D = Sh::D;
@@ -440,13 +559,13 @@ __global__ __launch_bounds__(kSliceLanes) void sig_backward_sliced_kernel(Backwa
     const int tid = threadIdx.x, nthr = blockDim.x;
     const int slice = (int)(blockIdx.x % slices);
     const int64_t piece = blockIdx.x / slices;
-    const int W = (!STREAM && A.segs > 1) ? A.segs : 1;
+    const int W = (!STREAM && !A.tiled && A.segs > 1) ? A.segs : 1;   // pieces that are workgroups of their own
+    const int tiles = (A.tiled && A.segs > 1) ? A.segs : 1;           // pieces this workgroup walks
     const int64_t b = piece / W;
     const int seg = (int)(piece - b * W);
-    const int64_t Kall = A.L - 1;                       // increments of the path
-    const int64_t k0 = (int64_t)seg * A.seg_steps;      // first increment of this piece (W == 1: 0)
-    const int64_t K = W > 1 ? (Kall - k0 < A.seg_steps ? Kall - k0 : A.seg_steps) : Kall;
-    if (K <= 0) return;                                 // a trailing segment without increments
+    const int64_t Kall = A.L - 1;                            // increments of the path
+    const int64_t T = (W > 1 || tiles > 1) ? A.seg_steps : Kall;
+    if (W > 1 && (int64_t)seg * T >= Kall) return;           // a trailing segment without increments
     const unsigned u_raw = (unsigned)(slice * kSliceLanes + tid);
     const bool active = u_raw < (unsigned)Q;
     const unsigned u = active ? u_raw : 0u;
@@ -459,15 +578,10 @@ __global__ __launch_bounds__(kSliceLanes) void sig_backward_sliced_kernel(Backwa
         for (int m = P - 1; m >= 0; --m) { letter[m] = (int)(rest % d); rest /= d; }
     }
 
-    // LDS: increments [K*d] (overwritten with this slice's sums), parked partial sums [TS][d][kParkRow], stretch sums
-    const int row_floats = (int)K * d;
+    // LDS: increments [T*d] (overwritten with this slice's sums), parked partial sums [TS][d][kParkRow], stretch sums
     float *tile = sig_backward_smem;
-    float *park = tile + (row_floats + 3) / 4 * 4;
+    float *park = tile + ((int)T * d + 3) / 4 * 4;
     float *red = park + TS * kParkStep;
-    {
-        const float *x = A.path + (b * A.L + k0) * d;
-        for (int i = tid; i < row_floats; i += nthr) tile[i] = x[i + d] - x[i];
-    }
 
     Lane<d, N, P> ln, ad;
     identity_state<d, N, P>(ln);
@@ -475,70 +589,80 @@ __global__ __launch_bounds__(kSliceLanes) void sig_backward_sliced_kernel(Backwa
     if (P == 0) ad.s[0] = 0.0f;
     if (active) {
         const bool inner = seg < W - 1;   // a segment that ends inside the path
-        const float *srow = STREAM ? A.sig + (b * K + (K - 1)) * D : inner ? A.seg_sig + piece * D : A.sig + b * D;
+        const float *srow = STREAM ? A.sig + (b * Kall + (Kall - 1)) * D : inner ? A.seg_sig + piece * D : A.sig + b * D;
         load_state<d, N, P>(srow, u, ln);
         if constexpr (!STREAM) load_adjoint<d, N, P, false>(inner ? A.seg_grad + piece * D : A.grad_out + b * D, u, ad);
     }
-    __syncthreads();
-
     Lane<d, N, P> up;   // upstream gradient of the row the sweep reaches next (stream mode), fetched one step ahead
     if constexpr (STREAM) {
         identity_state<d, N, P>(up);
         if (P == 0) up.s[0] = 0.0f;
-        if (active) load_adjoint<d, N, P, false>(A.grad_out + (b * K + (K - 1)) * D, u, up);
+        if (active) load_adjoint<d, N, P, false>(A.grad_out + (b * Kall + (Kall - 1)) * D, u, up);
     }
-    for (int64_t k = K - 1; k >= 0; --k) {
-        const int ts = (int)((K - 1 - k) % TS);
-        if constexpr (STREAM) {
-#pragma unroll
-            for (int i = 0; i < Sh::SZ; ++i) ad.s[i] += up.s[i];
-#pragma unroll
-            for (int i = 0; i < Sh::NPRE; ++i) ad.pre[i] += up.pre[i];
-            if (active && k > 0) load_adjoint<d, N, P, false>(A.grad_out + (b * K + (k - 1)) * D, u, up);
+
+    for (int tl = tiles - 1; tl >= 0; --tl) {
+        const int64_t k0 = (int64_t)(W > 1 ? seg : tl) * T;   // first increment of this piece (one piece: 0)
+        const int64_t K = Kall - k0 < T ? Kall - k0 : T;
+        const int row_floats = (int)K * d;
+        if (tl != tiles - 1) __syncthreads();   // the previous piece's sums have been written out
+        {
+            const float *x = A.path + (b * A.L + k0) * d;
+            for (int i = tid; i < row_floats; i += nthr) tile[i] = x[i + d] - x[i];
         }
-        Inc<d, P> inc, neg;
-        load_inc<d, P>(inc, tile + k * d, letter);
+        __syncthreads();
+        for (int64_t k = K - 1; k >= 0; --k) {
+            const int ts = (int)((K - 1 - k) % TS);
+            if constexpr (STREAM) {
 #pragma unroll
-        for (int a = 0; a < d; ++a) neg.v[a] = -inc.v[a];
-        neg.du[0] = 0.0f;
+                for (int i = 0; i < Sh::SZ; ++i) ad.s[i] += up.s[i];
 #pragma unroll
-        for (int m = 0; m < P; ++m) neg.du[m] = -inc.du[m];
-        if (k0 + k > 0) fused_step<d, N, P>(ln, neg);  // S_{k-1} = S_k (x) exp(-dX_k)
-        else identity_state<d, N, P>(ln);
-        float dbar[d];
-        backward_step<d, N, P>(ln, ad, inc, letter, dbar);
-#pragma unroll
-        for (int a = 0; a < d; ++a) park[ts * kParkStep + a * kParkRow + tid + (tid >> 5)] = active ? dbar[a] : 0.0f;
-        if (ts == TS - 1 || k == 0) {
-            __syncthreads();
-            // column c = (parked step t, channel a), first in kSliceSplit stretches of lanes, then the stretches
-            const int cols = (ts + 1) * d;
-            constexpr int stretch = kSliceLanes / kSliceSplit;
-            static_assert(stretch == 32, "the parked layout pads one float per 32 lanes");
-            for (int w = tid; w < cols * kSliceSplit; w += nthr) {
-                const int c = w / kSliceSplit, r = w - c * kSliceSplit;
-                const int t = c / d, a = c - t * d;
-                // (idle lanes parked zeros, so every stretch is summed in full: a fixed trip count lets the reads
-                // be issued together)
-                const float *src = park + t * kParkStep + a * kParkRow + r * (stretch + 1);
-                float sum = 0.0f;
-#pragma unroll
-                for (int q = 0; q < stretch; ++q) sum += src[q];
-                red[w] = sum;
+                for (int i = 0; i < Sh::NPRE; ++i) ad.pre[i] += up.pre[i];
+                if (active && k0 + k > 0) load_adjoint<d, N, P, false>(A.grad_out + (b * Kall + (k0 + k - 1)) * D, u, up);
             }
-            __syncthreads();
-            for (int c = tid; c < cols; c += nthr) {
-                const int t = c / d, a = c - t * d;
-                float sum = 0.0f;
+            Inc<d, P> inc, neg;
+            load_inc<d, P>(inc, tile + k * d, letter);
 #pragma unroll
-                for (int r = 0; r < kSliceSplit; ++r) sum += red[c * kSliceSplit + r];
-                tile[(k + (ts - t)) * d + a] = sum;   // replaces the increment, which no lane reads again
+            for (int a = 0; a < d; ++a) neg.v[a] = -inc.v[a];
+            neg.du[0] = 0.0f;
+#pragma unroll
+            for (int m = 0; m < P; ++m) neg.du[m] = -inc.du[m];
+            if (k0 + k > 0) fused_step<d, N, P>(ln, neg);  // S_{k-1} = S_k (x) exp(-dX_k)
+            else identity_state<d, N, P>(ln);
+            float dbar[d];
+            backward_step<d, N, P>(ln, ad, inc, letter, dbar);
+#pragma unroll
+            for (int a = 0; a < d; ++a) park[ts * kParkStep + a * kParkRow + tid + (tid >> 5)] = active ? dbar[a] : 0.0f;
+            if (ts == TS - 1 || k == 0) {
+                __syncthreads();
+                // column c = (parked step t, channel a), first in kSliceSplit stretches of lanes, then the stretches
+                const int cols = (ts + 1) * d;
+                constexpr int stretch = kSliceLanes / kSliceSplit;
+                static_assert(stretch == 32, "the parked layout pads one float per 32 lanes");
+                for (int w = tid; w < cols * kSliceSplit; w += nthr) {
+                    const int c = w / kSliceSplit, r = w - c * kSliceSplit;
+                    const int t = c / d, a = c - t * d;
+                    // (idle lanes parked zeros, so every stretch is summed in full: a fixed trip count lets the
+                    // reads be issued together)
+                    const float *src = park + t * kParkStep + a * kParkRow + r * (stretch + 1);
+                    float sum = 0.0f;
+#pragma unroll
+                    for (int q = 0; q < stretch; ++q) sum += src[q];
+                    red[w] = sum;
+                }
+                __syncthreads();
+                for (int c = tid; c < cols; c += nthr) {
+                    const int t = c / d, a = c - t * d;
+                    float sum = 0.0f;
+#pragma unroll
+                    for (int r = 0; r < kSliceSplit; ++r) sum += red[c * kSliceSplit + r];
+                    tile[(k + (ts - t)) * d + a] = sum;   // replaces the increment, which no lane reads again
+                }
+                __syncthreads();
             }
-            __syncthreads();
         }
+        float *dst = part + ((b * slices + slice) * Kall + k0) * d;
+        for (int i = tid; i < row_floats; i += nthr) dst[i] = tile[i];
     }
-    float *dst = part + ((b * slices + slice) * Kall + k0) * d;
-    for (int i = tid; i < row_floats; i += nthr) dst[i] = tile[i];
 }
 
 // LDS bytes of the sliced sweep over a path (or time segment) of L points with ts parked steps

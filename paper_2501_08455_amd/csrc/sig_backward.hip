@@ -362,13 +362,23 @@ int64_t backward_sliced_scratch_floats(int64_t B, int64_t L)
 }
 
 template <int d, int N, int P>
-hipError_t backward_sliced_launch(const BackwardArgs &A, float *scratch, int, int, hipStream_t st)
+hipError_t backward_sliced_launch(const BackwardArgs &A0, float *scratch, int, int, hipStream_t st)
 {
     constexpr int slices = (Shape<d, N, P>::Q + kSliceLanes - 1) / kSliceLanes;
-    const int ts = backward_sliced_steps<d>(A.L);
-    const int64_t lds = backward_sliced_bytes_with<d>(A.L, ts > 0 ? ts : 1);
+    BackwardArgs A = A0;
+    int64_t points = A.L;   // points of what is staged in LDS at a time
+    if (backward_sliced_steps<d>(A.L) < 1) {
+        // the path's increments do not fit LDS at once: the workgroup walks tiles of kTiledSteps increments
+        A.tiled = 1;
+        A.seg_steps = kTiledSteps;
+        A.segs = (int32_t)((A.L - 1 + kTiledSteps - 1) / kTiledSteps);
+        points = kTiledSteps + 1;
+    }
+    const int ts = backward_sliced_steps<d>(points);
+    const int64_t lds = backward_sliced_bytes_with<d>(points, ts > 0 ? ts : 1);
     const int64_t grid = A.B * slices;
-    if (!scratch || ts < 1 || lds > kMaxLdsBytes || grid <= 0 || grid > INT32_MAX) return hipErrorInvalidValue;
+    if (!scratch || ts < 1 || lds > kMaxLdsBytes || grid <= 0 || grid > INT32_MAX || (A.L - 1) / kTiledSteps > INT32_MAX / 2)
+        return hipErrorInvalidValue;
     if (A.stream_flag)
         hipLaunchKernelGGL((sig_backward_sliced_kernel<d, N, P, true>), dim3((unsigned)grid), dim3(kSliceLanes), (size_t)lds, st, A, scratch, ts);
     else
@@ -378,15 +388,42 @@ hipError_t backward_sliced_launch(const BackwardArgs &A, float *scratch, int, in
     return launch_backward_finish(scratch, A.grad_path, A.B, A.L, d, slices, st);
 }
 
+// the register sweep needs device scratch only for paths it has to walk in tiles: the sums over the increments
 template <int d, int N, int P>
-int64_t backward_no_scratch(int64_t, int64_t) { return 0; }
+int64_t backward_tiled_scratch_floats(int64_t B, int64_t L)
+{
+    return backward_lds_bytes<d, N, P>(L, 1) <= kMaxLdsBytes ? 0 : B * (L - 1) * d;
+}
 
 template <int d, int N, int P>
-hipError_t backward_launch(const BackwardArgs &A0, float *, int threads, int cus, hipStream_t st)
+hipError_t backward_launch(const BackwardArgs &A0, float *scratch, int threads, int cus, hipStream_t st)
 {
     constexpr int Q = Shape<d, N, P>::Q;
     if (threads < Q || threads > 256 || threads % kWave) return hipErrorInvalidValue;
     BackwardArgs A = A0;
+    if (backward_lds_bytes<d, N, P>(A.L, 1) > kMaxLdsBytes) {
+        // the path's increments do not fit LDS at once: tiles of kTiledSteps increments, walked by one workgroup
+        if (!scratch || (A.L - 1) / kTiledSteps > INT32_MAX / 2) return hipErrorInvalidValue;
+        A.tiled = 1;
+        A.seg_steps = kTiledSteps;
+        A.segs = (int32_t)((A.L - 1 + kTiledSteps - 1) / kTiledSteps);
+        A.seg_part = scratch;
+        int G = threads / Q;
+        const int64_t per_cu = (A.B + cus - 1) / (cus > 0 ? cus : 1);
+        if ((int64_t)G > per_cu) G = per_cu > 1 ? (int)per_cu : 1;
+        while (G > 1 && backward_lds_bytes<d, N, P>(kTiledSteps + 1, G) > kMaxLdsBytes) --G;
+        const size_t lds = (size_t)backward_lds_bytes<d, N, P>(kTiledSteps + 1, G);
+        const int64_t grid = (A.B + G - 1) / G;
+        if (lds > (size_t)kMaxLdsBytes || grid <= 0 || grid > INT32_MAX) return hipErrorInvalidValue;
+        A.groups = G;
+        if (A.stream_flag)
+            hipLaunchKernelGGL((sig_backward_tiled_kernel<d, N, P, true>), dim3((unsigned)grid), dim3(threads), lds, st, A);
+        else
+            hipLaunchKernelGGL((sig_backward_tiled_kernel<d, N, P, false>), dim3((unsigned)grid), dim3(threads), lds, st, A);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        return launch_backward_finish(scratch, A.grad_path, A.B, A.L, d, 1, st);
+    }
     // Few paths (fewer lanes than two wavefronts per SIMD): cut the sweep in time, one workgroup per path with
     // as many chunks as its threads and LDS hold, at least eight increments each.
     // (stream mode reads the upstream gradient twice when cut, so only far below one wavefront per SIMD)
@@ -430,7 +467,7 @@ struct BackwardEntry {
     int64_t (*scratch_floats)(int64_t, int64_t);
 };
 #define SIG_BACKWARD_ENTRY(d, N, P) \
-    {d, N, &onchip::backward_launch<d, N, P>, &onchip::backward_lds_bytes<d, N, P>, &onchip::backward_no_scratch<d, N, P>},
+    {d, N, &onchip::backward_launch<d, N, P>, &onchip::backward_lds_bytes<d, N, P>, &onchip::backward_tiled_scratch_floats<d, N, P>},
 #define SIG_BACKWARD_SLICED(d, N, P)                                                                  \
     {d, N, &onchip::backward_sliced_launch<d, N, P>, &onchip::backward_sliced_lds_bytes<d, N, P>, \
      &onchip::backward_sliced_scratch_floats<d, N, P>},
@@ -452,6 +489,12 @@ bool backward_fits(int d, int depth, int64_t L)
 {
     const BackwardEntry *e = find_backward(d, depth);
     return e && e->lds_bytes(L, 1) <= kMaxLdsBytes;
+}
+
+bool backward_tiles_fit(int d, int depth)
+{
+    const BackwardEntry *e = find_backward(d, depth);
+    return e && e->lds_bytes(onchip::kTiledSteps + 1, 1) <= kMaxLdsBytes;
 }
 
 int64_t backward_scratch_floats(int d, int depth, int64_t B, int64_t L)

@@ -55,8 +55,11 @@ hipError_t launch_level_scan(const float *path, float *out, float *scratch, int6
 
 // ---------------------------------------------------------------- gradient with respect to the path (compiled (d, depth) only)
 bool backward_available(int d, int depth);
-// false if even one path per workgroup does not fit LDS (the increments of a whole path are staged at once)
+// false if even one path per workgroup does not fit the LDS of the uncut sweep (the increments of a whole path are
+// staged at once); such paths are walked in tiles by launch_backward (sequential in time, needs scratch)
 bool backward_fits(int d, int depth, int64_t L);
+// whether a tile of the tiled sweep fits LDS (true for every compiled shape; checked before launching)
+bool backward_tiles_fit(int d, int depth);
 // device scratch the launch needs (shapes whose lanes per path span several workgroups keep per-slice sums), in floats
 int64_t backward_scratch_floats(int d, int depth, int64_t B, int64_t L);
 hipError_t launch_backward(const float *path, const float *sig, const float *grad_out, float *grad_path, float *scratch,

@@ -176,11 +176,23 @@ def test_backward_general_sweep(gpu, oracle, shape):
 def test_backward_paths_too_long_for_one_workgroup(gpu, oracle):
     """Paths whose increments exceed the LDS staging of the register kernels (here 3,500 to 20,000 points in five
     channels): final mode cuts them into time segments (also when the batch alone would fill the chip: 300 paths),
-    stream mode takes the general sweep.  The sweep undoes one increment at a time in fp32, so its error grows with
-    the length: measured against the same 1e-4 gate."""
+    stream mode walks them in tiles within one workgroup.  The sweep undoes one increment at a time in fp32, so its
+    error grows with the length: measured against the same 1e-4 gate."""
     for B, L, stream in [(2, 5000, False), (1, 20000, False), (300, 3500, False), (1, 4000, True)]:
         x = workloads.brownian_paths(B, L, 5, seed=8300 + L)
         check(gpu, oracle, x, 4, stream, seed=L, label="long path")
+
+
+@pytest.mark.parametrize("case", [(5, 4, 3, 3300, True), (7, 3, 2, 2500, True), (10, 2, 70, 1700, True), (2, 3, 5, 9000, True),
+                                  (10, 4, 1, 1500, True), (8, 4, 2, 2100, True), (6, 5, 1, 2800, True),
+                                  (10, 2, 2, 60000, False)], ids=lambda c: "-".join(str(v) for v in c))
+def test_backward_walks_long_paths_in_tiles(gpu, oracle, case):
+    """Stream-mode paths too long for LDS (register and sliced sweeps, several paths per workgroup, ragged last tile),
+    and a final-mode path too long even for 32 segments: one workgroup walks tiles of 256 increments."""
+    d, depth, B, L, stream = case
+    assert gpu.sig_backward_segments(None, B, L, d, depth, int(stream)) == 1
+    x = workloads.brownian_paths(B, L, d, seed=8600 + L)
+    check(gpu, oracle, x, depth, stream, seed=L, label="tiled sweep")
 
 
 def test_backward_on_the_configurations(gpu, oracle):
