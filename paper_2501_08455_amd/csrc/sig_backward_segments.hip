@@ -343,6 +343,9 @@ int backward_segments(int d, int depth, int64_t B, int64_t L, int cus, bool uncu
     if (W > kMaxSegments || W > K || (K + W - 1) / W < 2) return 1;
     const int64_t T = (K + W - 1) / W;   // increments per segment; no segment is left without increments
     W = (K + T - 1) / T;
+    // huge batches of long paths: the five sets of segment rows would take more than 2 GiB of scratch; the caller's
+    // tiled sweep needs none of them
+    if (5 * B * W * e->row > ((int64_t)1 << 29)) return 1;
     return W < 2 ? 1 : (int)W;
 }
 
