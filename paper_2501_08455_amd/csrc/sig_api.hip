@@ -822,16 +822,16 @@ int sig_backward(sig_ctx *ctx, const float *path, int64_t B, int64_t L, int d, i
     if (B == 0) return SIG_OK;
     if (!path || !out || !grad_out || !grad_path) return SIG_ERR_INVALID;
     const bool fits = backward_available(d, depth) && backward_fits(d, depth, L);
-    if (!stream_flag && backward_available(d, depth)) {
+    if (backward_available(d, depth)) {
         // few long paths (or paths too long for the LDS of the uncut sweep): the sweep cut in time across workgroups
-        const int segs = backward_segments(d, depth, B, L, ctx->num_cu, fits);
+        const int segs = backward_segments(d, depth, B, L, ctx->num_cu, fits, stream_flag);
         if (segs > 1) {
             const int64_t need = backward_segmented_scratch_floats(d, depth, B, L, segs);
             if (need <= 0 || need > (int64_t)1 << 36) return SIG_ERR_TOO_LARGE;
             rc = ensure_scratch(ctx, (size_t)need * sizeof(float));
             if (rc != SIG_OK) return rc;
-            hipError_t es = launch_backward_segmented(path, out, grad_out, grad_path, ctx->scratch, B, L, d, depth, segs,
-                                                      ctx->num_cu, (hipStream_t)hip_stream);
+            hipError_t es = launch_backward_segmented(path, out, grad_out, grad_path, ctx->scratch, B, L, d, depth, stream_flag,
+                                                      segs, ctx->num_cu, (hipStream_t)hip_stream);
             return es == hipSuccess ? SIG_OK : SIG_ERR_HIP;
         }
     }
@@ -863,8 +863,8 @@ int sig_backward_segments(const sig_ctx *ctx, int64_t B, int64_t L, int d, int d
     if (rc != SIG_OK) return -rc;
     if (!backward_available(d, depth)) return backward_general_available(d) ? 0 : -SIG_ERR_UNSUPPORTED;
     const bool fits = backward_fits(d, depth, L);
-    if (!stream_flag && B > 0) {
-        const int segs = backward_segments(d, depth, B, L, ctx ? ctx->num_cu : kDefaultCUs, fits);
+    if (B > 0) {
+        const int segs = backward_segments(d, depth, B, L, ctx ? ctx->num_cu : kDefaultCUs, fits, stream_flag);
         if (segs > 1) return segs;
     }
     return fits || backward_tiles_fit(d, depth) ? 1 : 0;

@@ -158,6 +158,9 @@ struct BackwardArgs {
     const float *seg_sig;
     const float *seg_grad;
     float *seg_part;        // register sweep cut in time: d(loss)/d(increment), [B][L-1][d]
+    float *seg_adj_out;     // first sweep of the stream-mode cut: what a piece's own rows leave at its start, see
+                            // sig_backward_segments.hip; row of piece (b, s >= 1) at (b * segs + s - 1), zeros at the
+                            // last row of every path
     // Long paths whose increments do not fit LDS at once (either mode): tiled != 0 makes a workgroup walk the segs
     // pieces of its paths one after the other, last first, with its state in registers; no seg_sig / seg_grad rows.
     int32_t tiled;
@@ -198,10 +201,15 @@ constexpr int kTiledSteps = 256;
 // = b * segs + s; every piece is swept as seg_steps increments (the last segment of a path is filled up with zero
 // increments behind its end, which leave the signature and the adjoint as they are), starts from the rows
 // seg_sig / seg_grad (see BackwardArgs) and leaves its sums over the increments in seg_part.
-template <int d, int N, int P, bool STREAM, bool SEG = false>
+// SEG in stream mode: a piece starts from the output row at its end (row k of a stream output is the signature of
+// the path up to increment k) and from the gradient seg_grad that the later pieces leave there, and adds the
+// upstream gradients of its own rows as it goes.  EMIT = false is the first of the two sweeps that provide seg_grad:
+// from a zero adjoint, without sums over the increments; it writes what the piece's own rows leave at its start to
+// seg_adj_out (the lanes' partial adjoints of a prefix word are added up there).
+template <int d, int N, int P, bool STREAM, bool SEG = false, bool EMIT = true>
 __global__ __launch_bounds__(256) void sig_backward_kernel(BackwardArgs A)
 {
-    static_assert(!(STREAM && SEG), "stream mode is not cut across workgroups");
+    static_assert(EMIT || (STREAM && SEG), "the sweep without output belongs to the stream-mode cut");
     using Sh = Shape<d, N, P>;
     constexpr int Q = Sh::Q;
     constexpr int D = Sh::D;
@@ -260,9 +268,15 @@ __global__ __launch_bounds__(256) void sig_backward_kernel(BackwardArgs A)
     if (P == 0) ad.s[0] = 0.0f;
     if (active) {
         const bool inner = SEG && seg < W - 1;   // a segment that ends inside the path
-        const float *srow = STREAM ? A.sig + (b * K + (K - 1)) * D : inner ? A.seg_sig + piece * D : A.sig + b * D;
-        load_state<d, N, P>(srow, u, ln);
-        if constexpr (!STREAM) load_adjoint<d, N, P, false>(inner ? A.seg_grad + piece * D : A.grad_out + b * D, u, ad);
+        if constexpr (STREAM && SEG) {
+            const int64_t last = k0 + K < Kall ? k0 + K - 1 : Kall - 1;   // last increment of the piece
+            load_state<d, N, P>(A.sig + (b * Kall + last) * D, u, ln);
+            if constexpr (EMIT) load_adjoint<d, N, P, false>(A.seg_grad + piece * D, u, ad);
+        } else {
+            const float *srow = STREAM ? A.sig + (b * K + (K - 1)) * D : inner ? A.seg_sig + piece * D : A.sig + b * D;
+            load_state<d, N, P>(srow, u, ln);
+            if constexpr (!STREAM) load_adjoint<d, N, P, false>(inner ? A.seg_grad + piece * D : A.grad_out + b * D, u, ad);
+        }
     }
     __syncthreads();
 
@@ -289,23 +303,25 @@ __global__ __launch_bounds__(256) void sig_backward_kernel(BackwardArgs A)
         else identity_state<d, N, P>(ln);               // before the first increment: the identity, exactly
         float dbar[d];
         backward_step<d, N, P>(ln, ad, inc, letter, dbar);
-        if (active) {
-#pragma unroll
-            for (int a = 0; a < d; ++a) mypark[Pk::at(ts, (int)u, a)] = dbar[a];
-        }
-        if (ts == TS - 1 || k == 0) {
-            __syncthreads();
-            // column c = (parked step t, channel a): the sum over the path's lanes is d(loss)/d(dX)[a] of step
-            // k + (ts - t); it replaces that increment, which no lane reads again
+        if constexpr (EMIT) {
             if (active) {
-                for (int c = (int)u; c < (ts + 1) * d; c += Q) {
-                    const int t = c / d, a = c - t * d;
-                    float sum = 0.0f;
-                    for (int q = 0; q < Q; ++q) sum += mypark[Pk::at(t, q, a)];
-                    myrow[(k + (ts - t)) * d + a] = sum;
-                }
+#pragma unroll
+                for (int a = 0; a < d; ++a) mypark[Pk::at(ts, (int)u, a)] = dbar[a];
             }
-            __syncthreads();
+            if (ts == TS - 1 || k == 0) {
+                __syncthreads();
+                // column c = (parked step t, channel a): the sum over the path's lanes is d(loss)/d(dX)[a] of step
+                // k + (ts - t); it replaces that increment, which no lane reads again
+                if (active) {
+                    for (int c = (int)u; c < (ts + 1) * d; c += Q) {
+                        const int t = c / d, a = c - t * d;
+                        float sum = 0.0f;
+                        for (int q = 0; q < Q; ++q) sum += mypark[Pk::at(t, q, a)];
+                        myrow[(k + (ts - t)) * d + a] = sum;
+                    }
+                }
+                __syncthreads();
+            }
         }
     };
     if constexpr (STREAM) {
@@ -318,7 +334,13 @@ __global__ __launch_bounds__(256) void sig_backward_kernel(BackwardArgs A)
             constexpr int j = decltype(jc)::value;
             identity_state<d, N, P>(up[j]);
             if (P == 0) up[j].s[0] = 0.0f;
-            if (active && K - 1 - j >= 0) load_adjoint<d, N, P, false>(A.grad_out + (b * K + (K - 1 - j)) * D, u, up[j]);
+            if constexpr (SEG) {
+                // (rows behind the end of the path, in the filled-up last piece, stay zero)
+                if (active && K - 1 - j >= 0 && k0 + K - 1 - j < Kall)
+                    load_adjoint<d, N, P, false>(A.grad_out + (b * Kall + (k0 + K - 1 - j)) * D, u, up[j]);
+            } else {
+                if (active && K - 1 - j >= 0) load_adjoint<d, N, P, false>(A.grad_out + (b * K + (K - 1 - j)) * D, u, up[j]);
+            }
         });
         for (int64_t kk = K - 1; kk >= 0; kk -= PD) {
             static_for<0, PD>([&](auto jc) __attribute__((always_inline)) {
@@ -326,7 +348,12 @@ __global__ __launch_bounds__(256) void sig_backward_kernel(BackwardArgs A)
                 const int64_t k = kk - j;
                 if (k >= 0) {
                     step(k, &up[j]);
-                    if (active && k - PD >= 0) load_adjoint<d, N, P, false>(A.grad_out + (b * K + (k - PD)) * D, u, up[j]);
+                    if constexpr (SEG) {
+                        if (active && k - PD >= 0 && k0 + k - PD < Kall)
+                            load_adjoint<d, N, P, false>(A.grad_out + (b * Kall + (k0 + k - PD)) * D, u, up[j]);
+                    } else {
+                        if (active && k - PD >= 0) load_adjoint<d, N, P, false>(A.grad_out + (b * K + (k - PD)) * D, u, up[j]);
+                    }
                 }
             });
         }
@@ -334,6 +361,38 @@ __global__ __launch_bounds__(256) void sig_backward_kernel(BackwardArgs A)
         for (int64_t k = K - 1; k >= 0; --k) step(k, nullptr);
     }
 
+    if constexpr (!EMIT) {
+        // what the piece's own rows leave at its start, as a row: a lane owns the words of its sub-tree; the partial
+        // adjoints of a shorter prefix word are added up over the lanes that share it (fixed order)
+        float *scr = mypark;   // [P-1][Q]
+        static_for<1, P>([&](auto mc) __attribute__((always_inline)) {
+            constexpr int m = decltype(mc)::value;
+            if (active) scr[(m - 1) * Q + u] = ad.pre[m - 1];
+        });
+        __syncthreads();
+        if (active) {
+            // piece (b, s) hands its row to the piece before it; the last row of a path is zero (nothing follows)
+            float *row = A.seg_adj_out + (seg > 0 ? piece - 1 : b * W + (W - 1)) * D;
+            const bool keep = seg > 0;
+            static_for<(P == 0 ? 1 : 0), Sh::R + 1>([&](auto rc) __attribute__((always_inline)) {
+                constexpr int r = decltype(rc)::value;
+                constexpr int cnt = cpow(d, r);
+#pragma unroll
+                for (int i = 0; i < cnt; ++i) row[Sh::row_off(P + r) + u * cnt + i] = keep ? ad.s[Sh::sub_off(r) + i] : 0.0f;
+            });
+            static_for<1, P>([&](auto mc) __attribute__((always_inline)) {
+                constexpr int m = decltype(mc)::value;
+                constexpr unsigned span = cpow(d, P - m);
+                if (u % span == 0) {
+                    float sum = 0.0f;
+#pragma unroll
+                    for (unsigned j = 0; j < span; ++j) sum += scr[(m - 1) * Q + u + j];
+                    row[Sh::row_off(m) + u / span] = keep ? sum : 0.0f;
+                }
+            });
+        }
+        return;
+    }
     if constexpr (SEG) {
         // the sums over the piece's own increments; another launch forms d(loss)/dX across the pieces
         for (int i = tid; i < G * row_floats; i += nthr) {

@@ -1,4 +1,5 @@
-// Gradient of the final signature with respect to the path, cut in time across workgroups: few long paths.
+// Gradient of the signature with respect to the path, cut in time across workgroups: few long paths (final mode;
+// stream mode further down, at sig_backward_segment_affine_kernel).
 //
 // The reverse sweep (see sig_backward.hip) walks the K increments of a path one after the other, and a workgroup
 // per path (and slice of its lanes) leaves most of the chip idle when there are few paths.  Chen's relation (paper
@@ -23,8 +24,10 @@ namespace onchip {
 
 // 1. E[(b, s)] = signature of segment s of path b alone
 template <int d, int N, int P>
+//    shifted != 0 (stream mode): piece (b, s >= 1) writes to row (b, s - 1) and row (b, W - 1) is the identity, so that
+//    row s holds the signature of the segment that follows segment s
 __global__ __launch_bounds__(kSliceLanes) void sig_backward_segment_fold_kernel(const float *path, float *E, int64_t L,
-                                                                                int W, int T)
+                                                                                int W, int T, int shifted)
 {
     using Sh = Shape<d, N, P>;
     constexpr int Q = Sh::Q;
@@ -64,7 +67,9 @@ __global__ __launch_bounds__(kSliceLanes) void sig_backward_segment_fold_kernel(
         load_inc<d, P>(inc, tile + k * d, letter);
         fused_step<d, N, P>(ln, inc);
     }
-    if (active) store_state<d, N, P>(E + piece * D, u, ln);
+    if (shifted && seg == 0) identity_state<d, N, P>(ln);
+    const int64_t dst = !shifted ? piece : seg > 0 ? piece - 1 : b * W + (W - 1);
+    if (active) store_state<d, N, P>(E + dst * D, u, ln);
 }
 
 // out[u] = sum over the words x (the empty one included) of A[(u, x)] E[x] on rows of D floats: the transpose of
@@ -73,7 +78,8 @@ __global__ __launch_bounds__(kSliceLanes) void sig_backward_segment_fold_kernel(
 // sum), a thread per word otherwise.  Called by `threads` threads numbered tid = 0 .. threads - 1 in whole
 // wavefronts (they may belong to several workgroups); out may not overlap A.
 template <int d, int N>
-__device__ __forceinline__ void row_adjoint_product(const float *A, const float *E, float *out, int tid, int threads)
+__device__ __forceinline__ void row_adjoint_product(const float *A, const float *E, float *out, int tid, int threads,
+                                                    const float *plus = nullptr)   // plus: a row added to the result
 {
     using Sh = Shape<d, N, 0>;
     const int lane = tid & (kWave - 1), wave = tid / kWave;
@@ -100,7 +106,7 @@ __device__ __forceinline__ void row_adjoint_product(const float *A, const float 
                 });
 #pragma unroll
                 for (int off = kWave / 2; off >= 1; off >>= 1) acc += __shfl_xor(acc, off, kWave);
-                if (lane == 0) out[Sh::row_off(j) + v] = A[Sh::row_off(j) + v] + acc;
+                if (lane == 0) out[Sh::row_off(j) + v] = A[Sh::row_off(j) + v] + acc + (plus ? plus[Sh::row_off(j) + v] : 0.0f);
             }
         } else {
             for (int v = tid; v < cnt; v += threads) {
@@ -113,7 +119,7 @@ __device__ __forceinline__ void row_adjoint_product(const float *A, const float 
 #pragma unroll
                     for (int x = 0; x < run; ++x) acc = fmaf(a[x], e[x], acc);
                 });
-                out[Sh::row_off(j) + v] = acc;
+                out[Sh::row_off(j) + v] = acc + (plus ? plus[Sh::row_off(j) + v] : 0.0f);
             }
         }
     });
@@ -170,6 +176,33 @@ __global__ __launch_bounds__(256) void sig_backward_segment_adjoint_kernel(const
                               256 * row_workgroups<d, N>());
 }
 
+// Stream mode.  Every output row has its own upstream gradient, so what reaches the end of segment s from the later
+// segments is  R_s = c_{s+1} + (the transpose of . (x) E_{s+1}) R_{s+1},  R_{W-1} = 0,  with c_t what the rows of
+// segment t themselves leave at its start (a first sweep of every segment from a zero adjoint).  One round of the
+// scan that solves this recursion for all s at once: row s stands for the map R_s = C_s + transpose(. (x) P_s) R_{s+off}
+// over a window of `off` segments, and two windows are joined by
+//     C_s <- C_s + transpose(. (x) P_s) C_{s+off},      P_s <- P_s (x) P_{s+off}          (s + off < W, else kept).
+// blockIdx.y = 0: the C rows, 1: the P rows; after ceil(log2 W) rounds C_s = R_s.
+template <int d, int N>
+__global__ __launch_bounds__(256) void sig_backward_segment_affine_kernel(const float *Cin, float *Cout, const float *Pin,
+                                                                          float *Pout, int W, int off)
+{
+    using RP = RowProduct<d, N>;
+    constexpr int D = Shape<d, N, 0>::D;
+    constexpr int threads = 256 * row_workgroups<d, N>();
+    const int tid = (int)(blockIdx.z * 256 + threadIdx.x);
+    const int64_t piece = blockIdx.x;
+    const int s = (int)(piece % W);
+    const bool joined = s + off < W;
+    if (blockIdx.y == 0) {
+        if (joined) row_adjoint_product<d, N>(Cin + (piece + off) * D, Pin + piece * D, Cout + piece * D, tid, threads, Cin + piece * D);
+        else for (int x = tid; x < D; x += threads) Cout[piece * D + x] = Cin[piece * D + x];
+    } else {
+        if (joined) for (int x = tid; x < RP::ITEMS; x += threads) RP::item(Pin + piece * D, Pin + (piece + off) * D, Pout + piece * D, x);
+        else for (int x = tid; x < D; x += threads) Pout[piece * D + x] = Pin[piece * D + x];
+    }
+}
+
 // shapes whose lanes fit a workgroup at least twice take the register sweep with several pieces per workgroup
 template <int d, int N, int P>
 constexpr bool segments_packed() { return Shape<d, N, P>::Q * 2 <= 256; }
@@ -189,17 +222,60 @@ hipError_t backward_segmented_launch(const BackwardArgs &A0, float *scratch, int
     constexpr bool packed = segments_packed<d, N, P>();
     constexpr int slices = (Sh::Q + kSliceLanes - 1) / kSliceLanes;
     const int64_t K = A0.L - 1;
-    if (W < 2 || W > K || !scratch || A0.stream_flag || cus < 1) return hipErrorInvalidValue;
+    if (W < 2 || W > K || !scratch || cus < 1 || (A0.stream_flag && !packed)) return hipErrorInvalidValue;
     const int64_t T = (K + W - 1) / W;
     W = (int)((K + T - 1) / T);   // no trailing segment without increments
     const int64_t pieces = A0.B * W;
     if (W < 2 || !segment_fits<d, N, P>(T) || pieces * slices > INT32_MAX || A0.B > INT32_MAX) return hipErrorInvalidValue;
     const int64_t rows = pieces * Sh::D;
     float *E = scratch, *S0 = E + rows, *S1 = S0 + rows, *Y0 = S1 + rows, *Y1 = Y0 + rows, *part = Y1 + rows;
+    if constexpr (packed) {
+        if (A0.stream_flag) {
+            // stream mode: fold (rows shifted by one segment), first sweep, the scan above, second sweep, finish
+            float *P0 = E, *P1 = S0, *C0 = S1, *C1 = Y0;
+            const int fold_threads = (Sh::Q + kWave - 1) / kWave * kWave;
+            hipLaunchKernelGGL((sig_backward_segment_fold_kernel<d, N, P>), dim3((unsigned)pieces), dim3(fold_threads),
+                               (size_t)(T * d) * sizeof(float), st, A0.path, P0, A0.L, W, (int)T, 1);
+            hipError_t e = hipGetLastError();
+            if (e != hipSuccess) return e;
+            BackwardArgs A = A0;
+            A.segs = W;
+            A.seg_steps = (int32_t)T;
+            A.seg_part = part;
+            int G = 256 / Sh::Q;
+            const int64_t per_cu = (pieces + cus - 1) / cus;
+            if ((int64_t)G > per_cu) G = (int)per_cu;
+            while (G > 1 && backward_lds_bytes<d, N, P>(T + 1, G) > kMaxLdsBytes) --G;
+            A.groups = G;
+            const size_t lds = (size_t)backward_lds_bytes<d, N, P>(T + 1, G);
+            const dim3 grid((unsigned)((pieces + G - 1) / G));
+            A.seg_adj_out = C0;
+            hipLaunchKernelGGL((sig_backward_kernel<d, N, P, true, true, false>), grid, dim3(256), lds, st, A);
+            e = hipGetLastError();
+            if (e != hipSuccess) return e;
+            const float *Cin = C0, *Pin = P0;
+            float *Cout = C1, *Pout = P1;
+            for (int off = 1; off < W; off *= 2) {
+                hipLaunchKernelGGL((sig_backward_segment_affine_kernel<d, N>), dim3((unsigned)pieces, 2, row_workgroups<d, N>()),
+                                   dim3(256), 0, st, Cin, Cout, Pin, Pout, W, off);
+                e = hipGetLastError();
+                if (e != hipSuccess) return e;
+                Cin = Cout;
+                Pin = Pout;
+                Cout = Cout == C1 ? C0 : C1;
+                Pout = Pout == P1 ? P0 : P1;
+            }
+            A.seg_grad = Cin;
+            hipLaunchKernelGGL((sig_backward_kernel<d, N, P, true, true, true>), grid, dim3(256), lds, st, A);
+            e = hipGetLastError();
+            if (e != hipSuccess) return e;
+            return launch_backward_finish(part, A.grad_path, A.B, A.L, d, 1, st);
+        }
+    }
 
     const int fold_threads = Sh::Q >= kSliceLanes ? kSliceLanes : (Sh::Q + kWave - 1) / kWave * kWave;
     hipLaunchKernelGGL((sig_backward_segment_fold_kernel<d, N, P>), dim3((unsigned)(pieces * slices)), dim3(fold_threads),
-                       (size_t)(T * d) * sizeof(float), st, A0.path, E, A0.L, W, (int)T);
+                       (size_t)(T * d) * sizeof(float), st, A0.path, E, A0.L, W, (int)T, 0);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const float *Sin = E, *Yin = E;
@@ -252,9 +328,9 @@ hipError_t backward_segmented_launch(const BackwardArgs &A0, float *scratch, int
 namespace {
 
 template <int d, int N, int P>
-int uncut_chunks(int64_t L)
+int uncut_chunks(int64_t L, int stream_flag)
 {
-    if constexpr (onchip::Shape<d, N, P>::Q <= 256) return onchip::backward_chunks<d, N, P>(L, 0, 256);
+    if constexpr (onchip::Shape<d, N, P>::Q <= 256) return onchip::backward_chunks<d, N, P>(L, stream_flag, 256);
     else return 1;
 }
 
@@ -264,7 +340,7 @@ struct SegmentedEntry {
     int64_t row;      // D
     hipError_t (*launch)(const onchip::BackwardArgs &, float *, int, int, hipStream_t);
     bool (*fits)(int64_t);             // does a segment of T increments fit the LDS of its sweep?
-    int (*uncut_chunks)(int64_t L);    // chunks the uncut sweep holds side by side in a workgroup (final mode)
+    int (*uncut_chunks)(int64_t L, int stream_flag);   // chunks the uncut sweep holds side by side in a workgroup
 };
 #define SIG_SEGMENTED_ENTRY(d, N, P) \
     {d, N, onchip::Shape<d, N, P>::Q, onchip::Shape<d, N, P>::D, &onchip::backward_segmented_launch<d, N, P>, &onchip::segment_fits<d, N, P>, \
@@ -305,20 +381,24 @@ constexpr int64_t kMaxSegmentRow = 1 << 17;   // one workgroup forms a product o
 //     four workgroups per compute unit, 16 MB;
 //   * a path whose increments do not fit the LDS of the uncut sweep (uncut_fits == false) is cut at any batch size,
 //     as little as makes a segment fit.
-int backward_segments(int d, int depth, int64_t B, int64_t L, int cus, bool uncut_fits)
+int backward_segments(int d, int depth, int64_t B, int64_t L, int cus, bool uncut_fits, int stream_flag)
 {
     const SegmentedEntry *e = find_segmented(d, depth);
     if (!e || e->row > kMaxSegmentRow || B <= 0) return 1;
     const int64_t K = L - 1;
     const bool packed = e->lanes * 2 <= onchip::kSliceLanes;   // several pieces share a workgroup
+    if (stream_flag && !packed) return 1;                       // stream mode: only the register sweep is cut
     const int64_t slices = (e->lanes + onchip::kSliceLanes - 1) / onchip::kSliceLanes;
     const int64_t chip_lanes = (int64_t)cus * 4 * kWave * 2;   // two wavefronts on every SIMD
     bool busy = B * slices >= 2 * (int64_t)cus;   // the uncut launch already has two workgroups for every compute unit
     int64_t min_steps = 128;
     if (packed && uncut_fits) {
-        const int chunks = e->uncut_chunks(L);
+        const int chunks = e->uncut_chunks(L, stream_flag);
         if (chunks >= 8) min_steps = 512;
         if (B > 32 && chunks >= 6) busy = true;
+        // stream mode, rows of a few dozen floats (d = 2 at depth 3, d = 5 at depth 2): the plain sweep with its
+        // chunks is as fast at every measured length
+        if (stream_flag && chunks >= 8 && e->row <= 32) busy = true;
     }
     if (uncut_fits && (K < min_steps || busy)) return 1;
     int64_t W = 2;
@@ -358,8 +438,8 @@ int64_t backward_segmented_scratch_floats(int d, int depth, int64_t B, int64_t L
 }
 
 hipError_t launch_backward_segmented(const float *path, const float *sig, const float *grad_out, float *grad_path,
-                                     float *scratch, int64_t B, int64_t L, int d, int depth, int segs, int cus,
-                                     hipStream_t st)
+                                     float *scratch, int64_t B, int64_t L, int d, int depth, int stream_flag, int segs,
+                                     int cus, hipStream_t st)
 {
     const SegmentedEntry *e = find_segmented(d, depth);
     if (!e) return hipErrorInvalidValue;
@@ -370,7 +450,7 @@ hipError_t launch_backward_segmented(const float *path, const float *sig, const 
     A.grad_path = grad_path;
     A.B = B;
     A.L = L;
-    A.stream_flag = 0;
+    A.stream_flag = stream_flag;
     return e->launch(A, scratch, segs, cus, st);
 }
 

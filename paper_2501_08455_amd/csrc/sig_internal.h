@@ -69,13 +69,13 @@ hipError_t launch_backward(const float *path, const float *sig, const float *gra
 hipError_t launch_backward_finish(const float *part, float *grad_path, int64_t B, int64_t L, int d, int slices,
                                   hipStream_t st);
 
-// ---------------------------------------------------------------- gradient cut in time across workgroups (final mode)
+// ---------------------------------------------------------------- gradient cut in time across workgroups
 // Time segments the sweep should be cut into (<= 1: do not cut); uncut_fits = backward_fits(d, depth, L)
-int backward_segments(int d, int depth, int64_t B, int64_t L, int cus, bool uncut_fits);
+int backward_segments(int d, int depth, int64_t B, int64_t L, int cus, bool uncut_fits, int stream_flag);
 int64_t backward_segmented_scratch_floats(int d, int depth, int64_t B, int64_t L, int segs);
 hipError_t launch_backward_segmented(const float *path, const float *sig, const float *grad_out, float *grad_path,
-                                     float *scratch, int64_t B, int64_t L, int d, int depth, int segs, int cus,
-                                     hipStream_t st);
+                                     float *scratch, int64_t B, int64_t L, int d, int depth, int stream_flag, int segs,
+                                     int cus, hipStream_t st);
 
 // ---------------------------------------------------------------- gradient, any (d <= 256, depth): one workgroup per path
 bool backward_general_available(int d);

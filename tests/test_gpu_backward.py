@@ -183,16 +183,33 @@ def test_backward_paths_too_long_for_one_workgroup(gpu, oracle):
         check(gpu, oracle, x, 4, stream, seed=L, label="long path")
 
 
-@pytest.mark.parametrize("case", [(5, 4, 3, 3300, True), (7, 3, 2, 2500, True), (10, 2, 70, 1700, True), (2, 3, 5, 9000, True),
-                                  (10, 4, 1, 1500, True), (8, 4, 2, 2100, True), (6, 5, 1, 2800, True),
-                                  (10, 2, 2, 60000, False)], ids=lambda c: "-".join(str(v) for v in c))
+@pytest.mark.parametrize("case", [(10, 4, 1, 1500, True), (8, 4, 2, 2100, True), (6, 5, 1, 2800, True), (10, 2, 2, 60000, True),
+                                  (10, 2, 2, 60000, False), (10, 3, 3, 40001, True)], ids=lambda c: "-".join(str(v) for v in c))
 def test_backward_walks_long_paths_in_tiles(gpu, oracle, case):
-    """Stream-mode paths too long for LDS (register and sliced sweeps, several paths per workgroup, ragged last tile),
-    and a final-mode path too long even for 32 segments: one workgroup walks tiles of 256 increments."""
+    """Paths too long for LDS where the sweep is not cut across workgroups — stream mode of the sliced shapes, and
+    paths too long even for 32 segments in either mode: one workgroup walks tiles of 256 increments (ragged last
+    tile, several paths per workgroup)."""
     d, depth, B, L, stream = case
     assert gpu.sig_backward_segments(None, B, L, d, depth, int(stream)) == 1
     x = workloads.brownian_paths(B, L, d, seed=8600 + L)
     check(gpu, oracle, x, depth, stream, seed=L, label="tiled sweep")
+
+
+STREAM_SEGMENTED_CASES = [
+    # d, depth, B, L: stream mode, few long paths of shapes whose lanes fit a workgroup at least twice: two sweeps per
+    # segment with a scan over the segments between them; lengths with ragged last segments, one and several paths,
+    # paths too long for the LDS of the uncut sweep at a batch that fills the chip
+    (5, 4, 1, 600), (5, 4, 3, 777), (2, 3, 2, 30001), (4, 4, 2, 1000), (3, 5, 1, 700), (5, 5, 1, 300), (6, 4, 2, 400),
+    (8, 3, 1, 900), (7, 3, 2, 2500), (2, 6, 1, 1200), (10, 2, 70, 1700), (9, 3, 2, 350), (5, 4, 3, 3300), (5, 2, 600, 3500),
+]
+
+
+@pytest.mark.parametrize("case", STREAM_SEGMENTED_CASES, ids=lambda c: "-".join(str(v) for v in c))
+def test_backward_stream_mode_cut_in_time(gpu, oracle, case):
+    d, depth, B, L = case
+    assert gpu.sig_backward_segments(None, B, L, d, depth, 1) > 1
+    x = workloads.brownian_paths(B, L, d, seed=8700 + 3 * L + d)
+    check(gpu, oracle, x, depth, True, seed=L + depth, label="stream, cut in time")
 
 
 def test_backward_on_the_configurations(gpu, oracle):
