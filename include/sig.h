@@ -185,9 +185,9 @@ int sig_combine(sig_ctx *ctx, const float *a, const float *b, int64_t B, int d, 
  * paths, for shapes with at most 32 lanes per path) and paths too long for that staging are cut into up to 32
  * time segments that are swept by different workgroups: by Eq. 3 a segment can start from the signature of the
  * path up to its end and the gradient with respect to it, which a scan over the segments' own signatures provides.
- * Stream mode is cut the same way for shapes with at most 128 lanes per path (two sweeps per segment and a scan
- * over the segments between them; the upstream gradient is read twice); other stream-mode paths too long for the
- * staging are walked in tiles of 256 increments by one workgroup.  Every shape
+ * Stream mode is cut the same way at smaller batches (two sweeps per segment and a scan over the segments between
+ * them; the upstream gradient is read twice); paths too long for the staging in a batch that fills the chip, or too
+ * long even for 32 segments, are walked in tiles of 256 increments by one workgroup.  Every shape
  * without a register kernel, d <= 256, takes a general sweep, one workgroup per path with its state in LDS or
  * device scratch (much slower); SIG_ERR_UNSUPPORTED only for d > 256.
  * Context scratch (allocated on first use, SIG_ERR_ALLOC if that fails): shapes whose index space is cut into more

@@ -602,14 +602,23 @@ constexpr int kParkRow = kSliceLanes + kSliceLanes / 32;
 template <int d>
 constexpr int slice_park_floats() { return d * kParkRow; }
 
-template <int d, int N, int P, bool STREAM>
+// words of the levels below the prefix depth, 1 .. P-1: the lanes that share such a word hold partial adjoints of it
+template <int d, int P>
+constexpr int shared_prefix_words() { return P > 1 ? geom(d, P) - 1 : 0; }   // d + ... + d^{P-1}
+
+template <int d, int N, int P, bool STREAM, bool EMIT = true>
 __global__ __launch_bounds__(kSliceLanes) void sig_backward_sliced_kernel(BackwardArgs A, float *part, int TS)
 {
     // TS: steps whose partial sums are parked before they are added up (at most slice_reduce_steps<d>(); fewer
     // when a long path leaves less LDS)
-    // A.segs > 1 cuts the path into pieces of A.seg_steps increments: every piece a workgroup of its own (final
-    // mode, see BackwardArgs), or with A.tiled the workgroup walks the pieces of its path one after the other, last
-    // first, with its state in registers, so that only one piece's increments are staged in LDS at a time.
+    // A.segs > 1 cuts the path into pieces of A.seg_steps increments: every piece a workgroup of its own (see
+    // BackwardArgs; in stream mode a piece starts from the output row at its end and from seg_grad, like the register
+    // sweep), or with A.tiled the workgroup walks the pieces of its path one after the other, last first, with its
+    // state in registers, so that only one piece's increments are staged in LDS at a time.
+    // EMIT = false (stream-mode pieces): the first of the two sweeps, from a zero adjoint and without sums over the
+    // increments; the lane's own words of what the piece's rows leave at its start go to seg_adj_out, the slice's
+    // sums of the partial adjoints of the shorter prefix words to `part` ([piece][slice][shared_prefix_words]).
+    static_assert(EMIT || STREAM, "the sweep without output belongs to the stream-mode cut");
     using Sh = Shape<d, N, P>;
     constexpr int Q = Sh::Q;
     constexpr int D = Sh::D;
@@ -618,7 +627,7 @@ __global__ __launch_bounds__(kSliceLanes) void sig_backward_sliced_kernel(Backwa
     const int tid = threadIdx.x, nthr = blockDim.x;
     const int slice = (int)(blockIdx.x % slices);
     const int64_t piece = blockIdx.x / slices;
-    const int W = (!STREAM && !A.tiled && A.segs > 1) ? A.segs : 1;   // pieces that are workgroups of their own
+    const int W = (!A.tiled && A.segs > 1) ? A.segs : 1;              // pieces that are workgroups of their own
     const int tiles = (A.tiled && A.segs > 1) ? A.segs : 1;           // pieces this workgroup walks
     const int64_t b = piece / W;
     const int seg = (int)(piece - b * W);
@@ -646,17 +655,20 @@ __global__ __launch_bounds__(kSliceLanes) void sig_backward_sliced_kernel(Backwa
     identity_state<d, N, P>(ln);
     identity_state<d, N, P>(ad);
     if (P == 0) ad.s[0] = 0.0f;
+    // last increment of the workgroup's first piece (the whole path unless it is a piece of its own)
+    const int64_t last = W > 1 && (int64_t)(seg + 1) * T < Kall ? (int64_t)(seg + 1) * T - 1 : Kall - 1;
     if (active) {
         const bool inner = seg < W - 1;   // a segment that ends inside the path
-        const float *srow = STREAM ? A.sig + (b * Kall + (Kall - 1)) * D : inner ? A.seg_sig + piece * D : A.sig + b * D;
+        const float *srow = STREAM ? A.sig + (b * Kall + last) * D : inner ? A.seg_sig + piece * D : A.sig + b * D;
         load_state<d, N, P>(srow, u, ln);
         if constexpr (!STREAM) load_adjoint<d, N, P, false>(inner ? A.seg_grad + piece * D : A.grad_out + b * D, u, ad);
+        else if (W > 1 && EMIT) load_adjoint<d, N, P, false>(A.seg_grad + piece * D, u, ad);
     }
     Lane<d, N, P> up;   // upstream gradient of the row the sweep reaches next (stream mode), fetched one step ahead
     if constexpr (STREAM) {
         identity_state<d, N, P>(up);
         if (P == 0) up.s[0] = 0.0f;
-        if (active) load_adjoint<d, N, P, false>(A.grad_out + (b * Kall + (Kall - 1)) * D, u, up);
+        if (active) load_adjoint<d, N, P, false>(A.grad_out + (b * Kall + last) * D, u, up);
     }
 
     for (int tl = tiles - 1; tl >= 0; --tl) {
@@ -689,6 +701,7 @@ __global__ __launch_bounds__(kSliceLanes) void sig_backward_sliced_kernel(Backwa
             else identity_state<d, N, P>(ln);
             float dbar[d];
             backward_step<d, N, P>(ln, ad, inc, letter, dbar);
+            if constexpr (!EMIT) continue;
 #pragma unroll
             for (int a = 0; a < d; ++a) park[ts * kParkStep + a * kParkRow + tid + (tid >> 5)] = active ? dbar[a] : 0.0f;
             if (ts == TS - 1 || k == 0) {
@@ -719,8 +732,50 @@ __global__ __launch_bounds__(kSliceLanes) void sig_backward_sliced_kernel(Backwa
                 __syncthreads();
             }
         }
-        float *dst = part + ((b * slices + slice) * Kall + k0) * d;
-        for (int i = tid; i < row_floats; i += nthr) dst[i] = tile[i];
+        if constexpr (EMIT) {
+            float *dst = part + ((b * slices + slice) * Kall + k0) * d;
+            for (int i = tid; i < row_floats; i += nthr) dst[i] = tile[i];
+        }
+    }
+    if constexpr (!EMIT) {
+        // piece (b, s) hands its row to the piece before it; the last row of a path is zero (nothing follows it)
+        const bool keep = seg > 0;
+        float *row = A.seg_adj_out + (keep ? piece - 1 : b * W + (W - 1)) * D;
+        if (active) {
+            static_for<(P == 0 ? 1 : 0), Sh::R + 1>([&](auto rc) __attribute__((always_inline)) {
+                constexpr int r = decltype(rc)::value;
+                constexpr int cnt = cpow(d, r);
+#pragma unroll
+                for (int i = 0; i < cnt; ++i) row[Sh::row_off(P + r) + u * cnt + i] = keep ? ad.s[Sh::sub_off(r) + i] : 0.0f;
+            });
+        }
+        // the slice's sums of the partial adjoints of the words of levels 1 .. P-1 (zero where no lane of the slice
+        // lies below a word); another launch adds the slices in order
+        constexpr int NW = shared_prefix_words<d, P>();
+        if constexpr (NW > 0) {
+            __syncthreads();
+            float *scr = park;   // [P-1][kSliceLanes]
+            static_for<1, P>([&](auto mc) __attribute__((always_inline)) {
+                constexpr int m = decltype(mc)::value;
+                scr[(m - 1) * kSliceLanes + tid] = active ? ad.pre[m - 1] : 0.0f;
+            });
+            __syncthreads();
+            float *side = part + (piece * slices + slice) * NW;
+            const int lane0 = slice * kSliceLanes;
+            static_for<1, P>([&](auto mc) __attribute__((always_inline)) {
+                constexpr int m = decltype(mc)::value;
+                constexpr int span = cpow(d, P - m);
+                constexpr int words = cpow(d, m);
+                for (int w = tid; w < words; w += nthr) {
+                    int lo = w * span - lane0, hi = lo + span;
+                    if (lo < 0) lo = 0;
+                    if (hi > kSliceLanes) hi = kSliceLanes;
+                    float sum = 0.0f;
+                    for (int j = lo; j < hi; ++j) sum += scr[(m - 1) * kSliceLanes + j];
+                    side[Sh::row_off(m) + w] = sum;
+                }
+            });
+        }
     }
 }
 

@@ -203,6 +203,24 @@ __global__ __launch_bounds__(256) void sig_backward_segment_affine_kernel(const 
     }
 }
 
+// Stream-mode cut of the sliced shapes: the first sweep leaves, per (piece, slice), the slice's sums of the partial
+// adjoints of the words of levels 1 .. P-1 (the first `words` floats of a row); this adds the slices in order into the
+// row that the sweep's lanes wrote their own words to (piece (b, s) hands its row to (b, s - 1); the last row of a
+// path is zero).
+__global__ __launch_bounds__(256) void sig_backward_segment_prefix_kernel(const float *side, float *rows, int64_t pieces,
+                                                                          int W, int slices, int words, int64_t D)
+{
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= pieces * words) return;
+    const int64_t piece = idx / words;
+    const int w = (int)(idx - piece * words);
+    const int64_t b = piece / W;
+    const int seg = (int)(piece - b * W);
+    float sum = 0.0f;
+    for (int sl = 0; sl < slices; ++sl) sum += side[(piece * slices + sl) * words + w];
+    rows[(seg > 0 ? piece - 1 : b * W + (W - 1)) * D + w] = seg > 0 ? sum : 0.0f;
+}
+
 // shapes whose lanes fit a workgroup at least twice take the register sweep with several pieces per workgroup
 template <int d, int N, int P>
 constexpr bool segments_packed() { return Shape<d, N, P>::Q * 2 <= 256; }
@@ -222,37 +240,57 @@ hipError_t backward_segmented_launch(const BackwardArgs &A0, float *scratch, int
     constexpr bool packed = segments_packed<d, N, P>();
     constexpr int slices = (Sh::Q + kSliceLanes - 1) / kSliceLanes;
     const int64_t K = A0.L - 1;
-    if (W < 2 || W > K || !scratch || cus < 1 || (A0.stream_flag && !packed)) return hipErrorInvalidValue;
+    if (W < 2 || W > K || !scratch || cus < 1) return hipErrorInvalidValue;
     const int64_t T = (K + W - 1) / W;
     W = (int)((K + T - 1) / T);   // no trailing segment without increments
     const int64_t pieces = A0.B * W;
     if (W < 2 || !segment_fits<d, N, P>(T) || pieces * slices > INT32_MAX || A0.B > INT32_MAX) return hipErrorInvalidValue;
     const int64_t rows = pieces * Sh::D;
     float *E = scratch, *S0 = E + rows, *S1 = S0 + rows, *Y0 = S1 + rows, *Y1 = Y0 + rows, *part = Y1 + rows;
-    if constexpr (packed) {
-        if (A0.stream_flag) {
-            // stream mode: fold (rows shifted by one segment), first sweep, the scan above, second sweep, finish
-            float *P0 = E, *P1 = S0, *C0 = S1, *C1 = Y0;
-            const int fold_threads = (Sh::Q + kWave - 1) / kWave * kWave;
-            hipLaunchKernelGGL((sig_backward_segment_fold_kernel<d, N, P>), dim3((unsigned)pieces), dim3(fold_threads),
-                               (size_t)(T * d) * sizeof(float), st, A0.path, P0, A0.L, W, (int)T, 1);
-            hipError_t e = hipGetLastError();
-            if (e != hipSuccess) return e;
-            BackwardArgs A = A0;
-            A.segs = W;
-            A.seg_steps = (int32_t)T;
-            A.seg_part = part;
-            int G = 256 / Sh::Q;
+    static_assert(slices * shared_prefix_words<d, P>() <= Sh::D, "the per-slice prefix sums of a piece fit one row");
+    if (A0.stream_flag) {
+        // stream mode: fold (rows shifted by one segment), first sweep, the scan above, second sweep, finish
+        float *P0 = E, *P1 = S0, *C0 = S1, *C1 = Y0, *side = Y1;
+        const int fold_threads = Sh::Q >= kSliceLanes ? kSliceLanes : (Sh::Q + kWave - 1) / kWave * kWave;
+        hipLaunchKernelGGL((sig_backward_segment_fold_kernel<d, N, P>), dim3((unsigned)(pieces * slices)), dim3(fold_threads),
+                           (size_t)(T * d) * sizeof(float), st, A0.path, P0, A0.L, W, (int)T, 1);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        BackwardArgs A = A0;
+        A.segs = W;
+        A.seg_steps = (int32_t)T;
+        A.seg_part = part;
+        A.seg_adj_out = C0;
+        // launch geometry of the two sweeps
+        int G = 1, ts = 1;
+        size_t lds;
+        dim3 grid;
+        if constexpr (packed) {
+            G = 256 / Sh::Q;
             const int64_t per_cu = (pieces + cus - 1) / cus;
             if ((int64_t)G > per_cu) G = (int)per_cu;
             while (G > 1 && backward_lds_bytes<d, N, P>(T + 1, G) > kMaxLdsBytes) --G;
             A.groups = G;
-            const size_t lds = (size_t)backward_lds_bytes<d, N, P>(T + 1, G);
-            const dim3 grid((unsigned)((pieces + G - 1) / G));
-            A.seg_adj_out = C0;
+            lds = (size_t)backward_lds_bytes<d, N, P>(T + 1, G);
+            grid = dim3((unsigned)((pieces + G - 1) / G));
             hipLaunchKernelGGL((sig_backward_kernel<d, N, P, true, true, false>), grid, dim3(256), lds, st, A);
+        } else {
+            ts = backward_sliced_steps<d>(T + 1);
+            lds = (size_t)backward_sliced_bytes_with<d>(T + 1, ts);
+            grid = dim3((unsigned)(pieces * slices));
+            hipLaunchKernelGGL((sig_backward_sliced_kernel<d, N, P, true, false>), grid, dim3(kSliceLanes), lds, st, A, side, ts);
             e = hipGetLastError();
             if (e != hipSuccess) return e;
+            constexpr int words = shared_prefix_words<d, P>();
+            if constexpr (words > 0) {
+                const int64_t blocks = (pieces * words + 255) / 256;
+                hipLaunchKernelGGL(sig_backward_segment_prefix_kernel, dim3((unsigned)blocks), dim3(256), 0, st, (const float *)side,
+                                   C0, pieces, W, slices, words, (int64_t)Sh::D);
+            }
+        }
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        {
             const float *Cin = C0, *Pin = P0;
             float *Cout = C1, *Pout = P1;
             for (int off = 1; off < W; off *= 2) {
@@ -266,10 +304,13 @@ hipError_t backward_segmented_launch(const BackwardArgs &A0, float *scratch, int
                 Pout = Pout == P1 ? P0 : P1;
             }
             A.seg_grad = Cin;
-            hipLaunchKernelGGL((sig_backward_kernel<d, N, P, true, true, true>), grid, dim3(256), lds, st, A);
+            if constexpr (packed)
+                hipLaunchKernelGGL((sig_backward_kernel<d, N, P, true, true, true>), grid, dim3(256), lds, st, A);
+            else
+                hipLaunchKernelGGL((sig_backward_sliced_kernel<d, N, P, true, true>), grid, dim3(kSliceLanes), lds, st, A, part, ts);
             e = hipGetLastError();
             if (e != hipSuccess) return e;
-            return launch_backward_finish(part, A.grad_path, A.B, A.L, d, 1, st);
+            return launch_backward_finish(part, A.grad_path, A.B, A.L, d, slices, st);
         }
     }
 
@@ -387,10 +428,12 @@ int backward_segments(int d, int depth, int64_t B, int64_t L, int cus, bool uncu
     if (!e || e->row > kMaxSegmentRow || B <= 0) return 1;
     const int64_t K = L - 1;
     const bool packed = e->lanes * 2 <= onchip::kSliceLanes;   // several pieces share a workgroup
-    if (stream_flag && !packed) return 1;                       // stream mode: only the register sweep is cut
     const int64_t slices = (e->lanes + onchip::kSliceLanes - 1) / onchip::kSliceLanes;
     const int64_t chip_lanes = (int64_t)cus * 4 * kWave * 2;   // two wavefronts on every SIMD
     bool busy = B * slices >= 2 * (int64_t)cus;   // the uncut launch already has two workgroups for every compute unit
+    // (stream mode cuts cost two sweeps and a second read of the upstream gradient: the sliced shapes are cut only
+    // below a workgroup per compute unit, half of that for paths under 512 increments)
+    if (stream_flag && !packed) busy = B * slices >= (K < 512 ? cus / 2 : cus);
     int64_t min_steps = 128;
     if (packed && uncut_fits) {
         const int chunks = e->uncut_chunks(L, stream_flag);
@@ -401,12 +444,14 @@ int backward_segments(int d, int depth, int64_t B, int64_t L, int cus, bool uncu
         if (stream_flag && chunks >= 8 && e->row <= 32) busy = true;
     }
     if (uncut_fits && (K < min_steps || busy)) return 1;
+    // a stream-mode batch that fills the chip: walking the path in tiles (one sweep) beats cutting it (two)
+    if (stream_flag && busy) return 1;
     int64_t W = 2;
     if (!busy) {
         W = K / 24;
         if (W > kMaxSegments) W = kMaxSegments;
         // a launch that already has a workgroup per compute unit takes at most four segments
-        const bool half_full = B * slices >= cus;
+        const bool half_full = !stream_flag && B * slices >= cus;
         if (half_full && W > 4) W = 4;
         const int64_t room = packed ? chip_lanes / (B * e->lanes) : ((half_full ? 4 : 2) * (int64_t)cus) / (B * slices);
         if (W > room) W = room;

@@ -226,13 +226,14 @@ def test_backward_segment_rule():
     assert seg(1, 400, 5, 4) == 1 and seg(1, 600, 5, 4) > 1 and seg(64, 600, 5, 4) == 1
     # ... unless the path is so long that the chunks no longer fit (the gradient of the third configuration)
     assert seg(128, 2000, 5, 4) > 1
-    # stream mode: the shapes whose lanes fit a workgroup at least twice are cut (two sweeps and a scan between them),
-    # the sliced ones are not; rows of a few dozen floats keep the plain sweep with its chunks
-    assert seg(1, 1000, 5, 4, 1) > 1 and seg(1, 1000, 10, 4, 1) == 1 and seg(4, 1000, 2, 3, 1) == 1
+    # stream mode is cut as well (two sweeps and a scan between them), at smaller batches than final mode; rows of a
+    # few dozen floats keep the plain sweep with its chunks
+    assert seg(1, 1000, 5, 4, 1) > 1 and seg(1, 1000, 10, 4, 1) > 1 and seg(4, 1000, 2, 3, 1) == 1
+    assert seg(64, 300, 10, 4, 1) == 1 and seg(8, 300, 10, 4, 1) > 1
     # paths too long for the LDS of one workgroup: cut across workgroups in final mode at any batch size ...
     assert seg(300, 3500, 5, 4) >= 2 and seg(1, 20000, 5, 4) >= 2
     # ... and walked in tiles by one workgroup where that is not possible (stream mode; final mode beyond 32 segments)
-    assert seg(1, 4000, 10, 4, 1) == 1 and seg(2, 60000, 10, 2) == 1 and seg(2, 60000, 10, 2, 1) == 1
+    assert seg(300, 1500, 10, 4, 1) == 1 and seg(2, 60000, 10, 2) == 1 and seg(2, 60000, 10, 2, 1) == 1
     assert seg(100000, 5000, 5, 4) == 1
     # no register kernel: the general sweep; beyond its limits and bad arguments: minus the status
     assert seg(4, 50, 11, 2) == 0 and seg(4, 50, 300, 2) == -binding.SIG_ERR_UNSUPPORTED

@@ -183,16 +183,31 @@ def test_backward_paths_too_long_for_one_workgroup(gpu, oracle):
         check(gpu, oracle, x, 4, stream, seed=L, label="long path")
 
 
-@pytest.mark.parametrize("case", [(10, 4, 1, 1500, True), (8, 4, 2, 2100, True), (6, 5, 1, 2800, True), (10, 2, 2, 60000, True),
-                                  (10, 2, 2, 60000, False), (10, 3, 3, 40001, True)], ids=lambda c: "-".join(str(v) for v in c))
+@pytest.mark.parametrize("case", [(10, 4, 300, 1500, True), (8, 4, 600, 2100, True), (10, 2, 2, 60000, True),
+                                  (10, 2, 2, 60000, False), (10, 3, 3, 40001, True), (5, 2, 600, 3500, True)], ids=lambda c: "-".join(str(v) for v in c))
 def test_backward_walks_long_paths_in_tiles(gpu, oracle, case):
-    """Paths too long for LDS where the sweep is not cut across workgroups — stream mode of the sliced shapes, and
-    paths too long even for 32 segments in either mode: one workgroup walks tiles of 256 increments (ragged last
-    tile, several paths per workgroup)."""
+    """Paths too long for LDS where the sweep is not cut across workgroups — stream mode of the sliced shapes at a
+    batch that fills the chip (checked on its first paths), and paths too long even for 32 segments in either mode:
+    one workgroup walks tiles of 256 increments (ragged last tile, several paths per workgroup)."""
     d, depth, B, L, stream = case
     assert gpu.sig_backward_segments(None, B, L, d, depth, int(stream)) == 1
+    if B <= 8:
+        x = workloads.brownian_paths(B, L, d, seed=8600 + L)
+        check(gpu, oracle, x, depth, stream, seed=L, label="tiled sweep")
+        return
+    # a large batch: the device sees all of it (zero upstream gradient beyond the first paths), the oracle only
+    # the paths whose gradient is not trivially zero, plus one more
+    import torch
+    keep = 3
     x = workloads.brownian_paths(B, L, d, seed=8600 + L)
-    check(gpu, oracle, x, depth, stream, seed=L, label="tiled sweep")
+    g = np.zeros((B, L - 1, gpu.sig_size(d, depth)), dtype=np.float32)
+    g[:keep] = upstream(np.random.default_rng(L), keep, L - 1, d, depth)
+    rc, got = run_backward(gpu, x, depth, True, g)
+    assert rc == gpu.SIG_OK and np.all(np.isfinite(got))
+    want = oracle.signature_backward(x[:keep + 1], depth, g[:keep + 1], stream=True)
+    err = np.linalg.norm(got[:keep + 1] - want) / np.linalg.norm(want)
+    say("  tiled sweep, %d paths: rel err of the first %d %.2e" % (B, keep + 1, err))
+    assert err <= TOL and not np.any(got[keep:])
 
 
 STREAM_SEGMENTED_CASES = [
@@ -200,7 +215,10 @@ STREAM_SEGMENTED_CASES = [
     # segment with a scan over the segments between them; lengths with ragged last segments, one and several paths,
     # paths too long for the LDS of the uncut sweep at a batch that fills the chip
     (5, 4, 1, 600), (5, 4, 3, 777), (2, 3, 2, 30001), (4, 4, 2, 1000), (3, 5, 1, 700), (5, 5, 1, 300), (6, 4, 2, 400),
-    (8, 3, 1, 900), (7, 3, 2, 2500), (2, 6, 1, 1200), (10, 2, 70, 1700), (9, 3, 2, 350), (5, 4, 3, 3300), (5, 2, 600, 3500),
+    (8, 3, 1, 900), (7, 3, 2, 2500), (2, 6, 1, 1200), (10, 2, 70, 1700), (9, 3, 2, 350), (5, 4, 3, 3300),
+    # the sliced shapes (lanes of a path in several workgroups: the prefix words' partial adjoints are added across slices)
+    (10, 4, 1, 600), (8, 4, 2, 777), (9, 4, 1, 400), (6, 5, 1, 300), (4, 6, 2, 500), (7, 5, 1, 200), (10, 4, 3, 1500),
+    (10, 5, 1, 150),
 ]
 
 
