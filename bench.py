@@ -426,10 +426,10 @@ def main():
             c = workloads.CONFIGS[name]
             extras.append(bench_backward(binding, workloads, ctx, c, B or c.B, steps, warm))
         # ... and on long paths, where the sweep is cut into time segments across workgroups: C3 (2,000 points), and
-        # single paths of 1,000 points in the shapes of C2 and of a ten-channel depth-4 layer
+        # single paths of 1,000 points in the shapes of C2 and of a ten-channel depth-4 layer (final and stream mode)
         extras.append(bench_backward(binding, workloads, ctx, workloads.CONFIGS["C3"], 128, 100, 50))
-        for d, depth in [(5, 4), (10, 4)]:
-            one = workloads.Config("one path", 1, 1000, d, depth, False, "normal")
+        for d, depth, stream in [(5, 4, False), (10, 4, False), (5, 4, True), (10, 4, True)]:
+            one = workloads.Config("one path", 1, 1000, d, depth, stream, "normal")
             extras.append(bench_backward(binding, workloads, ctx, one, 1, 200, 100, seed=workloads.BASE_SEED + 11))
         line["all_configs"] = extras
         line["table1_shapes"] = table1(binding, workloads, ctx)
