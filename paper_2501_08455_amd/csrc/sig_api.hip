@@ -69,12 +69,12 @@ bool join_fits_lds(const OnChipKernelInfo *ki, int segments, const RowShape &rs)
 }
 
 // Time segments for a join in device memory (a pairwise tree of batched row products, one launch of 5-8 us per
-// round): a power of two of at most `wanted`, only for long paths (the fold of K increments takes about 0.1 us per
-// increment when the chip is nearly empty, so fewer than about 500 do not pay for the rounds) and while one set of
-// partial rows stays within 8 MB.  Returns 1 when it does not pay.
+// round): a power of two of at most `wanted`, only from 256 increments on (measured on seven shapes, 1 to 256 paths:
+// 1.06-1.96x from there on, mixed below) and while one set of partial rows stays within 8 MB (with 32 MB the larger
+// batches lose up to 1.7x).  Returns 1 when it does not pay.
 int64_t tree_segments(int64_t wanted, int64_t B, int64_t K, const RowShape &rs)
 {
-    if (K < 512 || wanted < 4) return 1;
+    if (K < 256 || wanted < 4) return 1;
     int64_t W = 1;
     while (W * 2 <= wanted && W * 2 <= kMaxTreeSegments && B * W * 2 * rs.D <= ((int64_t)1 << 21)) W *= 2;
     return W;
@@ -374,7 +374,7 @@ int plan_auto(const sig_ctx *ctx, int64_t B, int64_t L, int stream_flag, const R
         // wavefronts per SIMD (measured there: up to 15x faster, e.g. d = 8, depth 4, one path of 500 points: 49
         // against 737 us; the estimates err on the side of the on-chip kernels).
         // Final mode: only plans that could not be cut in time at all (large lane states whose rows do not fit LDS
-        // for a join, on paths too short for a join in device memory) can lose, with few paths: K dependent steps
+        // for a join, on paths of fewer than 256 increments) can lose, with few paths: K dependent steps
         // of 0.1 + 0.002 us per state float against the level-scan family's launches plus 2.6 x its scratch tensor
         // at 2 TB/s.
         auto prefer_level_scan = [&](const sig_plan_t &chosen) {

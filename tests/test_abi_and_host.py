@@ -161,7 +161,7 @@ def test_stream_plans_of_few_long_paths_are_parallel_in_time():
     # 573 us uncut); shorter paths stay uncut, and of those only few-path plans lose to the level-by-level family
     rc, pl = binding.sig_plan(None, 1, 2000, 10, 4, 0)
     assert rc == binding.SIG_OK and pl.variant == binding.SIG_VARIANT_ON_CHIP and pl.segments == 32
-    rc, pl = binding.sig_plan(None, 1, 400, 10, 4, 0)
+    rc, pl = binding.sig_plan(None, 1, 200, 10, 4, 0)
     assert rc == binding.SIG_OK and (pl.variant == binding.SIG_VARIANT_LEVEL_SCAN or pl.segments == 1)
     rc, pl = binding.sig_plan(None, 128, 2000, 10, 4, 0)
     assert rc == binding.SIG_OK and pl.variant == binding.SIG_VARIANT_ON_CHIP
