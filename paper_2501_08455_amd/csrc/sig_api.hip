@@ -257,7 +257,11 @@ bool finish_on_chip(const OnChipKernelInfo *ki, int cus, int64_t B, int64_t L, i
 // chunk tree runs in registers; measured on d = 4, depth 4: 85 floats per lane lose to 21 by 1.5x at every
 // batch size), else the deepest one.  Stream mode is bound by the stores, not the arithmetic: take the deepest
 // prefix (most lanes, fewest registers, most stores in flight).
-const OnChipKernelInfo *pick_on_chip(int d, int depth, int stream_flag)
+// A shape may also have a prefix depth beyond the first one with a small state (d = 8, 10 at depth 4): more lanes
+// per path than a workgroup has threads and a state of about ten floats.  Final mode takes it only while the
+// batch is too small to give the chip a wavefront per compute unit with the shallower one (measured: 1.2-2.2x up
+// to about 128 paths, 1.7-2x slower from 1,024 on); stream mode stays with lanes that fit a workgroup.
+const OnChipKernelInfo *pick_on_chip(int d, int depth, int stream_flag, int64_t B, int cus)
 {
     const OnChipKernelInfo *best = nullptr;
     for (int t = 0; on_chip_subtable(t); ++t)
@@ -266,6 +270,8 @@ const OnChipKernelInfo *pick_on_chip(int d, int depth, int stream_flag)
         if (!best) { best = e; continue; }
         // entries are ordered by increasing prefix depth; p = 0 (one lane per path) is skipped when there is an
         // alternative: its LDS reads of the increments are not broadcasts (every lane reads another path's row)
+        const bool spans_workgroups = e->lanes_per_chunk > kThreads && best->lanes_per_chunk <= kThreads;
+        if (spans_workgroups && (stream_flag || B * best->lanes_per_chunk >= (int64_t)cus * kWave)) continue;
         if (stream_flag || best->state_floats > 64 || best->p == 0) best = e;
     }
     return best;
@@ -292,7 +298,7 @@ int plan_auto(const sig_ctx *ctx, int64_t B, int64_t L, int stream_flag, const R
     *pl = sig_plan_t{};
     pl->threads = kThreads;
 
-    const OnChipKernelInfo *ki = (B > 0) ? pick_on_chip(rs.d, rs.depth, stream_flag) : nullptr;
+    const OnChipKernelInfo *ki = (B > 0) ? pick_on_chip(rs.d, rs.depth, stream_flag, B, cus) : nullptr;
     if (ki) {
         // a large lane state leaves room for fewer wavefronts per SIMD: do not cut time to fill slots that the
         // registers cannot hold (estimate: state + 45 registers per lane, 512 per SIMD lane)

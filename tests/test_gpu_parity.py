@@ -123,6 +123,8 @@ TREE_JOIN_CASES = [
     (10, 4, 2, 1, 700, 8, 0), (10, 4, 2, 3, 333, 4, 0), (10, 4, 2, 2, 65, 32, 0), (8, 4, 2, 5, 200, 16, 7),
     (6, 5, 3, 2, 150, 8, 0), (7, 5, 3, 1, 130, 4, 0), (7, 5, 3, 2, 97, 16, 0), (9, 4, 2, 1, 40, 32, 0),
     (4, 6, 4, 1, 90, 8, 0),
+    # the deeper prefix of 8 and 10 channels at depth 4 (512 / 1,000 lanes per path), uncut and cut
+    (10, 4, 3, 3, 50, 1, 0), (8, 4, 3, 2, 300, 8, 0), (10, 4, 3, 1, 600, 16, 0), (8, 4, 3, 40, 23, 1, 5),
 ]
 
 
@@ -135,7 +137,7 @@ def test_on_chip_segments_joined_in_device_memory(gpu, oracle, case):
     check(gpu, oracle, x, depth, False, plan, label="on-chip, tree join")
     # not a power of two, or more than 32: refused on the host
     for bad in (3, 6, 64):
-        if bad * gpu.sig_size(d, depth) * 4 > 64 * 1024:
+        if segments > 1 and bad * gpu.sig_size(d, depth) * 4 > 64 * 1024:
             bad_plan = gpu.make_plan(gpu.SIG_VARIANT_ON_CHIP, prefix_depth=p, chunks=1, segments=bad)
             assert gpu.sig_plan_validate(B, L, d, depth, 0, bad_plan) == gpu.SIG_ERR_INVALID
 
