@@ -12,6 +12,7 @@ const OnChipKernelInfo kTable[] = {
     SIG_ON_CHIP_ENTRY(9, 2, 1),
     SIG_ON_CHIP_ENTRY(9, 3, 2),
     SIG_ON_CHIP_ENTRY(9, 4, 2),
+    SIG_ON_CHIP_ENTRY(9, 4, 3),   // for batches too small to fill the chip with 81 lanes per path
     SIG_ON_CHIP_ENTRY(7, 5, 3),
     SIG_ON_CHIP_ENTRY(8, 5, 3),
     SIG_ON_CHIP_ENTRY(9, 5, 3),

@@ -246,7 +246,7 @@ def test_prefix_depth_follows_the_batch_for_ten_channels_at_depth_four():
     """d = 8 and 10 at depth 4 have two compiled prefix depths: the deeper one (a thousand lanes per path) only while
     the batch is too small to give every compute unit a wavefront with the shallower one; stream mode keeps lanes
     that fit a workgroup."""
-    for d, small, large in [(10, 128, 256), (8, 128, 1024)]:
+    for d, small, large in [(10, 128, 256), (8, 128, 1024), (9, 128, 256)]:
         rc, pl = binding.sig_plan(None, small, 100, d, 4, 0)
         assert rc == binding.SIG_OK and pl.variant == binding.SIG_VARIANT_ON_CHIP and pl.prefix_depth == 3
         rc, pl = binding.sig_plan(None, large, 100, d, 4, 0)

@@ -125,6 +125,7 @@ TREE_JOIN_CASES = [
     (4, 6, 4, 1, 90, 8, 0),
     # the deeper prefix of 8 and 10 channels at depth 4 (512 / 1,000 lanes per path), uncut and cut
     (10, 4, 3, 3, 50, 1, 0), (8, 4, 3, 2, 300, 8, 0), (10, 4, 3, 1, 600, 16, 0), (8, 4, 3, 40, 23, 1, 5),
+    (9, 4, 3, 5, 77, 1, 0), (9, 4, 3, 1, 400, 4, 0),
 ]
 
 
