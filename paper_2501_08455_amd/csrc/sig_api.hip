@@ -261,7 +261,7 @@ bool finish_on_chip(const OnChipKernelInfo *ki, int cus, int64_t B, int64_t L, i
 // per path than a workgroup has threads and a state of about ten floats.  Final mode takes it only while the
 // batch is too small to give the chip a wavefront per compute unit with the shallower one (measured: 1.2-2.2x up
 // to about 128 paths, 1.7-2x slower from 1,024 on); stream mode stays with lanes that fit a workgroup.
-const OnChipKernelInfo *pick_on_chip(int d, int depth, int stream_flag, int64_t B, int cus)
+const OnChipKernelInfo *pick_on_chip(int d, int depth, int stream_flag, int64_t B, int64_t K, int cus)
 {
     const OnChipKernelInfo *best = nullptr;
     for (int t = 0; on_chip_subtable(t); ++t)
@@ -272,7 +272,16 @@ const OnChipKernelInfo *pick_on_chip(int d, int depth, int stream_flag, int64_t 
         // alternative: its LDS reads of the increments are not broadcasts (every lane reads another path's row)
         const bool spans_workgroups = e->lanes_per_chunk > kThreads && best->lanes_per_chunk <= kThreads;
         if (spans_workgroups && (stream_flag || B * best->lanes_per_chunk >= (int64_t)cus * kWave)) continue;
-        if (stream_flag || best->state_floats > 64 || best->p == 0) best = e;
+        // d = 5 at depth 4 also has p = 3 (125 lanes, six floats of state) behind the p = 2 that the rule below
+        // prefers: small batches of short paths are latency-bound, and four chunks of it in a workgroup of 512
+        // threads take 1.2x less time (128 paths of 100 points: 7.1 -> 5.9 us; from 500 points or 512 paths on p = 2
+        // with its ten chunks and its segments is as fast or faster)
+        const bool short_and_few = !stream_flag && best->state_floats <= 64 && best->p > 0 && e->lanes_per_chunk <= 128 &&
+                                   B * best->lanes_per_chunk <= (int64_t)cus * kWave / 2 && K <= 256;
+        // (stream mode, not measured with it, keeps p = 2)
+        const bool final_only = best->p > 0 && best->state_floats <= 64 && e->lanes_per_chunk > kWave && e->lanes_per_chunk <= 128;
+        if (stream_flag && final_only) continue;
+        if (stream_flag || best->state_floats > 64 || best->p == 0 || short_and_few) best = e;
     }
     return best;
 }
@@ -298,7 +307,7 @@ int plan_auto(const sig_ctx *ctx, int64_t B, int64_t L, int stream_flag, const R
     *pl = sig_plan_t{};
     pl->threads = kThreads;
 
-    const OnChipKernelInfo *ki = (B > 0) ? pick_on_chip(rs.d, rs.depth, stream_flag, B, cus) : nullptr;
+    const OnChipKernelInfo *ki = (B > 0) ? pick_on_chip(rs.d, rs.depth, stream_flag, B, K, cus) : nullptr;
     if (ki) {
         // a large lane state leaves room for fewer wavefronts per SIMD: do not cut time to fill slots that the
         // registers cannot hold (estimate: state + 45 registers per lane, 512 per SIMD lane)
@@ -312,11 +321,17 @@ int plan_auto(const sig_ctx *ctx, int64_t B, int64_t L, int stream_flag, const R
         pl->chunks = 1;
         pl->segments = 1;
         const int Q = ki->lanes_per_chunk;
+        // the deeper prefix that pick_on_chip takes for small batches of short paths runs four chunks in a
+        // workgroup of 512 threads
+        const OnChipKernelInfo *shallower = ki->p > 0 ? find_on_chip(rs.d, rs.depth, ki->p - 1) : nullptr;
+        const int wg = (!stream_flag && Q > kWave && Q <= 128 && shallower && shallower->p > 0 && shallower->state_floats <= 64)
+                           ? 2 * kThreads : kThreads;
+        pl->threads = wg;
         if (Q <= kThreads) {
             // cut time into pieces only as far as needed to fill the chip; every cut costs one Eq. 4 product
             int64_t pieces = ceil_div(want_lanes, B * Q);
             // chunks side by side in a workgroup (stream kernels keep a chunk's lanes inside one wavefront)
-            int64_t cmax = (stream_flag && Q <= kWave) ? (int64_t)(kThreads / kWave) * (kWave / Q) : kThreads / Q;
+            int64_t cmax = (stream_flag && Q <= kWave) ? (int64_t)(kThreads / kWave) * (kWave / Q) : wg / Q;
             // LDS for the chunk signatures: two buffers in stream mode, one when the tree runs in registers
             int64_t clds = (kMaxLdsBytes - kTileLdsBytes) /
                            ((stream_flag || ki->state_floats > 64 ? 2 : 1) * rs.D * (int64_t)sizeof(float));
@@ -331,7 +346,7 @@ int plan_auto(const sig_ctx *ctx, int64_t B, int64_t L, int stream_flag, const R
             if (!(stream_flag && Q <= kWave)) {
                 // lanes are packed group after group: prefer a nearby chunk count whose groups fill the workgroup
                 // (e.g. Q = 25: 6 chunks leave 106 of 256 lanes idle, 5 chunks fit twice)
-                auto used = [&](int64_t c) { return (kThreads / (c * Q)) * c * Q; };
+                auto used = [&](int64_t c) { return (wg / (c * Q)) * c * Q; };
                 int64_t best = C;
                 for (int64_t c = (C > 2 ? C - 2 : 1); c <= C + 4 && c <= cmax; ++c)
                     if (used(c) * 100 > used(best) * 105 || (used(c) * 100 > used(best) * 95 && best > C && c >= C && c < best)) best = c;
@@ -438,7 +453,7 @@ int plan_auto(const sig_ctx *ctx, int64_t B, int64_t L, int stream_flag, const R
         // the row length): fall back to smaller workgroups, then to fewer chunks, before giving up on the family
         const sig_plan_t want = *pl;
         for (int c = want.chunks; c >= 1; c = (c > 1 ? (c + 1) / 2 : 0)) {
-            for (int threads = kThreads; threads >= kWave; threads /= 2) {
+            for (int threads = (c == want.chunks ? want.threads : kThreads); threads >= kWave; threads /= 2) {
                 *pl = want;
                 pl->chunks = c;
                 pl->threads = threads;

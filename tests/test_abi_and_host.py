@@ -64,7 +64,7 @@ def test_plan_of_the_five_configs_is_on_chip_and_consistent(name):
     assert binding.sig_on_chip_available(cfg.d, cfg.depth, pl.prefix_depth)
     K = cfg.L - 1
     assert 1 <= pl.chunks * pl.segments <= K
-    assert pl.threads % 64 == 0 and 64 <= pl.threads <= 256
+    assert pl.threads % 64 == 0 and 64 <= pl.threads <= 512
     lanes = cfg.d ** pl.prefix_depth
     assert lanes > pl.threads or pl.chunks * lanes <= pl.threads
     if cfg.stream:
@@ -253,3 +253,17 @@ def test_prefix_depth_follows_the_batch_for_ten_channels_at_depth_four():
         assert rc == binding.SIG_OK and pl.variant == binding.SIG_VARIANT_ON_CHIP and pl.prefix_depth == 2
         rc, pl = binding.sig_plan(None, 4096, 100, d, 4, 1)
         assert rc == binding.SIG_OK and pl.variant == binding.SIG_VARIANT_ON_CHIP and pl.prefix_depth == 2
+
+
+def test_small_batches_of_short_paths_take_the_deeper_prefix_for_five_channels_at_depth_four():
+    """d = 5 at depth 4: p = 3 with four chunks in a workgroup of 512 threads while the batch leaves the chip mostly
+    idle and the path is short; otherwise, and in stream mode, p = 2 in 256 threads."""
+    for B, L in [(128, 100), (1, 100), (32, 50), (256, 200)]:
+        rc, pl = binding.sig_plan(None, B, L, 5, 4, 0)
+        assert rc == binding.SIG_OK and pl.variant == binding.SIG_VARIANT_ON_CHIP
+        assert (pl.prefix_depth, pl.chunks, pl.threads) == (3, 4, 512), (B, L)
+        assert binding.sig_plan_validate(B, L, 5, 4, 0, pl) == binding.SIG_OK
+    for B, L, stream in [(512, 100, 0), (128, 300, 0), (128, 2000, 0), (128, 100, 1), (4, 50, 1)]:
+        rc, pl = binding.sig_plan(None, B, L, 5, 4, stream)
+        assert rc == binding.SIG_OK and pl.variant == binding.SIG_VARIANT_ON_CHIP
+        assert pl.prefix_depth == 2 and pl.threads <= 256, (B, L, stream)

@@ -112,6 +112,11 @@ ON_CHIP_CASES = [
     (10, 6, 4, 2, 9, 1, 1, 0, False), (10, 6, 4, 1, 4, 1, 1, 2, True),
     (5, 4, 2, 40, 100, 7, 1, 0, False, 512), (4, 4, 2, 9, 256, 16, 1, 0, True, 512), (5, 4, 2, 9000, 30, 1, 1, 7, False),
     (4, 4, 2, 3000, 20, 1, 1, 6, True), (2, 3, 1, 70000, 9, 1, 1, 0, False), (5, 4, 2, 33, 300, 1, 4, 0, False, 128),
+    # the deeper prefix of five channels at depth 4 (125 lanes per path): the plan of small batches of short paths
+    # (four chunks in 512 threads), two chunks in 256, uncut, cut into segments, tiled, and in stream mode
+    (5, 4, 3, 128, 100, 4, 1, 0, False, 512), (5, 4, 3, 7, 33, 2, 1, 0, False), (5, 4, 3, 3, 20, 1, 1, 0, False),
+    (5, 4, 3, 5, 257, 4, 3, 0, False, 512), (5, 4, 3, 300, 64, 3, 1, 5, False, 512), (5, 4, 3, 6, 41, 2, 1, 0, True),
+    (5, 4, 3, 2, 2, 1, 1, 0, False),
 ]
 
 
