@@ -267,3 +267,20 @@ def test_small_batches_of_short_paths_take_the_deeper_prefix_for_five_channels_a
         rc, pl = binding.sig_plan(None, B, L, 5, 4, stream)
         assert rc == binding.SIG_OK and pl.variant == binding.SIG_VARIANT_ON_CHIP
         assert pl.prefix_depth == 2 and pl.threads <= 256, (B, L, stream)
+
+
+def test_small_batches_take_wide_workgroups_for_small_states_with_many_lanes():
+    """Final mode, lane state of at most 64 floats, more than 64 (and fewer than 256) lanes per path: 512 threads with
+    twice the chunks while 256 threads would leave the chip at or below a wavefront per SIMD."""
+    for d, depth, chunks in [(5, 5, 4), (6, 5, 2), (9, 3, 6), (10, 3, 4)]:
+        rc, pl = binding.sig_plan(None, 128, 100, d, depth, 0)
+        assert rc == binding.SIG_OK and pl.variant == binding.SIG_VARIANT_ON_CHIP
+        assert (pl.chunks, pl.threads) == (chunks, 512), (d, depth)
+        assert binding.sig_plan_validate(128, 100, d, depth, 0, pl) == binding.SIG_OK
+        rc, pl = binding.sig_plan(None, 512, 100, d, depth, 0)
+        assert rc == binding.SIG_OK and pl.threads == 256, (d, depth)
+        rc, pl = binding.sig_plan(None, 128, 100, d, depth, 1)
+        assert rc == binding.SIG_OK and pl.threads <= 256, (d, depth)
+    for d, depth in [(4, 6), (4, 4), (6, 4), (7, 4), (10, 4)]:
+        rc, pl = binding.sig_plan(None, 128, 100, d, depth, 0)
+        assert rc == binding.SIG_OK and pl.threads <= 256, (d, depth)

@@ -117,6 +117,10 @@ ON_CHIP_CASES = [
     (5, 4, 3, 128, 100, 4, 1, 0, False, 512), (5, 4, 3, 7, 33, 2, 1, 0, False), (5, 4, 3, 3, 20, 1, 1, 0, False),
     (5, 4, 3, 5, 257, 4, 3, 0, False, 512), (5, 4, 3, 300, 64, 3, 1, 5, False, 512), (5, 4, 3, 6, 41, 2, 1, 0, True),
     (5, 4, 3, 2, 2, 1, 1, 0, False),
+    # workgroups of 512 threads for the other small lane states with more than 64 lanes per path
+    (5, 5, 3, 9, 100, 4, 1, 0, False, 512), (5, 5, 3, 3, 500, 4, 2, 0, False, 512), (6, 5, 3, 5, 77, 2, 1, 0, False, 512),
+    (6, 5, 3, 2, 400, 2, 4, 0, False, 512), (9, 3, 2, 20, 100, 6, 1, 0, False, 512), (9, 3, 2, 3, 1000, 6, 6, 0, False, 512),
+    (10, 3, 2, 11, 130, 5, 2, 0, False, 512), (10, 3, 2, 300, 60, 4, 1, 7, False, 512),
 ]
 
 
