@@ -1,5 +1,6 @@
 // Host side of libsig: argument checking, the planner that maps a shape onto the GPU, scratch
 // management and kernel dispatch.  The C ABI is declared and documented in include/sig.h.
+#include <cmath>
 #include <new>
 
 #include "sig_internal.h"
@@ -374,6 +375,16 @@ int plan_auto(const sig_ctx *ctx, int64_t B, int64_t L, int stream_flag, const R
             if (!stream_flag) {
                 W = (pieces + C / 2) / C;  // rounded: a second launch is not worth a few missing lanes
                 int64_t wmax = K / (C * kMinSegmentChunkSteps);
+                // The launch takes about a K / (C W) + b W: steps of a chunk, of a cost that grows with the lane state,
+                // plus a join that walks W rows of D words.  The minimum, W = sqrt(a K / (b C)), fitted to 8 shapes with
+                // lane states of 21-63 floats and rows of 120-1,554 words on 1-128 paths of 1,000-4,000 points, is
+                // 1.7 sqrt(state K / (D C)); 48 steps per chunk left such paths with too few segments (1.1-2.4x, e.g.
+                // (5,3), 32 paths of 4,000 points: 36.9 -> 16 us).  Chunks keep at least eight steps.  Only while the
+                // chip is at most half a wavefront per SIMD full (512 paths of 1,000 points lost 1.2-1.7x with it), and
+                // not for two segments (the join is a second launch: 128 paths of 500 points lost 1.06-1.1x).
+                int64_t by_cost = (int64_t)(1.7 * std::sqrt((double)ki->state_floats * (double)K / ((double)rs.D * (double)C)));
+                if (by_cost > K / (C * kMinChunkSteps)) by_cost = K / (C * kMinChunkSteps);
+                if (by_cost >= 3 && B * Q * C <= (int64_t)cus * 2 * kWave && wmax < by_cost) wmax = by_cost;
                 if (W > wmax) W = wmax;
                 const int64_t wanted = W;
                 if (W > 8) W = 8;

@@ -284,3 +284,21 @@ def test_small_batches_take_wide_workgroups_for_small_states_with_many_lanes():
     for d, depth in [(4, 6), (4, 4), (6, 4), (7, 4), (10, 4)]:
         rc, pl = binding.sig_plan(None, 128, 100, d, depth, 0)
         assert rc == binding.SIG_OK and pl.threads <= 256, (d, depth)
+
+
+def test_few_long_paths_with_small_states_are_cut_into_more_segments():
+    """Final mode, chunked register kernels: while the chip is at most half a wavefront per SIMD full, the segment count
+    follows the cost model (steps of a chunk against a join over W rows) instead of 48 steps per chunk."""
+    for d, depth, B, L, segments in [(4, 4, 1, 1000, 3), (4, 4, 8, 2000, 4), (5, 4, 32, 1000, 3), (3, 5, 8, 2000, 4),
+                                     (5, 3, 8, 2000, 4), (6, 4, 1, 1000, 3)]:
+        rc, pl = binding.sig_plan(None, B, L, d, depth, 0)
+        assert rc == binding.SIG_OK and pl.variant == binding.SIG_VARIANT_ON_CHIP
+        assert pl.segments == segments, (d, depth, B, L, pl.segments)
+        assert (L - 1) // (pl.chunks * pl.segments) >= 8
+    # a busier chip keeps the longer chunks; two segments are not taken on the model's word alone
+    for d, depth, B, L in [(4, 4, 512, 1000), (3, 5, 512, 1000), (4, 4, 128, 500), (3, 5, 128, 500)]:
+        rc, pl = binding.sig_plan(None, B, L, d, depth, 0)
+        assert rc == binding.SIG_OK and pl.segments == 1, (d, depth, B, L)
+    # the third config is unchanged
+    rc, pl = binding.sig_plan(None, 128, 2000, 5, 4, 0)
+    assert rc == binding.SIG_OK and (pl.prefix_depth, pl.chunks, pl.segments) == (2, 10, 4)
