@@ -386,6 +386,17 @@ int plan_auto(const sig_ctx *ctx, int64_t B, int64_t L, int stream_flag, const R
                 if (by_cost > K / (C * kMinChunkSteps)) by_cost = K / (C * kMinChunkSteps);
                 if (by_cost >= 3 && B * Q * C <= (int64_t)cus * 2 * kWave && wmax < by_cost) wmax = by_cost;
                 if (W > wmax) W = wmax;
+                // small lane states: on a busy chip the second launch and the join cost more than the shorter chunks
+                // save, the sooner the shorter the path.  Measured best segment counts on (4,4), (5,4), (3,5), (5,3),
+                // (4,5), (6,4), (7,4), (5,5): 128 / 256 / 512 paths of 1,000 points 4 / 2 / 1, 128 / 384 / 1,024 paths of
+                // 2,000 points 4 / 2-4 / 1-2, 256 paths of 4,000 points 4-6: about (two wavefronts per SIMD / those of
+                // the chunks alone) x sqrt(K / 1,000); 1.1-1.4x against the eight wavefronts per SIMD the chunk count aims for
+                if (ki->state_floats <= 64) {
+                    const int64_t lanes = B * Q * C;
+                    int64_t by_occupancy = (int64_t)(2.0 * (double)cus * 4 * kWave / (double)lanes * std::sqrt((double)K / 1000.0) + 0.25);
+                    if (by_occupancy < 1) by_occupancy = 1;
+                    if (W > by_occupancy) W = by_occupancy;
+                }
                 const int64_t wanted = W;
                 if (W > 8) W = 8;
                 while (W > 1 && !join_fits_lds(ki, (int)W, rs)) --W;

@@ -299,6 +299,9 @@ def test_few_long_paths_with_small_states_are_cut_into_more_segments():
     for d, depth, B, L in [(4, 4, 512, 1000), (3, 5, 512, 1000), (4, 4, 128, 500), (3, 5, 128, 500)]:
         rc, pl = binding.sig_plan(None, B, L, d, depth, 0)
         assert rc == binding.SIG_OK and pl.segments == 1, (d, depth, B, L)
+    # the busier the chip, the fewer segments; the longer the path, the more
+    got = [binding.sig_plan(None, B, L, 5, 4, 0)[1].segments for B, L in [(128, 2000), (384, 2000), (1024, 2000), (512, 1000), (256, 4000)]]
+    assert got == [4, 2, 1, 1, 4], got
     # the third config is unchanged
     rc, pl = binding.sig_plan(None, 128, 2000, 5, 4, 0)
     assert rc == binding.SIG_OK and (pl.prefix_depth, pl.chunks, pl.segments) == (2, 10, 4)
