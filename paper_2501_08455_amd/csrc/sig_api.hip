@@ -273,14 +273,15 @@ const OnChipKernelInfo *pick_on_chip(int d, int depth, int stream_flag, int64_t 
         // alternative: its LDS reads of the increments are not broadcasts (every lane reads another path's row)
         const bool spans_workgroups = e->lanes_per_chunk > kThreads && best->lanes_per_chunk <= kThreads;
         if (spans_workgroups && (stream_flag || B * best->lanes_per_chunk >= (int64_t)cus * kWave)) continue;
-        // d = 5 at depth 4 also has p = 3 (125 lanes, six floats of state) behind the p = 2 that the rule below
-        // prefers: small batches of short paths are latency-bound, and four chunks of it in a workgroup of 512
-        // threads take 1.2x less time (128 paths of 100 points: 7.1 -> 5.9 us; from 500 points or 512 paths on p = 2
-        // with its ten chunks and its segments is as fast or faster)
+        // (5,4), (4,4), (5,3) and (6,3) also have a prefix depth (five to seven floats of state) behind the one that the
+        // rule below prefers: small batches of short paths are latency-bound, and the lighter steps take 1.1-1.35x
+        // less time ((5,4), 128 paths of 100 points, four chunks in 512 threads: 7.1 -> 5.9 us; (5,3) 6.3 -> 4.9;
+        // (6,3) 7.2 -> 5.4; (4,4) 6.1 -> 5.4; from 500 points or 512 paths on the shallower depth with its many
+        // chunks and its segments is as fast or faster)
         const bool short_and_few = !stream_flag && best->state_floats <= 64 && best->p > 0 && e->lanes_per_chunk <= 128 &&
                                    B * e->lanes_per_chunk * (kThreads / e->lanes_per_chunk) <= (int64_t)cus * 4 * kWave && K <= 256;
         // (stream mode, not measured with it, keeps p = 2)
-        const bool final_only = best->p > 0 && best->state_floats <= 64 && e->lanes_per_chunk > kWave && e->lanes_per_chunk <= 128;
+        const bool final_only = best->p > 0 && best->state_floats <= 64;
         if (stream_flag && final_only) continue;
         if (stream_flag || best->state_floats > 64 || best->p == 0 || short_and_few) best = e;
     }
@@ -330,7 +331,13 @@ int plan_auto(const sig_ctx *ctx, int64_t B, int64_t L, int stream_flag, const R
         // 100 points and lose to more segments on long paths.
         const int64_t slots256 = Q <= kThreads ? kThreads / Q : 1;
         const bool few = B * Q * slots256 <= (int64_t)cus * 4 * kWave;
-        const bool wide = !stream_flag && ki->state_floats <= 64 && Q > kWave && Q < kThreads && few;  // (256 lanes: not measured)
+        // The prefix depths behind the first one with a small state (picked by pick_on_chip for small batches of short
+        // paths) take them too once the path is long enough for twice the chunks ((5,3,2), (6,3,2), 128 paths of 200-257
+        // points: 1.04-1.18x; (4,4,3) with its 64 lanes at any length: 1.0-1.25x).
+        const OnChipKernelInfo *shallower = ki->p > 1 ? find_on_chip(rs.d, rs.depth, ki->p - 1) : nullptr;
+        const bool deeper = shallower && shallower->state_floats <= 64;
+        const bool wide = !stream_flag && ki->state_floats <= 64 && Q < kThreads && few &&   // (256 lanes: not measured)
+                          (Q > kWave || (deeper && (Q == kWave || K / kMinChunkSteps >= 2 * slots256)));
         const int wg = wide ? 2 * kThreads : kThreads;
         pl->threads = wg;
         if (Q <= kThreads) {

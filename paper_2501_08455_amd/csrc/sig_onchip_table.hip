@@ -9,6 +9,7 @@ const OnChipKernelInfo kTable[] = {
     SIG_ON_CHIP_ENTRY(2, 3, 1),
     SIG_ON_CHIP_ENTRY(4, 4, 1),
     SIG_ON_CHIP_ENTRY(4, 4, 2),
+    SIG_ON_CHIP_ENTRY(4, 4, 3),
     SIG_ON_CHIP_ENTRY(5, 4, 1),
     SIG_ON_CHIP_ENTRY(5, 4, 2),
     SIG_ON_CHIP_ENTRY(5, 4, 3),

@@ -121,6 +121,13 @@ ON_CHIP_CASES = [
     (5, 5, 3, 9, 100, 4, 1, 0, False, 512), (5, 5, 3, 3, 500, 4, 2, 0, False, 512), (6, 5, 3, 5, 77, 2, 1, 0, False, 512),
     (6, 5, 3, 2, 400, 2, 4, 0, False, 512), (9, 3, 2, 20, 100, 6, 1, 0, False, 512), (9, 3, 2, 3, 1000, 6, 6, 0, False, 512),
     (10, 3, 2, 11, 130, 5, 2, 0, False, 512), (10, 3, 2, 300, 60, 4, 1, 7, False, 512),
+    # the deeper prefix of (4,4), (5,3) and (6,3): the planner's small-batch plans, cut and tiled ones, and stream mode
+    (4, 4, 3, 128, 100, 8, 1, 0, False, 512), (4, 4, 3, 5, 50, 4, 1, 0, False), (4, 4, 3, 3, 300, 8, 2, 0, False, 512),
+    (4, 4, 3, 70, 64, 2, 1, 5, False), (4, 4, 3, 6, 41, 2, 1, 0, True), (4, 4, 3, 2, 9, 1, 1, 0, True),
+    (5, 3, 2, 128, 100, 8, 1, 0, False), (5, 3, 2, 9, 257, 16, 1, 0, False, 512), (5, 3, 2, 4, 500, 10, 3, 0, False),
+    (5, 3, 2, 300, 40, 3, 1, 6, False), (5, 3, 2, 7, 33, 4, 1, 0, True), (5, 3, 2, 2, 2, 1, 1, 0, False),
+    (6, 3, 2, 128, 100, 7, 1, 0, False), (6, 3, 2, 11, 200, 14, 1, 0, False, 512), (6, 3, 2, 3, 400, 7, 4, 0, False),
+    (6, 3, 2, 200, 30, 2, 1, 4, False), (6, 3, 2, 5, 29, 3, 1, 0, True),
 ]
 
 
