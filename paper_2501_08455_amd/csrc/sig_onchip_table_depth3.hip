@@ -8,11 +8,13 @@ namespace {
 const OnChipKernelInfo kTable[] = {
     SIG_ON_CHIP_ENTRY(3, 3, 1),
     SIG_ON_CHIP_ENTRY(4, 3, 1),
+    SIG_ON_CHIP_ENTRY(4, 3, 2),
     SIG_ON_CHIP_ENTRY(5, 3, 1),
     SIG_ON_CHIP_ENTRY(5, 3, 2),
     SIG_ON_CHIP_ENTRY(6, 3, 1),
     SIG_ON_CHIP_ENTRY(6, 3, 2),
     SIG_ON_CHIP_ENTRY(7, 3, 1),
+    SIG_ON_CHIP_ENTRY(7, 3, 2),
     SIG_ON_CHIP_ENTRY(8, 3, 2),
     SIG_ON_CHIP_ENTRY(10, 3, 2),
     {0, 0, 0, 0, 0, 0, nullptr, nullptr, nullptr},

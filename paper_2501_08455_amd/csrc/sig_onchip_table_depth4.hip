@@ -10,6 +10,7 @@ namespace {
 const OnChipKernelInfo kTable[] = {
     SIG_ON_CHIP_ENTRY(2, 4, 1),
     SIG_ON_CHIP_ENTRY(3, 4, 1),
+    SIG_ON_CHIP_ENTRY(3, 4, 2),
     SIG_ON_CHIP_ENTRY(6, 4, 2),
     SIG_ON_CHIP_ENTRY(7, 4, 2),
     SIG_ON_CHIP_ENTRY(8, 4, 2),

@@ -307,17 +307,17 @@ def test_few_long_paths_with_small_states_are_cut_into_more_segments():
     assert rc == binding.SIG_OK and (pl.prefix_depth, pl.chunks, pl.segments) == (2, 10, 4)
 
 
-def test_deeper_prefix_entries_of_four_five_and_six_channels():
-    """(4,4), (5,3) and (6,3) have a prefix depth behind the first one with a small lane state: taken in final mode for
+def test_deeper_prefix_entries_behind_the_first_small_state():
+    """(4,4), (5,3), (6,3), (4,3), (7,3), (3,4), (3,5), (2,6) and (3,6) have a prefix depth behind the first one with a small lane state: taken in final mode for
     small batches of short paths only; with 512 threads once the path is long enough for twice the chunks."""
-    for d, depth, p in [(4, 4, 3), (5, 3, 2), (6, 3, 2)]:
+    for d, depth, p in [(4, 4, 3), (5, 3, 2), (6, 3, 2), (4, 3, 2), (7, 3, 2), (3, 4, 2), (3, 5, 3), (2, 6, 2), (3, 6, 4)]:
         assert binding.sig_on_chip_available(d, depth, p)
         for B, L in [(16, 100), (128, 50), (128, 257), (256, 100)]:
             rc, pl = binding.sig_plan(None, B, L, d, depth, 0)
             assert rc == binding.SIG_OK and pl.variant == binding.SIG_VARIANT_ON_CHIP and pl.prefix_depth == p, (d, depth, B, L)
             assert binding.sig_plan_validate(B, L, d, depth, 0, pl) == binding.SIG_OK
         rc, pl = binding.sig_plan(None, 128, 257, d, depth, 0)
-        assert pl.threads == 512
+        assert pl.threads == (256 if (d, depth) in [(3, 4), (2, 6)] else 512)
         for B, L, stream in [(300, 100, 0), (128, 300, 0), (4096, 100, 0)]:
             rc, pl = binding.sig_plan(None, B, L, d, depth, stream)
             assert rc == binding.SIG_OK and pl.variant == binding.SIG_VARIANT_ON_CHIP and pl.prefix_depth == p - 1, (d, depth, B, L)

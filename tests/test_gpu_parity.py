@@ -128,6 +128,13 @@ ON_CHIP_CASES = [
     (5, 3, 2, 300, 40, 3, 1, 6, False), (5, 3, 2, 7, 33, 4, 1, 0, True), (5, 3, 2, 2, 2, 1, 1, 0, False),
     (6, 3, 2, 128, 100, 7, 1, 0, False), (6, 3, 2, 11, 200, 14, 1, 0, False, 512), (6, 3, 2, 3, 400, 7, 4, 0, False),
     (6, 3, 2, 200, 30, 2, 1, 4, False), (6, 3, 2, 5, 29, 3, 1, 0, True),
+    # ... and of (4,3), (7,3), (3,4), (3,5), (2,6), (3,6)
+    (4, 3, 2, 128, 100, 12, 1, 0, False), (4, 3, 2, 9, 257, 32, 1, 0, False, 512), (4, 3, 2, 5, 300, 8, 3, 0, False), (4, 3, 2, 7, 33, 4, 1, 0, True),
+    (7, 3, 2, 128, 100, 8, 1, 0, False, 512), (7, 3, 2, 64, 20, 1, 1, 0, False), (7, 3, 2, 3, 400, 5, 4, 0, False), (7, 3, 2, 6, 25, 2, 1, 0, True),
+    (3, 4, 2, 128, 100, 12, 1, 0, False), (3, 4, 2, 11, 257, 28, 1, 0, False), (3, 4, 2, 300, 40, 3, 1, 6, False), (3, 4, 2, 5, 31, 4, 1, 0, True),
+    (3, 5, 3, 128, 100, 8, 1, 0, False), (3, 5, 3, 9, 200, 16, 1, 0, False, 512), (3, 5, 3, 2, 500, 8, 4, 0, False), (3, 5, 3, 4, 27, 2, 1, 0, True),
+    (2, 6, 2, 128, 100, 12, 1, 0, False), (2, 6, 2, 7, 257, 32, 1, 0, False), (2, 6, 2, 3, 600, 16, 3, 0, False), (2, 6, 2, 5, 40, 4, 1, 0, True),
+    (3, 6, 4, 128, 100, 6, 1, 0, False, 512), (3, 6, 4, 64, 20, 2, 1, 0, False, 512), (3, 6, 4, 2, 300, 3, 4, 0, False), (3, 6, 4, 3, 19, 2, 1, 0, True),
 ]
 
 
