@@ -278,8 +278,11 @@ const OnChipKernelInfo *pick_on_chip(int d, int depth, int stream_flag, int64_t 
         // less time ((5,4), 128 paths of 100 points, four chunks in 512 threads: 7.1 -> 5.9 us; (5,3) 6.3 -> 4.9;
         // (6,3) 7.2 -> 5.4; (4,4) 6.1 -> 5.4; from 500 points or 512 paths on the shallower depth with its many
         // chunks and its segments is as fast or faster)
-        const bool short_and_few = !stream_flag && best->state_floats <= 64 && best->p > 0 && e->lanes_per_chunk <= 128 &&
-                                   B * e->lanes_per_chunk * (kThreads / e->lanes_per_chunk) <= (int64_t)cus * 4 * kWave && K <= 256;
+        // (a deeper kernel with more than 128 lanes per path runs only two chunks in 512 threads and wins up to about
+        // 128 increments: (6,4,3) 1.08-1.38x up to 100 points, 0.83-0.91x from 200 on)
+        const int64_t short_path = e->lanes_per_chunk > 128 ? 128 : 256;
+        const bool short_and_few = !stream_flag && best->state_floats <= 64 && best->p > 0 && e->lanes_per_chunk < kThreads &&
+                                   B * e->lanes_per_chunk * (kThreads / e->lanes_per_chunk) <= (int64_t)cus * 4 * kWave && K <= short_path;
         // (stream mode, not measured with it, keeps p = 2)
         const bool final_only = best->p > 0 && best->state_floats <= 64;
         if (stream_flag && final_only) continue;

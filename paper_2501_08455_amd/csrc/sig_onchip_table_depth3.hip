@@ -7,6 +7,7 @@ namespace sig {
 namespace {
 const OnChipKernelInfo kTable[] = {
     SIG_ON_CHIP_ENTRY(3, 3, 1),
+    SIG_ON_CHIP_ENTRY(3, 3, 2),
     SIG_ON_CHIP_ENTRY(4, 3, 1),
     SIG_ON_CHIP_ENTRY(4, 3, 2),
     SIG_ON_CHIP_ENTRY(5, 3, 1),

@@ -9,9 +9,12 @@ namespace sig {
 namespace {
 const OnChipKernelInfo kTable[] = {
     SIG_ON_CHIP_ENTRY(2, 4, 1),
+    SIG_ON_CHIP_ENTRY(2, 4, 2),
     SIG_ON_CHIP_ENTRY(3, 4, 1),
     SIG_ON_CHIP_ENTRY(3, 4, 2),
+    SIG_ON_CHIP_ENTRY(3, 4, 3),
     SIG_ON_CHIP_ENTRY(6, 4, 2),
+    SIG_ON_CHIP_ENTRY(6, 4, 3),
     SIG_ON_CHIP_ENTRY(7, 4, 2),
     SIG_ON_CHIP_ENTRY(8, 4, 2),
     SIG_ON_CHIP_ENTRY(8, 4, 3),

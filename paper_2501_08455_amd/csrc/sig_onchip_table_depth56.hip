@@ -7,6 +7,7 @@ namespace sig {
 namespace {
 const OnChipKernelInfo kTable[] = {
     SIG_ON_CHIP_ENTRY(2, 5, 1),
+    SIG_ON_CHIP_ENTRY(2, 5, 2),
     SIG_ON_CHIP_ENTRY(3, 5, 2),
     SIG_ON_CHIP_ENTRY(3, 5, 3),
     SIG_ON_CHIP_ENTRY(4, 5, 3),
@@ -14,6 +15,7 @@ const OnChipKernelInfo kTable[] = {
     SIG_ON_CHIP_ENTRY(6, 5, 3),
     SIG_ON_CHIP_ENTRY(2, 6, 1),
     SIG_ON_CHIP_ENTRY(2, 6, 2),
+    SIG_ON_CHIP_ENTRY(2, 6, 3),
     SIG_ON_CHIP_ENTRY(3, 6, 3),
     SIG_ON_CHIP_ENTRY(3, 6, 4),
     SIG_ON_CHIP_ENTRY(4, 6, 4),

@@ -281,7 +281,7 @@ def test_small_batches_take_wide_workgroups_for_small_states_with_many_lanes():
         assert rc == binding.SIG_OK and pl.threads == 256, (d, depth)
         rc, pl = binding.sig_plan(None, 128, 100, d, depth, 1)
         assert rc == binding.SIG_OK and pl.threads <= 256, (d, depth)
-    for d, depth in [(4, 6), (3, 5), (6, 4), (7, 4), (10, 4)]:
+    for d, depth in [(4, 6), (3, 5), (4, 5), (7, 4), (10, 4)]:
         rc, pl = binding.sig_plan(None, 128, 100, d, depth, 0)
         assert rc == binding.SIG_OK and pl.threads <= 256, (d, depth)
 
@@ -310,17 +310,26 @@ def test_few_long_paths_with_small_states_are_cut_into_more_segments():
 def test_deeper_prefix_entries_behind_the_first_small_state():
     """(4,4), (5,3), (6,3), (4,3), (7,3), (3,4), (3,5), (2,6) and (3,6) have a prefix depth behind the first one with a small lane state: taken in final mode for
     small batches of short paths only; with 512 threads once the path is long enough for twice the chunks."""
-    for d, depth, p in [(4, 4, 3), (5, 3, 2), (6, 3, 2), (4, 3, 2), (7, 3, 2), (3, 4, 2), (3, 5, 3), (2, 6, 2), (3, 6, 4)]:
+    for d, depth, p in [(4, 4, 3), (5, 3, 2), (6, 3, 2), (4, 3, 2), (7, 3, 2), (3, 4, 3), (3, 5, 3), (2, 6, 3), (3, 6, 4), (3, 3, 2), (2, 4, 2), (2, 5, 2)]:
         assert binding.sig_on_chip_available(d, depth, p)
         for B, L in [(16, 100), (128, 50), (128, 257), (256, 100)]:
             rc, pl = binding.sig_plan(None, B, L, d, depth, 0)
             assert rc == binding.SIG_OK and pl.variant == binding.SIG_VARIANT_ON_CHIP and pl.prefix_depth == p, (d, depth, B, L)
             assert binding.sig_plan_validate(B, L, d, depth, 0, pl) == binding.SIG_OK
         rc, pl = binding.sig_plan(None, 128, 257, d, depth, 0)
-        assert pl.threads == (256 if (d, depth) in [(3, 4), (2, 6)] else 512)
+        assert pl.threads == (256 if d == 2 or (d, depth) == (3, 3) else 512), (d, depth)
         for B, L, stream in [(300, 100, 0), (128, 300, 0), (4096, 100, 0)]:
             rc, pl = binding.sig_plan(None, B, L, d, depth, stream)
-            assert rc == binding.SIG_OK and pl.variant == binding.SIG_VARIANT_ON_CHIP and pl.prefix_depth == p - 1, (d, depth, B, L)
+            assert rc == binding.SIG_OK and pl.variant == binding.SIG_VARIANT_ON_CHIP and pl.prefix_depth < p, (d, depth, B, L)
         for B, L in [(128, 100), (4, 50), (4096, 256)]:
             rc, pl = binding.sig_plan(None, B, L, d, depth, 1)
-            assert rc == binding.SIG_OK and (pl.variant != binding.SIG_VARIANT_ON_CHIP or pl.prefix_depth == p - 1)
+            assert rc == binding.SIG_OK and (pl.variant != binding.SIG_VARIANT_ON_CHIP or pl.prefix_depth < p)
+
+
+def test_six_channels_at_depth_four_take_the_deeper_prefix_only_up_to_128_increments():
+    """(6,4,3) has 216 lanes per path: two chunks in 512 threads, which pays for short paths only."""
+    for B, L, p in [(128, 100, 3), (64, 20, 3), (256, 129, 3), (128, 200, 2), (128, 257, 2), (512, 100, 2)]:
+        rc, pl = binding.sig_plan(None, B, L, 6, 4, 0)
+        assert rc == binding.SIG_OK and pl.variant == binding.SIG_VARIANT_ON_CHIP and pl.prefix_depth == p, (B, L)
+    rc, pl = binding.sig_plan(None, 128, 100, 6, 4, 1)
+    assert rc == binding.SIG_OK and (pl.variant != binding.SIG_VARIANT_ON_CHIP or pl.prefix_depth == 2)

@@ -135,6 +135,14 @@ ON_CHIP_CASES = [
     (3, 5, 3, 128, 100, 8, 1, 0, False), (3, 5, 3, 9, 200, 16, 1, 0, False, 512), (3, 5, 3, 2, 500, 8, 4, 0, False), (3, 5, 3, 4, 27, 2, 1, 0, True),
     (2, 6, 2, 128, 100, 12, 1, 0, False), (2, 6, 2, 7, 257, 32, 1, 0, False), (2, 6, 2, 3, 600, 16, 3, 0, False), (2, 6, 2, 5, 40, 4, 1, 0, True),
     (3, 6, 4, 128, 100, 6, 1, 0, False, 512), (3, 6, 4, 64, 20, 2, 1, 0, False, 512), (3, 6, 4, 2, 300, 3, 4, 0, False), (3, 6, 4, 3, 19, 2, 1, 0, True),
+    # ... and (3,3), (2,4), (3,4) one deeper, (2,5), (2,6) one deeper, (6,4)
+    (3, 3, 2, 128, 100, 12, 1, 0, False), (3, 3, 2, 9, 257, 28, 1, 0, False), (3, 3, 2, 5, 300, 8, 3, 0, False), (3, 3, 2, 7, 33, 4, 1, 0, True),
+    (2, 4, 2, 128, 100, 12, 1, 0, False), (2, 4, 2, 9, 257, 32, 1, 0, False), (2, 4, 2, 5, 300, 8, 3, 0, False), (2, 4, 2, 7, 33, 4, 1, 0, True),
+    (3, 4, 3, 128, 100, 8, 1, 0, False), (3, 4, 3, 9, 257, 16, 1, 0, False, 512), (3, 4, 3, 5, 300, 8, 3, 0, False), (3, 4, 3, 7, 33, 4, 1, 0, True),
+    (2, 5, 2, 128, 100, 12, 1, 0, False), (2, 5, 2, 9, 257, 32, 1, 0, False), (2, 5, 2, 300, 40, 3, 1, 6, False), (2, 5, 2, 7, 33, 4, 1, 0, True),
+    (2, 6, 3, 128, 100, 8, 1, 0, False), (2, 6, 3, 9, 257, 32, 1, 0, False), (2, 6, 3, 5, 300, 8, 3, 0, False), (2, 6, 3, 7, 33, 4, 1, 0, True),
+    (6, 4, 3, 128, 100, 2, 1, 0, False, 512), (6, 4, 3, 64, 20, 1, 1, 0, False), (6, 4, 3, 3, 300, 2, 4, 0, False, 512), (6, 4, 3, 4, 21, 1, 1, 0, True),
+    (6, 4, 3, 50, 64, 1, 1, 5, False),
 ]
 
 
