@@ -283,9 +283,14 @@ const OnChipKernelInfo *pick_on_chip(int d, int depth, int stream_flag, int64_t 
         const int64_t short_path = e->lanes_per_chunk > 128 ? 128 : 256;
         const bool short_and_few = !stream_flag && best->state_floats <= 64 && best->p > 0 && e->lanes_per_chunk < kThreads &&
                                    B * e->lanes_per_chunk * (kThreads / e->lanes_per_chunk) <= (int64_t)cus * 4 * kWave && K <= short_path;
-        // (stream mode, not measured with it, keeps p = 2)
-        const bool final_only = best->p > 0 && best->state_floats <= 64;
-        if (stream_flag && final_only) continue;
+        // Stream mode takes an entry behind the first small state only while that one has fewer than 16 lanes per path:
+        // with so few lanes each writes long stretches of every row ((3,4), 4,096 paths of 256 points: 444 -> 108 us with
+        // 27 lanes instead of 3; (5,3) 293 -> 138; (6,3) 754 -> 222); from 16 lanes on the deeper entry is no faster
+        // ((4,4), (5,4): 0.8-1.0x).  Measured on ten shapes with d = 2 ... 7, 8-4,096 paths of 100-1,000 points: 1.1-4.1x
+        // against the best plan of the shallower entry or the level-scan family, except with four lanes per path on large
+        // batches ((2,5), 1,024 paths or more: 0.6-0.76x), which keep the shallower entry.
+        const bool behind_small = best->p > 0 && best->state_floats <= 64;
+        if (stream_flag && behind_small && (best->lanes_per_chunk >= 16 || (e->lanes_per_chunk < 8 && B > 512))) continue;
         if (stream_flag || best->state_floats > 64 || best->p == 0 || short_and_few) best = e;
     }
     return best;

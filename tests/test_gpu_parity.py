@@ -363,3 +363,13 @@ def test_very_large_batch_sampled(gpu, oracle):
     got = out[torch.from_numpy(pick).cuda()].cpu().numpy()
     want = oracle.signature(x[pick], depth)
     assert max(level_errors(got, want, d, depth)) <= TOL
+
+
+@pytest.mark.parametrize("d,depth", [(5, 3), (3, 4), (6, 3), (4, 3), (7, 3), (3, 3), (2, 4), (2, 5), (2, 6), (3, 5)])
+def test_stream_mode_auto_with_the_deeper_prefix_entries(gpu, oracle, d, depth):
+    """Stream mode takes the entry behind the first small lane state when that one has fewer than 16 lanes per path."""
+    for B, L in [(5, 40), (70, 23), (600, 12)]:
+        rc, pl = gpu.sig_plan(gpu.default_ctx(), B, L, d, depth, 1)
+        assert rc == gpu.SIG_OK
+        x = workloads.brownian_paths(B, L, d, seed=5400 + 13 * B + L + d)
+        check(gpu, oracle, x, depth, True, None, label="auto, stream, plan p=%d c=%d t=%d" % (pl.prefix_depth, pl.chunks, pl.threads))
