@@ -280,7 +280,11 @@ const OnChipKernelInfo *pick_on_chip(int d, int depth, int stream_flag, int64_t 
         // chunks and its segments is as fast or faster)
         // (a deeper kernel with more than 128 lanes per path runs only two chunks in 512 threads and wins up to about
         // 128 increments: (6,4,3) 1.08-1.38x up to 100 points, 0.83-0.91x from 200 on)
-        const int64_t short_path = e->lanes_per_chunk > 128 ? 128 : 256;
+        // Where the shallower entry has fewer than 16 lanes per path or a lane state of 40 floats or more, the deeper one
+        // wins on longer paths as well (measured up to 700 points on (5,3), (6,3), (7,3), (4,3), (3,4), (3,5), (2,6), (3,6):
+        // 1.16-1.9x; (4,4) 0.99-1.06x and (5,4) 0.94-1.2x keep the limit of 256 increments).
+        const bool heavy_shallower = best->lanes_per_chunk < 16 || best->state_floats >= 40;
+        const int64_t short_path = e->lanes_per_chunk > 128 ? 128 : heavy_shallower ? 768 : 256;
         const bool short_and_few = !stream_flag && best->state_floats <= 64 && best->p > 0 && e->lanes_per_chunk < kThreads &&
                                    B * e->lanes_per_chunk * (kThreads / e->lanes_per_chunk) <= (int64_t)cus * 4 * kWave && K <= short_path;
         // Stream mode takes an entry behind the first small state only while that one has fewer than 16 lanes per path:

@@ -318,7 +318,10 @@ def test_deeper_prefix_entries_behind_the_first_small_state():
             assert binding.sig_plan_validate(B, L, d, depth, 0, pl) == binding.SIG_OK
         rc, pl = binding.sig_plan(None, 128, 257, d, depth, 0)
         assert pl.threads == (256 if d == 2 or (d, depth) == (3, 3) else 512), (d, depth)
-        for B, L, stream in [(300, 100, 0), (128, 300, 0), (4096, 100, 0)]:
+        # longer paths: up to 768 increments where the shallower entry has few lanes or a large state, else 256
+        rc, pl = binding.sig_plan(None, 128, 500, d, depth, 0)
+        assert rc == binding.SIG_OK and (pl.prefix_depth == p) == ((d, depth) != (4, 4)), (d, depth)
+        for B, L, stream in [(300, 100, 0), (128, 1000, 0), (4096, 100, 0)]:
             rc, pl = binding.sig_plan(None, B, L, d, depth, stream)
             assert rc == binding.SIG_OK and pl.variant == binding.SIG_VARIANT_ON_CHIP and pl.prefix_depth < p, (d, depth, B, L)
         # stream mode takes them only behind an entry with fewer than 16 lanes per path (and with four lanes per path
