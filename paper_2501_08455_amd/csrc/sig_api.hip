@@ -285,8 +285,12 @@ const OnChipKernelInfo *pick_on_chip(int d, int depth, int stream_flag, int64_t 
         // 1.16-1.9x; (4,4) 0.99-1.06x and (5,4) 0.94-1.2x keep the limit of 256 increments).
         const bool heavy_shallower = best->lanes_per_chunk < 16 || best->state_floats >= 40;
         const int64_t short_path = e->lanes_per_chunk > 128 ? 128 : heavy_shallower ? 768 : 256;
+        // ... and on batches four times larger where the shallower entry has fewer than 16 lanes per path (1,024 paths of
+        // 100 points: 1.3-1.7x on (3,4), (5,3), (6,3), (7,3), (2,6), (3,5), (4,3); a tie at 8,192 paths, and from 32,768 on
+        // the shallower entry wins except on (3,4) and (2,6); (3,6), (4,4) and (5,4) lose already at 1,024)
+        const int64_t few_lanes = (int64_t)cus * 4 * kWave * (best->lanes_per_chunk < 16 ? 4 : 1);
         const bool short_and_few = !stream_flag && best->state_floats <= 64 && best->p > 0 && e->lanes_per_chunk < kThreads &&
-                                   B * e->lanes_per_chunk * (kThreads / e->lanes_per_chunk) <= (int64_t)cus * 4 * kWave && K <= short_path;
+                                   B * e->lanes_per_chunk * (kThreads / e->lanes_per_chunk) <= few_lanes && K <= short_path;
         // Stream mode takes an entry behind the first small state only while that one has fewer than 16 lanes per path:
         // with so few lanes each writes long stretches of every row ((3,4), 4,096 paths of 256 points: 444 -> 108 us with
         // 27 lanes instead of 3; (5,3) 293 -> 138; (6,3) 754 -> 222); from 16 lanes on the deeper entry is no faster

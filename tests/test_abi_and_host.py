@@ -321,7 +321,10 @@ def test_deeper_prefix_entries_behind_the_first_small_state():
         # longer paths: up to 768 increments where the shallower entry has few lanes or a large state, else 256
         rc, pl = binding.sig_plan(None, 128, 500, d, depth, 0)
         assert rc == binding.SIG_OK and (pl.prefix_depth == p) == ((d, depth) != (4, 4)), (d, depth)
-        for B, L, stream in [(300, 100, 0), (128, 1000, 0), (4096, 100, 0)]:
+        # larger batches: four times as many paths where the shallower entry has fewer than 16 lanes per path
+        rc, pl = binding.sig_plan(None, 1000, 100, d, depth, 0)
+        assert rc == binding.SIG_OK and (pl.prefix_depth == p) == ((d, depth) not in [(4, 4), (3, 6)]), (d, depth)
+        for B, L, stream in [(2000, 100, 0), (128, 1000, 0), (4096, 100, 0)]:
             rc, pl = binding.sig_plan(None, B, L, d, depth, stream)
             assert rc == binding.SIG_OK and pl.variant == binding.SIG_VARIANT_ON_CHIP and pl.prefix_depth < p, (d, depth, B, L)
         # stream mode takes them only behind an entry with fewer than 16 lanes per path (and with four lanes per path
