@@ -329,7 +329,9 @@ int plan_auto(const sig_ctx *ctx, int64_t B, int64_t L, int stream_flag, const R
     if (ki) {
         // a large lane state leaves room for fewer wavefronts per SIMD: do not cut time to fill slots that the
         // registers cannot hold (estimate: state + 45 registers per lane, 512 per SIMD lane)
-        if (!stream_flag && ki->state_floats > 64) {
+        // (also for kernels with fewer than 16 lanes per path, whose states of 31-63 floats leave room for four to six:
+        // 8,192 paths of 100 points took nine to twelve chunks where four are 1.15-1.45x faster)
+        if (!stream_flag && (ki->state_floats > 64 || (ki->lanes_per_chunk < 16 && ki->state_floats >= 31))) {
             int by_vgpr = 512 / (ki->state_floats + 45);
             if (by_vgpr < 1) by_vgpr = 1;
             if (by_vgpr < 8) want_lanes = (int64_t)cus * 4 * kWave * by_vgpr;
@@ -370,7 +372,9 @@ int plan_auto(const sig_ctx *ctx, int64_t B, int64_t L, int stream_flag, const R
             // (stream kernels fold every chunk twice and are bound by the sequential steps, not by the scan over
             // the chunk signatures: chunks of four steps measured 1.15-1.9x faster than eight on small lane states)
             // (and three steps on states of at most 16 floats: another 1.1-1.45x on d = 2, 3, 5 at depth 2-4)
-            const int64_t min_steps = !stream_flag ? kMinChunkSteps : ki->state_floats <= 16 ? 3 : ki->state_floats <= 32 ? 4 : kMinChunkSteps;
+            // (final mode, few-lane kernels with states of 31-63 floats: their chunk tree multiplies long rows with few
+            // lanes, and chunks of at least twelve steps measured best on 2,048-8,192 paths of 100 points: 1.2-1.6x)
+            const int64_t min_steps = !stream_flag ? ((Q < 16 && ki->state_floats >= 31 && ki->state_floats <= 64) ? 12 : kMinChunkSteps) : ki->state_floats <= 16 ? 3 : ki->state_floats <= 32 ? 4 : kMinChunkSteps;
             if (cmax > K / min_steps) cmax = K / min_steps;
             if (cmax < 1) cmax = 1;
             int64_t C = pieces < cmax ? pieces : cmax;
