@@ -19,7 +19,11 @@
  *     it alive until the HIP stream has passed the call;
  *   - `hip_stream` is a hipStream_t passed as void* (NULL = the default
  *     stream), so that this header needs no HIP include.  All work is enqueued
- *     on it and the call returns without synchronising;
+ *     on it and the call returns without synchronising -- with one exception:
+ *     a call that needs more context scratch than any earlier call on the
+ *     context waits for the device, frees the old buffer and allocates a larger
+ *     one (callers that must not allocate or wait size the scratch with one
+ *     eager call of the largest shape first, or use sig_compute_noalloc);
  *   - nothing is thrown, printed or aborted across this boundary: every
  *     failure is a return code (enum below) and leaves `out` unspecified;
  *   - a context owns reusable device scratch, so one context serves one stream
@@ -127,6 +131,22 @@ void sig_destroy(sig_ctx *ctx);
  */
 int sig_compute(sig_ctx *ctx, const float *path, int64_t B, int64_t L, int d, int depth,
                 int stream_flag, float *out, void *hip_stream);
+
+/*
+ * sig_compute for callers that cannot allocate device memory: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same arguments, same mapping, same kernels and the same results
+ * as sig_compute, but the scratch that some mappings need (partial signatures of time segments that a second
+ * launch joins; the lower-level tensors of the level-scan family in final mode) is a fixed array of
+ * SIG_NOALLOC_SCRATCH_BYTES that is part of the library's code object: every GPU the library runs on holds
+ * it from the library's first use until the process ends.  The call allocates and frees nothing and never
+ * waits for the device.  A shape whose mapping needs more scratch than that is refused with
+ * SIG_ERR_TOO_LARGE and nothing is launched (sig_compute takes such shapes).  All contexts of one GPU share
+ * the array: calls that overlap in time on one GPU (different streams, different contexts) race on it;
+ * calls ordered by one stream do not.  Nothing in it has to start at zero: every call writes what it reads.
+ */
+#define SIG_NOALLOC_SCRATCH_BYTES (16 * 1024 * 1024)
+int sig_compute_noalloc(sig_ctx *ctx, const float *path, int64_t B, int64_t L, int d, int depth,
+                        int stream_flag, float *out, void *hip_stream);
 
 /*
  * The mapping sig_compute would use for this shape (one remembered by sig_autotune for exactly this shape, else the

@@ -18,6 +18,7 @@ SIG_ERR_HIP = 4
 SIG_ERR_NO_DEVICE = 5
 
 SIG_ERR_UNSUPPORTED = 6
+SIG_NOALLOC_SCRATCH_BYTES = 16 * 1024 * 1024
 SIG_VARIANT_AUTO = 0
 SIG_VARIANT_HBM_STREAMING = 1
 SIG_VARIANT_ON_CHIP = 2
@@ -67,6 +68,8 @@ def load():
     lib.sig_destroy.argtypes = [vp]
     lib.sig_compute.restype = i32
     lib.sig_compute.argtypes = [vp, vp, i64, i64, i32, i32, i32, vp, vp]
+    lib.sig_compute_noalloc.restype = i32
+    lib.sig_compute_noalloc.argtypes = [vp, vp, i64, i64, i32, i32, i32, vp, vp]
     lib.sig_plan.restype = i32
     lib.sig_plan.argtypes = [vp, i64, i64, i32, i32, i32, ctypes.POINTER(sig_plan_t)]
     lib.sig_autotune.restype = i32
@@ -170,6 +173,13 @@ def sig_compute(ctx, path, depth, stream_flag, out, stream=None, plan=None):
     if plan is None:
         return load().sig_compute(*args, _stream_handle(stream))
     return load().sig_compute_planned(*args, ctypes.byref(plan), _stream_handle(stream))
+
+
+def sig_compute_noalloc(ctx, path, depth, stream_flag, out, stream=None):
+    """Raw call of the entry point that allocates nothing (fixed scratch inside the library).  Returns the status."""
+    B, L, d = path.shape
+    return load().sig_compute_noalloc(ctx, ctypes.c_void_p(path.data_ptr()), B, L, d, int(depth), int(stream_flag),
+                                      ctypes.c_void_p(out.data_ptr()), _stream_handle(stream))
 
 
 def bind_compute(ctx, path, depth, stream_flag, out, stream=None, plan=None):

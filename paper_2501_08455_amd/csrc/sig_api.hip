@@ -19,10 +19,18 @@ struct sig_ctx {
     int num_cu;
     float *scratch;        // partial signatures of time segments, [B][segments][D]
     size_t scratch_bytes;
+    float *fixed_scratch;  // this device's copy of the file-scope array below (sig_compute_noalloc)
     TunedPlan tuned[64];   // filled by sig_autotune, consulted by sig_compute and sig_plan (oldest overwritten)
     int tuned_count;
     int tuned_next;
 };
+
+// Scratch of sig_compute_noalloc, the entry point for callers that cannot allocate: part of the code object, so
+// every device the library runs on holds its own copy from the first use of the library until the process ends.
+// In host code the name only stands for the symbol; its device address is looked up once per context
+// (hipGetSymbolAddress in sig_create, with the context's device current) and kept in sig_ctx::fixed_scratch.
+constexpr size_t kFixedScratchBytes = (size_t)SIG_NOALLOC_SCRATCH_BYTES;
+static __device__ __align__(256) float fixed_scratch_storage[kFixedScratchBytes / sizeof(float)];
 
 namespace {
 
@@ -597,8 +605,22 @@ int ensure_scratch(sig_ctx *ctx, size_t bytes)
     return SIG_OK;
 }
 
+// Scratch of `bytes` for one call: the context's own buffer, grown on demand, or (fixed) the array that is part of
+// the code object, which is never grown: a call that needs more is refused.
+int get_scratch(sig_ctx *ctx, bool fixed, size_t bytes, float **p)
+{
+    if (fixed) {
+        if (bytes > kFixedScratchBytes) return SIG_ERR_TOO_LARGE;
+        *p = ctx->fixed_scratch;
+        return SIG_OK;
+    }
+    const int rc = ensure_scratch(ctx, bytes);
+    *p = ctx->scratch;
+    return rc;
+}
+
 int run_plan(sig_ctx *ctx, const float *path, int64_t B, int64_t L, const RowShape &rs, int stream_flag,
-             float *out, const sig_plan_t &pl, hipStream_t st)
+             float *out, const sig_plan_t &pl, hipStream_t st, bool fixed = false)
 {
     if (pl.variant == SIG_VARIANT_HBM_STREAMING) {
         if (pl.prefix_depth < 0 || pl.prefix_depth > rs.depth - 1) return SIG_ERR_INVALID;
@@ -612,11 +634,12 @@ int run_plan(sig_ctx *ctx, const float *path, int64_t B, int64_t L, const RowSha
         int rc = check_level_scan(B, L, rs, stream_flag, pl);
         if (rc != SIG_OK) return rc;
         const int64_t floats = level_scan_scratch_floats(B, L, rs, stream_flag);
+        float *work = nullptr;
         if (floats > 0) {
-            rc = ensure_scratch(ctx, (size_t)floats * sizeof(float));
+            rc = get_scratch(ctx, fixed, (size_t)floats * sizeof(float), &work);
             if (rc != SIG_OK) return rc;
         }
-        hipError_t e = launch_level_scan(path, out, ctx->scratch, B, L, rs, stream_flag, pl.chunks, ctx->num_cu, st);
+        hipError_t e = launch_level_scan(path, out, work, B, L, rs, stream_flag, pl.chunks, ctx->num_cu, st);
         return e == hipSuccess ? SIG_OK : SIG_ERR_HIP;
     }
     if (pl.variant != SIG_VARIANT_ON_CHIP) return SIG_ERR_INVALID;
@@ -629,21 +652,22 @@ int run_plan(sig_ctx *ctx, const float *path, int64_t B, int64_t L, const RowSha
     args.partial = nullptr;
     const bool lds_join = pl.segments > 1 && join_fits_lds(ki, pl.segments, rs);
     const size_t rows = (size_t)B * pl.segments * rs.D;   // floats of the partial rows
+    float *work = nullptr;
     if (pl.segments > 1) {
         // (the tree in device memory ping-pongs between two more buffers of half and a quarter of the rows)
-        int rc = ensure_scratch(ctx, (lds_join ? rows : rows + rows / 2 + rows / 4 + 4) * sizeof(float));
+        int rc = get_scratch(ctx, fixed, (lds_join ? rows : rows + rows / 2 + rows / 4 + 4) * sizeof(float), &work);
         if (rc != SIG_OK) return rc;
-        args.partial = ctx->scratch;
+        args.partial = work;
     }
     hipError_t e = ki->launch(args, st);
     if (e != hipSuccess) return SIG_ERR_HIP;
     if (lds_join) {
-        e = ki->join(ctx->scratch, out, B, pl.segments, st);
+        e = ki->join(work, out, B, pl.segments, st);
         if (e != hipSuccess) return SIG_ERR_HIP;
     } else if (pl.segments > 1) {
         // round r joins neighbours: row 2 i (x) row 2 i + 1 of the previous round's rows, the last round into `out`
-        const float *in = ctx->scratch;
-        float *buf[2] = {ctx->scratch + rows, ctx->scratch + rows + rows / 2};
+        const float *in = work;
+        float *buf[2] = {work + rows, work + rows + rows / 2};
         int which = 0;
         for (int64_t n = pl.segments; n > 1; n /= 2) {
             float *dst = n == 2 ? out : buf[which];
@@ -693,6 +717,14 @@ int sig_create(sig_ctx **ctx)
     c->num_cu = cus;
     c->scratch = nullptr;
     c->scratch_bytes = 0;
+    // the address of this device's copy of the fixed scratch array (the current device is the context's)
+    void *fixed = nullptr;
+    if (hipGetSymbolAddress(&fixed, HIP_SYMBOL(fixed_scratch_storage)) != hipSuccess || !fixed) {
+        (void)hipGetLastError();
+        delete c;
+        return SIG_ERR_HIP;
+    }
+    c->fixed_scratch = static_cast<float *>(fixed);
     c->tuned_count = 0;
     c->tuned_next = 0;
     *ctx = c;
@@ -764,6 +796,21 @@ int sig_compute(sig_ctx *ctx, const float *path, int64_t B, int64_t L, int d, in
     rc = plan_for(ctx, B, L, stream_flag, rs, &pl);
     if (rc != SIG_OK) return rc;
     return run_plan(ctx, path, B, L, rs, stream_flag, out, pl, static_cast<hipStream_t>(hip_stream));
+}
+
+int sig_compute_noalloc(sig_ctx *ctx, const float *path, int64_t B, int64_t L, int d, int depth,
+                        int stream_flag, float *out, void *hip_stream)
+{
+    if (!ctx) return SIG_ERR_INVALID;
+    RowShape rs;
+    int rc = check_shape(B, L, d, depth, stream_flag, &rs);
+    if (rc != SIG_OK) return rc;
+    if (B == 0) return SIG_OK;
+    if (!path || !out) return SIG_ERR_INVALID;
+    sig_plan_t pl;
+    rc = plan_for(ctx, B, L, stream_flag, rs, &pl);
+    if (rc != SIG_OK) return rc;
+    return run_plan(ctx, path, B, L, rs, stream_flag, out, pl, static_cast<hipStream_t>(hip_stream), true);
 }
 
 int sig_autotune(sig_ctx *ctx, int64_t B, int64_t L, int d, int depth, int stream_flag, sig_plan_t *chosen,

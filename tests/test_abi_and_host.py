@@ -24,7 +24,7 @@ def test_library_exports_every_declared_symbol():
     names = declared_functions()
     assert {"sig_create", "sig_compute", "sig_destroy", "sig_size", "sig_plan", "sig_compute_planned",
             "sig_combine", "sig_strerror", "sig_on_chip_available", "sig_plan_validate", "sig_autotune",
-            "sig_probe_copy", "sig_probe_fma"} <= set(names)
+            "sig_probe_copy", "sig_probe_fma", "sig_compute_noalloc"} <= set(names)
     for name in names:
         assert hasattr(lib, name), name
 
