@@ -1,8 +1,14 @@
 """GPU parity of sig_backward (through the C ABI binding) against the fp64 gradient oracle.
 
-Gate: ||gpu - oracle||_F / ||oracle||_F <= 1e-4 over the whole gradient of a call and over every channel of
-it (the tolerance of the forward transform, applied to the gradient: the kernel's extra error source, undoing
-one increment at a time in fp32, stays far below it for these path lengths).
+Gates, all at 1e-4 (the tolerance of the forward transform, applied to the gradient: the kernel's extra error
+source, undoing one increment at a time in fp32, stays far below it for these path lengths):
+  ||gpu - oracle||_F / ||oracle||_F over the whole gradient of a call, over every channel of it, and over the
+  gradient of every single path (so that one wrong path cannot hide in a large batch);
+  |gpu - oracle| <= 1e-4 x max|oracle| for every entry, at depths up to 8 (all compiled kernels; beyond that the
+  sweep's reconstruction of early prefixes in fp32, S_{k-1} = S_k (x) exp(-dX_k), loses the tiny top levels of the
+  first few prefixes -- relative errors above 1 at level 9 of a 22-increment path -- which the norm gates absorb but
+  single entries of the gradient at the first points of a path do not: measured 1.35e-4 on (d, depth) = (2, 10)).
+grad_path is poisoned with NaN before every call.
 """
 import sys
 
@@ -49,7 +55,7 @@ def run_backward(gpu, x, depth, stream, g):
     return rc, gx.cpu().numpy()
 
 
-def check(gpu, oracle, x, depth, stream, seed, label=""):
+def check(gpu, oracle, x, depth, stream, seed, label="", entry_gate=True):
     B, L, d = x.shape
     say("backward case %s shape=%s depth=%d stream=%s" % (label, x.shape, depth, stream))
     rng = np.random.default_rng(seed)
@@ -59,12 +65,24 @@ def check(gpu, oracle, x, depth, stream, seed, label=""):
     rc, got = run_backward(gpu, x, depth, stream, g)
     assert rc == gpu.SIG_OK, rc
     want = oracle.signature_backward(x, depth, g, stream=stream)
+    assert_gradient_parity(got, want, entry_gate)
+    return got
+
+
+def assert_gradient_parity(got, want, entry_gate=True):
+    """The gates of the module docstring on gradients of shape [paths][points][channels]."""
     assert got.shape == want.shape and np.all(np.isfinite(got))
+    d = want.shape[-1]
+    got = np.asarray(got, dtype=np.float64)
     err = np.linalg.norm(got - want) / np.linalg.norm(want)
     per_channel = [np.linalg.norm(got[..., a] - want[..., a]) / np.linalg.norm(want[..., a]) for a in range(d)]
-    say("  rel err %.2e, worst channel %.2e" % (err, max(per_channel)))
-    assert err <= TOL and max(per_channel) <= TOL
-    return got
+    num = np.sqrt(((got - want) ** 2).sum(axis=(1, 2)))
+    den = np.sqrt((want ** 2).sum(axis=(1, 2)))
+    per_path = np.where(den > 1e-30, num / np.maximum(den, 1e-30), num)
+    elem = np.max(np.abs(got - want)) / np.max(np.abs(want))
+    say("  rel err %.2e, worst channel %.2e, worst path %.2e (path %d), worst entry / max %.2e"
+        % (err, max(per_channel), per_path.max(), int(per_path.argmax()), elem))
+    assert err <= TOL and max(per_channel) <= TOL and per_path.max() <= TOL and (elem <= TOL or not entry_gate)
 
 
 CASES = [
@@ -170,7 +188,7 @@ def test_backward_general_sweep(gpu, oracle, shape):
     assert gpu.sig_backward_available(d, depth) == 0
     for B, L, stream in [(3, 23, False), (17, 5, False), (2, 11, True), (2, 2, False), (1, 2, True)]:
         x = workloads.brownian_paths(B, L, d, seed=8200 + 13 * d + depth + B)
-        check(gpu, oracle, x, depth, stream, seed=d + depth + L, label="general sweep")
+        check(gpu, oracle, x, depth, stream, seed=d + depth + L, label="general sweep", entry_gate=depth <= 8)
 
 
 def test_backward_paths_too_long_for_one_workgroup(gpu, oracle):
@@ -204,10 +222,10 @@ def test_backward_walks_long_paths_in_tiles(gpu, oracle, case):
     g[:keep] = upstream(np.random.default_rng(L), keep, L - 1, d, depth)
     rc, got = run_backward(gpu, x, depth, True, g)
     assert rc == gpu.SIG_OK and np.all(np.isfinite(got))
-    want = oracle.signature_backward(x[:keep + 1], depth, g[:keep + 1], stream=True)
-    err = np.linalg.norm(got[:keep + 1] - want) / np.linalg.norm(want)
-    say("  tiled sweep, %d paths: rel err of the first %d %.2e" % (B, keep + 1, err))
-    assert err <= TOL and not np.any(got[keep:])
+    want = oracle.signature_backward(x[:keep], depth, g[:keep], stream=True)
+    say("  tiled sweep, %d paths, the first %d:" % (B, keep))
+    assert_gradient_parity(got[:keep], want)
+    assert not np.any(got[keep:])
 
 
 STREAM_SEGMENTED_CASES = [
@@ -242,6 +260,41 @@ def test_backward_on_the_configurations(gpu, oracle):
     check(gpu, oracle, x, cfg.depth, cfg.stream, seed=32, label="C5, first path")
 
 
+def sampled_backward(gpu, oracle, x, depth, stream, pick, seed):
+    """sig_backward on the whole batch `x` (upstream gradient drawn on the device), the oracle on the paths `pick`."""
+    import torch
+    xt = torch.from_numpy(x).cuda()
+    out = gpu.signature(xt, depth, stream=stream)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(seed)
+    gt = torch.randn(out.shape, dtype=torch.float32, device="cuda", generator=gen)
+    gx = torch.full(x.shape, float("nan"), dtype=torch.float32, device="cuda")
+    assert gpu.sig_backward(gpu.default_ctx(), xt, depth, int(stream), out, gt, gx) == gpu.SIG_OK
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(gx).all())       # the gradient of every path of the batch was written
+    idx = torch.from_numpy(np.asarray(pick)).cuda()
+    want = oracle.signature_backward(x[pick], depth, gt[idx].cpu().numpy(), stream=stream)
+    assert_gradient_parity(gx[idx].cpu().numpy(), want)
+
+
+def test_backward_large_signature_at_the_benchmark_batch(gpu, oracle):
+    """The large-signature configuration at its full batch of 16 (what bench.py times), the oracle on the first and
+    the last path."""
+    cfg = workloads.CONFIGS["C5"]
+    x = workloads.make_paths(cfg)
+    say("backward case C5, B=%d, oracle on paths 0 and %d" % (x.shape[0], x.shape[0] - 1))
+    sampled_backward(gpu, oracle, x, cfg.depth, cfg.stream, [0, x.shape[0] - 1], seed=33)
+
+
+def test_backward_length_scaling_configuration_at_the_benchmark_batch(gpu, oracle):
+    """128 paths of 2,000 points (the sweep is cut into time segments across workgroups), the oracle on eight paths."""
+    cfg = workloads.CONFIGS["C3"]
+    x = workloads.make_paths(cfg)
+    pick = [0, 1, 17, 63, 64, 100, 126, 127]
+    say("backward case C3 literal, B=%d, oracle on paths %s" % (x.shape[0], pick))
+    sampled_backward(gpu, oracle, x, cfg.depth, cfg.stream, pick, seed=34)
+
+
 def test_backward_repeated_points_and_reproducible(gpu, oracle):
     x = workloads.brownian_paths(9, 30, 5, seed=12)
     x[:, 7] = x[:, 6]
@@ -269,7 +322,8 @@ def test_backward_status_codes(gpu):
 
 
 def test_autograd_wrapper(gpu, oracle):
-    """torch.autograd through the layer: Dense -> signature -> weighted sum, gradients against the oracle."""
+    """torch.autograd through the layer alone: signature -> weighted sum, the gradient with respect to the path
+    against the oracle (the full Dense -> signature -> Dense step is tests/test_gpu_training_step.py)."""
     import torch
     from paper_2501_08455_amd import autograd
     rng = np.random.default_rng(41)
@@ -281,8 +335,7 @@ def test_autograd_wrapper(gpu, oracle):
         (sig * torch.from_numpy(w).cuda()).sum().backward()
         torch.cuda.synchronize()
         want = oracle.signature_backward(x, 4, w, stream=stream)
-        got = xt.grad.cpu().numpy()
-        assert np.linalg.norm(got - want) / np.linalg.norm(want) <= TOL
+        assert_gradient_parity(xt.grad.cpu().numpy(), want)
 
 
 @pytest.mark.parametrize("name,B", [("C2", 65536), ("C4", 4096)])
@@ -292,20 +345,7 @@ def test_backward_saturated_variants_sampled(gpu, oracle, name, B):
     cfg = workloads.CONFIGS[name]
     x = workloads.make_paths(cfg, B=B, seed=98)
     say("backward case %s-sat B=%d" % (name, B))
-    xt = torch.from_numpy(x).cuda()
-    out = gpu.signature(xt, cfg.depth, stream=cfg.stream)
-    gen = torch.Generator(device="cuda")
-    gen.manual_seed(3)
-    gt = torch.randn(out.shape, dtype=torch.float32, device="cuda", generator=gen)
-    gx = torch.empty_like(xt)
-    assert gpu.sig_backward(gpu.default_ctx(), xt, cfg.depth, int(cfg.stream), out, gt, gx) == gpu.SIG_OK
-    torch.cuda.synchronize()
     rng = np.random.default_rng(6)
     pick = np.sort(rng.choice(B, size=64, replace=False))
     pick[0], pick[-1] = 0, B - 1
-    idx = torch.from_numpy(pick).cuda()
-    want = oracle.signature_backward(x[pick], cfg.depth, gt[idx].cpu().numpy(), stream=cfg.stream)
-    got = gx[idx].cpu().numpy()
-    err = np.linalg.norm(got - want) / np.linalg.norm(want)
-    say("  rel err %.2e" % err)
-    assert err <= TOL
+    sampled_backward(gpu, oracle, x, cfg.depth, cfg.stream, pick, seed=3)

@@ -1,7 +1,18 @@
 """GPU parity: libsig (through the C ABI binding) against the fp64 oracle, element by element.
 
-Gate (per level n): ||gpu_n - oracle_n||_F / ||oracle_n||_F <= 1e-4, the norm taken over
-every emitted row of the call.  A stricter per-row figure is printed for information.
+Gates, per level n of the output rows (Eq. 10), all at the stated tolerance 1e-4:
+  aggregate  ||gpu_n - oracle_n||_F / ||oracle_n||_F over every emitted row of the call (the stated metric);
+  per row    the same ratio for every single row (B rows, or B x (L-1) in stream mode), so that one wrong or
+             stale row cannot hide among thousands of right ones; rows whose oracle norm is below 1e-30
+             (repeated points: an exactly zero signature) are compared absolutely;
+  element    |gpu - oracle| <= 1e-4 x max|oracle_n| over the call, for every coefficient.
+Rows of a path that has come back towards its start have a small level-n norm that still carries the rounding
+error of the earlier, larger prefixes; the per-row figure therefore divides by max(||oracle row||, r^n / n!) with r
+the largest distance of the row's prefix from its first point (what level n reaches along a straight path of that
+extent; computed from the input alone, and small for the early rows of a stream, which stay strictly gated).
+The aggregate over these row scales is also held to a bound derived from the arithmetic (fp32 unit roundoff
+u = 2^-24, K increments folded one after the other: 20 u sqrt(K), at most 1e-4); measured: at most 2.8 u sqrt(K).
+Outputs are poisoned with NaN before the call, so a coefficient the kernels never write fails the finiteness check.
 """
 import sys
 
@@ -13,6 +24,7 @@ from paper_2501_08455_amd import workloads
 pytestmark = pytest.mark.gpu
 
 TOL = 1e-4
+UNIT_ROUNDOFF = 2.0 ** -24
 
 
 @pytest.fixture(scope="module")
@@ -43,24 +55,80 @@ def level_errors(got, want, d, depth):
     return errs
 
 
+def row_scales(x, depth, stream):
+    """Per emitted row and level n: r^n / n! with r the largest distance of the row's prefix of the path from its
+    first point, the size level n reaches somewhere along a straight path of that extent.  A row whose level-n
+    norm lies far below this has come back towards its start; the rounding error of its earlier, larger prefixes
+    remains in it, so its error is measured against this scale rather than against its own small norm."""
+    x = np.asarray(x, dtype=np.float64)
+    r = np.maximum.accumulate(np.linalg.norm(x[:, 1:] - x[:, :1], axis=2), axis=1)   # [B][K]
+    r = r if stream else r[:, -1:]
+    fact = np.cumprod(np.arange(1, depth + 1, dtype=np.float64))
+    return np.stack([r.reshape(-1) ** n / fact[n - 1] for n in range(1, depth + 1)], axis=1)   # [rows][depth]
+
+
+def row_and_element_errors(got, want, d, depth, scales):
+    """Per level: (worst per-row relative error, its row, worst |difference| over max|oracle| of the level,
+    aggregate error over the rows' norms or scales, whichever is larger)."""
+    got = np.asarray(got, dtype=np.float64).reshape(-1, got.shape[-1])
+    want = want.reshape(-1, want.shape[-1])
+    res, start = [], 0
+    for n in range(1, depth + 1):
+        sl = slice(start, start + d ** n)
+        diff = got[:, sl] - want[:, sl]
+        num = np.sqrt(np.einsum("ij,ij->i", diff, diff))
+        den = np.maximum(np.sqrt(np.einsum("ij,ij->i", want[:, sl], want[:, sl])), scales[:, n - 1])
+        rel = np.where(den > 1e-30, num / np.maximum(den, 1e-30), num)
+        worst = int(np.argmax(rel))
+        top = float(np.max(np.abs(want[:, sl])))
+        elem = float(np.max(np.abs(diff))) / top if top > 0 else float(np.max(np.abs(diff)))
+        agg = float(np.linalg.norm(num)) / max(float(np.linalg.norm(den)), 1e-30)
+        res.append((float(rel[worst]), worst, elem, agg))
+        start += d ** n
+    return res
+
+
+def aggregate_bound(K):
+    """What fp32 arithmetic allows the aggregate figure: 20 u sqrt(K) for K increments, never above the stated 1e-4."""
+    return min(TOL, 20.0 * UNIT_ROUNDOFF * np.sqrt(max(K, 1)))
+
+
+def assert_parity(got, want, x, depth, stream, arithmetic_bound=True):
+    """The gates of the module docstring; `x` is the batch of paths the rows of `got` and `want` belong to.
+    arithmetic_bound=False leaves out the bound derived from the arithmetic (the level-by-level family on one
+    channel: its sums over time add terms of both signs that are larger than their total)."""
+    d, K = x.shape[2], x.shape[1] - 1
+    assert got.shape == want.shape
+    assert np.all(np.isfinite(got))
+    errs = level_errors(got, want, d, depth)
+    rows = row_and_element_errors(got, want, d, depth, row_scales(x, depth, stream))
+    say("  per-level rel err: " + " ".join("%.2e" % e for e in errs))
+    say("  worst row (rel err @ row): " + " ".join("%.2e@%d" % (r[0], r[1]) for r in rows) +
+        " | worst element / max: " + " ".join("%.2e" % r[2] for r in rows) +
+        " | aggregate over row scales: " + " ".join("%.2e" % r[3] for r in rows) + " bound %.2e" % aggregate_bound(K))
+    assert max(errs) <= TOL, errs
+    assert max(r[0] for r in rows) <= TOL, rows
+    assert max(r[2] for r in rows) <= TOL, rows
+    assert not arithmetic_bound or max(r[3] for r in rows) <= aggregate_bound(K), (rows, aggregate_bound(K))
+
+
 def run_gpu(gpu, x, depth, stream, plan=None):
     import torch
     xt = torch.from_numpy(x).cuda()
-    out = gpu.signature(xt, depth, stream=stream, plan=plan)
+    B, L, d = x.shape
+    D = gpu.sig_size(d, depth)
+    out = torch.full((B, L - 1, D) if stream else (B, D), float("nan"), dtype=torch.float32, device="cuda")
+    out = gpu.signature(xt, depth, stream=stream, plan=plan, out=out)
     torch.cuda.synchronize()
     return out.cpu().numpy()
 
 
-def check(gpu, oracle, x, depth, stream, plan=None, label=""):
+def check(gpu, oracle, x, depth, stream, plan=None, label="", arithmetic_bound=True):
     say("case %s shape=%s depth=%d stream=%s plan=%s" % (label, x.shape, depth, stream,
                                                         plan.as_dict() if plan is not None else "auto"))
     got = run_gpu(gpu, x, depth, stream, plan)
     want = oracle.signature(x, depth, stream=stream)
-    assert got.shape == want.shape
-    assert np.all(np.isfinite(got))
-    errs = level_errors(got, want, x.shape[2], depth)
-    say("  per-level rel err: " + " ".join("%.2e" % e for e in errs))
-    assert max(errs) <= TOL, errs
+    assert_parity(got, want, x, depth, stream, arithmetic_bound)
     return got
 
 
@@ -333,16 +401,17 @@ def test_saturated_variants_sampled(gpu, oracle, name, B):
     x = workloads.make_paths(cfg, B=B, seed=99)
     say("case %s-sat B=%d" % (name, B))
     xt = torch.from_numpy(x).cuda()
-    out = gpu.signature(xt, cfg.depth, stream=cfg.stream)
+    D = gpu.sig_size(cfg.d, cfg.depth)
+    out = torch.full((B, cfg.L - 1, D) if cfg.stream else (B, D), float("nan"), dtype=torch.float32, device="cuda")
+    gpu.signature(xt, cfg.depth, stream=cfg.stream, out=out)
     torch.cuda.synchronize()
+    assert bool(torch.isfinite(out).all())      # every row of the whole batch was written
     rng = np.random.default_rng(5)
     pick = np.sort(rng.choice(B, size=128, replace=False))
     pick[0], pick[-1] = 0, B - 1
     got = out[torch.from_numpy(pick).cuda()].cpu().numpy()
     want = oracle.signature(x[pick], cfg.depth, stream=cfg.stream)
-    errs = level_errors(got, want, cfg.d, cfg.depth)
-    say("  per-level rel err: " + " ".join("%.2e" % e for e in errs))
-    assert max(errs) <= TOL
+    assert_parity(got, want, x[pick], cfg.depth, cfg.stream)
 
 
 # ---------------------------------------------------------------- long paths and very large batches
@@ -357,12 +426,15 @@ def test_very_large_batch_sampled(gpu, oracle):
     import torch
     B, L, d, depth = 1 << 21, 3, 2, 3
     x = workloads.brownian_paths(B, L, d, seed=17)
-    out = gpu.signature(torch.from_numpy(x).cuda(), depth)
+    out = torch.full((B, gpu.sig_size(d, depth)), float("nan"), dtype=torch.float32, device="cuda")
+    gpu.signature(torch.from_numpy(x).cuda(), depth, out=out)
     torch.cuda.synchronize()
-    pick = np.array([0, 1, 255, 256, 65535, 65536, B // 2, B - 2, B - 1])
+    assert bool(torch.isfinite(out).all())
+    pick = np.concatenate([np.array([0, 1, 255, 256, 65535, 65536, B // 2, B - 2, B - 1]),
+                           np.random.default_rng(6).choice(B, size=247, replace=False)])
     got = out[torch.from_numpy(pick).cuda()].cpu().numpy()
     want = oracle.signature(x[pick], depth)
-    assert max(level_errors(got, want, d, depth)) <= TOL
+    assert_parity(got, want, x[pick], depth, False)
 
 
 @pytest.mark.parametrize("d,depth", [(5, 3), (3, 4), (6, 3), (4, 3), (7, 3), (3, 3), (2, 4), (2, 5), (2, 6), (3, 5)])

@@ -5,8 +5,8 @@ import numpy as np
 import pytest
 
 from paper_2501_08455_amd import workloads
-from test_gpu_parity import TOL, gpu, level_errors, run_gpu, say  # noqa: F401  (gpu is a fixture)
-from test_gpu_backward import run_backward, upstream
+from test_gpu_parity import TOL, assert_parity, gpu, level_errors, run_gpu, say  # noqa: F401  (gpu is a fixture)
+from test_gpu_backward import assert_gradient_parity, run_backward, upstream
 
 pytestmark = pytest.mark.gpu
 
@@ -40,18 +40,15 @@ def test_random_shape(gpu, oracle, shape):
     x = workloads.brownian_paths(B, L, d, seed=B * 1000 + L * 10 + d)
     got = run_gpu(gpu, x, depth, stream, None)
     want = oracle.signature(x, depth, stream=stream)
-    errs = level_errors(got, want, d, depth)
-    say("  forward: " + " ".join("%.2e" % e for e in errs))
-    assert max(errs) <= TOL
+    assert_parity(got, want, x, depth, stream)
     g = upstream(np.random.default_rng(L + d), B, L - 1 if stream else 1, d, depth)
     if not stream:
         g = g[:, 0]
     rc, gx = run_backward(gpu, x, depth, stream, g)
     assert rc == gpu.SIG_OK
     want_g = oracle.signature_backward(x, depth, g, stream=stream)
-    err = np.linalg.norm(gx - want_g) / np.linalg.norm(want_g)
-    say("  gradient: %.2e (%s)" % (err, "register kernel" if gpu.sig_backward_available(d, depth) else "general sweep"))
-    assert np.all(np.isfinite(gx)) and err <= TOL
+    say("  gradient (%s):" % ("register kernel" if gpu.sig_backward_available(d, depth) else "general sweep"))
+    assert_gradient_parity(gx, want_g)
 
 
 def draw_long_paths(count, seed):
@@ -85,13 +82,9 @@ def test_random_long_paths(gpu, oracle, shape):
     say("long paths B=%d L=%d d=%d depth=%d plan=%s gradient segments=%d" % (B, L, d, depth, pl.as_dict(), segs))
     x = workloads.brownian_paths(B, L, d, seed=B * 1000 + L * 10 + d)
     got = run_gpu(gpu, x, depth, False, None)
-    errs = level_errors(got, oracle.signature(x, depth), d, depth)
-    say("  forward: " + " ".join("%.2e" % e for e in errs))
-    assert max(errs) <= TOL
+    assert_parity(got, oracle.signature(x, depth), x, depth, False)
     g = upstream(np.random.default_rng(L + d), B, 1, d, depth)[:, 0]
     rc, gx = run_backward(gpu, x, depth, False, g)
     assert rc == gpu.SIG_OK
     want_g = oracle.signature_backward(x, depth, g)
-    err = np.linalg.norm(gx - want_g) / np.linalg.norm(want_g)
-    say("  gradient: %.2e" % err)
-    assert np.all(np.isfinite(gx)) and err <= TOL
+    assert_gradient_parity(gx, want_g)
