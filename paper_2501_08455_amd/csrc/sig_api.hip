@@ -73,7 +73,10 @@ constexpr int kMaxTreeSegments = 32;
 bool join_fits_lds(const OnChipKernelInfo *ki, int segments, const RowShape &rs)
 {
     const int64_t row = rs.D * (int64_t)sizeof(float);
-    if (ki->state_floats > 64 && (segments + (segments + 1) / 2) * row > kMaxLdsBytes) return false;
+    // (the same predicate as the kernels' own choice of join: the register join needs a small lane state and a
+    // path's lanes inside one workgroup)
+    const bool reg_join = ki->state_floats <= 64 && ki->lanes_per_chunk <= 256;
+    if (!reg_join && (segments + (segments + 1) / 2) * row > kMaxLdsBytes) return false;
     return segments * row <= kMaxLdsBytes;
 }
 

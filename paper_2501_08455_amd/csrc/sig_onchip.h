@@ -683,7 +683,10 @@ __global__ __launch_bounds__((max_threads<d, N, P, CHUNKED>())) void sig_on_chip
                 int64_t nfl = (int64_t)G * row_stride + mis;
                 if (nfl > NF - F0a) nfl = NF - F0a;
                 const int nvec = (int)((nfl + 3) >> 2);
-                const int qmax = (int)(NF - d - 4 - F0a);  // >= 0: checked on the host
+                // last float offset from which both vectors can be read in full; taken in 64 bits (the path array may
+                // hold 2^31 floats or more) and clamped to the tile before narrowing.  >= 0: checked on the host
+                const int64_t qlast = NF - d - 4 - F0a;
+                const int qmax = (int)(qlast < (int64_t)4 * nvec ? qlast : (int64_t)4 * nvec);
                 const float *src = A.path + F0a;
                 __syncthreads();
                 SIG_PRIO_MEMORY();

@@ -127,6 +127,16 @@ def test_plan_validate_rejects_plans_the_kernels_cannot_run():
         == binding.SIG_OK
 
 
+def test_join_in_lds_is_checked_with_the_join_the_kernels_take():
+    """(8,4) with 512 lanes per path has a small lane state, but its lanes span several workgroups, so its segments
+    are joined by the LDS tree (one and a half times the rows), not by the register join: three rows of 18.7 KB would
+    fit, the tree's five do not, and three is no power of two for the join in device memory."""
+    three = binding.make_plan(binding.SIG_VARIANT_ON_CHIP, prefix_depth=3, chunks=1, segments=3)
+    assert binding.sig_plan_validate(4, 100, 8, 4, 0, three) == binding.SIG_ERR_INVALID
+    two = binding.make_plan(binding.SIG_VARIANT_ON_CHIP, prefix_depth=3, chunks=1, segments=2)
+    assert binding.sig_plan_validate(4, 100, 8, 4, 0, two) == binding.SIG_OK
+
+
 def test_planner_keeps_the_shape_grid_on_chip():
     """Every compiled (d, depth) gets an on-chip plan that validates, over the batch sizes and lengths of the
     paper's direct-computation tables (Section 4.1) and beyond; host only."""

@@ -223,7 +223,7 @@ TREE_JOIN_CASES = [
     (6, 5, 3, 2, 150, 8, 0), (7, 5, 3, 1, 130, 4, 0), (7, 5, 3, 2, 97, 16, 0), (9, 4, 2, 1, 40, 32, 0),
     (4, 6, 4, 1, 90, 8, 0),
     # the deeper prefix of 8 and 10 channels at depth 4 (512 / 1,000 lanes per path), uncut and cut
-    (10, 4, 3, 3, 50, 1, 0), (8, 4, 3, 2, 300, 8, 0), (10, 4, 3, 1, 600, 16, 0), (8, 4, 3, 40, 23, 1, 5),
+    (10, 4, 3, 3, 50, 1, 0), (8, 4, 3, 2, 300, 8, 0), (8, 4, 3, 3, 60, 2, 0), (9, 4, 3, 2, 41, 2, 0), (10, 4, 3, 1, 600, 16, 0), (8, 4, 3, 40, 23, 1, 5),
     (9, 4, 3, 5, 77, 1, 0), (9, 4, 3, 1, 400, 4, 0),
 ]
 
@@ -435,6 +435,34 @@ def test_very_large_batch_sampled(gpu, oracle):
     got = out[torch.from_numpy(pick).cuda()].cpu().numpy()
     want = oracle.signature(x[pick], depth)
     assert_parity(got, want, x[pick], depth, False)
+
+
+def test_path_array_of_more_than_2_31_floats(gpu, oracle):
+    """A batch whose path array holds 2.5e9 floats (10 GB): offsets into it do not fit 32 bits.  The straight-copy tile
+    loader of the first workgroups, the one of the last (which clamps its reads to the end of the array) and paths in
+    between are checked against the oracle; every output row must have been written."""
+    import torch
+    B, L, d, depth = 5_000_000, 100, 5, 4
+    rc, pl = gpu.sig_plan(gpu.default_ctx(), B, L, d, depth, 0)
+    assert rc == gpu.SIG_OK
+    say("case 2^31 floats: B=%d L=%d d=%d depth=%d plan=%s" % (B, L, d, depth, pl.as_dict()))
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(20)
+    xt = torch.empty((B, L, d), dtype=torch.float32, device="cuda")
+    xt.normal_(0.0, 0.1, generator=gen)
+    xt[:, 0] = 0.0
+    step = 500_000
+    for lo in range(0, B, step):      # running sums along time, a slice of the batch at a time (bounded temporaries)
+        torch.cumsum(xt[lo:lo + step], dim=1, out=xt[lo:lo + step])
+    out = torch.full((B, gpu.sig_size(d, depth)), float("nan"), dtype=torch.float32, device="cuda")
+    assert gpu.sig_compute(gpu.default_ctx(), xt, depth, 0, out) == gpu.SIG_OK
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(out).all())
+    pick = np.concatenate([np.arange(0, 12), np.arange(B - 12, B),
+                           np.sort(np.random.default_rng(8).choice(B, size=40, replace=False))])
+    idx = torch.from_numpy(pick).cuda()
+    x = xt[idx].cpu().numpy()
+    assert_parity(out[idx].cpu().numpy(), oracle.signature(x, depth), x, depth, False)
 
 
 @pytest.mark.parametrize("d,depth", [(5, 3), (3, 4), (6, 3), (4, 3), (7, 3), (3, 3), (2, 4), (2, 5), (2, 6), (3, 5)])
