@@ -82,13 +82,20 @@ enum sig_variant {
  *                 segments) by a pairwise tree of batched Eq. 4 products in device memory, one launch per round
  *   threads       workgroup size (multiple of 64)
  *   tile_steps    increments staged through LDS per tile by the loader (0: chosen by the library)
- *   reserved[0]   with chunks == 1: 0 = workgroup-wide tiles of increments (the default, faster in every
+ *   independent_waves  with chunks == 1: 0 = workgroup-wide tiles of increments (the default, faster in every
  *                 measurement so far); 1 = every wavefront stages its own increments and workgroups walk
  *                 several batches of paths without any barrier (kept for comparison)
- *   reserved[2]   loader of plans with several tiles per chunk: 0 = chosen by the library, 1 = the next tile's
- *                 loads stay in flight in registers while the current tile is consumed, 2 = load, barrier, consume
- *   reserved[1]   skewed start of the workgroups of a multi-round final-mode launch: 0 = chosen by the
+ *   stagger_ticks skewed start of the workgroups of a multi-round final-mode launch: 0 = chosen by the
  *                 library, > 0 = delay per residency slot in 100 MHz ticks, < 0 = off
+ *   tile_loader   loader of plans with several tiles per chunk: 0 = chosen by the library, 1 = the next tile's
+ *                 loads stay in flight in registers while the current tile is consumed, 2 = load, barrier, consume
+ *   shared_chain  final mode, one chunk, shapes whose d^prefix_depth lanes per path exceed a workgroup, prefix_depth
+ *                 >= 2, (path, segment) pieces short enough for one tile (128 increments for d = 10): a few threads of
+ *                 every workgroup evaluate the part of the Horner chains of Eq. 3 that depends on the first
+ *                 prefix_depth - 1 letters only, once, and the fold reads it from LDS.  0 = chosen by the library
+ *                 (taken for prefix_depth >= 4), 1 = insist (the plan is invalid where the kernel does not apply),
+ *                 2 = every lane carries and re-evaluates its own prefix chain
+ *   reserved      zero
  */
 typedef struct sig_plan_t {
     int32_t variant;
@@ -97,7 +104,11 @@ typedef struct sig_plan_t {
     int32_t segments;
     int32_t threads;
     int32_t tile_steps;
-    int32_t reserved[6];
+    int32_t independent_waves;
+    int32_t stagger_ticks;
+    int32_t tile_loader;
+    int32_t shared_chain;
+    int32_t reserved[2];
 } sig_plan_t;
 
 /*

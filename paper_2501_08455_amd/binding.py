@@ -29,10 +29,13 @@ class sig_plan_t(ctypes.Structure):
     _fields_ = [("variant", ctypes.c_int32), ("prefix_depth", ctypes.c_int32),
                 ("chunks", ctypes.c_int32), ("segments", ctypes.c_int32),
                 ("threads", ctypes.c_int32), ("tile_steps", ctypes.c_int32),
-                ("reserved", ctypes.c_int32 * 6)]
+                ("independent_waves", ctypes.c_int32), ("stagger_ticks", ctypes.c_int32),
+                ("tile_loader", ctypes.c_int32), ("shared_chain", ctypes.c_int32),
+                ("reserved", ctypes.c_int32 * 2)]
 
     def as_dict(self):
-        return {k: int(getattr(self, k)) for k, _ in self._fields_ if k != "reserved"}
+        skip = ("reserved", "independent_waves", "stagger_ticks", "tile_loader", "shared_chain")
+        return {k: int(getattr(self, k)) for k, _ in self._fields_ if k not in skip}
 
 
 class SigError(RuntimeError):
@@ -148,11 +151,12 @@ def sig_plan_validate(B, L, d, depth, stream_flag, plan):
 
 
 def make_plan(variant, prefix_depth=0, chunks=1, segments=1, threads=256, tile_steps=0, independent_waves=0,
-              stagger_ticks=0, tile_loader=0):
+              stagger_ticks=0, tile_loader=0, shared_chain=0):
     pl = sig_plan_t()
-    pl.reserved[0] = int(independent_waves)
-    pl.reserved[1] = int(stagger_ticks)
-    pl.reserved[2] = int(tile_loader)
+    pl.independent_waves = int(independent_waves)
+    pl.stagger_ticks = int(stagger_ticks)
+    pl.tile_loader = int(tile_loader)
+    pl.shared_chain = int(shared_chain)
     pl.variant, pl.prefix_depth, pl.chunks = int(variant), int(prefix_depth), int(chunks)
     pl.segments, pl.threads, pl.tile_steps = int(segments), int(threads), int(tile_steps)
     return pl

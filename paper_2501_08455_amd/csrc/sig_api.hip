@@ -123,7 +123,7 @@ bool finish_on_chip(const OnChipKernelInfo *ki, int cus, int64_t B, int64_t L, i
     args->segments = pl.segments;
     args->threads = pl.threads;
     args->stream_flag = stream_flag;
-    args->cooperative = pl.reserved[0] != 1 && pl.chunks == 1;
+    args->cooperative = pl.independent_waves != 1 && pl.chunks == 1;
     args->chunk_steps = (int)ceil_div(K, (int64_t)pl.chunks * pl.segments);
     if (ceil_div(K, (int64_t)pl.chunks * pl.segments) > INT32_MAX) return false;
     // groups per workgroup: as many as the threads hold, fewer if their chunk signatures overflow LDS
@@ -160,10 +160,10 @@ bool finish_on_chip(const OnChipKernelInfo *ki, int cus, int64_t B, int64_t L, i
         // Several tiles per chunk.  With four or more wavefronts per SIMD resident the other workgroups hide a
         // tile's load latency and the plain loader (load, barrier, consume) keeps the register count low; with
         // fewer, the next tile is kept in flight in registers while the current one is consumed.
-        // plan.reserved[2]: 1 forces the register-staged loader, 2 the plain one.
+        // plan.tile_loader: 1 forces the register-staged loader, 2 the plain one.
         bool pipe;
-        if (pl.reserved[2] == 1 || pl.reserved[2] == 2) {
-            pipe = pl.reserved[2] == 1;
+        if (pl.tile_loader == 1 || pl.tile_loader == 2) {
+            pipe = pl.tile_loader == 1;
         } else {
             const int waves_per_wg = pl.threads / kWave;
             int by_vgpr = 512 / (ki->state_floats + 45);
@@ -198,6 +198,21 @@ bool finish_on_chip(const OnChipKernelInfo *ki, int cus, int64_t B, int64_t L, i
         if (tt < 1) return false;
         args->pipe = pipe && tt < T;
     }
+    // Final mode, one chunk, the lanes of a path in several workgroups, two or more prefix letters, and a (path, segment)
+    // short enough to be one tile: the kernel that shares the prefix part of the Horner chains through a table in LDS.
+    // Taken by default where three or more prefix levels are shared (d = 10, depth 6, p = 4: 1.06-1.09x from 16 paths of
+    // 128 points on; with two shared levels it measured 0.94-1.05x on ten shapes, so those keep the other fold);
+    // plan.shared_chain: 1 insists on it (invalid where it does not apply), 2 switches it off.
+    args->shared_chain = 0;
+    if (pl.shared_chain < 0 || pl.shared_chain > 2) return false;
+    if (!stream_flag && pl.chunks == 1 && args->cooperative && ki->p >= 2 && Q > 256 && Q > pl.threads && pl.shared_chain != 2 &&
+        (pl.shared_chain == 1 || ki->p >= 4) && !forced && shared_chain_fits(ki->d, rs.depth, ki->p, pl.threads, T)) {
+        args->shared_chain = 1;
+        args->pipe = 0;
+        tt = T;
+    } else if (pl.shared_chain == 1) {
+        return false;   // asked for, but this shape or plan has no such kernel
+    }
     args->tile_steps = (int)tt;
     int shift = 0;
     while (((int64_t)1 << shift) < tt * ki->d) ++shift;
@@ -208,7 +223,7 @@ bool finish_on_chip(const OnChipKernelInfo *ki, int cus, int64_t B, int64_t L, i
     // (not with few lanes per path: then a wavefront reads many rows at once, and rows of L * d floats, unlike the
     // (L - 1) * d of the generic tile, tend to start in the same LDS bank)
     args->flat_tile = pl.chunks == 1 && pl.segments == 1 && args->cooperative && tt >= T && L * ki->d >= ki->d + 8 &&
-                      (int64_t)G * L * ki->d < (1 << 20) && Q >= 8;
+                      (int64_t)G * L * ki->d < (1 << 20) && Q >= 8 && !args->shared_chain;
     int64_t lds = ki->lds_bytes(*args);
     while (pl.chunks == 1 && !args->cooperative && !forced && lds > kMaxLdsBytes / 2 && args->tile_steps > 1) {
         // keep at least two workgroups per 64 KB: shorter tiles
@@ -236,11 +251,11 @@ bool finish_on_chip(const OnChipKernelInfo *ki, int cus, int64_t B, int64_t L, i
         // that the lock-step of loads, arithmetic and stores would repeat.  One workgroup's lifetime is
         // estimated as steps x vector instructions per step (1.25 x the FMAs per lane) x resident wavefronts
         // per SIMD x 2.4 cycles at 2.3 GHz, in 100 MHz ticks; the skew per residency slot is that lifetime
-        // divided by the slots of a CU.  plan.reserved[1]: > 0 sets the ticks, < 0 switches the skew off.
+        // divided by the slots of a CU.  plan.stagger_ticks: > 0 sets the ticks, < 0 switches the skew off.
         args->stagger_ticks = 0;
-        if (pl.reserved[1] > 0) {
-            args->stagger_ticks = pl.reserved[1];
-        } else if (pl.reserved[1] == 0 && !stream_flag && pl.chunks == 1 && args->cooperative && Q <= pl.threads &&
+        if (pl.stagger_ticks > 0) {
+            args->stagger_ticks = pl.stagger_ticks;
+        } else if (pl.stagger_ticks == 0 && !stream_flag && pl.chunks == 1 && args->cooperative && Q <= pl.threads &&
                    !args->flat_tile) {
             const int64_t items = ceil_div(B * pl.segments, G);
             // worth it only where the HBM time is a large part of the arithmetic time (measured: it gains 12 % at

@@ -108,7 +108,34 @@ struct OnChipArgs {
     int32_t flat_tile;    // 1: the workgroup's paths are whole and adjacent in memory and fit one tile: the tile is a
                           // straight copy of that range (rows of L * d floats), differenced on the way
     int32_t stream_flag;
+    int32_t shared_chain; // 1: final mode, one chunk, lanes of a path spanning several workgroups, prefix depth >= 2: the
+                          // prefix part of the Horner chains comes from a table in LDS that a few lanes of the workgroup
+                          // fill once (the whole (path, segment) is one tile: tile_steps = chunk_steps)
 };
+
+// The fold that shares the prefix part of the Horner chains (sig_shared_chain_kernel) takes the `steps` increments of a
+// (path, segment) as one tile.  LDS floats of a workgroup: the increments [steps][d], the table [steps][nq][depth - p + 1]
+// with nq the prefixes of length p - 1 the words of one workgroup can have, the chunk totals of the table's running sums
+// (one float per thread and level at most), and the totals of the words at the segment's end.
+constexpr int64_t shared_chain_round4(int64_t x) { return (x + 3) / 4 * 4; }
+constexpr int64_t shared_chain_prefixes(int d, int threads) { return (threads - 1) / d + 2; }
+constexpr int64_t shared_chain_lds_floats(int d, int depth, int p, int threads, int64_t steps)
+{
+    const int64_t nq = shared_chain_prefixes(d, threads);
+    return shared_chain_round4(steps * d) + shared_chain_round4(steps * nq * (depth - p + 1)) + (p - 1) * shared_chain_round4(threads) +
+           shared_chain_round4((p - 1) * nq);
+}
+// whether a segment of `steps` increments fits: 52 KB of LDS (three workgroups per compute unit), a table builder per
+// prefix among the threads, and at most 16 steps per builder (prefixes take a power of two of thread slots, the chunks of
+// steps the rest)
+constexpr bool shared_chain_fits(int d, int depth, int p, int threads, int64_t steps)
+{
+    const int64_t nq = shared_chain_prefixes(d, threads);
+    int64_t slots = 1;
+    while (slots < nq) slots *= 2;
+    return steps >= 1 && slots <= threads && (threads / slots) * 16 >= steps &&
+           shared_chain_lds_floats(d, depth, p, threads, steps) * (int64_t)sizeof(float) <= 52 * 1024;
+}
 
 struct OnChipKernelInfo {
     int d, depth, p;

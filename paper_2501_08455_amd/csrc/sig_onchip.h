@@ -920,6 +920,243 @@ __global__ __launch_bounds__((max_threads<d, N, P, CHUNKED>())) void sig_on_chip
 }
 
 // ------------------------------------------------------------------------------------------
+// Fold with the prefix part of the Horner chains shared by the workgroup (final signature, one time chunk per
+// (path, segment), shapes whose Q = d^P lanes per path exceed a workgroup; P >= 2).
+//
+// In the kernel above every lane carries the coefficients of the proper prefixes of its word u (levels 1 .. P-1)
+// and re-evaluates, for each target level n = P .. N, the chain g_m = S[u_{1:m}] + g_{m-1} v[u_m] / (n - m + 1)
+// up to m = P: for d = 10, depth 6, P = 4 that is 46 of a step's 170 vector instructions, repeated by all
+// 10^4 lanes of a path although the chain up to m = P-1 depends on the first P-1 letters only.  Here the lanes of
+// a workgroup own consecutive words u, so they share about (threads / d) + 1 prefixes q = u / d of length P-1.
+// Before a tile of increments is consumed, the workgroup builds
+//     table[step][q][n - P] = g_{P-1}^{(n)}(q) / (n - P + 1)
+// in LDS (see the kernel for how).  A lane of the fold then needs per step one multiply-add per target level,
+//     g_P^{(n)}(u) = S_P[u] + table[step][u / d][n - P] * v[u_P],
+// before it descends into its own sub-tree; it keeps no prefix coefficients at all (127 vector instructions per
+// step instead of 170 for d = 10, depth 6).
+template <int d, int N, int P>
+struct SharedChain {
+    using Sh = Shape<d, N, P>;
+    static constexpr int R = Sh::R;
+    static constexpr int E = N - P + 1;                       // target levels P .. N: floats per (step, prefix) of the table
+    // prefixes q = u / d that the words of one workgroup can have
+    static __host__ __device__ constexpr int nq(int threads) { return (threads - 1) / d + 2; }
+    // LDS of one tile: shared_chain_lds_floats (the kernel lays its arrays out in that order)
+
+    // sub-levels r >= 2 below the child `a` of u (local index idx in sub-level r - 1), target sub-level tgt
+    template <int tgt, int r>
+    static __device__ __forceinline__ void deeper(float (&s)[Sh::SZ], const float (&v)[d], float g, int idx)
+    {
+#pragma unroll
+        for (int a = 0; a < d; ++a) {
+            const int child = idx * d + a;
+            if constexpr (r == tgt) {
+                s[Sh::sub_off(tgt) + child] = fmaf(g, v[a], s[Sh::sub_off(tgt) + child]);
+            } else {
+                const float g2 = fmaf(g, v[a] * (1.0f / (float)(tgt - r + 1)), s[Sh::sub_off(r) + child]);
+                deeper<tgt, r + 1>(s, v, g2, child);
+            }
+        }
+    }
+
+    // One step S <- S (x) exp(v) on the sub-tree below u, given the chain values G at u's parent from the table and
+    // duP = v[u_P] (Eq. 3 with Eqs. 2 and 4 in Horner form; deeper levels first, they read the old upper ones).
+    static __device__ __forceinline__ void step(float (&s)[Sh::SZ], const float (&v)[d], const float (&G)[E], float duP)
+    {
+        // chain values at u for the target levels P + 1 .. N, then S[u] itself
+        float gu[E];
+#pragma unroll
+        for (int e = 1; e < E; ++e) gu[e] = fmaf(G[e], duP, s[0]);
+        s[0] = fmaf(G[0], duP, s[0]);
+        // per child a of u: the chain values below it for the target sub-levels 2 .. R (from the old S[u a]), S[u a]
+        // itself, then everything below it, deepest target first (one child at a time keeps few chain values live)
+#pragma unroll
+        for (int a = 0; a < d; ++a) {
+            float g2[R > 1 ? R - 1 : 1];
+#pragma unroll
+            for (int tg = 2; tg <= R; ++tg) g2[tg - 2] = fmaf(gu[tg] * (1.0f / (float)tg), v[a], s[Sh::sub_off(1) + a]);
+            s[Sh::sub_off(1) + a] = fmaf(gu[1], v[a], s[Sh::sub_off(1) + a]);
+            static_for<2, R + 1>([&](auto tc) __attribute__((always_inline)) {
+                constexpr int tg = R + 2 - decltype(tc)::value;   // R .. 2
+                deeper<tg, 2>(s, v, g2[tg - 2], a);
+            });
+        }
+    }
+};
+
+// wavefronts per SIMD the kernel is built for: what the lane state and about 45 more registers allow
+template <int d, int N, int P>
+constexpr int shared_chain_min_waves()
+{
+    constexpr int sz = Shape<d, N, P>::SZ;
+    return sz <= 60 ? 5 : sz <= 84 ? 4 : sz <= 124 ? 3 : 2;
+}
+
+constexpr int kSharedChainChunk = 16;   // steps of the table one thread builds (held in registers)
+
+template <int d, int N, int P>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(shared_chain_min_waves<d, N, P>())))
+void sig_shared_chain_kernel(OnChipArgs A)
+{
+    static_assert(P >= 2, "needs at least one prefix level to share");
+    using Sh = Shape<d, N, P>;
+    using SC = SharedChain<d, N, P>;
+    constexpr int Q = Sh::Q;
+    constexpr int D = Sh::D;
+    constexpr int E = SC::E;
+    constexpr int QP = cpow(d, P - 1);      // prefixes of length P-1 per path
+    constexpr int CL = kSharedChainChunk;
+
+    SIG_PRIO_MEMORY();
+    const int tid = threadIdx.x;
+    const int nthr = blockDim.x;
+    const int64_t K = A.L - 1;
+    const int W = A.segments, T = A.chunk_steps;
+    const unsigned NB = (Q + nthr - 1) / nthr;
+    const unsigned group = blockIdx.x / NB;              // (path, segment)
+    const unsigned u0 = (blockIdx.x % NB) * (unsigned)nthr;   // first word of this workgroup
+    const bool active = u0 + tid < (unsigned)Q;
+    const unsigned u = active ? u0 + tid : 0;            // the word of length P this lane works below
+    const unsigned b = group / (unsigned)W;
+    const int64_t k0 = (int64_t)(group - b * W) * T;
+    int64_t left = K - k0;
+    if (left > T) left = T;
+    const int steps = left > 0 ? (int)left : 0;          // increments of this segment: one tile (checked on the host)
+    const float *x0 = A.path + ((int64_t)b * A.L + k0) * d;
+
+    // prefixes q = u / d of this workgroup's words
+    unsigned u_last = u0 + nthr - 1;
+    if (u_last > (unsigned)Q - 1) u_last = Q - 1;
+    const unsigned q0 = u0 / d;
+    const int nq = (int)(u_last / d - q0) + 1;           // <= SC::nq(nthr)
+    const int NQ = SC::nq(nthr);
+    // wavefronts without a word (the tail of a path's last workgroup) only keep the barriers company
+    const bool wave_active = (u0 + (unsigned)(tid & ~(kWave - 1))) < (unsigned)Q;
+
+    float *inc = sig_onchip_smem;                        // [T][d]
+    float *table = inc + round4(T * d);                  // [T][NQ][E]
+    float *ctot = table + round4(T * NQ * E);            // [P-1][chunks][NQ]: chunk totals, at most one float per thread and level
+    float *total = ctot + (P - 1) * round4(nthr);        // [P-1][NQ]: S[q_{1:m}] at the end of the segment
+
+    for (int i = tid; i < steps * d; i += nthr) inc[i] = x0[i + d] - x0[i];
+
+    // ---- the table.  Thread -> (prefix bq, chunk bc of CL consecutive steps); the prefixes take a power of two of slots.
+    // Level by level (Eq. 3 restricted to the words q_{1:m}, summed over time): the term of step t at level m is
+    // h_{m-1}(t) v_t[q_m], with h the Horner chain over the lower levels before step t.  A thread holds its chunk's
+    // increments and running sums in registers, leaves its chunk's total per level in LDS, and after a barrier adds up
+    // the totals of the chunks before it.  This happens before the fold's lane state exists, so the registers are free.
+    int qslots = 1;
+    while (qslots < NQ) qslots <<= 1;
+    const int nchk = nthr / qslots;                      // >= 1 and nchk * CL >= steps (checked on the host)
+    const int bq = tid & (qslots - 1), bc = tid / qslots;
+    const bool builder = bq < nq && bc < nchk;
+    const int cl = (steps + nchk - 1) / nchk;            // steps per chunk, <= CL
+    const int t_begin = bc * cl < steps ? bc * cl : steps;
+    const int cnt = builder ? (t_begin + cl < steps ? cl : steps - t_begin) : 0;
+    __syncthreads();
+    {
+        int blet[P - 1];                                 // the letters of this thread's prefix
+        unsigned rest = q0 + (builder ? bq : 0);
+#pragma unroll
+        for (int m = P - 2; m >= 0; --m) { blet[m] = (int)(rest % d); rest /= d; }
+        float dv[CL][P - 1];                             // v_t[q_m] of the chunk's steps
+        float loc[P - 1][CL];                            // the chunk's own running sums before each of its steps
+        float cc[P - 1];                                 // totals of the chunks before this one
+#pragma unroll
+        for (int i = 0; i < CL; ++i) {
+            const float *row = inc + (t_begin + (i < cnt ? i : 0)) * d;
+#pragma unroll
+            for (int m = 0; m < P - 1; ++m) dv[i][m] = row[blet[m]];
+        }
+        static_for<1, P>([&](auto mc) __attribute__((always_inline)) {
+            constexpr int m = decltype(mc)::value;
+            float run = 0.0f;
+#pragma unroll
+            for (int i = 0; i < CL; ++i) {
+                if (i < cnt) {
+                    float hh = 1.0f;
+#pragma unroll
+                    for (int mm = 1; mm <= m - 1; ++mm) hh = fmaf(hh, dv[i][mm - 1] * (1.0f / (float)(m - mm + 1)), loc[mm - 1][i] + cc[mm - 1]);
+                    loc[m - 1][i] = run;
+                    run = fmaf(hh, dv[i][m - 1], run);
+                }
+            }
+            float *lvl = ctot + (m - 1) * round4(nthr);
+            if (builder) lvl[bc * NQ + bq] = run;
+            __syncthreads();
+            float sum = 0.0f;
+            if (builder) {
+                for (int c2 = 0; c2 < bc; ++c2) sum += lvl[c2 * NQ + bq];
+                if (bc == nchk - 1) total[(m - 1) * NQ + bq] = sum + run;
+            }
+            cc[m - 1] = sum;
+        });
+        // from S[q_{1:m}] before step t to the chain values the fold needs: g_{P-1}^{(n)}(q) / (n - P + 1), n = P .. N
+#pragma unroll
+        for (int i = 0; i < CL; ++i) {
+            if (i < cnt) {
+                float *cell = table + ((t_begin + i) * NQ + bq) * E;
+#pragma unroll
+                for (int e = 0; e < E; ++e) {
+                    float gg = 1.0f;
+#pragma unroll
+                    for (int mm = 1; mm <= P - 1; ++mm) gg = fmaf(gg, dv[i][mm - 1] * (1.0f / (float)(P + e - mm + 1)), loc[mm - 1][i] + cc[mm - 1]);
+                    cell[e] = gg * (1.0f / (float)(e + 1));
+                }
+            }
+        }
+    }
+    __syncthreads();
+
+    // ---- the fold: the sub-tree below u
+    SIG_PRIO_COMPUTE();
+    const int myql = (int)(u / d - q0);
+    const int letterP = (int)(u % d);
+    float st[Sh::SZ];
+#pragma unroll
+    for (int i = 0; i < Sh::SZ; ++i) st[i] = 0.0f;
+    if (wave_active) {
+        // operands of a step: the increment (all lanes of a wavefront read the same row: a broadcast), its component at
+        // u's last letter and the table's entries for u's parent
+        const float *row = inc;
+        const float *tab = table + myql * E;
+        for (int t = 0; t < steps; ++t, row += d, tab += NQ * E) {
+            float v[d], G[E];
+#pragma unroll
+            for (int a = 0; a < d; ++a) v[a] = row[a];
+            const float duP = row[letterP];
+#pragma unroll
+            for (int e = 0; e < E; ++e) G[e] = tab[e];
+            SC::step(st, v, G, duP);
+        }
+    }
+
+    // ---- results: the lanes' sub-trees, and the prefix words from the threads that hold their totals
+    SIG_PRIO_MEMORY();
+    float *dst = (W == 1) ? A.out + (int64_t)b * D : A.partial + (int64_t)group * D;
+    if (active) {
+        static_for<0, Sh::R + 1>([&](auto rcst) __attribute__((always_inline)) {
+            constexpr int r = decltype(rcst)::value;
+            constexpr int cnt_r = cpow(d, r);
+            store_run<Sh::sub_off(r), cnt_r, Sh::SZ>(dst + Sh::row_off(P + r) + u * cnt_r, st);
+        });
+    }
+    if (tid < nq && q0 + tid < (unsigned)QP) {
+        // the word q_{1:m} is written by the workgroup that holds the first word u below it (an empty segment has no
+        // totals: its words are zero)
+        const unsigned q_s = q0 + tid;
+        static_for<1, P>([&](auto mc) __attribute__((always_inline)) {
+            constexpr int m = decltype(mc)::value;
+            constexpr unsigned span = cpow(d, P - 1 - m);
+            if (q_s % span == 0 && q_s * d >= u0) dst[Sh::row_off(m) + q_s / span] = total[(m - 1) * NQ + tid];
+        });
+    }
+}
+
+template <int d, int N, int P>
+constexpr bool shared_chain_compiled() { return P >= 2 && Shape<d, N, P>::Q > 256; }
+
+// ------------------------------------------------------------------------------------------
 // Fold kernel for plans with one time chunk per (path, segment): independent wavefronts.
 //
 // A work item is a batch of `groups` (path, segment) pairs (or, when a chunk's Q lanes exceed the
@@ -1174,6 +1411,9 @@ template <int d, int N, int P>
 int64_t on_chip_lds_bytes(const OnChipArgs &A)
 {
     using Sh = Shape<d, N, P>;
+    if constexpr (shared_chain_compiled<d, N, P>()) {
+        if (A.shared_chain) return shared_chain_lds_floats(d, N, P, A.threads, A.chunk_steps) * (int64_t)sizeof(float);
+    }
     if (A.chunks == 1 && !A.cooperative) return fold_lds_bytes<d, N, P>(A);
     const int64_t NGC = (int64_t)A.groups * A.chunks;
     const bool pipe = A.pipe != 0;
@@ -1240,6 +1480,16 @@ hipError_t on_chip_launch(const OnChipArgs &A, hipStream_t st)
     const int64_t lds = on_chip_lds_bytes<d, N, P>(A);
     if (lds > kMaxLdsBytes) return hipErrorInvalidValue;
     const dim3 blk(A.threads);
+    if (A.shared_chain) {
+        if constexpr (shared_chain_compiled<d, N, P>()) {
+            if (A.stream_flag || A.chunks != 1 || Sh::Q <= A.threads || A.tile_steps != A.chunk_steps ||
+                !shared_chain_fits(d, N, P, A.threads, A.chunk_steps)) return hipErrorInvalidValue;
+            hipLaunchKernelGGL((sig_shared_chain_kernel<d, N, P>), dim3((unsigned)grid), blk, (size_t)lds, st, A);
+            return hipGetLastError();
+        } else {
+            return hipErrorInvalidValue;
+        }
+    }
     if (A.chunks > 1) {
         const dim3 g((unsigned)grid);
         if (A.stream_flag) on_chip_launch_pipe<d, N, P, true, true>(A, g, blk, (size_t)lds, st);

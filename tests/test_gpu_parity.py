@@ -251,6 +251,48 @@ def test_few_long_paths_with_large_states_auto(gpu, oracle, d, depth, B, L):
     check(gpu, oracle, x, depth, False, None, label="auto, tree join")
 
 
+# Shapes whose lanes per path exceed a workgroup, final mode: the fold that reads the shared prefix part of the Horner
+# chains from a table in LDS (shared_chain = 1; the whole (path, segment) is one tile, so it takes segments of up to
+# 16 steps per table-building thread: 128 for ten channels, fewer for five) and, with shared_chain = 2, the fold in which
+# every lane carries its own prefix chain.  Time segments (ragged and empty last ones), workgroups of 64 to 256 threads
+# (the last workgroup of a path is partly idle: 10^4 = 39 x 256 + 16), one-step paths.
+SHARED_CHAIN_CASES = [
+    # d, depth, p, B, L, segments, threads
+    (10, 6, 4, 2, 30, 1, 256), (10, 6, 4, 1, 128, 1, 256), (10, 6, 4, 1, 23, 2, 128), (10, 6, 4, 1, 9, 1, 64),
+    (10, 6, 4, 1, 300, 4, 256), (8, 4, 3, 3, 60, 1, 256), (8, 4, 3, 2, 300, 8, 256), (10, 4, 3, 5, 128, 1, 256),
+    (10, 4, 3, 1, 1000, 8, 128), (9, 4, 3, 2, 33, 1, 64), (7, 5, 3, 2, 60, 1, 256), (7, 5, 3, 1, 200, 4, 256),
+    (10, 5, 3, 1, 50, 1, 256), (8, 5, 3, 1, 45, 2, 256), (9, 5, 3, 1, 31, 1, 128), (5, 6, 4, 3, 60, 1, 256),
+    (5, 6, 4, 1, 400, 8, 256), (10, 4, 3, 3, 2, 1, 256), (8, 4, 3, 40, 23, 1, 256),
+]
+
+
+@pytest.mark.parametrize("case", SHARED_CHAIN_CASES, ids=lambda c: "-".join(str(v) for v in c))
+def test_shared_prefix_chain_fold(gpu, oracle, case):
+    d, depth, p, B, L, segments, threads = case
+    assert gpu.sig_on_chip_available(d, depth, p)
+    x = workloads.brownian_paths(B, L, d, seed=5600 + 17 * B + L + segments)
+    outs = []
+    for mode in (1, 2):
+        plan = gpu.make_plan(gpu.SIG_VARIANT_ON_CHIP, prefix_depth=p, chunks=1, segments=segments, threads=threads,
+                             shared_chain=mode)
+        assert gpu.sig_plan_validate(B, L, d, depth, 0, plan) == gpu.SIG_OK, (mode, case)
+        outs.append(check(gpu, oracle, x, depth, False, plan, label="shared chain %d" % mode))
+    # different evaluation orders of the same sums: equal to rounding
+    assert max(level_errors(outs[0], outs[1].astype(np.float64), d, depth)) <= 1e-6
+
+
+def test_shared_prefix_chain_fold_is_refused_where_it_does_not_fit(gpu):
+    """One tile per (path, segment): segments longer than the table builders can take, forced tiles and stream mode have
+    no such kernel; neither have shapes whose lanes fit a workgroup."""
+    for (B, L, d, depth, p, kw) in [(1, 300, 10, 6, 4, {}), (1, 100, 10, 6, 4, {"tile_steps": 7}), (1, 100, 5, 6, 4, {}),
+                                    (2, 50, 5, 4, 2, {}), (2, 50, 6, 4, 3, {})]:
+        plan = gpu.make_plan(gpu.SIG_VARIANT_ON_CHIP, prefix_depth=p, shared_chain=1, **kw)
+        assert gpu.sig_plan_validate(B, L, d, depth, 0, plan) == gpu.SIG_ERR_INVALID, (B, L, d, depth, p, kw)
+    plan = gpu.make_plan(gpu.SIG_VARIANT_ON_CHIP, prefix_depth=4, shared_chain=1)
+    assert gpu.sig_plan_validate(1, 100, 10, 6, 1, plan) == gpu.SIG_ERR_INVALID
+    assert gpu.sig_plan_validate(1, 100, 10, 6, 0, plan) == gpu.SIG_OK
+
+
 def split_case(case):
     d, depth, p, B, L, chunks, segments, tile, stream = case[:9]
     threads = case[9] if len(case) > 9 else 256
@@ -270,7 +312,7 @@ def test_on_chip_family(gpu, oracle, case):
 @pytest.mark.parametrize("loader", [1, 2], ids=["staged", "plain"])
 @pytest.mark.parametrize("case", [c for c in ON_CHIP_CASES if c[7] > 0], ids=lambda c: "-".join(str(v) for v in c))
 def test_on_chip_tile_loaders(gpu, oracle, case, loader):
-    """Plans with several tiles per chunk, with either loader (plan.reserved[2]) forced."""
+    """Plans with several tiles per chunk, with either loader (plan.tile_loader) forced."""
     d, depth, p, B, L, chunks, segments, tile, stream, threads = split_case(case)
     x = workloads.brownian_paths(B, L, d, seed=9000 + 11 * B + L + loader)
     plan = gpu.make_plan(gpu.SIG_VARIANT_ON_CHIP, prefix_depth=p, chunks=chunks, segments=segments,
@@ -282,7 +324,7 @@ def test_on_chip_tile_loaders(gpu, oracle, case, loader):
 
 @pytest.mark.parametrize("case", [c for c in ON_CHIP_CASES if c[5] == 1], ids=lambda c: "-".join(str(v) for v in c))
 def test_on_chip_independent_wavefronts(gpu, oracle, case):
-    """The barrier-free variant of the single-chunk kernels (plan.reserved[0] = 1)."""
+    """The barrier-free variant of the single-chunk kernels (plan.independent_waves = 1)."""
     d, depth, p, B, L, chunks, segments, tile, stream, threads = split_case(case)
     x = workloads.brownian_paths(B, L, d, seed=7000 + 13 * B + L)
     plan = gpu.make_plan(gpu.SIG_VARIANT_ON_CHIP, prefix_depth=p, chunks=1, segments=segments,
