@@ -18,20 +18,31 @@ if ROOT not in sys.path:
 PEAK_FP32_TFLOPS = 157.3   # MI355X vector fp32, published
 PEAK_HBM_GBS = 8000.0      # MI355X HBM3E, published
 
-# HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs scaled by the
-# copy kernel of the same run (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0); see profiles/hbm_traffic.md.
-# Keyed by (configuration, batch).
-MEASURED_TRAFFIC_BYTES = {
-    ("C1", 4): (2 * 11.9 + 0.3) * 1024,
-    ("C2", 128): (2 * 171.2 + 392.0) * 1024,
-    ("C3", 128): (2 * (2571.3 + 814.1) + 1568.0 + 392.0) * 1024,
-    ("C4", 64): (2 * 190.3 + 21722.9) * 1024,
-    ("C5", 16): (2 * 361.0 + 69693.7) * 1024,
-    ("C1", 1 << 20): (2 * 65559.8 + 57344.0) * 1024,
-    ("C2", 65536): (2 * 64439.9 + 199681.7) * 1024,
-    ("C3", 4096): (2 * 83023.9 + 12480.0) * 1024,
-    ("C4", 4096): (2 * 8286.8 + 1389966.8) * 1024,
-}
+PROFILES = os.path.join(ROOT, "profiles")
+
+
+def measured_traffic(workload, plan):
+    """HBM bytes per launch of the call's dominant kernel as the counters read them (rocprofv3 --pmc FETCH_SIZE /
+    WRITE_SIZE, scaled by the copy kernel of the same run), from profiles/hbm_traffic.md -- but only if that profile
+    was taken with the plan this run uses; otherwise None (the figure would describe another launch)."""
+    path = os.path.join(PROFILES, "hbm_traffic.md")
+    if not os.path.exists(path) or plan is None:
+        return None
+    want = json.dumps(plan, sort_keys=True)
+    best = None
+    for line in open(path):
+        cells = [c.strip() for c in line.strip().strip("|").split("|")]
+        if len(cells) < 6 or cells[0] != workload:
+            continue
+        if cells[2].strip("`") != want:
+            continue
+        try:
+            rd, wr = (float(v) for v in cells[5].split("+"))
+        except ValueError:
+            continue
+        if best is None or rd + wr > best:
+            best = rd + wr
+    return best
 
 
 def time_calls(binding, ctx, xt, depth, stream_flag, out, steps, warmup, plan=None):
@@ -93,8 +104,9 @@ def bench_config(binding, workloads, ctx, cfg, B, steps, warmup, plan=None, labe
                                                             "stream" if cfg.stream else "final", label),
            "ms_per_step": ms_ev, "ms_per_step_host_clock": ms_wall, "steps": steps,
            "paths_per_s": B / (ms_ev * 1e-3), "terms_per_s": B * rows * D / (ms_ev * 1e-3),
-           "roofline": roofline(flops, nbytes, ms_ev, MEASURED_TRAFFIC_BYTES.get((cfg.name, B))),
+           "roofline": roofline(flops, nbytes, ms_ev, None),
            "algorithmic": {"flops": flops, "bytes": nbytes}, "plan": pl.as_dict()}
+    res["roofline"]["traffic"] = measured_traffic(res["workload"], res["plan"])
     if plan is not None and plan.variant == binding.SIG_VARIANT_HBM_STREAMING:
         # the state-in-HBM design reads and writes every coefficient once per increment: its own byte count
         design_bytes = 8.0 * D * B * (cfg.L - 1)
@@ -114,7 +126,7 @@ def bench_config(binding, workloads, ctx, cfg, B, steps, warmup, plan=None, labe
         ach = design_bytes / (ms_ev * 1e-3) / 1e9
         res["roofline"] = {"bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                            "frac": ach / PEAK_HBM_GBS, "traffic": None,
-                           "note": "bytes of the level-by-level design of Section 2.2 (lower levels of every prefix "
+                           "note": "bytes of the level-by-level design of Section 3.2 (lower levels of every prefix "
                                    "written once and read once per level above); the HBM counters read the same "
                                    "amount (profiles/sig_level_scan_*.md)"}
     del xt, out
@@ -248,50 +260,71 @@ def stream_families(binding, workloads, ctx):
     return rows
 
 
-def training_step(workloads, B, L, d, depth, steps, warmup):
-    """One optimisation step of the paper's model (Section 4.2, Eq. 11): Dense(20 -> d) with tanh, signature of
-    depth `depth`, Dense(D -> 10), mean squared error, plain gradient descent; synthetic inputs of the stated
-    shape.  The two Dense layers are torch (rocBLAS / hipBLASLt GEMMs); the signature layer and its gradient are
-    libsig's kernels.  The paper does not name the activation; tanh is used here."""
+TRAIN_SAMPLES = 12765   # size of the training set of the paper's Section 4.2
+TRAIN_BATCH = 128
+
+
+def training_step(workloads, L, d, depth, steps, warmup):
+    """The paper's model (Section 4.2, Eq. 11): Dense(20 -> d) with tanh, signature of depth `depth`, Dense(D -> 10), mean
+    squared error, plain gradient descent; synthetic inputs of the stated shape (12,765 samples of L points in 20
+    channels, batches of 128 -- so the last batch of an epoch is ragged: 12,765 = 99 x 128 + 93).  The two Dense layers are
+    torch (rocBLAS / hipBLASLt GEMMs); the signature layer and its gradient are libsig's kernels.  The paper does not name
+    the activation; tanh is used here.  Reports one step at batch 128 and one whole epoch (100 steps over the set)."""
     import torch
     from paper_2501_08455_amd import autograd
     gen = torch.Generator(device="cuda")
     gen.manual_seed(11)
     D = workloads.sig_size(d, depth)
-    X = torch.randn((B, L, 20), device="cuda", generator=gen).cumsum(1) * (1.0 / L) ** 0.5
-    Y = torch.randn((B, 10), device="cuda", generator=gen)
+    X = torch.randn((TRAIN_SAMPLES, L, 20), device="cuda", generator=gen).cumsum(1) * (1.0 / L) ** 0.5
+    Y = torch.randn((TRAIN_SAMPLES, 10), device="cuda", generator=gen)
     W1 = (torch.randn((20, d), device="cuda", generator=gen) * 0.2).requires_grad_(True)
     b1 = torch.zeros(d, device="cuda", requires_grad=True)
     W2 = (torch.randn((D, 10), device="cuda", generator=gen) * 0.05).requires_grad_(True)
     b2 = torch.zeros(10, device="cuda", requires_grad=True)
     params = [W1, b1, W2, b2]
 
-    def one_step():
-        Z = torch.tanh(X @ W1 + b1)
+    def one_step(lo, hi):
+        Z = torch.tanh(X[lo:hi] @ W1 + b1)
         S = autograd.signature(Z, depth)
-        loss = ((S @ W2 + b2 - Y) ** 2).mean()
+        loss = ((S @ W2 + b2 - Y[lo:hi]) ** 2).mean()
         grads = torch.autograd.grad(loss, params)
         with torch.no_grad():
             for p_, g_ in zip(params, grads):
                 p_ -= 1e-3 * g_
         return loss
 
+    def one_epoch():
+        loss = None
+        for lo in range(0, TRAIN_SAMPLES, TRAIN_BATCH):
+            loss = one_step(lo, min(lo + TRAIN_BATCH, TRAIN_SAMPLES))
+        return loss
+
     for _ in range(warmup):
-        one_step()
+        one_step(0, TRAIN_BATCH)
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
     for _ in range(steps):
-        loss = one_step()
+        one_step(0, TRAIN_BATCH)
+    e1.record()
+    torch.cuda.synchronize()
+    ms_step = e0.elapsed_time(e1) / steps
+    one_epoch()                     # the ragged last batch plans and allocates once before it is timed
+    torch.cuda.synchronize()
+    e0.record()
+    loss = one_epoch()
     e1.record()
     torch.cuda.synchronize()
     return {"model": "Dense(20->%d, tanh) -> signature depth %d -> Dense(%d->10), MSE, SGD" % (d, depth, D),
-            "batch": B, "length": L, "ms_per_step": e0.elapsed_time(e1) / steps, "final_loss": float(loss.detach())}
+            "batch": TRAIN_BATCH, "length": L, "ms_per_step": ms_step, "samples": TRAIN_SAMPLES,
+            "steps_per_epoch": (TRAIN_SAMPLES + TRAIN_BATCH - 1) // TRAIN_BATCH, "last_batch": TRAIN_SAMPLES % TRAIN_BATCH,
+            "ms_per_epoch": e0.elapsed_time(e1), "final_loss": float(loss.detach())}
 
 
 def anchors(binding):
-    """Achievable rates on this GPU: a plain copy, a plain fill and the stream kernels' write pattern (HBM), and an
-    fp32 FMA loop without packed instructions."""
+    """Achievable rates on this GPU: a plain copy, a plain fill and the stream kernels' write pattern (HBM), an fp32 FMA
+    loop without packed instructions, and the FMA form of the fused kernels (acc[a][b] += g[a] * v[b], three vector
+    registers per instruction) at three and at eight wavefronts per SIMD."""
     import torch
     n = 1 << 28  # 1 GiB each way
     src = torch.ones(n, dtype=torch.float32, device="cuda")
@@ -303,7 +336,12 @@ def anchors(binding):
                            ("write_4096_streams_GBps", lambda: binding.sig_probe_write(dst, 4096), 4.0 * n / 1e9),
                            ("write_1024_streams_GBps", lambda: binding.sig_probe_write(dst, 1024), 4.0 * n / 1e9),
                            ("fma_TFLOPs", lambda: binding.sig_probe_fma(out, 8192, 20000),
-                            2.0 * 16 * 20000 * 8192 * 64 / 1e12)]:
+                            2.0 * 16 * 20000 * 8192 * 64 / 1e12),
+                           # one round of workgroups: 3 (LDS-limited) or 8 wavefronts on every SIMD of 256 compute units
+                           ("fma_outer_3_waves_per_simd_TFLOPs", lambda: binding.sig_probe_fma_outer(out, 3072, 4000, 53000),
+                            2.0 * 100 * 4000 * 3072 * 64 / 1e12),
+                           ("fma_outer_8_waves_per_simd_TFLOPs", lambda: binding.sig_probe_fma_outer(out, 8192, 4000, 0),
+                            2.0 * 100 * 4000 * 8192 * 64 / 1e12)]:
         for _ in range(3):
             assert fn() == 0
         torch.cuda.synchronize()
@@ -337,12 +375,22 @@ def cpu_baseline(workloads, cfg, max_paths, budget_s=20.0):
             "sample": "%d paths of the workload's shape, median of %d runs, %.4f s per run" % (n, len(times), t)}
 
 
+def compact(entry):
+    """The figures of one all_configs entry that fit a line: workload, time, throughput, bound and fraction."""
+    rf = entry["roofline"]
+    return {"workload": entry["workload"], "ms_per_step": round(entry["ms_per_step"], 6),
+            "paths_per_s": round(entry["paths_per_s"], 1), "bound": rf["bound"], "achieved": round(rf["achieved"], 2),
+            "unit": rf["unit"], "frac": round(rf["frac"], 4)}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5000)
     ap.add_argument("--warmup", type=int, default=2000)
-    ap.add_argument("--no-extras", action="store_true", help="skip the other configurations")
+    ap.add_argument("--no-extras", action="store_true", help="time the headline workload only")
+    ap.add_argument("--full", action="store_true",
+                    help="keep every field of the extra entries (plans, algorithmic work, host-clock times) instead of the compact rows")
     ap.add_argument("--anchors", action="store_true", help="also measure the copy and FMA-loop anchors")
     ap.add_argument("--workload", default="C2", help="configuration to time as the headline (C1..C5)")
     ap.add_argument("--batch", type=int, default=0, help="override the batch size (batch-saturated variants)")
@@ -351,7 +399,7 @@ def main():
     ap.add_argument("--stream-families", action="store_true",
                     help="also time stream mode on a grid of small and medium batches: planner's choice vs level-scan")
     ap.add_argument("--level-scan", action="store_true",
-                    help="time the level-by-level kernel family (the paper's Section 2.2) instead of the planner's choice")
+                    help="time the level-by-level kernel family (the paper's Section 3.2) instead of the planner's choice")
     ap.add_argument("--hbm-streaming", type=int, default=-1, metavar="P",
                     help="time the HBM-streaming kernel family with prefix depth P instead of the planner's choice")
     args = ap.parse_args()
@@ -397,49 +445,69 @@ def main():
                    "input": "Brownian paths, increments N(0, 1/L), seeded, resident in HBM"},
         "roofline": head["roofline"],
     }
+    keep = (lambda e: e) if args.full else compact
+    if not args.no_extras:
+        # The literal configurations are bound by launch latency (their ideal times are below one kernel launch); the
+        # fractions that say something about the kernels are those of the batch-saturated variants with the same
+        # (L, d, N, mode, distribution), and of the large-signature configuration, which fills the chip as it is.  They
+        # sit inside the roofline object of the headline so that they travel with it.
+        # (configuration, batch, timed steps, warm-up steps); warm-ups are long enough (tens of ms) for the shader clock
+        # to ramp up after idle
+        saturated = {}
+        for key, name, Bs, steps, warm in [("C1-sat", "C1", 1 << 20, 200, 200), ("C2-sat", "C2", 65536, 150, 100),
+                                           ("C3-sat", "C3", 4096, 80, 50), ("C4-sat", "C4", 4096, 60, 60),
+                                           ("C5", "C5", None, 300, 200), ("C5-sat", "C5", 64, 60, 30)]:
+            c = workloads.CONFIGS[name]
+            e = bench_config(binding, workloads, ctx, c, Bs or c.B, steps, warm)
+            row = compact(e)
+            row["traffic"] = e["roofline"]["traffic"]
+            saturated[key] = row
+        line["roofline"]["saturated"] = saturated
+        line["roofline"]["note"] = ("the headline workload is bound by launch latency at its literal size; `saturated` holds "
+                                    "the same kernels on batches that fill the chip")
     if not args.no_cpu:
         line["cpu_baseline"] = cpu_baseline(workloads, cfg, max_paths=min(B, 128))
     if not args.no_extras:
         extras = []
-        # (configuration, batch, timed steps, warm-up steps); warm-ups are long enough (tens of ms) for the
-        # shader clock to ramp up after idle
-        plan = [("C1", None, 3000, 3000), ("C3", None, 1000, 500), ("C4", None, 1000, 500), ("C5", None, 300, 200),
-                ("C1", 1 << 20, 200, 200), ("C2", 65536, 150, 100), ("C3", 4096, 80, 50), ("C4", 4096, 60, 60)]
-        for name, B, steps, warm in plan:
+        for name, steps, warm in [("C1", 3000, 3000), ("C3", 1000, 500), ("C4", 1000, 500)]:
             c = workloads.CONFIGS[name]
-            extras.append(bench_config(binding, workloads, ctx, c, B or c.B, steps, warm))
-        # the HBM-streaming family (the fallback for shapes without a compiled on-chip kernel) on C5
+            extras.append(bench_config(binding, workloads, ctx, c, c.B, steps, warm))
+        # the HBM-streaming family (the fallback for shapes that neither of the other families takes) on C5
         c5 = workloads.CONFIGS["C5"]
         hbm_plan = binding.make_plan(binding.SIG_VARIANT_HBM_STREAMING, prefix_depth=2)
         extras.append(bench_config(binding, workloads, ctx, c5, c5.B, 20, 5, plan=hbm_plan,
                                    label=" (HBM-streaming family)"))
-        # the paper's own level-by-level formulation (Section 2.2) as a kernel family, next to the fused fold above
+        # the paper's own level-by-level formulation (Section 3.2) as a kernel family, next to the fused fold above
         ls_plan = binding.make_plan(binding.SIG_VARIANT_LEVEL_SCAN, chunks=0)
-        for name, B, steps, warm in [("C2", None, 500, 200), ("C4", None, 500, 200), ("C5", None, 50, 20),
-                                     ("C2", 65536, 10, 3), ("C4", 4096, 20, 5)]:
+        for name, Bs, steps, warm in [("C2", None, 500, 200), ("C4", None, 500, 200), ("C5", None, 50, 20),
+                                      ("C2", 65536, 10, 3), ("C4", 4096, 20, 5)]:
             c = workloads.CONFIGS[name]
-            extras.append(bench_config(binding, workloads, ctx, c, B or c.B, steps, warm, plan=ls_plan,
+            extras.append(bench_config(binding, workloads, ctx, c, Bs or c.B, steps, warm, plan=ls_plan,
                                        label=" (level-scan family)"))
         # the gradient with respect to the path (reverse sweep) on the shapes it is compiled for
-        for name, B, steps, warm in [("C2", None, 1000, 500), ("C4", None, 300, 200), ("C5", None, 30, 10),
-                                     ("C2", 65536, 30, 20), ("C4", 4096, 20, 10)]:
+        for name, Bs, steps, warm in [("C2", None, 1000, 500), ("C4", None, 300, 200), ("C5", None, 30, 10),
+                                      ("C2", 65536, 30, 20), ("C4", 4096, 20, 10)]:
             c = workloads.CONFIGS[name]
-            extras.append(bench_backward(binding, workloads, ctx, c, B or c.B, steps, warm))
+            extras.append(bench_backward(binding, workloads, ctx, c, Bs or c.B, steps, warm))
         # ... and on long paths, where the sweep is cut into time segments across workgroups: C3 (2,000 points), and
         # single paths of 1,000 points in the shapes of C2 and of a ten-channel depth-4 layer (final and stream mode)
         extras.append(bench_backward(binding, workloads, ctx, workloads.CONFIGS["C3"], 128, 100, 50))
         for d, depth, stream in [(5, 4, False), (10, 4, False), (5, 4, True), (10, 4, True)]:
             one = workloads.Config("one path", 1, 1000, d, depth, stream, "normal")
             extras.append(bench_backward(binding, workloads, ctx, one, 1, 200, 100, seed=workloads.BASE_SEED + 11))
-        line["all_configs"] = extras
-        line["table1_shapes"] = table1(binding, workloads, ctx)
+        line["all_configs"] = [keep(e) for e in extras]
+        t1 = table1(binding, workloads, ctx)
+        line["table1_shapes"] = t1 if args.full else [
+            {"batch": r["batch"], "length": r["length"], "depth": r["depth"], "channels": r["channels"],
+             "ms": round(r["ms"], 5), "ms_autotuned": None if r["ms_autotuned"] is None else round(r["ms_autotuned"], 5),
+             "paper_ks_gpu_ms_rtx4090": r["paper_ks_gpu_ms_rtx4090"]} for r in t1]
         line["memory_wall_shape"] = memory_wall_shape(binding, workloads, ctx)
-        # a training step of the paper's model with the signature layer in the middle (context for Section 4.2)
-        line["training_step"] = [training_step(workloads, 128, L, d, depth, 100, 30)
+        # the paper's model with the signature layer in the middle (Section 4.2): one step and one epoch of 12,765 samples
+        line["training_step"] = [training_step(workloads, L, d, depth, 100, 30)
                                  for (L, d, depth) in [(100, 5, 4), (200, 6, 3), (500, 4, 4)]]
     if args.stream_families:
         line["stream_families"] = stream_families(binding, workloads, ctx)
-    if args.anchors:
+    if args.anchors or not args.no_extras:
         line["anchors"] = anchors(binding)
     print(json.dumps(line))
 

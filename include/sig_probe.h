@@ -30,6 +30,16 @@ int sig_probe_copy(float *dst, const float *src, int64_t n_floats, void *hip_str
 int sig_probe_fma(float *out, int64_t waves, int64_t iters, int ilp, int lds_bytes, void *hip_stream);
 
 /*
+ * The instruction form of the signature kernels' inner loops: every lane keeps a 10 x 10 block of accumulators and
+ * runs `iters` rounds of acc[a][b] += g[a] * v[b] (100 fp32 FMAs per round, each reading three vector registers:
+ * the accumulator and two operands that change from instruction to instruction), which is what the sum of rank-1
+ * updates of Eq. 3 compiles to.  The rate of this form, at the occupancy a kernel's register count allows, is the
+ * ceiling of the fused kernels; it lies below the rate of sig_probe_fma, whose FMAs take one operand from a literal.
+ * Same arguments as sig_probe_fma.  Flops = 2 * 100 * iters * waves * 64.
+ */
+int sig_probe_fma_outer(float *out, int64_t waves, int64_t iters, int lds_bytes, void *hip_stream);
+
+/*
  * Write-only anchors for the stream-mode kernels, whose traffic is almost all stores.
  * streams == 1: a plain fill, dst[i] = 1 for n_floats floats, the grid sweeping memory front to back.
  * streams  > 1: `streams` sequential write cursors advancing together, one wavefront per cursor (the pattern of

@@ -98,6 +98,8 @@ def load():
     lib.sig_probe_write.argtypes = [vp, i64, i64, vp]
     lib.sig_probe_fma.restype = i32
     lib.sig_probe_fma.argtypes = [vp, i64, i64, i32, i32, vp]
+    lib.sig_probe_fma_outer.restype = i32
+    lib.sig_probe_fma_outer.argtypes = [vp, i64, i64, i32, vp]
     lib.sig_strerror.restype = ctypes.c_char_p
     lib.sig_strerror.argtypes = [i32]
     _lib = lib
@@ -260,6 +262,12 @@ def sig_probe_fma(out, waves, iters, ilp=16, lds_bytes=0, stream=None):
     """FMA loop of include/sig_probe.h; `out` holds waves * 64 floats."""
     return load().sig_probe_fma(ctypes.c_void_p(out.data_ptr()), int(waves), int(iters), int(ilp), int(lds_bytes),
                                 _stream_handle(stream))
+
+
+def sig_probe_fma_outer(out, waves, iters, lds_bytes=0, stream=None):
+    """The fused kernels' FMA form (acc[a][b] += g[a] * v[b]) of include/sig_probe.h; `out` holds waves * 64 floats."""
+    return load().sig_probe_fma_outer(ctypes.c_void_p(out.data_ptr()), int(waves), int(iters), int(lds_bytes),
+                                      _stream_handle(stream))
 
 
 # ---------------------------------------------------------------- convenience on top of the raw calls

@@ -67,6 +67,32 @@ __global__ __launch_bounds__(256) void sig_probe_fma_kernel(float *out, int64_t 
     out[lane] = s;
 }
 
+// acc[a][b] += g[a] * v[b]: the three-register FMA form of the fused kernels' inner loops
+__global__ __launch_bounds__(256) void sig_probe_fma_outer_kernel(float *out, const float *seed, int64_t iters)
+{
+    const int64_t lane = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    float acc[100], g[10], v[10];
+    // operands the compiler cannot fold: they come from memory (the buffer is written before it is read back below)
+    const float s0 = seed[lane & 63];
+#pragma unroll
+    for (int i = 0; i < 100; ++i) acc[i] = s0 + (float)i * 0.001f;
+#pragma unroll
+    for (int i = 0; i < 10; ++i) {
+        g[i] = s0 * 0.01f + (float)i * 1e-4f;
+        v[i] = s0 * 0.02f - (float)i * 1e-4f;
+    }
+    for (int64_t it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int a = 0; a < 10; ++a)
+#pragma unroll
+            for (int b = 0; b < 10; ++b) acc[a * 10 + b] = fmaf(g[a], v[b], acc[a * 10 + b]);
+    }
+    float s = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 100; ++i) s += acc[i];
+    out[lane] = s;
+}
+
 }  // namespace
 
 extern "C" {
@@ -117,6 +143,16 @@ int sig_probe_fma(float *out, int64_t waves, int64_t iters, int ilp, int lds_byt
     case 16: hipLaunchKernelGGL(sig_probe_fma_kernel<16>, grid, block, (size_t)lds_bytes, st, out, iters); break;
     default: return SIG_ERR_INVALID;
     }
+    return hipGetLastError() == hipSuccess ? SIG_OK : SIG_ERR_HIP;
+}
+
+int sig_probe_fma_outer(float *out, int64_t waves, int64_t iters, int lds_bytes, void *hip_stream)
+{
+    if (!out || waves < 4 || waves % 4 || iters < 0 || waves / 4 > INT32_MAX) return SIG_ERR_INVALID;
+    if (lds_bytes < 0 || lds_bytes > sig::kMaxLdsBytes) return SIG_ERR_INVALID;
+    // the kernel reads its starting values from the first 64 floats of `out` (whatever they hold) and overwrites all of it
+    hipLaunchKernelGGL(sig_probe_fma_outer_kernel, dim3((unsigned)(waves / 4)), dim3(256), (size_t)lds_bytes,
+                       static_cast<hipStream_t>(hip_stream), out, out, iters);
     return hipGetLastError() == hipSuccess ? SIG_OK : SIG_ERR_HIP;
 }
 
