@@ -214,7 +214,7 @@ def table1(binding, workloads, ctx, d=5):
 
 
 def memory_wall_shape(binding, workloads, ctx):
-    """The shape the paper names as the memory wall of its level-by-level formulation (Section on limitations:
+    """The shape the paper names as the memory wall of its level-by-level formulation (Section 3.5, limitations:
     batch 128, length 500, 10 channels, depth 4, more than 700 million intermediate values): forward and gradient
     here, with the device scratch each call needs."""
     import torch

@@ -2,7 +2,7 @@
  * sig.h -- C ABI of libsig: the batched truncated path-signature transform on
  * one AMD MI355X (gfx950), hand-written HIP behind plain pointers and sizes.
  *
- * The operation (paper Section 2.1):
+ * The operation (paper Section 3.1):
  *   a path is L points in R^d; its K = L - 1 increments are dX_k = X_{k+1} - X_k;
  *   exp^N(v) = (1, v, v(x)v/2!, ..., v^{(x)N}/N!)                         (Eq. 2)
  *   Sig_1 = exp^N(dX_1),  Sig_k = Sig_{k-1} (x) exp^N(dX_k)               (Eq. 3, batched Eq. 5)
@@ -61,7 +61,7 @@ enum sig_variant {
      * and runs the fused multiply-by-exponential of Eq. 3 over its time chunk; chunks of one path
      * are joined by Eq. 4 products; only for the compiled (d, depth, prefix_depth) combinations */
     SIG_VARIANT_ON_CHIP = 2,
-    /* the level-by-level formulation of the paper's Section 2.2 (Eqs. 6-10): one launch per level, each a
+    /* the level-by-level formulation of the paper's Section 3.2 (Eqs. 6-10): one launch per level, each a
      * cumulative sum over time of per-step terms built from the lower levels of every prefix; those live in the
      * output rows (stream mode) or in context scratch of B * (L-1) * (D - d^depth) floats (final mode).
      * d <= 256 (a template parameter up to 10, a run-time value above), depth <= 8.  Built to measure the paper's own design against the fused fold on the same chip (where a
@@ -185,6 +185,15 @@ int sig_autotune(sig_ctx *ctx, int64_t B, int64_t L, int d, int depth, int strea
  * launched), else the status it would return.  Host only.
  */
 int sig_plan_validate(int64_t B, int64_t L, int d, int depth, int stream_flag, const sig_plan_t *plan);
+
+/*
+ * What a plan costs on the device, worked out on the host (nothing is launched; a device with 256 compute units is
+ * assumed): LDS bytes per workgroup, workgroups of the main launch, and bytes of context scratch the call needs (what
+ * sig_compute_noalloc compares with SIG_NOALLOC_SCRATCH_BYTES).  Each pointer may be NULL.  The level-scan family, one
+ * launch per level with its own geometry, reports -1 for the first two.  Returns what sig_plan_validate returns.
+ */
+int sig_plan_footprint(int64_t B, int64_t L, int d, int depth, int stream_flag, const sig_plan_t *plan,
+                       int64_t *lds_bytes, int64_t *workgroups, int64_t *scratch_bytes);
 
 /*
  * sig_compute with an explicit mapping.  The plan is validated against the

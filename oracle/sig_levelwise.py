@@ -2,8 +2,8 @@
 
 TEST INFRASTRUCTURE ONLY: nothing in the product imports this module.
 
-What it computes.  Section 2.2 of the paper ("GPU-Optimized Approach") reorganises the recursion of
-Section 2.1 so that time is handled by one cumulative sum per level (Eqs. 6-10): level n of every prefix
+What it computes.  Section 3.2 of the paper ("GPU-Optimized Approach") reorganises the recursion of
+Section 3.1 so that time is handled by one cumulative sum per level (Eqs. 6-10): level n of every prefix
 signature is the running sum over time of a per-step term built from the lower levels and from powers of
 the step's increment divided by factorials (Eq. 7).  This module takes those steps in the paper's order,
 with whole-tensor numpy operations of shape (batch, time, d^n) exactly as the section describes them

@@ -6,7 +6,7 @@
  * product never calls it: only the tests, the smoke check and the
  * cpu_baseline leg of the benchmark may load it.
  *
- * What it computes (paper, Section 2.1 "Traditional Approach"):
+ * What it computes (paper, Section 3.1 "Traditional Approach"):
  *   - increments  dX_k = X_{k+1} - X_k of a piecewise-linear path (text above Eq. 2);
  *   - the restricted tensor exponential of one increment        (Eq. 2);
  *   - the recursion  Sig_1 = exp(dX_1), Sig_k = Sig_{k-1} (x) exp(dX_k)   (Eq. 3, batched in Eq. 5);

@@ -80,6 +80,9 @@ def load():
                                  ctypes.POINTER(ctypes.c_float), vp]
     lib.sig_plan_validate.restype = i32
     lib.sig_plan_validate.argtypes = [i64, i64, i32, i32, i32, ctypes.POINTER(sig_plan_t)]
+    lib.sig_plan_footprint.restype = i32
+    lib.sig_plan_footprint.argtypes = [i64, i64, i32, i32, i32, ctypes.POINTER(sig_plan_t), ctypes.POINTER(i64),
+                                       ctypes.POINTER(i64), ctypes.POINTER(i64)]
     lib.sig_compute_planned.restype = i32
     lib.sig_compute_planned.argtypes = [vp, vp, i64, i64, i32, i32, i32, vp, ctypes.POINTER(sig_plan_t), vp]
     lib.sig_combine.restype = i32
@@ -150,6 +153,14 @@ def sig_autotune(ctx, B, L, d, depth, stream_flag, stream=None):
 
 def sig_plan_validate(B, L, d, depth, stream_flag, plan):
     return int(load().sig_plan_validate(int(B), int(L), int(d), int(depth), int(stream_flag), ctypes.byref(plan)))
+
+
+def sig_plan_footprint(B, L, d, depth, stream_flag, plan):
+    """(status, LDS bytes per workgroup, workgroups, scratch bytes) of a plan, worked out on the host."""
+    lds, wgs, scr = ctypes.c_int64(0), ctypes.c_int64(0), ctypes.c_int64(0)
+    rc = load().sig_plan_footprint(int(B), int(L), int(d), int(depth), int(stream_flag), ctypes.byref(plan),
+                                   ctypes.byref(lds), ctypes.byref(wgs), ctypes.byref(scr))
+    return int(rc), int(lds.value), int(wgs.value), int(scr.value)
 
 
 def make_plan(variant, prefix_depth=0, chunks=1, segments=1, threads=256, tile_steps=0, independent_waves=0,

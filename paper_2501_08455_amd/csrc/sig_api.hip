@@ -789,6 +789,48 @@ int sig_plan_validate(int64_t B, int64_t L, int d, int depth, int stream_flag, c
     return SIG_OK;
 }
 
+int sig_plan_footprint(int64_t B, int64_t L, int d, int depth, int stream_flag, const sig_plan_t *plan,
+                       int64_t *lds_bytes, int64_t *workgroups, int64_t *scratch_bytes)
+{
+    if (!plan) return SIG_ERR_INVALID;
+    RowShape rs;
+    int rc = check_shape(B, L, d, depth, stream_flag, &rs);
+    if (rc != SIG_OK) return rc;
+    int64_t lds = 0, wgs = 0, scratch = 0;
+    if (plan->variant == SIG_VARIANT_HBM_STREAMING) {
+        rc = sig_plan_validate(B, L, d, depth, stream_flag, plan);
+        if (rc != SIG_OK) return rc;
+        int tile = 8192 / rs.d;
+        if (tile > 64) tile = 64;
+        if (tile < 1) tile = 1;
+        const int64_t gcap = rs.pow[rs.depth - 1 - plan->prefix_depth];
+        lds = ((int64_t)tile * rs.d + 2 * gcap) * (int64_t)sizeof(float);
+        wgs = B * rs.pow[plan->prefix_depth];
+    } else if (plan->variant == SIG_VARIANT_LEVEL_SCAN) {
+        rc = check_level_scan(B, L, rs, stream_flag, *plan);
+        if (rc != SIG_OK) return rc;
+        lds = -1;   // one launch per level, each with its own geometry
+        wgs = -1;
+        scratch = B > 0 ? level_scan_scratch_floats(B, L, rs, stream_flag) * (int64_t)sizeof(float) : 0;
+    } else if (plan->variant == SIG_VARIANT_ON_CHIP) {
+        const OnChipKernelInfo *ki = find_on_chip(rs.d, rs.depth, plan->prefix_depth);
+        OnChipArgs args{};
+        if (!ki || !finish_on_chip(ki, kDefaultCUs, B, L, stream_flag, *plan, rs, &args)) return SIG_ERR_INVALID;
+        lds = ki->lds_bytes(args);
+        wgs = B > 0 ? on_chip_workgroups(ki->lanes_per_chunk, args) : 0;
+        if (plan->segments > 1) {
+            const int64_t rows = B * plan->segments * rs.D;
+            scratch = (join_fits_lds(ki, plan->segments, rs) ? rows : rows + rows / 2 + rows / 4 + 4) * (int64_t)sizeof(float);
+        }
+    } else {
+        return SIG_ERR_INVALID;
+    }
+    if (lds_bytes) *lds_bytes = lds;
+    if (workgroups) *workgroups = wgs;
+    if (scratch_bytes) *scratch_bytes = scratch;
+    return SIG_OK;
+}
+
 int sig_compute_planned(sig_ctx *ctx, const float *path, int64_t B, int64_t L, int d, int depth,
                         int stream_flag, float *out, const sig_plan_t *plan, void *hip_stream)
 {

@@ -41,7 +41,7 @@ hipError_t launch_combine_rows(const float *a, int64_t a_stride, const float *b,
                                hipStream_t st);
 
 // ---------------------------------------------------------------- level-scan family (d <= 256, depth <= 8)
-// The level-by-level formulation of the paper's Section 2.2: one launch per level, each a cumulative sum over time
+// The level-by-level formulation of the paper's Section 3.2: one launch per level, each a cumulative sum over time
 // of per-step terms built from the lower levels of every prefix, which live in the output rows (stream mode) or
 // in `scratch` (final mode: level_scan_scratch_floats floats, one dense [B][L-1][d^m] tensor per level m < depth).
 bool level_scan_available(int d, int depth);
@@ -148,6 +148,32 @@ struct OnChipKernelInfo {
     // out[b] = product over the `segments` partial rows of path b (second launch when segments > 1)
     hipError_t (*join)(const float *partial, float *out, int64_t B, int segments, hipStream_t);
 };
+
+// Work items of an on-chip launch with Q = d^p lanes per (path, chunk): one per slice of a path's lanes when they exceed
+// a workgroup, else one per `groups` (path, segment) pairs.  <= 0: invalid arguments.
+inline int64_t on_chip_work_items(int Q, const OnChipArgs &A)
+{
+    const int64_t ngroups = A.B * A.segments;
+    if (Q > A.threads) {
+        if (A.chunks != 1 || A.groups != 1) return -1;
+        return ngroups * ((Q + A.threads - 1) / A.threads);
+    }
+    if (A.groups < 1) return -1;
+    return (ngroups + A.groups - 1) / A.groups;
+}
+// Workgroups launched: one per work item, except that the kernels with independent wavefronts launch no more workgroups
+// than stay resident and let each walk the same number of items.
+inline int64_t on_chip_workgroups(int Q, const OnChipArgs &A)
+{
+    int64_t grid = on_chip_work_items(Q, A);
+    if (A.chunks == 1 && !A.cooperative && grid > 0) {
+        int64_t resident = A.resident_workgroups > 0 ? A.resident_workgroups : grid;
+        if (resident > grid) resident = grid;
+        const int64_t rounds = (grid + resident - 1) / resident;
+        grid = (grid + rounds - 1) / rounds;
+    }
+    return grid;
+}
 
 // table of compiled on-chip kernels; terminated by an entry with launch == nullptr
 // The compiled kernels live in several translation units (so that they build in parallel); sub-table i ends

@@ -1,6 +1,6 @@
-// Level-scan family: the level-by-level formulation of the paper's Section 2.2 (Eqs. 6-10), one launch per level.
+// Level-scan family: the level-by-level formulation of the paper's Section 3.2 (Eqs. 6-10), one launch per level.
 //
-// Section 2.2 replaces the fold over time by one cumulative sum per level: level n of every prefix signature is
+// Section 3.2 replaces the fold over time by one cumulative sum per level: level n of every prefix signature is
 // the running sum over the steps of a per-step term that needs only the LOWER levels of the prefix before the
 // step.  In the reading that agrees with Eq. 3 (S on the left, exclusive prefix, tensor powers over factorials):
 //     S_n(j) = sum_{i <= j} T_n(i),    T_n(i) = sum_{m=0}^{n-1} S_m(i-1) (x) dX_i^{(x)(n-m)} / (n-m)!.

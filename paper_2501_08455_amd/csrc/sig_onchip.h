@@ -43,29 +43,6 @@
 namespace sig {
 namespace onchip {
 
-// Phase time stamps of workgroup 0, only in diagnostic builds (-DSIG_DIAG_TIMING); read back with sig_diag_read.
-#ifdef SIG_DIAG_TIMING
-__device__ unsigned long long sig_diag_ticks[16];
-#ifdef SIG_DIAG_STEPS
-// stamps inside the step loop of workgroup 0, thread 0: 8 per step for the first 256 steps
-__device__ unsigned long long sig_diag_trace[16384 * 8];
-#define SIG_TICK(i) do { } while (0)
-#define SIG_STEP_TICK(step, i) do { if (threadIdx.x == 0 && blockIdx.x == 0 && (step) < 256) sig_diag_trace[(step) * 8 + (i)] = wall_clock64(); } while (0)
-#elif defined(SIG_DIAG_TRACE)
-// every workgroup's stamps (8 per workgroup; slot 7 holds the hardware id register)
-__device__ unsigned long long sig_diag_trace[16384 * 8];
-#define SIG_TICK(i) do { if (threadIdx.x == 0 && blockIdx.x < 16384) { sig_diag_trace[blockIdx.x * 8 + (i)] = wall_clock64(); \
-    if ((i) == 0) sig_diag_trace[blockIdx.x * 8 + 7] = __builtin_amdgcn_s_getreg(63492) | ((unsigned long long)__builtin_amdgcn_s_getreg(6164) << 32); } } while (0)
-#else
-#define SIG_TICK(i) do { if (threadIdx.x == 0 && blockIdx.x == 0) sig_diag_ticks[i] = wall_clock64(); } while (0)
-#endif
-#else
-#define SIG_TICK(i) do { } while (0)
-#endif
-#ifndef SIG_STEP_TICK
-#define SIG_STEP_TICK(step, i) do { } while (0)
-#endif
-
 typedef float vec4f __attribute__((ext_vector_type(4)));  // plain 16-byte vector for LDS -> HBM row copies
 
 constexpr int cpow(int b, int e)
@@ -444,7 +421,6 @@ __global__ __launch_bounds__((max_threads<d, N, P, CHUNKED>())) void sig_on_chip
     constexpr int Q = Sh::Q;
     constexpr int D = Sh::D;
 
-    SIG_TICK(0);
     SIG_PRIO_MEMORY();
     // Skewed start.  All workgroups of a launch would otherwise load, fold and store in lock-step, and
     // the HBM phases would not overlap the arithmetic.  The workgroups that are resident first are delayed by
@@ -622,21 +598,17 @@ __global__ __launch_bounds__((max_threads<d, N, P, CHUNKED>())) void sig_on_chip
             const float *row = tile + mygc * row_stride;
             Inc<d, P> inc;
             for (int t = 0; t < steps; ++t, row += d) {
-                SIG_STEP_TICK(t0 + t, 0);
                 load_inc<d, P>(inc, row, letter);
                 fused_step<d, N, P>(ln, inc);
                 if constexpr (emit && WAVE_SLOTS) {
                     // gather this wavefront's rows in LDS, then write them with consecutive lanes on
                     // consecutive addresses (LDS operations of one wavefront execute in order)
-                    SIG_STEP_TICK(t0 + t, 1);
                     if (active) store_state<d, N, P>(sigA + mygc * D, u, ln);
-                    SIG_STEP_TICK(t0 + t, 2);
                     if (FAST_EMIT && use_vec) {
                         if constexpr (FAST_EMIT) {
                             V val[NIT];
 #pragma unroll
                             for (int j = 0; j < NIT; ++j) val[j] = reinterpret_cast<const V *>(sigA)[eoff[j]];
-                            SIG_STEP_TICK(t0 + t, 3);
 #pragma unroll
                             for (int j = 0; j < NIT; ++j)
                                 if (t0 + t < elim[j]) eptr[j][(int64_t)(t0 + t) * ROWV] = val[j];
@@ -708,7 +680,6 @@ __global__ __launch_bounds__((max_threads<d, N, P, CHUNKED>())) void sig_on_chip
                 }
                 __syncthreads();
                 SIG_PRIO_COMPUTE();
-                SIG_TICK(6);
                 consume(tile0 + mis, 0, row_stride);
             } else {
             for (int t0 = 0; t0 < T; t0 += TT) {
@@ -779,7 +750,6 @@ __global__ __launch_bounds__((max_threads<d, N, P, CHUNKED>())) void sig_on_chip
                 }
                 __syncthreads();
                 SIG_PRIO_COMPUTE();
-                if (t0 == 0) SIG_TICK(6);
                 consume(tile0, t0, row_floats);
             }
             }
@@ -811,11 +781,9 @@ __global__ __launch_bounds__((max_threads<d, N, P, CHUNKED>())) void sig_on_chip
 
     identity_state<d, N, P>(ln);
     __syncthreads();  // descriptors visible
-    SIG_TICK(1);
 
     if constexpr (!CHUNKED) {
         fold_chunk(std::integral_constant<bool, STREAM>{});
-        SIG_TICK(2);
         SIG_PRIO_MEMORY();
         if constexpr (!STREAM) {
             if (active) {
@@ -826,13 +794,11 @@ __global__ __launch_bounds__((max_threads<d, N, P, CHUNKED>())) void sig_on_chip
     } else {
         using RP = RowProduct<d, N>;
         fold_chunk(std::false_type{});
-        SIG_TICK(2);
         if constexpr (!STREAM && Sh::SZ <= 64) {
             // pairwise tree with the left factor in registers: in the round with stride st chunk c (a multiple
             // of 2 st) absorbs chunk c + st, which has put its row into LDS; the result stays in c's lanes.
             // Only every other surviving chunk writes a row per round, so a group needs (C + 1) / 2 rows,
             // and they take the place of the increment tiles, which are dead by now.
-            SIG_TICK(3);
             __syncthreads();  // every lane is done with the tiles
             float *rows = tile0;
             const int HC = (C + 1) / 2;
@@ -843,7 +809,6 @@ __global__ __launch_bounds__((max_threads<d, N, P, CHUNKED>())) void sig_on_chip
                 if (active && (c & (2 * st - 1)) == 0 && c + st < C) reg_product<d, N, P, SIG_TREE_BATCH>(ln, slot, u);
                 if (2 * st < C) __syncthreads();  // the slots are rewritten in the next round
             }
-            SIG_TICK(4);
             if (active && c == 0) {
                 float *o = (W == 1) ? A.out + (int64_t)mygroup * D : A.partial + (int64_t)mygroup * D;
                 store_state<d, N, P>(o, u, ln);
@@ -855,9 +820,7 @@ __global__ __launch_bounds__((max_threads<d, N, P, CHUNKED>())) void sig_on_chip
         if constexpr (!STREAM) {
             float *src = sigA, *dst = sigB;
             int src_stride = C, dst_stride = (C + 1) / 2;
-            SIG_TICK(3);
             lds_tree_reduce<d, N>(src, dst, G, C, src_stride, dst_stride, tid, nthr);
-            SIG_TICK(4);
             for (int x = tid; x < G * D; x += nthr) {
                 const int g2 = x / D;
                 const int pos = x - g2 * D;
@@ -869,7 +832,6 @@ __global__ __launch_bounds__((max_threads<d, N, P, CHUNKED>())) void sig_on_chip
             }
         } else {
             // inclusive scan left to right into the second buffer: B[0] = A[0], B[c] = B[c-1] (x) A[c]
-            SIG_TICK(3);
             float *scanned = sigB;  // where the inclusive prefixes end up
             if constexpr (Sh::SZ <= 64 && WAVE_SLOTS) {
                 // Scan in log2(C) rounds with the left factor in registers: in the round with stride st the lanes
@@ -909,14 +871,12 @@ __global__ __launch_bounds__((max_threads<d, N, P, CHUNKED>())) void sig_on_chip
                 }
             }
             // every chunk restarts from the signature of everything before it and emits its prefixes
-            SIG_TICK(4);
             if (c == 0) identity_state<d, N, P>(ln);
             else load_state<d, N, P>(scanned + (mygc - 1) * D, u, ln);
             fold_chunk(std::true_type{});
         }
         }
     }
-    SIG_TICK(5);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1456,21 +1416,16 @@ hipError_t on_chip_launch(const OnChipArgs &A, hipStream_t st)
 {
     using Sh = Shape<d, N, P>;
     const int64_t ngroups = A.B * A.segments;
-    int64_t grid;
-    if (Sh::Q > A.threads) {
-        if (A.chunks != 1 || A.groups != 1) return hipErrorInvalidValue;
-        grid = ngroups * ((Sh::Q + A.threads - 1) / A.threads);
-    } else {
-        const int G = A.groups;
-        if (G < 1) return hipErrorInvalidValue;
+    if (Sh::Q <= A.threads) {
+        if (A.groups < 1) return hipErrorInvalidValue;
         if (A.stream_flag && Sh::Q <= kWave) {
-            if ((int64_t)G * A.chunks > (int64_t)(A.threads / kWave) * (kWave / Sh::Q)) return hipErrorInvalidValue;
-        } else if ((int64_t)G * A.chunks * Sh::Q > A.threads) {
+            if ((int64_t)A.groups * A.chunks > (int64_t)(A.threads / kWave) * (kWave / Sh::Q)) return hipErrorInvalidValue;
+        } else if ((int64_t)A.groups * A.chunks * Sh::Q > A.threads) {
             return hipErrorInvalidValue;
         }
-        grid = (ngroups + G - 1) / G;
     }
-    if (grid <= 0 || grid > INT32_MAX || ngroups > INT32_MAX) return hipErrorInvalidValue;
+    const int64_t grid = on_chip_workgroups(Sh::Q, A);
+    if (grid <= 0 || on_chip_work_items(Sh::Q, A) > INT32_MAX || ngroups > INT32_MAX) return hipErrorInvalidValue;
     if (A.threads > (A.chunks > 1 ? max_threads<d, N, P, true>() : 256)) return hipErrorInvalidValue;
     // loader geometry the kernel relies on
     const int64_t NGC = (int64_t)A.groups * A.chunks;
@@ -1499,12 +1454,8 @@ hipError_t on_chip_launch(const OnChipArgs &A, hipStream_t st)
         if (A.stream_flag) on_chip_launch_pipe<d, N, P, false, true>(A, g, blk, (size_t)lds, st);
         else on_chip_launch_pipe<d, N, P, false, false>(A, g, blk, (size_t)lds, st);
     } else {
-        // persistent: `grid` counts the work items; launch no more workgroups than stay resident, and so
-        // that every workgroup walks the same number of items
-        int64_t resident = A.resident_workgroups > 0 ? A.resident_workgroups : grid;
-        if (resident > grid) resident = grid;
-        const int64_t rounds = (grid + resident - 1) / resident;
-        const dim3 g((unsigned)((grid + rounds - 1) / rounds));
+        // persistent: no more workgroups than stay resident, each walking the same number of work items
+        const dim3 g((unsigned)grid);
         if (A.stream_flag) hipLaunchKernelGGL((sig_fold_kernel<d, N, P, true>), g, blk, (size_t)lds, st, A);
         else hipLaunchKernelGGL((sig_fold_kernel<d, N, P, false>), g, blk, (size_t)lds, st, A);
     }

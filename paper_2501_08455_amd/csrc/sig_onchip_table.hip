@@ -42,18 +42,3 @@ const OnChipKernelInfo *find_on_chip(int d, int depth, int p)
 }
 
 }  // namespace sig
-
-#ifdef SIG_DIAG_TIMING
-extern "C" int sig_diag_read(unsigned long long *host16)
-{
-    return (int)hipMemcpyFromSymbol(host16, HIP_SYMBOL(sig::onchip::sig_diag_ticks), 16 * sizeof(unsigned long long));
-}
-#if defined(SIG_DIAG_TRACE) || defined(SIG_DIAG_STEPS)
-extern "C" int sig_diag_trace_read(unsigned long long *host, int workgroups)
-{
-    if (workgroups > 16384) workgroups = 16384;
-    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(sig::onchip::sig_diag_trace),
-                                    (size_t)workgroups * 8 * sizeof(unsigned long long));
-}
-#endif
-#endif

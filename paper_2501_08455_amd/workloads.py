@@ -2,7 +2,7 @@
 
 This module holds input generation only (no signature arithmetic) so that the
 fp64 oracle and the HIP path can be fed the identical float32 buffers.  The
-paper's own benchmark inputs are unspecified synthetic tensors (Section 3.2
+paper's own benchmark inputs are unspecified synthetic tensors (Section 4.2
 says only "synthetic"); the shapes and distributions below are the five
 benchmark configurations of this build.
 

@@ -183,7 +183,7 @@ def test_stream_plans_of_few_long_paths_are_parallel_in_time():
 
 
 def test_level_scan_plans_are_checked_on_the_host():
-    """The level-by-level family (Section 2.2) takes d <= 256, depth <= 8, chunks >= 0 and rows that 32-bit lane
+    """The level-by-level family (Section 3.2) takes d <= 256, depth <= 8, chunks >= 0 and rows that 32-bit lane
     offsets can address; the planner chooses it only for shapes without an on-chip kernel."""
     ls = binding.SIG_VARIANT_LEVEL_SCAN
     mk = binding.make_plan

@@ -1,6 +1,6 @@
-"""GPU parity of the level-scan family (the level-by-level formulation of Section 2.2, Eqs. 6-10) through the C ABI.
+"""GPU parity of the level-scan family (the level-by-level formulation of Section 3.2, Eqs. 6-10) through the C ABI.
 
-Expected values come from the fp64 fold oracle (the definition, Section 2.1) and, on small cases, also from the
+Expected values come from the fp64 fold oracle (the definition, Section 3.1) and, on small cases, also from the
 level-by-level oracle written in the paper's own order; the gate is the same per-level relative error as for the
 other families.
 """

@@ -1,7 +1,7 @@
-"""Pins of the level-by-level oracle (oracle/sig_levelwise.py, Section 2.2, Eqs. 6-10 in the corrected reading).
+"""Pins of the level-by-level oracle (oracle/sig_levelwise.py, Section 3.2, Eqs. 6-10 in the corrected reading).
 
 The expected side of every check is a closed form, a hand-worked value, an explicit-index brute force or the
-separately written fold of Section 2.1 (oracle/sig_oracle.c, pinned on its own in test_oracle_pins.py): never the
+separately written fold of Section 3.1 (oracle/sig_oracle.c, pinned on its own in test_oracle_pins.py): never the
 level-by-level routine itself.  A dropped term of the inner sum, a wrong factorial, an inclusive instead of an
 exclusive prefix, or swapped tensor factors each break at least one of them.
 """

@@ -1,6 +1,6 @@
 """Pins of the fp64 oracle against facts that do not come from the oracle itself.
 
-Every check below is derived from the paper's definitions (Section 2.1: Eq. 1
+Every check below is derived from the paper's definitions (Section 3.1: Eq. 1
 iterated integrals, Eq. 2 tensor exponential, Eq. 3 recursion, Eq. 4 product,
 Eq. 10 output row) or from textbook properties of signatures, and is computed
 here with explicit indices or numpy outer products, not by calling the oracle's
