@@ -37,7 +37,7 @@ def measured_traffic(workload, plan):
         if cells[2].strip("`") != want:
             continue
         try:
-            rd, wr = (float(v) for v in cells[5].split("+"))
+            rd, wr = (float(v) for v in cells[5].split(" + "))
         except ValueError:
             continue
         if best is None or rd + wr > best:
