@@ -454,9 +454,12 @@ def main():
         # (configuration, batch, timed steps, warm-up steps); warm-ups are long enough (tens of ms) for the shader clock
         # to ramp up after idle
         saturated = {}
-        for key, name, Bs, steps, warm in [("C1-sat", "C1", 1 << 20, 200, 200), ("C2-sat", "C2", 65536, 150, 100),
-                                           ("C3-sat", "C3", 4096, 80, 50), ("C4-sat", "C4", 4096, 60, 60),
-                                           ("C5", "C5", None, 300, 200), ("C5-sat", "C5", 64, 60, 30)]:
+        # (and for its power management to settle: per-launch times of a saturated kernel start at their best, rise by
+        # 15-25 % after about eight launches and come back over the next 40-60 ms -- seen alike on every saturated
+        # workload in the kernel traces -- so the warm-ups here run for about 70 ms)
+        for key, name, Bs, steps, warm in [("C1-sat", "C1", 1 << 20, 400, 2000), ("C2-sat", "C2", 65536, 150, 400),
+                                           ("C3-sat", "C3", 4096, 80, 300), ("C4-sat", "C4", 4096, 60, 250),
+                                           ("C5", "C5", None, 300, 900), ("C5-sat", "C5", 64, 60, 300)]:
             c = workloads.CONFIGS[name]
             e = bench_config(binding, workloads, ctx, c, Bs or c.B, steps, warm)
             row = compact(e)

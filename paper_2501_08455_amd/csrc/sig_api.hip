@@ -278,16 +278,32 @@ bool finish_on_chip(const OnChipKernelInfo *ki, int cus, int64_t B, int64_t L, i
     return true;
 }
 
-// Which compiled prefix depth to use for (d, depth).  A wavefront issues a vector instruction only every
-// five to six cycles, so the fp32 rate needs several wavefronts per SIMD: for the final signature prefer
-// the smallest prefix depth whose per-lane state is at most 64 floats (six or more wavefronts per SIMD, and the
-// chunk tree runs in registers; measured on d = 4, depth 4: 85 floats per lane lose to 21 by 1.5x at every
-// batch size), else the deepest one.  Stream mode is bound by the stores, not the arithmetic: take the deepest
-// prefix (most lanes, fewest registers, most stores in flight).
-// A shape may also have a prefix depth beyond the first one with a small state (d = 8, 10 at depth 4): more lanes
-// per path than a workgroup has threads and a state of about ten floats.  Final mode takes it only while the
-// batch is too small to give the chip a wavefront per compute unit with the shallower one (measured: 1.2-2.2x up
-// to about 128 paths, 1.7-2x slower from 1,024 on); stream mode stays with lanes that fit a workgroup.
+// Constants of the planner, each fitted to timings on an MI355X (256 compute units, 2.4 GHz).  They decide between
+// mappings that all give the same result; sig_autotune replaces them by a measurement for one shape.
+namespace tune {
+constexpr int kSmallState = 64;          // lane states up to this many floats leave six to eight wavefronts per SIMD
+constexpr int kFewLanes = 16;            // kernels with fewer lanes per path write long stretches of a row per lane
+constexpr int kHeavyState = 40;          // ... or carry this many floats: the deeper entry then wins on longer paths too
+constexpr int kDeepShortPath = 256;      // increments up to which a deeper entry beats the first small-state one
+constexpr int kDeepShortPathHeavy = 768; // ... behind a few-lane or heavy entry
+constexpr int kDeepShortPathWide = 128;  // ... when the deeper entry has more than 128 lanes per path
+constexpr int kDeepBatchFactorFewLanes = 4;   // batch limit of the deeper entry, in units of one wavefront per SIMD
+constexpr int kStreamDeepMinLanes = 8;   // stream mode: deeper entries with fewer lanes only up to ...
+constexpr int kStreamDeepMaxPaths = 512; // ... this many paths
+constexpr int kFinalWavesPerSimd = 8;    // occupancy the final-mode time cut aims for
+constexpr int kFewLaneMinChunkSteps = 12;     // chunks of few-lane kernels with states of 31-63 floats
+constexpr int kFewLaneMinState = 31;
+constexpr double kSegmentCostFactor = 1.7;    // segments of a nearly empty chip: factor * sqrt(state K / (D C))
+constexpr double kSegmentOccupancyWaves = 2.0;  // segments on a busy chip: this many wavefronts per SIMD over the chunks' own
+constexpr int kMaxLdsJoinSegments = 8;
+}  // namespace tune
+
+// Which compiled prefix depth to use for (d, depth); entries of one (d, depth) are ordered by increasing prefix depth.
+//  - final mode: the first entry whose lane state is small (several wavefronts per SIMD, chunk tree in registers);
+//    an entry behind it (lighter steps, more lanes) for small batches of short paths, which are bound by the latency of
+//    the sequential steps; an entry whose lanes span several workgroups only while the batch cannot fill the chip;
+//  - stream mode: bound by the stores, so the deepest entry whose lanes fit a workgroup, but behind a small-state entry
+//    only while that one has few lanes per path.
 const OnChipKernelInfo *pick_on_chip(int d, int depth, int stream_flag, int64_t B, int64_t K, int cus)
 {
     const OnChipKernelInfo *best = nullptr;
@@ -295,37 +311,25 @@ const OnChipKernelInfo *pick_on_chip(int d, int depth, int stream_flag, int64_t 
     for (const OnChipKernelInfo *e = on_chip_subtable(t); e->launch; ++e) {
         if (e->d != d || e->depth != depth) continue;
         if (!best) { best = e; continue; }
-        // entries are ordered by increasing prefix depth; p = 0 (one lane per path) is skipped when there is an
-        // alternative: its LDS reads of the increments are not broadcasts (every lane reads another path's row)
         const bool spans_workgroups = e->lanes_per_chunk > kThreads && best->lanes_per_chunk <= kThreads;
         if (spans_workgroups && (stream_flag || B * best->lanes_per_chunk >= (int64_t)cus * kWave)) continue;
-        // (5,4), (4,4), (5,3) and (6,3) also have a prefix depth (five to seven floats of state) behind the one that the
-        // rule below prefers: small batches of short paths are latency-bound, and the lighter steps take 1.1-1.35x
-        // less time ((5,4), 128 paths of 100 points, four chunks in 512 threads: 7.1 -> 5.9 us; (5,3) 6.3 -> 4.9;
-        // (6,3) 7.2 -> 5.4; (4,4) 6.1 -> 5.4; from 500 points or 512 paths on the shallower depth with its many
-        // chunks and its segments is as fast or faster)
-        // (a deeper kernel with more than 128 lanes per path runs only two chunks in 512 threads and wins up to about
-        // 128 increments: (6,4,3) 1.08-1.38x up to 100 points, 0.83-0.91x from 200 on)
-        // Where the shallower entry has fewer than 16 lanes per path or a lane state of 40 floats or more, the deeper one
-        // wins on longer paths as well (measured up to 700 points on (5,3), (6,3), (7,3), (4,3), (3,4), (3,5), (2,6), (3,6):
-        // 1.16-1.9x; (4,4) 0.99-1.06x and (5,4) 0.94-1.2x keep the limit of 256 increments).
-        const bool heavy_shallower = best->lanes_per_chunk < 16 || best->state_floats >= 40;
-        const int64_t short_path = e->lanes_per_chunk > 128 ? 128 : heavy_shallower ? 768 : 256;
-        // ... and on batches four times larger where the shallower entry has fewer than 16 lanes per path (1,024 paths of
-        // 100 points: 1.3-1.7x on (3,4), (5,3), (6,3), (7,3), (2,6), (3,5), (4,3); a tie at 8,192 paths, and from 32,768 on
-        // the shallower entry wins except on (3,4) and (2,6); (3,6), (4,4) and (5,4) lose already at 1,024)
-        const int64_t few_lanes = (int64_t)cus * 4 * kWave * (best->lanes_per_chunk < 16 ? 4 : 1);
-        const bool short_and_few = !stream_flag && best->state_floats <= 64 && best->p > 0 && e->lanes_per_chunk < kThreads &&
+        const bool best_small = best->p > 0 && best->state_floats <= tune::kSmallState;
+        const bool best_few_lanes = best->lanes_per_chunk < tune::kFewLanes;
+        // final mode, behind a small-state entry: short paths and a batch below one wavefront per SIMD (four behind a
+        // few-lane entry)
+        const bool heavy_shallower = best_few_lanes || best->state_floats >= tune::kHeavyState;
+        const int64_t short_path = e->lanes_per_chunk > 128 ? tune::kDeepShortPathWide
+                                   : heavy_shallower        ? tune::kDeepShortPathHeavy
+                                                            : tune::kDeepShortPath;
+        const int64_t few_lanes = (int64_t)cus * 4 * kWave * (best_few_lanes ? tune::kDeepBatchFactorFewLanes : 1);
+        const bool short_and_few = !stream_flag && best_small && e->lanes_per_chunk < kThreads &&
                                    B * e->lanes_per_chunk * (kThreads / e->lanes_per_chunk) <= few_lanes && K <= short_path;
-        // Stream mode takes an entry behind the first small state only while that one has fewer than 16 lanes per path:
-        // with so few lanes each writes long stretches of every row ((3,4), 4,096 paths of 256 points: 444 -> 108 us with
-        // 27 lanes instead of 3; (5,3) 293 -> 138; (6,3) 754 -> 222); from 16 lanes on the deeper entry is no faster
-        // ((4,4), (5,4): 0.8-1.0x).  Measured on ten shapes with d = 2 ... 7, 8-4,096 paths of 100-1,000 points: 1.1-4.1x
-        // against the best plan of the shallower entry or the level-scan family, except with four lanes per path on large
-        // batches ((2,5), 1,024 paths or more: 0.6-0.76x), which keep the shallower entry.
-        const bool behind_small = best->p > 0 && best->state_floats <= 64;
-        if (stream_flag && behind_small && (best->lanes_per_chunk >= 16 || (e->lanes_per_chunk < 8 && B > 512))) continue;
-        if (stream_flag || best->state_floats > 64 || best->p == 0 || short_and_few) best = e;
+        // stream mode, behind a small-state entry: only while that one has few lanes, and not with very few lanes per
+        // path on large batches
+        if (stream_flag && best_small &&
+            (!best_few_lanes || (e->lanes_per_chunk < tune::kStreamDeepMinLanes && B > tune::kStreamDeepMaxPaths)))
+            continue;
+        if (stream_flag || best->state_floats > tune::kSmallState || best->p == 0 || short_and_few) best = e;
     }
     return best;
 }
@@ -345,62 +349,55 @@ int plan_auto(const sig_ctx *ctx, int64_t B, int64_t L, int stream_flag, const R
 {
     const int cus = ctx ? ctx->num_cu : kDefaultCUs;
     const int64_t K = L - 1;
-    // lanes that fill the chip: eight wavefronts on every SIMD for the arithmetic-bound final mode, one for
-    // stream mode (bound by the stores; cutting time there costs a second fold)
-    int64_t want_lanes = (int64_t)cus * 4 * kWave * (stream_flag ? 1 : 8);
+    const int64_t simd_lanes = (int64_t)cus * 4 * kWave;   // one wavefront on every SIMD
+    // lanes that fill the chip: eight wavefronts on every SIMD for the arithmetic-bound final mode, one for stream mode
+    // (bound by the stores; cutting time there costs a second fold)
+    int64_t want_lanes = simd_lanes * (stream_flag ? 1 : tune::kFinalWavesPerSimd);
     *pl = sig_plan_t{};
     pl->threads = kThreads;
 
     const OnChipKernelInfo *ki = (B > 0) ? pick_on_chip(rs.d, rs.depth, stream_flag, B, K, cus) : nullptr;
     if (ki) {
-        // a large lane state leaves room for fewer wavefronts per SIMD: do not cut time to fill slots that the
-        // registers cannot hold (estimate: state + 45 registers per lane, 512 per SIMD lane)
-        // (also for kernels with fewer than 16 lanes per path, whose states of 31-63 floats leave room for four to six:
-        // 8,192 paths of 100 points took nine to twelve chunks where four are 1.15-1.45x faster)
-        if (!stream_flag && (ki->state_floats > 64 || (ki->lanes_per_chunk < 16 && ki->state_floats >= 31))) {
-            int by_vgpr = 512 / (ki->state_floats + 45);
+        const int Q = ki->lanes_per_chunk;
+        const int state = ki->state_floats;
+        const bool small_state = state <= tune::kSmallState;
+        const bool few_lane_heavy = Q < tune::kFewLanes && state >= tune::kFewLaneMinState;   // few lanes, 31 floats or more each
+        // do not cut time to fill wavefront slots that the registers cannot hold (state + 45 registers per lane)
+        if (!stream_flag && (!small_state || few_lane_heavy)) {
+            int by_vgpr = 512 / (state + 45);
             if (by_vgpr < 1) by_vgpr = 1;
-            if (by_vgpr < 8) want_lanes = (int64_t)cus * 4 * kWave * by_vgpr;
+            if (by_vgpr < tune::kFinalWavesPerSimd) want_lanes = simd_lanes * by_vgpr;
         }
         pl->variant = SIG_VARIANT_ON_CHIP;
         pl->prefix_depth = ki->p;
         pl->chunks = 1;
         pl->segments = 1;
-        const int Q = ki->lanes_per_chunk;
-        // Workgroups of 512 threads for small batches of kernels with a small lane state and more than 64 lanes per
-        // path (one to three chunks in 256 threads), final mode: such calls are bound by the latency of the sequential
-        // steps, and twice the chunks per workgroup halve them.  Taken while 256 threads would leave the chip at or
-        // below a wavefront per SIMD (measured on (5,5), (6,5), (9,3), (10,3), 16-256 paths of 100-500 points and 8 of
-        // 2,000: 1.04-1.6x; from 512 paths on 0.95-1.0x).  Kernels with at most 64 lanes per path gain nothing at
-        // 100 points and lose to more segments on long paths.
+        // Workgroups of 512 threads (twice the chunks side by side) for small lane states on batches that would leave
+        // the chip at or below a wavefront per SIMD with 256: kernels with more than 64 lanes per path, and the entries
+        // behind the first small state once the path is long enough for twice the chunks.
         const int64_t slots256 = Q <= kThreads ? kThreads / Q : 1;
-        const bool few = B * Q * slots256 <= (int64_t)cus * 4 * kWave;
-        // The prefix depths behind the first one with a small state (picked by pick_on_chip for small batches of short
-        // paths) take them too once the path is long enough for twice the chunks ((5,3,2), (6,3,2), 128 paths of 200-257
-        // points: 1.04-1.18x; (4,4,3) with its 64 lanes at any length: 1.0-1.25x).
+        const bool few = B * Q * slots256 <= simd_lanes;
         const OnChipKernelInfo *shallower = ki->p > 1 ? find_on_chip(rs.d, rs.depth, ki->p - 1) : nullptr;
-        const bool deeper = shallower && shallower->state_floats <= 64;
-        const bool wide = !stream_flag && ki->state_floats <= 64 && Q < kThreads && few &&   // (256 lanes: not measured)
+        const bool deeper = shallower && shallower->state_floats <= tune::kSmallState;
+        const bool wide = !stream_flag && small_state && Q < kThreads && few &&
                           (Q > kWave || (deeper && (Q == kWave || K / kMinChunkSteps >= 2 * slots256)));
         const int wg = wide ? 2 * kThreads : kThreads;
         pl->threads = wg;
         if (Q <= kThreads) {
             // cut time into pieces only as far as needed to fill the chip; every cut costs one Eq. 4 product
             int64_t pieces = ceil_div(want_lanes, B * Q);
-            // chunks side by side in a workgroup (stream kernels keep a chunk's lanes inside one wavefront)
+            // chunks side by side in a workgroup (stream kernels keep a chunk's lanes inside one wavefront), within the
+            // LDS their rows take: two buffers in stream mode and for the LDS tree, half of one for the register tree
             int64_t cmax = (stream_flag && Q <= kWave) ? (int64_t)(kThreads / kWave) * (kWave / Q) : wg / Q;
-            // LDS for the chunk signatures: two buffers in stream mode, one when the tree runs in registers
             int64_t clds = (kMaxLdsBytes - kTileLdsBytes) /
-                           ((stream_flag || ki->state_floats > 64 ? 2 : 1) * rs.D * (int64_t)sizeof(float));
-            // (the register tree of the small lane states keeps only every other chunk row; the wide workgroups count on it)
+                           ((stream_flag || !small_state ? 2 : 1) * rs.D * (int64_t)sizeof(float));
             if (wide) clds *= 2;
             if (cmax > clds) cmax = clds;
-            // (stream kernels fold every chunk twice and are bound by the sequential steps, not by the scan over
-            // the chunk signatures: chunks of four steps measured 1.15-1.9x faster than eight on small lane states)
-            // (and three steps on states of at most 16 floats: another 1.1-1.45x on d = 2, 3, 5 at depth 2-4)
-            // (final mode, few-lane kernels with states of 31-63 floats: their chunk tree multiplies long rows with few
-            // lanes, and chunks of at least twelve steps measured best on 2,048-8,192 paths of 100 points: 1.2-1.6x)
-            const int64_t min_steps = !stream_flag ? ((Q < 16 && ki->state_floats >= 31 && ki->state_floats <= 64) ? 12 : kMinChunkSteps) : ki->state_floats <= 16 ? 3 : ki->state_floats <= 32 ? 4 : kMinChunkSteps;
+            // shortest chunk: eight steps; stream mode (every chunk is folded twice, the sequential steps dominate) four
+            // up to 32 floats of state and three up to 16; twelve for the few-lane kernels with heavy states in final mode
+            // (their chunk tree multiplies long rows with few lanes)
+            const int64_t min_steps = !stream_flag ? ((few_lane_heavy && small_state) ? tune::kFewLaneMinChunkSteps : kMinChunkSteps)
+                                      : state <= 16 ? 3 : state <= 32 ? 4 : kMinChunkSteps;
             if (cmax > K / min_steps) cmax = K / min_steps;
             if (cmax < 1) cmax = 1;
             int64_t C = pieces < cmax ? pieces : cmax;
@@ -413,47 +410,35 @@ int plan_auto(const sig_ctx *ctx, int64_t B, int64_t L, int stream_flag, const R
                     if (used(c) * 100 > used(best) * 105 || (used(c) * 100 > used(best) * 95 && best > C && c >= C && c < best)) best = c;
                 C = best;
             }
-            // The chunk tree has ceil(log2 C) rounds of about 0.8 us each when the workgroup is alone on its CU.
-            // If the chip is far from full (twice as many pieces wanted as chunks fit), a power of two just below C
-            // saves a round for a few more steps per chunk (measured: 8 chunks 7.2 us, 10 chunks 7.6 us on
-            // 128 paths of 99 increments); with long chunks the steps cost more than the round (499 increments:
-            // 15.2 against 13.9 us).
+            // far from a full chip with short chunks: a power of two just below C saves a round of the chunk tree
             if (!stream_flag && pieces >= 2 * C && C >= 5 && K <= 24 * C) {
                 int64_t p2 = 1;
                 while (p2 * 2 <= C) p2 *= 2;
                 if (p2 < C && 4 * p2 >= 3 * C) C = p2;
             }
-            // further workgroups along time only while each chunk keeps a long sequential run
+            // further workgroups along time (a second launch joins them) only while each chunk keeps a long run
             int64_t W = 1;
             if (!stream_flag) {
                 W = (pieces + C / 2) / C;  // rounded: a second launch is not worth a few missing lanes
                 int64_t wmax = K / (C * kMinSegmentChunkSteps);
-                // The launch takes about a K / (C W) + b W: steps of a chunk, of a cost that grows with the lane state,
-                // plus a join that walks W rows of D words.  The minimum, W = sqrt(a K / (b C)), fitted to 8 shapes with
-                // lane states of 21-63 floats and rows of 120-1,554 words on 1-128 paths of 1,000-4,000 points, is
-                // 1.7 sqrt(state K / (D C)); 48 steps per chunk left such paths with too few segments (1.1-2.4x, e.g.
-                // (5,3), 32 paths of 4,000 points: 36.9 -> 16 us).  Chunks keep at least eight steps.  Only while the
-                // chip is at most half a wavefront per SIMD full (512 paths of 1,000 points lost 1.2-1.7x with it), and
-                // not for two segments (the join is a second launch: 128 paths of 500 points lost 1.06-1.1x).
-                int64_t by_cost = (int64_t)(1.7 * std::sqrt((double)ki->state_floats * (double)K / ((double)rs.D * (double)C)));
+                // nearly empty chip (at most half a wavefront per SIMD): the launch takes about a K / (C W) + b W, minimal
+                // at W = factor * sqrt(state K / (D C)); chunks keep at least eight steps; not for fewer than three
+                int64_t by_cost = (int64_t)(tune::kSegmentCostFactor * std::sqrt((double)state * (double)K / ((double)rs.D * (double)C)));
                 if (by_cost > K / (C * kMinChunkSteps)) by_cost = K / (C * kMinChunkSteps);
-                if (by_cost >= 3 && B * Q * C <= (int64_t)cus * 2 * kWave && wmax < by_cost) wmax = by_cost;
+                if (by_cost >= 3 && B * Q * C <= simd_lanes / 2 && wmax < by_cost) wmax = by_cost;
                 if (W > wmax) W = wmax;
-                // small lane states: on a busy chip the second launch and the join cost more than the shorter chunks
-                // save, the sooner the shorter the path.  Measured best segment counts on (4,4), (5,4), (3,5), (5,3),
-                // (4,5), (6,4), (7,4), (5,5): 128 / 256 / 512 paths of 1,000 points 4 / 2 / 1, 128 / 384 / 1,024 paths of
-                // 2,000 points 4 / 2-4 / 1-2, 256 paths of 4,000 points 4-6: about (two wavefronts per SIMD / those of
-                // the chunks alone) x sqrt(K / 1,000); 1.1-1.4x against the eight wavefronts per SIMD the chunk count aims for
-                if (ki->state_floats <= 64) {
+                // busy chip, small lane states: the second launch and the join pay only for long paths
+                if (small_state) {
                     const int64_t lanes = B * Q * C;
-                    int64_t by_occupancy = (int64_t)(2.0 * (double)cus * 4 * kWave / (double)lanes * std::sqrt((double)K / 1000.0) + 0.25);
+                    int64_t by_occupancy = (int64_t)(tune::kSegmentOccupancyWaves * (double)simd_lanes / (double)lanes * std::sqrt((double)K / 1000.0) + 0.25);
                     if (by_occupancy < 1) by_occupancy = 1;
                     if (W > by_occupancy) W = by_occupancy;
                 }
                 const int64_t wanted = W;
-                if (W > 8) W = 8;
+                if (W > tune::kMaxLdsJoinSegments) W = tune::kMaxLdsJoinSegments;
                 while (W > 1 && !join_fits_lds(ki, (int)W, rs)) --W;
                 if (W < 1) W = 1;
+                // rows too long for the LDS of a join kernel: a tree in device memory if it allows four times the segments
                 const int64_t tree = tree_segments(wanted, B, K, rs);
                 if (tree >= 4 && tree >= 4 * W) W = tree;
             }
