@@ -597,7 +597,19 @@ __global__ __launch_bounds__((max_threads<d, N, P, CHUNKED>())) void sig_on_chip
             const int steps = (T - t0 < TT) ? T - t0 : TT;
             const float *row = tile + mygc * row_stride;
             Inc<d, P> inc;
-            for (int t = 0; t < steps; ++t, row += d) {
+            int t = 0;
+            if constexpr (!emit && Sh::SZ <= 40) {
+                // small lane states, final mode: two steps per round, both increments read first (one wait and one set of
+                // address updates per pair; the seven extra registers cost no occupancy at these state sizes)
+                Inc<d, P> inc2;
+                for (; t + 1 < steps; t += 2, row += 2 * d) {
+                    load_inc<d, P>(inc, row, letter);
+                    load_inc<d, P>(inc2, row + d, letter);
+                    fused_step<d, N, P>(ln, inc);
+                    fused_step<d, N, P>(ln, inc2);
+                }
+            }
+            for (; t < steps; ++t, row += d) {
                 load_inc<d, P>(inc, row, letter);
                 fused_step<d, N, P>(ln, inc);
                 if constexpr (emit && WAVE_SLOTS) {
