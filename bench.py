@@ -118,7 +118,9 @@ def bench_config(binding, workloads, ctx, cfg, B, steps, warmup, plan=None, labe
     if plan is not None and plan.variant == binding.SIG_VARIANT_LEVEL_SCAN:
         # the level-by-level design keeps the lower levels of every prefix in memory: per path and step it writes
         # level n once (all levels in stream mode, all but the top one in final mode) and level n's launch reads
-        # the distinct coefficients of levels 1 .. n-1 once
+        # the distinct coefficients of levels 1 .. n-1 once.  (The kernels of the stream mode write the lower levels
+        # twice, into dense tensors and into the rows, and read them twice where a level is cut in time; those
+        # bytes are the kernels' own and are not counted here.)
         d, N, K = cfg.d, cfg.depth, cfg.L - 1
         reads = sum(d ** m for n in range(2, N + 1) for m in range(1, n))
         writes = D if cfg.stream else D - d ** N
@@ -127,8 +129,8 @@ def bench_config(binding, workloads, ctx, cfg, B, steps, warmup, plan=None, labe
         res["roofline"] = {"bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                            "frac": ach / PEAK_HBM_GBS, "traffic": None,
                            "note": "bytes of the level-by-level design of Section 3.2 (lower levels of every prefix "
-                                   "written once and read once per level above); the HBM counters read the same "
-                                   "amount (profiles/sig_level_scan_*.md)"}
+                                   "written once and read once per level above); what the HBM counters read is in "
+                                   "profiles/sig_level_scan_*.md"}
     del xt, out
     return res
 

@@ -62,8 +62,9 @@ enum sig_variant {
      * are joined by Eq. 4 products; only for the compiled (d, depth, prefix_depth) combinations */
     SIG_VARIANT_ON_CHIP = 2,
     /* the level-by-level formulation of the paper's Section 3.2 (Eqs. 6-10): one launch per level, each a
-     * cumulative sum over time of per-step terms built from the lower levels of every prefix; those live in the
-     * output rows (stream mode) or in context scratch of B * (L-1) * (D - d^depth) floats (final mode).
+     * cumulative sum over time of per-step terms built from the lower levels of every prefix; those live in
+     * context scratch of B * (L-1) * (D - d^depth) floats, in both modes (in stream mode the launch of the top level
+     * writes whole output rows, the lower levels it has read included).
      * d <= 256 (a template parameter up to 10, a run-time value above), depth <= 8.  Built to measure the paper's own design against the fused fold on the same chip (where a
      * fused kernel is compiled, that one is several times faster); sig_plan chooses it for shapes without an on-chip
      * kernel, where its parallelism in time beats the HBM-streaming sweep.  Plan fields used: chunks (time chunks per word and launch, at most 64; 0 = chosen

@@ -457,8 +457,9 @@ int plan_auto(const sig_ctx *ctx, int64_t B, int64_t L, int stream_flag, const R
         // shapes, B = 1 .. 8192, L = 100 and 500).  On-chip, per step: 0.1 + 0.01 per state float, plus 0.022 per
         // row-copy iteration of a wavefront (0.1 when the rows are short enough for the per-lane element table);
         // kernels whose lanes store their own state (more than 64 lanes per path): 0.0125 per state float.  The
-        // level-scan family: 5 + 0.008 K per level (6.5 in final mode; 2 more from 8 paths on) plus 1.3 x its output at 2 TB/s.  It is
-        // taken when the on-chip estimate is 1.4 times larger and the on-chip plan leaves the chip below two
+        // level-scan family: 6.4 + 0.0062 K per level (1 more from 8 paths on) plus its output at 2.36 TB/s (a fit to
+        // 248 measured calls, 14 % rms; final mode: 6.5 + 0.008 K per level, 2 more from 8 paths on).  It is
+        // taken when the on-chip estimate is 1.3 times larger and the on-chip plan leaves the chip below two
         // wavefronts per SIMD (measured there: up to 15x faster, e.g. d = 8, depth 4, one path of 500 points: 49
         // against 737 us; the estimates err on the side of the on-chip kernels).
         // Final mode: only plans that could not be cut in time at all (large lane states whose rows do not fit LDS
@@ -469,14 +470,15 @@ int plan_auto(const sig_ctx *ctx, int64_t B, int64_t L, int stream_flag, const R
             sig_plan_t ls{};
             ls.variant = SIG_VARIANT_LEVEL_SCAN;
             if (check_level_scan(B, L, rs, stream_flag, ls) != SIG_OK) return false;
+            if (level_scan_scratch_floats(B, L, rs, stream_flag) > (int64_t)1 << 31) return false;
             const int C = chosen.chunks;
             const double waves = (double)B * Q * C / kWave;
             if (waves > 2.0 * cus * 4) return false;
-            const double launches = rs.depth * ((stream_flag ? 5.0 : 6.5) + 0.008 * (double)K + (B >= 8 ? 2.0 : 0.0));
+            const double launches = stream_flag ? rs.depth * (6.4 + 0.0062 * (double)K + (B >= 8 ? 1.0 : 0.0))
+                                                : rs.depth * (6.5 + 0.008 * (double)K + (B >= 8 ? 2.0 : 0.0));
             if (!stream_flag) {
                 if (C != 1 || chosen.segments != 1) return false;
                 const int64_t floats = level_scan_scratch_floats(B, L, rs, 0);
-                if (floats > (int64_t)1 << 31) return false;
                 const double on_chip_final = 6.0 + (double)K * (0.1 + 0.002 * ki->state_floats);
                 return on_chip_final > 1.4 * (launches + 2.6 * 4.0 * (double)floats / 2.0e6);
             }
@@ -492,7 +494,7 @@ int plan_auto(const sig_ctx *ctx, int64_t B, int64_t L, int stream_flag, const R
             }
             const double on_chip = 6.0 + seq * step;
             const double out_bytes = 4.0 * (double)B * (double)K * (double)rs.D;
-            return on_chip > 1.4 * (launches + 1.3 * out_bytes / 2.0e6);
+            return on_chip > 1.3 * (launches + out_bytes / 2.36e6);
         };
         auto take_level_scan = [&]() {
             *pl = sig_plan_t{};

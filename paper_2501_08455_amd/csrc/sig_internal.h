@@ -42,8 +42,8 @@ hipError_t launch_combine_rows(const float *a, int64_t a_stride, const float *b,
 
 // ---------------------------------------------------------------- level-scan family (d <= 256, depth <= 8)
 // The level-by-level formulation of the paper's Section 3.2: one launch per level, each a cumulative sum over time
-// of per-step terms built from the lower levels of every prefix, which live in the output rows (stream mode) or
-// in `scratch` (final mode: level_scan_scratch_floats floats, one dense [B][L-1][d^m] tensor per level m < depth).
+// of per-step terms built from the lower levels of every prefix, which live in `scratch` (level_scan_scratch_floats
+// floats in both modes, one dense [B][L-1][d^m] tensor per level m < depth).
 bool level_scan_available(int d, int depth);
 int64_t level_scan_scratch_floats(int64_t B, int64_t L, const RowShape &rs, int stream_flag);
 // false if the rows of one path cannot be addressed with 32-bit offsets

@@ -9,8 +9,11 @@
 //     g_0 = 1,  g_m = S_m(i-1)[w_{1:m}] + g_{m-1} * dX_i[w_m] / (n-m+1)   (m = 1 .. n-1),   T_n(i)[w.a] = g_{n-1} * dX_i[a],
 // so a term costs n-1 loads of lower-level coefficients, n-1+d FMAs and touches no other word.  The lower levels
 // of every prefix must therefore be in memory (the intermediates of shape (B, L-1, d^m) the paper names as its
-// memory cost): in stream mode they are the output rows themselves, in final mode one dense scratch tensor per
-// level, [B][L-1][d^m], as in the paper.
+// memory cost): one dense scratch tensor per level below the top one, [B][L-1][d^m], as in the paper.  In stream
+// mode the launch of the top level also writes the lower levels it reads into the output rows (the concatenation
+// of Eq. 10), so that every byte of a row is written by one launch and every lower level is read from a dense
+// tensor: when the lower levels lived inside the rows, a 16-byte read at the start of a 1,360-byte row cost a
+// whole 64-byte fetch, and the launches fetched 2.7 times what they used.
 //
 // Mapping.  Level 1 is the running sum of the increments, which telescopes to X_{j+1} - X_0: one elementwise
 // launch.  Launch n >= 2 computes level n from levels 1 .. n-1.  A lane owns one parent word w (its d children are
@@ -24,8 +27,8 @@
 // second pass.  C falls to 1 once B * d^{n-1} alone fills the chip.
 //
 // Traffic per path and step in floats: level n reads the n-1 lower levels at its parents' prefixes (d^{n-1} +
-// d^{n-2} + ... distinct floats, twice when C > 1) and writes d^n; over all levels that is D written once plus
-// about D / (d - 1) read (stream mode), or 2 * (D - d^N) * (1 + 1 / (d - 1)) moved through scratch (final mode).
+// d^{n-2} + ... distinct floats, twice when C > 1) and writes d^n; over all levels that is about
+// 2 * (D - d^N) * (1 + 1 / (d - 1)) moved through scratch, plus the D floats of a row written once in stream mode.
 #include "sig_internal.h"
 
 namespace sig {
@@ -45,6 +48,8 @@ struct LevelScanArgs {
     int32_t lo_stride[kLsMaxLevel];  // K * lo_stride[m] fits 31 bits (checked by the host)
     float *hi;                       // level n of prefix (b, j) goes to hi + (b * K + j) * hi_stride; null: not stored
     float *fin;                      // level n of the whole path goes to fin + b * fin_stride; null: not stored
+    float *cat;                      // stream mode, top level: level m < n of prefix (b, j) is copied to
+    int32_t cat_off[kLsMaxLevel];    //   cat + (b * K + j) * hi_stride + cat_off[m]; null: no copies
     int64_t hi_stride, fin_stride;
     int64_t B, L;
     int32_t d;           // channels (the kernels for d <= 10 have it as a template parameter as well)
@@ -161,6 +166,24 @@ __global__ __launch_bounds__(kLsThreads) void sig_level_scan_kernel(LevelScanArg
     const int j_begin = c * T;
     const int j_end = (j_begin + T < K32) ? j_begin + T : K32;   // may be <= j_begin for trailing chunks
     const int hi_stride = (int)A.hi_stride;
+    // Copies of the lower levels into the output rows: a lane writes the values it has loaded for its chain.  Of the
+    // lanes that share a prefix of their parent words, which all hold its value, the first one writes it (a store
+    // instruction whose lanes hit one address several times measured 30 % slower over the whole launch); a row the
+    // fetch was clamped to is written once more with what was read from it.
+    float *cat_base = A.cat ? A.cat + b0 * K * A.hi_stride : nullptr;
+    uint32_t cat_lane[M];
+    bool cat_own[M];
+    {
+        int rest = lane_ok ? w : 0;
+        bool first_of_prefix = lane_ok && first_child == 0;
+#pragma unroll
+        for (int m = M; m >= 1; --m) {
+            cat_lane[m - 1] = (uint32_t)(lane_ok ? g : 0) * (uint32_t)(K32 * hi_stride) + (uint32_t)A.cat_off[m] + (uint32_t)rest;
+            cat_own[m - 1] = first_of_prefix;
+            first_of_prefix = first_of_prefix && rest % d == 0;
+            rest /= d;
+        }
+    }
     float *hi_base = A.hi ? A.hi + b0 * K * A.hi_stride : nullptr;
     const uint32_t hi_off = (uint32_t)(lane_ok ? g : 0) * (uint32_t)(K32 * hi_stride) + (uint32_t)(lane_ok ? w : 0) * d;
     const float *my_tile = tile + (size_t)((g < G ? g : 0) * C + c) * TP * d;
@@ -215,7 +238,15 @@ __global__ __launch_bounds__(kLsThreads) void sig_level_scan_kernel(LevelScanArg
     // nothing; when levels are stored it stores the unchanged sum once more over the row of the chunk's last step, so
     // that every step issues the same memory operations and the wait counters stay exact.
     const bool has_work = lane_ok && j_begin < j_end;
-    auto step = [&](int jt, int t, int n_on, bool first, const float (&s)[M], auto emit_c) {
+    auto step = [&](int jt, int t, int n_on, bool first, const float (&s)[M], auto emit_c, auto cat_c) {
+        if constexpr (decltype(cat_c)::value) {
+            int jj = jt + t - 1;      // the row `fetch` read s from
+            jj = jj < 0 ? 0 : jj;
+            jj = jj > last_row ? last_row : jj;
+#pragma unroll
+            for (int m = 0; m < M; ++m)
+                if (cat_own[m]) cat_base[cat_lane[m] + __umul24((uint32_t)jj, (uint32_t)hi_stride)] = s[m];
+        }
         const float *dx = my_tile + t * d;
         float h = 1.0f;
 #pragma unroll
@@ -230,7 +261,7 @@ __global__ __launch_bounds__(kLsThreads) void sig_level_scan_kernel(LevelScanArg
         }
     };
 
-    auto sweep = [&](auto emit_c, bool reload) {
+    auto sweep = [&](auto emit_c, auto cat_c, bool reload) {
         for (int i = 0; i < tiles; ++i) {
             if (reload) {
                 __syncthreads();   // the previous tile has been consumed
@@ -248,11 +279,11 @@ __global__ __launch_bounds__(kLsThreads) void sig_level_scan_kernel(LevelScanArg
 #pragma unroll
                 for (int u = 0; u < kLsBatch; ++u) fetch(jt, t0 + kLsBatch + u, pong[u]);
 #pragma unroll
-                for (int u = 0; u < kLsBatch; ++u) step(jt, t0 + u, n_on, u == 0 && jt + t0 == 0, ping[u], emit_c);
+                for (int u = 0; u < kLsBatch; ++u) step(jt, t0 + u, n_on, u == 0 && jt + t0 == 0, ping[u], emit_c, cat_c);
 #pragma unroll
                 for (int u = 0; u < kLsBatch; ++u) fetch(jt, t0 + 2 * kLsBatch + u, ping[u]);
 #pragma unroll
-                for (int u = 0; u < kLsBatch; ++u) step(jt, t0 + kLsBatch + u, n_on, false, pong[u], emit_c);
+                for (int u = 0; u < kLsBatch; ++u) step(jt, t0 + kLsBatch + u, n_on, false, pong[u], emit_c, cat_c);
             }
         }
     };
@@ -262,7 +293,7 @@ __global__ __launch_bounds__(kLsThreads) void sig_level_scan_kernel(LevelScanArg
         __syncthreads();
     }
     if (C > 1) {
-        sweep(No{}, !one_tile);
+        sweep(No{}, No{}, !one_tile);
         float *mine = tot + (size_t)tid * DB;
         if (tid < G * C * PW) {
 #pragma unroll
@@ -294,10 +325,19 @@ __global__ __launch_bounds__(kLsThreads) void sig_level_scan_kernel(LevelScanArg
             }
         }
     }
-    if (A.hi) sweep(Yes{}, !one_tile);
-    else sweep(No{}, !one_tile);
+    if (A.hi && A.cat) sweep(Yes{}, Yes{}, !one_tile);
+    else if (A.hi) sweep(Yes{}, No{}, !one_tile);
+    else sweep(No{}, No{}, !one_tile);
     // the chunk that holds the last step also holds the level of the whole path
     if (lane_ok && A.fin && j_begin < K32 && j_end == K32) store_acc(A.fin + b * A.fin_stride + (int64_t)w * d);
+    // ... and copies the lower levels of the last row, which no step reads
+    if (lane_ok && A.cat && j_begin < K32 && j_end == K32) {
+#pragma unroll
+        for (int m = 0; m < M; ++m)
+            if (cat_own[m])
+                cat_base[cat_lane[m] + __umul24((uint32_t)(K32 - 1), (uint32_t)hi_stride)] =
+                    base[m][lane_off[m] + __umul24((uint32_t)(K32 - 1), (uint32_t)stride[m])];
+    }
 }
 
 template <int d, int n>
@@ -366,7 +406,8 @@ bool level_scan_available(int d, int depth) { return d >= 1 && d <= kLsMaxD && d
 
 int64_t level_scan_scratch_floats(int64_t B, int64_t L, const RowShape &rs, int stream_flag)
 {
-    if (stream_flag || rs.depth == 1) return 0;
+    (void)stream_flag;   // both modes keep the levels below the top one in dense tensors
+    if (rs.depth == 1) return 0;
     return B * (L - 1) * (rs.D - rs.pow[rs.depth]);
 }
 
@@ -403,9 +444,10 @@ hipError_t launch_level_scan(const float *path, float *out, float *scratch, int6
     if (!level_scan_available(rs.d, rs.depth) || !level_scan_fits(L, rs, stream_flag)) return hipErrorInvalidValue;
     const int d = rs.d, N = rs.depth;
     const int64_t K = L - 1;
-    // where level m of every prefix lives: inside the output rows, or in the dense scratch tensor of the level
-    auto level_base = [&](int m) { return stream_flag ? out + rs.off[m] : scratch + B * K * rs.off[m]; };
-    auto level_stride = [&](int m) { return stream_flag ? rs.D : rs.pow[m]; };
+    // where level m of every prefix lives: the dense scratch tensor of the level; the top level of the stream mode
+    // goes straight into the output rows
+    auto level_base = [&](int m) { return (stream_flag && m == N) ? out + rs.off[m] : scratch + B * K * rs.off[m]; };
+    auto level_stride = [&](int m) { return (stream_flag && m == N) ? rs.D : rs.pow[m]; };
     for (int n = 1; n <= N; ++n) {
         float *hi = (stream_flag || n < N) ? level_base(n) : nullptr;
         float *fin = stream_flag ? nullptr : out + rs.off[n];
@@ -432,6 +474,10 @@ hipError_t launch_level_scan(const float *path, float *out, float *scratch, int6
         A.hi_stride = hi_stride;
         A.fin = fin;
         A.fin_stride = fin_stride;
+        if (stream_flag && n == N) {
+            A.cat = out;
+            for (int m = 1; m < n; ++m) A.cat_off[m] = (int32_t)rs.off[m];
+        }
         const int vh = store_width(hi, hi_stride), vf = store_width(fin, fin_stride);
         const int vec = vh < vf ? vh : vf;
         // work items of a path: one per parent word, or (more than 10 channels) one per block of four children
