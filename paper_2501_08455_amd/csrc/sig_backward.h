@@ -206,14 +206,17 @@ constexpr int kTiledSteps = 256;
 // upstream gradients of its own rows as it goes.  EMIT = false is the first of the two sweeps that provide seg_grad:
 // from a zero adjoint, without sums over the increments; it writes what the piece's own rows leave at its start to
 // seg_adj_out (the lanes' partial adjoints of a prefix word are added up there).
-template <int d, int N, int P, bool STREAM, bool SEG = false, bool EMIT = true>
+// TSV: steps whose partial sums are parked before they are added up; 0 = reduce_steps, the most that is useful.
+// Fewer steps take less LDS, which buys resident workgroups on saturated batches (kShortPark, see backward_launch).
+constexpr int kShortPark = 3;
+template <int d, int N, int P, bool STREAM, bool SEG = false, bool EMIT = true, int TSV = 0>
 __global__ __launch_bounds__(256) void sig_backward_kernel(BackwardArgs A)
 {
     static_assert(EMIT || (STREAM && SEG), "the sweep without output belongs to the stream-mode cut");
     using Sh = Shape<d, N, P>;
     constexpr int Q = Sh::Q;
     constexpr int D = Sh::D;
-    constexpr int TS = reduce_steps<d, P>();  // steps whose partial sums are parked before they are added up
+    constexpr int TS = TSV > 0 ? TSV : reduce_steps<d, P>();
     const int tid = threadIdx.x, nthr = blockDim.x;
     const int64_t Kall = A.L - 1;                     // increments of a path
     const int64_t K = SEG ? A.seg_steps : Kall;       // increments of a workgroup's rows
@@ -530,13 +533,19 @@ __global__ __launch_bounds__(256) void sig_backward_tiled_kernel(BackwardArgs A)
     }
 }
 
-// LDS bytes of the register sweep with `groups` paths (or pieces) of L points per workgroup
+// LDS bytes of the register sweep with `groups` paths (or pieces) of L points per workgroup and park_steps parked
+// steps (0: reduce_steps)
+template <int d, int N, int P>
+int64_t backward_lds_bytes(int64_t L, int groups, int park_steps)
+{
+    const int64_t tile = ((int64_t)groups * (L - 1) * d + 3) / 4 * 4;
+    const int64_t park = (int64_t)groups * (park_steps > 0 ? park_steps : reduce_steps<d, P>()) * Park<d, P>::kStepFloats;
+    return (tile + park) * (int64_t)sizeof(float);
+}
 template <int d, int N, int P>
 int64_t backward_lds_bytes(int64_t L, int groups)
 {
-    const int64_t tile = ((int64_t)groups * (L - 1) * d + 3) / 4 * 4;
-    const int64_t park = (int64_t)groups * reduce_steps<d, P>() * Park<d, P>::kStepFloats;
-    return (tile + park) * (int64_t)sizeof(float);
+    return backward_lds_bytes<d, N, P>(L, groups, 0);
 }
 
 // LDS of the sweep cut in time inside a workgroup (sig_backward_chunked_kernel): a lane's registers in LDS, one

@@ -13,6 +13,7 @@ namespace sig {
 constexpr int kMaxDepth = 30;        // d^depth must also fit in int32
 constexpr int kWave = 64;
 constexpr int kMaxLdsBytes = 64 * 1024;  // per-workgroup LDS this library asks for at most
+constexpr int kCuLdsBytes = 160 * 1024;  // LDS of one compute unit, shared by its resident workgroups
 constexpr int kTileLdsBytes = 19968;     // LDS the increment tile(s) of one workgroup may take (8 workgroups share 160 KB)
 constexpr int kFoldTileSteps = 32;       // increments a wavefront of the fold kernel stages at a time
 constexpr int kLoaderStage = 8;          // floats of the next tile one thread holds in registers when tiles are pipelined
