@@ -354,6 +354,19 @@ def anchors(binding):
         e1.record()
         torch.cuda.synchronize()
         res[name] = work / (e0.elapsed_time(e1) / 10 * 1e-3)
+    # The same FMA loop after a third of a second of it: what the chip sustains once its power management has
+    # settled (the figures above are taken within its first 40 ms).  Boxes of this pool differ here by up to 15 %,
+    # and the saturated rows of this file, which run for tens of milliseconds each, differ with it.
+    fn = lambda: binding.sig_probe_fma_outer(out, 8192, 4000, 0)
+    for _ in range(100):
+        fn()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(30):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    res["fma_outer_8_waves_per_simd_sustained_TFLOPs"] = 2.0 * 100 * 4000 * 8192 * 64 / 1e12 / (e0.elapsed_time(e1) / 30 * 1e-3)
     return res
 
 
