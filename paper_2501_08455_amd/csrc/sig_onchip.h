@@ -956,12 +956,14 @@ struct SharedChain {
     }
 };
 
-// wavefronts per SIMD the kernel is built for: what the lane state and about 45 more registers allow
+// wavefronts per SIMD the kernel is built for: what the lane state and about 45 more registers allow, and no more
+// than four when the table's build holds three levels of 16 steps in registers (five spilled ten registers of it)
 template <int d, int N, int P>
 constexpr int shared_chain_min_waves()
 {
     constexpr int sz = Shape<d, N, P>::SZ;
-    return sz <= 60 ? 5 : sz <= 84 ? 4 : sz <= 124 ? 3 : 2;
+    constexpr int by_state = sz <= 60 ? 5 : sz <= 84 ? 4 : sz <= 124 ? 3 : 2;
+    return P >= 4 && by_state > 4 ? 4 : by_state;
 }
 
 constexpr int kSharedChainChunk = 16;   // steps of the table one thread builds (held in registers)

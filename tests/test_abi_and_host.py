@@ -357,3 +357,19 @@ def test_six_channels_at_depth_four_take_the_deeper_prefix_only_up_to_128_increm
         assert rc == binding.SIG_OK and pl.variant == binding.SIG_VARIANT_ON_CHIP and pl.prefix_depth == p, (B, L)
     rc, pl = binding.sig_plan(None, 128, 100, 6, 4, 1)
     assert rc == binding.SIG_OK and (pl.variant != binding.SIG_VARIANT_ON_CHIP or pl.prefix_depth == 2)
+
+
+def test_no_kernel_uses_private_memory():
+    """The build records what the compiler reports for every kernel (registers, LDS, private memory).  A kernel whose
+    per-lane arrays end up in private memory (an array the optimiser could not turn into registers, or spilled
+    vector registers) still computes the right thing, several times slower, and no parity test would notice."""
+    import json
+    import os
+    from paper_2501_08455_amd import build
+    if not os.path.exists(build.RESOURCES):
+        pytest.skip("no resource report beside the library (built by another build step)")
+    report = json.load(open(build.RESOURCES))
+    kernels = [(src, name, use) for src, ks in report.items() for name, use in ks.items()]
+    assert len(kernels) > 1000                      # every translation unit reported
+    bad = [(src, name) for src, name, use in kernels if use.get("ScratchSize", 0) or use.get("VGPRs Spill", 0)]
+    assert not bad, bad[:5]
