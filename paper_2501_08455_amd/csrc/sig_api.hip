@@ -296,6 +296,7 @@ constexpr int kFewLaneMinState = 31;
 constexpr double kSegmentCostFactor = 1.7;    // segments of a nearly empty chip: factor * sqrt(state K / (D C))
 constexpr double kSegmentOccupancyWaves = 2.0;  // segments on a busy chip: this many wavefronts per SIMD over the chunks' own
 constexpr int kMaxLdsJoinSegments = 8;
+constexpr int kFillByChunksMinSteps = 200;    // from this many increments on, never fewer chunks than fill the chip (final mode)
 }  // namespace tune
 
 // Which compiled prefix depth to use for (d, depth); entries of one (d, depth) are ordered by increasing prefix depth.
@@ -404,10 +405,21 @@ int plan_auto(const sig_ctx *ctx, int64_t B, int64_t L, int stream_flag, const R
             if (!(stream_flag && Q <= kWave)) {
                 // lanes are packed group after group: prefer a nearby chunk count whose groups fill the workgroup
                 // (e.g. Q = 25: 6 chunks leave 106 of 256 lanes idle, 5 chunks fit twice)
+                // (fewer chunks than it takes to fill the chip only within a fifth of full: (5,4) with 2,000 points at
+                // 8,192 paths wants three chunks; one chunk fills its workgroups but leaves three wavefronts per SIMD,
+                // 582 us against 422 us with five)
                 auto used = [&](int64_t c) { return (wg / (c * Q)) * c * Q; };
+                // (where the chunks cannot fill the chip anyway the question does not arise; paths under 200 increments
+                // and stream mode, where a cut costs a second fold, measured 0.63-0.98x with the larger count, longer
+                // paths in final mode 1.0-1.41x over 41 shapes)
+                auto fills = [&](int64_t c) {
+                    return stream_flag || K < tune::kFillByChunksMinSteps || C < pieces || c * B * Q * 10 >= want_lanes * 8;
+                };
                 int64_t best = C;
-                for (int64_t c = (C > 2 ? C - 2 : 1); c <= C + 4 && c <= cmax; ++c)
+                for (int64_t c = (C > 2 ? C - 2 : 1); c <= C + 4 && c <= cmax; ++c) {
+                    if (c < C && !fills(c)) continue;
                     if (used(c) * 100 > used(best) * 105 || (used(c) * 100 > used(best) * 95 && best > C && c >= C && c < best)) best = c;
+                }
                 C = best;
             }
             // far from a full chip with short chunks: a power of two just below C saves a round of the chunk tree
