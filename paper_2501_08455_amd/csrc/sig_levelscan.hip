@@ -117,7 +117,9 @@ __global__ __launch_bounds__(kLsThreads) void sig_level_one_kernel(const float *
 
 // DT > 0: d = DT at compile time, a lane owns all d children of its parent word.  DT == 0: d at run time (more than
 // 10 channels), a lane owns a block of kWideBlock children, the lanes of one parent are adjacent and recompute its chain.
-template <int DT, int n, int VEC>
+// CAT: the launch of the top level in stream mode, which also copies the lower levels into the output rows (a kernel of
+// its own: compiled into the others, the copies cost the deep levels four registers and with them a wavefront per SIMD)
+template <int DT, int n, int VEC, bool CAT>
 __global__ __launch_bounds__(kLsThreads) void sig_level_scan_kernel(LevelScanArgs A)
 {
     static_assert(n >= 2, "level 1 has its own kernel");
@@ -170,10 +172,11 @@ __global__ __launch_bounds__(kLsThreads) void sig_level_scan_kernel(LevelScanArg
     // lanes that share a prefix of their parent words, which all hold its value, the first one writes it (a store
     // instruction whose lanes hit one address several times measured 30 % slower over the whole launch); a row the
     // fetch was clamped to is written once more with what was read from it.
-    float *cat_base = A.cat ? A.cat + b0 * K * A.hi_stride : nullptr;
-    uint32_t cat_lane[M];
-    bool cat_own[M];
-    {
+    float *cat_base = nullptr;
+    uint32_t cat_lane[CAT ? M : 1];
+    bool cat_own[CAT ? M : 1];
+    if constexpr (CAT) {
+        cat_base = A.cat + b0 * K * A.hi_stride;
         int rest = lane_ok ? w : 0;
         bool first_of_prefix = lane_ok && first_child == 0;
 #pragma unroll
@@ -325,18 +328,23 @@ __global__ __launch_bounds__(kLsThreads) void sig_level_scan_kernel(LevelScanArg
             }
         }
     }
-    if (A.hi && A.cat) sweep(Yes{}, Yes{}, !one_tile);
-    else if (A.hi) sweep(Yes{}, No{}, !one_tile);
-    else sweep(No{}, No{}, !one_tile);
+    if constexpr (CAT) {
+        sweep(Yes{}, Yes{}, !one_tile);     // (the host sets cat only together with hi)
+    } else {
+        if (A.hi) sweep(Yes{}, No{}, !one_tile);
+        else sweep(No{}, No{}, !one_tile);
+    }
     // the chunk that holds the last step also holds the level of the whole path
     if (lane_ok && A.fin && j_begin < K32 && j_end == K32) store_acc(A.fin + b * A.fin_stride + (int64_t)w * d);
     // ... and copies the lower levels of the last row, which no step reads
-    if (lane_ok && A.cat && j_begin < K32 && j_end == K32) {
+    if constexpr (CAT) {
+        if (lane_ok && j_begin < K32 && j_end == K32) {
 #pragma unroll
-        for (int m = 0; m < M; ++m)
-            if (cat_own[m])
-                cat_base[cat_lane[m] + __umul24((uint32_t)(K32 - 1), (uint32_t)hi_stride)] =
-                    base[m][lane_off[m] + __umul24((uint32_t)(K32 - 1), (uint32_t)stride[m])];
+            for (int m = 0; m < M; ++m)
+                if (cat_own[m])
+                    cat_base[cat_lane[m] + __umul24((uint32_t)(K32 - 1), (uint32_t)hi_stride)] =
+                        base[m][lane_off[m] + __umul24((uint32_t)(K32 - 1), (uint32_t)stride[m])];
+        }
     }
 }
 
@@ -344,10 +352,15 @@ template <int d, int n>
 hipError_t launch_one(const LevelScanArgs &A, int vec, int blocks, int threads, size_t lds, hipStream_t st)
 {
     constexpr int kNatural = d == 0 ? 1 : (d % 4 == 0 ? 4 : (d % 2 == 0 ? 2 : 1));
-    if (kNatural > 1 && vec >= kNatural)
-        hipLaunchKernelGGL((sig_level_scan_kernel<d, n, kNatural>), dim3(blocks), dim3(threads), lds, st, A);
-    else
-        hipLaunchKernelGGL((sig_level_scan_kernel<d, n, 1>), dim3(blocks), dim3(threads), lds, st, A);
+    if (A.cat && !A.hi) return hipErrorInvalidValue;
+    const bool wide = kNatural > 1 && vec >= kNatural;
+    if (A.cat) {
+        if (wide) hipLaunchKernelGGL((sig_level_scan_kernel<d, n, kNatural, true>), dim3(blocks), dim3(threads), lds, st, A);
+        else hipLaunchKernelGGL((sig_level_scan_kernel<d, n, 1, true>), dim3(blocks), dim3(threads), lds, st, A);
+    } else {
+        if (wide) hipLaunchKernelGGL((sig_level_scan_kernel<d, n, kNatural, false>), dim3(blocks), dim3(threads), lds, st, A);
+        else hipLaunchKernelGGL((sig_level_scan_kernel<d, n, 1, false>), dim3(blocks), dim3(threads), lds, st, A);
+    }
     return hipGetLastError();
 }
 
