@@ -148,7 +148,7 @@ int sig_compute(sig_ctx *ctx, const float *path, int64_t B, int64_t L, int d, in
  * sig_compute for callers that cannot allocate device memory: code under HIP graph capture, tight serving
  * loops, harnesses that forbid hipMalloc.  Same arguments, same mapping, same kernels and the same results
  * as sig_compute, but the scratch that some mappings need (partial signatures of time segments that a second
- * launch joins; the lower-level tensors of the level-scan family in final mode) is a fixed array of
+ * launch joins; the lower-level tensors of the level-scan family) is a fixed array of
  * SIG_NOALLOC_SCRATCH_BYTES that is part of the library's code object: every GPU the library runs on holds
  * it from the library's first use until the process ends.  The call allocates and frees nothing and never
  * waits for the device.  A shape whose mapping needs more scratch than that is refused with
