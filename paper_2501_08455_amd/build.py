@@ -19,7 +19,7 @@ RESOURCES = os.path.join(OBJ, "kernel_resources.json")
 
 SOURCES = ["sig_api.hip", "sig_streaming.hip", "sig_onchip_table.hip", "sig_onchip_table_depth2.hip",
            "sig_onchip_table_depth3.hip", "sig_onchip_table_depth4.hip", "sig_onchip_table_depth56.hip", "sig_onchip_table_odd.hip",
-           "sig_backward.hip", "sig_backward_segments.hip", "sig_backward_general.hip", "sig_levelscan.hip", "sig_probe.hip"]
+           "sig_backward.hip", "sig_backward_segments.hip", "sig_backward_general.hip", "sig_levelscan.hip", "sig_levelscan_rows.hip", "sig_probe.hip"]
 
 # packed FP32 instructions are switched off for every device translation unit
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
