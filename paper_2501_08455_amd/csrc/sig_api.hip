@@ -330,7 +330,11 @@ const OnChipKernelInfo *pick_on_chip(int d, int depth, int stream_flag, int64_t 
         if (stream_flag && best_small &&
             (!best_few_lanes || (e->lanes_per_chunk < tune::kStreamDeepMinLanes && B > tune::kStreamDeepMaxPaths)))
             continue;
-        if (stream_flag || best->state_floats > tune::kSmallState || best->p == 0 || short_and_few) best = e;
+        // final mode, behind an entry with two lanes per path (two channels, p = 1): the next one (four lanes, half the
+        // state) measured 1.1-1.6x at every batch and length once it fits its small-state budget
+        const bool two_lanes = !stream_flag && best_small && best->lanes_per_chunk <= 2 &&
+                               e->state_floats <= tune::kSmallState && e->lanes_per_chunk <= 4;
+        if (stream_flag || best->state_floats > tune::kSmallState || best->p == 0 || short_and_few || two_lanes) best = e;
     }
     return best;
 }
