@@ -377,3 +377,18 @@ def test_no_kernel_uses_private_memory():
     assert len(kernels) > 1000                      # every translation unit reported
     bad = [(src, name) for src, name, use in kernels if use.get("ScratchSize", 0) or use.get("VGPRs Spill", 0)]
     assert not bad, bad[:5]
+
+
+def test_time_cut_fills_the_chip_on_long_paths():
+    """Final mode, paths of 200 increments or more: the planner does not trade the chunks that fill the chip for a
+    count that merely packs its workgroups better ((5,4) at 8,192 paths of 2,000 points once got one chunk: three
+    wavefronts per SIMD, 1.4 times slower than five chunks)."""
+    lanes_for_a_full_chip = 256 * 4 * 64 * 8
+    for d, depth, B, L in [(5, 4, 8192, 2000), (5, 4, 8192, 500), (5, 4, 6144, 2000), (3, 5, 8192, 1000), (9, 3, 4096, 2000)]:
+        rc, pl = binding.sig_plan(None, B, L, d, depth, 0)
+        assert rc == binding.SIG_OK and pl.variant == binding.SIG_VARIANT_ON_CHIP
+        lanes = B * d ** pl.prefix_depth * pl.chunks * pl.segments
+        assert lanes * 10 >= lanes_for_a_full_chip * 8, (d, depth, B, L, pl.as_dict())
+    # short paths keep the count that packs the workgroup (measured faster there)
+    rc, pl = binding.sig_plan(None, 8192, 100, 5, 4, 0)
+    assert rc == binding.SIG_OK and pl.chunks == 1
