@@ -228,7 +228,9 @@ int sig_combine(sig_ctx *ctx, const float *a, const float *b, int64_t B, int d, 
  * path up to its end and the gradient with respect to it, which a scan over the segments' own signatures provides.
  * Stream mode is cut the same way at smaller batches (two sweeps per segment and a scan over the segments between
  * them; the upstream gradient is read twice); paths too long for the staging in a batch that fills the chip, or too
- * long even for 32 segments, are walked in tiles of 256 increments by one workgroup.  Every shape
+ * long even for 32 segments, are walked in tiles of 256 increments by one workgroup; so are, in a batch that fills
+ * the chip, paths that fit the staging only a few at a time (kernels with 16 lanes per path or more; those with fewer
+ * are cut in time inside the workgroup there, as for few paths).  Every shape
  * without a register kernel, d <= 256, takes a general sweep, one workgroup per path with its state in LDS or
  * device scratch (much slower); SIG_ERR_UNSUPPORTED only for d > 256.
  * Context scratch (allocated on first use, SIG_ERR_ALLOC if that fails): shapes whose index space is cut into more

@@ -389,10 +389,29 @@ hipError_t backward_sliced_launch(const BackwardArgs &A0, float *scratch, int, i
 }
 
 // the register sweep needs device scratch only for paths it has to walk in tiles: the sums over the increments
+// The increments of a path fit LDS, but so few paths' worth of them that at most half of the lanes of 256 threads
+// would hold a path (long paths: (5,4) with 2,000 points takes 40 KB, one path and 25 lanes per workgroup).  On a batch
+// that fills the chip the plain sweep then runs 1.4-5.7 times slower than either alternative: the sweep cut in time
+// inside the workgroup (one path per workgroup, its chunks side by side), which wins for kernels with fewer than 16
+// lanes per path (measured 1.15-1.6x over the tiled walk), and the walk in tiles of kTiledSteps increments, which
+// wins for the others ((5,4) with 2,000 points at 16,384 paths: plain 24.3 ms, cut in time 10.9 ms, tiles 6.0 ms).
+constexpr int kStarvedChunkedMaxLanes = 16;
+template <int d, int N, int P>
+bool backward_starved(int64_t L)
+{
+    constexpr int Q = Shape<d, N, P>::Q;
+    if (backward_lds_bytes<d, N, P>(L, 1) > kMaxLdsBytes) return false;
+    int G = 256 / Q;
+    while (G > 1 && backward_lds_bytes<d, N, P>(L, G) > kMaxLdsBytes) --G;
+    return G * Q * 2 <= 256;
+}
+
 template <int d, int N, int P>
 int64_t backward_tiled_scratch_floats(int64_t B, int64_t L)
 {
-    return backward_lds_bytes<d, N, P>(L, 1) <= kMaxLdsBytes ? 0 : B * (L - 1) * d;
+    constexpr bool tiles_when_starved = Shape<d, N, P>::Q >= kStarvedChunkedMaxLanes;
+    const bool starved = tiles_when_starved && backward_starved<d, N, P>(L);
+    return backward_lds_bytes<d, N, P>(L, 1) <= kMaxLdsBytes && !starved ? 0 : B * (L - 1) * d;
 }
 
 // wavefronts per SIMD that the registers of a kernel allow (512 registers per lane of a SIMD, allocated in eights,
@@ -427,7 +446,11 @@ hipError_t backward_launch(const BackwardArgs &A0, float *scratch, int threads, 
     constexpr int Q = Shape<d, N, P>::Q;
     if (threads < Q || threads > 256 || threads % kWave) return hipErrorInvalidValue;
     BackwardArgs A = A0;
-    if (backward_lds_bytes<d, N, P>(A.L, 1) > kMaxLdsBytes) {
+    const int64_t few_lanes = A.stream_flag ? (int64_t)cus * kWave : (int64_t)cus * 4 * kWave * 2;
+    const bool starved = backward_starved<d, N, P>(A.L) && A.B * Q >= few_lanes;
+    const bool starved_tiles = starved && Q >= kStarvedChunkedMaxLanes && scratch;
+    const bool starved_chunks = starved && Q < kStarvedChunkedMaxLanes;
+    if (backward_lds_bytes<d, N, P>(A.L, 1) > kMaxLdsBytes || starved_tiles) {
         // the path's increments do not fit LDS at once: tiles of kTiledSteps increments, walked by one workgroup
         if (!scratch || (A.L - 1) / kTiledSteps > INT32_MAX / 2) return hipErrorInvalidValue;
         A.tiled = 1;
@@ -453,8 +476,7 @@ hipError_t backward_launch(const BackwardArgs &A0, float *scratch, int threads, 
     // Few paths (fewer lanes than two wavefronts per SIMD): cut the sweep in time, one workgroup per path with
     // as many chunks as its threads and LDS hold, at least eight increments each.
     // (stream mode reads the upstream gradient twice when cut, so only far below one wavefront per SIMD)
-    const int64_t few_lanes = A.stream_flag ? (int64_t)cus * kWave : (int64_t)cus * 4 * kWave * 2;
-    if (A.B * Q < few_lanes && A.B <= INT32_MAX) {
+    if ((A.B * Q < few_lanes || starved_chunks) && A.B <= INT32_MAX) {
         const int C = backward_chunks<d, N, P>(A.L, A.stream_flag, threads);
         if (C > 1) {
             A.groups = C;

@@ -349,3 +349,20 @@ def test_backward_saturated_variants_sampled(gpu, oracle, name, B):
     pick = np.sort(rng.choice(B, size=64, replace=False))
     pick[0], pick[-1] = 0, B - 1
     sampled_backward(gpu, oracle, x, cfg.depth, cfg.stream, pick, seed=3)
+
+
+@pytest.mark.parametrize("d,depth,L,B,stream", [
+    (5, 4, 700, 5400, False),     # 25 lanes per path, four paths' increments per workgroup: walked in tiles
+    (4, 4, 1200, 8300, False),    # 16 lanes per path: walked in tiles
+    (4, 3, 500, 33000, False),    # four lanes per path: cut in time inside the workgroup
+    (10, 2, 500, 1700, True),     # ten lanes per path, stream mode: cut in time inside the workgroup
+    (5, 4, 700, 700, True),       # stream mode, 25 lanes per path: walked in tiles
+])
+def test_backward_of_long_paths_in_a_batch_that_fills_the_chip(gpu, oracle, d, depth, L, B, stream):
+    """Paths whose increments fit the staging only a few at a time, in a batch large enough to fill the chip: the
+    sweep that keeps the lanes busy is taken instead of the plain one (tiles, or chunks side by side in a workgroup);
+    the oracle on six paths spread over the batch."""
+    x = workloads.brownian_paths(B, L, d, seed=900 + d + depth)
+    pick = [0, 1, B // 3, B // 2, B - 2, B - 1]
+    say("backward case d=%d depth=%d L=%d B=%d stream=%s, oracle on paths %s" % (d, depth, L, B, stream, pick))
+    sampled_backward(gpu, oracle, x, depth, stream, pick, seed=70 + d)
