@@ -288,8 +288,6 @@ constexpr int kDeepShortPath = 256;      // increments up to which a deeper entr
 constexpr int kDeepShortPathHeavy = 768; // ... behind a few-lane or heavy entry
 constexpr int kDeepShortPathWide = 128;  // ... when the deeper entry has more than 128 lanes per path
 constexpr int kDeepBatchFactorFewLanes = 4;   // batch limit of the deeper entry, in units of one wavefront per SIMD
-constexpr int kStreamDeepMinLanes = 8;   // stream mode: deeper entries with fewer lanes only up to ...
-constexpr int kStreamDeepMaxPaths = 512; // ... this many paths
 constexpr int kFinalWavesPerSimd = 8;    // occupancy the final-mode time cut aims for
 constexpr int kFewLaneMinChunkSteps = 12;     // chunks of few-lane kernels with states of 31-63 floats
 constexpr int kFewLaneMinState = 31;
@@ -325,11 +323,9 @@ const OnChipKernelInfo *pick_on_chip(int d, int depth, int stream_flag, int64_t 
         const int64_t few_lanes = (int64_t)cus * 4 * kWave * (best_few_lanes ? tune::kDeepBatchFactorFewLanes : 1);
         const bool short_and_few = !stream_flag && best_small && e->lanes_per_chunk < kThreads &&
                                    B * e->lanes_per_chunk * (kThreads / e->lanes_per_chunk) <= few_lanes && K <= short_path;
-        // stream mode, behind a small-state entry: only while that one has few lanes, and not with very few lanes per
-        // path on large batches
-        if (stream_flag && best_small &&
-            (!best_few_lanes || (e->lanes_per_chunk < tune::kStreamDeepMinLanes && B > tune::kStreamDeepMaxPaths)))
-            continue;
+        // stream mode, behind a small-state entry: only while that one has few lanes per path (the four-lane entry of
+        // two channels measured 1.9-4.4x over the two-lane one at 1,024 to 16,384 paths as well as below)
+        if (stream_flag && best_small && !best_few_lanes) continue;
         // final mode, behind an entry with two lanes per path (two channels, p = 1): the next one (four lanes, half the
         // state) measured 1.1-1.6x at every batch and length once it fits its small-state budget
         const bool two_lanes = !stream_flag && best_small && best->lanes_per_chunk <= 2 &&

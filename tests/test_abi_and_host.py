@@ -341,14 +341,13 @@ def test_deeper_prefix_entries_behind_the_first_small_state():
             rc, pl = binding.sig_plan(None, B, L, d, depth, stream)
             assert rc == binding.SIG_OK and pl.variant == binding.SIG_VARIANT_ON_CHIP, (d, depth, B, L)
             assert (pl.prefix_depth == p) if behind_two_lanes else (pl.prefix_depth < p), (d, depth, B, L)
-        # stream mode takes them only behind an entry with fewer than 16 lanes per path (and with four lanes per path
-        # only up to 512 paths)
+        # stream mode takes them only behind an entry with fewer than 16 lanes per path, at every batch
         for B, L in [(128, 100), (4, 50), (4096, 256)]:
             rc, pl = binding.sig_plan(None, B, L, d, depth, 1)
             assert rc == binding.SIG_OK
             if pl.variant != binding.SIG_VARIANT_ON_CHIP:
                 continue
-            if (d, depth) in [(4, 4), (5, 4), (3, 6), (6, 4)] or (d == 2 and depth < 6 and B > 512):
+            if (d, depth) in [(4, 4), (5, 4), (3, 6), (6, 4)]:
                 assert pl.prefix_depth < p, (d, depth, B, L)
             else:
                 assert pl.prefix_depth == p, (d, depth, B, L)
