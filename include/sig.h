@@ -64,7 +64,8 @@ enum sig_variant {
     /* the level-by-level formulation of the paper's Section 3.2 (Eqs. 6-10): one launch per level, each a
      * cumulative sum over time of per-step terms built from the lower levels of every prefix; those live in
      * context scratch of B * (L-1) * (D - d^depth) floats, in both modes (in stream mode the launch of the top level
-     * writes whole output rows, the lower levels it has read included).
+     * writes whole output rows, the lower levels it has read included); a batch that would need more than 8 GiB is
+     * taken in equal slices of paths that share the buffer, one after the other on the caller's stream.
      * d <= 256 (a template parameter up to 10, a run-time value above), depth <= 8.  Built to measure the paper's own design against the fused fold on the same chip (where a
      * fused kernel is compiled, that one is several times faster); sig_plan chooses it for shapes without an on-chip
      * kernel, where its parallelism in time beats the HBM-streaming sweep.  Plan fields used: chunks (time chunks per word and launch, at most 64; 0 = chosen

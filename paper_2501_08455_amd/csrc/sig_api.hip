@@ -335,13 +335,30 @@ const OnChipKernelInfo *pick_on_chip(int d, int depth, int stream_flag, int64_t 
     return best;
 }
 
+// The level-scan family keeps the levels below the top one of every prefix in scratch: a batch whose tensors would
+// exceed 8 GiB is taken in equal slices of paths, one after the other on the caller's stream, which share the
+// buffer (a slice of that size fills the chip many times over, so nothing is lost but the memory).
+constexpr int64_t kLevelScanSliceFloats = (int64_t)1 << 31;
+
+int64_t level_scan_slice_paths(int64_t B, int64_t L, const RowShape &rs, int stream_flag)
+{
+    const int64_t per_path = level_scan_scratch_floats(1, L, rs, stream_flag);
+    if (B <= 1 || per_path <= 0 || per_path <= kLevelScanSliceFloats / B) return B;
+    int64_t paths = kLevelScanSliceFloats / per_path;
+    if (paths < 1) paths = 1;
+    const int64_t slices = ceil_div(B, paths);
+    return ceil_div(B, slices);
+}
+
 // the level-scan family takes chunks >= 0 and ignores the other mapping fields
 int check_level_scan(int64_t B, int64_t L, const RowShape &rs, int stream_flag, const sig_plan_t &pl)
 {
     if (!level_scan_available(rs.d, rs.depth)) return SIG_ERR_INVALID;
     if (pl.chunks < 0) return SIG_ERR_INVALID;
-    if (B * rs.pow[rs.depth - 1] > INT32_MAX || !level_scan_fits(L, rs, stream_flag)) return SIG_ERR_TOO_LARGE;
-    const int64_t floats = level_scan_scratch_floats(B, L, rs, stream_flag);
+    if (!level_scan_fits(L, rs, stream_flag)) return SIG_ERR_TOO_LARGE;   // also bounds one path's scratch (2^31)
+    const int64_t S = level_scan_slice_paths(B, L, rs, stream_flag);
+    if (S * rs.pow[rs.depth - 1] > INT32_MAX) return SIG_ERR_TOO_LARGE;
+    const int64_t floats = level_scan_scratch_floats(S, L, rs, stream_flag);
     if (floats < 0 || floats > (int64_t)1 << 36) return SIG_ERR_TOO_LARGE;
     return SIG_OK;
 }
@@ -554,14 +571,15 @@ int plan_auto(const sig_ctx *ctx, int64_t B, int64_t L, int stream_flag, const R
     }
     // No on-chip kernel for this shape.  The level-by-level family is parallel in time and measured 2-25x faster
     // than the state-in-HBM sweep on every such shape (few paths above all), so it is the fallback wherever it
-    // applies (d <= 256, depth <= 8) and its scratch tensor stays below 8 GiB; the HBM-streaming family takes the rest.
+    // applies (d <= 256, depth <= 8) and the scratch tensor of one path stays below 8 GiB (larger batches go in
+    // slices); the HBM-streaming family takes the rest.
     if (B > 0) {
         sig_plan_t ls{};
         ls.variant = SIG_VARIANT_LEVEL_SCAN;
         ls.threads = kThreads;
         ls.segments = 1;
         if (check_level_scan(B, L, rs, stream_flag, ls) == SIG_OK &&
-            level_scan_scratch_floats(B, L, rs, stream_flag) <= (int64_t)1 << 31) {
+            level_scan_scratch_floats(1, L, rs, stream_flag) <= kLevelScanSliceFloats) {
             *pl = ls;
             return SIG_OK;
         }
@@ -650,14 +668,21 @@ int run_plan(sig_ctx *ctx, const float *path, int64_t B, int64_t L, const RowSha
     if (pl.variant == SIG_VARIANT_LEVEL_SCAN) {
         int rc = check_level_scan(B, L, rs, stream_flag, pl);
         if (rc != SIG_OK) return rc;
-        const int64_t floats = level_scan_scratch_floats(B, L, rs, stream_flag);
+        const int64_t S = level_scan_slice_paths(B, L, rs, stream_flag);
+        const int64_t floats = level_scan_scratch_floats(S, L, rs, stream_flag);
         float *work = nullptr;
         if (floats > 0) {
             rc = get_scratch(ctx, fixed, (size_t)floats * sizeof(float), &work);
             if (rc != SIG_OK) return rc;
         }
-        hipError_t e = launch_level_scan(path, out, work, B, L, rs, stream_flag, pl.chunks, ctx->num_cu, st);
-        return e == hipSuccess ? SIG_OK : SIG_ERR_HIP;
+        const int64_t out_per_path = stream_flag ? (L - 1) * rs.D : rs.D;
+        for (int64_t b0 = 0; b0 < B; b0 += S) {
+            const int64_t nb = B - b0 < S ? B - b0 : S;
+            hipError_t e = launch_level_scan(path + b0 * L * rs.d, out + b0 * out_per_path, work, nb, L, rs, stream_flag,
+                                             pl.chunks, ctx->num_cu, st);
+            if (e != hipSuccess) return SIG_ERR_HIP;
+        }
+        return SIG_OK;
     }
     if (pl.variant != SIG_VARIANT_ON_CHIP) return SIG_ERR_INVALID;
     const OnChipKernelInfo *ki = find_on_chip(rs.d, rs.depth, pl.prefix_depth);
@@ -810,7 +835,9 @@ int sig_plan_footprint(int64_t B, int64_t L, int d, int depth, int stream_flag, 
         if (rc != SIG_OK) return rc;
         lds = -1;   // one launch per level, each with its own geometry
         wgs = -1;
-        scratch = B > 0 ? level_scan_scratch_floats(B, L, rs, stream_flag) * (int64_t)sizeof(float) : 0;
+        scratch = B > 0 ? level_scan_scratch_floats(level_scan_slice_paths(B, L, rs, stream_flag), L, rs, stream_flag) *
+                              (int64_t)sizeof(float)
+                        : 0;
     } else if (plan->variant == SIG_VARIANT_ON_CHIP) {
         const OnChipKernelInfo *ki = find_on_chip(rs.d, rs.depth, plan->prefix_depth);
         OnChipArgs args{};
@@ -896,7 +923,7 @@ int sig_autotune(sig_ctx *ctx, int64_t B, int64_t L, int d, int depth, int strea
         ls.threads = kThreads;
         ls.segments = 1;
         if (base.variant != SIG_VARIANT_LEVEL_SCAN && check_level_scan(B, L, rs, stream_flag, ls) == SIG_OK &&
-            level_scan_scratch_floats(B, L, rs, stream_flag) <= (int64_t)1 << 31)
+            level_scan_scratch_floats(1, L, rs, stream_flag) <= kLevelScanSliceFloats)
             cand[n++] = ls;
     }
     for (int p = 0; p < depth && n < 20; ++p) {

@@ -72,8 +72,8 @@ def test_plan_of_the_five_configs_is_on_chip_and_consistent(name):
 
 
 def test_plan_falls_back_for_uncompiled_shapes():
-    """Without an on-chip kernel: the level-by-level family where it applies (d <= 256, depth <= 8, scratch below
-    8 GiB), else the HBM-streaming family."""
+    """Without an on-chip kernel: the level-by-level family where it applies (d <= 256, depth <= 8, levels short
+    enough for 32-bit offsets), else the HBM-streaming family."""
     for stream in (0, 1):
         rc, pl = binding.sig_plan(None, 7, 30, 9, 6, stream)
         assert rc == binding.SIG_OK and pl.variant == binding.SIG_VARIANT_LEVEL_SCAN
@@ -85,7 +85,15 @@ def test_plan_falls_back_for_uncompiled_shapes():
         assert 0 <= pl.prefix_depth <= 1
         rc, pl = binding.sig_plan(None, 7, 30, 2, 9, stream)       # deeper than 8
         assert rc == binding.SIG_OK and pl.variant == binding.SIG_VARIANT_HBM_STREAMING
-    rc, pl = binding.sig_plan(None, 512, 1000, 9, 6, 0)            # lower levels of every prefix: 136 GB of scratch
+    # lower levels of every prefix: 136 GB for the batch, which is therefore taken in slices that need 8 GiB at most
+    rc, pl = binding.sig_plan(None, 512, 1000, 9, 6, 0)
+    assert rc == binding.SIG_OK and pl.variant == binding.SIG_VARIANT_LEVEL_SCAN
+    rc, _, _, scratch = binding.sig_plan_footprint(512, 1000, 9, 6, 0, pl)
+    assert rc == binding.SIG_OK and 4 << 30 < scratch <= 8 << 30
+    per_path = 999 * (binding.sig_size(9, 6) - 9 ** 6) * 4
+    assert scratch % per_path == 0 and 512 % (scratch // per_path) == 0      # 16 equal slices of 32 paths
+    # one path of a level too long for the family's 32-bit offsets
+    rc, pl = binding.sig_plan(None, 2, 500, 9, 8, 0)
     assert rc == binding.SIG_OK and pl.variant == binding.SIG_VARIANT_HBM_STREAMING
 
 

@@ -116,3 +116,31 @@ def test_saturated_variants_sampled(gpu, oracle, name, B):
     got = out[torch.from_numpy(pick).cuda()].cpu().numpy()
     want = oracle.signature(x[pick], cfg.depth, stream=cfg.stream)
     assert_parity(got, want, x[pick], cfg.depth, cfg.stream)
+
+
+@pytest.mark.parametrize("B,L,d,depth,stream", [(65536, 30, 3, 8, False), (24576, 30, 3, 8, True)])
+def test_batches_whose_lower_levels_exceed_the_scratch_limit_go_in_slices(gpu, oracle, B, L, d, depth, stream):
+    """The lower levels of every prefix of these batches would take 25 and 9.3 GB: the planner's own choice for
+    them (no on-chip kernel) runs the family on equal slices of the batch that share 8 GiB or less.  Sampled
+    paths on both sides of every slice boundary against the oracle; every row checked for having been written."""
+    import torch
+    rc, pl = gpu.sig_plan(None, B, L, d, depth, int(stream))
+    assert rc == gpu.SIG_OK and pl.variant == gpu.SIG_VARIANT_LEVEL_SCAN
+    rc, _, _, scratch = gpu.sig_plan_footprint(B, L, d, depth, int(stream), pl)
+    D = gpu.sig_size(d, depth)
+    per_path = (L - 1) * (D - d ** depth) * 4
+    assert rc == gpu.SIG_OK and scratch <= 8 << 30 and scratch % per_path == 0
+    S = scratch // per_path
+    assert S < B
+    rng = np.random.default_rng(B + L)
+    x = np.cumsum(rng.normal(0, 1.0 / np.sqrt(L), size=(B, L, d)), axis=1).astype(np.float32)
+    say("level-scan sliced batch B=%d L=%d d=%d depth=%d stream=%s slice=%d" % (B, L, d, depth, stream, S))
+    out = torch.full((B, L - 1, D) if stream else (B, D), float("nan"), dtype=torch.float32, device="cuda")
+    gpu.signature(torch.from_numpy(x).cuda(), depth, stream=stream, out=out)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(out).all())
+    edges = [b for s in range(S, B, S) for b in (s - 1, s)]
+    pick = np.unique(np.concatenate([[0, B - 1], edges, rng.choice(B, size=8, replace=False)]))
+    got = out[torch.from_numpy(pick).cuda()].cpu().numpy()
+    want = oracle.signature(x[pick], depth, stream=stream)
+    assert_parity(got, want, x[pick], depth, stream)
