@@ -116,7 +116,8 @@ __device__ __forceinline__ void backward_step(const Lane<d, N, P> &ln, Lane<d, N
 }
 
 // ad (+)= row, laid out like an output row; the prefix words are taken by the lane whose remaining letters are 0
-template <int d, int N, int P, bool ADD>
+// OWNED = false leaves the choice of the lane that takes a prefix word to the caller: every lane gets the value
+template <int d, int N, int P, bool ADD, bool OWNED = true>
 __device__ __forceinline__ void load_adjoint(const float *row, unsigned u, Lane<d, N, P> &ad)
 {
     using Sh = Shape<d, N, P>;
@@ -131,14 +132,40 @@ __device__ __forceinline__ void load_adjoint(const float *row, unsigned u, Lane<
         }
     });
     if constexpr (P == 0 && !ADD) ad.s[0] = 0.0f;
+    // (!OWNED: every lane loads.  A load under a condition would keep the compiler from counting the loads in
+    // flight, and a sweep that fetches rows ahead would wait for all of them at every step)
     static_for<1, P>([&](auto mc) __attribute__((always_inline)) {
         constexpr int m = decltype(mc)::value;
         constexpr unsigned span = cpow(d, P - m);
         float g = 0.0f;
-        if (u % span == 0) g = row[Sh::row_off(m) + u / span];
+        if (!OWNED || u % span == 0) g = row[Sh::row_off(m) + u / span];
         if constexpr (ADD) ad.pre[m - 1] += g;
         else ad.pre[m - 1] = g;
     });
+}
+
+// The lanes that take the prefix words of a row (word u_{1:m}: the lane whose remaining letters are 0), for rows
+// fetched with OWNED = false, and the sum ad += row of such a row.  The choice is made where the row is used and not
+// where it is fetched: a fetch that masks its own loads waits for them at once, and a sweep that fetches rows ahead
+// of their use would have nothing in flight.
+template <int d, int N, int P>
+struct PrefixOwner {
+    bool w[Shape<d, N, P>::NPRE];
+    __device__ __forceinline__ explicit PrefixOwner(unsigned u)
+    {
+#pragma unroll
+        for (int i = 0; i < Shape<d, N, P>::NPRE; ++i) w[i] = i + 1 < P && u % cpow(d, P - 1 - i) == 0;
+    }
+};
+template <int d, int N, int P>
+__device__ __forceinline__ void add_row(Lane<d, N, P> &ad, const Lane<d, N, P> &row, const PrefixOwner<d, N, P> &own,
+                                        bool use = true)
+{
+    using Sh = Shape<d, N, P>;
+#pragma unroll
+    for (int i = 0; i < Sh::SZ; ++i) ad.s[i] += use ? row.s[i] : 0.0f;
+#pragma unroll
+    for (int i = 0; i < Sh::NPRE; ++i) ad.pre[i] += (use && own.w[i]) ? row.pre[i] : 0.0f;
 }
 
 struct BackwardArgs {
@@ -209,9 +236,12 @@ constexpr int kTiledSteps = 256;
 // TSV: steps whose partial sums are parked before they are added up; 0 = reduce_steps, the most that is useful.
 // Fewer steps take less LDS, which buys resident workgroups on saturated batches (kShortPark, see backward_launch).
 constexpr int kShortPark = 3;
-template <int d, int N, int P, bool STREAM, bool SEG = false, bool EMIT = true, int TSV = 0>
+// PIPE (stream mode, uncut): the upstream rows are fetched as a software pipeline that keeps PD rows in flight
+// at every step; for launches that leave the SIMDs a wavefront each or less, where nothing else hides a row's latency.
+template <int d, int N, int P, bool STREAM, bool SEG = false, bool EMIT = true, int TSV = 0, bool PIPE = false>
 __global__ __launch_bounds__(256) void sig_backward_kernel(BackwardArgs A)
 {
+    static_assert(!PIPE || (STREAM && !SEG), "the pipelined fetch belongs to the uncut stream sweep");
     static_assert(EMIT || (STREAM && SEG), "the sweep without output belongs to the stream-mode cut");
     using Sh = Shape<d, N, P>;
     constexpr int Q = Sh::Q;
@@ -286,14 +316,20 @@ __global__ __launch_bounds__(256) void sig_backward_kernel(BackwardArgs A)
     using Pk = Park<d, P>;
     float *mypark = park + (size_t)gi * TS * Pk::kStepFloats;
     float *myrow = tile + gi * row_floats;
+    const PrefixOwner<d, N, P> owner(u);
     // One step of the sweep; `upk` is the upstream gradient of row k (stream mode).
     auto step = [&](int64_t k, const Lane<d, N, P> *upk) __attribute__((always_inline)) {
         const int ts = (int)((K - 1 - k) % TS);
         if constexpr (STREAM) {
+            // (rows behind the end of the path, in the filled-up last piece of a cut sweep, count as zero)
+            if constexpr (PIPE) {
+                add_row<d, N, P>(ad, *upk, owner);
+            } else {
 #pragma unroll
-            for (int i = 0; i < Sh::SZ; ++i) ad.s[i] += upk->s[i];
+                for (int i = 0; i < Sh::SZ; ++i) ad.s[i] += upk->s[i];
 #pragma unroll
-            for (int i = 0; i < Sh::NPRE; ++i) ad.pre[i] += upk->pre[i];
+                for (int i = 0; i < Sh::NPRE; ++i) ad.pre[i] += upk->pre[i];
+            }
         }
         Inc<d, P> inc, neg;
         load_inc<d, P>(inc, myrow + k * d, letter);
@@ -327,7 +363,56 @@ __global__ __launch_bounds__(256) void sig_backward_kernel(BackwardArgs A)
             }
         }
     };
-    if constexpr (STREAM) {
+    // A wavefront none of whose lanes has a path (the workgroup's paths need not fill its threads) only keeps the
+    // other wavefronts' barriers company: one pair for every TS steps.
+    const int first_group = __builtin_amdgcn_readfirstlane(tid) / Q;
+    const bool idle_wavefront = !(first_group < G && b0 + first_group < rows);
+    if (idle_wavefront) {
+        if constexpr (EMIT) {
+            for (int64_t e = 0; e < (K + TS - 1) / TS; ++e) {
+                __syncthreads();
+                __syncthreads();
+            }
+        }
+    } else if constexpr (STREAM && PIPE) {
+        // The upstream gradient rows are fetched PD steps ahead into registers, as in the plain stream sweep
+        // below, but every lane fetches at every step, from a row that exists: the compiler waits for a fetched row
+        // by counting the loads issued after it, and a load under a condition makes that count zero, i.e. a wait
+        // for everything in flight (the plain sweep waits like that once in PD steps).  Idle lanes read the first
+        // path's rows; the fetches behind the first row read it again.  One fetch per call, in the order of the sweep.
+        constexpr int PD = Sh::SZ <= 24 ? 4 : Sh::SZ <= 48 ? 2 : 1;
+        Lane<d, N, P> up[PD];
+        const float *next_row = A.grad_out + (b * Kall + (Kall - 1)) * D;
+        int64_t kn = K - 1;
+        auto fetch = [&](Lane<d, N, P> &dst) __attribute__((always_inline)) {
+            load_adjoint<d, N, P, false, false>(next_row, u, dst);
+            next_row -= kn > 0 ? D : 0;
+            --kn;
+        };
+        static_for<0, PD>([&](auto jc) __attribute__((always_inline)) {
+            constexpr int j = decltype(jc)::value;
+            identity_state<d, N, P>(up[j]);   // (the fields that a row does not fill)
+            fetch(up[j]);
+        });
+        int64_t kk = K - 1;
+        for (; kk >= PD - 1; kk -= PD) {
+            static_for<0, PD>([&](auto jc) __attribute__((always_inline)) {
+                constexpr int j = decltype(jc)::value;
+                step(kk - j, &up[j]);
+                // (the loads stay behind the step that uses the row they replace: moved up, they would need
+                // registers of their own and a copy at the top of the loop, which waits for every row in flight;
+                // arithmetic and LDS reads of the next step may pass them)
+                __builtin_amdgcn_sched_barrier(0);
+                fetch(up[j]);
+                __builtin_amdgcn_sched_barrier(0x81);
+            });
+        }
+        // the K % PD steps that are left
+        static_for<0, PD - 1>([&](auto jc) __attribute__((always_inline)) {
+            constexpr int j = decltype(jc)::value;
+            if (kk - j >= 0) step(kk - j, &up[j]);
+        });
+    } else if constexpr (STREAM) {
         // The upstream gradient rows are fetched PD steps ahead into registers: a row's HBM latency (well over
         // a microsecond) is several steps long, and at one or two wavefronts per SIMD nothing else hides it.
         // (as many rows as the registers hold beside the two lane states)
@@ -446,6 +531,7 @@ __global__ __launch_bounds__(256) void sig_backward_tiled_kernel(BackwardArgs A)
     const bool active = gi_raw < G && b0 + gi_raw < A.B;
     const int gi = gi_raw < G ? gi_raw : 0;
     const int64_t b = active ? b0 + gi : 0;
+    const PrefixOwner<d, N, P> owner(u);
 
     int letter[P > 0 ? P : 1];
     letter[0] = 0;
@@ -468,7 +554,7 @@ __global__ __launch_bounds__(256) void sig_backward_tiled_kernel(BackwardArgs A)
     if (P == 0) { ad.s[0] = 0.0f; up.s[0] = 0.0f; }
     if (active) {
         load_state<d, N, P>(STREAM ? A.sig + (b * Kall + (Kall - 1)) * D : A.sig + b * D, u, ln);
-        if constexpr (STREAM) load_adjoint<d, N, P, false>(A.grad_out + (b * Kall + (Kall - 1)) * D, u, up);
+        if constexpr (STREAM) load_adjoint<d, N, P, false, false>(A.grad_out + (b * Kall + (Kall - 1)) * D, u, up);
         else load_adjoint<d, N, P, false>(A.grad_out + b * D, u, ad);
     }
 
@@ -491,11 +577,8 @@ __global__ __launch_bounds__(256) void sig_backward_tiled_kernel(BackwardArgs A)
         for (int64_t k = K - 1; k >= 0; --k) {
             const int ts = (int)((K - 1 - k) % TS);
             if constexpr (STREAM) {
-#pragma unroll
-                for (int i = 0; i < Sh::SZ; ++i) ad.s[i] += up.s[i];
-#pragma unroll
-                for (int i = 0; i < Sh::NPRE; ++i) ad.pre[i] += up.pre[i];
-                if (active && k0 + k > 0) load_adjoint<d, N, P, false>(A.grad_out + (b * Kall + (k0 + k - 1)) * D, u, up);
+                add_row<d, N, P>(ad, up, owner);
+                if (active && k0 + k > 0) load_adjoint<d, N, P, false, false>(A.grad_out + (b * Kall + (k0 + k - 1)) * D, u, up);
             }
             Inc<d, P> inc, neg;
             load_inc<d, P>(inc, myrow + k * d, letter);

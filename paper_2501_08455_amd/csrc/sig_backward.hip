@@ -178,6 +178,7 @@ __global__ __launch_bounds__(256) void sig_backward_chunked_kernel(BackwardArgs 
     float *mypark = rowsE + c * ROW;
     using Pk = Park<d, P>;
     constexpr int PD = !STREAM ? 1 : Sh::SZ <= 24 ? 4 : Sh::SZ <= 48 ? 2 : 1;
+    const PrefixOwner<d, N, P> owner(u);
     auto sweep = [&](auto emit_tag) __attribute__((always_inline)) {
         constexpr bool EMIT = decltype(emit_tag)::value;
         Lane<d, N, P> up[PD];
@@ -187,7 +188,7 @@ __global__ __launch_bounds__(256) void sig_backward_chunked_kernel(BackwardArgs 
                 identity_state<d, N, P>(up[j]);
                 const int t = T - 1 - j;
                 if (t >= 0 && t < steps)
-                    load_adjoint<d, N, P, false>(A.grad_out + (b * K + (c * T + t)) * D, u, up[j]);
+                    load_adjoint<d, N, P, false, false>(A.grad_out + (b * K + (c * T + t)) * D, u, up[j]);
             });
         }
         for (int t0 = T - 1; t0 >= 0; t0 -= PD) {
@@ -202,10 +203,7 @@ __global__ __launch_bounds__(256) void sig_backward_chunked_kernel(BackwardArgs 
                     if (t < steps) {
                         const int k = c * T + t;
                         if constexpr (STREAM) {
-#pragma unroll
-                            for (int i = 0; i < Sh::SZ; ++i) ad.s[i] += up[j].s[i];
-#pragma unroll
-                            for (int i = 0; i < Sh::NPRE; ++i) ad.pre[i] += up[j].pre[i];
+                            add_row<d, N, P>(ad, up[j], owner);
                         }
                         Inc<d, P> inc, neg;
                         load_inc<d, P>(inc, tile + k * d, letter);
@@ -221,7 +219,7 @@ __global__ __launch_bounds__(256) void sig_backward_chunked_kernel(BackwardArgs 
                     if constexpr (STREAM) {
                         const int tn = t - PD;
                         if (tn >= 0 && tn < steps)
-                            load_adjoint<d, N, P, false>(A.grad_out + (b * K + (c * T + tn)) * D, u, up[j]);
+                            load_adjoint<d, N, P, false, false>(A.grad_out + (b * K + (c * T + tn)) * D, u, up[j]);
                     }
                     if constexpr (EMIT) {
                         if (active) {
@@ -523,7 +521,14 @@ hipError_t backward_launch(const BackwardArgs &A0, float *scratch, int threads, 
             return hipGetLastError();
         }
     }
-    if (A.stream_flag)
+    // Stream mode on a launch that leaves the SIMDs a wavefront each or less: the upstream rows as a software pipeline
+    // (measured against the plain fetch: (4,4), 256 points, 1,024 paths 156 -> 114 us; (3,5), 100 points, 4,096
+    // paths 162 -> 134; with more wavefronts than SIMDs it loses 3-10 %: its rows in flight evict each other's
+    // lines from the vector cache, whose requests to L2 rise by a fifth).
+    const int64_t busy_wavefronts = grid * (((int64_t)G * Q + kWave - 1) / kWave);
+    if (A.stream_flag && busy_wavefronts <= (int64_t)cus * 4)
+        hipLaunchKernelGGL((sig_backward_kernel<d, N, P, true, false, true, 0, true>), dim3((unsigned)grid), dim3(threads), lds, st, A);
+    else if (A.stream_flag)
         hipLaunchKernelGGL((sig_backward_kernel<d, N, P, true>), dim3((unsigned)grid), dim3(threads), lds, st, A);
     else
         hipLaunchKernelGGL((sig_backward_kernel<d, N, P, false>), dim3((unsigned)grid), dim3(threads), lds, st, A);
