@@ -110,9 +110,11 @@ __device__ __forceinline__ void load_private(const float *buf, unsigned u, Lane<
 //                    start; the lanes of chunk 0 then walk the chunks from the last to the first   (T steps, C products)
 //   4. every chunk runs the reverse sweep over its own increments from (S_end(c), A_end(c))       (T steps)
 // so the critical path is about 2 T (stream: 3 T) steps and 2 C short products instead of C T steps.
-template <int d, int N, int P, bool STREAM>
+// PIPE (stream mode): the fetch of the upstream rows as a software pipeline, see sig_backward_kernel.
+template <int d, int N, int P, bool STREAM, bool PIPE = false>
 __global__ __launch_bounds__(256) void sig_backward_chunked_kernel(BackwardArgs A)
 {
+    static_assert(!PIPE || STREAM, "the pipelined fetch belongs to stream mode");
     using Sh = Shape<d, N, P>;
     constexpr int Q = Sh::Q;
     constexpr int D = Sh::D;
@@ -182,68 +184,105 @@ __global__ __launch_bounds__(256) void sig_backward_chunked_kernel(BackwardArgs 
     auto sweep = [&](auto emit_tag) __attribute__((always_inline)) {
         constexpr bool EMIT = decltype(emit_tag)::value;
         Lane<d, N, P> up[PD];
+        // Stream mode: the upstream rows of the chunk, one fetch per step in the order of the sweep, PD steps
+        // ahead and without conditions (see the PIPE sweep of sig_backward_kernel): row min(c T + max(t, 0), K - 1)
+        // for t = T - 1, T - 2, ...; rows of steps that the chunk does not have are fetched and not used.
+        const int top = c * T + T - 1 < K - 1 ? c * T + T - 1 : K - 1;
+        [[maybe_unused]] const float *next_row = A.grad_out + (b * K + top) * D;
+        [[maybe_unused]] int tn = T - 1;
+        [[maybe_unused]] auto fetch = [&](Lane<d, N, P> &dst) __attribute__((always_inline)) {
+            load_adjoint<d, N, P, false, false>(next_row, u, dst);
+            next_row -= (tn > 0 && c * T + tn <= K - 1) ? D : 0;
+            --tn;
+        };
         if constexpr (STREAM) {
             static_for<0, PD>([&](auto jc) __attribute__((always_inline)) {
                 constexpr int j = decltype(jc)::value;
                 identity_state<d, N, P>(up[j]);
-                const int t = T - 1 - j;
-                if (t >= 0 && t < steps)
-                    load_adjoint<d, N, P, false, false>(A.grad_out + (b * K + (c * T + t)) * D, u, up[j]);
-            });
-        }
-        for (int t0 = T - 1; t0 >= 0; t0 -= PD) {
-            static_for<0, PD>([&](auto jc) __attribute__((always_inline)) {
-                constexpr int j = decltype(jc)::value;
-                const int t = t0 - j;
-                if (t >= 0) {
-                    const int ts = (T - 1 - t) % TS;
-                    float dbar[d];
-#pragma unroll
-                    for (int a = 0; a < d; ++a) dbar[a] = 0.0f;
-                    if (t < steps) {
-                        const int k = c * T + t;
-                        if constexpr (STREAM) {
-                            add_row<d, N, P>(ad, up[j], owner);
-                        }
-                        Inc<d, P> inc, neg;
-                        load_inc<d, P>(inc, tile + k * d, letter);
-#pragma unroll
-                        for (int a = 0; a < d; ++a) neg.v[a] = -inc.v[a];
-                        neg.du[0] = 0.0f;
-#pragma unroll
-                        for (int m = 0; m < P; ++m) neg.du[m] = -inc.du[m];
-                        if (k > 0) fused_step<d, N, P>(ln, neg);
-                        else identity_state<d, N, P>(ln);
-                        backward_step<d, N, P>(ln, ad, inc, letter, dbar);
-                    }
-                    if constexpr (STREAM) {
-                        const int tn = t - PD;
-                        if (tn >= 0 && tn < steps)
-                            load_adjoint<d, N, P, false, false>(A.grad_out + (b * K + (c * T + tn)) * D, u, up[j]);
-                    }
-                    if constexpr (EMIT) {
-                        if (active) {
-#pragma unroll
-                            for (int a = 0; a < d; ++a) mypark[Pk::at(ts, (int)u, a)] = dbar[a];
-                        }
-                        if (ts == TS - 1 || t == 0) {
-                            __syncthreads();
-                            if (active) {
-                                for (int col = (int)u; col < (ts + 1) * d; col += Q) {
-                                    const int tp = col / d, a = col - tp * d;
-                                    const int tt = t + (ts - tp);  // step of this chunk the column belongs to
-                                    if (tt < steps) {
-                                        float sum = 0.0f;
-                                        for (int q = 0; q < Q; ++q) sum += mypark[Pk::at(tp, q, a)];
-                                        tile[(c * T + tt) * d + a] = sum;
-                                    }
-                                }
-                            }
-                            __syncthreads();
-                        }
-                    }
+                if constexpr (PIPE) {
+                    fetch(up[j]);
+                } else {
+                    const int t = T - 1 - j;
+                    if (t >= 0 && t < steps)
+                        load_adjoint<d, N, P, false, false>(A.grad_out + (b * K + (c * T + t)) * D, u, up[j]);
                 }
             });
+        }
+        // one step of the sweep; `refill` runs between the arithmetic and the parked sums (the plain fetch of the
+        // row that replaces `row`)
+        auto one = [&](int t, const Lane<d, N, P> &row, auto refill) __attribute__((always_inline)) {
+            const int ts = (T - 1 - t) % TS;
+            float dbar[d];
+#pragma unroll
+            for (int a = 0; a < d; ++a) dbar[a] = 0.0f;
+            if (t < steps) {
+                const int k = c * T + t;
+                if constexpr (STREAM) add_row<d, N, P>(ad, row, owner);
+                Inc<d, P> inc, neg;
+                load_inc<d, P>(inc, tile + k * d, letter);
+#pragma unroll
+                for (int a = 0; a < d; ++a) neg.v[a] = -inc.v[a];
+                neg.du[0] = 0.0f;
+#pragma unroll
+                for (int m = 0; m < P; ++m) neg.du[m] = -inc.du[m];
+                if (k > 0) fused_step<d, N, P>(ln, neg);
+                else identity_state<d, N, P>(ln);
+                backward_step<d, N, P>(ln, ad, inc, letter, dbar);
+            }
+            refill();
+            if constexpr (EMIT) {
+                if (active) {
+#pragma unroll
+                    for (int a = 0; a < d; ++a) mypark[Pk::at(ts, (int)u, a)] = dbar[a];
+                }
+                if (ts == TS - 1 || t == 0) {
+                    __syncthreads();
+                    if (active) {
+                        for (int col = (int)u; col < (ts + 1) * d; col += Q) {
+                            const int tp = col / d, a = col - tp * d;
+                            const int tt = t + (ts - tp);  // step of this chunk the column belongs to
+                            if (tt < steps) {
+                                float sum = 0.0f;
+                                for (int q = 0; q < Q; ++q) sum += mypark[Pk::at(tp, q, a)];
+                                tile[(c * T + tt) * d + a] = sum;
+                            }
+                        }
+                    }
+                    __syncthreads();
+                }
+            }
+        };
+        if constexpr (PIPE) {
+            int t0 = T - 1;
+            for (; t0 >= PD - 1; t0 -= PD) {
+                static_for<0, PD>([&](auto jc) __attribute__((always_inline)) {
+                    constexpr int j = decltype(jc)::value;
+                    one(t0 - j, up[j], [] {});
+                    __builtin_amdgcn_sched_barrier(0);
+                    fetch(up[j]);
+                    __builtin_amdgcn_sched_barrier(0x81);
+                });
+            }
+            static_for<0, PD - 1>([&](auto jc) __attribute__((always_inline)) {
+                constexpr int j = decltype(jc)::value;
+                if (t0 - j >= 0) one(t0 - j, up[j], [] {});
+            });
+        } else {
+            for (int t0 = T - 1; t0 >= 0; t0 -= PD) {
+                static_for<0, PD>([&](auto jc) __attribute__((always_inline)) {
+                    constexpr int j = decltype(jc)::value;
+                    const int t = t0 - j;
+                    if (t >= 0) {
+                        one(t, up[j], [&]() __attribute__((always_inline)) {
+                            if constexpr (STREAM) {
+                                const int tnext = t - PD;
+                                if (tnext >= 0 && tnext < steps)
+                                    load_adjoint<d, N, P, false, false>(A.grad_out + (b * K + (c * T + tnext)) * D, u, up[j]);
+                            }
+                        });
+                    }
+                });
+            }
         }
     };
 
@@ -479,7 +518,14 @@ hipError_t backward_launch(const BackwardArgs &A0, float *scratch, int threads, 
         if (C > 1) {
             A.groups = C;
             const size_t lds = (size_t)backward_chunked_lds_bytes<d, N, P>(A.L, C, A.stream_flag);
-            if (A.stream_flag)
+            // (stream mode fetches the upstream rows as a pipeline where four rows fit the registers and the launch
+            // leaves the SIMDs a wavefront each or less: (4,4), 256 points, 128 paths 45 -> 37 us; with two rows,
+            // or on fuller chips, the plain fetch is up to a quarter faster)
+            constexpr bool kFourRows = Shape<d, N, P>::SZ <= 24;
+            const int64_t busy_wavefronts = A.B * (((int64_t)C * Q + kWave - 1) / kWave);
+            if (A.stream_flag && kFourRows && busy_wavefronts <= (int64_t)cus * 4)
+                hipLaunchKernelGGL((sig_backward_chunked_kernel<d, N, P, true, kFourRows>), dim3((unsigned)A.B), dim3(threads), lds, st, A);
+            else if (A.stream_flag)
                 hipLaunchKernelGGL((sig_backward_chunked_kernel<d, N, P, true>), dim3((unsigned)A.B), dim3(threads), lds, st, A);
             else
                 hipLaunchKernelGGL((sig_backward_chunked_kernel<d, N, P, false>), dim3((unsigned)A.B), dim3(threads), lds, st, A);
