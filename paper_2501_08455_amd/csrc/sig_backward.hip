@@ -486,7 +486,19 @@ hipError_t backward_launch(const BackwardArgs &A0, float *scratch, int threads, 
     const int64_t few_lanes = A.stream_flag ? (int64_t)cus * kWave : (int64_t)cus * 4 * kWave * 2;
     const bool starved = backward_starved<d, N, P>(A.L) && A.B * Q >= few_lanes;
     const bool starved_tiles = starved && Q >= kStarvedChunkedMaxLanes && scratch;
-    const bool starved_chunks = starved && Q < kStarvedChunkedMaxLanes;
+    bool starved_chunks = starved && Q < kStarvedChunkedMaxLanes;
+    if (starved_chunks && N >= 3) {
+        // ... unless the plain sweep still keeps enough lanes on a CU.  The cut in time sweeps every increment
+        // three times (stream mode; twice in final mode) and multiplies whole rows between the chunks, which costs
+        // more the deeper the signature: measured on 14 shapes x 64 ... 2,000 points x 2,048 ... 32,768 paths, the plain
+        // sweep is 1.1-7x faster above these lane counts (stream mode, 256 points, 8,192 paths: (2,6) 2,504 -> 501
+        // us, (3,4) 843 -> 261, (5,3) 636 -> 426) and up to 5x slower below them; at depth 2 the cut always wins.
+        int G = threads / Q;
+        while (G > 1 && backward_lds_bytes<d, N, P>(A.L, G) > kMaxLdsBytes) --G;
+        const int64_t lanes = resident_sweep_workgroups<d, N, P>(A.L, A.stream_flag, threads, G, 0) * G * Q;
+        const int64_t enough = !A.stream_flag ? 224 : N >= 4 ? 56 : 112;
+        if (lanes >= enough) starved_chunks = false;
+    }
     if (backward_lds_bytes<d, N, P>(A.L, 1) > kMaxLdsBytes || starved_tiles) {
         // the path's increments do not fit LDS at once: tiles of kTiledSteps increments, walked by one workgroup
         if (!scratch || (A.L - 1) / kTiledSteps > INT32_MAX / 2) return hipErrorInvalidValue;

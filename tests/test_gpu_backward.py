@@ -357,6 +357,11 @@ def test_backward_saturated_variants_sampled(gpu, oracle, name, B):
     (4, 3, 500, 33000, False),    # four lanes per path: cut in time inside the workgroup
     (10, 2, 500, 1700, True),     # ten lanes per path, stream mode: cut in time inside the workgroup
     (5, 4, 700, 700, True),       # stream mode, 25 lanes per path: walked in tiles
+    # the same kind of shape with paths short enough for the plain sweep to keep enough lanes on a CU: not cut
+    (2, 6, 128, 8200, True),      # two lanes per path, stream mode (pipelined fetch would not apply: the chip is full)
+    (3, 4, 256, 8200, True),      # three lanes per path, stream mode
+    (5, 3, 128, 33000, False),    # five lanes per path, final mode
+    (3, 3, 500, 8200, True),      # stream mode, depth 3 with too few lanes left: still cut in time
 ])
 def test_backward_of_long_paths_in_a_batch_that_fills_the_chip(gpu, oracle, d, depth, L, B, stream):
     """Paths whose increments fit the staging only a few at a time, in a batch large enough to fill the chip: the
