@@ -293,7 +293,9 @@ def training_step(workloads, L, d, depth, steps, warmup):
         with torch.no_grad():
             for p_, g_ in zip(params, grads):
                 p_ -= 1e-3 * g_
-        return loss
+        # (detached: a loss that is kept would keep the step's autograd graph, and with it the parameters' gradient
+        # nodes and the stream they were made on, alive into the capture below, which torch warns can break it)
+        return loss.detach()
 
     def one_epoch():
         loss = None
@@ -317,10 +319,56 @@ def training_step(workloads, L, d, depth, steps, warmup):
     loss = one_epoch()
     e1.record()
     torch.cuda.synchronize()
+    ms_epoch = e0.elapsed_time(e1)
+    final_loss = float(loss)
+
+    # The same step as a HIP graph (one launch per step): one graph for the full batch, one for the ragged last batch;
+    # a batch is copied into the graph's input tensors before every replay, inside the timed region.
+    last = TRAIN_SAMPLES % TRAIN_BATCH
+    del loss
+    gparams = [p_.detach().clone().requires_grad_(True) for p_ in params]   # parameters of their own, no history
+    graphs = {}
+    for nb in sorted({TRAIN_BATCH, last} - {0}):
+        xb, yb = X[:nb].clone(), Y[:nb].clone()
+
+        def graph_step(xb=xb, yb=yb):
+            Z = torch.tanh(xb @ gparams[0] + gparams[1])
+            S = autograd.signature(Z, depth)
+            loss_ = ((S @ gparams[2] + gparams[3] - yb) ** 2).mean()
+            grads = torch.autograd.grad(loss_, gparams)
+            with torch.no_grad():
+                for p_, g_ in zip(gparams, grads):
+                    p_ -= 1e-3 * g_
+            return loss_.detach()
+        graphs[nb] = (xb, yb) + autograd.capture(graph_step)
+
+    def graph_replay(lo, hi):
+        xb, yb, graph, loss_ = graphs[hi - lo]
+        xb.copy_(X[lo:hi])
+        yb.copy_(Y[lo:hi])
+        graph.replay()
+        return loss_
+
+    for _ in range(warmup):
+        graph_replay(0, TRAIN_BATCH)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(steps):
+        graph_replay(0, TRAIN_BATCH)
+    e1.record()
+    torch.cuda.synchronize()
+    ms_step_graph = e0.elapsed_time(e1) / steps
+    e0.record()
+    for lo in range(0, TRAIN_SAMPLES, TRAIN_BATCH):
+        loss_g = graph_replay(lo, min(lo + TRAIN_BATCH, TRAIN_SAMPLES))
+    e1.record()
+    torch.cuda.synchronize()
     return {"model": "Dense(20->%d, tanh) -> signature depth %d -> Dense(%d->10), MSE, SGD" % (d, depth, D),
             "batch": TRAIN_BATCH, "length": L, "ms_per_step": ms_step, "samples": TRAIN_SAMPLES,
-            "steps_per_epoch": (TRAIN_SAMPLES + TRAIN_BATCH - 1) // TRAIN_BATCH, "last_batch": TRAIN_SAMPLES % TRAIN_BATCH,
-            "ms_per_epoch": e0.elapsed_time(e1), "final_loss": float(loss.detach())}
+            "steps_per_epoch": (TRAIN_SAMPLES + TRAIN_BATCH - 1) // TRAIN_BATCH, "last_batch": last,
+            "ms_per_epoch": ms_epoch, "final_loss": final_loss,
+            "ms_per_step_graph": ms_step_graph, "ms_per_epoch_graph": e0.elapsed_time(e1),
+            "final_loss_graph": float(loss_g)}
 
 
 def anchors(binding):

@@ -132,3 +132,55 @@ def test_an_epoch_over_the_ragged_set_runs_and_lowers_the_loss(oracle):
     after = full_loss()
     say("  loss over the set: %.4f -> %.4f" % (before, after))
     assert after < before
+
+
+@pytest.mark.parametrize("L,d,depth,B", [(100, 5, 4, 128), (200, 6, 3, 93)])
+def test_training_step_as_a_graph_replays_like_the_eager_step(L, d, depth, B):
+    """The whole step (both Dense layers, the signature layer forward and backward, the update) captured once as a HIP
+    graph and replayed on four different batches, with eager work and synchronisation between the replays: after every
+    replay the parameters equal those of the same steps run eagerly from the same start."""
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2501_08455_amd import autograd, workloads
+    D = workloads.sig_size(d, depth)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(5 + L)
+    batches = [(torch.randn((B, L, 20), device="cuda", generator=gen).cumsum(1) / L ** 0.5,
+                torch.randn((B, 10), device="cuda", generator=gen)) for _ in range(4)]
+    start = [torch.randn((20, d), device="cuda", generator=gen) * 0.2, torch.zeros(d, device="cuda"),
+             torch.randn((D, 10), device="cuda", generator=gen) * 0.05, torch.zeros(10, device="cuda")]
+
+    def make(params, xb, yb):
+        def step():
+            Z = torch.tanh(xb @ params[0] + params[1])
+            S = autograd.signature(Z, depth)
+            loss = ((S @ params[2] + params[3] - yb) ** 2).mean()
+            grads = torch.autograd.grad(loss, params)
+            with torch.no_grad():
+                for p_, g_ in zip(params, grads):
+                    p_ -= 1e-2 * g_
+            return loss
+        return step
+
+    eager = [p.clone().requires_grad_(True) for p in start]
+    graphed = [p.clone().requires_grad_(True) for p in start]
+    xb, yb = batches[0][0].clone(), batches[0][1].clone()
+    graph_step = make(graphed, xb, yb)
+    say("capturing the step L=%d d=%d depth=%d B=%d" % (L, d, depth, B))
+    graph, loss_g = autograd.capture(graph_step)
+    with torch.no_grad():                      # the warm-up and the capture moved the parameters: start again
+        for p_, s_ in zip(graphed, start):
+            p_.copy_(s_)
+    for i, (x, y) in enumerate(batches):
+        say("replay %d" % i)
+        xb.copy_(x)
+        yb.copy_(y)
+        graph.replay()
+        loss_e = make(eager, x, y)()           # the program's own eager work between the replays
+        torch.cuda.synchronize()
+        lg, le = float(loss_g.detach()), float(loss_e.detach())
+        assert np.isfinite(lg) and abs(lg - le) <= 1e-5 * abs(le)
+        for pg, pe in zip(graphed, eager):
+            err = float((pg - pe).norm() / pe.norm().clamp_min(1e-30))
+            assert err <= 1e-5, (i, err)
