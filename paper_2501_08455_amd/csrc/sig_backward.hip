@@ -510,6 +510,10 @@ hipError_t backward_launch(const BackwardArgs &A0, float *scratch, int threads, 
         const int64_t per_cu = (A.B + cus - 1) / (cus > 0 ? cus : 1);
         if ((int64_t)G > per_cu) G = per_cu > 1 ? (int)per_cu : 1;
         while (G > 1 && backward_lds_bytes<d, N, P>(kTiledSteps + 1, G) > kMaxLdsBytes) --G;
+        if (per_cu > G) {   // the same number of paths on every CU, see below
+            const int64_t rounds = (per_cu + G - 1) / G;
+            G = (int)((per_cu + rounds - 1) / rounds);
+        }
         const size_t lds = (size_t)backward_lds_bytes<d, N, P>(kTiledSteps + 1, G);
         const int64_t grid = (A.B + G - 1) / G;
         if (lds > (size_t)kMaxLdsBytes || grid <= 0 || grid > INT32_MAX) return hipErrorInvalidValue;
@@ -549,6 +553,12 @@ hipError_t backward_launch(const BackwardArgs &A0, float *scratch, int threads, 
     const int64_t per_cu = (A.B + cus - 1) / (cus > 0 ? cus : 1);
     if ((int64_t)G > per_cu) G = per_cu > 1 ? (int)per_cu : 1;
     while (G > 1 && backward_lds_bytes<d, N, P>(A.L, G) > kMaxLdsBytes) --G;
+    // ... and the same number of paths on every CU: with 16 paths per CU and room for 12 per workgroup, workgroups of 8
+    // put two on every CU where workgroups of 12 put two on a third of the CUs and one on the rest
+    if (per_cu > G) {
+        const int64_t rounds = (per_cu + G - 1) / G;
+        G = (int)((per_cu + rounds - 1) / rounds);
+    }
     // Parked steps: the most that is useful, unless fewer keep more workgroups resident on a batch that fills
     // the chip.  Measured at kShortPark against the most: (5,4) at 65,536 paths 749 -> 698 us, (6,4) 352 -> 333,
     // (8,3) 895 -> 657, (5,4) of 300 points 1199 -> 950; where the residency is the same (stream mode, whose
