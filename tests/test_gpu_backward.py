@@ -371,3 +371,33 @@ def test_backward_of_long_paths_in_a_batch_that_fills_the_chip(gpu, oracle, d, d
     pick = [0, 1, B // 3, B // 2, B - 2, B - 1]
     say("backward case d=%d depth=%d L=%d B=%d stream=%s, oracle on paths %s" % (d, depth, L, B, stream, pick))
     sampled_backward(gpu, oracle, x, depth, stream, pick, seed=70 + d)
+
+
+def _random_backward_cases():
+    """Seeded draws over the compiled shapes: batches from one path to a few thousand (so that workgroups end ragged,
+    a CU's share of paths is split over several rounds, and both the pipelined and the plain fetch of the upstream rows
+    are taken), lengths from 2 points up, both modes."""
+    rng = np.random.default_rng(20250108)
+    shapes = [(2, 2), (2, 3), (2, 4), (2, 5), (2, 6), (3, 2), (3, 3), (3, 4), (3, 5), (3, 6), (4, 2), (4, 3), (4, 4),
+              (4, 5), (5, 2), (5, 3), (5, 4), (5, 5), (6, 2), (6, 3), (6, 4), (7, 2), (7, 3), (7, 4), (8, 2), (8, 3),
+              (9, 2), (9, 3), (10, 2), (10, 3)]
+    cases = []
+    for i in range(60):
+        d, depth = shapes[int(rng.integers(len(shapes)))]
+        D = workloads.sig_size(d, depth)
+        stream = bool(rng.integers(2))
+        L = int(rng.choice([2, 3, 5, 9, 17, 33, 64, 100, 131, 257, 300]))
+        B = int(rng.choice([1, 2, 7, 31, 100, 257, 700, 1500, 2900, 4500]))
+        while B > 1 and B * (L - 1 if stream else 1) * D * 4 > 3e8:
+            B //= 2
+        cases.append((d, depth, L, B, stream, i))
+    return cases
+
+
+@pytest.mark.parametrize("d,depth,L,B,stream,seed", _random_backward_cases())
+def test_backward_random_shapes(gpu, oracle, d, depth, L, B, stream, seed):
+    x = workloads.brownian_paths(B, L, d, seed=4000 + seed)
+    rng = np.random.default_rng(seed)
+    pick = sorted(set([0, B - 1] + [int(v) for v in rng.integers(0, B, size=10)]))
+    say("backward random case d=%d depth=%d L=%d B=%d stream=%s, oracle on %d paths" % (d, depth, L, B, stream, len(pick)))
+    sampled_backward(gpu, oracle, x, depth, stream, pick, seed=500 + seed)
