@@ -288,6 +288,7 @@ constexpr int kDeepShortPath = 256;      // increments up to which a deeper entr
 constexpr int kDeepShortPathHeavy = 768; // ... behind a few-lane or heavy entry
 constexpr int kDeepShortPathWide = 128;  // ... when the deeper entry has more than 128 lanes per path
 constexpr int kDeepBatchFactorFewLanes = 4;   // batch limit of the deeper entry, in units of one wavefront per SIMD
+constexpr int kStreamFewLanes = 10;      // stream mode: kernels with at most this many lanes per path aim at two wavefronts per SIMD
 constexpr int kFinalWavesPerSimd = 8;    // occupancy the final-mode time cut aims for
 constexpr int kFewLaneMinChunkSteps = 12;     // chunks of few-lane kernels with states of 31-63 floats
 constexpr int kFewLaneMinState = 31;
@@ -386,6 +387,11 @@ int plan_auto(const sig_ctx *ctx, int64_t B, int64_t L, int stream_flag, const R
             if (by_vgpr < 1) by_vgpr = 1;
             if (by_vgpr < tune::kFinalWavesPerSimd) want_lanes = simd_lanes * by_vgpr;
         }
+        // stream mode, kernels with at most ten lanes per path (each lane stores a long stretch of every row): two
+        // wavefronts per SIMD.  Planner against autotuner on 16 shapes x 50 ... 1,000 points x 64 ... 16,384 paths: the tuner
+        // doubled the chunks of these kernels almost everywhere (1.2-1.8x at 1,024 and 4,096 paths) and halved or
+        // kept those of the kernels with 16 lanes or more (twice the chunks: 0.8-0.9x there).
+        if (stream_flag && Q <= tune::kStreamFewLanes) want_lanes = 2 * simd_lanes;
         pl->variant = SIG_VARIANT_ON_CHIP;
         pl->prefix_depth = ki->p;
         pl->chunks = 1;
