@@ -288,6 +288,8 @@ constexpr int kDeepShortPath = 256;      // increments up to which a deeper entr
 constexpr int kDeepShortPathHeavy = 768; // ... behind a few-lane or heavy entry
 constexpr int kDeepShortPathWide = 128;  // ... when the deeper entry has more than 128 lanes per path
 constexpr int kDeepBatchFactorFewLanes = 4;   // batch limit of the deeper entry, in units of one wavefront per SIMD
+constexpr int kStreamDeepShortPath = 128;   // stream mode, under-filled chip: the entry behind a small state up to this many increments ...
+constexpr int kStreamDeepHeavyState = 32;   // ... or at any length behind a small state of more floats than this
 constexpr int kStreamFewLanes = 10;      // stream mode: kernels with at most this many lanes per path aim at two wavefronts per SIMD
 constexpr int kFinalWavesPerSimd = 8;    // occupancy the final-mode time cut aims for
 constexpr int kFewLaneMinChunkSteps = 12;     // chunks of few-lane kernels with states of 31-63 floats
@@ -326,7 +328,15 @@ const OnChipKernelInfo *pick_on_chip(int d, int depth, int stream_flag, int64_t 
                                    B * e->lanes_per_chunk * (kThreads / e->lanes_per_chunk) <= few_lanes && K <= short_path;
         // stream mode, behind a small-state entry: only while that one has few lanes per path (the four-lane entry of
         // two channels measured 1.9-4.4x over the two-lane one at 1,024 to 16,384 paths as well as below)
-        if (stream_flag && best_small && !best_few_lanes) continue;
+        // ... or the batch leaves the small-state entry at most half a wavefront per SIMD and the deeper one fits a
+        // workgroup: more lanes per path and lighter steps then, on short paths (up to 128 increments) and behind the
+        // heavier small states (more than 32 floats).  Measured on (4,4), (5,4), (6,4) over 50 ... 1,000 points and
+        // 16 ... 4,096 paths: (6,4) up to 256 paths 1.2-2.8x (50 points, 64 paths: 33 -> 13 us), (4,4) with up to 100
+        // points 1.06-1.5x; long paths of (4,4) and (5,4) 0.8-0.95x, hence the two conditions.
+        const bool stream_underfilled = e->lanes_per_chunk <= kThreads &&
+                                        B * best->lanes_per_chunk * 2 <= (int64_t)cus * 4 * kWave &&
+                                        (K <= tune::kStreamDeepShortPath || best->state_floats > tune::kStreamDeepHeavyState);
+        if (stream_flag && best_small && !best_few_lanes && !stream_underfilled) continue;
         // final mode, behind an entry with two lanes per path (two channels, p = 1): the next one (four lanes, half the
         // state) measured 1.1-1.6x at every batch and length once it fits its small-state budget
         const bool two_lanes = !stream_flag && best_small && best->lanes_per_chunk <= 2 &&

@@ -275,16 +275,22 @@ def test_prefix_depth_follows_the_batch_for_ten_channels_at_depth_four():
 
 def test_small_batches_of_short_paths_take_the_deeper_prefix_for_five_channels_at_depth_four():
     """d = 5 at depth 4: p = 3 with four chunks in a workgroup of 512 threads while the batch leaves the chip mostly
-    idle and the path is short; otherwise, and in stream mode, p = 2 in 256 threads."""
+    idle and the path is short; otherwise p = 2 in 256 threads.  Stream mode takes p = 3 (256 threads) on short paths
+    of a batch that leaves p = 2 at most half a wavefront per SIMD, and p = 2 otherwise."""
     for B, L in [(128, 100), (1, 100), (32, 50), (256, 200)]:
         rc, pl = binding.sig_plan(None, B, L, 5, 4, 0)
         assert rc == binding.SIG_OK and pl.variant == binding.SIG_VARIANT_ON_CHIP
         assert (pl.prefix_depth, pl.chunks, pl.threads) == (3, 4, 512), (B, L)
         assert binding.sig_plan_validate(B, L, 5, 4, 0, pl) == binding.SIG_OK
-    for B, L, stream in [(512, 100, 0), (128, 300, 0), (128, 2000, 0), (128, 100, 1), (4, 50, 1)]:
+    for B, L, stream in [(512, 100, 0), (128, 300, 0), (128, 2000, 0), (128, 300, 1), (2048, 100, 1)]:
         rc, pl = binding.sig_plan(None, B, L, 5, 4, stream)
         assert rc == binding.SIG_OK and pl.variant == binding.SIG_VARIANT_ON_CHIP
         assert pl.prefix_depth == 2 and pl.threads <= 256, (B, L, stream)
+    for B, L in [(128, 100), (4, 50), (1024, 129)]:
+        rc, pl = binding.sig_plan(None, B, L, 5, 4, 1)
+        assert rc == binding.SIG_OK and pl.variant == binding.SIG_VARIANT_ON_CHIP
+        assert pl.prefix_depth == 3 and pl.threads <= 256, (B, L)
+        assert binding.sig_plan_validate(B, L, 5, 4, 1, pl) == binding.SIG_OK
 
 
 def test_small_batches_take_wide_workgroups_for_small_states_with_many_lanes():
@@ -349,13 +355,14 @@ def test_deeper_prefix_entries_behind_the_first_small_state():
             rc, pl = binding.sig_plan(None, B, L, d, depth, stream)
             assert rc == binding.SIG_OK and pl.variant == binding.SIG_VARIANT_ON_CHIP, (d, depth, B, L)
             assert (pl.prefix_depth == p) if behind_two_lanes else (pl.prefix_depth < p), (d, depth, B, L)
-        # stream mode takes them only behind an entry with fewer than 16 lanes per path, at every batch
+        # stream mode takes them behind an entry with fewer than 16 lanes per path, at every batch; behind the others
+        # ((4,4): 16 lanes, (3,6): 27) on short paths of batches that leave the chip at most half a wavefront per SIMD
         for B, L in [(128, 100), (4, 50), (4096, 256)]:
             rc, pl = binding.sig_plan(None, B, L, d, depth, 1)
             assert rc == binding.SIG_OK
             if pl.variant != binding.SIG_VARIANT_ON_CHIP:
                 continue
-            if (d, depth) in [(4, 4), (5, 4), (3, 6), (6, 4)]:
+            if (d, depth) in [(4, 4), (3, 6)] and B == 4096:
                 assert pl.prefix_depth < p, (d, depth, B, L)
             else:
                 assert pl.prefix_depth == p, (d, depth, B, L)
@@ -366,8 +373,11 @@ def test_six_channels_at_depth_four_take_the_deeper_prefix_only_up_to_128_increm
     for B, L, p in [(128, 100, 3), (64, 20, 3), (256, 129, 3), (128, 200, 2), (128, 257, 2), (512, 100, 2)]:
         rc, pl = binding.sig_plan(None, B, L, 6, 4, 0)
         assert rc == binding.SIG_OK and pl.variant == binding.SIG_VARIANT_ON_CHIP and pl.prefix_depth == p, (B, L)
-    rc, pl = binding.sig_plan(None, 128, 100, 6, 4, 1)
-    assert rc == binding.SIG_OK and (pl.variant != binding.SIG_VARIANT_ON_CHIP or pl.prefix_depth == 2)
+    # stream mode: p = 3 at any length while p = 2 (36 lanes of 43 floats) would leave the chip at most half a wavefront
+    # per SIMD, p = 2 beyond
+    for B, L, p in [(128, 100, 3), (256, 1000, 3), (900, 50, 3), (1024, 100, 2), (4096, 50, 2)]:
+        rc, pl = binding.sig_plan(None, B, L, 6, 4, 1)
+        assert rc == binding.SIG_OK and pl.variant == binding.SIG_VARIANT_ON_CHIP and pl.prefix_depth == p, (B, L)
 
 
 def test_no_kernel_uses_private_memory():
