@@ -483,8 +483,19 @@ hipError_t backward_launch(const BackwardArgs &A0, float *scratch, int threads, 
     constexpr int Q = Shape<d, N, P>::Q;
     if (threads < Q || threads > 256 || threads % kWave) return hipErrorInvalidValue;
     BackwardArgs A = A0;
-    const int64_t few_lanes = A.stream_flag ? (int64_t)cus * kWave : (int64_t)cus * 4 * kWave * 2;
-    const bool starved = backward_starved<d, N, P>(A.L) && A.B * Q >= few_lanes;
+    // Lanes below which the sweep is cut in time inside the workgroup (one path per workgroup).  The cut sweeps every
+    // increment twice (three times in stream mode) and multiplies rows between the chunks, so it pays only while the
+    // plain sweep would leave the chip nearly empty: final mode below one wavefront per SIMD, half of one for paths of
+    // up to 128 increments of kernels with fewer than 64 lanes per path (14 shapes x 32 ... 500 points x 128 ... 8,192 paths against a limit of two: (5,4), 100 points,
+    // 4,096 paths 208 -> 80 us, (3,5), 32 points, 8,192 paths 120 -> 31; long paths between half a wavefront and one
+    // lose 10-45 % with the lower limit); stream mode below a wavefront per CU.
+    const int64_t full_lanes = (int64_t)cus * 4 * kWave * 2;
+    const int64_t few_lanes = A.stream_flag ? (int64_t)cus * kWave
+                              : (A.L - 1 <= 128 && Q < kWave) ? (int64_t)cus * 4 * kWave / 2 : (int64_t)cus * 4 * kWave;
+    // (a shape that fills at most half of its lanes keeps the cut up to two wavefronts per SIMD, from where it is
+    // walked in tiles or cut anyway, see backward_starved)
+    const bool half_empty = backward_starved<d, N, P>(A.L);
+    const bool starved = half_empty && A.B * Q >= (A.stream_flag ? few_lanes : full_lanes);
     const bool starved_tiles = starved && Q >= kStarvedChunkedMaxLanes && scratch;
     bool starved_chunks = starved && Q < kStarvedChunkedMaxLanes;
     if (starved_chunks && N >= 3) {
@@ -529,7 +540,7 @@ hipError_t backward_launch(const BackwardArgs &A0, float *scratch, int threads, 
     // Few paths (fewer lanes than two wavefronts per SIMD): cut the sweep in time, one workgroup per path with
     // as many chunks as its threads and LDS hold, at least eight increments each.
     // (stream mode reads the upstream gradient twice when cut, so only far below one wavefront per SIMD)
-    if ((A.B * Q < few_lanes || starved_chunks) && A.B <= INT32_MAX) {
+    if ((A.B * Q < few_lanes || (!A.stream_flag && half_empty && A.B * Q < full_lanes) || starved_chunks) && A.B <= INT32_MAX) {
         const int C = backward_chunks<d, N, P>(A.L, A.stream_flag, threads);
         if (C > 1) {
             A.groups = C;
