@@ -492,24 +492,32 @@ hipError_t backward_launch(const BackwardArgs &A0, float *scratch, int threads, 
     const int64_t full_lanes = (int64_t)cus * 4 * kWave * 2;
     const int64_t few_lanes = A.stream_flag ? (int64_t)cus * kWave
                               : (A.L - 1 <= 128 && Q < kWave) ? (int64_t)cus * 4 * kWave / 2 : (int64_t)cus * 4 * kWave;
-    // (a shape that fills at most half of its lanes keeps the cut up to two wavefronts per SIMD, from where it is
-    // walked in tiles or cut anyway, see backward_starved)
-    const bool half_empty = backward_starved<d, N, P>(A.L);
-    const bool starved = half_empty && A.B * Q >= (A.stream_flag ? few_lanes : full_lanes);
-    const bool starved_tiles = starved && Q >= kStarvedChunkedMaxLanes && scratch;
-    bool starved_chunks = starved && Q < kStarvedChunkedMaxLanes;
-    if (starved_chunks && N >= 3) {
-        // ... unless the plain sweep still keeps enough lanes on a CU.  The cut in time sweeps every increment
-        // three times (stream mode; twice in final mode) and multiplies whole rows between the chunks, which costs
-        // more the deeper the signature: measured on 14 shapes x 64 ... 2,000 points x 2,048 ... 32,768 paths, the plain
-        // sweep is 1.1-7x faster above these lane counts (stream mode, 256 points, 8,192 paths: (2,6) 2,504 -> 501
-        // us, (3,4) 843 -> 261, (5,3) 636 -> 426) and up to 5x slower below them; at depth 2 the cut always wins.
+    // A shape that fills at most half of a workgroup's lanes (see backward_starved) ...
+    bool half_empty = backward_starved<d, N, P>(A.L);
+    if (half_empty && Q < kStarvedChunkedMaxLanes && N >= 3) {
+        // ... unless, for the kernels with few lanes per path, the plain sweep still keeps enough lanes on a CU.  The
+        // cut in time sweeps every increment three times (stream mode; twice in final mode) and multiplies whole rows
+        // between the chunks, which costs more the deeper the signature: measured on 14 shapes x 64 ... 2,000 points x
+        // 2,048 ... 32,768 paths, the plain sweep is 1.1-7x faster above these lane counts (stream mode, 256 points,
+        // 8,192 paths: (2,6) 2,504 -> 501 us, (3,4) 843 -> 261, (5,3) 636 -> 426) and up to 5x slower below them; at
+        // depth 2 the cut always wins.
         int G = threads / Q;
         while (G > 1 && backward_lds_bytes<d, N, P>(A.L, G) > kMaxLdsBytes) --G;
         const int64_t lanes = resident_sweep_workgroups<d, N, P>(A.L, A.stream_flag, threads, G, 0) * G * Q;
         const int64_t enough = !A.stream_flag ? 224 : N >= 4 ? 56 : 112;
-        if (lanes >= enough) starved_chunks = false;
+        if (lanes >= enough) half_empty = false;
     }
+    // ... keeps the cut further: final mode up to two wavefronts per SIMD; stream mode, where the row products between
+    // the chunks are cheap (depth up to 3, or rows of up to 400 floats), up to two wavefronts per CU, four for kernels
+    // with 64 lanes per path or more ((4,4), 500 points, 1,024 paths 381 -> 269 us; (8,3), 256 points, 512 paths 176
+    // -> 111; (10,3), 512 paths 239 -> 141; (5,4), (6,4), (4,5) lose 15-35 % there).  From there on it is walked in
+    // tiles, or cut anyway if it has fewer than 16 lanes per path.
+    constexpr bool cheap_products = N <= 3 || Shape<d, N, P>::D <= 400;
+    const int64_t half_empty_lanes = !A.stream_flag ? full_lanes
+                                     : cheap_products ? few_lanes * (Q >= kWave ? 4 : 2) : few_lanes;
+    const bool starved = half_empty && A.B * Q >= half_empty_lanes;
+    const bool starved_tiles = starved && Q >= kStarvedChunkedMaxLanes && scratch;
+    const bool starved_chunks = starved && Q < kStarvedChunkedMaxLanes;
     if (backward_lds_bytes<d, N, P>(A.L, 1) > kMaxLdsBytes || starved_tiles) {
         // the path's increments do not fit LDS at once: tiles of kTiledSteps increments, walked by one workgroup
         if (!scratch || (A.L - 1) / kTiledSteps > INT32_MAX / 2) return hipErrorInvalidValue;
@@ -540,7 +548,7 @@ hipError_t backward_launch(const BackwardArgs &A0, float *scratch, int threads, 
     // Few paths (fewer lanes than two wavefronts per SIMD): cut the sweep in time, one workgroup per path with
     // as many chunks as its threads and LDS hold, at least eight increments each.
     // (stream mode reads the upstream gradient twice when cut, so only far below one wavefront per SIMD)
-    if ((A.B * Q < few_lanes || (!A.stream_flag && half_empty && A.B * Q < full_lanes) || starved_chunks) && A.B <= INT32_MAX) {
+    if ((A.B * Q < few_lanes || (half_empty && A.B * Q < half_empty_lanes) || starved_chunks) && A.B <= INT32_MAX) {
         const int C = backward_chunks<d, N, P>(A.L, A.stream_flag, threads);
         if (C > 1) {
             A.groups = C;
