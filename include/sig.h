@@ -231,7 +231,8 @@ int sig_combine(sig_ctx *ctx, const float *a, const float *b, int64_t B, int d, 
  * them; the upstream gradient is read twice); paths too long for the staging in a batch that fills the chip, or too
  * long even for 32 segments, are walked in tiles of 256 increments by one workgroup; so are, in a batch that fills
  * the chip, paths that fit the staging only a few at a time (kernels with 16 lanes per path or more; those with fewer
- * are cut in time inside the workgroup there, as for few paths).  Every shape
+ * are cut in time inside the workgroup there, as for few paths, unless the plain sweep still keeps enough lanes busy).
+ * Which sweep a call takes never changes its result beyond the rounding order.  Every shape
  * without a register kernel, d <= 256, takes a general sweep, one workgroup per path with its state in LDS or
  * device scratch (much slower); SIG_ERR_UNSUPPORTED only for d > 256.
  * Context scratch (allocated on first use, SIG_ERR_ALLOC if that fails): shapes whose index space is cut into more
