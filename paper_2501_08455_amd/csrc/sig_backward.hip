@@ -443,11 +443,33 @@ bool backward_starved(int64_t L)
     return G * Q * 2 <= 256;
 }
 
+// Kernels with fewer than 16 lanes per path whose LDS holds fewer paths than a workgroup has lanes for (the
+// increments of a path take L d floats for a handful of lanes): on a batch that needs the plain sweep's resident
+// workgroups more than one and a half times over (final mode), the paths are walked in short tiles instead, sized so that a full
+// workgroup's tiles take 32 KB and two or more workgroups stay on a CU.  Measured: (5,3), 100 points, 65,536 paths
+// 461 -> 303 us; stream mode, 256 points, 16,384 paths 1,001 -> 685; (6,3), (7,3), (3,4), (2,6) at 100 points
+// 1.25-1.35x; on a chip that the plain sweep fills about once it loses 20-40 %.  Returns the tile length, 0 if the
+// shape is not of this kind.
+template <int d, int N, int P>
+int backward_short_tile(int64_t L, int threads)
+{
+    constexpr int Q = Shape<d, N, P>::Q;
+    if (Q >= kStarvedChunkedMaxLanes || threads < Q || backward_lds_bytes<d, N, P>(L, 1) > kMaxLdsBytes) return 0;
+    const int full = threads / Q;
+    int fit = full;
+    while (fit > 1 && backward_lds_bytes<d, N, P>(L, fit) > kMaxLdsBytes) --fit;
+    if (fit >= full) return 0;
+    int T = kTiledSteps;
+    while (T > 16 && backward_lds_bytes<d, N, P>(T + 1, full) > 32 * 1024) T -= 8;
+    return T < L - 1 ? T : 0;
+}
+
 template <int d, int N, int P>
 int64_t backward_tiled_scratch_floats(int64_t B, int64_t L)
 {
     constexpr bool tiles_when_starved = Shape<d, N, P>::Q >= kStarvedChunkedMaxLanes;
     const bool starved = tiles_when_starved && backward_starved<d, N, P>(L);
+    if (backward_short_tile<d, N, P>(L, 256) > 0) return B * (L - 1) * d;
     return backward_lds_bytes<d, N, P>(L, 1) <= kMaxLdsBytes && !starved ? 0 : B * (L - 1) * d;
 }
 
@@ -518,22 +540,39 @@ hipError_t backward_launch(const BackwardArgs &A0, float *scratch, int threads, 
     const bool starved = half_empty && A.B * Q >= half_empty_lanes;
     const bool starved_tiles = starved && Q >= kStarvedChunkedMaxLanes && scratch;
     const bool starved_chunks = starved && Q < kStarvedChunkedMaxLanes;
-    if (backward_lds_bytes<d, N, P>(A.L, 1) > kMaxLdsBytes || starved_tiles) {
-        // the path's increments do not fit LDS at once: tiles of kTiledSteps increments, walked by one workgroup
+    // few-lane kernels that LDS keeps from filling their workgroups, on a batch that needs the plain sweep's resident
+    // workgroups more than one and a half times over: short tiles (see backward_short_tile)
+    int short_tile = 0;
+    if (scratch && !half_empty && A.B * Q >= few_lanes) {
+        short_tile = backward_short_tile<d, N, P>(A.L, threads);
+        if (short_tile) {
+            int fit = threads / Q;
+            while (fit > 1 && backward_lds_bytes<d, N, P>(A.L, fit) > kMaxLdsBytes) --fit;
+            const int64_t resident = resident_sweep_workgroups<d, N, P>(A.L, A.stream_flag, threads, fit, 0) * fit * Q * cus;
+            // (stream mode, whose tiles fetch the upstream rows one step ahead only: from two and a half times over,
+            // unless the lane state is large; (2,3) and (2,4) with 256 points lose a quarter at twice over, (2,6)
+            // gains 2x there)
+            const int64_t times2 = !A.stream_flag || Shape<d, N, P>::SZ >= 48 ? 3 : 5;
+            if (A.B * Q * 2 < resident * times2) short_tile = 0;
+        }
+    }
+    if (backward_lds_bytes<d, N, P>(A.L, 1) > kMaxLdsBytes || starved_tiles || short_tile) {
+        // the path's increments do not fit LDS at once (or too few paths' do): tiles of increments, walked by one workgroup
         if (!scratch || (A.L - 1) / kTiledSteps > INT32_MAX / 2) return hipErrorInvalidValue;
+        const int tile = short_tile ? short_tile : kTiledSteps;
         A.tiled = 1;
-        A.seg_steps = kTiledSteps;
-        A.segs = (int32_t)((A.L - 1 + kTiledSteps - 1) / kTiledSteps);
+        A.seg_steps = tile;
+        A.segs = (int32_t)((A.L - 1 + tile - 1) / tile);
         A.seg_part = scratch;
         int G = threads / Q;
         const int64_t per_cu = (A.B + cus - 1) / (cus > 0 ? cus : 1);
         if ((int64_t)G > per_cu) G = per_cu > 1 ? (int)per_cu : 1;
-        while (G > 1 && backward_lds_bytes<d, N, P>(kTiledSteps + 1, G) > kMaxLdsBytes) --G;
+        while (G > 1 && backward_lds_bytes<d, N, P>(tile + 1, G) > kMaxLdsBytes) --G;
         if (per_cu > G) {   // the same number of paths on every CU, see below
             const int64_t rounds = (per_cu + G - 1) / G;
             G = (int)((per_cu + rounds - 1) / rounds);
         }
-        const size_t lds = (size_t)backward_lds_bytes<d, N, P>(kTiledSteps + 1, G);
+        const size_t lds = (size_t)backward_lds_bytes<d, N, P>(tile + 1, G);
         const int64_t grid = (A.B + G - 1) / G;
         if (lds > (size_t)kMaxLdsBytes || grid <= 0 || grid > INT32_MAX) return hipErrorInvalidValue;
         A.groups = G;

@@ -362,6 +362,12 @@ def test_backward_saturated_variants_sampled(gpu, oracle, name, B):
     (3, 4, 256, 8200, True),      # three lanes per path, stream mode
     (5, 3, 128, 33000, False),    # five lanes per path, final mode
     (3, 3, 500, 8200, True),      # stream mode, depth 3 with too few lanes left: still cut in time
+    # few-lane kernels whose LDS holds fewer paths than a workgroup has lanes for, on batches that need the plain sweep's
+    # resident workgroups several times over: walked in short tiles
+    (5, 3, 100, 66000, False),
+    (10, 2, 100, 17000, True),
+    (5, 3, 256, 16500, True),
+    (6, 3, 100, 33000, False),
 ])
 def test_backward_of_long_paths_in_a_batch_that_fills_the_chip(gpu, oracle, d, depth, L, B, stream):
     """Paths whose increments fit the staging only a few at a time, in a batch large enough to fill the chip: the
