@@ -234,6 +234,58 @@ __global__ __launch_bounds__(256) void sig_combine_rows_lds_kernel(CombineParams
     }
 }
 
+// Many short rows (a batch of products of signatures of a few hundred to a few thousand floats): `per_wg` rows to a
+// workgroup, so that every thread has several words to do between the two barriers and the loads of several rows are
+// in flight together.  The lower levels of the workgroup's rows are staged in LDS as above; the words of its rows are
+// taken flattened (thread t: words t, t + 256, ... of the per_wg * D), consecutive threads on consecutive floats.
+__global__ __launch_bounds__(256) void sig_combine_short_rows_kernel(CombineParams P, int64_t rows, int per_wg)
+{
+    const int N = P.depth;
+    const int low = (int)P.off[N];     // floats of levels 1 .. N-1
+    float *sa = sig_smem;              // [per_wg][low]
+    float *sb = sig_smem + (size_t)per_wg * low;
+    const int tid = threadIdx.x, nthr = blockDim.x;
+    const int64_t row0 = (int64_t)blockIdx.x * per_wg;
+    const int nr = rows - row0 < per_wg ? (int)(rows - row0) : per_wg;
+    // (index / length by a float multiply with a one-step correction: exact below 2^24, which the host checks)
+    const float inv_low = 1.0f / (float)(low > 0 ? low : 1);
+    for (int i = tid; i < nr * low; i += nthr) {
+        int r = (int)((float)i * inv_low);
+        int x = i - r * low;
+        if (x < 0) { --r; x += low; }
+        else if (x >= low) { ++r; x -= low; }
+        sa[i] = P.a[(row0 + r) * P.a_stride + x];
+        sb[i] = P.b[(row0 + r) * P.b_stride + x];
+    }
+    __syncthreads();
+    // level by level, so that the level and its split points are the same for the whole workgroup (a lane that looks
+    // them up by its own level indexes the kernel arguments per lane, which costs more than the product)
+    for (int n = 1; n <= N; ++n) {
+        const int cnt = (int)P.pw[n], base = (int)P.off[n];
+        const float inv_cnt = P.inv_pw[n];
+        for (int idx = tid; idx < nr * cnt; idx += nthr) {
+            int r = (int)((float)idx * inv_cnt);
+            int wi = idx - r * cnt;
+            if (wi < 0) { --r; wi += cnt; }
+            else if (wi >= cnt) { ++r; wi -= cnt; }
+            const uint32_t w = (uint32_t)wi;
+            const float *la = sa + (size_t)r * low, *lb = sb + (size_t)r * low;
+            float c = (n == N) ? P.a[(row0 + r) * P.a_stride + base + wi] + P.b[(row0 + r) * P.b_stride + base + wi]
+                               : la[base + wi] + lb[base + wi];
+            const float wf = (float)w;
+            for (int k = 1; k < n; ++k) {
+                const uint32_t split = P.pw[n - k];
+                uint32_t hi = (uint32_t)(wf * P.inv_pw[n - k]);
+                int32_t q = (int32_t)(w - hi * split);
+                if (q < 0) { --hi; q += (int32_t)split; }
+                else if (q >= (int32_t)split) { ++hi; q -= (int32_t)split; }
+                c = fmaf(la[P.off[k] + hi], lb[P.off[n - k] + q], c);
+            }
+            P.out[(row0 + r) * P.out_stride + base + wi] = c;
+        }
+    }
+}
+
 }  // namespace
 
 bool make_row_shape(int d, int depth, RowShape *rs)
@@ -303,6 +355,18 @@ hipError_t launch_combine_rows(const float *a, int64_t a_stride, const float *b,
     for (int n = 1; n <= rs.depth + 1; ++n) P.off[n] = rs.off[n];
     P.off[0] = 0;
     const int64_t low = rs.off[rs.depth];   // floats of the levels below the top one
+    // A batch of short rows: several rows to a workgroup, about 3,072 words, within 48 KB of staged lower levels.
+    if (rs.depth >= 2 && rs.D >= 64 && rs.D <= 4096 && B >= 2048) {
+        int64_t per_wg = (3072 + rs.D - 1) / rs.D;
+        while (per_wg > 1 && 2 * per_wg * low * (int64_t)sizeof(float) > 48 * 1024) --per_wg;
+        if (per_wg > B / 1024) per_wg = B / 1024;   // at least four workgroups for every compute unit
+        const int64_t grid = (B + per_wg - 1) / per_wg;
+        if (2 * per_wg * low * (int64_t)sizeof(float) <= 48 * 1024 && grid <= INT32_MAX) {
+            const size_t lds = (size_t)(2 * per_wg * low) * sizeof(float);
+            hipLaunchKernelGGL(sig_combine_short_rows_kernel, dim3((unsigned)grid), dim3(256), lds, st, P, B, (int)per_wg);
+            return hipGetLastError();
+        }
+    }
     if (rs.D >= 64 && rs.pow[rs.depth] <= ((int64_t)1 << 24) && 2 * low * (int64_t)sizeof(float) <= 48 * 1024) {
         // lower levels staged in LDS; pieces of at least 8192 top-level words, enough workgroups to fill the chip
         int64_t slices = rs.pow[rs.depth] / 8192;
