@@ -547,21 +547,33 @@ __global__ __launch_bounds__(256) void sig_backward_tiled_kernel(BackwardArgs A)
     float *mypark = park + (size_t)gi * TS * Pk::kStepFloats;
     float *myrow = tile + gi * row_stride;
 
-    Lane<d, N, P> ln, ad, up;
+    // Stream mode: the upstream rows of a tile are fetched PD steps ahead into registers, as in the plain sweep; every
+    // tile starts with its first PD rows, asked for before its increments are staged.
+    constexpr int PD = !STREAM ? 1 : Sh::SZ <= 24 ? 4 : Sh::SZ <= 48 ? 2 : 1;
+    Lane<d, N, P> ln, ad, up[PD];
     identity_state<d, N, P>(ln);
     identity_state<d, N, P>(ad);
-    identity_state<d, N, P>(up);
-    if (P == 0) { ad.s[0] = 0.0f; up.s[0] = 0.0f; }
+    static_for<0, PD>([&](auto jc) __attribute__((always_inline)) {
+        identity_state<d, N, P>(up[decltype(jc)::value]);
+        if (P == 0) up[decltype(jc)::value].s[0] = 0.0f;
+    });
+    if (P == 0) ad.s[0] = 0.0f;
     if (active) {
         load_state<d, N, P>(STREAM ? A.sig + (b * Kall + (Kall - 1)) * D : A.sig + b * D, u, ln);
-        if constexpr (STREAM) load_adjoint<d, N, P, false, false>(A.grad_out + (b * Kall + (Kall - 1)) * D, u, up);
-        else load_adjoint<d, N, P, false>(A.grad_out + b * D, u, ad);
+        if constexpr (!STREAM) load_adjoint<d, N, P, false>(A.grad_out + b * D, u, ad);
     }
 
     for (int tl = A.segs - 1; tl >= 0; --tl) {
         const int64_t k0 = (int64_t)tl * T;
         const int64_t K = Kall - k0 < T ? Kall - k0 : T;
         const int row_floats = (int)K * d;
+        if constexpr (STREAM) {
+            static_for<0, PD>([&](auto jc) __attribute__((always_inline)) {
+                constexpr int j = decltype(jc)::value;
+                if (active && K - 1 - j >= 0)
+                    load_adjoint<d, N, P, false, false>(A.grad_out + (b * Kall + (k0 + K - 1 - j)) * D, u, up[j]);
+            });
+        }
         if (tl != A.segs - 1) __syncthreads();   // the previous tile's sums have been written out
         for (int i = tid; i < G * row_floats; i += nthr) {
             const int g2 = i / row_floats;
@@ -574,11 +586,16 @@ __global__ __launch_bounds__(256) void sig_backward_tiled_kernel(BackwardArgs A)
             tile[g2 * row_stride + r] = v;
         }
         __syncthreads();
-        for (int64_t k = K - 1; k >= 0; --k) {
+        for (int64_t kk = K - 1; kk >= 0; kk -= PD)
+        static_for<0, PD>([&](auto jc) __attribute__((always_inline)) {
+            constexpr int j = decltype(jc)::value;
+            const int64_t k = kk - j;
+            if (k < 0) return;
             const int ts = (int)((K - 1 - k) % TS);
             if constexpr (STREAM) {
-                add_row<d, N, P>(ad, up, owner);
-                if (active && k0 + k > 0) load_adjoint<d, N, P, false, false>(A.grad_out + (b * Kall + (k0 + k - 1)) * D, u, up);
+                add_row<d, N, P>(ad, up[j], owner);
+                if (active && k - PD >= 0)
+                    load_adjoint<d, N, P, false, false>(A.grad_out + (b * Kall + (k0 + k - PD)) * D, u, up[j]);
             }
             Inc<d, P> inc, neg;
             load_inc<d, P>(inc, myrow + k * d, letter);
@@ -607,7 +624,7 @@ __global__ __launch_bounds__(256) void sig_backward_tiled_kernel(BackwardArgs A)
                 }
                 __syncthreads();
             }
-        }
+        });
         for (int i = tid; i < G * row_floats; i += nthr) {
             const int g2 = i / row_floats;
             const int r = i - g2 * row_floats;
