@@ -549,9 +549,8 @@ hipError_t backward_launch(const BackwardArgs &A0, float *scratch, int threads, 
             int fit = threads / Q;
             while (fit > 1 && backward_lds_bytes<d, N, P>(A.L, fit) > kMaxLdsBytes) --fit;
             const int64_t resident = resident_sweep_workgroups<d, N, P>(A.L, A.stream_flag, threads, fit, 0) * fit * Q * cus;
-            // (stream mode, whose tiles fetch the upstream rows one step ahead only: from two and a half times over,
-            // unless the lane state is large; (2,3) and (2,4) with 256 points lose a quarter at twice over, (2,6)
-            // gains 2x there)
+            // (stream mode: from two and a half times over, unless the lane state is large; at twice over (2,3),
+            // (2,4), (3,4) and (6,3) with 256 points lose 15-25 % to the plain sweep, (2,6) gains 2x)
             const int64_t times2 = !A.stream_flag || Shape<d, N, P>::SZ >= 48 ? 3 : 5;
             if (A.B * Q * 2 < resident * times2) short_tile = 0;
         }
