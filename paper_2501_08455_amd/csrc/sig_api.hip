@@ -402,6 +402,11 @@ int plan_auto(const sig_ctx *ctx, int64_t B, int64_t L, int stream_flag, const R
         // doubled the chunks of these kernels almost everywhere (1.2-1.8x at 1,024 and 4,096 paths) and halved or
         // kept those of the kernels with 16 lanes or more (twice the chunks: 0.8-0.9x there).
         if (stream_flag && Q <= tune::kStreamFewLanes) want_lanes = 2 * simd_lanes;
+        // (the kernels with up to 63 lanes of at most 16 floats gain 1.05-1.25x from twice the chunks too, but only
+        // where the time is cut anyway: an uncut plan keeps its narrow workgroups, which twice the lanes would give up
+        // for 0.8-0.9x)
+        if (stream_flag && Q > tune::kStreamFewLanes && Q < kWave && state <= 16 && B * Q < simd_lanes)
+            want_lanes = 2 * simd_lanes;
         pl->variant = SIG_VARIANT_ON_CHIP;
         pl->prefix_depth = ki->p;
         pl->chunks = 1;
