@@ -172,8 +172,8 @@ int sig_plan(const sig_ctx *ctx, int64_t B, int64_t L, int d, int depth, int str
 /*
  * Optional tuning of the mapping of one shape (the shape grid of the paper's tables, Section 4.1, is where it
  * pays: few paths, where launch and latency effects decide).  Times candidate mappings on the device -- the
- * planner's choice, the level-scan family, the compiled register kernels with neighbouring time cuts -- on
- * synthetic input of this shape and remembers the fastest in the context: later sig_compute and sig_plan calls
+ * planner's choice, the level-scan family, the compiled register kernels with neighbouring time cuts, then the
+ * fastest of these with smaller workgroups (192, 128, 64 threads) -- on synthetic input of this shape and remembers the fastest in the context: later sig_compute and sig_plan calls
  * with exactly this (B, L, d, depth, stream_flag) use it (64 shapes per context, the oldest is replaced).
  *   chosen, microseconds   HOST, may be NULL: the mapping taken and its measured time per call
  * Unlike the other entry points it allocates temporary device buffers of the input and output size, enqueues a few
