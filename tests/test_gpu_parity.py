@@ -417,7 +417,8 @@ def test_runs_are_bitwise_reproducible(gpu):
                                         (2, 25, 1),
                                         # batches of short rows, several rows to a workgroup: a ragged last workgroup,
                                         # one to ten rows per workgroup, the longest rows that kernel takes
-                                        (5, 4, 2049), (4, 4, 4100), (2, 6, 3001), (6, 4, 2500), (3, 7, 2100), (8, 2, 9000)])
+                                        (5, 4, 2049), (4, 4, 4100), (2, 6, 3001), (6, 4, 2500), (3, 7, 2100), (8, 2, 9000),
+                                        (2, 3, 5000), (2, 2, 3000), (3, 2, 2500)])
 def test_sig_combine_matches_eq4(gpu, oracle, d, depth, B):
     """Batched truncated product (Eq. 4) against the oracle's; (2, 25) has levels of more than 2^24 words, where the
     kernel's index arithmetic takes its integer-division path."""
