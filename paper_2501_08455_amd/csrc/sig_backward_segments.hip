@@ -270,6 +270,10 @@ hipError_t backward_segmented_launch(const BackwardArgs &A0, float *scratch, int
             const int64_t per_cu = (pieces + cus - 1) / cus;
             if ((int64_t)G > per_cu) G = (int)per_cu;
             while (G > 1 && backward_lds_bytes<d, N, P>(T + 1, G) > kMaxLdsBytes) --G;
+            if (per_cu > G) {   // the same number of pieces on every compute unit (see backward_launch)
+                const int64_t rounds = (per_cu + G - 1) / G;
+                G = (int)((per_cu + rounds - 1) / rounds);
+            }
             A.groups = G;
             lds = (size_t)backward_lds_bytes<d, N, P>(T + 1, G);
             grid = dim3((unsigned)((pieces + G - 1) / G));
@@ -349,6 +353,10 @@ hipError_t backward_segmented_launch(const BackwardArgs &A0, float *scratch, int
         const int64_t per_cu = (pieces + cus - 1) / cus;
         if ((int64_t)G > per_cu) G = (int)per_cu;
         while (G > 1 && backward_lds_bytes<d, N, P>(T + 1, G) > kMaxLdsBytes) --G;
+        if (per_cu > G) {   // the same number of pieces on every compute unit (see backward_launch)
+            const int64_t rounds = (per_cu + G - 1) / G;
+            G = (int)((per_cu + rounds - 1) / rounds);
+        }
         A.groups = G;
         const size_t lds = (size_t)backward_lds_bytes<d, N, P>(T + 1, G);
         hipLaunchKernelGGL((sig_backward_kernel<d, N, P, false, true>), dim3((unsigned)((pieces + G - 1) / G)), dim3(256), lds,
